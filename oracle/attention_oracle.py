@@ -1,0 +1,174 @@
+"""Float64 CPU oracle for exact scaled-dot-product attention, forward and backward.
+
+TEST INFRASTRUCTURE ONLY. Nothing in the product path may import this file;
+only tests/, the smoke check and the benchmark's cpu_baseline leg call it.
+It shares no code with the HIP kernels and imports nothing but numpy.
+
+The tiled method of the paper reaches exactly (up to rounding order) the result
+of the standard definition (section 2.2, "Standard Attention Implementation";
+section 3.1.1 states that Algorithm 1 returns softmax(QK^T)V with no
+approximation), so this oracle is that definition written out, materialising
+the full score matrix S and probability matrix P per (sequence, query head):
+
+    S = scale * Q K^T          (section 2.2; the scaling is the footnote there)
+    S[r, c] = -inf for c > r   (causal mask, section 3.1.1 "Causal masking")
+    P = softmax_rows(S),  L = rowmax(S) + log(rowsum(exp(S - rowmax(S))))
+                               (L: the logsumexp of section 3.1.1, tweak 2)
+    O = P V
+
+and, given dO (section 2.2, backward equations; Algorithm 2 for D and dS):
+
+    dV = P^T dO,  dP = dO V^T,  D = rowsum(dO o O),  dS = P o (dP - D)
+    dQ = scale * dS K,  dK = scale * dS^T Q
+
+Readings taken where the text is silent or inconsistent:
+  * the backward equations are printed without the softmax scaling; the chain
+    rule through S = scale*QK^T puts `scale` on dQ and dK;
+  * section 2.2 prints dK = Q dS^T, which does not type-check for N x d
+    operands; Algorithm 2's dS^T Q is used;
+  * Algorithm 2 declares D in R^d; it has one entry per query row (R^N);
+  * grouped-query attention (section 3.1.2 paragraph on MQA/GQA): query head h
+    reads key/value head h // (Hq / Hkv); dK, dV are summed over the query
+    heads of a group;
+  * packed ragged batches are not in the paper: each sequence, delimited by
+    cumulative offsets, is an independent attention problem.
+
+Layouts: dense Q,O,dO,dQ [B, N, Hq, d]; K,V,dK,dV [B, N, Hkv, d]; L [B, Hq, N].
+Packed: Q.. [T, Hq, d]; K.. [T, Hkv, d]; L [Hq, T].
+All arithmetic is float64. Every function here is pinned by tests/test_oracle_pins.py.
+"""
+import numpy as np
+
+
+def widen_bf16(bits):
+    """bfloat16 bit patterns (uint16) -> float64, exactly."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def scores(q, k, scale, causal):
+    """S for one head: q [N, d], k [N, d] -> [N, N] (section 2.2; causal
+    entries with column index above the row index are -inf)."""
+    s = scale * (q @ k.T)
+    if causal:
+        n = s.shape[0]
+        r = np.arange(n)[:, None]
+        c = np.arange(s.shape[1])[None, :]
+        s = np.where(c > r, -np.inf, s)
+    return s
+
+
+def softmax_rows(s):
+    """Row-wise softmax and logsumexp of a score matrix (section 2.2 and the
+    logsumexp L of section 3.1.1)."""
+    m = np.max(s, axis=1, keepdims=True)
+    e = np.exp(s - m)
+    l = np.sum(e, axis=1, keepdims=True)
+    return e / l, (m + np.log(l))[:, 0]
+
+
+def head_forward(q, k, v, scale, causal):
+    """One head: returns O [N, d], L [N], P [N, N]."""
+    p, lse = softmax_rows(scores(q, k, scale, causal))
+    return p @ v, lse, p
+
+
+def head_backward(q, k, v, do, scale, causal):
+    """One head: returns dQ, dK, dV (section 2.2 backward; Algorithm 2 for the
+    form dS = P o (dP - D) with D = rowsum(dO o O))."""
+    o, _, p = head_forward(q, k, v, scale, causal)
+    dv = p.T @ do
+    dp = do @ v.T
+    big_d = np.sum(do * o, axis=1, keepdims=True)
+    ds = p * (dp - big_d)
+    dq = scale * (ds @ k)
+    dk = scale * (ds.T @ q)
+    return dq, dk, dv
+
+
+def _group(Hq, Hkv):
+    if Hkv <= 0 or Hq % Hkv != 0:
+        raise ValueError("Hq must be a positive multiple of Hkv")
+    return Hq // Hkv
+
+
+def attention_forward(Q, K, V, scale, causal):
+    """Dense batch forward. Q [B,N,Hq,d], K,V [B,N,Hkv,d] float64.
+    Returns O [B,N,Hq,d], L [B,Hq,N]."""
+    B, N, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    O = np.empty((B, N, Hq, d), dtype=np.float64)
+    L = np.empty((B, Hq, N), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            o, lse, _ = head_forward(Q[b, :, h, :], K[b, :, g, :], V[b, :, g, :], scale, causal)
+            O[b, :, h, :] = o
+            L[b, h, :] = lse
+    return O, L
+
+
+def attention_backward(Q, K, V, dO, scale, causal):
+    """Dense batch backward. Returns dQ [B,N,Hq,d], dK, dV [B,N,Hkv,d]."""
+    B, N, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    G = _group(Hq, Hkv)
+    dQ = np.zeros((B, N, Hq, d), dtype=np.float64)
+    dK = np.zeros((B, N, Hkv, d), dtype=np.float64)
+    dV = np.zeros((B, N, Hkv, d), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            dq, dk, dv = head_backward(Q[b, :, h, :], K[b, :, g, :], V[b, :, g, :],
+                                       dO[b, :, h, :], scale, causal)
+            dQ[b, :, h, :] = dq
+            dK[b, :, g, :] += dk
+            dV[b, :, g, :] += dv
+    return dQ, dK, dV
+
+
+def varlen_forward(Q, K, V, cu_seqlens, scale, causal):
+    """Packed ragged forward. Q [T,Hq,d], K,V [T,Hkv,d]; returns O [T,Hq,d], L [Hq,T]."""
+    T, Hq, d = Q.shape
+    O = np.zeros((T, Hq, d), dtype=np.float64)
+    L = np.zeros((Hq, T), dtype=np.float64)
+    for s in range(len(cu_seqlens) - 1):
+        a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        if e == a:
+            continue
+        o, lse = attention_forward(Q[None, a:e], K[None, a:e], V[None, a:e], scale, causal)
+        O[a:e] = o[0]
+        L[:, a:e] = lse[0]
+    return O, L
+
+
+def varlen_backward(Q, K, V, dO, cu_seqlens, scale, causal):
+    """Packed ragged backward. Returns dQ [T,Hq,d], dK, dV [T,Hkv,d]."""
+    dQ = np.zeros(Q.shape, dtype=np.float64)
+    dK = np.zeros(K.shape, dtype=np.float64)
+    dV = np.zeros(V.shape, dtype=np.float64)
+    for s in range(len(cu_seqlens) - 1):
+        a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        if e == a:
+            continue
+        dq, dk, dv = attention_backward(Q[None, a:e], K[None, a:e], V[None, a:e],
+                                        dO[None, a:e], scale, causal)
+        dQ[a:e], dK[a:e], dV[a:e] = dq[0], dk[0], dv[0]
+    return dQ, dK, dV
+
+
+# ---------------------------------------------------------------------------
+# Sampled evaluation for full-size workloads: the same definition, restricted
+# to chosen (sequence, query head) units or to chosen query rows, so a parity
+# test can check a large GPU result without materialising every N x N matrix.
+# ---------------------------------------------------------------------------
+
+def rows_forward(q_rows, row_idx, k, v, scale, causal):
+    """Forward for selected query rows of one head: q_rows [R,d] are the rows
+    `row_idx` of Q; k, v [N,d]. Returns O rows [R,d] and L [R]."""
+    s = scale * (q_rows @ k.T)
+    if causal:
+        c = np.arange(k.shape[0])[None, :]
+        s = np.where(c > np.asarray(row_idx)[:, None], -np.inf, s)
+    p, lse = softmax_rows(s)
+    return p @ v, lse

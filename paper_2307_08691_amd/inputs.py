@@ -1,0 +1,172 @@
+"""Seeded synthetic inputs for the attention hot path.
+
+This module holds no attention arithmetic: it only draws standard-normal
+numbers with numpy's counter-based generator, rounds them to bfloat16 (round to
+nearest, ties to even) and hands out the 16-bit patterns. Both the GPU parity
+tests and the float64 CPU checker consume the same bit patterns, so neither
+side ever sees a value the other did not.
+
+The benchmark in the paper's "Benchmarking Attention" section is itself
+synthetic (random Q, K, V at hidden size 2048, head dim 64 or 128, 16k tokens
+in total); the recipes below reproduce those shapes.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+__all__ = [
+    "f32_to_bf16_bits",
+    "bf16_bits_to_f32",
+    "AttnProblem",
+    "make_dense",
+    "make_varlen",
+    "CONFIGS",
+    "make_config",
+]
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (RNE) and return the uint16 bit patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    rounding = ((u >> 16) & 1) + 0x7FFF
+    out = ((u + rounding) >> 16).astype(np.uint16)
+    nan = np.isnan(x)
+    if nan.any():
+        out[nan] = 0x7FC0
+    return out
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns to float32 exactly."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+@dataclass
+class AttnProblem:
+    """One attention problem: bf16 bit patterns plus its shape parameters.
+
+    Dense layout: Q, dO are [B, N, Hq, d]; K, V are [B, N, Hkv, d].
+    Packed ragged layout (cu_seqlens is not None): Q, dO are [T, Hq, d];
+    K, V are [T, Hkv, d]; sequence s owns token rows cu_seqlens[s]:cu_seqlens[s+1].
+    """
+
+    name: str
+    Q: np.ndarray
+    K: np.ndarray
+    V: np.ndarray
+    dO: np.ndarray
+    Hq: int
+    Hkv: int
+    d: int
+    scale: float
+    causal: bool
+    B: int = 0
+    N: int = 0
+    cu_seqlens: Optional[np.ndarray] = None
+    seed: int = 0
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def varlen(self) -> bool:
+        return self.cu_seqlens is not None
+
+    @property
+    def total_tokens(self) -> int:
+        return int(self.cu_seqlens[-1]) if self.varlen else self.B * self.N
+
+    @property
+    def seqlens(self) -> np.ndarray:
+        if self.varlen:
+            return np.diff(self.cu_seqlens)
+        return np.full(self.B, self.N, dtype=np.int64)
+
+    def fwd_flops(self) -> float:
+        """Metric FLOPs of the forward pass: 4*N^2*d per query head and
+        sequence, halved under the causal mask (the paper's benchmark formula)."""
+        n2 = float(np.sum(self.seqlens.astype(np.float64) ** 2))
+        f = 4.0 * self.Hq * self.d * n2
+        return f / 2.0 if self.causal else f
+
+    def bwd_flops(self) -> float:
+        return 2.5 * self.fwd_flops()
+
+
+def _draw(rng: np.random.Generator, shape, mult: float = 1.0) -> np.ndarray:
+    x = rng.standard_normal(size=shape, dtype=np.float32)
+    if mult != 1.0:
+        x = x * np.float32(mult)
+    return f32_to_bf16_bits(x)
+
+
+def make_dense(B, N, Hq, Hkv, d, causal, seed, scale=None, qk_mult=1.0,
+               name="dense") -> AttnProblem:
+    """Draw Q, K, V, dO (in that order) i.i.d. N(0,1), optionally scaling Q and
+    K by `qk_mult` before the bf16 rounding."""
+    rng = np.random.default_rng(seed)
+    Q = _draw(rng, (B, N, Hq, d), qk_mult)
+    K = _draw(rng, (B, N, Hkv, d), qk_mult)
+    V = _draw(rng, (B, N, Hkv, d))
+    dO = _draw(rng, (B, N, Hq, d))
+    return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
+                       scale=float(scale if scale is not None else d ** -0.5),
+                       causal=bool(causal), B=B, N=N, seed=seed)
+
+
+def make_varlen(seqlens, Hq, Hkv, d, causal, seed, scale=None,
+                name="varlen") -> AttnProblem:
+    """Packed ragged batch: tokens of all sequences concatenated."""
+    seqlens = np.asarray(seqlens, dtype=np.int64)
+    cu = np.zeros(len(seqlens) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(seqlens)
+    T = int(cu[-1])
+    rng = np.random.default_rng(seed)
+    Q = _draw(rng, (T, Hq, d))
+    K = _draw(rng, (T, Hkv, d))
+    V = _draw(rng, (T, Hkv, d))
+    dO = _draw(rng, (T, Hq, d))
+    return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
+                       scale=float(scale if scale is not None else d ** -0.5),
+                       causal=bool(causal), cu_seqlens=cu, seed=seed,
+                       meta={"max_seqlen": int(seqlens.max()) if len(seqlens) else 0})
+
+
+# Named workloads. Seeds are 1000 + index of the workload family.
+CONFIGS = {
+    "tiny": dict(kind="dense", B=1, N=128, Hq=2, Hkv=2, d=64, causal=False, seed=1001),
+    "d128_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1003),
+    "long_n16k_causal_x3": dict(kind="dense", B=1, N=16384, Hq=16, Hkv=16, d=128, causal=True,
+                                seed=1004, qk_mult=3.0),
+    "gqa_ragged": dict(kind="varlen", nseq=16, lo=256, hi=4096, Hq=32, Hkv=8, d=128, causal=True,
+                       seed=1005),
+}
+
+
+def sweep_name(d: int, N: int, causal: bool) -> str:
+    return f"sweep_d{d}_n{N}_{'causal' if causal else 'full'}"
+
+
+for _d, _H in ((64, 32), (128, 16)):
+    for _N in (512, 1024, 2048, 4096, 8192, 16384):
+        for _c in (False, True):
+            CONFIGS[sweep_name(_d, _N, _c)] = dict(kind="dense", B=16384 // _N, N=_N, Hq=_H, Hkv=_H,
+                                                   d=_d, causal=_c, seed=1002)
+
+
+def ragged_lengths(seed: int, nseq: int, lo: int, hi: int) -> np.ndarray:
+    """Sequence lengths uniform in [lo, hi], drawn before the tensors from a
+    generator of their own so they do not depend on the tensor shapes."""
+    return np.random.default_rng(seed + 7919).integers(lo, hi + 1, nseq)
+
+
+def make_config(name: str) -> AttnProblem:
+    c = dict(CONFIGS[name])
+    kind = c.pop("kind")
+    if kind == "dense":
+        return make_dense(name=name, **c)
+    lens = ragged_lengths(c["seed"], c.pop("nseq"), c.pop("lo"), c.pop("hi"))
+    return make_varlen(lens, name=name, **c)

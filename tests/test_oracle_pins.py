@@ -1,0 +1,385 @@
+"""Pins for the float64 oracle: closed forms, invariants, brute force and finite
+differences. None of these retype the oracle's matrix formulas; each checks it
+against something the mathematics fixes independently (section 2.2 definitions,
+section 3.1.1 online-softmax identity and causal mask, the MQA/GQA paragraph)."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import attention_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ----------------------------------------------------------------------------
+# brute force: scalar loops with math.exp, written from the definition
+# ----------------------------------------------------------------------------
+
+def brute_forward(q, k, v, scale, causal):
+    n, d = len(q), len(q[0])
+    O = [[0.0] * d for _ in range(n)]
+    L = [0.0] * n
+    for r in range(n):
+        cols = range(r + 1) if causal else range(n)
+        w = {c: math.exp(scale * sum(q[r][t] * k[c][t] for t in range(d))) for c in cols}
+        z = sum(w.values())
+        L[r] = math.log(z)
+        for t in range(d):
+            O[r][t] = sum(w[c] * v[c][t] for c in cols) / z
+    return O, L
+
+
+def loss_of(q, k, v, do, scale, causal):
+    """f = sum(O o dO) through the scalar-loop forward."""
+    O, _ = brute_forward(q.tolist(), k.tolist(), v.tolist(), scale, causal)
+    return float(np.sum(np.asarray(O) * do))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("n,d", [(1, 3), (2, 1), (5, 4), (9, 2)])
+def test_forward_matches_scalar_brute_force(n, d, causal):
+    q, k, v = rnd(1, n, d), rnd(2, n, d), rnd(3, n, d)
+    o, lse, _ = orc.head_forward(q, k, v, 0.37, causal)
+    bo, bl = brute_forward(q.tolist(), k.tolist(), v.tolist(), 0.37, causal)
+    np.testing.assert_allclose(o, np.asarray(bo), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, np.asarray(bl), rtol=1e-12, atol=1e-13)
+
+
+def test_single_token_is_identity_on_v():
+    q, k, v = rnd(4, 1, 8), rnd(5, 1, 8), rnd(6, 1, 8)
+    for causal in (False, True):
+        o, lse, _ = orc.head_forward(q, k, v, 0.25, causal)
+        np.testing.assert_allclose(o, v, atol=1e-15)
+        np.testing.assert_allclose(lse, [0.25 * float(q[0] @ k[0])], rtol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# golden closed-form fixture
+# ----------------------------------------------------------------------------
+
+def _sub(x):
+    env = {"LN2": math.log(2.0), "LN3": math.log(3.0), "LN4": math.log(4.0)}
+    if isinstance(x, list):
+        return [_sub(y) for y in x]
+    if isinstance(x, str):
+        return float(eval(x, {"__builtins__": {}}, env))
+    return float(x)
+
+
+@pytest.mark.parametrize("mode", ["full", "causal"])
+def test_two_token_closed_form(mode):
+    with open(os.path.join(GOLDEN, "two_token_closed_form.json")) as f:
+        g = json.load(f)
+    q, k, v, do = (np.asarray(_sub(g[n])) for n in ("Q", "K", "V", "dO"))
+    exp = {n: np.asarray(_sub(x)) for n, x in g[mode].items()}
+    causal = mode == "causal"
+    o, lse, p = orc.head_forward(q, k, v, 1.0, causal)
+    dq, dk, dv = orc.head_backward(q, k, v, do, 1.0, causal)
+    np.testing.assert_allclose(p, exp["P"], atol=1e-15)
+    np.testing.assert_allclose(o, exp["O"], atol=1e-15)
+    np.testing.assert_allclose(lse, exp["L"], atol=1e-15)
+    np.testing.assert_allclose(dv, exp["dV"], atol=1e-15)
+    np.testing.assert_allclose(dq, exp["dQ"], atol=1e-15)
+    np.testing.assert_allclose(dk, exp["dK"], atol=1e-15)
+
+
+# ----------------------------------------------------------------------------
+# softmax / forward invariants
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_softmax_rows_sum_to_one_and_mask_shape(causal):
+    q, k, v = rnd(7, 33, 16) * 3, rnd(8, 33, 16) * 3, rnd(9, 33, 16)
+    _, _, p = orc.head_forward(q, k, v, 0.25, causal)
+    assert np.all(p >= 0)
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-12)
+    if causal:
+        assert np.all(np.triu(p, 1) == 0.0)
+        assert np.all(np.diag(p) > 0)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_constant_v_returns_that_constant(causal):
+    q, k = rnd(10, 40, 8) * 2, rnd(11, 40, 8) * 2
+    row = rnd(12, 8)
+    v = np.tile(row, (40, 1))
+    o, _, _ = orc.head_forward(q, k, v, 0.3, causal)
+    np.testing.assert_allclose(o, v, atol=1e-12)
+
+
+def test_zero_q_gives_mean_of_v_and_log_n():
+    n, d = 37, 8
+    k, v = rnd(13, n, d), rnd(14, n, d)
+    q = np.zeros((n, d))
+    o, lse, _ = orc.head_forward(q, k, v, 0.5, False)
+    np.testing.assert_allclose(o, np.tile(v.mean(axis=0), (n, 1)), atol=1e-13)
+    np.testing.assert_allclose(lse, math.log(n), atol=1e-13)
+    o, lse, _ = orc.head_forward(q, k, v, 0.5, True)
+    prefix = np.cumsum(v, axis=0) / np.arange(1, n + 1)[:, None]
+    np.testing.assert_allclose(o, prefix, atol=1e-13)
+    np.testing.assert_allclose(lse, np.log(np.arange(1, n + 1)), atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_key_shift_moves_lse_only(causal):
+    n, d, scale = 21, 6, 0.4
+    q, k, v, c = rnd(15, n, d), rnd(16, n, d), rnd(17, n, d), rnd(18, d)
+    o0, l0, _ = orc.head_forward(q, k, v, scale, causal)
+    o1, l1, _ = orc.head_forward(q, k + c, v, scale, causal)
+    np.testing.assert_allclose(o1, o0, atol=1e-12)
+    np.testing.assert_allclose(l1 - l0, scale * (q @ c), atol=1e-12)
+
+
+def test_joint_permutation_of_keys_and_values():
+    n, d = 19, 5
+    q, k, v = rnd(19, n, d), rnd(20, n, d), rnd(21, n, d)
+    perm = np.random.default_rng(22).permutation(n)
+    o0, l0, _ = orc.head_forward(q, k, v, 0.7, False)
+    o1, l1, _ = orc.head_forward(q, k[perm], v[perm], 0.7, False)
+    np.testing.assert_allclose(o1, o0, atol=1e-13)
+    np.testing.assert_allclose(l1, l0, atol=1e-13)
+
+
+def test_scale_is_applied_before_softmax():
+    # scale*QK^T == (scale*Q)K^T: a scale applied after the softmax, or to V, fails this
+    n, d = 12, 4
+    q, k, v = rnd(23, n, d), rnd(24, n, d), rnd(25, n, d)
+    o0, l0, _ = orc.head_forward(q, k, v, 0.2, True)
+    o1, l1, _ = orc.head_forward(0.2 * q, k, v, 1.0, True)
+    np.testing.assert_allclose(o1, o0, atol=1e-13)
+    np.testing.assert_allclose(l1, l0, atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_scipy_softmax_and_logsumexp_agree(causal):
+    q, k, v = rnd(26, 30, 8) * 2, rnd(27, 30, 8) * 2, rnd(28, 30, 8)
+    s = orc.scores(q, k, 0.35, causal)
+    _, lse, p = orc.head_forward(q, k, v, 0.35, causal)
+    np.testing.assert_allclose(lse, scipy.special.logsumexp(s, axis=1), atol=1e-12)
+    np.testing.assert_allclose(p, scipy.special.softmax(s, axis=1), atol=1e-13)
+
+
+def test_large_scores_do_not_overflow():
+    q, k, v = rnd(29, 16, 8) * 40, rnd(30, 16, 8) * 40, rnd(31, 16, 8)
+    o, lse, p = orc.head_forward(q, k, v, 1.0, False)
+    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# the online-softmax identity of section 3.1.1 (two column blocks), with the
+# rescale read as multiplication by exp(m_old - m_new): it must reproduce the
+# one-shot result. Independent of the oracle's code path except for the target.
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("split", [1, 5, 11])
+def test_two_block_online_softmax_identity(split):
+    n, d = 7, 4
+    q, k, v = rnd(32, n, d) * 2, rnd(33, 12, d) * 2, rnd(34, 12, d)
+    s = q @ k.T
+    s1, s2, v1, v2 = s[:, :split], s[:, split:], v[:split], v[split:]
+    m1 = s1.max(axis=1)
+    l1 = np.exp(s1 - m1[:, None]).sum(axis=1)
+    o1 = np.exp(s1 - m1[:, None]) @ v1
+    m2 = np.maximum(m1, s2.max(axis=1))
+    alpha = np.exp(m1 - m2)
+    l2 = alpha * l1 + np.exp(s2 - m2[:, None]).sum(axis=1)
+    o2 = alpha[:, None] * o1 + np.exp(s2 - m2[:, None]) @ v2
+    p_full, lse_full = orc.softmax_rows(s)
+    np.testing.assert_allclose(o2 / l2[:, None], p_full @ v, atol=1e-13)
+    np.testing.assert_allclose(m2 + np.log(l2), lse_full, atol=1e-13)
+    # with the inverse as printed the identity must NOT hold (guards the reading)
+    bad = o1 / alpha[:, None] + np.exp(s2 - m2[:, None]) @ v2
+    assert np.max(np.abs(bad / l2[:, None] - p_full @ v)) > 1e-3
+
+
+# ----------------------------------------------------------------------------
+# backward: central finite differences through the scalar-loop forward
+# ----------------------------------------------------------------------------
+
+def fd_grad(q, k, v, do, scale, causal, which, h=1e-5):
+    arrs = {"q": q.copy(), "k": k.copy(), "v": v.copy()}
+    x = arrs[which]
+    g = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        old = x[idx]
+        x[idx] = old + h
+        fp = loss_of(arrs["q"], arrs["k"], arrs["v"], do, scale, causal)
+        x[idx] = old - h
+        fm = loss_of(arrs["q"], arrs["k"], arrs["v"], do, scale, causal)
+        x[idx] = old
+        g[idx] = (fp - fm) / (2 * h)
+    return g
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("n,d,scale", [(3, 2, 1.0), (6, 4, 0.5), (8, 3, 0.31)])
+def test_backward_matches_finite_differences(n, d, scale, causal):
+    q, k, v, do = rnd(40, n, d), rnd(41, n, d), rnd(42, n, d), rnd(43, n, d)
+    dq, dk, dv = orc.head_backward(q, k, v, do, scale, causal)
+    for got, which in ((dq, "q"), (dk, "k"), (dv, "v")):
+        ref = fd_grad(q, k, v, do, scale, causal, which)
+        err = np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref)))
+        assert err < 1e-6, (which, err)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_invariants(causal):
+    n, d = 17, 5
+    q, k, v, do = rnd(44, n, d), rnd(45, n, d), rnd(46, n, d), rnd(47, n, d)
+    dq, dk, dv = orc.head_backward(q, k, v, do, 0.45, causal)
+    # P rows sum to one => columns of dV sum to columns of dO
+    np.testing.assert_allclose(dv.sum(axis=0), do.sum(axis=0), atol=1e-12)
+    # softmax is shift invariant per row => each row of dS sums to zero =>
+    # dK summed over keys weighted... check through K-shift: f(K + c) = f(K)
+    # so the directional derivative of f along "all key rows += c" vanishes.
+    np.testing.assert_allclose(dk.sum(axis=0), 0.0, atol=1e-12)
+    # constant V => O independent of Q, K
+    vc = np.tile(rnd(48, d), (n, 1))
+    dq, dk, _ = orc.head_backward(q, k, vc, do, 0.45, causal)
+    np.testing.assert_allclose(dq, 0.0, atol=1e-12)
+    np.testing.assert_allclose(dk, 0.0, atol=1e-12)
+
+
+def test_planted_mistakes_are_caught_by_the_pins():
+    """Each mutant is one plausible slip in the backward; finite differences
+    must reject every one of them (so the pin set has teeth)."""
+    n, d, scale = 6, 4, 0.5
+    q, k, v, do = rnd(40, n, d), rnd(41, n, d), rnd(42, n, d), rnd(43, n, d)
+    refs = {w: fd_grad(q, k, v, do, scale, True, w) for w in "qkv"}
+    o, _, p = orc.head_forward(q, k, v, scale, True)
+    dp = do @ v.T
+    big_d = np.sum(do * o, axis=1, keepdims=True)
+    ds = p * (dp - big_d)
+    mutants = {
+        "no_scale_dq": (ds @ k, "q"),
+        "no_scale_dk": (ds.T @ q, "k"),
+        "dk_untransposed": (scale * (ds @ q), "k"),
+        "dv_untransposed": (p @ do, "v"),
+        "ds_without_D": (scale * ((p * dp) @ k), "q"),
+        "ds_sign": (scale * ((p * (big_d - dp)) @ k), "q"),
+    }
+    for name, (g, which) in mutants.items():
+        err = np.max(np.abs(g - refs[which])) / max(1.0, np.max(np.abs(refs[which])))
+        assert err > 1e-3, name
+
+
+# ----------------------------------------------------------------------------
+# batch wrappers: head mapping, GQA, ragged packing
+# ----------------------------------------------------------------------------
+
+def test_batch_wrapper_matches_per_head_brute_force():
+    B, N, H, d = 2, 5, 3, 2
+    Q, K, V = rnd(50, B, N, H, d), rnd(51, B, N, H, d), rnd(52, B, N, H, d)
+    O, L = orc.attention_forward(Q, K, V, 0.6, True)
+    assert O.shape == (B, N, H, d) and L.shape == (B, H, N)
+    for b in range(B):
+        for h in range(H):
+            bo, bl = brute_forward(Q[b, :, h].tolist(), K[b, :, h].tolist(), V[b, :, h].tolist(), 0.6, True)
+            np.testing.assert_allclose(O[b, :, h], np.asarray(bo), atol=1e-13)
+            np.testing.assert_allclose(L[b, h], np.asarray(bl), atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_gqa_equals_mha_on_repeated_kv_heads(causal):
+    B, N, Hq, Hkv, d = 2, 11, 6, 2, 4
+    G = Hq // Hkv
+    Q, dO = rnd(53, B, N, Hq, d), rnd(54, B, N, Hq, d)
+    K, V = rnd(55, B, N, Hkv, d), rnd(56, B, N, Hkv, d)
+    Kr, Vr = np.repeat(K, G, axis=2), np.repeat(V, G, axis=2)
+    O, L = orc.attention_forward(Q, K, V, 0.5, causal)
+    Or, Lr = orc.attention_forward(Q, Kr, Vr, 0.5, causal)
+    np.testing.assert_allclose(O, Or, atol=1e-14)
+    np.testing.assert_allclose(L, Lr, atol=1e-14)
+    dQ, dK, dV = orc.attention_backward(Q, K, V, dO, 0.5, causal)
+    dQr, dKr, dVr = orc.attention_backward(Q, Kr, Vr, dO, 0.5, causal)
+    np.testing.assert_allclose(dQ, dQr, atol=1e-13)
+    np.testing.assert_allclose(dK, dKr.reshape(B, N, Hkv, G, d).sum(axis=3), atol=1e-13)
+    np.testing.assert_allclose(dV, dVr.reshape(B, N, Hkv, G, d).sum(axis=3), atol=1e-13)
+
+
+def test_gqa_backward_matches_finite_differences():
+    B, N, Hq, Hkv, d, scale = 1, 4, 4, 2, 2, 0.7
+    Q, dO = rnd(57, B, N, Hq, d), rnd(58, B, N, Hq, d)
+    K, V = rnd(59, B, N, Hkv, d), rnd(60, B, N, Hkv, d)
+    dQ, dK, dV = orc.attention_backward(Q, K, V, dO, scale, True)
+
+    def f(Kx, Vx):
+        tot = 0.0
+        for h in range(Hq):
+            tot += loss_of(Q[0, :, h], Kx[0, :, h // 2], Vx[0, :, h // 2], dO[0, :, h], scale, True)
+        return tot
+
+    h = 1e-5
+    for arr, grad, isk in ((K, dK, True), (V, dV, False)):
+        for idx in np.ndindex(*arr.shape):
+            x = arr.copy()
+            x[idx] += h
+            fp = f(x, V) if isk else f(K, x)
+            x[idx] -= 2 * h
+            fm = f(x, V) if isk else f(K, x)
+            assert abs((fp - fm) / (2 * h) - grad[idx]) < 1e-6
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_ragged_equals_per_sequence_and_sequences_do_not_interact(causal):
+    lens = [3, 1, 7, 4]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, Hq, Hkv, d = int(cu[-1]), 4, 2, 3
+    Q, dO = rnd(61, T, Hq, d), rnd(62, T, Hq, d)
+    K, V = rnd(63, T, Hkv, d), rnd(64, T, Hkv, d)
+    O, L = orc.varlen_forward(Q, K, V, cu, 0.5, causal)
+    dQ, dK, dV = orc.varlen_backward(Q, K, V, dO, cu, 0.5, causal)
+    for s in range(len(lens)):
+        a, e = cu[s], cu[s + 1]
+        o, l = orc.attention_forward(Q[None, a:e], K[None, a:e], V[None, a:e], 0.5, causal)
+        np.testing.assert_array_equal(O[a:e], o[0])
+        np.testing.assert_array_equal(L[:, a:e], l[0])
+        dq, dk, dv = orc.attention_backward(Q[None, a:e], K[None, a:e], V[None, a:e], dO[None, a:e], 0.5, causal)
+        np.testing.assert_array_equal(dQ[a:e], dq[0])
+        np.testing.assert_array_equal(dK[a:e], dk[0])
+        np.testing.assert_array_equal(dV[a:e], dv[0])
+    # perturb sequence 2: every other sequence's outputs stay bit-identical
+    K2, V2 = K.copy(), V.copy()
+    K2[cu[2]:cu[3]] += 1.0
+    V2[cu[2]:cu[3]] -= 2.0
+    O2, L2 = orc.varlen_forward(Q, K2, V2, cu, 0.5, causal)
+    keep = np.ones(T, dtype=bool)
+    keep[cu[2]:cu[3]] = False
+    np.testing.assert_array_equal(O2[keep], O[keep])
+    np.testing.assert_array_equal(L2[:, keep], L[:, keep])
+    assert not np.array_equal(O2[~keep], O[~keep])
+
+
+def test_empty_sequence_in_ragged_batch():
+    cu = np.asarray([0, 4, 4, 6], dtype=np.int32)
+    Q, K, V = rnd(65, 6, 2, 3), rnd(66, 6, 2, 3), rnd(67, 6, 2, 3)
+    O, L = orc.varlen_forward(Q, K, V, cu, 0.5, True)
+    o, l = orc.attention_forward(Q[None, 4:6], K[None, 4:6], V[None, 4:6], 0.5, True)
+    np.testing.assert_array_equal(O[4:6], o[0])
+
+
+def test_rows_forward_is_a_restriction_of_the_full_forward():
+    n, d = 23, 6
+    q, k, v = rnd(68, n, d), rnd(69, n, d), rnd(70, n, d)
+    rows = np.asarray([0, 5, 22])
+    for causal in (False, True):
+        o, lse, _ = orc.head_forward(q, k, v, 0.4, causal)
+        ro, rl = orc.rows_forward(q[rows], rows, k, v, 0.4, causal)
+        np.testing.assert_allclose(ro, o[rows], atol=1e-14)
+        np.testing.assert_allclose(rl, lse[rows], atol=1e-14)
+
+
+def test_widen_bf16_is_exact():
+    bits = np.asarray([0x3F80, 0xBF80, 0x4000, 0x0000, 0x3DCD, 0x7F7F], dtype=np.uint16)
+    got = orc.widen_bf16(bits)
+    exp = [1.0, -1.0, 2.0, 0.0, float(np.float32(0.10009765625)), 3.3895313892515355e38]
+    np.testing.assert_array_equal(got, np.asarray(exp))
