@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+fa_fwd (Algorithm 1) followed by fa_bwd (Algorithm 2: prep, main, convert) on
+the workload named in `config.workload`, inputs resident in HBM. Throughput is
+counted with the paper's formula (section 4.1): forward 4*N^2*d FLOPs per head
+and sequence, halved under the causal mask, backward 2.5x that.
+
+Prints ONE JSON line. Besides the contract fields it carries
+  roofline     - the dominant kernel (backward main) against the bf16 MFMA peak,
+                 its duration measured with HIP events inside the timed loop;
+  roofline_fwd - the same for the forward kernel;
+  cpu_baseline - the float64 oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+
+
+def cpu_baseline(prob, budget_units: int = 1):
+    """Time the float64 oracle (forward + backward) on `budget_units`
+    (sequence, head) units of the workload, all host cores, and scale to the
+    metric's unit with the same FLOP formula."""
+    import numpy as np
+    from oracle import attention_oracle as orc
+
+    cores = len(os.sched_getaffinity(0))
+    G = prob.Hq // prob.Hkv
+    units = [(0, 0)][:budget_units]
+    t0 = time.perf_counter()
+    for (b, h) in units:
+        q = orc.widen_bf16(prob.Q[b, :, h])
+        k = orc.widen_bf16(prob.K[b, :, h // G])
+        v = orc.widen_bf16(prob.V[b, :, h // G])
+        do = orc.widen_bf16(prob.dO[b, :, h])
+        orc.head_backward(q, k, v, do, prob.scale, prob.causal)  # recomputes the forward inside
+    dt = time.perf_counter() - t0
+    per_unit = 3.5 * (4.0 * prob.N ** 2 * prob.d) * (0.5 if prob.causal else 1.0)
+    return {
+        "value": per_unit * len(units) / dt / 1e12,
+        "unit": "TFLOPs/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"{len(units)} of {prob.B * prob.Hq} (sequence, head) units of {prob.name}, forward+backward, "
+                  f"float64 numpy, {dt:.1f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="d128_n8k_causal")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fwd-only", action="store_true", help="profiling aid: time the forward alone")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2307_08691_amd import binding, inputs
+
+    binding.load()
+    torch.cuda.set_device(0)
+    prob = inputs.make_config(args.workload)
+    if prob.varlen:
+        print("bench.py: pick a dense workload", file=sys.stderr)
+        return 2
+
+    def gpu(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    Q, K, V, dO = (gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    B, N, Hq, d = Q.shape
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    ws = torch.empty(binding.fa_bwd_workspace_bytes(B, Hq, prob.Hkv, N, d), dtype=torch.uint8, device="cuda")
+    sc, ca = prob.scale, prob.causal
+
+    def step(ev=None):
+        """fa_fwd + the three backward launches, in the order fa_bwd issues them; with `ev`
+        the forward kernel and the backward main kernel are bracketed by events."""
+        if ev:
+            ev[0].record()
+        binding.fa_fwd(Q, K, V, sc, ca, O=O, LSE=LSE)
+        if ev:
+            ev[1].record()
+        if args.fwd_only:
+            return
+        binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 1, dQ, dK, dV, ws)
+        if ev:
+            ev[2].record()
+        binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 2, dQ, dK, dV, ws)
+        if ev:
+            ev[3].record()
+        binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 4, dQ, dK, dV, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # events are recorded on torch's current stream, the one the kernels are launched on
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    fwd_fl, bwd_fl = prob.fwd_flops(), prob.bwd_flops()
+    total_fl = fwd_fl if args.fwd_only else fwd_fl + bwd_fl
+    value = total_fl / (ms_per_step * 1e-3) / 1e12
+
+    def roof(flops, ms):
+        ach = flops / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_kernel_ms": ms}
+
+    out = {
+        "metric": "attention fwd+bwd TFLOPs/s (bf16)" if not args.fwd_only else "attention fwd TFLOPs/s (bf16)",
+        "value": value,
+        "unit": "TFLOPs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": prob.name, "B": B, "N": N, "Hq": Hq, "Hkv": prob.Hkv, "d": d, "causal": ca,
+                   "scale": sc, "fwd_flops": fwd_fl, "bwd_flops": bwd_fl},
+        "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
+        "roofline_fwd": dict(roof(fwd_fl, fwd_ms), kernel="fwd_kernel"),
+    }
+    if not args.fwd_only:
+        main_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+        out["roofline"] = dict(roof(bwd_fl, main_ms), kernel="bwd_kernel")
+    else:
+        out["roofline"] = out["roofline_fwd"]
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(prob)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,132 @@
+/*
+ * fa.h - C ABI of the MI355X (gfx950) exact-attention library.
+ *
+ * The library computes scaled-dot-product attention
+ *     O = softmax(scale * Q K^T [+ causal mask]) V
+ * and its gradients tile by tile with an online softmax, so the N x N score and
+ * probability matrices are never written to device memory (Algorithm 1 and
+ * Algorithm 2 of the paper; problem statement in section 2.2).
+ *
+ * Conventions common to every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller. The library
+ *     never allocates, frees or retains memory and never synchronises: work is
+ *     enqueued on `stream` (a hipStream_t handle passed as void*, NULL = the
+ *     default stream) and the call returns at once.
+ *   - Element type of Q, K, V, O, dO, dQ, dK, dV is bfloat16 (2 bytes). LSE and
+ *     the workspace are float32. All tensor pointers must be 16-byte aligned.
+ *   - Dense layout (token-major, head dim contiguous, no padding):
+ *         Q, O, dO, dQ : [B, N, Hq,  d]
+ *         K, V, dK, dV : [B, N, Hkv, d]
+ *         LSE          : [B, Hq, N]
+ *     Packed ragged layout: the tokens of all sequences are concatenated,
+ *     T = cu_seqlens[nseq]; sequence s owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1:
+ *         Q, O, dO, dQ : [T, Hq,  d]
+ *         K, V, dK, dV : [T, Hkv, d]
+ *         LSE          : [Hq, T]
+ *   - Supported: d in {64, 128}; Hq a positive multiple of Hkv (grouped-query
+ *     attention: query head h reads key/value head h / (Hq/Hkv), paragraph
+ *     "Multi-query attention and grouped-query attention" of section 3.1);
+ *     scale > 0; self-attention (one length per sequence).
+ *   - causal != 0 masks score (r, c) with c > r inside each sequence
+ *     (section 3.1.1, "Causal masking").
+ *   - Return value: FA_OK or a negative FA_ERR_* code. Arguments are validated
+ *     before anything is launched, so an error return means nothing ran.
+ *     Inputs are never written. Outputs are fully overwritten (gradients are
+ *     not accumulated into). Calls on different streams may overlap as long as
+ *     they do not share output or workspace buffers.
+ */
+#ifndef FA_H_
+#define FA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FA_OK 0
+#define FA_ERR_NULL (-1)        /* a required pointer is NULL */
+#define FA_ERR_SHAPE (-2)       /* non-positive dimension, Hq % Hkv != 0, scale <= 0 or not finite,
+                                   inconsistent ragged description */
+#define FA_ERR_UNSUPPORTED (-3) /* head dim not in {64, 128} */
+#define FA_ERR_ALIGN (-4)       /* a tensor pointer is not 16-byte aligned */
+#define FA_ERR_WORKSPACE (-5)   /* workspace smaller than fa_*_workspace_bytes() */
+#define FA_ERR_LAUNCH (-6)      /* the HIP runtime refused a launch; see fa_last_hip_error() */
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int fa_version(void);
+
+/* Static, NUL-terminated description of a status code. Never NULL. */
+const char* fa_status_string(int status);
+
+/* Numeric hipError_t of the most recent failed launch on this thread (0 if none). */
+int fa_last_hip_error(void);
+
+/*
+ * Forward pass (Algorithm 1): O and the row-wise logsumexp
+ *     LSE[b, h, r] = log sum_c exp(scale * q_r . k_c)   (natural log, masked columns excluded)
+ * which is the only softmax statistic the backward pass needs (section 3.1.1,
+ * second tweak). Dense layout.
+ */
+int fa_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+           int B, int Hq, int Hkv, int N, int d, float scale, int causal, void* stream);
+
+/*
+ * Backward pass (Algorithm 2). Needs the O and LSE that fa_fwd produced for the
+ * same Q, K, V, scale and causal flag. Writes dQ, dK, dV (bfloat16).
+ * `workspace` is device scratch of at least fa_bwd_workspace_bytes() bytes,
+ * 16-byte aligned; its contents are undefined on entry and on return. It holds
+ * D = rowsum(dO o O) (Algorithm 2, line 4) and a float32 accumulator for dQ,
+ * into which the column-block workgroups add their partial products with
+ * atomic adds (section 3.2, "Backward pass"); dQ is therefore reproducible only
+ * up to float32 summation order, dK and dV are bit-reproducible.
+ */
+size_t fa_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int d);
+int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+           const float* LSE, void* dQ, void* dK, void* dV,
+           void* workspace, size_t workspace_bytes,
+           int B, int Hq, int Hkv, int N, int d, float scale, int causal, void* stream);
+
+/*
+ * Profiling aid: fa_bwd restricted to a subset of its three launches, so that
+ * each can be timed on its own. `stages` is a bit mask; fa_bwd equals
+ * FA_STAGE_PREP | FA_STAGE_MAIN | FA_STAGE_CONVERT. The main stage adds into
+ * the accumulator the prep stage zeroes, so a correct dQ needs all three, in
+ * that order, with the same arguments. Same validation and errors as fa_bwd;
+ * stages == 0 or bits outside the mask return FA_ERR_SHAPE.
+ */
+#define FA_STAGE_PREP 1    /* D = rowsum(dO o O); zero the dQ accumulator (Algorithm 2, lines 3-4) */
+#define FA_STAGE_MAIN 2    /* the column-block loop (Algorithm 2, lines 5-19) */
+#define FA_STAGE_CONVERT 4 /* dQ = bf16(scale * accumulator) */
+int fa_bwd_stages(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                  const float* LSE, void* dQ, void* dK, void* dV,
+                  void* workspace, size_t workspace_bytes,
+                  int B, int Hq, int Hkv, int N, int d, float scale, int causal, int stages,
+                  void* stream);
+
+/*
+ * Packed ragged batch (not in the paper; each sequence is an independent
+ * attention problem of Algorithm 1 / Algorithm 2). `cu_seqlens` is a DEVICE
+ * array of nseq + 1 non-decreasing int32 offsets starting at 0;
+ * `total_tokens` must equal cu_seqlens[nseq] and `max_seqlen` must be at least
+ * the longest sequence (both are host-side copies the caller already has; the
+ * library does not read the device array on the host). Empty sequences are
+ * allowed. Rows of an output that belong to no sequence do not exist, so every
+ * output row is written.
+ */
+int fa_varlen_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                  const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                  int Hq, int Hkv, int d, float scale, int causal, void* stream);
+
+size_t fa_varlen_bwd_workspace_bytes(int total_tokens, int Hq, int Hkv, int d);
+int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                  const float* LSE, void* dQ, void* dK, void* dV,
+                  void* workspace, size_t workspace_bytes,
+                  const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                  int Hq, int Hkv, int d, float scale, int causal, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FA_H_ */

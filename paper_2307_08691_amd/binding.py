@@ -1,0 +1,228 @@
+"""Thin ctypes binding over the C ABI declared in include/fa.h.
+
+Argument marshalling only: every step of attention runs in the HIP kernels of
+libfa_gfx950.so. torch is used for device memory and the current stream. There
+is no fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfa_gfx950.so")
+
+FA_OK = 0
+FA_ERR_NULL = -1
+FA_ERR_SHAPE = -2
+FA_ERR_UNSUPPORTED = -3
+FA_ERR_ALIGN = -4
+FA_ERR_WORKSPACE = -5
+FA_ERR_LAUNCH = -6
+
+_c_int = ctypes.c_int
+_c_void_p = ctypes.c_void_p
+_c_float = ctypes.c_float
+_c_size_t = ctypes.c_size_t
+
+# name -> (restype, argtypes); mirrors include/fa.h one to one
+SIGNATURES = {
+    "fa_version": (_c_int, []),
+    "fa_status_string": (ctypes.c_char_p, [_c_int]),
+    "fa_last_hip_error": (_c_int, []),
+    "fa_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_float, _c_int, _c_void_p]),
+    "fa_bwd_workspace_bytes": (_c_size_t, [_c_int] * 5),
+    "fa_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 5 + [_c_float, _c_int, _c_void_p]),
+    "fa_bwd_stages": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 5 +
+                      [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_varlen_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_bwd_workspace_bytes": (_c_size_t, [_c_int] * 4),
+    "fa_varlen_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
+                      [_c_float, _c_int, _c_void_p]),
+}
+
+_lib = None
+
+
+class FaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"fa status {status}: {message}")
+        self.status = status
+
+
+def load() -> ctypes.CDLL:
+    """Load the shared library (once). Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2307_08691_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().fa_status_string(status).decode()
+
+
+def _check(status: int) -> None:
+    if status != FA_OK:
+        raise FaError(status, status_string(status))
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def fa_version() -> int:
+    return load().fa_version()
+
+
+# ---------------------------------------------------------------------------
+# raw calls: pointers and sizes in, status out (used by the error-path tests)
+# ---------------------------------------------------------------------------
+
+def fa_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, N, d, scale, causal, stream=0) -> int:
+    return load().fa_fwd(Q, K, V, O, LSE, B, Hq, Hkv, N, d, scale, int(causal), stream)
+
+
+def fa_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, causal, stream=0) -> int:
+    return load().fa_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, int(causal), stream)
+
+
+def fa_bwd_stages_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, causal, stages,
+                      stream=0) -> int:
+    return load().fa_bwd_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, int(causal),
+                                stages, stream)
+
+
+def fa_varlen_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, causal, stream=0) -> int:
+    return load().fa_varlen_fwd(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, int(causal), stream)
+
+
+def fa_varlen_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale,
+                      causal, stream=0) -> int:
+    return load().fa_varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv,
+                                d, scale, int(causal), stream)
+
+
+def fa_bwd_workspace_bytes(B, Hq, Hkv, N, d) -> int:
+    return load().fa_bwd_workspace_bytes(B, Hq, Hkv, N, d)
+
+
+def fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d) -> int:
+    return load().fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d)
+
+
+# ---------------------------------------------------------------------------
+# tensor-level wrappers: same names as the C entry points
+# ---------------------------------------------------------------------------
+
+def _need(t, name, dtype=None):
+    import torch
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}")
+
+
+def fa_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None) -> Tuple["torch.Tensor", "torch.Tensor"]:
+    """Dense forward. Q [B,N,Hq,d], K,V [B,N,Hkv,d] bf16 -> O [B,N,Hq,d] bf16, LSE [B,Hq,N] fp32."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    B, N, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    if K.shape != (B, N, Hkv, d) or V.shape != K.shape:
+        raise ValueError("K, V must be [B, N, Hkv, d]")
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq, N), dtype=torch.float32, device=Q.device)
+    _check(fa_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, N, d, scale, causal, _stream()))
+    return O, LSE
+
+
+def fa_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
+    """Dense backward. Returns dQ [B,N,Hq,d], dK, dV [B,N,Hkv,d] (bf16)."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    _need(LSE, "LSE", torch.float32)
+    B, N, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    nbytes = fa_bwd_workspace_bytes(B, Hq, Hkv, N, d)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    _check(fa_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                      _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, N, d, scale, causal,
+                      _stream()))
+    return dQ, dK, dV
+
+
+def fa_bwd_stages(Q, K, V, O, dO, LSE, scale: float, causal: bool, stages: int, dQ, dK, dV, workspace) -> None:
+    """Profiling aid: run the selected stages (1 prep | 2 main | 4 convert) of the dense backward."""
+    B, N, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    _check(fa_bwd_stages_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, N, d, scale,
+                             causal, stages, _stream()))
+
+
+def fa_varlen_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, causal: bool, O=None, LSE=None):
+    """Packed ragged forward. Q [T,Hq,d], K,V [T,Hkv,d] bf16, cu_seqlens int32 on the GPU.
+    Returns O [T,Hq,d] bf16 and LSE [Hq,T] fp32."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    _need(cu_seqlens, "cu_seqlens", torch.int32)
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    nseq = cu_seqlens.numel() - 1
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((Hq, T), dtype=torch.float32, device=Q.device)
+    _check(fa_varlen_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), nseq, T, max_seqlen,
+                             Hq, Hkv, d, scale, causal, _stream()))
+    return O, LSE
+
+
+def fa_varlen_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, causal: bool,
+                  dQ=None, dK=None, dV=None, workspace=None):
+    """Packed ragged backward. Returns dQ [T,Hq,d], dK, dV [T,Hkv,d] (bf16)."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    _need(LSE, "LSE", torch.float32)
+    _need(cu_seqlens, "cu_seqlens", torch.int32)
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    nseq = cu_seqlens.numel() - 1
+    nbytes = fa_varlen_bwd_workspace_bytes(T, Hq, Hkv, d)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    _check(fa_varlen_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(cu_seqlens), nseq, T,
+                             max_seqlen, Hq, Hkv, d, scale, causal, _stream()))
+    return dQ, dK, dV

@@ -1,0 +1,197 @@
+// C ABI of the attention library: argument validation, workspace carving, launches.
+#include "../../include/fa.h"
+#include "fa_kernels.h"
+
+#include <cmath>
+#include <cstdlib>
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_common(int Hq, int Hkv, int d, float scale) {
+  if (Hq <= 0 || Hkv <= 0 || d <= 0) return FA_ERR_SHAPE;
+  if (Hq % Hkv != 0) return FA_ERR_SHAPE;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return FA_ERR_SHAPE;
+  if (d != 64 && d != 128) return FA_ERR_UNSUPPORTED;
+  return FA_OK;
+}
+
+fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Hq, int Hkv, long total, float scale) {
+  fa::Problem p;
+  p.cu_seqlens = cu;
+  p.nseq = nseq;
+  p.N = N;
+  p.Hq = Hq;
+  p.Hkv = Hkv;
+  p.G = Hq / Hkv;
+  p.total_tokens = (int)total;
+  p.lse_seq_stride = cu ? 0 : (long)Hq * N;
+  p.lse_head_stride = cu ? total : N;
+  p.scale = scale;
+  p.scale_log2e = scale * fa::kLog2e;
+  return p;
+}
+
+// Row-block shape of the forward kernel. FA_FWD_NQ=1|2 overrides it for tuning runs.
+int pick_fwd_nq(int d, int max_n) {
+  if (const char* e = std::getenv("FA_FWD_NQ")) {
+    int v = std::atoi(e);
+    if (v == 1 || v == 2) return v;
+  }
+  (void)d;
+  (void)max_n;
+  return 1;
+}
+
+size_t ws_bytes(long tokens, int Hq, int d) {
+  size_t dvec = round_up((size_t)tokens * Hq * sizeof(float), 256);
+  size_t dq = (size_t)tokens * Hq * d * sizeof(float);
+  return dvec + dq;
+}
+
+int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
+            long total, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
+  fa::FwdArgs a;
+  a.p = make_problem(cu, nseq, N, Hq, Hkv, total, scale);
+  a.Q = (const __bf16*)Q;
+  a.K = (const __bf16*)K;
+  a.V = (const __bf16*)V;
+  a.O = (__bf16*)O;
+  a.LSE = LSE;
+  a.cfg_nq = pick_fwd_nq(d, N);
+  hipError_t e = fa::launch_fwd(a, d, causal, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
+int run_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE, void* dQ,
+            void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, long total, int Hq, int Hkv, int d,
+            float scale, int causal, int stages, void* stream) {
+  fa::BwdArgs a;
+  a.p = make_problem(cu, nseq, N, Hq, Hkv, total, scale);
+  a.Q = (const __bf16*)Q;
+  a.K = (const __bf16*)K;
+  a.V = (const __bf16*)V;
+  a.O = (const __bf16*)O;
+  a.dO = (const __bf16*)dO;
+  a.LSE = LSE;
+  a.dQ = (__bf16*)dQ;
+  a.dK = (__bf16*)dK;
+  a.dV = (__bf16*)dV;
+  a.Dvec = (float*)ws;
+  a.dQacc = (float*)((char*)ws + round_up((size_t)total * Hq * sizeof(float), 256));
+  hipError_t e = fa::launch_bwd(a, d, causal, stages, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fa_version(void) { return 100; }
+
+const char* fa_status_string(int status) {
+  switch (status) {
+    case FA_OK: return "ok";
+    case FA_ERR_NULL: return "a required pointer is NULL";
+    case FA_ERR_SHAPE: return "invalid shape, head grouping, scale or ragged description";
+    case FA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are supported)";
+    case FA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+    case FA_ERR_WORKSPACE: return "workspace too small";
+    case FA_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status";
+  }
+}
+
+int fa_last_hip_error(void) { return g_last_hip_error; }
+
+int fa_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N, int d,
+           float scale, int causal, void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (B <= 0 || N <= 0) return FA_ERR_SHAPE;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if ((long)B * N > 0x7fffffffL) return FA_ERR_SHAPE;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  return run_fwd(Q, K, V, O, LSE, nullptr, B, N, (long)B * N, Hq, Hkv, d, scale, causal, stream);
+}
+
+size_t fa_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int d) {
+  (void)Hkv;
+  if (B <= 0 || Hq <= 0 || N <= 0 || d <= 0) return 0;
+  return ws_bytes((long)B * N, Hq, d);
+}
+
+int fa_bwd_stages(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                  void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int N,
+                  int d, float scale, int causal, int stages, void* stream) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (B <= 0 || N <= 0) return FA_ERR_SHAPE;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if ((long)B * N > 0x7fffffffL) return FA_ERR_SHAPE;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes((long)B * N, Hq, d)) return FA_ERR_WORKSPACE;
+  if (stages <= 0 || (stages & ~7)) return FA_ERR_SHAPE;
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, N, (long)B * N, Hq, Hkv, d, scale, causal,
+                 stages, stream);
+}
+
+int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE, void* dQ,
+           void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int N, int d,
+           float scale, int causal, void* stream) {
+  return fa_bwd_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, N, d, scale, causal,
+                       FA_STAGE_PREP | FA_STAGE_MAIN | FA_STAGE_CONVERT, stream);
+}
+
+static int check_varlen(const int32_t* cu, int nseq, int total_tokens, int max_seqlen) {
+  if (!cu) return FA_ERR_NULL;
+  if (nseq <= 0 || total_tokens <= 0 || max_seqlen <= 0) return FA_ERR_SHAPE;
+  if (max_seqlen > total_tokens) return FA_ERR_SHAPE;
+  if ((long)max_seqlen * nseq < (long)total_tokens) return FA_ERR_SHAPE;  // lengths cannot add up
+  return FA_OK;
+}
+
+int fa_varlen_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
+                  int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
+                  void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  return run_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, max_seqlen, total_tokens, Hq, Hkv, d, scale, causal, stream);
+}
+
+size_t fa_varlen_bwd_workspace_bytes(int total_tokens, int Hq, int Hkv, int d) {
+  (void)Hkv;
+  if (total_tokens <= 0 || Hq <= 0 || d <= 0) return 0;
+  return ws_bytes(total_tokens, Hq, d);
+}
+
+int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                  void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, const int32_t* cu_seqlens,
+                  int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
+                  void* stream) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes(total_tokens, Hq, d)) return FA_ERR_WORKSPACE;
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, cu_seqlens, nseq, max_seqlen, total_tokens, Hq, Hkv, d,
+                 scale, causal, 7, stream);
+}
+
+}  // extern "C"

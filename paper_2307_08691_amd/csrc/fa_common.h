@@ -1,0 +1,135 @@
+// Shared device-side helpers for the gfx950 attention kernels: vector types,
+// MFMA wrappers and the lane layouts they imply.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fa {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Problem description shared by the forward and backward kernels. A "sequence"
+// is one batch entry (dense) or one entry of cu_seqlens (packed ragged).
+struct Problem {
+  const int32_t* cu_seqlens;  // device, nseq + 1 entries; nullptr for the dense layout
+  int nseq;                   // number of sequences (dense: batch size)
+  int N;                      // dense: sequence length; ragged: upper bound on any length
+  int Hq, Hkv, G;             // G = Hq / Hkv
+  int total_tokens;
+  long lse_seq_stride;        // dense: Hq * N, ragged: 0
+  long lse_head_stride;       // dense: N, ragged: total_tokens
+  float scale;                // softmax scaling
+  float scale_log2e;          // scale * log2(e)
+};
+
+struct SeqInfo {
+  long tok0;  // first token row of the sequence in the packed [tokens, H, d] view
+  int n;      // its length
+};
+
+__device__ __forceinline__ SeqInfo seq_info(const Problem& p, int s) {
+  SeqInfo r;
+  if (p.cu_seqlens) {
+    int a = p.cu_seqlens[s];
+    r.tok0 = a;
+    r.n = p.cu_seqlens[s + 1] - a;
+  } else {
+    r.tok0 = (long)s * p.N;
+    r.n = p.N;
+  }
+  return r;
+}
+
+// D = A(32 x 16) * B(16 x 32) + C on one wavefront, bf16 inputs, fp32 accumulate.
+// Lane l supplies A[l % 32][8 * (l / 32) + t] and B[8 * (l / 32) + t][l % 32], t = 0..7,
+// and owns C[8 * (r / 4) + 4 * (l / 32) + (r % 4)][l % 32] in register r = 0..15.
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of the 32 x 32 accumulator tile that register r of lane-half hh holds.
+__device__ __forceinline__ constexpr int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Transposing LDS read (ds_read_b64_tr_b16). Within each group of 16 lanes,
+// lane p passes the address of 4 consecutive 16-bit elements; lane i receives,
+// in slot t, element (i % 4) of the four that lane (i / 4 + 4 * t) pointed at.
+__device__ __forceinline__ s16x4 lds_read_tr(const __bf16* ptr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)ptr);
+}
+
+// Build a 32 x 16 (rows x contraction) MFMA operand whose rows are COLUMNS
+// col0 .. col0+31 of a row-major LDS tile and whose 16 contraction slots are
+// tile rows row0 + {4*hh + 0..3, 8 + 4*hh + 0..3} for lane-half hh: exactly the
+// row set that registers 8s .. 8s+7 of a 32 x 32 accumulator cover, so an
+// accumulator tile (cast to bf16) can be contracted against it without moving
+// data between lanes. `stride` is the LDS row pitch in elements.
+__device__ __forceinline__ bf16x8 lds_frag_transposed(const __bf16* tile, int stride, int row0, int col0, int lane) {
+  const int p = lane & 15, g16 = (lane >> 4) & 1, hh = lane >> 5;
+  const __bf16* a = tile + (row0 + 4 * hh + (p >> 2)) * stride + col0 + 16 * g16 + 4 * (p & 3);
+  s16x4 lo = lds_read_tr(a);
+  s16x4 hi = lds_read_tr(a + 8 * stride);
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Plain operand: rows are tile rows row0 + (lane % 32), contraction slots are 8
+// consecutive columns starting at col0 + 8 * (lane / 32).
+__device__ __forceinline__ bf16x8 lds_frag(const __bf16* tile, int stride, int row0, int col0, int lane) {
+  return *(const bf16x8*)(tile + (row0 + (lane & 31)) * stride + col0 + 8 * (lane >> 5));
+}
+
+// Exchange a value between lane l and lane l ^ 32 and return the partner's.
+__device__ __forceinline__ float partner32(float x) {
+  int xi = __builtin_bit_cast(int, x);
+  auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  int lo = sw[0], hi = sw[1];
+  // lanes < 32 see (own, partner); lanes >= 32 see (partner, own)
+  return __builtin_bit_cast(float, (threadIdx.x & 32) ? lo : hi);
+}
+
+__device__ __forceinline__ float max_with_partner32(float x) {
+  int xi = __builtin_bit_cast(int, x);
+  auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  return fmaxf(__builtin_bit_cast(float, (int)sw[0]), __builtin_bit_cast(float, (int)sw[1]));
+}
+
+__device__ __forceinline__ float sum_with_partner32(float x) {
+  int xi = __builtin_bit_cast(int, x);
+  auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  return __builtin_bit_cast(float, (int)sw[0]) + __builtin_bit_cast(float, (int)sw[1]);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// Registers 8s .. 8s+7 of an accumulator tile, rounded to bf16, as an MFMA operand.
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int s) {
+  u32x4 r;
+  r[0] = pack_bf16(v[8 * s + 0], v[8 * s + 1]);
+  r[1] = pack_bf16(v[8 * s + 2], v[8 * s + 3]);
+  r[2] = pack_bf16(v[8 * s + 4], v[8 * s + 5]);
+  r[3] = pack_bf16(v[8 * s + 6], v[8 * s + 7]);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+}  // namespace fa

@@ -1,0 +1,36 @@
+// Internal interface between the C ABI (fa_api.hip) and the kernel files.
+#pragma once
+#include "fa_common.h"
+
+namespace fa {
+
+struct FwdArgs {
+  Problem p;
+  const __bf16* Q;
+  const __bf16* K;
+  const __bf16* V;
+  __bf16* O;
+  float* LSE;
+  int cfg_nq;  // 32-row query tiles per wavefront (1 or 2): row block = 128 * cfg_nq
+};
+
+struct BwdArgs {
+  Problem p;
+  const __bf16* Q;
+  const __bf16* K;
+  const __bf16* V;
+  const __bf16* O;
+  const __bf16* dO;
+  const float* LSE;
+  __bf16* dQ;
+  __bf16* dK;
+  __bf16* dV;
+  float* Dvec;   // workspace: rowsum(dO o O), laid out like LSE
+  float* dQacc;  // workspace: float32 accumulator for dQ, [tokens, Hq, d]
+};
+
+hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st);
+// stages: bit 0 prep, bit 1 main, bit 2 convert
+hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st);
+
+}  // namespace fa

@@ -1,0 +1,123 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function that
+include/fa.h declares, and rejects bad arguments before anything is launched
+(no GPU is touched: validation precedes every HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2307_08691_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fa.h")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(fa_[a-z_]+)\s*\(", src)))
+
+
+def test_header_declares_the_entry_points():
+    names = declared_functions()
+    for must in ("fa_fwd", "fa_bwd", "fa_bwd_workspace_bytes", "fa_varlen_fwd", "fa_varlen_bwd",
+                 "fa_varlen_bwd_workspace_bytes", "fa_version", "fa_status_string", "fa_last_hip_error"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol_and_binding_covers_them():
+    lib = binding.load()
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+        assert name in binding.SIGNATURES, name
+    assert sorted(binding.SIGNATURES) == declared_functions()
+
+
+def test_version_and_status_strings():
+    assert binding.fa_version() >= 100
+    seen = set()
+    for code in range(0, -7, -1):
+        s = binding.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert binding.status_string(-99) == "unknown status"
+
+
+P = 0x10000  # a non-null, 16-byte aligned fake device address; never dereferenced on these paths
+
+
+def fwd(Q=P, K=P, V=P, O=P, L=P, B=1, Hq=2, Hkv=2, N=128, d=64, scale=0.125, causal=0):
+    return binding.fa_fwd_raw(Q, K, V, O, L, B, Hq, Hkv, N, d, scale, causal, 0)
+
+
+def bwd(ptrs=None, ws=P, ws_bytes=1 << 30, B=1, Hq=2, Hkv=2, N=128, d=64, scale=0.125, causal=0):
+    ptrs = ptrs or [P] * 9
+    return binding.fa_bwd_raw(*ptrs, ws, ws_bytes, B, Hq, Hkv, N, d, scale, causal, 0)
+
+
+def test_fwd_rejects_bad_arguments():
+    assert fwd(Q=0) == binding.FA_ERR_NULL
+    assert fwd(L=0) == binding.FA_ERR_NULL
+    assert fwd(B=0) == binding.FA_ERR_SHAPE
+    assert fwd(N=-3) == binding.FA_ERR_SHAPE
+    assert fwd(Hq=3, Hkv=2) == binding.FA_ERR_SHAPE
+    assert fwd(Hkv=0) == binding.FA_ERR_SHAPE
+    assert fwd(scale=0.0) == binding.FA_ERR_SHAPE
+    assert fwd(scale=-1.0) == binding.FA_ERR_SHAPE
+    assert fwd(scale=float("nan")) == binding.FA_ERR_SHAPE
+    assert fwd(scale=float("inf")) == binding.FA_ERR_SHAPE
+    assert fwd(d=96) == binding.FA_ERR_UNSUPPORTED
+    assert fwd(d=256) == binding.FA_ERR_UNSUPPORTED
+    assert fwd(K=P + 2) == binding.FA_ERR_ALIGN
+    assert fwd(O=P + 8) == binding.FA_ERR_ALIGN
+
+
+def test_bwd_rejects_bad_arguments():
+    for i in range(9):
+        ptrs = [P] * 9
+        ptrs[i] = 0
+        assert bwd(ptrs) == binding.FA_ERR_NULL
+    assert bwd(ws=0) == binding.FA_ERR_NULL
+    assert bwd(Hq=4, Hkv=3) == binding.FA_ERR_SHAPE
+    assert bwd(d=32) == binding.FA_ERR_UNSUPPORTED
+    ptrs = [P] * 9
+    ptrs[6] = P + 4
+    assert bwd(ptrs) == binding.FA_ERR_ALIGN
+    need = binding.fa_bwd_workspace_bytes(1, 2, 2, 128, 64)
+    assert bwd(ws_bytes=need - 1) == binding.FA_ERR_WORKSPACE
+
+
+def test_workspace_size_formula():
+    # D (one float per query row and head, rounded up to 256 B) + float32 dQ accumulator
+    assert binding.fa_bwd_workspace_bytes(1, 2, 2, 128, 64) == 1024 + 128 * 2 * 64 * 4
+    assert binding.fa_bwd_workspace_bytes(2, 16, 16, 8192, 128) == 2 * 8192 * 16 * 4 + 2 * 8192 * 16 * 128 * 4
+    assert binding.fa_varlen_bwd_workspace_bytes(100, 4, 2, 128) == 1792 + 100 * 4 * 128 * 4
+    assert binding.fa_bwd_workspace_bytes(0, 2, 2, 128, 64) == 0
+    assert binding.fa_bwd_workspace_bytes(1, 8, 2, 16, 128) >= 16 * 8 * 128 * 4
+
+
+def test_varlen_rejects_bad_arguments():
+    def vf(cu=P, nseq=4, total=1000, mx=400, Hq=4, Hkv=2, d=128, scale=0.1, Q=P):
+        return binding.fa_varlen_fwd_raw(Q, P, P, P, P, cu, nseq, total, mx, Hq, Hkv, d, scale, 1, 0)
+    assert vf(cu=0) == binding.FA_ERR_NULL
+    assert vf(Q=0) == binding.FA_ERR_NULL
+    assert vf(nseq=0) == binding.FA_ERR_SHAPE
+    assert vf(total=0) == binding.FA_ERR_SHAPE
+    assert vf(mx=2000) == binding.FA_ERR_SHAPE      # longest sequence longer than the whole batch
+    assert vf(mx=100) == binding.FA_ERR_SHAPE       # 4 sequences of at most 100 cannot hold 1000 tokens
+    assert vf(Hq=5) == binding.FA_ERR_SHAPE
+    assert vf(d=80) == binding.FA_ERR_UNSUPPORTED
+
+    def vb(ws_bytes=1 << 30, mx=400):
+        return binding.fa_varlen_bwd_raw(*([P] * 9), P, ws_bytes, P, 4, 1000, mx, 4, 2, 128, 0.1, 1, 0)
+    assert vb(ws_bytes=16) == binding.FA_ERR_WORKSPACE
+    assert vb(mx=0) == binding.FA_ERR_SHAPE
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()
