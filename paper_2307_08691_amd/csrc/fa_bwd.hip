@@ -17,7 +17,7 @@
 // whose left-hand operands come from transposing LDS reads of the row-major
 // Q_i / dO_i tiles. Only dQ_i = dS K_j contracts over keys, i.e. across the
 // wavefronts: dS goes through LDS once and every wavefront then forms a
-// (32 x 32) tile of dQ_i^T over all 128 keys.
+// (32 x 32) tile of dQ_i over all 128 keys.
 #include "fa_common.h"
 #include "fa_kernels.h"
 
@@ -212,20 +212,22 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(BwdArgs a) {
       }
       __syncthreads();  // dS of all 128 keys is in LDS
 
-      // ---- dQ_i^T += K_j^T dS^T (line 15): each wavefront forms NTILE (32 x 32) tiles over all keys
+      // ---- dQ_i += dS K_j (line 15): each wavefront forms NTILE (32 x 32) tiles over all 128 keys.
+      //      Rows = queries, columns = head dim, so one atomic instruction covers two
+      //      128-byte row segments of the accumulator.
 #pragma unroll
       for (int tt = 0; tt < NTILE; ++tt) {
         const int tile = w + 4 * tt, dt = tile % DT, qt = tile / DT;
         f32x16 acc = {0};
 #pragma unroll
         for (int kk = 0; kk < BC / 16; ++kk)
-          acc = mfma32(lds_frag_transposed(Ks, KSTR, 16 * kk, 32 * dt, lane),
-                       lds_frag_transposed(dSs, SSTR, 16 * kk, 32 * qt, lane), acc);
-        const int row = i0 + 32 * qt + lq;
-        if (row < n) {
-          float* dst = dQb + (long)row * qstride + 32 * dt + 4 * hh;
+          acc = mfma32(lds_frag_transposed(dSs, SSTR, 16 * kk, 32 * qt, lane),
+                       lds_frag_transposed(Ks, KSTR, 16 * kk, 32 * dt, lane), acc);
+        float* dst = dQb + 32 * dt + lq;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) unsafeAtomicAdd(dst + 8 * (r / 4) + (r % 4), acc[r]);
+        for (int r = 0; r < 16; ++r) {
+          const int row = i0 + 32 * qt + acc_row(r, hh);
+          if (row < n) unsafeAtomicAdd(dst + (long)row * qstride, acc[r]);
         }
       }
     }
