@@ -28,18 +28,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
 
-def cpu_baseline(prob, budget_units: int = 1):
-    """Time the float64 oracle (forward + backward) on `budget_units`
-    (sequence, head) units of the workload, all host cores, and scale to the
-    metric's unit with the same FLOP formula."""
+def cpu_baseline(prob, budget_s: float = 12.0):
+    """Time the float64 oracle (forward + backward) on as many (sequence, head)
+    units of the workload as fit in about `budget_s` seconds, all host cores,
+    and scale to the metric's unit with the same FLOP formula."""
     import numpy as np
     from oracle import attention_oracle as orc
 
     cores = len(os.sched_getaffinity(0))
     G = prob.Hq // prob.Hkv
-    units = [(0, 0)][:budget_units]
+    units = []
     t0 = time.perf_counter()
-    for (b, h) in units:
+    for (b, h) in [(b, h) for b in range(prob.B) for h in range(prob.Hq)]:
+        if units and time.perf_counter() - t0 > budget_s:
+            break
+        units.append((b, h))
         q = orc.widen_bf16(prob.Q[b, :, h])
         k = orc.widen_bf16(prob.K[b, :, h // G])
         v = orc.widen_bf16(prob.V[b, :, h // G])
