@@ -72,28 +72,111 @@ __global__ __launch_bounds__(256) void bwd_convert_kernel(BwdArgs a) {
   *(u32x4*)(a.dQ + 8 * i) = r;
 }
 
-template <int D, int QT, bool CAUSAL>
-__global__ __launch_bounds__(256, 1) void bwd_kernel(BwdArgs a) {
-  constexpr int BC = 128, BR = 32 * QT;
-  constexpr int KS = D / 16, DT = D / 32;
-  constexpr int QSTR = D + 8;      // Q_i / dO_i tile pitch (elements)
-  constexpr int KSTR = D + 32;     // K_j tile pitch
-  constexpr int SSTR = BR + 8;     // dS tile pitch: [key][query]
-  constexpr int CPR = D / 8;       // 16-byte chunks per row
-  constexpr int NLD = BR * CPR / 256;  // chunks per thread per Q_i (or dO_i) tile
-  constexpr int NTILE = DT * QT / 4;   // dQ^T tiles per wavefront
-  static_assert(DT * QT % 4 == 0, "dQ tiles must divide over 4 wavefronts");
-  static_assert(BR * CPR % 256 == 0, "tile must divide over 256 threads");
+// Workgroup barrier that only waits for this wavefront's LDS traffic: global
+// loads and atomics that are still in flight stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-  __shared__ __attribute__((aligned(16))) __bf16 Qs[BR * QSTR];
-  __shared__ __attribute__((aligned(16))) __bf16 dOs[BR * QSTR];
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[BC * KSTR];
-  __shared__ __attribute__((aligned(16))) __bf16 dSs[BC * SSTR];
-  __shared__ __attribute__((aligned(16))) float Ls[BR];
-  __shared__ __attribute__((aligned(16))) float Ds[BR];
+// ---- swizzled LDS tiles -----------------------------------------------------
+// Tiles are stored without padding, rows of ROWB = 128 or 256 bytes, as 16-byte
+// chunks whose position inside the row is XOR-ed with a function of the row. The
+// function is chosen so that BOTH access patterns used here are conflict free:
+//   * 16-byte row reads, 16 consecutive rows at the same chunk index, and
+//   * transposing 8-byte reads, 4 consecutive rows x 64 contiguous bytes.
+template <int ROWB>
+__device__ __forceinline__ int swz(int row) {
+  if (ROWB == 256) return ((row & 3) << 2) | ((row >> 2) & 3);
+  const int k = (row >> 1) & 7;  // two 128-byte rows share one 256-byte bank line
+  return ((k & 1) << 2) | (k >> 1);
+}
+template <int ROWB>
+__device__ __forceinline__ int swz_off(int row, int chunk) { return row * ROWB + 16 * (chunk ^ swz<ROWB>(row)); }
+
+// MFMA operand whose rows are tile rows row0 + (lane % 32) and whose contraction
+// slots are the 8 elements starting at column col0 + 8 * (lane / 32).
+template <int ROWB>
+__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int row0, int col0, int lane) {
+  return *(const bf16x8*)(tile + swz_off<ROWB>(row0 + (lane & 31), (col0 >> 3) + (lane >> 5)));
+}
+// MFMA operand whose rows are tile COLUMNS col0 + (lane % 32) and whose contraction
+// slots are tile rows row0 + {4*hh + 0..3, 8 + 4*hh + 0..3} (hh = lane / 32): the row
+// set registers 8s..8s+7 of a 32x32 accumulator cover.
+template <int ROWB>
+__device__ __forceinline__ bf16x8 frag_cols(const char* tile, int row0, int col0, int lane) {
+  const int p = lane & 15, g16 = (lane >> 4) & 1, hh = lane >> 5;
+  const int row = row0 + 4 * hh + (p >> 2);
+  const int col = col0 + 16 * g16 + 4 * (p & 3);
+  const int within = (col & 7) * 2;
+  s16x4 lo = lds_read_tr((const __bf16*)(tile + swz_off<ROWB>(row, col >> 3) + within));
+  s16x4 hi = lds_read_tr((const __bf16*)(tile + swz_off<ROWB>(row + 8, col >> 3) + within));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Copy `nrows` rows of D bf16 elements (row pitch `gstride` elements, first row
+// `row_first`, rows clamped to `row_last`) from global memory straight into a
+// swizzled LDS tile, 16 bytes per lane, without passing through registers. Each
+// wavefront instruction fills 1 KiB of consecutive LDS; the swizzle is applied by
+// choosing which global chunk each lane fetches.
+template <int D, int NROWS>
+__device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase, long gstride, int row_first,
+                                                int row_last, int wave, int lane) {
+  constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI;
+  static_assert(NI % 8 == 0, "tile must divide over 8 wavefronts");
+#pragma unroll
+  for (int u = 0; u < NI / 8; ++u) {
+    const int rb = (wave + 8 * u) * RPI;
+    const int r = rb + lane / CPR;
+    const int c = (lane % CPR) ^ swz<ROWB>(r);
+    int grow = row_first + r;
+    grow = grow < row_last ? grow : row_last;
+    __builtin_amdgcn_global_load_lds((gptr_t)(gbase + (long)grow * gstride + 8 * c), (lptr_t)(tile + rb * ROWB), 16, 0, 0);
+  }
+}
+
+__device__ __forceinline__ bf16x8 lds_b128(const char* smem, int off) { return *(const bf16x8*)(smem + off); }
+__device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int off_hi) {
+  s16x4 lo = lds_read_tr((const __bf16*)(smem + off_lo));
+  s16x4 hi = lds_read_tr((const __bf16*)(smem + off_hi));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Main backward kernel: 8 wavefronts, two per SIMD so that one can run MFMAs while
+// the other does the elementwise work. Wavefront (kg, qh) owns keys 32*kg.. of the
+// column block and the query tiles qh*QTW.. of each step.
+//
+// LDS addressing. Every tile is swizzled (see swz<>). Because the XOR only touches
+// address bits 4..7 while row offsets live in bits >= 7/8, the address of every MFMA
+// operand is (lane constant) ^ (compile-time constant) + (immediate): the lane
+// constants are a handful of registers computed once, instead of one register per
+// distinct operand.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
+  constexpr int BC = 128;               // keys per workgroup
+  constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
+  constexpr int BR = 64 * QTW;          // query rows per step
+  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int ROWB = 2 * D;           // row bytes of the Q_i, dO_i, K_j, V_j tiles
+  constexpr int SROWB = 2 * BR;         // row bytes of the dS tile, stored [key][query]
+  static_assert((BR / 32) * DT == 8, "one dQ tile per wavefront");
+  // byte offsets inside the LDS block
+  constexpr int KT_OFF = 0, VT_OFF = BC * ROWB, QDO_OFF = 2 * BC * ROWB;
+  constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one buffer = Q_i | dO_i
+  constexpr int DS_OFF = QDO_OFF + 2 * BUFB;
+  constexpr int LS_OFF = DS_OFF + BC * SROWB, DV_OFF = LS_OFF + 2 * BR * 4;
+  constexpr int SMEM = DV_OFF + 2 * BR * 4;
+  static_assert(VT_OFF + BC * ROWB <= 65536 && BUFB <= 32768, "immediate offsets must fit 16 bits");
+
+  __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
   const Problem& p = a.p;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int v = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kg = v & 3, qh = v >> 2;
   const int lq = lane & 31, hh = lane >> 5;
   const int g = blockIdx.y, s = blockIdx.z;
   const SeqInfo si = seq_info(p, s);
@@ -101,159 +184,197 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(BwdArgs a) {
   const int j0 = blockIdx.x * BC;
   if (j0 >= n) return;
   const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
-  const __bf16* Kb = a.K + (si.tok0 * p.Hkv + g) * D;
-  const __bf16* Vb = a.V + (si.tok0 * p.Hkv + g) * D;
-
-  // ---- K_j, V_j: this wavefront's 32 keys as right-hand operands in registers
-  //      (Algorithm 2, line 6), and all of K_j in LDS for the dQ product
-  const int key = j0 + 32 * w + lq;  // this lane's key column
-  bf16x8 Kf[KS], Vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    if (key < n) {
-      Kf[ks] = *(const bf16x8*)(Kb + key * kstride + 16 * ks + 8 * hh);
-      Vf[ks] = *(const bf16x8*)(Vb + key * kstride + 16 * ks + 8 * hh);
-    } else {
-      Kf[ks] = (bf16x8){0};
-      Vf[ks] = (bf16x8){0};
-    }
-  }
-  for (int id = tid; id < BC * CPR; id += 256) {
-    int r = id / CPR, c = id % CPR;
-    u32x4 v = {0, 0, 0, 0};
-    if (j0 + r < n) v = *(const u32x4*)(Kb + (long)(j0 + r) * kstride + 8 * c);
-    *(u32x4*)(Ks + r * KSTR + 8 * c) = v;
-  }
-
-  // ---- dK_j^T, dV_j^T accumulators (line 7): rows = head dim, columns = this wavefront's keys
-  f32x16 dKt[DT], dVt[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt) dKt[dt] = dVt[dt] = (f32x16){0};
 
   const float c2 = p.scale_log2e;
   const int nrb = (n + BR - 1) / BR;
   const int i_first = CAUSAL ? j0 / BR : 0;  // row blocks entirely above the diagonal are skipped
+  const int per_head = nrb - i_first;
+  const int nsteps = per_head * p.G;
+  const long stat_base = s * p.lse_seq_stride + (p.cu_seqlens ? si.tok0 : 0);
 
-  for (int hq = g * p.G; hq < (g + 1) * p.G; ++hq) {
-    const __bf16* Qb = a.Q + (si.tok0 * p.Hq + hq) * D;
-    const __bf16* dOb = a.dO + (si.tok0 * p.Hq + hq) * D;
-    const long stat0 = s * p.lse_seq_stride + (long)hq * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0);
-    float* dQb = a.dQacc + (si.tok0 * p.Hq + hq) * D;
-
-    for (int i = i_first; i < nrb; ++i) {
-      const int i0 = i * BR;
-      __syncthreads();  // readers of the previous step's tiles are done
-      // ---- load Q_i, dO_i, L_i, D_i (line 9)
-#pragma unroll
-      for (int u = 0; u < NLD; ++u) {
-        int id = tid + 256 * u;
-        int r = id / CPR, c = id % CPR;
-        u32x4 q = {0, 0, 0, 0}, d = {0, 0, 0, 0};
-        if (i0 + r < n) {
-          q = *(const u32x4*)(Qb + (long)(i0 + r) * qstride + 8 * c);
-          d = *(const u32x4*)(dOb + (long)(i0 + r) * qstride + 8 * c);
-        }
-        *(u32x4*)(Qs + r * QSTR + 8 * c) = q;
-        *(u32x4*)(dOs + r * QSTR + 8 * c) = d;
-      }
-      if (tid < BR) {
-        const bool ok = i0 + tid < n;
-        // rows past the end get L = +inf so that P = exp2(. - inf) = 0 there
-        Ls[tid] = ok ? a.LSE[stat0 + i0 + tid] * kLog2e : INFINITY;
-        Ds[tid] = ok ? a.Dvec[stat0 + i0 + tid] : 0.f;
-      }
-      __syncthreads();
-
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        // ---- S = Q_i K_j^T (line 10) and dP = dO_i V_j^T (line 13)
-        f32x16 S = {0}, dP = {0};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          S = mfma32(lds_frag(Qs, QSTR, 32 * qt, 16 * ks, lane), Kf[ks], S);
-          dP = mfma32(lds_frag(dOs, QSTR, 32 * qt, 16 * ks, lane), Vf[ks], dP);
-        }
-        // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
-        const bool key_ok = key < n;
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int q0 = 32 * qt + 8 * r4 + 4 * hh;
-          const f32x4 Lv = *(const f32x4*)(Ls + q0);
-          const f32x4 Dv = *(const f32x4*)(Ds + q0);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const int r = 4 * r4 + t;
-            float pr = fast_exp2(__builtin_fmaf(S[r], c2, -Lv[t]));
-            const bool vis = key_ok && (!CAUSAL || key <= i0 + q0 + t);
-            pr = vis ? pr : 0.f;
-            S[r] = pr;
-            dP[r] = pr * (dP[r] - Dv[t]);
-          }
-        }
-        bf16x8 Pf[2], dSf[2];
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          Pf[s2] = pack8(S, s2);
-          dSf[s2] = pack8(dP, s2);
-          // dS^T to LDS: row = key, 4 consecutive queries per 8-byte store
-          u32x4 v = __builtin_bit_cast(u32x4, dSf[s2]);
-          __bf16* dst = dSs + (32 * w + lq) * SSTR + 32 * qt + 4 * hh;
-          *(u32x2*)(dst + 8 * (2 * s2)) = (u32x2){v[0], v[1]};
-          *(u32x2*)(dst + 8 * (2 * s2 + 1)) = (u32x2){v[2], v[3]};
-        }
-        // ---- dV_j^T += dO_i^T P (line 12), dK_j^T += Q_i^T dS (line 16)
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            dVt[dt] = mfma32(lds_frag_transposed(dOs, QSTR, 32 * qt + 16 * s2, 32 * dt, lane), Pf[s2], dVt[dt]);
-            dKt[dt] = mfma32(lds_frag_transposed(Qs, QSTR, 32 * qt + 16 * s2, 32 * dt, lane), dSf[s2], dKt[dt]);
-          }
-      }
-      __syncthreads();  // dS of all 128 keys is in LDS
-
-      // ---- dQ_i += dS K_j (line 15): each wavefront forms NTILE (32 x 32) tiles over all 128 keys.
-      //      Rows = queries, columns = head dim, so one atomic instruction covers two
-      //      128-byte row segments of the accumulator.
-#pragma unroll
-      for (int tt = 0; tt < NTILE; ++tt) {
-        const int tile = w + 4 * tt, dt = tile % DT, qt = tile / DT;
-        f32x16 acc = {0};
-#pragma unroll
-        for (int kk = 0; kk < BC / 16; ++kk)
-          acc = mfma32(lds_frag_transposed(dSs, SSTR, 16 * kk, 32 * qt, lane),
-                       lds_frag_transposed(Ks, KSTR, 16 * kk, 32 * dt, lane), acc);
-        float* dst = dQb + 32 * dt + lq;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = i0 + 32 * qt + acc_row(r, hh);
-          if (row < n) unsafeAtomicAdd(dst + (long)row * qstride, acc[r]);
-        }
-      }
+  // Q_i, dO_i (line 9) go HBM -> LDS directly, one step ahead, into the other buffer;
+  // L_i, D_i travel through two registers of the first BR threads.
+  float lreg = 0.f, dreg = 0.f;
+  auto issue_loads = [&](int t, int buf) {
+    const int hq = g * p.G + t / per_head;
+    const int i0 = (i_first + t % per_head) * BR;
+    char* dst = smem + QDO_OFF + buf * BUFB;
+    tile_load_async<D, BR>(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
+    tile_load_async<D, BR>(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
+    if (tid < BR) {
+      const bool ok = i0 + tid < n;
+      const long si_ = stat_base + (long)hq * p.lse_head_stride + i0 + tid;
+      // rows past the end get L = +inf so that P = exp2(. - inf) = 0 there
+      lreg = ok ? a.LSE[si_] * kLog2e : INFINITY;
+      dreg = ok ? a.Dvec[si_] : 0.f;
     }
-  }
+  };
+  auto commit_stats = [&](int buf) {
+    if (tid < BR) {
+      *(float*)(smem + LS_OFF + (buf * BR + tid) * 4) = lreg;
+      *(float*)(smem + DV_OFF + (buf * BR + tid) * 4) = dreg;
+    }
+  };
 
-  // ---- write dK_j, dV_j (line 18); dK carries the softmax scaling
-  if (key < n) {
-    __bf16* dKp = a.dK + ((si.tok0 + key) * p.Hkv + g) * D + 4 * hh;
-    __bf16* dVp = a.dV + ((si.tok0 + key) * p.Hkv + g) * D + 4 * hh;
-    const float sc = p.scale;
+  // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop
+  tile_load_async<D, BC>(smem + KT_OFF, a.K + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
+  tile_load_async<D, BC>(smem + VT_OFF, a.V + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
+  issue_loads(0, 0);
+  wait_vmem();
+  commit_stats(0);
+  lds_barrier();
+
+  // ---- lane constants of the LDS addressing
+  // row operands (rows row0 + lq, row0 a multiple of 32): address = (zrow ^ 32*ks) + row0 * ROWB + tile
+  const int zrow = lq * ROWB + 16 * (hh ^ swz<ROWB>(lq));
+  // column operands (rows row0 + 4*hh + (p >> 2) + 8*u, row0 a multiple of 16, columns 32*dt..):
+  // address = (zcol[u] ^ 64*dt) + row0 * ROWB + tile
+  const int p16 = lane & 15, g16 = (lane >> 4) & 1;
+  int zcol[2], zds[2];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+  for (int u = 0; u < 2; ++u) {
+    const int r = 4 * hh + (p16 >> 2) + 8 * u, c = 2 * g16 + ((p16 & 3) >> 1);
+    zcol[u] = swz_off<ROWB>(r, c) + 8 * (p16 & 1);
+    zds[u] = swz_off<SROWB>(r, c) + 8 * (p16 & 1);
+  }
+  const int dq_dt = v % DT, dq_qt = v / DT;  // the dQ tile this wavefront forms
+  const int zk = zrow + 32 * kg * ROWB;      // K_j / V_j row operands of this wavefront
+  const int zkc0 = (zcol[0] ^ (64 * dq_dt)) + KT_OFF, zkc1 = (zcol[1] ^ (64 * dq_dt)) + KT_OFF;
+  const int zdc0 = (zds[0] ^ (64 * dq_qt)) + DS_OFF, zdc1 = (zds[1] ^ (64 * dq_qt)) + DS_OFF;
+  // dS stores: row 32*kg + lq, chunk 4*qtile + r4, 8*hh bytes into the chunk
+  const int dsr = 32 * kg + lq;
+  const int zdw = DS_OFF + dsr * SROWB + 16 * swz<SROWB>(dsr) + 8 * hh;
+
+  // ---- dK_j^T, dV_j^T accumulators (line 7): rows = head dim, columns = this wavefront's
+  //      32 keys; partial over this wavefront's half of the query rows
+  f32x16 dKt[DT], dVt[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) dKt[dt] = dVt[dt] = (f32x16){0};
+
+  const int key = j0 + 32 * kg + lq;  // this lane's key column
+  const bool key_ok = key < n;
+
+  for (int t = 0; t < nsteps; ++t) {
+    const int buf = t & 1;
+    const int hq = g * p.G + t / per_head;
+    const int i0 = (i_first + t % per_head) * BR;
+    if (t + 1 < nsteps) issue_loads(t + 1, buf ^ 1);
+    const int qoff = QDO_OFF + buf * BUFB;  // this step's Q_i tile; dO_i follows at + TILEB
+    const int zq = zrow + qoff, zc0 = zcol[0] + qoff, zc1 = zcol[1] + qoff;
+    const int stat_off = buf * BR * 4;
+
+#pragma unroll
+    for (int tq = 0; tq < QTW; ++tq) {
+      const int qtile = qh * QTW + tq;
+      const int r0 = i0 + 32 * qtile;  // first query row of this tile
+      const int zw = zdw ^ (64 * qtile);
+      // ---- S = Q_i K_j^T (line 10) and dP = dO_i V_j^T (line 13)
+      f32x16 S = {0}, dP = {0};
+      const int qrow = 32 * qtile * ROWB;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        S = mfma32(lds_b128(smem, (zq ^ (32 * ks)) + qrow), lds_b128(smem, (zk ^ (32 * ks)) + KT_OFF), S);
+        dP = mfma32(lds_b128(smem, (zq ^ (32 * ks)) + qrow + TILEB), lds_b128(smem, (zk ^ (32 * ks)) + VT_OFF), dP);
+      }
+      // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
+      const bool need_mask = (CAUSAL && j0 + 32 * kg + 31 > r0) || (j0 + BC > n);
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        u32x2 kv, vv;
-        kv[0] = pack_bf16(dKt[dt][4 * r4 + 0] * sc, dKt[dt][4 * r4 + 1] * sc);
-        kv[1] = pack_bf16(dKt[dt][4 * r4 + 2] * sc, dKt[dt][4 * r4 + 3] * sc);
-        vv[0] = pack_bf16(dVt[dt][4 * r4 + 0], dVt[dt][4 * r4 + 1]);
-        vv[1] = pack_bf16(dVt[dt][4 * r4 + 2], dVt[dt][4 * r4 + 3]);
-        *(u32x2*)(dKp + 32 * dt + 8 * r4) = kv;
-        *(u32x2*)(dVp + 32 * dt + 8 * r4) = vv;
+        const int q0 = 32 * qtile + 8 * r4 + 4 * hh;
+        const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + q0 * 4);
+        const f32x4 Dv = *(const f32x4*)(smem + DV_OFF + stat_off + q0 * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = 4 * r4 + u;
+          float pr = fast_exp2(__builtin_fmaf(S[r], c2, -Lv[u]));
+          if (need_mask) {
+            const bool vis = key_ok && (!CAUSAL || key <= i0 + q0 + u);
+            pr = vis ? pr : 0.f;
+          }
+          S[r] = pr;
+          dP[r] = pr * (dP[r] - Dv[u]);
+        }
       }
+      bf16x8 Pf[2], dSf[2];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        Pf[s2] = pack8(S, s2);
+        dSf[s2] = pack8(dP, s2);
+        // dS^T to LDS: row = key, 4 consecutive queries per 8-byte store
+        u32x4 x = __builtin_bit_cast(u32x4, dSf[s2]);
+        *(u32x2*)(smem + (zw ^ (16 * (2 * s2)))) = (u32x2){x[0], x[1]};
+        *(u32x2*)(smem + (zw ^ (16 * (2 * s2 + 1)))) = (u32x2){x[2], x[3]};
+      }
+      // ---- dV_j^T += dO_i^T P (line 12), dK_j^T += Q_i^T dS (line 16)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const int ro = (32 * qtile + 16 * s2) * ROWB;
+          const int a0 = (zc0 ^ (64 * dt)) + ro, a1 = (zc1 ^ (64 * dt)) + ro;
+          dVt[dt] = mfma32(lds_tr_pair(smem, a0 + TILEB, a1 + TILEB), Pf[s2], dVt[dt]);
+          dKt[dt] = mfma32(lds_tr_pair(smem, a0, a1), dSf[s2], dKt[dt]);
+        }
+    }
+    lds_barrier();  // dS of all 128 keys x BR rows is in LDS; nobody reads this step's Q_i / dO_i any more
+
+    // ---- dQ_i += dS K_j (line 15): each wavefront forms one (32 x 32) tile over all 128 keys.
+    //      Rows = queries, columns = head dim, so one atomic instruction covers two
+    //      128-byte row segments of the accumulator.
+    f32x16 acc = {0};
+#pragma unroll
+    for (int kk = 0; kk < BC / 16; ++kk)
+      acc = mfma32(lds_tr_pair(smem, zdc0 + 16 * kk * SROWB, zdc1 + 16 * kk * SROWB),
+                   lds_tr_pair(smem, zkc0 + 16 * kk * ROWB, zkc1 + 16 * kk * ROWB), acc);
+    // the next step's tiles and statistics, requested before this step's compute, must
+    // have landed before the barrier below publishes them; waiting here, ahead of the
+    // atomics, leaves the atomics a whole step to drain
+    wait_vmem();
+    commit_stats(buf ^ 1);
+    float* dQb = a.dQacc + (si.tok0 * p.Hq + hq) * D + 32 * dq_dt + lq;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = i0 + 32 * dq_qt + acc_row(r, hh);
+      if (row < n) unsafeAtomicAdd(dQb + (long)row * qstride, acc[r]);
+    }
+    lds_barrier();  // next tiles visible; everyone is done reading dS
+  }
+
+  // ---- combine the two query halves and write dK_j, dV_j (line 18); dK carries the scaling
+  float* red = (float*)(smem + QDO_OFF);  // 4 * DT * 16 * 64 floats <= 64 KiB, free after the loop
+  const float sc = p.scale;
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    f32x16* accs = which == 0 ? dKt : dVt;
+    if (qh == 1) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[((kg * DT + dt) * 16 + r) * 64 + lane] = accs[dt][r];
+    }
+    __syncthreads();
+    if (qh == 0 && key_ok) {
+      __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0 + key) * p.Hkv + g) * D + 4 * hh;
+      const float mul = which == 0 ? sc : 1.f;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          float x[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            x[u] = (accs[dt][4 * r4 + u] + red[((kg * DT + dt) * 16 + 4 * r4 + u) * 64 + lane]) * mul;
+          u32x2 o;
+          o[0] = pack_bf16(x[0], x[1]);
+          o[1] = pack_bf16(x[2], x[3]);
+          *(u32x2*)(dst + 32 * dt + 8 * r4) = o;
+        }
+    }
+    __syncthreads();
   }
 }
 
-template <int D, int QT>
+template <int D>
 static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStream_t st) {
   const long nrows = (long)a.p.total_tokens * a.p.Hq;
   constexpr int RPB = 256 / (D / 8);
@@ -264,8 +385,8 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   }
   if (stages & 2) {
     dim3 grid((a.p.N + 127) / 128, a.p.Hkv, a.p.nseq);
-    if (causal) hipLaunchKernelGGL((bwd_kernel<D, QT, true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bwd_kernel<D, QT, false>), grid, dim3(256), 0, st, a);
+    if (causal) hipLaunchKernelGGL((bwd_kernel<D, true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((bwd_kernel<D, false>), grid, dim3(512), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 4) {
@@ -277,8 +398,8 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
 }
 
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st) {
-  if (d == 64) return launch_bwd_d<64, 2>(a, causal, stages, st);
-  return launch_bwd_d<128, 1>(a, causal, stages, st);
+  if (d == 64) return launch_bwd_d<64>(a, causal, stages, st);
+  return launch_bwd_d<128>(a, causal, stages, st);
 }
 
 }  // namespace fa
