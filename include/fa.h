@@ -77,10 +77,11 @@ int fa_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
  * same Q, K, V, scale and causal flag. Writes dQ, dK, dV (bfloat16).
  * `workspace` is device scratch of at least fa_bwd_workspace_bytes() bytes,
  * 16-byte aligned; its contents are undefined on entry and on return. It holds
- * D = rowsum(dO o O) (Algorithm 2, line 4) and a float32 accumulator for dQ,
- * into which the column-block workgroups add their partial products with
- * atomic adds (section 3.2, "Backward pass"); dQ is therefore reproducible only
- * up to float32 summation order, dK and dV are bit-reproducible.
+ * D = rowsum(dO o O) (Algorithm 2, line 4). Three kernels are enqueued: the D
+ * pre-pass, a column-block kernel that produces dK and dV (section 3.2,
+ * "Backward pass"), and a row-block kernel that produces dQ by recomputing
+ * the probabilities once more instead of accumulating across workgroups with
+ * atomic adds. All three outputs are bit-reproducible.
  */
 size_t fa_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int d);
 int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
@@ -91,14 +92,14 @@ int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const voi
 /*
  * Profiling aid: fa_bwd restricted to a subset of its three launches, so that
  * each can be timed on its own. `stages` is a bit mask; fa_bwd equals
- * FA_STAGE_PREP | FA_STAGE_MAIN | FA_STAGE_CONVERT. The main stage adds into
- * the accumulator the prep stage zeroes, so a correct dQ needs all three, in
- * that order, with the same arguments. Same validation and errors as fa_bwd;
- * stages == 0 or bits outside the mask return FA_ERR_SHAPE.
+ * FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ. Both later stages read the D
+ * the prep stage writes, so results are correct only if it ran first on the
+ * same arguments. Same validation and errors as fa_bwd; stages == 0 or bits
+ * outside the mask return FA_ERR_SHAPE.
  */
-#define FA_STAGE_PREP 1    /* D = rowsum(dO o O); zero the dQ accumulator (Algorithm 2, lines 3-4) */
-#define FA_STAGE_MAIN 2    /* the column-block loop (Algorithm 2, lines 5-19) */
-#define FA_STAGE_CONVERT 4 /* dQ = bf16(scale * accumulator) */
+#define FA_STAGE_PREP 1 /* D = rowsum(dO o O) (Algorithm 2, line 4) */
+#define FA_STAGE_DKDV 2 /* column-block loop: dK, dV (Algorithm 2, lines 5-19 without line 15) */
+#define FA_STAGE_DQ 4   /* row-block loop: dQ (Algorithm 2, line 15) */
 int fa_bwd_stages(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                   const float* LSE, void* dQ, void* dK, void* dV,
                   void* workspace, size_t workspace_bytes,

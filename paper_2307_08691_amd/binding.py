@@ -178,7 +178,7 @@ def fa_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV
 
 
 def fa_bwd_stages(Q, K, V, O, dO, LSE, scale: float, causal: bool, stages: int, dQ, dK, dV, workspace) -> None:
-    """Profiling aid: run the selected stages (1 prep | 2 main | 4 convert) of the dense backward."""
+    """Profiling aid: run the selected stages (1 D pre-pass | 2 dK/dV | 4 dQ) of the dense backward."""
     B, N, Hq, d = Q.shape
     Hkv = K.shape[2]
     _check(fa_bwd_stages_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),

@@ -48,9 +48,8 @@ int pick_fwd_nq(int d, int max_n) {
 }
 
 size_t ws_bytes(long tokens, int Hq, int d) {
-  size_t dvec = round_up((size_t)tokens * Hq * sizeof(float), 256);
-  size_t dq = (size_t)tokens * Hq * d * sizeof(float);
-  return dvec + dq;
+  (void)d;
+  return round_up((size_t)tokens * Hq * sizeof(float), 256);  // D = rowsum(dO o O)
 }
 
 int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
@@ -86,7 +85,6 @@ int run_bwd(const void* Q, const void* K, const void* V, const void* O, const vo
   a.dK = (__bf16*)dK;
   a.dV = (__bf16*)dV;
   a.Dvec = (float*)ws;
-  a.dQacc = (float*)((char*)ws + round_up((size_t)total * Hq * sizeof(float), 256));
   hipError_t e = fa::launch_bwd(a, d, causal, stages, (hipStream_t)stream);
   if (e != hipSuccess) {
     g_last_hip_error = (int)e;
@@ -152,7 +150,7 @@ int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const voi
            void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int N, int d,
            float scale, int causal, void* stream) {
   return fa_bwd_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, N, d, scale, causal,
-                       FA_STAGE_PREP | FA_STAGE_MAIN | FA_STAGE_CONVERT, stream);
+                       FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
 }
 
 static int check_varlen(const int32_t* cu, int nseq, int total_tokens, int max_seqlen) {

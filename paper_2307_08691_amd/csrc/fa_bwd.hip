@@ -1,23 +1,29 @@
 // Backward pass of exact attention for gfx950 (Algorithm 2 of the paper).
 //
 // Three launches on the caller's stream:
-//   1. prep:    D = rowsum(dO o O) (Algorithm 2, line 4) and dQ accumulator := 0 (line 3)
-//   2. main:    one workgroup per block of BC = 128 keys of one (sequence, key/value
-//               head) (section 3.2 "Backward pass"); it loops over the query heads
-//               that share the key/value head and over the row blocks i, recomputes
-//               P from the saved logsumexp (line 11), keeps dK_j, dV_j in MFMA
-//               accumulators for the whole loop and adds its dQ_i contributions to a
-//               float32 buffer with atomic adds
-//   3. convert: dQ = bf16(scale * accumulator)
+//   1. prep:  D = rowsum(dO o O) (Algorithm 2, line 4)
+//   2. dK/dV: one workgroup per block of 128 keys of one (sequence, key/value head)
+//             (section 3.2 "Backward pass"); it loops over the query heads that share the
+//             key/value head and over the row blocks i, recomputes P from the saved
+//             logsumexp (line 11) and keeps dK_j, dV_j in MFMA accumulators for the whole
+//             loop (lines 12-16 without line 15)
+//   3. dQ:    one workgroup per block of 128 query rows; it loops over the column blocks,
+//             recomputes P and dS and keeps dQ_i in MFMA accumulators (line 15)
 //
-// Lane layout of the main kernel: each of the 4 wavefronts owns 32 keys and the
-// scores are computed UN-transposed, S = Q_i K_j^T, so a lane holds one key
-// column; P and dS, rounded to bf16, are then directly the right-hand operands of
-// dV_j^T += dO_i^T P and dK_j^T += Q_i^T dS (contractions over the query rows),
-// whose left-hand operands come from transposing LDS reads of the row-major
-// Q_i / dO_i tiles. Only dQ_i = dS K_j contracts over keys, i.e. across the
-// wavefronts: dS goes through LDS once and every wavefront then forms a
-// (32 x 32) tile of dQ_i over all 128 keys.
+// The paper accumulates dQ from the column-block workers with atomic adds (section 3.2).
+// On MI355X float32 atomics into L2 retire at roughly 1.3 TB/s chip-wide: with them the
+// single-kernel form of Algorithm 2 spent more than half its time waiting for the atomic
+// unit (6.8 ms against 3.1 ms with the atomics removed, d = 128, N = 8192, 32 heads). The
+// dQ pass here instead recomputes S and dP (7 products instead of 5) and needs no
+// cross-workgroup accumulation at all; dQ, dK and dV are bit-reproducible.
+//
+// Lane layouts. dK/dV kernel: scores are computed UN-transposed, S = Q_i K_j^T, so a lane
+// holds one key column; P and dS, rounded to bf16, are directly the right-hand operands of
+// dV_j^T += dO_i^T P and dK_j^T += Q_i^T dS (contractions over the query rows), whose
+// left-hand operands come from transposing LDS reads of the row-major Q_i / dO_i tiles.
+// dQ kernel: scores are computed transposed, S^T = K_j Q_i^T, so a lane holds one query
+// row (L_i, D_i are per-lane scalars) and dS^T in bf16 is the right-hand operand of
+// dQ_i^T += K_j^T dS^T, with K_j^T from transposing reads of the K tile.
 #include "fa_common.h"
 #include "fa_kernels.h"
 
@@ -43,9 +49,6 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
     bf16x8 g = *(const bf16x8*)(a.dO + row * D + 8 * c);
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
-    f32x4 z = {0.f, 0.f, 0.f, 0.f};
-    *(f32x4*)(a.dQacc + row * D + 8 * c) = z;
-    *(f32x4*)(a.dQacc + row * D + 8 * c + 4) = z;
   }
 #pragma unroll
   for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
@@ -54,22 +57,6 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
     int h = (int)(row - tok * a.p.Hq);
     a.Dvec[stat_index(a.p, tok, h)] = acc;
   }
-}
-
-template <int D>
-__global__ __launch_bounds__(256) void bwd_convert_kernel(BwdArgs a) {
-  const long n8 = (long)a.p.total_tokens * a.p.Hq * D / 8;
-  const long i = (long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n8) return;
-  f32x4 x = *(const f32x4*)(a.dQacc + 8 * i);
-  f32x4 y = *(const f32x4*)(a.dQacc + 8 * i + 4);
-  const float sc = a.p.scale;
-  u32x4 r;
-  r[0] = pack_bf16(x[0] * sc, x[1] * sc);
-  r[1] = pack_bf16(x[2] * sc, x[3] * sc);
-  r[2] = pack_bf16(y[0] * sc, y[1] * sc);
-  r[3] = pack_bf16(y[2] * sc, y[3] * sc);
-  *(u32x4*)(a.dQ + 8 * i) = r;
 }
 
 // Workgroup barrier that only waits for this wavefront's LDS traffic: global
@@ -121,14 +108,14 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // swizzled LDS tile, 16 bytes per lane, without passing through registers. Each
 // wavefront instruction fills 1 KiB of consecutive LDS; the swizzle is applied by
 // choosing which global chunk each lane fetches.
-template <int D, int NROWS>
+template <int D, int NROWS, int NW>
 __device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase, long gstride, int row_first,
                                                 int row_last, int wave, int lane) {
   constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI;
-  static_assert(NI % 8 == 0, "tile must divide over 8 wavefronts");
+  static_assert(NI % NW == 0, "tile must divide over the wavefronts");
 #pragma unroll
-  for (int u = 0; u < NI / 8; ++u) {
-    const int rb = (wave + 8 * u) * RPI;
+  for (int u = 0; u < NI / NW; ++u) {
+    const int rb = (wave + NW * u) * RPI;
     const int r = rb + lane / CPR;
     const int c = (lane % CPR) ^ swz<ROWB>(r);
     int grow = row_first + r;
@@ -145,9 +132,9 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int 
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// Main backward kernel: 8 wavefronts, two per SIMD so that one can run MFMAs while
-// the other does the elementwise work. Wavefront (kg, qh) owns keys 32*kg.. of the
-// column block and the query tiles qh*QTW.. of each step.
+// dK/dV kernel: 8 wavefronts, two per SIMD so that one can run MFMAs while the other
+// does the elementwise work. Wavefront (kg, qh) owns keys 32*kg.. of the column block
+// and the query tiles qh*QTW.. of each step.
 //
 // LDS addressing. Every tile is swizzled (see swz<>). Because the XOR only touches
 // address bits 4..7 while row offsets live in bits >= 7/8, the address of every MFMA
@@ -155,19 +142,16 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int 
 // constants are a handful of registers computed once, instead of one register per
 // distinct operand.
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
+__global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int BC = 128;               // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
   constexpr int BR = 64 * QTW;          // query rows per step
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int ROWB = 2 * D;           // row bytes of the Q_i, dO_i, K_j, V_j tiles
-  constexpr int SROWB = 2 * BR;         // row bytes of the dS tile, stored [key][query]
-  static_assert((BR / 32) * DT == 8, "one dQ tile per wavefront");
   // byte offsets inside the LDS block
   constexpr int KT_OFF = 0, VT_OFF = BC * ROWB, QDO_OFF = 2 * BC * ROWB;
   constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one buffer = Q_i | dO_i
-  constexpr int DS_OFF = QDO_OFF + 2 * BUFB;
-  constexpr int LS_OFF = DS_OFF + BC * SROWB, DV_OFF = LS_OFF + 2 * BR * 4;
+  constexpr int LS_OFF = QDO_OFF + 2 * BUFB, DV_OFF = LS_OFF + 2 * BR * 4;
   constexpr int SMEM = DV_OFF + 2 * BR * 4;
   static_assert(VT_OFF + BC * ROWB <= 65536 && BUFB <= 32768, "immediate offsets must fit 16 bits");
 
@@ -178,10 +162,11 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
   const int v = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = v & 3, qh = v >> 2;
   const int lq = lane & 31, hh = lane >> 5;
-  const int g = blockIdx.y, s = blockIdx.z;
+  const BlockCoord bc = block_coord<CAUSAL>((p.N + BC - 1) / BC, p.Hkv);  // causal: block 0 is the longest
+  const int g = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
   const int n = si.n;
-  const int j0 = blockIdx.x * BC;
+  const int j0 = bc.blk * BC;
   if (j0 >= n) return;
   const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
 
@@ -199,8 +184,8 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
     const int hq = g * p.G + t / per_head;
     const int i0 = (i_first + t % per_head) * BR;
     char* dst = smem + QDO_OFF + buf * BUFB;
-    tile_load_async<D, BR>(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
-    tile_load_async<D, BR>(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
+    tile_load_async<D, BR, 8>(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
+    tile_load_async<D, BR, 8>(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
     if (tid < BR) {
       const bool ok = i0 + tid < n;
       const long si_ = stat_base + (long)hq * p.lse_head_stride + i0 + tid;
@@ -217,8 +202,8 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
   };
 
   // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop
-  tile_load_async<D, BC>(smem + KT_OFF, a.K + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
-  tile_load_async<D, BC>(smem + VT_OFF, a.V + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
+  tile_load_async<D, BC, 8>(smem + KT_OFF, a.K + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
+  tile_load_async<D, BC, 8>(smem + VT_OFF, a.V + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
   issue_loads(0, 0);
   wait_vmem();
   commit_stats(0);
@@ -230,20 +215,11 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
   // column operands (rows row0 + 4*hh + (p >> 2) + 8*u, row0 a multiple of 16, columns 32*dt..):
   // address = (zcol[u] ^ 64*dt) + row0 * ROWB + tile
   const int p16 = lane & 15, g16 = (lane >> 4) & 1;
-  int zcol[2], zds[2];
+  int zcol[2];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = 4 * hh + (p16 >> 2) + 8 * u, c = 2 * g16 + ((p16 & 3) >> 1);
-    zcol[u] = swz_off<ROWB>(r, c) + 8 * (p16 & 1);
-    zds[u] = swz_off<SROWB>(r, c) + 8 * (p16 & 1);
-  }
-  const int dq_dt = v % DT, dq_qt = v / DT;  // the dQ tile this wavefront forms
-  const int zk = zrow + 32 * kg * ROWB;      // K_j / V_j row operands of this wavefront
-  const int zkc0 = (zcol[0] ^ (64 * dq_dt)) + KT_OFF, zkc1 = (zcol[1] ^ (64 * dq_dt)) + KT_OFF;
-  const int zdc0 = (zds[0] ^ (64 * dq_qt)) + DS_OFF, zdc1 = (zds[1] ^ (64 * dq_qt)) + DS_OFF;
-  // dS stores: row 32*kg + lq, chunk 4*qtile + r4, 8*hh bytes into the chunk
-  const int dsr = 32 * kg + lq;
-  const int zdw = DS_OFF + dsr * SROWB + 16 * swz<SROWB>(dsr) + 8 * hh;
+  for (int u = 0; u < 2; ++u)
+    zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
+  const int zk = zrow + 32 * kg * ROWB;  // K_j / V_j row operands of this wavefront
 
   // ---- dK_j^T, dV_j^T accumulators (line 7): rows = head dim, columns = this wavefront's
   //      32 keys; partial over this wavefront's half of the query rows
@@ -256,7 +232,6 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
 
   for (int t = 0; t < nsteps; ++t) {
     const int buf = t & 1;
-    const int hq = g * p.G + t / per_head;
     const int i0 = (i_first + t % per_head) * BR;
     if (t + 1 < nsteps) issue_loads(t + 1, buf ^ 1);
     const int qoff = QDO_OFF + buf * BUFB;  // this step's Q_i tile; dO_i follows at + TILEB
@@ -267,7 +242,6 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
     for (int tq = 0; tq < QTW; ++tq) {
       const int qtile = qh * QTW + tq;
       const int r0 = i0 + 32 * qtile;  // first query row of this tile
-      const int zw = zdw ^ (64 * qtile);
       // ---- S = Q_i K_j^T (line 10) and dP = dO_i V_j^T (line 13)
       f32x16 S = {0}, dP = {0};
       const int qrow = 32 * qtile * ROWB;
@@ -300,10 +274,6 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
       for (int s2 = 0; s2 < 2; ++s2) {
         Pf[s2] = pack8(S, s2);
         dSf[s2] = pack8(dP, s2);
-        // dS^T to LDS: row = key, 4 consecutive queries per 8-byte store
-        u32x4 x = __builtin_bit_cast(u32x4, dSf[s2]);
-        *(u32x2*)(smem + (zw ^ (16 * (2 * s2)))) = (u32x2){x[0], x[1]};
-        *(u32x2*)(smem + (zw ^ (16 * (2 * s2 + 1)))) = (u32x2){x[2], x[3]};
       }
       // ---- dV_j^T += dO_i^T P (line 12), dK_j^T += Q_i^T dS (line 16)
 #pragma unroll
@@ -316,28 +286,10 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
           dKt[dt] = mfma32(lds_tr_pair(smem, a0, a1), dSf[s2], dKt[dt]);
         }
     }
-    lds_barrier();  // dS of all 128 keys x BR rows is in LDS; nobody reads this step's Q_i / dO_i any more
-
-    // ---- dQ_i += dS K_j (line 15): each wavefront forms one (32 x 32) tile over all 128 keys.
-    //      Rows = queries, columns = head dim, so one atomic instruction covers two
-    //      128-byte row segments of the accumulator.
-    f32x16 acc = {0};
-#pragma unroll
-    for (int kk = 0; kk < BC / 16; ++kk)
-      acc = mfma32(lds_tr_pair(smem, zdc0 + 16 * kk * SROWB, zdc1 + 16 * kk * SROWB),
-                   lds_tr_pair(smem, zkc0 + 16 * kk * ROWB, zkc1 + 16 * kk * ROWB), acc);
-    // the next step's tiles and statistics, requested before this step's compute, must
-    // have landed before the barrier below publishes them; waiting here, ahead of the
-    // atomics, leaves the atomics a whole step to drain
+    // the next step's tiles and statistics were requested before this step's compute
     wait_vmem();
     commit_stats(buf ^ 1);
-    float* dQb = a.dQacc + (si.tok0 * p.Hq + hq) * D + 32 * dq_dt + lq;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = i0 + 32 * dq_qt + acc_row(r, hh);
-      if (row < n) unsafeAtomicAdd(dQb + (long)row * qstride, acc[r]);
-    }
-    lds_barrier();  // next tiles visible; everyone is done reading dS
+    lds_barrier();  // next tiles visible; nobody reads this step's Q_i / dO_i any more
   }
 
   // ---- combine the two query halves and write dK_j, dV_j (line 18); dK carries the scaling
@@ -374,6 +326,141 @@ __global__ __launch_bounds__(512) void bwd_kernel(BwdArgs a) {
   }
 }
 
+// dQ kernel: 4 wavefronts, each owning 32 whole query rows of a 128-row block; two
+// workgroups per CU. K_j, V_j tiles of 64 keys stream HBM -> LDS one step ahead.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
+  constexpr int BR = 128, BC = 64;
+  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int ROWB = 2 * D;
+  constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
+
+  __shared__ __attribute__((aligned(1024))) char smem[2 * BUFB];
+
+  const Problem& p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lq = lane & 31, hh = lane >> 5;
+  const int nblk = (p.N + BR - 1) / BR;
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq);
+  const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
+  const int h = bc.head, s = bc.seq;
+  const SeqInfo si = seq_info(p, s);
+  const int n = si.n;
+  const int i0 = rowblk * BR;
+  if (i0 >= n) return;
+  const int g = h / p.G;
+  const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
+  const __bf16* Kb = a.K + (si.tok0 * p.Hkv + g) * D;
+  const __bf16* Vb = a.V + (si.tok0 * p.Hkv + g) * D;
+
+  // ---- Q_i, dO_i operands and L_i, D_i of this lane's query row: registers for the whole kernel
+  const int wrow0 = i0 + 32 * w;
+  const int row = wrow0 + lq;
+  const int rowc = row < n ? row : n - 1;
+  bf16x8 Qf[KS], dOf[KS];
+  {
+    const __bf16* qp = a.Q + ((si.tok0 + rowc) * p.Hq + h) * D + 8 * hh;
+    const __bf16* gp = a.dO + ((si.tok0 + rowc) * p.Hq + h) * D + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      Qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+      dOf[ks] = *(const bf16x8*)(gp + 16 * ks);
+    }
+  }
+  const long stat = s * p.lse_seq_stride + (long)h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + rowc;
+  const float Lq = row < n ? a.LSE[stat] * kLog2e : INFINITY;  // rows past the end: P = 0
+  const float Dq = a.Dvec[stat];
+
+  f32x16 dQt[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) dQt[dt] = (f32x16){0};
+
+  const int ncol_all = (n + BC - 1) / BC;
+  int ncol = ncol_all;
+  if (CAUSAL) {
+    const int last_row = (i0 + BR < n ? i0 + BR : n) - 1;
+    const int c = last_row / BC + 1;
+    ncol = c < ncol_all ? c : ncol_all;
+  }
+
+  auto issue_loads = [&](int j, int buf) {
+    tile_load_async<D, BC, 4>(smem + buf * BUFB, Kb, kstride, j * BC, n - 1, w, lane);
+    tile_load_async<D, BC, 4>(smem + buf * BUFB + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
+  };
+  issue_loads(0, 0);
+  wait_vmem();
+  lds_barrier();
+
+  const int zrow = lq * ROWB + 16 * (hh ^ swz<ROWB>(lq));
+  const int p16 = lane & 15, g16 = (lane >> 4) & 1;
+  int zcol[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+    zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
+
+  const float c2 = p.scale_log2e;
+  const int wrow_last = wrow0 + 31;
+  const int lim_row = CAUSAL ? (row < n - 1 ? row : n - 1) : n - 1;  // last visible column of this lane's row
+
+  for (int j = 0; j < ncol; ++j) {
+    const int buf = j & 1;
+    if (j + 1 < ncol) issue_loads(j + 1, buf ^ 1);
+    const int col0 = j * BC;
+    const bool active = !CAUSAL || col0 <= wrow_last;  // else every score of this wavefront is masked
+    if (active) {
+      const int zk = zrow + buf * BUFB, zc0 = zcol[0] + buf * BUFB, zc1 = zcol[1] + buf * BUFB;
+      const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
+      bf16x8 dSf[2][2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
+        f32x16 S = {0}, dP = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          S = mfma32(lds_b128(smem, (zk ^ (32 * ks)) + 32 * kt * ROWB), Qf[ks], S);
+          dP = mfma32(lds_b128(smem, (zk ^ (32 * ks)) + 32 * kt * ROWB + TILEB), dOf[ks], dP);
+        }
+        // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float pr = fast_exp2(__builtin_fmaf(S[r], c2, -Lq));
+          if (need_mask) pr = (col0 + 32 * kt + acc_row(r, hh) <= lim_row) ? pr : 0.f;
+          dP[r] = pr * (dP[r] - Dq);
+        }
+        dSf[kt][0] = pack8(dP, 0);
+        dSf[kt][1] = pack8(dP, 1);
+      }
+      // ---- dQ_i^T += K_j^T dS^T (line 15)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const int ro = (32 * kt + 16 * s2) * ROWB;
+            dQt[dt] = mfma32(lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro), dSf[kt][s2], dQt[dt]);
+          }
+    }
+    wait_vmem();
+    lds_barrier();  // next tiles visible; this step's tiles are free
+  }
+
+  if (row < n) {
+    __bf16* op = a.dQ + ((si.tok0 + row) * p.Hq + h) * D + 4 * hh;
+    const float sc = p.scale;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        u32x2 o;
+        o[0] = pack_bf16(dQt[dt][4 * r4 + 0] * sc, dQt[dt][4 * r4 + 1] * sc);
+        o[1] = pack_bf16(dQt[dt][4 * r4 + 2] * sc, dQt[dt][4 * r4 + 3] * sc);
+        *(u32x2*)(op + 32 * dt + 8 * r4) = o;
+      }
+  }
+}
+
 template <int D>
 static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStream_t st) {
   const long nrows = (long)a.p.total_tokens * a.p.Hq;
@@ -384,14 +471,15 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 2) {
-    dim3 grid((a.p.N + 127) / 128, a.p.Hkv, a.p.nseq);
-    if (causal) hipLaunchKernelGGL((bwd_kernel<D, true>), grid, dim3(512), 0, st, a);
-    else hipLaunchKernelGGL((bwd_kernel<D, false>), grid, dim3(512), 0, st, a);
+    dim3 grid((unsigned)((a.p.N + 127) / 128) * a.p.Hkv * a.p.nseq);
+    if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false>), grid, dim3(512), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 4) {
-    const long n8 = nrows * D / 8;
-    hipLaunchKernelGGL((bwd_convert_kernel<D>), dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, a);
+    dim3 grid((unsigned)((a.p.N + 127) / 128) * a.p.Hq * a.p.nseq);
+    if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((bwd_dq_kernel<D, false>), grid, dim3(256), 0, st, a);
     e = hipGetLastError();
   }
   return e;

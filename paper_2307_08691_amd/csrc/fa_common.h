@@ -52,6 +52,34 @@ __device__ __forceinline__ SeqInfo seq_info(const Problem& p, int s) {
   return r;
 }
 
+// Launch index -> (block of rows or columns, head, sequence). Kernels are launched on a
+// 1-D grid of nblk * nheads * nseq workgroups, dispatched in index order. Under the
+// causal mask the work of a block grows (row blocks) or shrinks (column blocks) with its
+// index, so there the block index is the SLOW coordinate: all heads' heaviest blocks go
+// first and the lightest fill the tail. Without a mask every block costs the same and
+// the block index is the fast coordinate, which keeps one head's K/V hot in L2.
+struct BlockCoord {
+  int blk, head, seq;
+};
+template <bool WORK_SORTED>
+__device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads) {
+  const int L = blockIdx.x;
+  BlockCoord c;
+  if (WORK_SORTED) {
+    const int pairs = gridDim.x / nblk;
+    const int pr = L % pairs;
+    c.blk = L / pairs;
+    c.head = pr % nheads;
+    c.seq = pr / nheads;
+  } else {
+    c.blk = L % nblk;
+    const int pr = L / nblk;
+    c.head = pr % nheads;
+    c.seq = pr / nheads;
+  }
+  return c;
+}
+
 // D = A(32 x 16) * B(16 x 32) + C on one wavefront, bf16 inputs, fp32 accumulate.
 // Lane l supplies A[l % 32][8 * (l / 32) + t] and B[8 * (l / 32) + t][l % 32], t = 0..7,
 // and owns C[8 * (r / 4) + 4 * (l / 32) + (r % 4)][l % 32] in register r = 0..15.

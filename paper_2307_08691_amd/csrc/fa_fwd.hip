@@ -33,8 +33,10 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void fwd_kernel(FwdArgs a) 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
-  const int rowblk = gridDim.x - 1 - blockIdx.x;  // longest causal rows first
-  const int h = blockIdx.y, s = blockIdx.z;
+  const int nblk = (p.N + BR - 1) / BR;
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq);
+  const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
+  const int h = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
   const int n = si.n;
   const int i0 = rowblk * BR;
@@ -230,7 +232,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void fwd_kernel(FwdArgs a) 
 template <int D, int NQ>
 static hipError_t launch_fwd_nq(const FwdArgs& a, int causal, hipStream_t st) {
   constexpr int BR = 128 * NQ;
-  dim3 grid((a.p.N + BR - 1) / BR, a.p.Hq, a.p.nseq), block(256);
+  dim3 grid((unsigned)((a.p.N + BR - 1) / BR) * a.p.Hq * a.p.nseq), block(256);
   if (causal) hipLaunchKernelGGL((fwd_kernel<D, NQ, true>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((fwd_kernel<D, NQ, false>), grid, block, 0, st, a);
   return hipGetLastError();

@@ -26,11 +26,10 @@ struct BwdArgs {
   __bf16* dK;
   __bf16* dV;
   float* Dvec;   // workspace: rowsum(dO o O), laid out like LSE
-  float* dQacc;  // workspace: float32 accumulator for dQ, [tokens, Hq, d]
 };
 
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st);
-// stages: bit 0 prep, bit 1 main, bit 2 convert
+// stages: bit 0 D pre-pass, bit 1 dK/dV kernel, bit 2 dQ kernel
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st);
 
 }  // namespace fa

@@ -90,12 +90,12 @@ def test_bwd_rejects_bad_arguments():
 
 
 def test_workspace_size_formula():
-    # D (one float per query row and head, rounded up to 256 B) + float32 dQ accumulator
-    assert binding.fa_bwd_workspace_bytes(1, 2, 2, 128, 64) == 1024 + 128 * 2 * 64 * 4
-    assert binding.fa_bwd_workspace_bytes(2, 16, 16, 8192, 128) == 2 * 8192 * 16 * 4 + 2 * 8192 * 16 * 128 * 4
-    assert binding.fa_varlen_bwd_workspace_bytes(100, 4, 2, 128) == 1792 + 100 * 4 * 128 * 4
+    # D: one float per query row and head, rounded up to 256 bytes
+    assert binding.fa_bwd_workspace_bytes(1, 2, 2, 128, 64) == 1024
+    assert binding.fa_bwd_workspace_bytes(2, 16, 16, 8192, 128) == 2 * 8192 * 16 * 4
+    assert binding.fa_varlen_bwd_workspace_bytes(100, 4, 2, 128) == 1792
     assert binding.fa_bwd_workspace_bytes(0, 2, 2, 128, 64) == 0
-    assert binding.fa_bwd_workspace_bytes(1, 8, 2, 16, 128) >= 16 * 8 * 128 * 4
+    assert binding.fa_bwd_workspace_bytes(1, 8, 2, 16, 128) >= 16 * 8 * 4
 
 
 def test_varlen_rejects_bad_arguments():
