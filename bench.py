@@ -8,9 +8,10 @@ counted with the paper's formula (section 4.1): forward 4*N^2*d FLOPs per head
 and sequence, halved under the causal mask, backward 2.5x that.
 
 Prints ONE JSON line. Besides the contract fields it carries
-  roofline     - the dominant kernel (backward main) against the bf16 MFMA peak,
-                 its duration measured with HIP events inside the timed loop;
-  roofline_fwd - the same for the forward kernel;
+  roofline     - the dominant kernel (backward dK/dV) against the bf16 MFMA peak: the
+                 FLOPs of the four products it performs divided by its duration, which
+                 is measured with HIP events inside the timed loop;
+  roofline_fwd, roofline_dq - the same for the forward and the dQ kernels;
   cpu_baseline - the float64 oracle timed on the host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -97,7 +98,7 @@ def main() -> int:
 
     def step(ev=None):
         """fa_fwd + the three backward launches, in the order fa_bwd issues them; with `ev`
-        the forward kernel and the backward main kernel are bracketed by events."""
+        the forward, dK/dV and dQ kernels are bracketed by events."""
         if ev:
             ev[0].record()
         binding.fa_fwd(Q, K, V, sc, ca, O=O, LSE=LSE)
@@ -112,12 +113,14 @@ def main() -> int:
         if ev:
             ev[3].record()
         binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 4, dQ, dK, dV, ws)
+        if ev:
+            ev[4].record()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     # events are recorded on torch's current stream, the one the kernels are launched on
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -154,8 +157,12 @@ def main() -> int:
         "roofline_fwd": dict(roof(fwd_fl, fwd_ms), kernel="fwd_kernel"),
     }
     if not args.fwd_only:
-        main_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
-        out["roofline"] = dict(roof(bwd_fl, main_ms), kernel="bwd_kernel")
+        # metric FLOPs count 5 products (2.5 x forward); the dK/dV kernel performs 4 of them
+        # (S, dP, dV, dK) and the dQ kernel 3 (S, dP recomputed, dQ): 2 x and 1.5 x forward
+        dkdv_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+        dq_ms = sum(e[3].elapsed_time(e[4]) for e in evs) / args.steps
+        out["roofline"] = dict(roof(2.0 * fwd_fl, dkdv_ms), kernel="bwd_dkdv_kernel")
+        out["roofline_dq"] = dict(roof(1.5 * fwd_fl, dq_ms), kernel="bwd_dq_kernel")
     else:
         out["roofline"] = out["roofline_fwd"]
     if not args.no_cpu_baseline:

@@ -36,17 +36,6 @@ fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Hq, int Hkv, lo
   return p;
 }
 
-// Row-block shape of the forward kernel. FA_FWD_NQ=1|2 overrides it for tuning runs.
-int pick_fwd_nq(int d, int max_n) {
-  if (const char* e = std::getenv("FA_FWD_NQ")) {
-    int v = std::atoi(e);
-    if (v == 1 || v == 2) return v;
-  }
-  (void)d;
-  (void)max_n;
-  return 1;
-}
-
 size_t ws_bytes(long tokens, int Hq, int d) {
   (void)d;
   return round_up((size_t)tokens * Hq * sizeof(float), 256);  // D = rowsum(dO o O)
@@ -61,7 +50,6 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
   a.V = (const __bf16*)V;
   a.O = (__bf16*)O;
   a.LSE = LSE;
-  a.cfg_nq = pick_fwd_nq(d, N);
   hipError_t e = fa::launch_fwd(a, d, causal, (hipStream_t)stream);
   if (e != hipSuccess) {
     g_last_hip_error = (int)e;

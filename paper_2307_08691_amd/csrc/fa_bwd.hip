@@ -26,6 +26,7 @@
 // dQ_i^T += K_j^T dS^T, with K_j^T from transposing reads of the K tile.
 #include "fa_common.h"
 #include "fa_kernels.h"
+#include "fa_lds.h"
 
 namespace fa {
 
@@ -59,78 +60,6 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
   }
 }
 
-// Workgroup barrier that only waits for this wavefront's LDS traffic: global
-// loads and atomics that are still in flight stay in flight across it.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// ---- swizzled LDS tiles -----------------------------------------------------
-// Tiles are stored without padding, rows of ROWB = 128 or 256 bytes, as 16-byte
-// chunks whose position inside the row is XOR-ed with a function of the row. The
-// function is chosen so that BOTH access patterns used here are conflict free:
-//   * 16-byte row reads, 16 consecutive rows at the same chunk index, and
-//   * transposing 8-byte reads, 4 consecutive rows x 64 contiguous bytes.
-template <int ROWB>
-__device__ __forceinline__ int swz(int row) {
-  if (ROWB == 256) return ((row & 3) << 2) | ((row >> 2) & 3);
-  const int k = (row >> 1) & 7;  // two 128-byte rows share one 256-byte bank line
-  return ((k & 1) << 2) | (k >> 1);
-}
-template <int ROWB>
-__device__ __forceinline__ int swz_off(int row, int chunk) { return row * ROWB + 16 * (chunk ^ swz<ROWB>(row)); }
-
-// MFMA operand whose rows are tile rows row0 + (lane % 32) and whose contraction
-// slots are the 8 elements starting at column col0 + 8 * (lane / 32).
-template <int ROWB>
-__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int row0, int col0, int lane) {
-  return *(const bf16x8*)(tile + swz_off<ROWB>(row0 + (lane & 31), (col0 >> 3) + (lane >> 5)));
-}
-// MFMA operand whose rows are tile COLUMNS col0 + (lane % 32) and whose contraction
-// slots are tile rows row0 + {4*hh + 0..3, 8 + 4*hh + 0..3} (hh = lane / 32): the row
-// set registers 8s..8s+7 of a 32x32 accumulator cover.
-template <int ROWB>
-__device__ __forceinline__ bf16x8 frag_cols(const char* tile, int row0, int col0, int lane) {
-  const int p = lane & 15, g16 = (lane >> 4) & 1, hh = lane >> 5;
-  const int row = row0 + 4 * hh + (p >> 2);
-  const int col = col0 + 16 * g16 + 4 * (p & 3);
-  const int within = (col & 7) * 2;
-  s16x4 lo = lds_read_tr((const __bf16*)(tile + swz_off<ROWB>(row, col >> 3) + within));
-  s16x4 hi = lds_read_tr((const __bf16*)(tile + swz_off<ROWB>(row + 8, col >> 3) + within));
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// Copy `nrows` rows of D bf16 elements (row pitch `gstride` elements, first row
-// `row_first`, rows clamped to `row_last`) from global memory straight into a
-// swizzled LDS tile, 16 bytes per lane, without passing through registers. Each
-// wavefront instruction fills 1 KiB of consecutive LDS; the swizzle is applied by
-// choosing which global chunk each lane fetches.
-template <int D, int NROWS, int NW>
-__device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase, long gstride, int row_first,
-                                                int row_last, int wave, int lane) {
-  constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI;
-  static_assert(NI % NW == 0, "tile must divide over the wavefronts");
-#pragma unroll
-  for (int u = 0; u < NI / NW; ++u) {
-    const int rb = (wave + NW * u) * RPI;
-    const int r = rb + lane / CPR;
-    const int c = (lane % CPR) ^ swz<ROWB>(r);
-    int grow = row_first + r;
-    grow = grow < row_last ? grow : row_last;
-    __builtin_amdgcn_global_load_lds((gptr_t)(gbase + (long)grow * gstride + 8 * c), (lptr_t)(tile + rb * ROWB), 16, 0, 0);
-  }
-}
-
-__device__ __forceinline__ bf16x8 lds_b128(const char* smem, int off) { return *(const bf16x8*)(smem + off); }
-__device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int off_hi) {
-  s16x4 lo = lds_read_tr((const __bf16*)(smem + off_lo));
-  s16x4 hi = lds_read_tr((const __bf16*)(smem + off_hi));
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
 
 // dK/dV kernel: 8 wavefronts, two per SIMD so that one can run MFMAs while the other
 // does the elementwise work. Wavefront (kg, qh) owns keys 32*kg.. of the column block

@@ -11,7 +11,6 @@ struct FwdArgs {
   const __bf16* V;
   __bf16* O;
   float* LSE;
-  int cfg_nq;  // 32-row query tiles per wavefront (1 or 2): row block = 128 * cfg_nq
 };
 
 struct BwdArgs {
