@@ -174,29 +174,37 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       // ---- S = Q_i K_j^T (line 10) and dP = dO_i V_j^T (line 13)
       f32x16 S = {0}, dP = {0};
       const int qrow = 32 * qtile * ROWB;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        S = mfma32(lds_b128(smem, (zq ^ (32 * ks)) + qrow), lds_b128(smem, (zk ^ (32 * ks)) + KT_OFF), S);
-        dP = mfma32(lds_b128(smem, (zq ^ (32 * ks)) + qrow + TILEB), lds_b128(smem, (zk ^ (32 * ks)) + VT_OFF), dP);
-      }
+      mfma_stream<2 * KS, 3, 2>(
+          [&](int i) {
+            const int x = 32 * (i >> 1);
+            return OperandPair{lds_b128(smem, (zq ^ x) + qrow + (i & 1) * TILEB),
+                               lds_b128(smem, (zk ^ x) + ((i & 1) ? VT_OFF : KT_OFF))};
+          },
+          [&](int i, const OperandPair& o) {
+            if (i & 1) dP = mfma32(o.a, o.b, dP);
+            else S = mfma32(o.a, o.b, S);
+          });
       // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
       const bool need_mask = (CAUSAL && j0 + 32 * kg + 31 > r0) || (j0 + BC > n);
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int q0 = 32 * qtile + 8 * r4 + 4 * hh;
-        const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + q0 * 4);
-        const f32x4 Dv = *(const f32x4*)(smem + DV_OFF + stat_off + q0 * 4);
+        const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * qtile + 8 * r4 + 4 * hh) * 4);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int r = 4 * r4 + u;
-          float pr = fast_exp2(__builtin_fmaf(S[r], c2, -Lv[u]));
-          if (need_mask) {
-            const bool vis = key_ok && (!CAUSAL || key <= i0 + q0 + u);
-            pr = vis ? pr : 0.f;
-          }
-          S[r] = pr;
-          dP[r] = pr * (dP[r] - Dv[u]);
+        for (int u = 0; u < 4; ++u) S[4 * r4 + u] = fast_exp2(__builtin_fmaf(S[4 * r4 + u], c2, -Lv[u]));
+      }
+      if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
+        asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const bool vis = key_ok && (!CAUSAL || key <= r0 + acc_row(r, hh));
+          if (!vis) S[r] = 0.f;
         }
+      }
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 Dv = *(const f32x4*)(smem + DV_OFF + stat_off + (32 * qtile + 8 * r4 + 4 * hh) * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dP[4 * r4 + u] = S[4 * r4 + u] * (dP[4 * r4 + u] - Dv[u]);
       }
       bf16x8 Pf[2], dSf[2];
 #pragma unroll
@@ -205,15 +213,17 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         dSf[s2] = pack8(dP, s2);
       }
       // ---- dV_j^T += dO_i^T P (line 12), dK_j^T += Q_i^T dS (line 16)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const int ro = (32 * qtile + 16 * s2) * ROWB;
-          const int a0 = (zc0 ^ (64 * dt)) + ro, a1 = (zc1 ^ (64 * dt)) + ro;
-          dVt[dt] = mfma32(lds_tr_pair(smem, a0 + TILEB, a1 + TILEB), Pf[s2], dVt[dt]);
-          dKt[dt] = mfma32(lds_tr_pair(smem, a0, a1), dSf[s2], dKt[dt]);
-        }
+      mfma_stream<4 * DT, 4, 2>(
+          [&](int i) {
+            const int dt = i >> 2, s2 = (i >> 1) & 1;
+            const int ro = (32 * qtile + 16 * s2) * ROWB + (i & 1) * TILEB;
+            return lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro);
+          },
+          [&](int i, bf16x8 x) {
+            const int dt = i >> 2, s2 = (i >> 1) & 1;
+            if (i & 1) dVt[dt] = mfma32(x, Pf[s2], dVt[dt]);
+            else dKt[dt] = mfma32(x, dSf[s2], dKt[dt]);
+          });
     }
     // the next step's tiles and statistics were requested before this step's compute
     wait_vmem();
@@ -345,31 +355,33 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
       for (int kt = 0; kt < 2; ++kt) {
         // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
         f32x16 S = {0}, dP = {0};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          S = mfma32(lds_b128(smem, (zk ^ (32 * ks)) + 32 * kt * ROWB), Qf[ks], S);
-          dP = mfma32(lds_b128(smem, (zk ^ (32 * ks)) + 32 * kt * ROWB + TILEB), dOf[ks], dP);
-        }
+        mfma_stream<2 * KS, 6, 1>(
+            [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + 32 * kt * ROWB + (i & 1) * TILEB); },
+            [&](int i, bf16x8 x) {
+              if (i & 1) dP = mfma32(x, dOf[i >> 1], dP);
+              else S = mfma32(x, Qf[i >> 1], S);
+            });
         // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pr = fast_exp2(__builtin_fmaf(S[r], c2, -Lq));
-          if (need_mask) pr = (col0 + 32 * kt + acc_row(r, hh) <= lim_row) ? pr : 0.f;
-          dP[r] = pr * (dP[r] - Dq);
+        for (int r = 0; r < 16; ++r) S[r] = fast_exp2(__builtin_fmaf(S[r], c2, -Lq));
+        if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
+          asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[r] = 0.f;
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dP[r] = S[r] * (dP[r] - Dq);
         dSf[kt][0] = pack8(dP, 0);
         dSf[kt][1] = pack8(dP, 1);
       }
       // ---- dQ_i^T += K_j^T dS^T (line 15)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const int ro = (32 * kt + 16 * s2) * ROWB;
-            dQt[dt] = mfma32(lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro), dSf[kt][s2], dQt[dt]);
-          }
+      mfma_stream<4 * DT, 4, 2>(
+          [&](int i) {
+            const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
+            return lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro);
+          },
+          [&](int i, bf16x8 x) { dQt[i >> 2] = mfma32(x, dSf[(i >> 1) & 1][i & 1], dQt[i >> 2]); });
     }
     wait_vmem();
     lds_barrier();  // next tiles visible; this step's tiles are free

@@ -77,4 +77,37 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int 
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
+// Issue-order hints for the machine scheduler (one scheduling group each, in program
+// order): without them the compiler tends to wait for every LDS operand right before
+// the MFMA that uses it, which exposes the LDS latency once per MFMA.
+#define FA_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define FA_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+#define FA_SCHED_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
+
+struct OperandPair {
+  bf16x8 a, b;
+};
+
+// A sequence of N MFMAs whose operands come from LDS, with the operand reads issued
+// AHEAD MFMAs early. load(i) returns the operand(s) of MFMA i (a bf16x8 or an
+// OperandPair), mma(i, operands) performs MFMA i; READS is the number of LDS read
+// instructions load(i) takes.
+template <int N, int AHEAD, int READS, class LoadF, class MmaF>
+__device__ __forceinline__ void mfma_stream(LoadF load, MmaF mma) {
+  decltype(load(0)) ring[AHEAD];
+#pragma unroll
+  for (int i = 0; i < AHEAD && i < N; ++i) ring[i] = load(i);
+  FA_SCHED_DSRD(READS * (AHEAD < N ? AHEAD : N));
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const auto cur = ring[i % AHEAD];
+    if (i + AHEAD < N) {
+      ring[i % AHEAD] = load(i + AHEAD);
+      FA_SCHED_DSRD(READS);
+    }
+    mma(i, cur);
+    FA_SCHED_MFMA(1);
+  }
+}
+
 }  // namespace fa
