@@ -1,11 +1,10 @@
 // Forward pass of exact attention for gfx950 (Algorithm 1 of the paper).
 //
-// One workgroup (4 wavefronts) owns one block of BR = 128 query rows of one
+// One workgroup (8 wavefronts) owns one block of BR = 256 query rows of one
 // (sequence, query head) and walks the key/value sequence in blocks of BC = 64
 // (the inner loop over column blocks j; the outer loop over row blocks i is the
 // grid, section 3.2 "Forward pass"). Each wavefront owns 32 whole query rows, so
-// no reduction between wavefronts is ever needed (section 3.3). Two workgroups
-// share a CU: while one wavefront of a SIMD runs MFMAs the other does softmax.
+// no reduction between wavefronts is ever needed (section 3.3).
 //
 // The scores are computed TRANSPOSED, S^T = K_j Q_i^T, with 32x32x16 bf16 MFMAs:
 // a lane then holds 16 keys of ONE query per 32x32 tile, the row maximum and row
@@ -14,8 +13,16 @@
 // second product O^T += V_j^T P^T. V_j^T operands come from transposing LDS reads
 // of the row-major V tile, so nothing is ever transposed in memory.
 //
-// K_j and V_j travel HBM -> LDS directly (no registers), one tile ahead, into the
-// other half of a double buffer; the tiles are swizzled, not padded.
+// Phases. On this chip a wavefront cannot overlap its own MFMAs with its own
+// vector ALU work, but two wavefronts on one SIMD can. The loop is therefore cut
+// into phases separated by workgroup barriers: a matrix phase (S^T for block j
+// and the O^T update with block j-1) and a vector phase (the online softmax of
+// block j). Wavefronts 0-3 and 4-7, which share the four SIMDs pairwise, run the
+// same program one phase apart, so at any time one wavefront of every SIMD is in
+// its matrix phase and the other in its vector phase.
+//
+// K_j and V_j travel HBM -> LDS directly (no registers), two blocks ahead, into a
+// ring of four swizzled (unpadded) buffers shared by all eight wavefronts.
 #include "fa_common.h"
 #include "fa_kernels.h"
 #include "fa_lds.h"
@@ -25,18 +32,20 @@ namespace fa {
 __device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
-  constexpr int BR = 128, BC = 64;
+__global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
+  constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
   constexpr int DT = D / 32;  // 32-row tiles of O^T
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
+  constexpr int LPP = 2 * (BC / (1024 / ROWB)) / 8;   // load instructions per wavefront per (K_j, V_j) pair
 
-  __shared__ __attribute__((aligned(1024))) char smem[2 * BUFB];
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = w >> 2;  // 0: matrix phase on even phases, 1: on odd phases
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
   const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq);
@@ -69,7 +78,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   float m = -INFINITY;  // running row maximum, raw score units
   float l = 0.f;        // this lane's share of the row sum (the two lane halves are added at the end)
 
-  // column blocks to visit: all of them, or (causal) those not entirely above the diagonal
+  // column blocks the workgroup visits: all of them, or (causal) those not entirely above the diagonal
   const int ncol_all = (n + BC - 1) / BC;
   int ncol = ncol_all;
   if (CAUSAL) {
@@ -78,12 +87,16 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     ncol = c < ncol_all ? c : ncol_all;
   }
 
-  auto issue_loads = [&](int j, int buf) {
-    tile_load_async<D, BC, 4>(smem + buf * BUFB, Kb, kstride, j * BC, n - 1, w, lane);
-    tile_load_async<D, BC, 4>(smem + buf * BUFB + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
+  // Every wavefront issues exactly LPP load instructions per block, also past the last block
+  // (rows are clamped, the data is never read): the wait below can then count instructions.
+  auto issue_loads = [&](int j) {
+    char* dst = smem + (j % RING) * BUFB;
+    tile_load_async<D, BC, 8>(dst, Kb, kstride, j * BC, n - 1, w, lane);
+    tile_load_async<D, BC, 8>(dst + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
   };
-  issue_loads(0, 0);
-  wait_vmem();
+  issue_loads(0);
+  issue_loads(1);
+  wait_vmem_upto<LPP>();  // block 0 has landed
   lds_barrier();
 
   // lane constants of the LDS addressing (see fa_lds.h)
@@ -98,87 +111,113 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   const int wrow_last = wrow0 + 31;
   const int lim_row = CAUSAL ? (row < n - 1 ? row : n - 1) : n - 1;  // last visible column of this lane's row
 
-  for (int j = 0; j < ncol; ++j) {
-    const int buf = j & 1;
-    if (j + 1 < ncol) issue_loads(j + 1, buf ^ 1);  // in flight while this tile is computed
-    const int col0 = j * BC;
-    const bool active = !CAUSAL || col0 <= wrow_last;  // else every score of this wavefront is masked
-    if (active) {
-      const int zk = zrow + buf * BUFB;
-      const int zv0 = zcol[0] + buf * BUFB + TILEB, zv1 = zcol[1] + buf * BUFB + TILEB;
+  f32x16 S[2];
+  bf16x8 Pf[2][2];
 
+  // ================= matrix phase j: S^T of block j, O^T update with block j - 1 =================
+  auto matrix_phase = [&](int j) {
+    // a block is skipped by a wavefront when every score it would produce is masked
+    if (j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
       // ---- S^T = K_j Q_i^T (Algorithm 1, line 8)
-      f32x16 S[2];
+      const int zk = zrow + (j % RING) * BUFB;
       S[0] = S[1] = (f32x16){0};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        S[0] = mfma32(lds_b128(smem, zk ^ (32 * ks)), Qf[ks], S[0]);
-        S[1] = mfma32(lds_b128(smem, (zk ^ (32 * ks)) + 32 * ROWB), Qf[ks], S[1]);
-      }
+      mfma_stream<2 * KS, 4, 1>(
+          [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
+          [&](int i, bf16x8 x) { S[i & 1] = mfma32(x, Qf[i >> 1], S[i & 1]); });
+    }
+    if (j >= 1 && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
+      // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10)
+      const int vb = ((j - 1) % RING) * BUFB + TILEB;
+      const int zv0 = zcol[0] + vb, zv1 = zcol[1] + vb;
+      mfma_stream<4 * DT, 3, 2>(
+          [&](int i) {
+            const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
+            return lds_tr_pair(smem, (zv0 ^ (64 * dt)) + ro, (zv1 ^ (64 * dt)) + ro);
+          },
+          [&](int i, bf16x8 x) { O[i >> 2] = mfma32(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
+    }
+  };
 
-      // ---- mask: causal entries above the diagonal and columns past the end
-      const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
-      if (need_mask) {
+  // ================= vector phase j: online softmax of block j (Algorithm 1, line 9) =================
+  auto vector_phase = [&](int j) {
+    if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
+    const int col0 = j * BC;
+    // ---- mask: causal entries above the diagonal and columns past the end
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
+    if (need_mask) {
+      asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[kt][r] = -INFINITY;
-      }
-
-      // ---- online softmax (Algorithm 1, line 9) and rescale of O (line 10)
-      float mx = max3(S[0][0], S[0][1], S[1][0]);
+        for (int r = 0; r < 16; ++r)
+          if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[kt][r] = -INFINITY;
+    }
+    float mx = max3(S[0][0], S[0][1], S[1][0]);
 #pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
-      mx = max3(mx, S[1][1], S[1][2]);
-      mx = fmaxf(mx, S[1][3]);
+    for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
+    mx = max3(mx, S[1][1], S[1][2]);
+    mx = fmaxf(mx, S[1][3]);
 #pragma unroll
-      for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
-      mx = max_with_partner32(mx);
-      const float m_new = fmaxf(m, mx);
-      // column 0 is visible to every row and tiles are walked in ascending order,
-      // so m_new is finite from the first tile on and exp2(-inf) = 0 covers the start.
-      if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
-        const float alpha = fast_exp2((m - m_new) * c2);
-        l *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-        m = m_new;
-      }
-      const float mc = m_new * c2;
-      bf16x8 Pf[2][2];
-      float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], c2, -mc));
-          const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -mc));
-          S[kt][r] = e0;
-          S[kt][r + 1] = e1;
-          rs0 += e0;
-          rs1 += e1;
-        }
-        Pf[kt][0] = pack8(S[kt], 0);
-        Pf[kt][1] = pack8(S[kt], 1);
-      }
-      l += rs0 + rs1;
-
-      // ---- O^T += V_j^T P^T (Algorithm 1, line 10)
+    for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
+    mx = max_with_partner32(mx);
+    const float m_new = fmaxf(m, mx);
+    // column 0 is visible to every row and blocks are walked in ascending order,
+    // so m_new is finite from the first block on and exp2(-inf) = 0 covers the start.
+    // The rescale of O (line 10) is skipped when no row's maximum moved (factor exactly 1).
+    if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
+      const float alpha = fast_exp2((m - m_new) * c2);
+      l *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const int ro = (32 * kt + 16 * s2) * ROWB;
-            O[dt] = mfma32(lds_tr_pair(smem, (zv0 ^ (64 * dt)) + ro, (zv1 ^ (64 * dt)) + ro), Pf[kt][s2], O[dt]);
-          }
+        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+      m = m_new;
     }
-    wait_vmem();
-    lds_barrier();  // next tiles visible; this step's tiles are free
+    const float mc = m_new * c2;
+    float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], c2, -mc));
+        const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -mc));
+        S[kt][r] = e0;
+        S[kt][r + 1] = e1;
+        rs0 += e0;
+        rs1 += e1;
+      }
+      Pf[kt][0] = pack8(S[kt], 0);
+      Pf[kt][1] = pack8(S[kt], 1);
+    }
+    l += rs0 + rs1;
+  };
+
+  // Global phases phi = 0 .. 2 * ncol + 1, a barrier after each. Group 0 runs matrix phase j at
+  // phi = 2j and vector phase j at phi = 2j + 1; group 1 runs one phase later. Loads of block
+  // phi / 2 + 2 are issued at the start of every even phase; at the end of every odd phase all
+  // but the newest block's loads must have landed (that block is read two phases later).
+  if (grp == 0) {
+    for (int j = 0; j <= ncol; ++j) {
+      issue_loads(j + 2);
+      matrix_phase(j);
+      lds_barrier();
+      vector_phase(j);
+      wait_vmem_upto<LPP>();
+      lds_barrier();
+    }
+  } else {
+    issue_loads(2);
+    lds_barrier();
+    for (int j = 0; j <= ncol; ++j) {
+      matrix_phase(j);
+      wait_vmem_upto<LPP>();
+      lds_barrier();
+      if (j < ncol) {
+        issue_loads(j + 3);
+        vector_phase(j);
+        lds_barrier();
+      }
+    }
   }
 
   // ---- epilogue: O = diag(l)^-1 O, L = m + log l (Algorithm 1, lines 12-15)
@@ -203,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
 
 template <int D>
 static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
-  dim3 grid((unsigned)((a.p.N + 127) / 128) * a.p.Hq * a.p.nseq), block(256);
+  dim3 grid((unsigned)((a.p.N + 255) / 256) * a.p.Hq * a.p.nseq), block(512);
   if (causal) hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((fwd_kernel<D, false>), grid, block, 0, st, a);
   return hipGetLastError();

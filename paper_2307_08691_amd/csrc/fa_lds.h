@@ -9,6 +9,12 @@ namespace fa {
 // loads and atomics that are still in flight stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Wait until at most N of this wavefront's global loads (they complete in order) are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vmem_upto() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // ---- swizzled LDS tiles -----------------------------------------------------
 // Tiles are stored without padding, rows of ROWB = 128 or 256 bytes, as 16-byte
