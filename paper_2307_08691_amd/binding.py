@@ -11,7 +11,7 @@ import os
 from typing import Optional, Tuple
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libfa_gfx950.so")
+LIB_PATH = os.environ.get("FA_LIB_PATH") or os.path.join(HERE, "libfa_gfx950.so")  # override: tuning builds
 
 FA_OK = 0
 FA_ERR_NULL = -1

@@ -29,9 +29,10 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every HIP source and link the shared library. Always recompiles."""
-    cmd = [hipcc(), *FLAGS, *extra_flags, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Compile every HIP source and link the shared library. Always recompiles.
+    `extra_flags` (e.g. -DFA_FWD_AHEAD_QK=6) and `out` serve tuning builds."""
+    cmd = [hipcc(), *FLAGS, *extra_flags, "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -41,7 +42,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err:
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

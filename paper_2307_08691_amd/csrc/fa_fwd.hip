@@ -27,6 +27,23 @@
 #include "fa_kernels.h"
 #include "fa_lds.h"
 
+// How many MFMAs ahead the LDS operands of the two products are requested.
+#ifndef FA_FWD_AHEAD_QK
+#define FA_FWD_AHEAD_QK 4
+#endif
+#ifndef FA_FWD_AHEAD_PV
+#define FA_FWD_AHEAD_PV 3
+#endif
+#ifndef FA_FWD_MATRIX_PRIO
+#define FA_FWD_MATRIX_PRIO 2
+#endif
+// The running maximum is only advanced (and O, l rescaled) when some row's maximum grew by
+// more than 2^FA_FWD_LAZY_LOG2; until then exponentials are taken against the older
+// reference and may reach 2^FA_FWD_LAZY_LOG2. 0 = advance on every change.
+#ifndef FA_FWD_LAZY_LOG2
+#define FA_FWD_LAZY_LOG2 8
+#endif
+
 namespace fa {
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
@@ -89,10 +106,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
   // Every wavefront issues exactly LPP load instructions per block, also past the last block
   // (rows are clamped, the data is never read): the wait below can then count instructions.
+  TileLoader<D, BC, 8> loader;
+  loader.init(kstride, w, lane);
   auto issue_loads = [&](int j) {
     char* dst = smem + (j % RING) * BUFB;
-    tile_load_async<D, BC, 8>(dst, Kb, kstride, j * BC, n - 1, w, lane);
-    tile_load_async<D, BC, 8>(dst + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
+    loader.load(dst, Kb, kstride, j * BC, n - 1, w, lane);
+    loader.load(dst + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
   };
   issue_loads(0);
   issue_loads(1);
@@ -116,12 +135,13 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
   // ================= matrix phase j: S^T of block j, O^T update with block j - 1 =================
   auto matrix_phase = [&](int j) {
+    __builtin_amdgcn_s_setprio(FA_FWD_MATRIX_PRIO);  // the MFMA stream must not wait behind the other group's VALU work
     // a block is skipped by a wavefront when every score it would produce is masked
     if (j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
       // ---- S^T = K_j Q_i^T (Algorithm 1, line 8)
       const int zk = zrow + (j % RING) * BUFB;
       S[0] = S[1] = (f32x16){0};
-      mfma_stream<2 * KS, 4, 1>(
+      mfma_stream<2 * KS, FA_FWD_AHEAD_QK, 1>(
           [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
           [&](int i, bf16x8 x) { S[i & 1] = mfma32(x, Qf[i >> 1], S[i & 1]); });
     }
@@ -129,13 +149,14 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
       // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10)
       const int vb = ((j - 1) % RING) * BUFB + TILEB;
       const int zv0 = zcol[0] + vb, zv1 = zcol[1] + vb;
-      mfma_stream<4 * DT, 3, 2>(
+      mfma_stream<4 * DT, FA_FWD_AHEAD_PV, 2>(
           [&](int i) {
             const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
             return lds_tr_pair(smem, (zv0 ^ (64 * dt)) + ro, (zv1 ^ (64 * dt)) + ro);
           },
           [&](int i, bf16x8 x) { O[i >> 2] = mfma32(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
     }
+    __builtin_amdgcn_s_setprio(0);
   };
 
   // ================= vector phase j: online softmax of block j (Algorithm 1, line 9) =================
@@ -163,8 +184,11 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const float m_new = fmaxf(m, mx);
     // column 0 is visible to every row and blocks are walked in ascending order,
     // so m_new is finite from the first block on and exp2(-inf) = 0 covers the start.
-    // The rescale of O (line 10) is skipped when no row's maximum moved (factor exactly 1).
-    if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
+    // Rescaling O (line 10) by exp(m_old - m_new) only matters for the range of the numbers,
+    // not for the result: O and l are relative to the same reference m whatever it is. The
+    // reference is therefore advanced only when some row's maximum outgrew it by a factor
+    // 2^FA_FWD_LAZY_LOG2, which after the first few blocks is rare.
+    if (__builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)FA_FWD_LAZY_LOG2) != 0) {
       const float alpha = fast_exp2((m - m_new) * c2);
       l *= alpha;
 #pragma unroll
@@ -173,7 +197,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
       m = m_new;
     }
-    const float mc = m_new * c2;
+    const float mc = m * c2;
+    // the row sum is taken from the float32 exponentials, not from their bf16 roundings:
+    // rows that see only a few keys would otherwise miss the 1e-3 bound on L
     float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -196,12 +222,32 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   // phi = 2j and vector phase j at phi = 2j + 1; group 1 runs one phase later. Loads of block
   // phi / 2 + 2 are issued at the start of every even phase; at the end of every odd phase all
   // but the newest block's loads must have landed (that block is read two phases later).
+#ifdef FA_TRACE
+  // tuning builds only: wavefronts 0 and 4 of workgroup 0 log the shader clock at every phase
+  // boundary into the floats that follow the LSE tensor (the caller over-allocates it)
+  int* trace = (int*)(a.LSE + (long)p.nseq * p.Hq * p.N) + grp * 2048;
+  int tn = 0;
+  const long long tr0 = clock64();
+  const bool tron = blockIdx.x == 0 && (w & 3) == 0 && lane == 0;
+#define FA_TRACE_POINT() \
+  do {                   \
+    if (tron && tn < 2040) trace[tn++] = (int)(clock64() - tr0); \
+  } while (0)
+#else
+#define FA_TRACE_POINT() \
+  do {                   \
+  } while (0)
+#endif
   if (grp == 0) {
     for (int j = 0; j <= ncol; ++j) {
       issue_loads(j + 2);
+      FA_TRACE_POINT();
       matrix_phase(j);
+      FA_TRACE_POINT();
       lds_barrier();
+      FA_TRACE_POINT();
       vector_phase(j);
+      FA_TRACE_POINT();
       wait_vmem_upto<LPP>();
       lds_barrier();
     }
@@ -209,12 +255,16 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     issue_loads(2);
     lds_barrier();
     for (int j = 0; j <= ncol; ++j) {
+      FA_TRACE_POINT();
       matrix_phase(j);
+      FA_TRACE_POINT();
       wait_vmem_upto<LPP>();
       lds_barrier();
       if (j < ncol) {
         issue_loads(j + 3);
+        FA_TRACE_POINT();
         vector_phase(j);
+        FA_TRACE_POINT();
         lds_barrier();
       }
     }

@@ -83,6 +83,37 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int 
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
+// The same copy for kernels that stream many tiles of one tensor: the per-lane byte offsets
+// of an interior tile are computed once (TileLoader::init) and every tile then costs one
+// scalar base-address update plus the load instructions. Tiles that reach past `row_last`
+// take the clamping path above.
+template <int D, int NROWS, int NW>
+struct TileLoader {
+  static constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI, PER = NI / NW;
+  static_assert(NI % NW == 0, "tile must divide over the wavefronts");
+  unsigned voff[PER];  // byte offset of this lane's chunk from the tile's first row
+  __device__ __forceinline__ void init(long gstride, int wave, int lane) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int r = (wave + NW * u) * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ swz<ROWB>(r);
+      voff[u] = (unsigned)(r * gstride + 8 * c) * 2u;
+    }
+  }
+  __device__ __forceinline__ void load(char* tile, const __bf16* gbase, long gstride, int row_first, int row_last,
+                                       int wave, int lane) const {
+    if (row_first + NROWS - 1 <= row_last) {
+      const char* base = (const char*)(gbase + (long)row_first * gstride);  // wave-uniform
+#pragma unroll
+      for (int u = 0; u < PER; ++u)
+        __builtin_amdgcn_global_load_lds((gptr_t)(base + voff[u]), (lptr_t)(tile + (wave + NW * u) * RPI * ROWB), 16, 0,
+                                         0);
+    } else {
+      tile_load_async<D, NROWS, NW>(tile, gbase, gstride, row_first, row_last, wave, lane);
+    }
+  }
+};
+
 // Issue-order hints for the machine scheduler (one scheduling group each, in program
 // order): without them the compiler tends to wait for every LDS operand right before
 // the MFMA that uses it, which exposes the LDS latency once per MFMA.
