@@ -52,8 +52,26 @@ __device__ __forceinline__ bf16x8 frag_cols(const char* tile, int row0, int col0
   return __builtin_bit_cast(bf16x8, v);
 }
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
+// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane i's
+// data lands at lds + 16 * i, `lds` being wave-uniform. Written as inline assembly on
+// purpose: the compiler would otherwise make every later LDS read wait for ALL outstanding
+// copies (it cannot tell the ring buffers apart), which serialises the prefetch. The
+// kernels order these copies themselves with wait_vmem*() + barriers. M0 holds the LDS
+// base for the duration of the instruction only; the compiler keeps no value live in M0.
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p;
+}
+__device__ __forceinline__ void dma16(const void* gaddr, const void* lds) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gaddr),
+               "s"(__builtin_amdgcn_readfirstlane(lds_address(lds)))
+               : "memory");
+}
+// same with a wave-uniform base pointer and a 32-bit per-lane byte offset
+__device__ __forceinline__ void dma16_uniform(const void* gbase, unsigned voff, const void* lds) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase),
+               "s"(__builtin_amdgcn_readfirstlane(lds_address(lds)))
+               : "memory");
+}
 
 // Copy `nrows` rows of D bf16 elements (row pitch `gstride` elements, first row
 // `row_first`, rows clamped to `row_last`) from global memory straight into a
@@ -72,7 +90,7 @@ __device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase,
     const int c = (lane % CPR) ^ swz<ROWB>(r);
     int grow = row_first + r;
     grow = grow < row_last ? grow : row_last;
-    __builtin_amdgcn_global_load_lds((gptr_t)(gbase + (long)grow * gstride + 8 * c), (lptr_t)(tile + rb * ROWB), 16, 0, 0);
+    dma16(gbase + (long)grow * gstride + 8 * c, tile + rb * ROWB);
   }
 }
 
@@ -106,8 +124,7 @@ struct TileLoader {
       const char* base = (const char*)(gbase + (long)row_first * gstride);  // wave-uniform
 #pragma unroll
       for (int u = 0; u < PER; ++u)
-        __builtin_amdgcn_global_load_lds((gptr_t)(base + voff[u]), (lptr_t)(tile + (wave + NW * u) * RPI * ROWB), 16, 0,
-                                         0);
+        dma16_uniform(base, voff[u], tile + (wave + NW * u) * RPI * ROWB);
     } else {
       tile_load_async<D, NROWS, NW>(tile, gbase, gstride, row_first, row_last, wave, lane);
     }
