@@ -91,7 +91,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int v = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = v & 3, qh = v >> 2;
   const int lq = lane & 31, hh = lane >> 5;
-  const BlockCoord bc = block_coord<CAUSAL>((p.N + BC - 1) / BC, p.Hkv);  // causal: block 0 is the longest
+  const BlockCoord bc = block_coord((p.N + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
+  if (!bc.valid) return;
   const int g = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
   const int n = si.n;
@@ -281,7 +282,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq);
+  const BlockCoord bc = block_coord(nblk, p.Hq, p.nseq);
+  if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
@@ -328,6 +330,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
     tile_load_async<D, BC, 4>(smem + buf * BUFB + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
   };
   issue_loads(0, 0);
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    touch(Qf[ks]);
+    touch(dOf[ks]);
+  }
+  touch(Lq);
+  touch(Dq);
   wait_vmem();
   lds_barrier();
 
@@ -412,13 +421,13 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 2) {
-    dim3 grid((unsigned)((a.p.N + 127) / 128) * a.p.Hkv * a.p.nseq);
+    dim3 grid(grid_size((a.p.N + 127) / 128, a.p.Hkv * a.p.nseq));
     if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true>), grid, dim3(512), 0, st, a);
     else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false>), grid, dim3(512), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 4) {
-    dim3 grid((unsigned)((a.p.N + 127) / 128) * a.p.Hq * a.p.nseq);
+    dim3 grid(grid_size((a.p.N + 127) / 128, a.p.Hq * a.p.nseq));
     if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((bwd_dq_kernel<D, false>), grid, dim3(256), 0, st, a);
     e = hipGetLastError();

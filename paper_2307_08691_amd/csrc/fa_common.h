@@ -52,31 +52,33 @@ __device__ __forceinline__ SeqInfo seq_info(const Problem& p, int s) {
   return r;
 }
 
-// Launch index -> (block of rows or columns, head, sequence). Kernels are launched on a
-// 1-D grid of nblk * nheads * nseq workgroups, dispatched in index order. Under the
-// causal mask the work of a block grows (row blocks) or shrinks (column blocks) with its
-// index, so there the block index is the SLOW coordinate: all heads' heaviest blocks go
-// first and the lightest fill the tail. Without a mask every block costs the same and
-// the block index is the fast coordinate, which keeps one head's K/V hot in L2.
+// Launch index -> (block of rows or columns, head, sequence).
+//
+// The chip has 8 XCDs, each with 32 CUs and a private 4 MiB L2; the hardware hands
+// consecutive workgroup indices to consecutive XCDs. Every workgroup of one (head,
+// sequence) pair streams the same K/V (or Q/dO) through L2, about 4 MiB at d = 128 and
+// N = 8192. The mapping below therefore gives all blocks of a pair to ONE XCD and lets an
+// XCD walk its pairs one after the other, so its 32 CUs share one pair's operands at a time
+// instead of thrashing L2 with eight. Under the causal mask a pair's blocks are dispatched
+// heaviest first. Kernels are launched on grid_size(nblk, pairs) workgroups; indices that
+// fall past the last pair return valid = false.
+constexpr int kXcds = 8;
 struct BlockCoord {
   int blk, head, seq;
+  bool valid;
 };
-template <bool WORK_SORTED>
-__device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads) {
+__host__ __device__ inline unsigned grid_size(int nblk, int pairs) {
+  return (unsigned)(((pairs + kXcds - 1) / kXcds) * kXcds * nblk);
+}
+__device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads, int nseq) {
   const int L = blockIdx.x;
+  const int x = L % kXcds, k = L / kXcds;
+  const int pr = (k / nblk) * kXcds + x;
   BlockCoord c;
-  if (WORK_SORTED) {
-    const int pairs = gridDim.x / nblk;
-    const int pr = L % pairs;
-    c.blk = L / pairs;
-    c.head = pr % nheads;
-    c.seq = pr / nheads;
-  } else {
-    c.blk = L % nblk;
-    const int pr = L / nblk;
-    c.head = pr % nheads;
-    c.seq = pr / nheads;
-  }
+  c.blk = k % nblk;
+  c.head = pr % nheads;
+  c.seq = pr / nheads;
+  c.valid = pr < nheads * nseq;
   return c;
 }
 

@@ -55,17 +55,21 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   constexpr int DT = D / 32;  // 32-row tiles of O^T
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
-  constexpr int LPP = 2 * (BC / (1024 / ROWB)) / 8;   // load instructions per wavefront per (K_j, V_j) pair
 
   __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef FA_EXP_SWAP_GROUPS
+  const int grp = 1 - (w >> 2);
+#else
   const int grp = w >> 2;  // 0: matrix phase on even phases, 1: on odd phases
+#endif
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq);
+  const BlockCoord bc = block_coord(nblk, p.Hq, p.nseq);
+  if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
@@ -104,19 +108,27 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     ncol = c < ncol_all ? c : ncol_all;
   }
 
-  // Every wavefront issues exactly LPP load instructions per block, also past the last block
-  // (rows are clamped, the data is never read): the wait below can then count instructions.
-  TileLoader<D, BC, 8> loader;
-  loader.init(kstride, w, lane);
-  auto issue_loads = [&](int j) {
-    char* dst = smem + (j % RING) * BUFB;
-    loader.load(dst, Kb, kstride, j * BC, n - 1, w, lane);
-    loader.load(dst + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
+  // Tile loads. Issuing a tile's copies stalls the issuing wavefronts for a few hundred
+  // cycles (the memory pipeline takes 16 bytes x 64 lanes at a time), so a wavefront only
+  // issues copies at the start of its VECTOR phase, while the other group keeps the MFMA pipe
+  // busy: group 1 brings in the K tiles, group 0 the V tiles, each two blocks ahead. Every
+  // wavefront issues exactly TPW copies per own vector phase, also past the last block (rows
+  // are clamped, the data is never read), so the waits below can count instructions.
+  TileLoader<D, BC, 4> loader;
+  loader.init(kstride, w & 3, lane);
+  constexpr int TPW = TileLoader<D, BC, 4>::PER;  // copies per wavefront per tile
+  auto issue_tile = [&](int j) {  // group 0: V_j, group 1: K_j
+    char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
+    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, n - 1, w & 3, lane);
   };
-  issue_loads(0);
-  issue_loads(1);
-  wait_vmem_upto<LPP>();  // block 0 has landed
-  lds_barrier();
+  {  // blocks 0 and 1: both tiles, split over the two groups as above
+    issue_tile(0);
+    issue_tile(1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
+    wait_vmem();
+    lds_barrier();
+  }
 
   // lane constants of the LDS addressing (see fa_lds.h)
   const int zrow = lq * ROWB + 16 * (hh ^ swz<ROWB>(lq));
@@ -219,16 +231,20 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   };
 
   // Global phases phi = 0 .. 2 * ncol + 1, a barrier after each. Group 0 runs matrix phase j at
-  // phi = 2j and vector phase j at phi = 2j + 1; group 1 runs one phase later. Loads of block
-  // phi / 2 + 2 are issued at the start of every even phase; at the end of every odd phase all
-  // but the newest block's loads must have landed (that block is read two phases later).
+  // phi = 2j and vector phase j at phi = 2j + 1; group 1 runs one phase later. K_{m+2} is
+  // requested (by group 1) at phi = 2m and first read at phi = 2m + 4; V_{m+2} is requested
+  // (by group 0) at phi = 2m + 1 and first read at phi = 2m + 6. A group waits, at the end of
+  // a later phase of its own, until only its newest tile is still in flight.
 #ifdef FA_TRACE
+#ifndef FA_TRACE_BLOCK
+#define FA_TRACE_BLOCK 0
+#endif
   // tuning builds only: wavefronts 0 and 4 of workgroup 0 log the shader clock at every phase
   // boundary into the floats that follow the LSE tensor (the caller over-allocates it)
   int* trace = (int*)(a.LSE + (long)p.nseq * p.Hq * p.N) + grp * 2048;
   int tn = 0;
   const long long tr0 = clock64();
-  const bool tron = blockIdx.x == 0 && (w & 3) == 0 && lane == 0;
+  const bool tron = blockIdx.x == FA_TRACE_BLOCK && (w & 3) == 0 && lane == 0;
 #define FA_TRACE_POINT() \
   do {                   \
     if (tron && tn < 2040) trace[tn++] = (int)(clock64() - tr0); \
@@ -240,28 +256,29 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #endif
   if (grp == 0) {
     for (int j = 0; j <= ncol; ++j) {
-      issue_loads(j + 2);
       FA_TRACE_POINT();
       matrix_phase(j);
       FA_TRACE_POINT();
       lds_barrier();
+      issue_tile(j + 2);
       FA_TRACE_POINT();
       vector_phase(j);
       FA_TRACE_POINT();
-      wait_vmem_upto<LPP>();
+      wait_vmem_upto<TPW>();
+      FA_TRACE_POINT();
       lds_barrier();
     }
   } else {
-    issue_loads(2);
+    issue_tile(2);
     lds_barrier();
     for (int j = 0; j <= ncol; ++j) {
       FA_TRACE_POINT();
       matrix_phase(j);
       FA_TRACE_POINT();
-      wait_vmem_upto<LPP>();
+      wait_vmem_upto<TPW>();
       lds_barrier();
       if (j < ncol) {
-        issue_loads(j + 3);
+        issue_tile(j + 3);
         FA_TRACE_POINT();
         vector_phase(j);
         FA_TRACE_POINT();
@@ -292,7 +309,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
 template <int D>
 static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
-  dim3 grid((unsigned)((a.p.N + 255) / 256) * a.p.Hq * a.p.nseq), block(512);
+  dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq)), block(512);
   if (causal) hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((fwd_kernel<D, false>), grid, block, 0, st, a);
   return hipGetLastError();

@@ -131,6 +131,17 @@ struct TileLoader {
   }
 };
 
+// Tell the compiler that a value loaded from global memory is needed NOW. The kernels
+// order their direct-to-LDS copies with hand-written s_waitcnt (the compiler does not see
+// those copies), so the compiler never learns that ordinary loads issued before the main
+// loop have long completed and would re-wait for them, with vmcnt(0), inside the loop,
+// which also waits for every copy in flight. Touching the values once before the loop makes
+// it place that wait there.
+template <class T>
+__device__ __forceinline__ void touch(const T& x) {
+  asm volatile("" ::"v"(x));
+}
+
 // Issue-order hints for the machine scheduler (one scheduling group each, in program
 // order): without them the compiler tends to wait for every LDS operand right before
 // the MFMA that uses it, which exposes the LDS latency once per MFMA.
