@@ -266,20 +266,23 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   }
 }
 
-// dQ kernel: 4 wavefronts, each owning 32 whole query rows of a 128-row block; two
-// workgroups per CU. K_j, V_j tiles of 64 keys stream HBM -> LDS one step ahead.
+// dQ kernel: 8 wavefronts, each owning 32 whole query rows of a 256-row block. Same phase
+// structure as the forward kernel: a matrix phase (S^T, dP^T of block j and the dQ^T update
+// with block j - 1) and a vector phase (P and dS of block j), the two wave groups one phase
+// apart, K_j / V_j tiles streaming HBM -> LDS two blocks ahead into a ring of four buffers.
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
-  constexpr int BR = 128, BC = 64;
+__global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
+  constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
 
-  __shared__ __attribute__((aligned(1024))) char smem[2 * BUFB];
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = w >> 2;  // 0: matrix phase on even phases, 1: on odd phases
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
   const BlockCoord bc = block_coord(nblk, p.Hq, p.nseq);
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
   const int i0 = rowblk * BR;
   if (i0 >= n) return;
   const int g = h / p.G;
-  const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
+  const long kstride = (long)p.Hkv * D;
   const __bf16* Kb = a.K + (si.tok0 * p.Hkv + g) * D;
   const __bf16* Vb = a.V + (si.tok0 * p.Hkv + g) * D;
 
@@ -325,11 +328,17 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
     ncol = c < ncol_all ? c : ncol_all;
   }
 
-  auto issue_loads = [&](int j, int buf) {
-    tile_load_async<D, BC, 4>(smem + buf * BUFB, Kb, kstride, j * BC, n - 1, w, lane);
-    tile_load_async<D, BC, 4>(smem + buf * BUFB + TILEB, Vb, kstride, j * BC, n - 1, w, lane);
+  // tile copies: group 1 brings in the K tiles, group 0 the V tiles, each at the start of its
+  // own vector phase (see the forward kernel)
+  TileLoader<D, BC, 4> loader;
+  loader.init(kstride, w & 3, lane);
+  constexpr int TPW = TileLoader<D, BC, 4>::PER;
+  auto issue_tile = [&](int j) {
+    char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
+    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, n - 1, w & 3, lane);
   };
-  issue_loads(0, 0);
+  issue_tile(0);
+  issue_tile(1);
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     touch(Qf[ks]);
@@ -351,49 +360,86 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(BwdArgs a) {
   const int wrow_last = wrow0 + 31;
   const int lim_row = CAUSAL ? (row < n - 1 ? row : n - 1) : n - 1;  // last visible column of this lane's row
 
-  for (int j = 0; j < ncol; ++j) {
-    const int buf = j & 1;
-    if (j + 1 < ncol) issue_loads(j + 1, buf ^ 1);
-    const int col0 = j * BC;
-    const bool active = !CAUSAL || col0 <= wrow_last;  // else every score of this wavefront is masked
-    if (active) {
-      const int zk = zrow + buf * BUFB, zc0 = zcol[0] + buf * BUFB, zc1 = zcol[1] + buf * BUFB;
-      const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
-      bf16x8 dSf[2][2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
-        f32x16 S = {0}, dP = {0};
-        mfma_stream<2 * KS, 6, 1>(
-            [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + 32 * kt * ROWB + (i & 1) * TILEB); },
-            [&](int i, bf16x8 x) {
-              if (i & 1) dP = mfma32(x, dOf[i >> 1], dP);
-              else S = mfma32(x, Qf[i >> 1], S);
-            });
-        // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[r] = fast_exp2(__builtin_fmaf(S[r], c2, -Lq));
-        if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
-          asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[r] = 0.f;
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dP[r] = S[r] * (dP[r] - Dq);
-        dSf[kt][0] = pack8(dP, 0);
-        dSf[kt][1] = pack8(dP, 1);
-      }
-      // ---- dQ_i^T += K_j^T dS^T (line 15)
-      mfma_stream<4 * DT, 4, 2>(
+  f32x16 S[2], dP[2];
+  bf16x8 dSf[2][2];
+
+  // ================= matrix phase j =================
+  auto matrix_phase = [&](int j) {
+    __builtin_amdgcn_s_setprio(2);
+    if (j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
+      // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
+      const int zk = zrow + (j % RING) * BUFB;
+      S[0] = S[1] = dP[0] = dP[1] = (f32x16){0};
+      mfma_stream<4 * KS, 4, 1>(
+          [&](int i) {
+            const int ks = i >> 2, kt = (i >> 1) & 1;
+            return lds_b128(smem, (zk ^ (32 * ks)) + 32 * kt * ROWB + (i & 1) * TILEB);
+          },
+          [&](int i, bf16x8 x) {
+            const int ks = i >> 2, kt = (i >> 1) & 1;
+            if (i & 1) dP[kt] = mfma32(x, dOf[ks], dP[kt]);
+            else S[kt] = mfma32(x, Qf[ks], S[kt]);
+          });
+    }
+    if (j >= 1 && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
+      // ---- dQ_i^T += K_{j-1}^T dS^T (line 15)
+      const int kb = ((j - 1) % RING) * BUFB;
+      const int zc0 = zcol[0] + kb, zc1 = zcol[1] + kb;
+      mfma_stream<4 * DT, 3, 2>(
           [&](int i) {
             const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
             return lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro);
           },
           [&](int i, bf16x8 x) { dQt[i >> 2] = mfma32(x, dSf[(i >> 1) & 1][i & 1], dQt[i >> 2]); });
     }
-    wait_vmem();
-    lds_barrier();  // next tiles visible; this step's tiles are free
+    __builtin_amdgcn_s_setprio(0);
+  };
+
+  // ================= vector phase j: P = exp(S - L) (line 11), dS = P o (dP - D) (line 14) =================
+  auto vector_phase = [&](int j) {
+    if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
+    const int col0 = j * BC;
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) S[kt][r] = fast_exp2(__builtin_fmaf(S[kt][r], c2, -Lq));
+      if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
+        asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[kt][r] = 0.f;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dP[kt][r] = S[kt][r] * (dP[kt][r] - Dq);
+      dSf[kt][0] = pack8(dP[kt], 0);
+      dSf[kt][1] = pack8(dP[kt], 1);
+    }
+  };
+
+  // phases: see the forward kernel
+  if (grp == 0) {
+    for (int j = 0; j <= ncol; ++j) {
+      matrix_phase(j);
+      lds_barrier();
+      issue_tile(j + 2);
+      vector_phase(j);
+      wait_vmem_upto<TPW>();
+      lds_barrier();
+    }
+  } else {
+    issue_tile(2);
+    lds_barrier();
+    for (int j = 0; j <= ncol; ++j) {
+      matrix_phase(j);
+      wait_vmem_upto<TPW>();
+      lds_barrier();
+      if (j < ncol) {
+        issue_tile(j + 3);
+        vector_phase(j);
+        lds_barrier();
+      }
+    }
   }
 
   if (row < n) {
@@ -427,9 +473,9 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 4) {
-    dim3 grid(grid_size((a.p.N + 127) / 128, a.p.Hq * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bwd_dq_kernel<D, false>), grid, dim3(256), 0, st, a);
+    dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+    if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((bwd_dq_kernel<D, false>), grid, dim3(512), 0, st, a);
     e = hipGetLastError();
   }
   return e;

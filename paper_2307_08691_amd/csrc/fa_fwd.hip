@@ -142,6 +142,25 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   const int wrow_last = wrow0 + 31;
   const int lim_row = CAUSAL ? (row < n - 1 ? row : n - 1) : n - 1;  // last visible column of this lane's row
 
+#ifdef FA_TRACE
+#ifndef FA_TRACE_BLOCK
+#define FA_TRACE_BLOCK 0
+#endif
+  // tuning builds only: wavefronts 0 and 4 of workgroup 0 log the shader clock at every phase
+  // boundary into the floats that follow the LSE tensor (the caller over-allocates it)
+  int* trace = (int*)(a.LSE + (long)p.nseq * p.Hq * p.N) + grp * 2048;
+  int tn = 0;
+  const long long tr0 = clock64();
+  const bool tron = blockIdx.x == FA_TRACE_BLOCK && (w & 3) == 0 && lane == 0;
+#define FA_TRACE_POINT() \
+  do {                   \
+    if (tron && tn < 2040) trace[tn++] = (int)(clock64() - tr0); \
+  } while (0)
+#else
+#define FA_TRACE_POINT() \
+  do {                   \
+  } while (0)
+#endif
   f32x16 S[2];
   bf16x8 Pf[2][2];
 
@@ -193,6 +212,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
     for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
     mx = max_with_partner32(mx);
+    FA_TRACE_POINT();
     const float m_new = fmaxf(m, mx);
     // column 0 is visible to every row and blocks are walked in ascending order,
     // so m_new is finite from the first block on and exp2(-inf) = 0 covers the start.
@@ -209,6 +229,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
       m = m_new;
     }
+    FA_TRACE_POINT();
     const float mc = m * c2;
     // the row sum is taken from the float32 exponentials, not from their bf16 roundings:
     // rows that see only a few keys would otherwise miss the 1e-3 bound on L
@@ -235,25 +256,6 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   // requested (by group 1) at phi = 2m and first read at phi = 2m + 4; V_{m+2} is requested
   // (by group 0) at phi = 2m + 1 and first read at phi = 2m + 6. A group waits, at the end of
   // a later phase of its own, until only its newest tile is still in flight.
-#ifdef FA_TRACE
-#ifndef FA_TRACE_BLOCK
-#define FA_TRACE_BLOCK 0
-#endif
-  // tuning builds only: wavefronts 0 and 4 of workgroup 0 log the shader clock at every phase
-  // boundary into the floats that follow the LSE tensor (the caller over-allocates it)
-  int* trace = (int*)(a.LSE + (long)p.nseq * p.Hq * p.N) + grp * 2048;
-  int tn = 0;
-  const long long tr0 = clock64();
-  const bool tron = blockIdx.x == FA_TRACE_BLOCK && (w & 3) == 0 && lane == 0;
-#define FA_TRACE_POINT() \
-  do {                   \
-    if (tron && tn < 2040) trace[tn++] = (int)(clock64() - tr0); \
-  } while (0)
-#else
-#define FA_TRACE_POINT() \
-  do {                   \
-  } while (0)
-#endif
   if (grp == 0) {
     for (int j = 0; j <= ncol; ++j) {
       FA_TRACE_POINT();
