@@ -109,7 +109,11 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 
   // Q_i, dO_i (line 9) go HBM -> LDS directly, one step ahead, into the other buffer;
   // L_i, D_i travel through two registers of the first BR threads.
-  float lreg = 0.f, dreg = 0.f;
+  // The raw statistics are only touched (scaled, masked) when they are committed to LDS at
+  // the end of the step: using them earlier would make the compiler wait for them right
+  // after the tile copies were issued, i.e. for the copies themselves.
+  float lraw = 0.f, draw = 0.f;
+  bool stat_ok = false;
   auto issue_loads = [&](int t, int buf) {
     const int hq = g * p.G + t / per_head;
     const int i0 = (i_first + t % per_head) * BR;
@@ -117,17 +121,18 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     tile_load_async<D, BR, 8>(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
     tile_load_async<D, BR, 8>(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
     if (tid < BR) {
-      const bool ok = i0 + tid < n;
-      const long si_ = stat_base + (long)hq * p.lse_head_stride + i0 + tid;
-      // rows past the end get L = +inf so that P = exp2(. - inf) = 0 there
-      lreg = ok ? a.LSE[si_] * kLog2e : INFINITY;
-      dreg = ok ? a.Dvec[si_] : 0.f;
+      stat_ok = i0 + tid < n;
+      const int r = stat_ok ? i0 + tid : n - 1;
+      const long si_ = stat_base + (long)hq * p.lse_head_stride + r;
+      lraw = a.LSE[si_];
+      draw = a.Dvec[si_];
     }
   };
   auto commit_stats = [&](int buf) {
     if (tid < BR) {
-      *(float*)(smem + LS_OFF + (buf * BR + tid) * 4) = lreg;
-      *(float*)(smem + DV_OFF + (buf * BR + tid) * 4) = dreg;
+      // rows past the end get L = +inf so that P = exp2(. - inf) = 0 there
+      *(float*)(smem + LS_OFF + (buf * BR + tid) * 4) = stat_ok ? lraw * kLog2e : INFINITY;
+      *(float*)(smem + DV_OFF + (buf * BR + tid) * 4) = stat_ok ? draw : 0.f;
     }
   };
 
