@@ -91,7 +91,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int v = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = v & 3, qh = v >> 2;
   const int lq = lane & 31, hh = lane >> 5;
-  const BlockCoord bc = block_coord((p.N + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
+  const BlockCoord bc = block_coord<CAUSAL>((p.N + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
   if (!bc.valid) return;
   const int g = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const int grp = w >> 2;  // 0: matrix phase on even phases, 1: on odd phases
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord(nblk, p.Hq, p.nseq);
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq);
   if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;

@@ -59,8 +59,9 @@ __device__ __forceinline__ SeqInfo seq_info(const Problem& p, int s) {
 // sequence) pair streams the same K/V (or Q/dO) through L2, about 4 MiB at d = 128 and
 // N = 8192. The mapping below therefore gives all blocks of a pair to ONE XCD and lets an
 // XCD walk its pairs one after the other, so its 32 CUs share one pair's operands at a time
-// instead of thrashing L2 with eight. Under the causal mask a pair's blocks are dispatched
-// heaviest first. Kernels are launched on grid_size(nblk, pairs) workgroups; indices that
+// instead of thrashing L2 with eight. Under the causal mask block costs differ by up to
+// the number of blocks, so there the XCD's pairs are interleaved and all their heaviest
+// blocks are dispatched first (longest-processing-time order), lightest last. Kernels are launched on grid_size(nblk, pairs) workgroups; indices that
 // fall past the last pair return valid = false.
 constexpr int kXcds = 8;
 struct BlockCoord {
@@ -70,12 +71,21 @@ struct BlockCoord {
 __host__ __device__ inline unsigned grid_size(int nblk, int pairs) {
   return (unsigned)(((pairs + kXcds - 1) / kXcds) * kXcds * nblk);
 }
+template <bool WORK_SORTED>
 __device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads, int nseq) {
   const int L = blockIdx.x;
   const int x = L % kXcds, k = L / kXcds;
-  const int pr = (k / nblk) * kXcds + x;
+  const int ppx = gridDim.x / (kXcds * nblk);  // pairs per XCD
+  int pl;                                       // which of this XCD's pairs
   BlockCoord c;
-  c.blk = k % nblk;
+  if (WORK_SORTED) {  // causal: the XCD's pairs take turns, every pair's heaviest blocks first
+    c.blk = k / ppx;
+    pl = k % ppx;
+  } else {  // one pair at a time
+    c.blk = k % nblk;
+    pl = k / nblk;
+  }
+  const int pr = pl * kXcds + x;
   c.head = pr % nheads;
   c.seq = pr / nheads;
   c.valid = pr < nheads * nseq;

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #endif
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord(nblk, p.Hq, p.nseq);
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq);
   if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;
