@@ -114,12 +114,14 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // after the tile copies were issued, i.e. for the copies themselves.
   float lraw = 0.f, draw = 0.f;
   bool stat_ok = false;
+  TileLoader<D, BR, 8> qloader;  // Q_i and dO_i tiles have the same shape and row pitch
+  qloader.init(qstride, v, lane);
   auto issue_loads = [&](int t, int buf) {
     const int hq = g * p.G + t / per_head;
     const int i0 = (i_first + t % per_head) * BR;
     char* dst = smem + QDO_OFF + buf * BUFB;
-    tile_load_async<D, BR, 8>(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
-    tile_load_async<D, BR, 8>(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
+    qloader.load(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
+    qloader.load(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
     if (tid < BR) {
       stat_ok = i0 + tid < n;
       const int r = stat_ok ? i0 + tid : n - 1;
