@@ -61,35 +61,57 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 }
 
 
-// dK/dV kernel: 8 wavefronts, two per SIMD so that one can run MFMAs while the other
-// does the elementwise work. Wavefront (kg, qh) owns keys 32*kg.. of the column block
-// and the query tiles qh*QTW.. of each step.
+// dK/dV kernel: 8 wavefronts in two groups of four. Wavefront (kg, grp) owns keys 32*kg..
+// of the column block; the groups take the 32*QTW-row query tiles alternately (group = tile
+// index mod 2) and accumulate partial dK_j^T, dV_j^T over their own tiles.
+//
+// Phases. Tile T passes through three stages, one per global phase, a workgroup barrier
+// after every phase:
+//   phase T     M : S = Q_i K_j^T (line 10) and dP = dO_i V_j^T (line 13)          [MFMA]
+//   phase T + 1 V : P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)           [vector ALU]
+//   phase T + 2 M': dV_j^T += dO_i^T P (line 12), dK_j^T += Q_i^T dS (line 16)      [MFMA]
+// so in phase F the group F mod 2 is in its matrix phase (M' of tile F - 2, then M of tile F)
+// while the other group is in its vector phase (V of tile F - 1): the two wavefronts of a
+// SIMD alternate between the matrix pipe and the vector ALU.
+//
+// Q_i | dO_i tiles live in a ring of 5 LDS slots shared by the groups: tile T is read in
+// phases T and T + 2, its slot is refilled with tile T + 5, requested at the start of the
+// vector phase F = T + 3 (by the group in that phase, so the copy instructions do not hold up
+// the matrix pipe) and complete before the barrier that ends phase F + 1.
 //
 // LDS addressing. Every tile is swizzled (see swz<>). Because the XOR only touches
 // address bits 4..7 while row offsets live in bits >= 7/8, the address of every MFMA
 // operand is (lane constant) ^ (compile-time constant) + (immediate): the lane
 // constants are a handful of registers computed once, instead of one register per
 // distinct operand.
+#ifndef FA_DKDV_AHEAD
+#define FA_DKDV_AHEAD 4
+#endif
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int BC = 128;               // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
-  constexpr int BR = 64 * QTW;          // query rows per step
+  constexpr int BR = 32 * QTW;          // query rows of one tile
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int ROWB = 2 * D;           // row bytes of the Q_i, dO_i, K_j, V_j tiles
+  constexpr int RING = 5;
   // byte offsets inside the LDS block
   constexpr int KT_OFF = 0, VT_OFF = BC * ROWB, QDO_OFF = 2 * BC * ROWB;
-  constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one buffer = Q_i | dO_i
-  constexpr int LS_OFF = QDO_OFF + 2 * BUFB, DV_OFF = LS_OFF + 2 * BR * 4;
-  constexpr int SMEM = DV_OFF + 2 * BR * 4;
+  constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one ring slot = Q_i | dO_i
+  constexpr int LS_OFF = QDO_OFF + RING * BUFB;       // [slot][row] floats
+  constexpr int DV_OFF = LS_OFF + RING * BR * 4;
+  constexpr int SMEM = DV_OFF + RING * BR * 4;
   static_assert(VT_OFF + BC * ROWB <= 65536 && BUFB <= 32768, "immediate offsets must fit 16 bits");
+  static_assert(4 * DT * 16 * 64 * 4 <= RING * BUFB, "the final reduction reuses the ring");
+  static_assert(SMEM <= 160 * 1024, "LDS of one compute unit");
 
   __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
   const int v = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kg = v & 3, qh = v >> 2;
+  const int kg = v & 3, grp = v >> 2;
+  const int gtid = tid & 255;  // thread index inside the group
   const int lq = lane & 31, hh = lane >> 5;
   const BlockCoord bc = block_coord<CAUSAL>((p.N + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
   if (!bc.valid) return;
@@ -101,49 +123,120 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
 
   const float c2 = p.scale_log2e;
-  const int nrb = (n + BR - 1) / BR;
-  const int i_first = CAUSAL ? j0 / BR : 0;  // row blocks entirely above the diagonal are skipped
-  const int per_head = nrb - i_first;
-  const int nsteps = per_head * p.G;
+  const int nrt = (n + BR - 1) / BR;         // row tiles of the sequence
+  const int i_first = CAUSAL ? j0 / BR : 0;  // row tiles entirely above the diagonal are skipped
+  const int T = (nrt - i_first) * p.G;       // tiles this workgroup visits, over the group's query heads
   const long stat_base = s * p.lse_seq_stride + (p.cu_seqlens ? si.tok0 : 0);
 
-  // Q_i, dO_i (line 9) go HBM -> LDS directly, one step ahead, into the other buffer;
-  // L_i, D_i travel through two registers of the first BR threads.
-  // The raw statistics are only touched (scaled, masked) when they are committed to LDS at
-  // the end of the step: using them earlier would make the compiler wait for them right
-  // after the tile copies were issued, i.e. for the copies themselves.
-  float lraw = 0.f, draw = 0.f;
-  bool stat_ok = false;
-  TileLoader<D, BR, 8> qloader;  // Q_i and dO_i tiles have the same shape and row pitch
-  qloader.init(qstride, v, lane);
-  auto issue_loads = [&](int t, int buf) {
-    const int hq = g * p.G + t / per_head;
-    const int i0 = (i_first + t % per_head) * BR;
-    char* dst = smem + QDO_OFF + buf * BUFB;
-    qloader.load(dst, a.Q + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
-    qloader.load(dst + TILEB, a.dO + (si.tok0 * p.Hq + hq) * D, qstride, i0, n - 1, v, lane);
-    if (tid < BR) {
-      stat_ok = i0 + tid < n;
-      const int r = stat_ok ? i0 + tid : n - 1;
-      const long si_ = stat_base + (long)hq * p.lse_head_stride + r;
-      lraw = a.LSE[si_];
-      draw = a.Dvec[si_];
+#ifdef FA_TRACE
+  // tuning builds only: wavefronts 0 and 4 of workgroup 0 log the shader clock at phase
+  // boundaries into spare LDS; the log is copied into the (unused) dQ buffer at the end
+  __shared__ int trace_lds[2][1536];
+  int tn = 0;
+  const long long tr0 = clock64();
+  const bool tron = blockIdx.x == 0 && kg == 0 && lane == 0;
+#define FA_STAMP() do { if (tron && tn < 1536) trace_lds[grp][tn++] = (int)(clock64() - tr0); } while (0)
+#else
+#define FA_STAMP() do {} while (0)
+#endif
+#if FA_TRACE == 2
+#define FA_TP() do {} while (0)
+#define FA_TP2() FA_STAMP()
+#else
+#define FA_TP() FA_STAMP()
+#define FA_TP2() do {} while (0)
+#endif
+
+  // Position of a tile in the visiting order: query head, row tile, ring slot, and where the
+  // tile starts in Q / dO (elements) and in L / D. Advancing is a few scalar additions.
+  struct Cursor {
+    int hq, it, slot;
+    long qoff, soff;
+  };
+  const long wrap_q = D - (long)(nrt - i_first) * BR * qstride;  // last row tile of a head -> first of the next
+  const long wrap_s = p.lse_head_stride - (long)(nrt - i_first) * BR;
+  auto advance = [&](Cursor& c, int steps) {
+    for (int k = 0; k < steps; ++k) {
+      ++c.it;
+      c.qoff += BR * qstride;
+      c.soff += BR;
+      if (c.it == nrt) {
+        c.it = i_first;
+        ++c.hq;
+        c.qoff += wrap_q;
+        c.soff += wrap_s;
+      }
+      c.slot = c.slot + 1 == RING ? 0 : c.slot + 1;
     }
   };
-  auto commit_stats = [&](int buf) {
-    if (tid < BR) {
-      // rows past the end get L = +inf so that P = exp2(. - inf) = 0 there
-      *(float*)(smem + LS_OFF + (buf * BR + tid) * 4) = stat_ok ? lraw * kLog2e : INFINITY;
-      *(float*)(smem + DV_OFF + (buf * BR + tid) * 4) = stat_ok ? draw : 0.f;
+  const Cursor tile0 = {g * p.G, i_first, 0, ((si.tok0 + (long)i_first * BR) * p.Hq + g * p.G) * D,
+                        stat_base + (long)g * p.G * p.lse_head_stride + (long)i_first * BR};
+
+  // Q_i, dO_i (line 9) go HBM -> LDS directly; L_i, D_i travel through two registers of the
+  // issuing group's first BR threads. The raw statistics are only touched (scaled, masked)
+  // when they are committed to LDS: using them earlier would make the compiler wait for
+  // them, and with them for the copies in flight.
+  float lraw = 0.f, draw = 0.f;
+  bool stat_ok = false;
+  TileLoader<D, BR, 4> qloader;  // Q_i and dO_i tiles have the same shape and row pitch
+  qloader.init(qstride, kg, lane);
+  auto issue_loads = [&](const Cursor& c) {
+    char* dst = smem + QDO_OFF + c.slot * BUFB;
+    if ((c.it + 1) * BR <= n) {  // all rows exist
+      qloader.load_at(dst, a.Q + c.qoff, kg);
+      qloader.load_at(dst + TILEB, a.dO + c.qoff, kg);
+      if (gtid < BR) {
+        stat_ok = true;
+        lraw = (a.LSE + c.soff)[gtid];
+        draw = (a.Dvec + c.soff)[gtid];
+      }
+    } else {  // the last rows of the sequence: rows past the end repeat row n - 1
+      const int i0 = c.it * BR;
+      const long first = c.qoff - (long)i0 * qstride;  // row 0 of this head
+      tile_load_async<D, BR, 4>(dst, a.Q + first, qstride, i0, n - 1, kg, lane);
+      tile_load_async<D, BR, 4>(dst + TILEB, a.dO + first, qstride, i0, n - 1, kg, lane);
+      if (gtid < BR) {
+        stat_ok = i0 + gtid < n;
+        const int r = stat_ok ? gtid : n - 1 - i0;
+        lraw = (a.LSE + c.soff)[r];
+        draw = (a.Dvec + c.soff)[r];
+      }
+    }
+  };
+  auto commit_stats = [&](int slot) {
+    if (gtid < BR) {
+      const int o = (slot * BR + gtid) * 4;
+      // L in the exponent's base; rows past the end get L = +inf so that P = exp2(. - inf) = 0.
+      // D is stored negated: it is the initial value of the dP accumulator (line 14).
+      *(float*)(smem + LS_OFF + o) = stat_ok ? lraw * kLog2e : INFINITY;
+      *(float*)(smem + DV_OFF + o) = stat_ok ? -draw : 0.f;
     }
   };
 
-  // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop
+  // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop; tiles 0..2 are
+  //      requested up front by all wavefronts
   tile_load_async<D, BC, 8>(smem + KT_OFF, a.K + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
   tile_load_async<D, BC, 8>(smem + VT_OFF, a.V + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
-  issue_loads(0, 0);
+  {
+    Cursor c = tile0;
+    for (int t = 0; t < 3 && t < T; ++t) {
+      const long first = c.qoff - (long)c.it * BR * qstride;  // row 0 of this head
+      char* dst = smem + QDO_OFF + c.slot * BUFB;
+      tile_load_async<D, BR, 8>(dst, a.Q + first, qstride, c.it * BR, n - 1, v, lane);
+      tile_load_async<D, BR, 8>(dst + TILEB, a.dO + first, qstride, c.it * BR, n - 1, v, lane);
+      if (tid >= t * BR && tid < (t + 1) * BR) {  // 3 * BR <= 512 threads
+        const int row = c.it * BR + tid - t * BR;
+        const bool ok = row < n;
+        const long si_ = stat_base + (long)c.hq * p.lse_head_stride + (ok ? row : n - 1);
+        const float l = a.LSE[si_], dd = a.Dvec[si_];
+        const int o = (c.slot * BR + tid - t * BR) * 4;
+        *(float*)(smem + LS_OFF + o) = ok ? l * kLog2e : INFINITY;
+        *(float*)(smem + DV_OFF + o) = ok ? -dd : 0.f;
+      }
+      advance(c, 1);
+    }
+  }
   wait_vmem();
-  commit_stats(0);
   lds_barrier();
 
   // ---- lane constants of the LDS addressing
@@ -159,7 +252,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int zk = zrow + 32 * kg * ROWB;  // K_j / V_j row operands of this wavefront
 
   // ---- dK_j^T, dV_j^T accumulators (line 7): rows = head dim, columns = this wavefront's
-  //      32 keys; partial over this wavefront's half of the query rows
+  //      32 keys; partial over this group's tiles
   f32x16 dKt[DT], dVt[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dKt[dt] = dVt[dt] = (f32x16){0};
@@ -167,92 +260,191 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int key = j0 + 32 * kg + lq;  // this lane's key column
   const bool key_ok = key < n;
 
-  for (int t = 0; t < nsteps; ++t) {
-    const int buf = t & 1;
-    const int i0 = (i_first + t % per_head) * BR;
-    if (t + 1 < nsteps) issue_loads(t + 1, buf ^ 1);
-    const int qoff = QDO_OFF + buf * BUFB;  // this step's Q_i tile; dO_i follows at + TILEB
-    const int zq = zrow + qoff, zc0 = zcol[0] + qoff, zc1 = zcol[1] + qoff;
-    const int stat_off = buf * BR * 4;
+  f32x16 S[QTW], dP[QTW];
+  bf16x8 Pf[QTW][2], dSf[QTW][2];
 
+  // ---- the MFMA work of a tile, as index -> (operand reads, MFMA) maps for mfma_stream_*
+  constexpr int NM = QTW * 2 * KS;   // S and dP: 16 MFMAs
+  constexpr int NM2 = QTW * 4 * DT;  // dV and dK: 16 MFMAs
+  constexpr int AH = FA_DKDV_AHEAD;
+  bf16x8 pre[AH];  // first operands of the next M', requested at the end of the vector phase before it
+  auto load_m = [&](const Cursor& c, int i) {  // operands of S (even i) and dP (odd i)
+    const int tq = i / (2 * KS), k = i % (2 * KS), x = 32 * (k >> 1);
+    const int zq = zrow + QDO_OFF + c.slot * BUFB;
+    if (k == 1) {
+      // dP starts at -D_i, so the products leave dP - D in the accumulator (line 14); read
+      // together with the operands of the first dP product
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 Dn = *(const f32x4*)(smem + DV_OFF + c.slot * BR * 4 + (32 * tq + 8 * r4 + 4 * hh) * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dP[tq][4 * r4 + u] = Dn[u];
+      }
+      FA_SCHED_DSRD(4);
+    }
+    return OperandPair{lds_b128(smem, (zq ^ x) + 32 * tq * ROWB + (i & 1) * TILEB),
+                       lds_b128(smem, (zk ^ x) + ((i & 1) ? VT_OFF : KT_OFF))};
+  };
+  auto mma_m = [&](int i, const OperandPair& o) {
+    const int tq = i / (2 * KS), k = i % (2 * KS);
+    if (k & 1) dP[tq] = mfma32(o.a, o.b, dP[tq]);
+    else S[tq] = mfma32(o.a, o.b, k == 0 ? (f32x16){0} : S[tq]);
+  };
+  auto load_m2 = [&](const Cursor& c, int i) {  // Q_i^T (even i) or dO_i^T (odd i) operand of dK / dV
+    const int tq = i / (4 * DT), k = i % (4 * DT), dt = k >> 2, s2 = (k >> 1) & 1;
+    const int qoff = QDO_OFF + c.slot * BUFB + (32 * tq + 16 * s2) * ROWB + (i & 1) * TILEB;
+    return lds_tr_pair(smem, ((zcol[0] + qoff) ^ (64 * dt)), ((zcol[1] + qoff) ^ (64 * dt)));
+  };
+  auto mma_m2 = [&](int i, bf16x8 x) {
+    const int tq = i / (4 * DT), k = i % (4 * DT), dt = k >> 2, s2 = (k >> 1) & 1;
+    if (i & 1) dVt[dt] = mfma32(x, Pf[tq][s2], dVt[dt]);
+    else dKt[dt] = mfma32(x, dSf[tq][s2], dKt[dt]);
+  };
+  auto phase_v = [&](const Cursor& c) {  // P, dS
+    const int i0 = c.it * BR;
+    const int stat_off = c.slot * BR * 4;
 #pragma unroll
     for (int tq = 0; tq < QTW; ++tq) {
-      const int qtile = qh * QTW + tq;
-      const int r0 = i0 + 32 * qtile;  // first query row of this tile
-      // ---- S = Q_i K_j^T (line 10) and dP = dO_i V_j^T (line 13)
-      f32x16 S = {0}, dP = {0};
-      const int qrow = 32 * qtile * ROWB;
-      mfma_stream<2 * KS, 3, 2>(
-          [&](int i) {
-            const int x = 32 * (i >> 1);
-            return OperandPair{lds_b128(smem, (zq ^ x) + qrow + (i & 1) * TILEB),
-                               lds_b128(smem, (zk ^ x) + ((i & 1) ? VT_OFF : KT_OFF))};
-          },
-          [&](int i, const OperandPair& o) {
-            if (i & 1) dP = mfma32(o.a, o.b, dP);
-            else S = mfma32(o.a, o.b, S);
-          });
-      // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
+      const int r0 = i0 + 32 * tq;  // first query row of this tile
       const bool need_mask = (CAUSAL && j0 + 32 * kg + 31 > r0) || (j0 + BC > n);
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * qtile + 8 * r4 + 4 * hh) * 4);
+        const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * tq + 8 * r4 + 4 * hh) * 4);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) S[4 * r4 + u] = fast_exp2(__builtin_fmaf(S[4 * r4 + u], c2, -Lv[u]));
+        for (int u = 0; u < 4; ++u) S[tq][4 * r4 + u] = fast_exp2(__builtin_fmaf(S[tq][4 * r4 + u], c2, -Lv[u]));
       }
       if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
         asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const bool vis = key_ok && (!CAUSAL || key <= r0 + acc_row(r, hh));
-          if (!vis) S[r] = 0.f;
+          if (!vis) S[tq][r] = 0.f;
         }
       }
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const f32x4 Dv = *(const f32x4*)(smem + DV_OFF + stat_off + (32 * qtile + 8 * r4 + 4 * hh) * 4);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) dP[4 * r4 + u] = S[4 * r4 + u] * (dP[4 * r4 + u] - Dv[u]);
-      }
-      bf16x8 Pf[2], dSf[2];
+      for (int r = 0; r < 16; ++r) dP[tq][r] *= S[tq][r];  // dS = P o (dP - D)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        Pf[s2] = pack8(S, s2);
-        dSf[s2] = pack8(dP, s2);
+        Pf[tq][s2] = pack8(S[tq], s2);
+        dSf[tq][s2] = pack8(dP[tq], s2);
       }
-      // ---- dV_j^T += dO_i^T P (line 12), dK_j^T += Q_i^T dS (line 16)
-      mfma_stream<4 * DT, 4, 2>(
-          [&](int i) {
-            const int dt = i >> 2, s2 = (i >> 1) & 1;
-            const int ro = (32 * qtile + 16 * s2) * ROWB + (i & 1) * TILEB;
-            return lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro);
-          },
-          [&](int i, bf16x8 x) {
-            const int dt = i >> 2, s2 = (i >> 1) & 1;
-            if (i & 1) dVt[dt] = mfma32(x, Pf[s2], dVt[dt]);
-            else dKt[dt] = mfma32(x, dSf[s2], dKt[dt]);
-          });
     }
-    // the next step's tiles and statistics were requested before this step's compute
+  };
+
+  // Phases 0 .. T + 1. This group's matrix phases are tau = grp, grp + 2, ..; each is followed
+  // by its vector phase tau + 1. Group 1 idles through phase 0. A matrix phase is one stream
+  // of MFMAs, M' of the previous tile running into M of the current one, and the first
+  // operand reads of M' are issued at the end of the vector phase before it: the tile they
+  // read has been in LDS for two phases, so they need not wait for the barrier.
+  Cursor cur = tile0, prev = tile0, ld = tile0;
+  advance(cur, grp);
+  advance(ld, 3 + grp);  // first refill: tile 3 in phase 1 (group 0), tile 4 in phase 2 (group 1)
+  int pending = -1;      // ring slot whose statistics wait in lraw / draw
+  auto end_matrix_phase = [&]() {
+    __builtin_amdgcn_s_setprio(0);
+    FA_TP();
+    // The copies requested in the last vector phase: complete, then visible. The wait and the
+    // touches are unconditional so that the compiler sees no path on which the statistics
+    // loads are still in flight when their registers are written again: it would otherwise
+    // put a full wait right behind the next tile's copy requests.
     wait_vmem();
-    commit_stats(buf ^ 1);
-    lds_barrier();  // next tiles visible; nobody reads this step's Q_i / dO_i any more
+    touch(lraw);
+    touch(draw);
+    if (pending >= 0) {
+      commit_stats(pending);
+      pending = -1;
+    }
+    FA_TP();
+    lds_barrier();
+  };
+  auto vector_phase = [&](int tau, bool do_v) {  // phase tau + 1, if it exists
+    if (tau + 1 > T + 1) return;
+    FA_TP();
+    if (tau + 3 < T) {  // the slot of tile tau - 2, free since the last barrier
+      issue_loads(ld);
+      pending = ld.slot;
+      advance(ld, 2);
+    }
+    FA_TP();
+    if (do_v) {
+      phase_v(cur);
+      mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
+    }
+    FA_TP();
+    lds_barrier();
+  };
+
+  int tau = grp;
+  if (grp == 1) lds_barrier();
+  // the group's first matrix phase: M only
+  const bool have_first = tau < T;
+  FA_TP();
+  if (have_first) {
+    __builtin_amdgcn_s_setprio(2);
+    mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
+  }
+  end_matrix_phase();
+  vector_phase(tau, have_first);
+  prev = cur;
+  advance(cur, 2);
+  // steady state: M' of the previous tile, then M of the current one
+  for (tau += 2; tau < T; tau += 2) {
+    FA_TP();
+    __builtin_amdgcn_s_setprio(2);
+    OperandPair ring[AH];
+#pragma unroll
+    for (int i = 0; i < AH; ++i) ring[i].a = pre[i];
+    mfma_stream_run<NM2 + NM, AH, 2>(
+        ring,
+        [&](int i) {
+          if (i < NM2) {
+            const bf16x8 x = load_m2(prev, i);
+            return OperandPair{x, x};
+          }
+          return load_m(cur, i - NM2);
+        },
+        [&](int i, const OperandPair& o) {
+          if (i < NM2) mma_m2(i, o.a);
+          else mma_m(i - NM2, o);
+        });
+    end_matrix_phase();
+    vector_phase(tau, true);
+    prev = cur;
+    advance(cur, 2);
+  }
+  // the last tile's M', then whatever phases remain
+  bool have_prev = have_first;
+  for (; tau <= T + 1; tau += 2) {
+    FA_TP();
+    if (have_prev) {
+      __builtin_amdgcn_s_setprio(2);
+      mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
+      have_prev = false;
+    }
+    end_matrix_phase();
+    vector_phase(tau, false);
   }
 
-  // ---- combine the two query halves and write dK_j, dV_j (line 18); dK carries the scaling
-  float* red = (float*)(smem + QDO_OFF);  // 4 * DT * 16 * 64 floats <= 64 KiB, free after the loop
+#ifdef FA_TRACE
+  if (tron) {
+    int* trace = (int*)a.dQ + grp * 2048;
+    for (int i = 0; i < tn; ++i) trace[i] = trace_lds[grp][i];
+  }
+#endif
+  // ---- combine the two groups' partial sums and write dK_j, dV_j (line 18); dK carries the scaling
+  float* red = (float*)(smem + QDO_OFF);  // 4 * DT * 16 * 64 floats, free after the loop
   const float sc = p.scale;
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
     f32x16* accs = which == 0 ? dKt : dVt;
-    if (qh == 1) {
+    if (grp == 1) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) red[((kg * DT + dt) * 16 + r) * 64 + lane] = accs[dt][r];
     }
     __syncthreads();
-    if (qh == 0 && key_ok) {
+    if (grp == 0 && key_ok) {
       __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0 + key) * p.Hkv + g) * D + 4 * hh;
       const float mul = which == 0 ? sc : 1.f;
 #pragma unroll

@@ -68,6 +68,10 @@ __device__ __forceinline__ void dma16(const void* gaddr, const void* lds) {
 }
 // same with a wave-uniform base pointer and a 32-bit per-lane byte offset
 __device__ __forceinline__ void dma16_uniform(const void* gbase, unsigned voff, const void* lds) {
+  // the base must sit in scalar registers whatever the compiler believes about its uniformity
+  const unsigned long long b = (unsigned long long)gbase;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+  gbase = (const void*)(((unsigned long long)hi << 32) | lo);
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase),
                "s"(__builtin_amdgcn_readfirstlane(lds_address(lds)))
                : "memory");
@@ -118,6 +122,11 @@ struct TileLoader {
       voff[u] = (unsigned)(r * gstride + 8 * c) * 2u;
     }
   }
+  // an interior tile whose first row starts at `first_row` (wave-uniform)
+  __device__ __forceinline__ void load_at(char* tile, const __bf16* first_row, int wave) const {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) dma16_uniform(first_row, voff[u], tile + (wave + NW * u) * RPI * ROWB);
+  }
   __device__ __forceinline__ void load(char* tile, const __bf16* gbase, long gstride, int row_first, int row_last,
                                        int wave, int lane) const {
     if (row_first + NROWS - 1 <= row_last) {
@@ -128,6 +137,45 @@ struct TileLoader {
     } else {
       tile_load_async<D, NROWS, NW>(tile, gbase, gstride, row_first, row_last, wave, lane);
     }
+  }
+};
+
+// The same tile copy staged through registers: load() fetches this lane's 16-byte chunks
+// with ordinary global loads (which the compiler tracks, so it places the waits itself) and
+// store() writes them to the swizzled LDS tile later, e.g. one phase after the request.
+template <int D, int NROWS, int NW>
+struct TileStager {
+  static constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI, PER = NI / NW;
+  static_assert(NI % NW == 0, "tile must divide over the wavefronts");
+  unsigned voff[PER];  // byte offset of this lane's chunk from the tile's first row
+  __device__ __forceinline__ void init(long gstride, int wave, int lane) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int r = (wave + NW * u) * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ swz<ROWB>(r);
+      voff[u] = (unsigned)(r * gstride + 8 * c) * 2u;
+    }
+  }
+  __device__ __forceinline__ void load(u32x4 (&regs)[PER], const __bf16* gbase, long gstride, int row_first,
+                                       int row_last, int wave, int lane) const {
+    if (row_first + NROWS - 1 <= row_last) {
+      const char* base = (const char*)(gbase + (long)row_first * gstride);  // wave-uniform
+#pragma unroll
+      for (int u = 0; u < PER; ++u) regs[u] = *(const u32x4*)(base + voff[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < PER; ++u) {
+        const int r = (wave + NW * u) * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ swz<ROWB>(r);
+        int grow = row_first + r;
+        grow = grow < row_last ? grow : row_last;
+        regs[u] = *(const u32x4*)(gbase + (long)grow * gstride + 8 * c);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(char* tile, const u32x4 (&regs)[PER], int wave, int lane) const {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) *(u32x4*)(tile + (wave + NW * u) * RPI * ROWB + 16 * lane) = regs[u];
   }
 };
 
@@ -156,16 +204,20 @@ struct OperandPair {
 // A sequence of N MFMAs whose operands come from LDS, with the operand reads issued
 // AHEAD MFMAs early. load(i) returns the operand(s) of MFMA i (a bf16x8 or an
 // OperandPair), mma(i, operands) performs MFMA i; READS is the number of LDS read
-// instructions load(i) takes.
-template <int N, int AHEAD, int READS, class LoadF, class MmaF>
-__device__ __forceinline__ void mfma_stream(LoadF load, MmaF mma) {
-  decltype(load(0)) ring[AHEAD];
+// instructions load(i) takes. The two halves can be called apart when the first reads may
+// start earlier than the MFMAs (before a barrier, say): begin() issues the reads of MFMAs
+// 0 .. AHEAD-1 into `ring`, run() does everything else.
+template <int N, int AHEAD, int READS, class T, class LoadF>
+__device__ __forceinline__ void mfma_stream_begin(T (&ring)[AHEAD], LoadF load) {
 #pragma unroll
   for (int i = 0; i < AHEAD && i < N; ++i) ring[i] = load(i);
   FA_SCHED_DSRD(READS * (AHEAD < N ? AHEAD : N));
+}
+template <int N, int AHEAD, int READS, class T, class LoadF, class MmaF>
+__device__ __forceinline__ void mfma_stream_run(T (&ring)[AHEAD], LoadF load, MmaF mma) {
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    const auto cur = ring[i % AHEAD];
+    const T cur = ring[i % AHEAD];
     if (i + AHEAD < N) {
       ring[i % AHEAD] = load(i + AHEAD);
       FA_SCHED_DSRD(READS);
@@ -173,6 +225,12 @@ __device__ __forceinline__ void mfma_stream(LoadF load, MmaF mma) {
     mma(i, cur);
     FA_SCHED_MFMA(1);
   }
+}
+template <int N, int AHEAD, int READS, class LoadF, class MmaF>
+__device__ __forceinline__ void mfma_stream(LoadF load, MmaF mma) {
+  decltype(load(0)) ring[AHEAD];
+  mfma_stream_begin<N, AHEAD, READS>(ring, load);
+  mfma_stream_run<N, AHEAD, READS>(ring, load, mma);
 }
 
 }  // namespace fa
