@@ -69,6 +69,9 @@ def main() -> int:
     ap.add_argument("--workload", default="d128_n8k_causal")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true", help="profiling aid: time the forward alone")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="profiling aid: instead of the benchmark, run 5 device-to-device copies of BYTES bytes; "
+                         "under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE they give the counters' scale factors")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -80,6 +83,15 @@ def main() -> int:
 
     binding.load()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.full((args.copy_calibration,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": args.copy_calibration, "copies": 5}))
+        return 0
     prob = inputs.make_config(args.workload)
     if prob.varlen:
         print("bench.py: pick a dense workload", file=sys.stderr)

@@ -128,25 +128,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int T = (nrt - i_first) * p.G;       // tiles this workgroup visits, over the group's query heads
   const long stat_base = s * p.lse_seq_stride + (p.cu_seqlens ? si.tok0 : 0);
 
-#ifdef FA_TRACE
-  // tuning builds only: wavefronts 0 and 4 of workgroup 0 log the shader clock at phase
-  // boundaries into spare LDS; the log is copied into the (unused) dQ buffer at the end
-  __shared__ int trace_lds[2][1536];
-  int tn = 0;
-  const long long tr0 = clock64();
-  const bool tron = blockIdx.x == 0 && kg == 0 && lane == 0;
-#define FA_STAMP() do { if (tron && tn < 1536) trace_lds[grp][tn++] = (int)(clock64() - tr0); } while (0)
-#else
-#define FA_STAMP() do {} while (0)
-#endif
-#if FA_TRACE == 2
-#define FA_TP() do {} while (0)
-#define FA_TP2() FA_STAMP()
-#else
-#define FA_TP() FA_STAMP()
-#define FA_TP2() do {} while (0)
-#endif
-
   // Position of a tile in the visiting order: query head, row tile, ring slot, and where the
   // tile starts in Q / dO (elements) and in L / D. Advancing is a few scalar additions.
   struct Cursor {
@@ -342,7 +323,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   int pending = -1;      // ring slot whose statistics wait in lraw / draw
   auto end_matrix_phase = [&]() {
     __builtin_amdgcn_s_setprio(0);
-    FA_TP();
     // The copies requested in the last vector phase: complete, then visible. The wait and the
     // touches are unconditional so that the compiler sees no path on which the statistics
     // loads are still in flight when their registers are written again: it would otherwise
@@ -354,23 +334,19 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       commit_stats(pending);
       pending = -1;
     }
-    FA_TP();
     lds_barrier();
   };
   auto vector_phase = [&](int tau, bool do_v) {  // phase tau + 1, if it exists
     if (tau + 1 > T + 1) return;
-    FA_TP();
     if (tau + 3 < T) {  // the slot of tile tau - 2, free since the last barrier
       issue_loads(ld);
       pending = ld.slot;
       advance(ld, 2);
     }
-    FA_TP();
     if (do_v) {
       phase_v(cur);
       mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
     }
-    FA_TP();
     lds_barrier();
   };
 
@@ -378,7 +354,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   if (grp == 1) lds_barrier();
   // the group's first matrix phase: M only
   const bool have_first = tau < T;
-  FA_TP();
   if (have_first) {
     __builtin_amdgcn_s_setprio(2);
     mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
@@ -389,7 +364,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   advance(cur, 2);
   // steady state: M' of the previous tile, then M of the current one
   for (tau += 2; tau < T; tau += 2) {
-    FA_TP();
     __builtin_amdgcn_s_setprio(2);
     OperandPair ring[AH];
 #pragma unroll
@@ -415,7 +389,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // the last tile's M', then whatever phases remain
   bool have_prev = have_first;
   for (; tau <= T + 1; tau += 2) {
-    FA_TP();
     if (have_prev) {
       __builtin_amdgcn_s_setprio(2);
       mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
@@ -425,12 +398,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     vector_phase(tau, false);
   }
 
-#ifdef FA_TRACE
-  if (tron) {
-    int* trace = (int*)a.dQ + grp * 2048;
-    for (int i = 0; i < tn; ++i) trace[i] = trace_lds[grp][i];
-  }
-#endif
   // ---- combine the two groups' partial sums and write dK_j, dV_j (line 18); dK carries the scaling
   float* red = (float*)(smem + QDO_OFF);  // 4 * DT * 16 * 64 floats, free after the loop
   const float sc = p.scale;

@@ -7,7 +7,6 @@
 namespace fa {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -111,36 +110,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* ptr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)ptr);
 }
 
-// Build a 32 x 16 (rows x contraction) MFMA operand whose rows are COLUMNS
-// col0 .. col0+31 of a row-major LDS tile and whose 16 contraction slots are
-// tile rows row0 + {4*hh + 0..3, 8 + 4*hh + 0..3} for lane-half hh: exactly the
-// row set that registers 8s .. 8s+7 of a 32 x 32 accumulator cover, so an
-// accumulator tile (cast to bf16) can be contracted against it without moving
-// data between lanes. `stride` is the LDS row pitch in elements.
-__device__ __forceinline__ bf16x8 lds_frag_transposed(const __bf16* tile, int stride, int row0, int col0, int lane) {
-  const int p = lane & 15, g16 = (lane >> 4) & 1, hh = lane >> 5;
-  const __bf16* a = tile + (row0 + 4 * hh + (p >> 2)) * stride + col0 + 16 * g16 + 4 * (p & 3);
-  s16x4 lo = lds_read_tr(a);
-  s16x4 hi = lds_read_tr(a + 8 * stride);
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// Plain operand: rows are tile rows row0 + (lane % 32), contraction slots are 8
-// consecutive columns starting at col0 + 8 * (lane / 32).
-__device__ __forceinline__ bf16x8 lds_frag(const __bf16* tile, int stride, int row0, int col0, int lane) {
-  return *(const bf16x8*)(tile + (row0 + (lane & 31)) * stride + col0 + 8 * (lane >> 5));
-}
-
-// Exchange a value between lane l and lane l ^ 32 and return the partner's.
-__device__ __forceinline__ float partner32(float x) {
-  int xi = __builtin_bit_cast(int, x);
-  auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
-  int lo = sw[0], hi = sw[1];
-  // lanes < 32 see (own, partner); lanes >= 32 see (partner, own)
-  return __builtin_bit_cast(float, (threadIdx.x & 32) ? lo : hi);
-}
-
+// Maximum / sum of a value with the one held by lane l ^ 32 (v_permlane32_swap).
 __device__ __forceinline__ float max_with_partner32(float x) {
   int xi = __builtin_bit_cast(int, x);
   auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);

@@ -31,27 +31,6 @@ __device__ __forceinline__ int swz(int row) {
 template <int ROWB>
 __device__ __forceinline__ int swz_off(int row, int chunk) { return row * ROWB + 16 * (chunk ^ swz<ROWB>(row)); }
 
-// MFMA operand whose rows are tile rows row0 + (lane % 32) and whose contraction
-// slots are the 8 elements starting at column col0 + 8 * (lane / 32).
-template <int ROWB>
-__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int row0, int col0, int lane) {
-  return *(const bf16x8*)(tile + swz_off<ROWB>(row0 + (lane & 31), (col0 >> 3) + (lane >> 5)));
-}
-// MFMA operand whose rows are tile COLUMNS col0 + (lane % 32) and whose contraction
-// slots are tile rows row0 + {4*hh + 0..3, 8 + 4*hh + 0..3} (hh = lane / 32): the row
-// set registers 8s..8s+7 of a 32x32 accumulator cover.
-template <int ROWB>
-__device__ __forceinline__ bf16x8 frag_cols(const char* tile, int row0, int col0, int lane) {
-  const int p = lane & 15, g16 = (lane >> 4) & 1, hh = lane >> 5;
-  const int row = row0 + 4 * hh + (p >> 2);
-  const int col = col0 + 16 * g16 + 4 * (p & 3);
-  const int within = (col & 7) * 2;
-  s16x4 lo = lds_read_tr((const __bf16*)(tile + swz_off<ROWB>(row, col >> 3) + within));
-  s16x4 hi = lds_read_tr((const __bf16*)(tile + swz_off<ROWB>(row + 8, col >> 3) + within));
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
 // 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane i's
 // data lands at lds + 16 * i, `lds` being wave-uniform. Written as inline assembly on
 // purpose: the compiler would otherwise make every later LDS read wait for ALL outstanding
@@ -140,45 +119,6 @@ struct TileLoader {
   }
 };
 
-// The same tile copy staged through registers: load() fetches this lane's 16-byte chunks
-// with ordinary global loads (which the compiler tracks, so it places the waits itself) and
-// store() writes them to the swizzled LDS tile later, e.g. one phase after the request.
-template <int D, int NROWS, int NW>
-struct TileStager {
-  static constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI, PER = NI / NW;
-  static_assert(NI % NW == 0, "tile must divide over the wavefronts");
-  unsigned voff[PER];  // byte offset of this lane's chunk from the tile's first row
-  __device__ __forceinline__ void init(long gstride, int wave, int lane) {
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int r = (wave + NW * u) * RPI + lane / CPR;
-      const int c = (lane % CPR) ^ swz<ROWB>(r);
-      voff[u] = (unsigned)(r * gstride + 8 * c) * 2u;
-    }
-  }
-  __device__ __forceinline__ void load(u32x4 (&regs)[PER], const __bf16* gbase, long gstride, int row_first,
-                                       int row_last, int wave, int lane) const {
-    if (row_first + NROWS - 1 <= row_last) {
-      const char* base = (const char*)(gbase + (long)row_first * gstride);  // wave-uniform
-#pragma unroll
-      for (int u = 0; u < PER; ++u) regs[u] = *(const u32x4*)(base + voff[u]);
-    } else {
-#pragma unroll
-      for (int u = 0; u < PER; ++u) {
-        const int r = (wave + NW * u) * RPI + lane / CPR;
-        const int c = (lane % CPR) ^ swz<ROWB>(r);
-        int grow = row_first + r;
-        grow = grow < row_last ? grow : row_last;
-        regs[u] = *(const u32x4*)(gbase + (long)grow * gstride + 8 * c);
-      }
-    }
-  }
-  __device__ __forceinline__ void store(char* tile, const u32x4 (&regs)[PER], int wave, int lane) const {
-#pragma unroll
-    for (int u = 0; u < PER; ++u) *(u32x4*)(tile + (wave + NW * u) * RPI * ROWB + 16 * lane) = regs[u];
-  }
-};
-
 // Tell the compiler that a value loaded from global memory is needed NOW. The kernels
 // order their direct-to-LDS copies with hand-written s_waitcnt (the compiler does not see
 // those copies), so the compiler never learns that ordinary loads issued before the main
@@ -195,7 +135,6 @@ __device__ __forceinline__ void touch(const T& x) {
 // the MFMA that uses it, which exposes the LDS latency once per MFMA.
 #define FA_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
 #define FA_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
-#define FA_SCHED_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
 
 struct OperandPair {
   bf16x8 a, b;
