@@ -28,6 +28,14 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
+# HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes recorded
+# under profiles/pmc_<workload>_kernels.md, already scaled by the copy-kernel factors given there.
+# A counter pass cannot run inside this script; workloads without a recorded pass report null.
+MEASURED_TRAFFIC = {
+    "d128_n8k_causal": {"fwd_kernel": 611378786, "bwd_dkdv_kernel": 876994220, "bwd_dq_kernel": 741008190},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269965491, "bwd_dkdv_kernel": 541287234, "bwd_dq_kernel": 337960649},
+}
+
 
 def cpu_baseline(prob, budget_s: float = 12.0):
     """Time the float64 oracle (forward + backward) on as many (sequence, head)
@@ -145,10 +153,11 @@ def main() -> int:
     total_fl = fwd_fl if args.fwd_only else fwd_fl + bwd_fl
     value = total_fl / (ms_per_step * 1e-3) / 1e12
 
-    def roof(flops, ms):
+    def roof(flops, ms, kernel):
         ach = flops / (ms * 1e-3) / 1e12
         return {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_kernel_ms": ms}
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(prob.name, {}).get(kernel),
+                "avg_kernel_ms": ms, "kernel": kernel}
 
     out = {
         "metric": "attention fwd+bwd TFLOPs/s (bf16)" if not args.fwd_only else "attention fwd TFLOPs/s (bf16)",
@@ -166,15 +175,15 @@ def main() -> int:
         "config": {"workload": prob.name, "B": B, "N": N, "Hq": Hq, "Hkv": prob.Hkv, "d": d, "causal": ca,
                    "scale": sc, "fwd_flops": fwd_fl, "bwd_flops": bwd_fl},
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
-        "roofline_fwd": dict(roof(fwd_fl, fwd_ms), kernel="fwd_kernel"),
+        "roofline_fwd": roof(fwd_fl, fwd_ms, "fwd_kernel"),
     }
     if not args.fwd_only:
         # metric FLOPs count 5 products (2.5 x forward); the dK/dV kernel performs 4 of them
         # (S, dP, dV, dK) and the dQ kernel 3 (S, dP recomputed, dQ): 2 x and 1.5 x forward
         dkdv_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
         dq_ms = sum(e[3].elapsed_time(e[4]) for e in evs) / args.steps
-        out["roofline"] = dict(roof(2.0 * fwd_fl, dkdv_ms), kernel="bwd_dkdv_kernel")
-        out["roofline_dq"] = dict(roof(1.5 * fwd_fl, dq_ms), kernel="bwd_dq_kernel")
+        out["roofline"] = roof(2.0 * fwd_fl, dkdv_ms, "bwd_dkdv_kernel")
+        out["roofline_dq"] = roof(1.5 * fwd_fl, dq_ms, "bwd_dq_kernel")
     else:
         out["roofline"] = out["roofline_fwd"]
     if not args.no_cpu_baseline:
