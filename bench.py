@@ -12,6 +12,8 @@ Prints ONE JSON line. Besides the contract fields it carries
                  FLOPs of the four products it performs divided by its duration, which
                  is measured with HIP events inside the timed loop;
   roofline_fwd, roofline_dq - the same for the forward and the dQ kernels;
+  mfma_loop    - TFLOP/s and shader clock of a register-resident loop of the same MFMA on
+                 constant and on pseudo-random operands: what the pipe sustains on this box;
   cpu_baseline - the float64 oracle timed on the host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -186,6 +188,11 @@ def main() -> int:
         out["roofline_dq"] = roof(1.5 * fwd_fl, dq_ms, "bwd_dq_kernel")
     else:
         out["roofline"] = out["roofline_fwd"]
+    # what the matrix pipe sustains on this machine with every operand in registers (outside the timed region)
+    out["mfma_loop"] = {}
+    for key, rnd in (("constant_operands", False), ("random_operands", True)):
+        tf, ghz = binding.fa_mfma_probe(2000, rnd)
+        out["mfma_loop"][key] = {"tflops": tf, "shader_clock_ghz": ghz}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(prob)
     print(json.dumps(out))

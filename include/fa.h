@@ -127,6 +127,22 @@ int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, co
                   const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
                   int Hq, int Hkv, int d, float scale, int causal, void* stream);
 
+/*
+ * Measurement aid, not part of either algorithm: a register-resident loop of the bf16 MFMA
+ * the kernels are built on (v_mfma_f32_32x32x16_bf16), the "matmul throughput" the paper
+ * sets the non-matmul work against (section 2.1, section 3.1), measured on this device
+ * instead of read off a datasheet. 256 workgroups of 8 wavefronts each issue iters * 32
+ * MFMAs (iters * 32 * 32768 FLOPs per wavefront); the caller times the launch.
+ * `random_operands` = 0 uses constant operands, 1 pseudo-random bf16 bit patterns: under
+ * the chip's power limit the sustained clock depends on it.
+ * `scratch` is caller-owned DEVICE memory of at least fa_mfma_probe_scratch_bytes() bytes,
+ * 16-byte aligned; on completion its first 16 bytes hold two int64: shader-clock cycles and
+ * ticks of the constant 100 MHz counter spent in the loop by one wavefront (their ratio is
+ * the shader clock). Errors: FA_ERR_NULL, FA_ERR_ALIGN, FA_ERR_SHAPE (iters < 1), FA_ERR_LAUNCH.
+ */
+size_t fa_mfma_probe_scratch_bytes(void);
+int fa_mfma_probe(int iters, int random_operands, void* scratch, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

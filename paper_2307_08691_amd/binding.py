@@ -40,6 +40,8 @@ SIGNATURES = {
     "fa_varlen_bwd_workspace_bytes": (_c_size_t, [_c_int] * 4),
     "fa_varlen_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
                       [_c_float, _c_int, _c_void_p]),
+    "fa_mfma_probe_scratch_bytes": (_c_size_t, []),
+    "fa_mfma_probe": (_c_int, [_c_int, _c_int, _c_void_p, _c_void_p]),
 }
 
 _lib = None
@@ -124,6 +126,14 @@ def fa_bwd_workspace_bytes(B, Hq, Hkv, N, d) -> int:
 
 def fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d) -> int:
     return load().fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d)
+
+
+def fa_mfma_probe_scratch_bytes() -> int:
+    return load().fa_mfma_probe_scratch_bytes()
+
+
+def fa_mfma_probe_raw(iters, random_operands, scratch, stream=0) -> int:
+    return load().fa_mfma_probe(iters, int(random_operands), scratch, stream)
 
 
 # ---------------------------------------------------------------------------
@@ -226,3 +236,19 @@ def fa_varlen_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float
                              _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(cu_seqlens), nseq, T,
                              max_seqlen, Hq, Hkv, d, scale, causal, _stream()))
     return dQ, dK, dV
+
+
+def fa_mfma_probe(iters: int, random_operands: bool):
+    """Time the register-resident MFMA loop: returns (TFLOP/s, shader clock in GHz)."""
+    import torch
+    scratch = torch.zeros(fa_mfma_probe_scratch_bytes(), dtype=torch.uint8, device="cuda")
+    _check(fa_mfma_probe_raw(max(1, iters // 10), random_operands, _ptr(scratch), _stream()))  # warm-up
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _check(fa_mfma_probe_raw(iters, random_operands, _ptr(scratch), _stream()))
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    cycles, ticks = scratch[:16].view(torch.int64).tolist()
+    flops = 256.0 * 8 * iters * 32 * 32768.0
+    return flops / (ms * 1e-3) / 1e12, cycles / (ticks * 10.0)

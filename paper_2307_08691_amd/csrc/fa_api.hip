@@ -180,4 +180,19 @@ int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, co
                  scale, causal, 7, stream);
 }
 
+size_t fa_mfma_probe_scratch_bytes(void) { return 16 + (size_t)256 * 512 * sizeof(float); }
+
+int fa_mfma_probe(int iters, int random_operands, void* scratch, void* stream) {
+  if (!scratch) return FA_ERR_NULL;
+  if ((uintptr_t)scratch % 16 != 0) return FA_ERR_ALIGN;
+  if (iters < 1) return FA_ERR_SHAPE;
+  hipError_t e = fa::launch_mfma_probe((float*)((char*)scratch + 16), (long long*)scratch, 256, iters,
+                                       random_operands, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
 }  // extern "C"

@@ -116,6 +116,13 @@ def test_varlen_rejects_bad_arguments():
     assert vb(mx=0) == binding.FA_ERR_SHAPE
 
 
+def test_mfma_probe_rejects_bad_arguments():
+    assert binding.fa_mfma_probe_scratch_bytes() == 16 + 256 * 512 * 4
+    assert binding.fa_mfma_probe_raw(10, 0, 0) == binding.FA_ERR_NULL
+    assert binding.fa_mfma_probe_raw(10, 0, P + 8) == binding.FA_ERR_ALIGN
+    assert binding.fa_mfma_probe_raw(0, 1, P) == binding.FA_ERR_SHAPE
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))

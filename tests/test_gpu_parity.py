@@ -9,7 +9,7 @@ implementation) by more than one bf16 ulp at the tensor's largest magnitude.
 import numpy as np
 import pytest
 
-from paper_2307_08691_amd import inputs
+from paper_2307_08691_amd import binding, inputs
 from oracle import attention_oracle as orc
 
 pytestmark = pytest.mark.gpu
@@ -173,3 +173,13 @@ def test_closed_forms_on_the_gpu():
     got = pu.run_hip(prob2, backward=False)
     vv = orc.widen_bf16(prob2.V)
     assert pu.maxdiff(pu.to_f64(got["O"]), vv) <= pu.bf16_ulp(float(np.abs(vv).max()))
+
+
+@pytest.mark.gpu
+def test_mfma_probe_runs_and_reports_a_plausible_rate():
+    """The register-resident MFMA loop: bounded by the datasheet rate at the clock it reports."""
+    for rnd in (False, True):
+        tf, ghz = binding.fa_mfma_probe(500, rnd)
+        assert 0.5 < ghz < 2.6
+        peak_at_clock = 256 * 4 * 1024 * ghz / 1e3  # TFLOP/s: 1024 FLOPs per SIMD and cycle
+        assert 0.3 * peak_at_clock < tf < 1.05 * peak_at_clock
