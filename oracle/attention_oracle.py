@@ -31,9 +31,18 @@ Readings taken where the text is silent or inconsistent:
     reads key/value head h // (Hq / Hkv); dK, dV are summed over the query
     heads of a group;
   * packed ragged batches are not in the paper: each sequence, delimited by
-    cumulative offsets, is an independent attention problem.
+    cumulative offsets, is an independent attention problem;
+  * two lengths (Nq queries against Nk keys; cross-attention, or the newest Nq
+    tokens against a key/value cache, the inference setting the MQA/GQA
+    paragraph of section 3.1.2 has in mind): section 2.2 defines S = QK^T for
+    any two row counts; the causal mask of section 3.1.1 is stated for square S
+    only. Reading: the queries are the LAST Nq positions of the Nk keys, so
+    query r sits at position r + Nk - Nq and S[r, c] = -inf for
+    c > r + Nk - Nq. Nq = Nk gives the printed mask. Causal with Nq > Nk would
+    leave rows without any key and is rejected.
 
-Layouts: dense Q,O,dO,dQ [B, N, Hq, d]; K,V,dK,dV [B, N, Hkv, d]; L [B, Hq, N].
+Layouts: dense Q,O,dO,dQ [B, Nq, Hq, d]; K,V,dK,dV [B, Nk, Hkv, d]; L [B, Hq, Nq]
+(Nq = Nk = N for self-attention).
 Packed: Q.. [T, Hq, d]; K.. [T, Hkv, d]; L [Hq, T].
 All arithmetic is float64. Every function here is pinned by tests/test_oracle_pins.py.
 """
@@ -47,13 +56,16 @@ def widen_bf16(bits):
 
 
 def scores(q, k, scale, causal):
-    """S for one head: q [N, d], k [N, d] -> [N, N] (section 2.2; causal
-    entries with column index above the row index are -inf)."""
+    """S for one head: q [Nq, d], k [Nk, d] -> [Nq, Nk] (section 2.2). Causal:
+    query r is at position r + Nk - Nq; entries with a column index above
+    that position are -inf (section 3.1.1 for Nq = Nk)."""
     s = scale * (q @ k.T)
     if causal:
-        n = s.shape[0]
-        r = np.arange(n)[:, None]
-        c = np.arange(s.shape[1])[None, :]
+        nq, nk = s.shape
+        if nq > nk:
+            raise ValueError("causal attention needs at least as many keys as queries")
+        r = np.arange(nq)[:, None] + (nk - nq)
+        c = np.arange(nk)[None, :]
         s = np.where(c > r, -np.inf, s)
     return s
 
@@ -93,8 +105,8 @@ def _group(Hq, Hkv):
 
 
 def attention_forward(Q, K, V, scale, causal):
-    """Dense batch forward. Q [B,N,Hq,d], K,V [B,N,Hkv,d] float64.
-    Returns O [B,N,Hq,d], L [B,Hq,N]."""
+    """Dense batch forward. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] float64.
+    Returns O [B,Nq,Hq,d], L [B,Hq,Nq]."""
     B, N, Hq, d = Q.shape
     G = _group(Hq, K.shape[2])
     O = np.empty((B, N, Hq, d), dtype=np.float64)
@@ -109,13 +121,13 @@ def attention_forward(Q, K, V, scale, causal):
 
 
 def attention_backward(Q, K, V, dO, scale, causal):
-    """Dense batch backward. Returns dQ [B,N,Hq,d], dK, dV [B,N,Hkv,d]."""
+    """Dense batch backward. Returns dQ [B,Nq,Hq,d], dK, dV [B,Nk,Hkv,d]."""
     B, N, Hq, d = Q.shape
     Hkv = K.shape[2]
     G = _group(Hq, Hkv)
     dQ = np.zeros((B, N, Hq, d), dtype=np.float64)
-    dK = np.zeros((B, N, Hkv, d), dtype=np.float64)
-    dV = np.zeros((B, N, Hkv, d), dtype=np.float64)
+    dK = np.zeros(K.shape, dtype=np.float64)
+    dV = np.zeros(V.shape, dtype=np.float64)
     for b in range(B):
         for h in range(Hq):
             g = h // G
@@ -163,12 +175,15 @@ def varlen_backward(Q, K, V, dO, cu_seqlens, scale, causal):
 # test can check a large GPU result without materialising every N x N matrix.
 # ---------------------------------------------------------------------------
 
-def rows_forward(q_rows, row_idx, k, v, scale, causal):
+def rows_forward(q_rows, row_idx, k, v, scale, causal, nq=None):
     """Forward for selected query rows of one head: q_rows [R,d] are the rows
-    `row_idx` of Q; k, v [N,d]. Returns O rows [R,d] and L [R]."""
+    `row_idx` of Q (which has `nq` rows; default: as many as there are keys);
+    k, v [Nk,d]. Returns O rows [R,d] and L [R]."""
     s = scale * (q_rows @ k.T)
     if causal:
-        c = np.arange(k.shape[0])[None, :]
-        s = np.where(c > np.asarray(row_idx)[:, None], -np.inf, s)
+        nk = k.shape[0]
+        c = np.arange(nk)[None, :]
+        pos = np.asarray(row_idx)[:, None] + (nk - (nk if nq is None else nq))
+        s = np.where(c > pos, -np.inf, s)
     p, lse = softmax_rows(s)
     return p @ v, lse

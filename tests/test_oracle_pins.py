@@ -24,11 +24,12 @@ def rnd(seed, *shape):
 # ----------------------------------------------------------------------------
 
 def brute_forward(q, k, v, scale, causal):
-    n, d = len(q), len(q[0])
+    """q has n rows, k and v have nk; under the mask query r stands at position r + nk - n."""
+    n, nk, d = len(q), len(k), len(q[0])
     O = [[0.0] * d for _ in range(n)]
     L = [0.0] * n
     for r in range(n):
-        cols = range(r + 1) if causal else range(n)
+        cols = range(r + nk - n + 1) if causal else range(nk)
         w = {c: math.exp(scale * sum(q[r][t] * k[c][t] for t in range(d))) for c in cols}
         z = sum(w.values())
         L[r] = math.log(z)
@@ -383,3 +384,107 @@ def test_widen_bf16_is_exact():
     got = orc.widen_bf16(bits)
     exp = [1.0, -1.0, 2.0, 0.0, float(np.float32(0.10009765625)), 3.3895313892515355e38]
     np.testing.assert_array_equal(got, np.asarray(exp))
+
+
+# ----------------------------------------------------------------------------
+# two lengths: Nq queries against Nk keys (the queries are the newest Nq positions)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nq,nk,d", [(1, 7, 3), (3, 8, 2), (5, 6, 4), (4, 4, 2)])
+def test_two_lengths_match_scalar_brute_force(nq, nk, d, causal):
+    q, k, v = rnd(61, nq, d), rnd(62, nk, d), rnd(63, nk, d)
+    o, lse, p = orc.head_forward(q, k, v, 0.41, causal)
+    bo, bl = brute_forward(q.tolist(), k.tolist(), v.tolist(), 0.41, causal)
+    assert p.shape == (nq, nk)
+    np.testing.assert_allclose(o, np.asarray(bo), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, np.asarray(bl), rtol=1e-12, atol=1e-13)
+
+
+def test_more_queries_than_keys_without_mask():
+    q, k, v = rnd(64, 9, 3), rnd(65, 4, 3), rnd(66, 4, 3)
+    o, lse, _ = orc.head_forward(q, k, v, 0.5, False)
+    bo, bl = brute_forward(q.tolist(), k.tolist(), v.tolist(), 0.5, False)
+    np.testing.assert_allclose(o, np.asarray(bo), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, np.asarray(bl), rtol=1e-12, atol=1e-13)
+
+
+def test_causal_with_more_queries_than_keys_is_rejected():
+    with pytest.raises(ValueError):
+        orc.head_forward(rnd(1, 5, 2), rnd(2, 4, 2), rnd(3, 4, 2), 1.0, True)
+
+
+@pytest.mark.parametrize("nq,nk", [(1, 6), (3, 8), (7, 8)])
+def test_causal_two_lengths_are_the_last_rows_of_self_attention(nq, nk):
+    """The newest nq tokens attending to all nk: the same numbers as rows nk-nq.. of the
+    square problem, whatever the older queries are. Needs no formula for the alignment."""
+    d = 4
+    q_full, k, v, do_full = rnd(70, nk, d), rnd(71, nk, d), rnd(72, nk, d), rnd(73, nk, d)
+    do_full[: nk - nq] = 0.0  # the older rows carry no gradient
+    o_sq, l_sq, _ = orc.head_forward(q_full, k, v, 0.3, True)
+    dq_sq, dk_sq, dv_sq = orc.head_backward(q_full, k, v, do_full, 0.3, True)
+    q, do = q_full[nk - nq:], do_full[nk - nq:]
+    o, lse, _ = orc.head_forward(q, k, v, 0.3, True)
+    dq, dk, dv = orc.head_backward(q, k, v, do, 0.3, True)
+    np.testing.assert_allclose(o, o_sq[nk - nq:], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lse, l_sq[nk - nq:], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dq, dq_sq[nk - nq:], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dk, dk_sq, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dv, dv_sq, rtol=1e-12, atol=1e-14)
+    # a top-left aligned mask (query r sees keys 0..r) is a different function
+    s_wrong = 0.3 * (q @ k.T)
+    s_wrong = np.where(np.arange(nk)[None, :] > np.arange(nq)[:, None], -np.inf, s_wrong)
+    p_wrong, _ = orc.softmax_rows(s_wrong)
+    assert np.max(np.abs(p_wrong @ v - o_sq[nk - nq:])) > 1e-3
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_two_lengths_equal_keys_give_the_mean_of_the_visible_values(causal):
+    nq, nk, d = 3, 7, 2
+    q, v = rnd(74, nq, d), rnd(75, nk, d)
+    k = np.tile(rnd(76, 1, d), (nk, 1))  # every key alike: uniform probabilities
+    o, lse, _ = orc.head_forward(q, k, v, 0.7, causal)
+    for r in range(nq):
+        vis = r + nk - nq + 1 if causal else nk
+        np.testing.assert_allclose(o[r], v[:vis].mean(axis=0), rtol=1e-12)
+        np.testing.assert_allclose(lse[r], 0.7 * float(q[r] @ k[0]) + math.log(vis), rtol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nq,nk", [(2, 5), (4, 6)])
+def test_two_lengths_backward_matches_finite_differences(nq, nk, causal):
+    d, scale = 3, 0.45
+    q, k, v, do = rnd(80, nq, d), rnd(81, nk, d), rnd(82, nk, d), rnd(83, nq, d)
+    dq, dk, dv = orc.head_backward(q, k, v, do, scale, causal)
+    assert dq.shape == q.shape and dk.shape == k.shape and dv.shape == v.shape
+    for got, which in ((dq, "q"), (dk, "k"), (dv, "v")):
+        ref = fd_grad(q, k, v, do, scale, causal, which)
+        err = np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref)))
+        assert err < 1e-6, (which, err)
+
+
+def test_two_lengths_batch_wrapper_with_grouped_heads():
+    B, nq, nk, Hq, Hkv, d = 2, 3, 6, 4, 2, 2
+    Q, K, V, dO = rnd(90, B, nq, Hq, d), rnd(91, B, nk, Hkv, d), rnd(92, B, nk, Hkv, d), rnd(93, B, nq, Hq, d)
+    O, L = orc.attention_forward(Q, K, V, 0.5, True)
+    dQ, dK, dV = orc.attention_backward(Q, K, V, dO, 0.5, True)
+    assert O.shape == Q.shape and L.shape == (B, Hq, nq) and dK.shape == K.shape and dV.shape == V.shape
+    for b in range(B):
+        dk_sum = np.zeros((nk, Hkv, d))
+        for h in range(Hq):
+            g = h // 2
+            bo, bl = brute_forward(Q[b, :, h].tolist(), K[b, :, g].tolist(), V[b, :, g].tolist(), 0.5, True)
+            np.testing.assert_allclose(O[b, :, h], np.asarray(bo), rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(L[b, h], np.asarray(bl), rtol=1e-12, atol=1e-13)
+            dk_sum[:, g] += orc.head_backward(Q[b, :, h], K[b, :, g], V[b, :, g], dO[b, :, h], 0.5, True)[1]
+        np.testing.assert_allclose(dK[b], dk_sum, rtol=1e-12, atol=1e-13)
+
+
+def test_rows_forward_with_two_lengths():
+    nq, nk, d = 5, 9, 3
+    q, k, v = rnd(94, nq, d), rnd(95, nk, d), rnd(96, nk, d)
+    o, lse, _ = orc.head_forward(q, k, v, 0.6, True)
+    rows = [0, 2, 4]
+    o_r, l_r = orc.rows_forward(q[rows], rows, k, v, 0.6, True, nq=nq)
+    np.testing.assert_allclose(o_r, o[rows], rtol=1e-13)
+    np.testing.assert_allclose(l_r, lse[rows], rtol=1e-13)
