@@ -128,6 +128,27 @@ int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, co
                   int Hq, int Hkv, int d, float scale, int causal, void* stream);
 
 /*
+ * Two lengths: Nq query rows against Nk key/value rows per sequence (cross-attention, or the
+ * newest Nq tokens against a key/value cache of Nk, the inference setting the multi-/grouped-
+ * query paragraph of section 3.1.2 refers to). Section 2.2 defines S = QK^T for any two row
+ * counts and Algorithms 1 and 2 never use that S is square; the causal mask of section 3.1.1
+ * is only stated for Nq = Nk. Here query r stands at position r + Nk - Nq of the keys, i.e.
+ * sees keys c <= r + Nk - Nq (Nq = Nk is the printed mask); causal with Nq > Nk would leave
+ * rows without keys and returns FA_ERR_SHAPE.
+ * Layout: Q, O, dO, dQ [B, Nq, Hq, d]; K, V, dK, dV [B, Nk, Hkv, d]; LSE [B, Hq, Nq];
+ * everything else (ownership, alignment, errors, workspace, what is overwritten) as for
+ * fa_fwd / fa_bwd, which are the case Nq = Nk = N. A few query rows against many keys run on
+ * one workgroup per 256 query rows and head: the key sequence is not split across workgroups.
+ */
+int fa_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                 int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
+size_t fa_cross_bwd_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int d);
+int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                 const float* LSE, void* dQ, void* dK, void* dV,
+                 void* workspace, size_t workspace_bytes,
+                 int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
+
+/*
  * Measurement aid, not part of either algorithm: a register-resident loop of the bf16 MFMA
  * the kernels are built on (v_mfma_f32_32x32x16_bf16), the "matmul throughput" the paper
  * sets the non-matmul work against (section 2.1, section 3.1), measured on this device

@@ -40,6 +40,9 @@ SIGNATURES = {
     "fa_varlen_bwd_workspace_bytes": (_c_size_t, [_c_int] * 4),
     "fa_varlen_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
                       [_c_float, _c_int, _c_void_p]),
+    "fa_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_cross_bwd_workspace_bytes": (_c_size_t, [_c_int] * 6),
+    "fa_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_mfma_probe_scratch_bytes": (_c_size_t, []),
     "fa_mfma_probe": (_c_int, [_c_int, _c_int, _c_void_p, _c_void_p]),
 }
@@ -126,6 +129,20 @@ def fa_bwd_workspace_bytes(B, Hq, Hkv, N, d) -> int:
 
 def fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d) -> int:
     return load().fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d)
+
+
+def fa_cross_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream=0) -> int:
+    return load().fa_cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), stream)
+
+
+def fa_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                     stream=0) -> int:
+    return load().fa_cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                               int(causal), stream)
+
+
+def fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d) -> int:
+    return load().fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
 
 
 def fa_mfma_probe_scratch_bytes() -> int:
@@ -235,6 +252,42 @@ def fa_varlen_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float
     _check(fa_varlen_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                              _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(cu_seqlens), nseq, T,
                              max_seqlen, Hq, Hkv, d, scale, causal, _stream()))
+    return dQ, dK, dV
+
+
+def fa_cross_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None):
+    """Two lengths. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 -> O [B,Nq,Hq,d] bf16, LSE [B,Hq,Nq] fp32."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
+    _check(fa_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                            _stream()))
+    return O, LSE
+
+
+def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
+    """Two lengths, backward. Returns dQ [B,Nq,Hq,d], dK, dV [B,Nk,Hkv,d] bf16."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    _need(LSE, "LSE", torch.float32)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    need = fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    _check(fa_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                            _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
+                            scale, causal, _stream()))
     return dQ, dK, dV
 
 

@@ -20,11 +20,12 @@ int check_common(int Hq, int Hkv, int d, float scale) {
   return FA_OK;
 }
 
-fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Hq, int Hkv, long total, float scale) {
+fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int Hkv, long total, float scale) {
   fa::Problem p;
   p.cu_seqlens = cu;
   p.nseq = nseq;
   p.N = N;
+  p.Nk = Nk;
   p.Hq = Hq;
   p.Hkv = Hkv;
   p.G = Hq / Hkv;
@@ -42,9 +43,9 @@ size_t ws_bytes(long tokens, int Hq, int d) {
 }
 
 int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
-            long total, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
+            int Nk, long total, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
   fa::FwdArgs a;
-  a.p = make_problem(cu, nseq, N, Hq, Hkv, total, scale);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -59,10 +60,10 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
 }
 
 int run_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE, void* dQ,
-            void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, long total, int Hq, int Hkv, int d,
+            void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, int Nk, long total, int Hq, int Hkv, int d,
             float scale, int causal, int stages, void* stream) {
   fa::BwdArgs a;
-  a.p = make_problem(cu, nseq, N, Hq, Hkv, total, scale);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -109,7 +110,7 @@ int fa_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   if (int e = check_common(Hq, Hkv, d, scale)) return e;
   if ((long)B * N > 0x7fffffffL) return FA_ERR_SHAPE;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
-  return run_fwd(Q, K, V, O, LSE, nullptr, B, N, (long)B * N, Hq, Hkv, d, scale, causal, stream);
+  return run_fwd(Q, K, V, O, LSE, nullptr, B, N, N, (long)B * N, Hq, Hkv, d, scale, causal, stream);
 }
 
 size_t fa_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int d) {
@@ -130,7 +131,7 @@ int fa_bwd_stages(const void* Q, const void* K, const void* V, const void* O, co
     return FA_ERR_ALIGN;
   if (workspace_bytes < ws_bytes((long)B * N, Hq, d)) return FA_ERR_WORKSPACE;
   if (stages <= 0 || (stages & ~7)) return FA_ERR_SHAPE;
-  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, N, (long)B * N, Hq, Hkv, d, scale, causal,
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, N, N, (long)B * N, Hq, Hkv, d, scale, causal,
                  stages, stream);
 }
 
@@ -156,7 +157,8 @@ int fa_varlen_fwd(const void* Q, const void* K, const void* V, void* O, float* L
   if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
   if (int e = check_common(Hq, Hkv, d, scale)) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
-  return run_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, max_seqlen, total_tokens, Hq, Hkv, d, scale, causal, stream);
+  return run_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, max_seqlen, max_seqlen, total_tokens, Hq, Hkv, d, scale, causal,
+                 stream);
 }
 
 size_t fa_varlen_bwd_workspace_bytes(int total_tokens, int Hq, int Hkv, int d) {
@@ -176,8 +178,44 @@ int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, co
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return FA_ERR_ALIGN;
   if (workspace_bytes < ws_bytes(total_tokens, Hq, d)) return FA_ERR_WORKSPACE;
-  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, cu_seqlens, nseq, max_seqlen, total_tokens, Hq, Hkv, d,
-                 scale, causal, 7, stream);
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, cu_seqlens, nseq, max_seqlen, max_seqlen, total_tokens, Hq,
+                 Hkv, d, scale, causal, 7, stream);
+}
+
+static int check_cross(int B, int Nq, int Nk, int causal) {
+  if (B <= 0 || Nq <= 0 || Nk <= 0) return FA_ERR_SHAPE;
+  if (causal && Nq > Nk) return FA_ERR_SHAPE;  // some query would see no key
+  if ((long)B * Nq > 0x7fffffffL || (long)B * Nk > 0x7fffffffL) return FA_ERR_SHAPE;
+  return FA_OK;
+}
+
+int fa_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                 int Nk, int d, float scale, int causal, void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream);
+}
+
+size_t fa_cross_bwd_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int d) {
+  (void)Hkv;
+  if (B <= 0 || Hq <= 0 || Nq <= 0 || Nk <= 0 || d <= 0) return 0;
+  return ws_bytes((long)B * Nq, Hq, d);
+}
+
+int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                 int Nq, int Nk, int d, float scale, int causal, void* stream) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
+                 causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
 }
 
 size_t fa_mfma_probe_scratch_bytes(void) { return 16 + (size_t)256 * 512 * sizeof(float); }

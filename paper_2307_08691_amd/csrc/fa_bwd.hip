@@ -113,18 +113,21 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int kg = v & 3, grp = v >> 2;
   const int gtid = tid & 255;  // thread index inside the group
   const int lq = lane & 31, hh = lane >> 5;
-  const BlockCoord bc = block_coord<CAUSAL>((p.N + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
+  const BlockCoord bc = block_coord<CAUSAL>((p.Nk + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
   if (!bc.valid) return;
   const int g = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
-  const int n = si.n;
+  const int n = si.n, nk = si.nk;  // query rows, key rows
+  const int off = nk - n;          // position of query 0 among the keys (causal alignment)
   const int j0 = bc.blk * BC;
-  if (j0 >= n) return;
+  if (j0 >= nk) return;
   const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
 
   const float c2 = p.scale_log2e;
   const int nrt = (n + BR - 1) / BR;         // row tiles of the sequence
-  const int i_first = CAUSAL ? j0 / BR : 0;  // row tiles entirely above the diagonal are skipped
+  // row tiles entirely above the diagonal are skipped; past the last row tile there is nothing to do
+  int i_first = CAUSAL && j0 > off ? (j0 - off) / BR : 0;
+  if (i_first > nrt) i_first = nrt;
   const int T = (nrt - i_first) * p.G;       // tiles this workgroup visits, over the group's query heads
   const long stat_base = s * p.lse_seq_stride + (p.cu_seqlens ? si.tok0 : 0);
 
@@ -196,8 +199,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 
   // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop; tiles 0..2 are
   //      requested up front by all wavefronts
-  tile_load_async<D, BC, 8>(smem + KT_OFF, a.K + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
-  tile_load_async<D, BC, 8>(smem + VT_OFF, a.V + (si.tok0 * p.Hkv + g) * D, kstride, j0, n - 1, v, lane);
+  tile_load_async<D, BC, 8>(smem + KT_OFF, a.K + (si.tok0k * p.Hkv + g) * D, kstride, j0, nk - 1, v, lane);
+  tile_load_async<D, BC, 8>(smem + VT_OFF, a.V + (si.tok0k * p.Hkv + g) * D, kstride, j0, nk - 1, v, lane);
   {
     Cursor c = tile0;
     for (int t = 0; t < 3 && t < T; ++t) {
@@ -239,7 +242,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   for (int dt = 0; dt < DT; ++dt) dKt[dt] = dVt[dt] = (f32x16){0};
 
   const int key = j0 + 32 * kg + lq;  // this lane's key column
-  const bool key_ok = key < n;
+  const bool key_ok = key < nk;
 
   f32x16 S[QTW], dP[QTW];
   bf16x8 Pf[QTW][2], dSf[QTW][2];
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int tq = 0; tq < QTW; ++tq) {
       const int r0 = i0 + 32 * tq;  // first query row of this tile
-      const bool need_mask = (CAUSAL && j0 + 32 * kg + 31 > r0) || (j0 + BC > n);
+      const bool need_mask = (CAUSAL && j0 + 32 * kg + 31 > r0 + off) || (j0 + BC > nk);
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * tq + 8 * r4 + 4 * hh) * 4);
@@ -298,7 +301,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const bool vis = key_ok && (!CAUSAL || key <= r0 + acc_row(r, hh));
+          const bool vis = key_ok && (!CAUSAL || key <= r0 + off + acc_row(r, hh));
           if (!vis) S[tq][r] = 0.f;
         }
       }
@@ -412,7 +415,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     }
     __syncthreads();
     if (grp == 0 && key_ok) {
-      __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0 + key) * p.Hkv + g) * D + 4 * hh;
+      __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0k + key) * p.Hkv + g) * D + 4 * hh;
       const float mul = which == 0 ? sc : 1.f;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -456,13 +459,13 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
-  const int n = si.n;
+  const int n = si.n, nk = si.nk, off = nk - n;  // query rows, key rows, position of query 0
   const int i0 = rowblk * BR;
   if (i0 >= n) return;
   const int g = h / p.G;
   const long kstride = (long)p.Hkv * D;
-  const __bf16* Kb = a.K + (si.tok0 * p.Hkv + g) * D;
-  const __bf16* Vb = a.V + (si.tok0 * p.Hkv + g) * D;
+  const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;
+  const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * D;
 
   // ---- Q_i, dO_i operands and L_i, D_i of this lane's query row: registers for the whole kernel
   const int wrow0 = i0 + 32 * w;
@@ -486,11 +489,11 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dQt[dt] = (f32x16){0};
 
-  const int ncol_all = (n + BC - 1) / BC;
+  const int ncol_all = (nk + BC - 1) / BC;
   int ncol = ncol_all;
   if (CAUSAL) {
-    const int last_row = (i0 + BR < n ? i0 + BR : n) - 1;
-    const int c = last_row / BC + 1;
+    const int last_pos = (i0 + BR < n ? i0 + BR : n) - 1 + off;
+    const int c = last_pos / BC + 1;
     ncol = c < ncol_all ? c : ncol_all;
   }
 
@@ -501,7 +504,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   constexpr int TPW = TileLoader<D, BC, 4>::PER;
   auto issue_tile = [&](int j) {
     char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
-    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, n - 1, w & 3, lane);
+    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
   };
   issue_tile(0);
   issue_tile(1);
@@ -523,8 +526,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
 
   const float c2 = p.scale_log2e;
-  const int wrow_last = wrow0 + 31;
-  const int lim_row = CAUSAL ? (row < n - 1 ? row : n - 1) : n - 1;  // last visible column of this lane's row
+  const int wrow_last = wrow0 + 31 + off;  // position of the last row among the keys
+  const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;  // last visible column of this lane's row
 
   f32x16 S[2], dP[2];
   bf16x8 dSf[2][2];
@@ -565,7 +568,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   auto vector_phase = [&](int j) {
     if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
     const int col0 = j * BC;
-    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
@@ -633,7 +636,7 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 2) {
-    dim3 grid(grid_size((a.p.N + 127) / 128, a.p.Hkv * a.p.nseq));
+    dim3 grid(grid_size((a.p.Nk + 127) / 128, a.p.Hkv * a.p.nseq));
     if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true>), grid, dim3(512), 0, st, a);
     else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false>), grid, dim3(512), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;

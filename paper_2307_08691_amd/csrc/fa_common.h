@@ -20,11 +20,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 // Problem description shared by the forward and backward kernels. A "sequence"
-// is one batch entry (dense) or one entry of cu_seqlens (packed ragged).
+// is one batch entry (dense) or one entry of cu_seqlens (packed ragged). A sequence has
+// nq query rows and nk key/value rows (equal except through the two-length entry points);
+// under the causal mask query r stands at position r + nk - nq of the keys.
 struct Problem {
   const int32_t* cu_seqlens;  // device, nseq + 1 entries; nullptr for the dense layout
   int nseq;                   // number of sequences (dense: batch size)
-  int N;                      // dense: sequence length; ragged: upper bound on any length
+  int N;                      // dense: number of query rows; ragged: upper bound on any length
+  int Nk;                     // dense: number of key/value rows; ragged: same bound
   int Hq, Hkv, G;             // G = Hq / Hkv
   int total_tokens;
   long lse_seq_stride;        // dense: Hq * N, ragged: 0
@@ -34,19 +37,23 @@ struct Problem {
 };
 
 struct SeqInfo {
-  long tok0;  // first token row of the sequence in the packed [tokens, H, d] view
-  int n;      // its length
+  long tok0;   // first query row of the sequence in the packed [tokens, H, d] view
+  long tok0k;  // first key/value row
+  int n;       // query rows
+  int nk;      // key/value rows
 };
 
 __device__ __forceinline__ SeqInfo seq_info(const Problem& p, int s) {
   SeqInfo r;
   if (p.cu_seqlens) {
     int a = p.cu_seqlens[s];
-    r.tok0 = a;
-    r.n = p.cu_seqlens[s + 1] - a;
+    r.tok0 = r.tok0k = a;
+    r.n = r.nk = p.cu_seqlens[s + 1] - a;
   } else {
     r.tok0 = (long)s * p.N;
+    r.tok0k = (long)s * p.Nk;
     r.n = p.N;
+    r.nk = p.Nk;
   }
   return r;
 }

@@ -72,13 +72,14 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;
   const SeqInfo si = seq_info(p, s);
-  const int n = si.n;
+  const int n = si.n, nk = si.nk;  // query rows, key rows
+  const int off = nk - n;          // position of query 0 among the keys (causal alignment)
   const int i0 = rowblk * BR;
   if (i0 >= n) return;
   const int g = h / p.G;
   const long kstride = (long)p.Hkv * D;
-  const __bf16* Kb = a.K + (si.tok0 * p.Hkv + g) * D;
-  const __bf16* Vb = a.V + (si.tok0 * p.Hkv + g) * D;
+  const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;
+  const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * D;
 
   // ---- Q_i operands: registers for the whole kernel (Algorithm 1, line 4)
   const int wrow0 = i0 + 32 * w;  // first query row of this wavefront
@@ -99,11 +100,11 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   float l = 0.f;        // this lane's share of the row sum (the two lane halves are added at the end)
 
   // column blocks the workgroup visits: all of them, or (causal) those not entirely above the diagonal
-  const int ncol_all = (n + BC - 1) / BC;
+  const int ncol_all = (nk + BC - 1) / BC;
   int ncol = ncol_all;
   if (CAUSAL) {
-    const int last_row = (i0 + BR < n ? i0 + BR : n) - 1;
-    const int c = last_row / BC + 1;
+    const int last_pos = (i0 + BR < n ? i0 + BR : n) - 1 + off;
+    const int c = last_pos / BC + 1;
     ncol = c < ncol_all ? c : ncol_all;
   }
 
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   constexpr int TPW = TileLoader<D, BC, 4>::PER;  // copies per wavefront per tile
   auto issue_tile = [&](int j) {  // group 0: V_j, group 1: K_j
     char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
-    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, n - 1, w & 3, lane);
+    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
   };
   {  // blocks 0 and 1: both tiles, split over the two groups as above
     issue_tile(0);
@@ -138,8 +139,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
 
   const float c2 = p.scale_log2e;
-  const int wrow_last = wrow0 + 31;
-  const int lim_row = CAUSAL ? (row < n - 1 ? row : n - 1) : n - 1;  // last visible column of this lane's row
+  const int wrow_last = wrow0 + 31 + off;  // position of the last row among the keys
+  const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;  // last visible column of this lane's row
 
   f32x16 S[2];
   bf16x8 Pf[2][2];
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
     const int col0 = j * BC;
     // ---- mask: causal entries above the diagonal and columns past the end
-    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0) || (col0 + BC > n);
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
     if (need_mask) {
       asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
 #pragma unroll

@@ -22,6 +22,7 @@ __all__ = [
     "bf16_bits_to_f32",
     "AttnProblem",
     "make_dense",
+    "make_cross",
     "make_varlen",
     "CONFIGS",
     "make_config",
@@ -50,7 +51,8 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
 class AttnProblem:
     """One attention problem: bf16 bit patterns plus its shape parameters.
 
-    Dense layout: Q, dO are [B, N, Hq, d]; K, V are [B, N, Hkv, d].
+    Dense layout: Q, dO are [B, N, Hq, d]; K, V are [B, Nk, Hkv, d] (Nk = N unless the
+    problem has two lengths, `Nk` > 0).
     Packed ragged layout (cu_seqlens is not None): Q, dO are [T, Hq, d];
     K, V are [T, Hkv, d]; sequence s owns token rows cu_seqlens[s]:cu_seqlens[s+1].
     """
@@ -67,6 +69,7 @@ class AttnProblem:
     causal: bool
     B: int = 0
     N: int = 0
+    Nk: int = 0
     cu_seqlens: Optional[np.ndarray] = None
     seed: int = 0
     meta: dict = field(default_factory=dict)
@@ -85,9 +88,19 @@ class AttnProblem:
             return np.diff(self.cu_seqlens)
         return np.full(self.B, self.N, dtype=np.int64)
 
+    @property
+    def keys(self) -> int:
+        """Key/value rows per sequence of a dense problem."""
+        return self.Nk or self.N
+
     def fwd_flops(self) -> float:
         """Metric FLOPs of the forward pass: 4*N^2*d per query head and
-        sequence, halved under the causal mask (the paper's benchmark formula)."""
+        sequence, halved under the causal mask (the paper's benchmark formula).
+        Two lengths: 4*d per visible (query, key) pair, Nq*Nk of them without
+        the mask and Nq*Nk - Nq^2/2 with it (the same count for Nq = Nk)."""
+        if self.Nk and not self.varlen:
+            pairs = float(self.N) * self.Nk - (0.5 * float(self.N) ** 2 if self.causal else 0.0)
+            return 4.0 * self.B * self.Hq * self.d * pairs
         n2 = float(np.sum(self.seqlens.astype(np.float64) ** 2))
         f = 4.0 * self.Hq * self.d * n2
         return f / 2.0 if self.causal else f
@@ -117,6 +130,18 @@ def make_dense(B, N, Hq, Hkv, d, causal, seed, scale=None, qk_mult=1.0,
                        causal=bool(causal), B=B, N=N, seed=seed)
 
 
+def make_cross(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="cross") -> AttnProblem:
+    """Two lengths: Nq query rows against Nk key/value rows; Q, K, V, dO drawn in that order."""
+    rng = np.random.default_rng(seed)
+    Q = _draw(rng, (B, Nq, Hq, d))
+    K = _draw(rng, (B, Nk, Hkv, d))
+    V = _draw(rng, (B, Nk, Hkv, d))
+    dO = _draw(rng, (B, Nq, Hq, d))
+    return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
+                       scale=float(scale if scale is not None else d ** -0.5),
+                       causal=bool(causal), B=B, N=Nq, Nk=Nk, seed=seed)
+
+
 def make_varlen(seqlens, Hq, Hkv, d, causal, seed, scale=None,
                 name="varlen") -> AttnProblem:
     """Packed ragged batch: tokens of all sequences concatenated."""
@@ -143,6 +168,9 @@ CONFIGS = {
                                 seed=1004, qk_mult=3.0),
     "gqa_ragged": dict(kind="varlen", nseq=16, lo=256, hi=4096, Hq=32, Hkv=8, d=128, causal=True,
                        seed=1005),
+    # two lengths: a chunk of 512 new tokens against a cache of 8192 keys, and plain cross-attention
+    "chunk_512_on_8k": dict(kind="cross", B=8, Nq=512, Nk=8192, Hq=32, Hkv=8, d=128, causal=True, seed=1006),
+    "cross_2k_on_8k": dict(kind="cross", B=4, Nq=2048, Nk=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1007),
 }
 
 
@@ -168,5 +196,7 @@ def make_config(name: str) -> AttnProblem:
     kind = c.pop("kind")
     if kind == "dense":
         return make_dense(name=name, **c)
+    if kind == "cross":
+        return make_cross(name=name, **c)
     lens = ragged_lengths(c["seed"], c.pop("nseq"), c.pop("lo"), c.pop("hi"))
     return make_varlen(lens, name=name, **c)

@@ -68,6 +68,12 @@ def run_hip(prob: AttnProblem, backward: bool = True):
         if backward:
             dQ, dK, dV = binding.fa_varlen_bwd(Q, K, V, O, dO, LSE, cu, mx, prob.scale, prob.causal)
             out.update(dQ=dQ, dK=dK, dV=dV)
+    elif prob.Nk:
+        O, LSE = binding.fa_cross_fwd(Q, K, V, prob.scale, prob.causal)
+        out.update(O=O, LSE=LSE)
+        if backward:
+            dQ, dK, dV = binding.fa_cross_bwd(Q, K, V, O, dO, LSE, prob.scale, prob.causal)
+            out.update(dQ=dQ, dK=dK, dV=dV)
     else:
         O, LSE = binding.fa_fwd(Q, K, V, prob.scale, prob.causal)
         out.update(O=O, LSE=LSE)
@@ -102,8 +108,8 @@ def bf16_reference_head(q, k, v, do, scale, causal):
     s = ((q @ k.T).float() * scale).to(bf)
     sf = s.float()
     if causal:
-        n = q.shape[0]
-        mask = torch.ones(n, n, dtype=torch.bool, device=q.device).triu(1)
+        n, nk = q.shape[0], k.shape[0]
+        mask = torch.ones(n, nk, dtype=torch.bool, device=q.device).triu(1 + nk - n)
         sf = sf.masked_fill(mask, float("-inf"))
     p32 = torch.softmax(sf, dim=-1)
     p = p32.to(bf)

@@ -116,6 +116,26 @@ def test_varlen_rejects_bad_arguments():
     assert vb(mx=0) == binding.FA_ERR_SHAPE
 
 
+def cross(Q=P, B=1, Hq=2, Hkv=2, Nq=8, Nk=128, d=64, scale=0.125, causal=0):
+    return binding.fa_cross_fwd_raw(Q, P, P, P, P, B, Hq, Hkv, Nq, Nk, d, scale, causal, 0)
+
+
+def test_two_length_entry_points_reject_bad_arguments():
+    assert cross(Q=0) == binding.FA_ERR_NULL
+    assert cross(Nq=0) == binding.FA_ERR_SHAPE
+    assert cross(Nk=0) == binding.FA_ERR_SHAPE
+    assert cross(Nq=129, Nk=128, causal=1) == binding.FA_ERR_SHAPE  # a query row without keys
+    assert cross(d=96) == binding.FA_ERR_UNSUPPORTED
+    assert cross(Q=P + 2) == binding.FA_ERR_ALIGN
+    assert cross(Hq=3) == binding.FA_ERR_SHAPE
+    ptrs = [P] * 9
+    assert binding.fa_cross_bwd_raw(*ptrs, P, 0, 1, 2, 2, 8, 128, 64, 0.125, 0, 0) == binding.FA_ERR_WORKSPACE
+    assert binding.fa_cross_bwd_raw(*ptrs, 0, 1 << 20, 1, 2, 2, 8, 128, 64, 0.125, 0, 0) == binding.FA_ERR_NULL
+    # the workspace holds D: one float per query row and query head
+    assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == 512
+    assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == binding.fa_bwd_workspace_bytes(3, 4, 2, 10, 64)
+
+
 def test_mfma_probe_rejects_bad_arguments():
     assert binding.fa_mfma_probe_scratch_bytes() == 16 + 256 * 512 * 4
     assert binding.fa_mfma_probe_raw(10, 0, 0) == binding.FA_ERR_NULL

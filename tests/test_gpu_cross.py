@@ -1,0 +1,108 @@
+"""GPU parity for two lengths (Nq query rows against Nk key/value rows): the HIP path
+through fa_cross_fwd / fa_cross_bwd against the float64 oracle, element by element, at
+sizes that span several tiles, ragged tails on either side, a single query row, more
+queries than keys (no mask), grouped heads; plus the identity with the one-length entry
+points and sampled units of the two full-size workloads."""
+import numpy as np
+import pytest
+
+from paper_2307_08691_amd import binding, inputs
+from oracle import attention_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import parity_util as pu  # noqa: E402
+from test_gpu_parity import check  # noqa: E402
+from test_gpu_fullsize import check_units  # noqa: E402
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq,Nk", [(1, 1), (1, 300), (7, 64), (31, 129), (64, 65), (128, 515), (200, 1000),
+                                   (257, 300), (300, 301), (33, 2049)])
+def test_fewer_queries_than_keys(Nq, Nk, d, causal):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=2, Hkv=2, d=d, causal=causal, seed=3000 + Nq + Nk)
+    check(prob)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq,Nk", [(64, 7), (300, 129), (515, 64), (129, 1)])
+def test_more_queries_than_keys_without_mask(Nq, Nk, d):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=2, Hkv=2, d=d, causal=False, seed=3100 + Nq + Nk)
+    check(prob)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 4, 2), (128, 8, 2), (128, 4, 1)])
+def test_grouped_heads_with_two_lengths(d, Hq, Hkv, causal):
+    prob = inputs.make_cross(B=2, Nq=70, Nk=333, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=3200 + Hq)
+    check(prob)
+
+
+def test_single_new_token_against_a_cache():
+    """Decoding shape: one query row per sequence, grouped heads, a long key sequence."""
+    prob = inputs.make_cross(B=4, Nq=1, Nk=4097, Hq=8, Hkv=2, d=128, causal=True, seed=3300)
+    check(prob)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_equal_lengths_reproduce_the_one_length_entry_points_bitwise(causal):
+    prob = inputs.make_dense(B=2, N=300, Hq=4, Hkv=2, d=128, causal=causal, seed=3400)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    O1, L1 = binding.fa_fwd(Q, K, V, prob.scale, causal)
+    O2, L2 = binding.fa_cross_fwd(Q, K, V, prob.scale, causal)
+    g1 = binding.fa_bwd(Q, K, V, O1, dO, L1, prob.scale, causal)
+    g2 = binding.fa_cross_bwd(Q, K, V, O2, dO, L2, prob.scale, causal)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
+
+
+def test_causal_chunk_equals_the_last_rows_of_the_square_problem():
+    """The newest Nq rows of a causal self-attention problem, run through the two-length
+    entry points, give the same O and LSE rows (same keys, same alignment)."""
+    prob = inputs.make_dense(B=1, N=777, Hq=2, Hkv=2, d=64, causal=True, seed=3500)
+    Q, K, V = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V))
+    O, L = binding.fa_fwd(Q, K, V, prob.scale, True)
+    nq = 200
+    Oc, Lc = binding.fa_cross_fwd(Q[:, -nq:].contiguous(), K, V, prob.scale, True)
+    torch.cuda.synchronize()
+    assert float((O[:, -nq:].float() - Oc.float()).abs().max()) <= 2e-2
+    assert float((L[:, :, -nq:] - Lc).abs().max()) <= 1e-3
+
+
+def test_guard_values_around_outputs_survive():
+    """Outputs of different lengths: nothing is written outside dQ (Nq rows) or dK, dV (Nk rows)."""
+    prob = inputs.make_cross(B=1, Nq=37, Nk=211, Hq=2, Hkv=2, d=64, causal=True, seed=3600)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    pad = 4096
+
+    def guarded(like):
+        buf = torch.full((like.numel() + 2 * pad,), 7.0, dtype=torch.bfloat16, device="cuda")
+        return buf, buf[pad:pad + like.numel()].view(like.shape)
+
+    bO, O = guarded(Q)
+    bQ, dQ = guarded(Q)
+    bK, dK = guarded(K)
+    bV, dV = guarded(V)
+    O, L = binding.fa_cross_fwd(Q, K, V, prob.scale, True, O=O)
+    binding.fa_cross_bwd(Q, K, V, O, dO, L, prob.scale, True, dQ=dQ, dK=dK, dV=dV)
+    torch.cuda.synchronize()
+    for buf in (bO, bQ, bK, bV):
+        assert bool((buf[:pad] == 7.0).all()) and bool((buf[-pad:] == 7.0).all())
+    exp = pu.run_oracle(prob)
+    for nm, t in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        assert pu.maxdiff(pu.to_f64(t), exp[nm]) <= pu.tolerance(nm, exp[nm])
+
+
+@pytest.mark.parametrize("name", ["chunk_512_on_8k", "cross_2k_on_8k"])
+def test_full_size_two_length_workloads_sampled_units(name):
+    prob = inputs.make_config(name)
+    got = pu.run_hip(prob)
+    for nm, t in got.items():
+        assert torch.isfinite(t.float()).all(), f"{name}: {nm} not finite"
+    units = [(0, 0), (prob.B - 1, prob.Hkv - 1)]
+    worst = check_units(prob, got, units)
+    print(name, worst)
