@@ -36,6 +36,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 MEASURED_TRAFFIC = {
     "d128_n8k_causal": {"fwd_kernel": 611378786, "bwd_dkdv_kernel": 876994220, "bwd_dq_kernel": 741008190},
     "sweep_d128_n8192_full": {"fwd_kernel": 269965491, "bwd_dkdv_kernel": 541287234, "bwd_dq_kernel": 337960649},
+    "decode_b8_on_8k": {"fwd_kernel": 288777216},  # split kernel + merge, profiles/bench_decode_b8_on_8k_kernel_stats.md
 }
 
 
@@ -60,7 +61,7 @@ def cpu_baseline(prob, budget_s: float = 12.0):
         do = orc.widen_bf16(prob.dO[b, :, h])
         orc.head_backward(q, k, v, do, prob.scale, prob.causal)  # recomputes the forward inside
     dt = time.perf_counter() - t0
-    per_unit = 3.5 * (4.0 * prob.N ** 2 * prob.d) * (0.5 if prob.causal else 1.0)
+    per_unit = 3.5 * prob.fwd_flops() / (prob.B * prob.Hq)  # the metric's forward + backward FLOPs of one unit
     return {
         "value": per_unit * len(units) / dt / 1e12,
         "unit": "TFLOPs/s",
@@ -69,6 +70,66 @@ def cpu_baseline(prob, budget_s: float = 12.0):
         "sample": f"{len(units)} of {prob.B * prob.Hq} (sequence, head) units of {prob.name}, forward+backward, "
                   f"float64 numpy, {dt:.1f} s",
     }
+
+
+def bench_decode(args, prob, binding) -> int:
+    """Few query rows against a long key/value cache: one step is one fa_splitkv_fwd call (the split
+    kernel and the merge). HBM-bound: the roofline is bytes that must move over the call's duration."""
+    import numpy as np
+    import torch
+
+    def gpu(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    Q, K, V = (gpu(x) for x in (prob.Q, prob.K, prob.V))
+    B, Nq, Hq, d = Q.shape
+    splits = binding.splitkv_default_splits(B, Hq, prob.Hkv, Nq, prob.Nk)
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(binding.fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, splits), dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.fa_splitkv_fwd(Q, K, V, prob.scale, prob.causal, splits, O=O, LSE=LSE, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = e0.elapsed_time(e1) / args.steps
+    # bytes that must move: K and V once, Q read and O written once, LSE written
+    alg_bytes = 2.0 * (K.numel() + V.numel() + Q.numel() + O.numel()) + 4.0 * LSE.numel()
+    gbs = alg_bytes / (kern_ms * 1e-3) / 1e9
+    out = {
+        "metric": "decode attention forward, GB/s of compulsory traffic (bf16)", "value": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": prob.name, "B": B, "Nq": Nq, "Nk": prob.Nk, "Hq": Hq, "Hkv": prob.Hkv, "d": d,
+                   "causal": prob.causal, "num_splits": splits, "algorithmic_bytes": alg_bytes},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
+                     "traffic": MEASURED_TRAFFIC.get(prob.name, {}).get("fwd_kernel"), "avg_kernel_ms": kern_ms,
+                     "kernel": "fwd_kernel<.., split> + fwd_merge_kernel"},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import attention_oracle as orc
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 10.0:
+            b = n % B
+            orc.attention_forward(orc.widen_bf16(prob.Q[b:b + 1]), orc.widen_bf16(prob.K[b:b + 1]),
+                                  orc.widen_bf16(prob.V[b:b + 1]), prob.scale, prob.causal)
+            n += 1
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": alg_bytes / B * n / dt / 1e9, "unit": "GB/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"{n} sequence passes of {prob.name} (all heads), forward, float64 numpy, {dt:.1f} s"}
+    print(json.dumps(out))
+    return 0
 
 
 def main() -> int:
@@ -106,6 +167,8 @@ def main() -> int:
     if prob.varlen:
         print("bench.py: pick a dense workload", file=sys.stderr)
         return 2
+    if prob.Nk and prob.N * (prob.Hq // prob.Hkv) <= 256:
+        return bench_decode(args, prob, binding)
 
     def gpu(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -123,6 +186,16 @@ def main() -> int:
         the forward, dK/dV and dQ kernels are bracketed by events."""
         if ev:
             ev[0].record()
+        if prob.Nk:  # two lengths: one call per pass, the backward is not taken apart
+            binding.fa_cross_fwd(Q, K, V, sc, ca, O=O, LSE=LSE)
+            if ev:
+                ev[1].record()
+            if not args.fwd_only:
+                binding.fa_cross_bwd(Q, K, V, O, dO, LSE, sc, ca, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+            if ev:
+                for e in ev[2:]:
+                    e.record()
+            return
         binding.fa_fwd(Q, K, V, sc, ca, O=O, LSE=LSE)
         if ev:
             ev[1].record()
@@ -179,7 +252,11 @@ def main() -> int:
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
         "roofline_fwd": roof(fwd_fl, fwd_ms, "fwd_kernel"),
     }
-    if not args.fwd_only:
+    if prob.Nk and not args.fwd_only:
+        bwd_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+        out["roofline"] = roof(3.5 * fwd_fl, bwd_ms, "bwd_prep_kernel + bwd_dkdv_kernel + bwd_dq_kernel")
+        out["config"]["Nk"] = prob.Nk
+    elif not args.fwd_only:
         # metric FLOPs count 5 products (2.5 x forward); the dK/dV kernel performs 4 of them
         # (S, dP, dV, dK) and the dQ kernel 3 (S, dP recomputed, dQ): 2 x and 1.5 x forward
         dkdv_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps

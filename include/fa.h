@@ -149,6 +149,27 @@ int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, con
                  int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
 
 /*
+ * Forward pass for FEW query rows against MANY keys (decoding against a key/value cache):
+ * same result and layout as fa_cross_fwd, but the key sequence of every (sequence, key/value
+ * head) is cut into `num_splits` shares handled by different workgroups, and the Hq / Hkv
+ * query heads that share a key/value head are packed into one row block, so K and V are read
+ * once. Each share leaves a normalised partial O and its logsumexp (float32) in `workspace`;
+ * a second launch combines them with the identity section 3.1.1 uses between blocks,
+ * O = sum_k exp(L_k - L) O_k, L = log sum_k exp(L_k). Shares in which a row sees no key
+ * contribute nothing. `workspace`: caller-owned DEVICE memory, 16-byte aligned, at least
+ * fa_splitkv_fwd_workspace_bytes() bytes, undefined on entry and exit. 1 <= num_splits <=
+ * FA_SPLITKV_MAX_SPLITS, otherwise FA_ERR_SHAPE; more shares than 64-key blocks leave the
+ * extra ones empty. Results differ from fa_cross_fwd only by rounding (the partial sums are
+ * combined in a different order).
+ */
+#define FA_SPLITKV_MAX_SPLITS 128
+size_t fa_splitkv_fwd_workspace_bytes(int B, int Hq, int Nq, int d, int num_splits);
+int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                   int num_splits, void* stream);
+
+/*
  * Measurement aid, not part of either algorithm: a register-resident loop of the bf16 MFMA
  * the kernels are built on (v_mfma_f32_32x32x16_bf16), the "matmul throughput" the paper
  * sets the non-matmul work against (section 2.1, section 3.1), measured on this device

@@ -43,6 +43,8 @@ SIGNATURES = {
     "fa_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_bwd_workspace_bytes": (_c_size_t, [_c_int] * 6),
     "fa_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_splitkv_fwd_workspace_bytes": (_c_size_t, [_c_int] * 5),
+    "fa_splitkv_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_mfma_probe_scratch_bytes": (_c_size_t, []),
     "fa_mfma_probe": (_c_int, [_c_int, _c_int, _c_void_p, _c_void_p]),
 }
@@ -143,6 +145,15 @@ def fa_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, 
 
 def fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d) -> int:
     return load().fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
+
+
+def fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits) -> int:
+    return load().fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)
+
+
+def fa_splitkv_fwd_raw(Q, K, V, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, num_splits, stream=0) -> int:
+    return load().fa_splitkv_fwd(Q, K, V, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), num_splits,
+                                 stream)
 
 
 def fa_mfma_probe_scratch_bytes() -> int:
@@ -289,6 +300,39 @@ def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=No
                             _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
                             scale, causal, _stream()))
     return dQ, dK, dV
+
+
+FA_SPLITKV_MAX_SPLITS = 128
+
+
+def splitkv_default_splits(B, Hq, Hkv, Nq, Nk) -> int:
+    """About one workgroup per compute unit, and at least 8 blocks of 64 keys per share (measured:
+    more, shorter shares cost more in prologues and in the merge than they gain in parallelism)."""
+    units = B * Hkv * ((Nq * (Hq // Hkv) + 255) // 256)
+    blocks = (Nk + 63) // 64
+    return max(1, min(FA_SPLITKV_MAX_SPLITS, blocks // 8, -(-256 // units)))
+
+
+def fa_splitkv_fwd(Q, K, V, scale: float, causal: bool, num_splits: int = 0, O=None, LSE=None, workspace=None):
+    """Few query rows against many keys; layouts and results as fa_cross_fwd. num_splits = 0 picks a default."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    if num_splits <= 0:
+        num_splits = splitkv_default_splits(B, Hq, Hkv, Nq, Nk)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
+    if workspace is None:
+        workspace = torch.empty(fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits), dtype=torch.uint8,
+                                device=Q.device)
+    _check(fa_splitkv_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(workspace),
+                              workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                              num_splits, _stream()))
+    return O, LSE
 
 
 def fa_mfma_probe(iters: int, random_operands: bool):

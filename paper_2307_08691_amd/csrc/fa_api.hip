@@ -43,8 +43,12 @@ size_t ws_bytes(long tokens, int Hq, int d) {
 }
 
 int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
-            int Nk, long total, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
+            int Nk, long total, int Hq, int Hkv, int d, float scale, int causal, void* stream, int nsplit = 0,
+            void* ws = nullptr) {
   fa::FwdArgs a;
+  a.nsplit = nsplit;
+  a.Opart = (float*)ws;  // [nsplit, tokens, Hq, d], then the partial logsumexps [nsplit, B, Hq, Nq]
+  a.Lpart = ws ? (float*)ws + (size_t)nsplit * total * Hq * d : nullptr;
   a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
@@ -216,6 +220,26 @@ int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, con
   if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
   return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
                  causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
+}
+
+size_t fa_splitkv_fwd_workspace_bytes(int B, int Hq, int Nq, int d, int num_splits) {
+  if (B <= 0 || Hq <= 0 || Nq <= 0 || d <= 0 || num_splits <= 0) return 0;
+  return round_up((size_t)num_splits * B * Nq * Hq * (d + 1) * sizeof(float), 256);
+}
+
+int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, void* workspace,
+                   size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                   int num_splits, void* stream) {
+  if (!Q || !K || !V || !O || !LSE || !workspace) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (num_splits < 1 || num_splits > FA_SPLITKV_MAX_SPLITS) return FA_ERR_SHAPE;
+  if ((long)Nq * (Hq / Hkv) > 0x7fffffffL) return FA_ERR_SHAPE;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)) return FA_ERR_WORKSPACE;
+  return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, num_splits,
+                 workspace);
 }
 
 size_t fa_mfma_probe_scratch_bytes(void) { return 16 + (size_t)256 * 512 * sizeof(float); }

@@ -51,7 +51,13 @@ namespace fa {
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-template <int D, bool CAUSAL>
+// SPLIT (forward only, few query rows against many keys): the workgroups of one (sequence,
+// key/value head) also split the KEY sequence, each writing a normalised partial O and its
+// logsumexp in float32; fwd_merge_kernel combines them with the identity the paper uses
+// between blocks, O = sum_k e^{L_k - L} O_k, L = logsumexp_k L_k (section 3.1.1). The G query
+// heads that share the key/value head are packed into the row block (row = query * G + head),
+// so K and V are read once for all of them.
+template <int D, bool CAUSAL, bool SPLIT>
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
@@ -66,25 +72,38 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = w >> 2;  // 0: matrix phase on even phases, 1: on odd phases
   const int lq = lane & 31, hh = lane >> 5;
-  const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq);
+  const int nsplit = SPLIT ? a.nsplit : 1;
+  const int nblk = ((SPLIT ? p.N * p.G : p.N) + BR - 1) / BR;
+  const BlockCoord bc = block_coord<CAUSAL && !SPLIT>(nblk * nsplit, SPLIT ? p.Hkv : p.Hq, p.nseq);
   if (!bc.valid) return;
-  const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
-  const int h = bc.head, s = bc.seq;
+  const int split = SPLIT ? bc.blk % nsplit : 0;
+  const int rowblk = SPLIT ? bc.blk / nsplit : nblk - 1 - bc.blk;  // not split: longest causal rows first
+  const int s = bc.seq;
   const SeqInfo si = seq_info(p, s);
   const int n = si.n, nk = si.nk;  // query rows, key rows
   const int off = nk - n;          // position of query 0 among the keys (causal alignment)
+  const int nrows = SPLIT ? n * p.G : n;  // rows of the (packed) row dimension
   const int i0 = rowblk * BR;
-  if (i0 >= n) return;
-  const int g = h / p.G;
+  if (i0 >= nrows) return;
+  const int g = SPLIT ? bc.head : bc.head / p.G;
   const long kstride = (long)p.Hkv * D;
   const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;
   const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * D;
 
   // ---- Q_i operands: registers for the whole kernel (Algorithm 1, line 4)
-  const int wrow0 = i0 + 32 * w;  // first query row of this wavefront
-  const int row = wrow0 + lq;
-  const int rowc = row < n ? row : n - 1;  // rows past the end compute on a copy and are never stored
+  // row: this lane's query (index into the sequence), h: its head. Packed rows interleave the
+  // heads of the group, so both are per lane there.
+  const int prow0 = i0 + 32 * w;  // first (packed) row of this wavefront
+  const int prow = prow0 + lq;
+  const bool row_ok = prow < nrows;
+  const int prowc = row_ok ? prow : nrows - 1;  // rows past the end compute on a copy and are never stored
+  const int row = SPLIT ? prowc / p.G : prow;
+  const int rowc = SPLIT ? row : prowc;
+  const int h = SPLIT ? g * p.G + prowc % p.G : bc.head;
+  const int prow_last = prow0 + 31 < nrows ? prow0 + 31 : nrows - 1;
+  const int wrow0 = SPLIT ? prow0 / p.G : prow0;             // first and last query of this wavefront
+  const int wq_last = SPLIT ? prow_last / p.G : prow0 + 31;
+  const bool wave_on = !SPLIT || prow0 < nrows;  // a wavefront without rows only helps with the copies
   bf16x8 Qf[KS];
   {
     const __bf16* qp = a.Q + ((si.tok0 + rowc) * p.Hq + h) * D + 8 * hh;
@@ -100,13 +119,18 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   float l = 0.f;        // this lane's share of the row sum (the two lane halves are added at the end)
 
   // column blocks the workgroup visits: all of them, or (causal) those not entirely above the diagonal
+  // (split: this workgroup's share jb .. of them)
   const int ncol_all = (nk + BC - 1) / BC;
-  int ncol = ncol_all;
+  const int per_split = (ncol_all + nsplit - 1) / nsplit;
+  const int jb = split * per_split;
+  int ncol = jb + per_split < ncol_all ? jb + per_split : ncol_all;
   if (CAUSAL) {
-    const int last_pos = (i0 + BR < n ? i0 + BR : n) - 1 + off;
+    const int last_prow = (i0 + BR < nrows ? i0 + BR : nrows) - 1;
+    const int last_pos = (SPLIT ? last_prow / p.G : last_prow) + off;
     const int c = last_pos / BC + 1;
-    ncol = c < ncol_all ? c : ncol_all;
+    ncol = c < ncol ? c : ncol;
   }
+  if (ncol < jb) ncol = jb;  // nothing visible in this share: the loops below still run once
 
   // Tile loads. Issuing a tile's copies stalls the issuing wavefronts for a few hundred
   // cycles (the memory pipeline takes 16 bytes x 64 lanes at a time), so a wavefront only
@@ -122,8 +146,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
   };
   {  // blocks 0 and 1: both tiles, split over the two groups as above
-    issue_tile(0);
-    issue_tile(1);
+    issue_tile(jb);
+    issue_tile(jb + 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
     wait_vmem();
@@ -139,7 +163,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
 
   const float c2 = p.scale_log2e;
-  const int wrow_last = wrow0 + 31 + off;  // position of the last row among the keys
+  const int wrow_last = wq_last + off;  // position of the wavefront's last query among the keys
   const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;  // last visible column of this lane's row
 
   f32x16 S[2];
@@ -149,7 +173,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   auto matrix_phase = [&](int j) {
     __builtin_amdgcn_s_setprio(FA_FWD_MATRIX_PRIO);  // the MFMA stream must not wait behind the other group's VALU work
     // a block is skipped by a wavefront when every score it would produce is masked
-    if (j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
+    if (wave_on && j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
       // ---- S^T = K_j Q_i^T (Algorithm 1, line 8)
       const int zk = zrow + (j % RING) * BUFB;
       S[0] = S[1] = (f32x16){0};
@@ -157,7 +181,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
           [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
           [&](int i, bf16x8 x) { S[i & 1] = mfma32(x, Qf[i >> 1], S[i & 1]); });
     }
-    if (j >= 1 && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
+    if (wave_on && j > jb && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
       // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10)
       const int vb = ((j - 1) % RING) * BUFB + TILEB;
       const int zv0 = zcol[0] + vb, zv1 = zcol[1] + vb;
@@ -173,7 +197,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
   // ================= vector phase j: online softmax of block j (Algorithm 1, line 9) =================
   auto vector_phase = [&](int j) {
-    if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
+    if (!wave_on || j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
     const int col0 = j * BC;
     // ---- mask: causal entries above the diagonal and columns past the end
     const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
@@ -201,7 +225,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // reference is therefore advanced only when some row's maximum outgrew it by a factor
     // 2^FA_FWD_LAZY_LOG2, which after the first few blocks is rare.
     if (__builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)FA_FWD_LAZY_LOG2) != 0) {
-      const float alpha = fast_exp2((m - m_new) * c2);
+      // (split: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
+      const float alpha = SPLIT && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * c2);
       l *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -209,7 +234,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
       m = m_new;
     }
-    const float mc = m * c2;
+    // (split: a row may have seen no key yet; its scores are all -inf and must give P = 0)
+    const float mc = (SPLIT && m == -INFINITY ? 0.f : m) * c2;
     // the row sum is taken from the float32 exponentials, not from their bf16 roundings:
     // rows that see only a few keys would otherwise miss the 1e-3 bound on L
     float rs0 = 0.f, rs1 = 0.f;
@@ -236,7 +262,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   // (by group 0) at phi = 2m + 1 and first read at phi = 2m + 6. A group waits, at the end of
   // a later phase of its own, until only its newest tile is still in flight.
   if (grp == 0) {
-    for (int j = 0; j <= ncol; ++j) {
+    for (int j = jb; j <= ncol; ++j) {
       matrix_phase(j);
       lds_barrier();
       issue_tile(j + 2);
@@ -245,9 +271,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
       lds_barrier();
     }
   } else {
-    issue_tile(2);
+    issue_tile(jb + 2);
     lds_barrier();
-    for (int j = 0; j <= ncol; ++j) {
+    for (int j = jb; j <= ncol; ++j) {
       matrix_phase(j);
       wait_vmem_upto<TPW>();
       lds_barrier();
@@ -261,6 +287,26 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
   // ---- epilogue: O = diag(l)^-1 O, L = m + log l (Algorithm 1, lines 12-15)
   const float lsum = sum_with_partner32(l);
+  if (SPLIT) {  // partial result of this share of the keys, float32; no visible key: O = 0, L = -inf
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    if (row_ok) {
+      const long tok = si.tok0 + row;
+      float* op = a.Opart + (((long)split * p.total_tokens + tok) * p.Hq + h) * D + 4 * hh;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 o;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) o[u] = O[dt][4 * r4 + u] * inv;
+          *(f32x4*)(op + 32 * dt + 8 * r4) = o;
+        }
+      if (hh == 0)
+        a.Lpart[(long)split * p.total_tokens * p.Hq + s * p.lse_seq_stride + h * p.lse_head_stride + row] =
+            lsum > 0.f ? m * p.scale + fast_log2(lsum) * kLn2 : -INFINITY;
+    }
+    return;
+  }
   const float inv = 1.0f / lsum;
   if (row < n) {
     __bf16* op = a.O + ((si.tok0 + row) * p.Hq + h) * D + 4 * hh;
@@ -279,11 +325,54 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   }
 }
 
+// Combine the partial results of the key shares: one thread per 4 output elements.
+template <int D>
+__global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
+  constexpr int TPR = D / 4;  // threads per (token, head) row
+  const Problem& p = a.p;
+  const long nrows = (long)p.total_tokens * p.Hq;
+  const long r = (long)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+  if (r >= nrows) return;
+  const int c = threadIdx.x % TPR;
+  const long tok = r / p.Hq;
+  const int h = (int)(r - tok * p.Hq);
+  const long b = tok / p.N, q = tok - b * p.N;
+  const long li = b * p.lse_seq_stride + (long)h * p.lse_head_stride + q;
+  float mx = -INFINITY;
+  for (int k = 0; k < a.nsplit; ++k) mx = fmaxf(mx, a.Lpart[(long)k * nrows + li]);
+  float z = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < a.nsplit; ++k) {
+    const float wgt = __expf(a.Lpart[(long)k * nrows + li] - mx);  // shares without keys: exp(-inf) = 0
+    const f32x4 o = *(const f32x4*)(a.Opart + ((long)k * nrows + r) * D + 4 * c);
+    z += wgt;
+    acc += o * wgt;
+  }
+  const float inv = 1.f / z;  // at least one share holds a visible key
+  u32x2 o;
+  o[0] = pack_bf16(acc[0] * inv, acc[1] * inv);
+  o[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
+  *(u32x2*)(a.O + r * D + 4 * c) = o;
+  if (c == 0) a.LSE[li] = mx + __logf(z);
+}
+
 template <int D>
 static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
-  dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq)), block(512);
-  if (causal) hipLaunchKernelGGL((fwd_kernel<D, true>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((fwd_kernel<D, false>), grid, block, 0, st, a);
+  dim3 block(512);
+  if (a.nsplit > 0) {
+    const int nblk = (a.p.N * a.p.G + 255) / 256;
+    dim3 grid(grid_size(nblk * a.nsplit, a.p.Hkv * a.p.nseq));
+    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fwd_kernel<D, false, true>), grid, block, 0, st, a);
+    if (hipError_t e = hipGetLastError()) return e;
+    constexpr int RPB = 256 / (D / 4);
+    const long nrows = (long)a.p.total_tokens * a.p.Hq;
+    hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
+  dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+  if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((fwd_kernel<D, false, false>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 

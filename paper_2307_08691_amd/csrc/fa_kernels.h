@@ -11,6 +11,11 @@ struct FwdArgs {
   const __bf16* V;
   __bf16* O;
   float* LSE;
+  // key sequence split over workgroups (0: not split): partial O [nsplit, tokens, Hq, d] and
+  // partial logsumexp [nsplit] x (layout of LSE), float32, in caller-provided workspace
+  int nsplit;
+  float* Opart;
+  float* Lpart;
 };
 
 struct BwdArgs {

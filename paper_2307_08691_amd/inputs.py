@@ -171,6 +171,9 @@ CONFIGS = {
     # two lengths: a chunk of 512 new tokens against a cache of 8192 keys, and plain cross-attention
     "chunk_512_on_8k": dict(kind="cross", B=8, Nq=512, Nk=8192, Hq=32, Hkv=8, d=128, causal=True, seed=1006),
     "cross_2k_on_8k": dict(kind="cross", B=4, Nq=2048, Nk=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1007),
+    # decoding: one new token per sequence against a cache of 8192 keys, grouped heads (forward only)
+    "decode_b8_on_8k": dict(kind="cross", B=8, Nq=1, Nk=8192, Hq=32, Hkv=8, d=128, causal=True, seed=1008),
+    "decode_b1_on_128k": dict(kind="cross", B=1, Nq=1, Nk=131072, Hq=32, Hkv=8, d=128, causal=True, seed=1009),
 }
 
 

@@ -136,6 +136,25 @@ def test_two_length_entry_points_reject_bad_arguments():
     assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == binding.fa_bwd_workspace_bytes(3, 4, 2, 10, 64)
 
 
+def test_split_key_entry_point_rejects_bad_arguments():
+    def run(Q=P, ws=P, ws_bytes=1 << 30, B=1, Hq=4, Hkv=2, Nq=1, Nk=1000, d=128, scale=0.1, causal=1, splits=4):
+        return binding.fa_splitkv_fwd_raw(Q, P, P, P, P, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, splits, 0)
+    assert run(Q=0) == binding.FA_ERR_NULL
+    assert run(ws=0) == binding.FA_ERR_NULL
+    assert run(splits=0) == binding.FA_ERR_SHAPE
+    assert run(splits=129) == binding.FA_ERR_SHAPE
+    assert run(Nq=1001) == binding.FA_ERR_SHAPE  # causal, more queries than keys
+    assert run(ws=P + 4) == binding.FA_ERR_ALIGN
+    assert run(d=256) == binding.FA_ERR_UNSUPPORTED
+    need = binding.fa_splitkv_fwd_workspace_bytes(1, 4, 1, 128, 4)
+    assert need == 4 * 1 * 1 * 4 * 129 * 4 + (-(4 * 4 * 129 * 4)) % 256
+    assert run(ws_bytes=need - 1) == binding.FA_ERR_WORKSPACE
+    assert binding.splitkv_default_splits(1, 32, 8, 1, 8192) == 16
+    assert binding.splitkv_default_splits(8, 32, 8, 1, 8192) == 4
+    assert binding.splitkv_default_splits(64, 32, 8, 1, 8192) == 1
+    assert binding.splitkv_default_splits(1, 8, 8, 1, 100) == 1
+
+
 def test_mfma_probe_rejects_bad_arguments():
     assert binding.fa_mfma_probe_scratch_bytes() == 16 + 256 * 512 * 4
     assert binding.fa_mfma_probe_raw(10, 0, 0) == binding.FA_ERR_NULL

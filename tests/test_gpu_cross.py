@@ -106,3 +106,44 @@ def test_full_size_two_length_workloads_sampled_units(name):
     units = [(0, 0), (prob.B - 1, prob.Hkv - 1)]
     worst = check_units(prob, got, units)
     print(name, worst)
+
+
+# ---------------------------------------------------------------------------------------------
+# key sequence split over workgroups (fa_splitkv_fwd): same result as the definition
+# ---------------------------------------------------------------------------------------------
+
+def check_splitkv(prob, num_splits):
+    Q, K, V = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V))
+    O, L = binding.fa_splitkv_fwd(Q, K, V, prob.scale, prob.causal, num_splits)
+    torch.cuda.synchronize()
+    exp = pu.run_oracle(prob, backward=False)
+    assert torch.isfinite(O.float()).all() and torch.isfinite(L).all()
+    eo, el = pu.maxdiff(pu.to_f64(O), exp["O"]), pu.maxdiff(pu.to_f64(L), exp["LSE"])
+    assert eo <= pu.tolerance("O", exp["O"]), f"{prob.name} splits={num_splits}: O err {eo:.3e}"
+    assert el <= pu.TOL_LSE, f"{prob.name} splits={num_splits}: LSE err {el:.3e}"
+    return O, L
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("num_splits", [1, 2, 3, 7, 0])
+@pytest.mark.parametrize("Nq,Nk,Hq,Hkv,d", [(1, 1, 2, 2, 64), (1, 300, 8, 2, 128), (1, 4097, 8, 1, 128), (3, 65, 4, 4, 64),
+                                            (17, 1000, 6, 2, 128), (100, 129, 4, 2, 64), (70, 515, 8, 2, 128)])
+def test_split_keys_match_the_oracle(Nq, Nk, Hq, Hkv, d, num_splits, causal):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=3700 + Nq + Nk)
+    check_splitkv(prob, num_splits)
+
+
+def test_more_shares_than_key_blocks_and_rows_without_keys_in_a_share():
+    """Causal, the first queries see only the first keys: most shares hold nothing for them."""
+    prob = inputs.make_cross(B=1, Nq=200, Nk=260, Hq=2, Hkv=1, d=64, causal=True, seed=3800)
+    check_splitkv(prob, 5)    # 5 blocks of 64 keys, one per share
+    check_splitkv(prob, 40)   # 35 empty shares
+
+
+def test_split_keys_agree_with_the_unsplit_entry_point():
+    prob = inputs.make_cross(B=3, Nq=5, Nk=2049, Hq=8, Hkv=2, d=128, causal=True, seed=3900)
+    Q, K, V = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V))
+    O1, L1 = binding.fa_cross_fwd(Q, K, V, prob.scale, True)
+    O2, L2 = check_splitkv(prob, 6)
+    assert float((O1.float() - O2.float()).abs().max()) <= 2 * pu.bf16_ulp(float(O1.float().abs().max()))
+    assert float((L1 - L2).abs().max()) <= 1e-4
