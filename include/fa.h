@@ -149,6 +149,30 @@ int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, con
                  int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
 
 /*
+ * Two lengths in the packed ragged layout: sequence s owns query rows
+ * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
+ * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].
+ * Both offset arrays are DEVICE arrays of nseq + 1 non-decreasing int32 starting at 0;
+ * total_* and max_seqlen_* are the caller's host copies of their last entries and of (upper
+ * bounds on) the longest sequences. Each sequence is an independent problem as for
+ * fa_cross_fwd / fa_cross_bwd, with the same causal alignment. Under the causal mask every
+ * sequence must have at least as many keys as queries: the library cannot see the device
+ * arrays, so for a sequence that breaks this the outputs of that sequence are unspecified
+ * (nothing outside the output tensors is touched). The backward workspace is that of
+ * fa_varlen_bwd for total_q tokens (fa_varlen_bwd_workspace_bytes).
+ */
+int fa_varlen_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                        const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq,
+                        int total_q, int total_k, int max_seqlen_q, int max_seqlen_k,
+                        int Hq, int Hkv, int d, float scale, int causal, void* stream);
+int fa_varlen_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* LSE, void* dQ, void* dK, void* dV,
+                        void* workspace, size_t workspace_bytes,
+                        const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq,
+                        int total_q, int total_k, int max_seqlen_q, int max_seqlen_k,
+                        int Hq, int Hkv, int d, float scale, int causal, void* stream);
+
+/*
  * Forward pass for FEW query rows against MANY keys (decoding against a key/value cache):
  * same result and layout as fa_cross_fwd, but the key sequence of every (sequence, key/value
  * head) is cut into `num_splits` shares handled by different workgroups, and the Hq / Hkv

@@ -139,33 +139,39 @@ def attention_backward(Q, K, V, dO, scale, causal):
     return dQ, dK, dV
 
 
-def varlen_forward(Q, K, V, cu_seqlens, scale, causal):
-    """Packed ragged forward. Q [T,Hq,d], K,V [T,Hkv,d]; returns O [T,Hq,d], L [Hq,T]."""
+def varlen_forward(Q, K, V, cu_seqlens, scale, causal, cu_seqlens_k=None):
+    """Packed ragged forward. Q [T,Hq,d], K,V [Tk,Hkv,d]; returns O [T,Hq,d], L [Hq,T].
+    Sequence s owns query rows cu_seqlens[s]:cu_seqlens[s+1] and key/value rows
+    cu_seqlens_k[s]:cu_seqlens_k[s+1] (the same rows when cu_seqlens_k is None)."""
     T, Hq, d = Q.shape
+    cu_k = cu_seqlens if cu_seqlens_k is None else cu_seqlens_k
     O = np.zeros((T, Hq, d), dtype=np.float64)
     L = np.zeros((Hq, T), dtype=np.float64)
     for s in range(len(cu_seqlens) - 1):
         a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        ak, ek = int(cu_k[s]), int(cu_k[s + 1])
         if e == a:
             continue
-        o, lse = attention_forward(Q[None, a:e], K[None, a:e], V[None, a:e], scale, causal)
+        o, lse = attention_forward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek], scale, causal)
         O[a:e] = o[0]
         L[:, a:e] = lse[0]
     return O, L
 
 
-def varlen_backward(Q, K, V, dO, cu_seqlens, scale, causal):
-    """Packed ragged backward. Returns dQ [T,Hq,d], dK, dV [T,Hkv,d]."""
+def varlen_backward(Q, K, V, dO, cu_seqlens, scale, causal, cu_seqlens_k=None):
+    """Packed ragged backward. Returns dQ [T,Hq,d], dK, dV [Tk,Hkv,d]."""
+    cu_k = cu_seqlens if cu_seqlens_k is None else cu_seqlens_k
     dQ = np.zeros(Q.shape, dtype=np.float64)
     dK = np.zeros(K.shape, dtype=np.float64)
     dV = np.zeros(V.shape, dtype=np.float64)
     for s in range(len(cu_seqlens) - 1):
         a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        ak, ek = int(cu_k[s]), int(cu_k[s + 1])
         if e == a:
             continue
-        dq, dk, dv = attention_backward(Q[None, a:e], K[None, a:e], V[None, a:e],
+        dq, dk, dv = attention_backward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek],
                                         dO[None, a:e], scale, causal)
-        dQ[a:e], dK[a:e], dV[a:e] = dq[0], dk[0], dv[0]
+        dQ[a:e], dK[ak:ek], dV[ak:ek] = dq[0], dk[0], dv[0]
     return dQ, dK, dV
 
 

@@ -43,6 +43,9 @@ SIGNATURES = {
     "fa_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_bwd_workspace_bytes": (_c_size_t, [_c_int] * 6),
     "fa_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
+                            [_c_float, _c_int, _c_void_p]),
     "fa_splitkv_fwd_workspace_bytes": (_c_size_t, [_c_int] * 5),
     "fa_splitkv_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_mfma_probe_scratch_bytes": (_c_size_t, []),
@@ -145,6 +148,18 @@ def fa_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, 
 
 def fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d) -> int:
     return load().fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
+
+
+def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
+                            causal, stream=0) -> int:
+    return load().fa_varlen_cross_fwd(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d,
+                                      scale, int(causal), stream)
+
+
+def fa_varlen_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu_q, cu_k, nseq, total_q, total_k, max_q,
+                            max_k, Hq, Hkv, d, scale, causal, stream=0) -> int:
+    return load().fa_varlen_cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu_q, cu_k, nseq, total_q,
+                                      total_k, max_q, max_k, Hq, Hkv, d, scale, int(causal), stream)
 
 
 def fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits) -> int:
@@ -299,6 +314,47 @@ def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=No
     _check(fa_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                             _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
                             scale, causal, _stream()))
+    return dQ, dK, dV
+
+
+def fa_varlen_cross_fwd(Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int, scale: float,
+                        causal: bool, O=None, LSE=None):
+    """Packed ragged forward with two lengths. Q [Tq,Hq,d], K,V [Tk,Hkv,d] bf16; offsets int32 on the GPU."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    _need(cu_seqlens_q, "cu_seqlens_q", torch.int32)
+    _need(cu_seqlens_k, "cu_seqlens_k", torch.int32)
+    Tq, Hq, d = Q.shape
+    Tk, Hkv = K.shape[0], K.shape[1]
+    nseq = cu_seqlens_q.numel() - 1
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((Hq, Tq), dtype=torch.float32, device=Q.device)
+    _check(fa_varlen_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens_q), _ptr(cu_seqlens_k),
+                                   nseq, Tq, Tk, max_seqlen_q, max_seqlen_k, Hq, Hkv, d, scale, causal, _stream()))
+    return O, LSE
+
+
+def fa_varlen_cross_bwd(Q, K, V, O, dO, LSE, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int,
+                        scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
+    """Packed ragged backward with two lengths. Returns dQ [Tq,Hq,d], dK, dV [Tk,Hkv,d] bf16."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    Tq, Hq, d = Q.shape
+    Tk, Hkv = K.shape[0], K.shape[1]
+    nseq = cu_seqlens_q.numel() - 1
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    if workspace is None:
+        workspace = torch.empty(fa_varlen_bwd_workspace_bytes(Tq, Hq, Hkv, d), dtype=torch.uint8, device=Q.device)
+    _check(fa_varlen_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(cu_seqlens_q),
+                                   _ptr(cu_seqlens_k), nseq, Tq, Tk, max_seqlen_q, max_seqlen_k, Hq, Hkv, d, scale,
+                                   causal, _stream()))
     return dQ, dK, dV
 
 

@@ -20,9 +20,11 @@ int check_common(int Hq, int Hkv, int d, float scale) {
   return FA_OK;
 }
 
-fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int Hkv, long total, float scale) {
+fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int Hkv, long total, float scale,
+                         const int32_t* cu_k = nullptr) {
   fa::Problem p;
   p.cu_seqlens = cu;
+  p.cu_seqlens_k = cu_k;
   p.nseq = nseq;
   p.N = N;
   p.Nk = Nk;
@@ -44,12 +46,12 @@ size_t ws_bytes(long tokens, int Hq, int d) {
 
 int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
             int Nk, long total, int Hq, int Hkv, int d, float scale, int causal, void* stream, int nsplit = 0,
-            void* ws = nullptr) {
+            void* ws = nullptr, const int32_t* cu_k = nullptr) {
   fa::FwdArgs a;
   a.nsplit = nsplit;
   a.Opart = (float*)ws;  // [nsplit, tokens, Hq, d], then the partial logsumexps [nsplit, B, Hq, Nq]
   a.Lpart = ws ? (float*)ws + (size_t)nsplit * total * Hq * d : nullptr;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -65,9 +67,9 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
 
 int run_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE, void* dQ,
             void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, int Nk, long total, int Hq, int Hkv, int d,
-            float scale, int causal, int stages, void* stream) {
+            float scale, int causal, int stages, void* stream, const int32_t* cu_k = nullptr) {
   fa::BwdArgs a;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -220,6 +222,39 @@ int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, con
   if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
   return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
                  causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
+}
+
+static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,
+                              int max_k) {
+  if (int e = check_varlen(cu_q, nseq, total_q, max_q)) return e;
+  return check_varlen(cu_k, nseq, total_k, max_k);
+}
+
+int fa_varlen_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens_q,
+                        const int32_t* cu_seqlens_k, int nseq, int total_q, int total_k, int max_seqlen_q,
+                        int max_seqlen_k, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_varlen_cross(cu_seqlens_q, cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q, max_seqlen_k)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  return run_fwd(Q, K, V, O, LSE, cu_seqlens_q, nseq, max_seqlen_q, max_seqlen_k, total_q, Hq, Hkv, d, scale, causal,
+                 stream, 0, nullptr, cu_seqlens_k);
+}
+
+int fa_varlen_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                        void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                        const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq, int total_q, int total_k,
+                        int max_seqlen_q, int max_seqlen_k, int Hq, int Hkv, int d, float scale, int causal,
+                        void* stream) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (int e = check_varlen_cross(cu_seqlens_q, cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q, max_seqlen_k)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes(total_q, Hq, d)) return FA_ERR_WORKSPACE;
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, cu_seqlens_q, nseq, max_seqlen_q, max_seqlen_k, total_q,
+                 Hq, Hkv, d, scale, causal, 7, stream, cu_seqlens_k);
 }
 
 size_t fa_splitkv_fwd_workspace_bytes(int B, int Hq, int Nq, int d, int num_splits) {

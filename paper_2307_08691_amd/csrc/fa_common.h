@@ -25,6 +25,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 // under the causal mask query r stands at position r + nk - nq of the keys.
 struct Problem {
   const int32_t* cu_seqlens;  // device, nseq + 1 entries; nullptr for the dense layout
+  const int32_t* cu_seqlens_k;  // ragged with two lengths: the key/value rows' offsets; else nullptr
   int nseq;                   // number of sequences (dense: batch size)
   int N;                      // dense: number of query rows; ragged: upper bound on any length
   int Nk;                     // dense: number of key/value rows; ragged: same bound
@@ -49,6 +50,11 @@ __device__ __forceinline__ SeqInfo seq_info(const Problem& p, int s) {
     int a = p.cu_seqlens[s];
     r.tok0 = r.tok0k = a;
     r.n = r.nk = p.cu_seqlens[s + 1] - a;
+    if (p.cu_seqlens_k) {
+      a = p.cu_seqlens_k[s];
+      r.tok0k = a;
+      r.nk = p.cu_seqlens_k[s + 1] - a;
+    }
   } else {
     r.tok0 = (long)s * p.N;
     r.tok0k = (long)s * p.Nk;

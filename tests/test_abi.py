@@ -136,6 +136,18 @@ def test_two_length_entry_points_reject_bad_arguments():
     assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == binding.fa_bwd_workspace_bytes(3, 4, 2, 10, 64)
 
 
+def test_ragged_two_length_entry_points_reject_bad_arguments():
+    def run(Q=P, cu_q=P, cu_k=P, nseq=2, tq=10, tk=100, mq=8, mk=60, d=64):
+        return binding.fa_varlen_cross_fwd_raw(Q, P, P, P, P, cu_q, cu_k, nseq, tq, tk, mq, mk, 2, 2, d, 0.125, 1, 0)
+    assert run(Q=0) == binding.FA_ERR_NULL
+    assert run(cu_k=0) == binding.FA_ERR_NULL
+    assert run(mq=4) == binding.FA_ERR_SHAPE   # two sequences of at most 4 rows cannot hold 10
+    assert run(mk=101) == binding.FA_ERR_SHAPE
+    assert run(d=80) == binding.FA_ERR_UNSUPPORTED
+    ptrs = [P] * 9
+    assert binding.fa_varlen_cross_bwd_raw(*ptrs, P, 16, P, P, 2, 10, 100, 8, 60, 2, 2, 64, 0.125, 1, 0) == binding.FA_ERR_WORKSPACE
+
+
 def test_split_key_entry_point_rejects_bad_arguments():
     def run(Q=P, ws=P, ws_bytes=1 << 30, B=1, Hq=4, Hkv=2, Nq=1, Nk=1000, d=128, scale=0.1, causal=1, splits=4):
         return binding.fa_splitkv_fwd_raw(Q, P, P, P, P, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, splits, 0)

@@ -147,3 +147,53 @@ def test_split_keys_agree_with_the_unsplit_entry_point():
     O2, L2 = check_splitkv(prob, 6)
     assert float((O1.float() - O2.float()).abs().max()) <= 2 * pu.bf16_ulp(float(O1.float().abs().max()))
     assert float((L1 - L2).abs().max()) <= 1e-4
+
+
+# ---------------------------------------------------------------------------------------------
+# packed ragged batches with two lengths per sequence
+# ---------------------------------------------------------------------------------------------
+
+def ragged_cross(lq, lk, Hq, Hkv, d, seed):
+    rng = np.random.default_rng(seed)
+    cu_q = np.concatenate([[0], np.cumsum(lq)]).astype(np.int32)
+    cu_k = np.concatenate([[0], np.cumsum(lk)]).astype(np.int32)
+    draw = lambda *shape: inputs.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+    return cu_q, cu_k, draw(cu_q[-1], Hq, d), draw(cu_k[-1], Hkv, d), draw(cu_k[-1], Hkv, d), draw(cu_q[-1], Hq, d)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 2, 2), (128, 8, 2)])
+def test_ragged_batches_with_two_lengths(d, Hq, Hkv, causal):
+    lq = [1, 70, 0, 300, 64, 5]
+    lk = [257, 70, 33, 515, 65, 1000]
+    cu_q, cu_k, Qb, Kb, Vb, dOb = ragged_cross(lq, lk, Hq, Hkv, d, 4000 + d)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (Qb, Kb, Vb, dOb))
+    cq, ck = torch.from_numpy(cu_q).cuda(), torch.from_numpy(cu_k).cuda()
+    scale = d ** -0.5
+    O, L = binding.fa_varlen_cross_fwd(Q, K, V, cq, ck, max(lq), max(lk), scale, causal)
+    dQ, dK, dV = binding.fa_varlen_cross_bwd(Q, K, V, O, dO, L, cq, ck, max(lq), max(lk), scale, causal)
+    torch.cuda.synchronize()
+    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (Qb, Kb, Vb, dOb))
+    eO, eL = orc.varlen_forward(Qf, Kf, Vf, cu_q, scale, causal, cu_seqlens_k=cu_k)
+    edQ, edK, edV = orc.varlen_backward(Qf, Kf, Vf, dOf, cu_q, scale, causal, cu_seqlens_k=cu_k)
+    for nm, got, exp in (("O", O, eO), ("LSE", L, eL), ("dQ", dQ, edQ), ("dK", dK, edK), ("dV", dV, edV)):
+        g = pu.to_f64(got)
+        assert np.all(np.isfinite(g)), nm
+        err = pu.maxdiff(g, exp)
+        assert err <= pu.tolerance(nm, exp), f"{nm}: {err:.3e}"
+    # the keys of the sequence without queries receive exactly zero
+    assert not bool(dK[cu_k[2]:cu_k[3]].any()) and not bool(dV[cu_k[2]:cu_k[3]].any())
+
+
+def test_ragged_two_lengths_with_equal_offsets_reproduce_the_one_length_entry_points():
+    prob = inputs.make_varlen([100, 257, 31], Hq=4, Hkv=2, d=128, causal=True, seed=4100)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
+    O1, L1 = binding.fa_varlen_fwd(Q, K, V, cu, 257, prob.scale, True)
+    O2, L2 = binding.fa_varlen_cross_fwd(Q, K, V, cu, cu.clone(), 257, 257, prob.scale, True)
+    g1 = binding.fa_varlen_bwd(Q, K, V, O1, dO, L1, cu, 257, prob.scale, True)
+    g2 = binding.fa_varlen_cross_bwd(Q, K, V, O2, dO, L2, cu, cu.clone(), 257, 257, prob.scale, True)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)

@@ -488,3 +488,32 @@ def test_rows_forward_with_two_lengths():
     o_r, l_r = orc.rows_forward(q[rows], rows, k, v, 0.6, True, nq=nq)
     np.testing.assert_allclose(o_r, o[rows], rtol=1e-13)
     np.testing.assert_allclose(l_r, lse[rows], rtol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_ragged_two_lengths_equal_per_sequence_brute_force(causal):
+    """Every sequence of the packed batch is its own problem: compare with the scalar loops
+    sequence by sequence, and check that rows of other sequences do not leak in."""
+    lq, lk = [2, 0, 3], [4, 3, 3]
+    cu_q, cu_k = np.concatenate([[0], np.cumsum(lq)]), np.concatenate([[0], np.cumsum(lk)])
+    Hq, Hkv, d = 2, 1, 2
+    Q, K, V, dO = rnd(100, cu_q[-1], Hq, d), rnd(101, cu_k[-1], Hkv, d), rnd(102, cu_k[-1], Hkv, d), rnd(103, cu_q[-1], Hq, d)
+    O, L = orc.varlen_forward(Q, K, V, cu_q, 0.6, causal, cu_seqlens_k=cu_k)
+    dQ, dK, dV = orc.varlen_backward(Q, K, V, dO, cu_q, 0.6, causal, cu_seqlens_k=cu_k)
+    assert dK.shape == K.shape and dV.shape == V.shape
+    for s in range(3):
+        a, e, ak, ek = cu_q[s], cu_q[s + 1], cu_k[s], cu_k[s + 1]
+        if e == a:
+            assert not dK[ak:ek].any() and not dV[ak:ek].any()  # keys nobody attends to get no gradient
+            continue
+        for h in range(Hq):
+            bo, bl = brute_forward(Q[a:e, h].tolist(), K[ak:ek, 0].tolist(), V[ak:ek, 0].tolist(), 0.6, causal)
+            np.testing.assert_allclose(O[a:e, h], np.asarray(bo), rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(L[h, a:e], np.asarray(bl), rtol=1e-12, atol=1e-13)
+        dk = sum(orc.head_backward(Q[a:e, h], K[ak:ek, 0], V[ak:ek, 0], dO[a:e, h], 0.6, causal)[1] for h in range(Hq))
+        np.testing.assert_allclose(dK[ak:ek, 0], dk, rtol=1e-12, atol=1e-13)
+    # perturbing another sequence's keys changes nothing here
+    K2 = K.copy()
+    K2[cu_k[2]:] += 1.0
+    O2, _ = orc.varlen_forward(Q, K2, V, cu_q, 0.6, causal, cu_seqlens_k=cu_k)
+    np.testing.assert_array_equal(O2[:cu_q[2]], O[:cu_q[2]])
