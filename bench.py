@@ -2,8 +2,11 @@
 """Benchmark of the attention hot path on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic input:
-fa_fwd (Algorithm 1) followed by fa_bwd (Algorithm 2: prep, main, convert) on
-the workload named in `config.workload`, inputs resident in HBM. Throughput is
+fa_fwd (Algorithm 1) followed by fa_bwd (Algorithm 2: D pre-pass, dK/dV kernel, dQ
+kernel) on the workload named in `config.workload`, inputs resident in HBM.
+Workloads with two lengths run fa_cross_fwd + fa_cross_bwd; workloads with a
+handful of query rows against a long cache run fa_splitkv_fwd alone and report
+GB/s of compulsory traffic against the HBM roofline. Throughput is
 counted with the paper's formula (section 4.1): forward 4*N^2*d FLOPs per head
 and sequence, halved under the causal mask, backward 2.5x that.
 

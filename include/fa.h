@@ -26,7 +26,9 @@
  *   - Supported: d in {64, 128}; Hq a positive multiple of Hkv (grouped-query
  *     attention: query head h reads key/value head h / (Hq/Hkv), paragraph
  *     "Multi-query attention and grouped-query attention" of section 3.1);
- *     scale > 0; self-attention (one length per sequence).
+ *     scale > 0. fa_fwd, fa_bwd and fa_varlen_* take one length per sequence
+ *     (self-attention); the fa_cross_*, fa_varlen_cross_* and fa_splitkv_* entry
+ *     points take a query length and a key length.
  *   - causal != 0 masks score (r, c) with c > r inside each sequence
  *     (section 3.1.1, "Causal masking").
  *   - Return value: FA_OK or a negative FA_ERR_* code. Arguments are validated

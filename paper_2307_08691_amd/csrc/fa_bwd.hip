@@ -7,7 +7,7 @@
 //             key/value head and over the row blocks i, recomputes P from the saved
 //             logsumexp (line 11) and keeps dK_j, dV_j in MFMA accumulators for the whole
 //             loop (lines 12-16 without line 15)
-//   3. dQ:    one workgroup per block of 128 query rows; it loops over the column blocks,
+//   3. dQ:    one workgroup per block of 256 query rows; it loops over the column blocks,
 //             recomputes P and dS and keeps dQ_i in MFMA accumulators (line 15)
 //
 // The paper accumulates dQ from the column-block workers with atomic adds (section 3.2).
