@@ -151,6 +151,22 @@ int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, con
                  int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
 
 /*
+ * The same two entry points for IEEE half precision (fp16) elements instead of bfloat16: every
+ * 16-bit tensor (Q, K, V, O, dO, dQ, dK, dV) holds fp16; LSE and the workspace stay float32
+ * (fa_cross_bwd_workspace_bytes). The paper's hardware argument (section 2.1) is made for
+ * FP16/BF16 matrix units alike; the kernels differ only in the MFMA instruction and in how
+ * float32 results are rounded. Nq = Nk gives plain self-attention. fp16 has a narrower
+ * exponent range than bfloat16: scores and gradients beyond 65504 overflow, as in any fp16
+ * implementation.
+ */
+int fa_cross_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
+int fa_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                     const float* LSE, void* dQ, void* dK, void* dV,
+                     void* workspace, size_t workspace_bytes,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
+
+/*
  * Two lengths in the packed ragged layout: sequence s owns query rows
  * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
  * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].

@@ -55,6 +55,11 @@ def widen_bf16(bits):
     return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
+def widen_f16(bits):
+    """IEEE half precision bit patterns (uint16) -> float64, exactly."""
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
 def scores(q, k, scale, causal):
     """S for one head: q [Nq, d], k [Nk, d] -> [Nq, Nk] (section 2.2). Causal:
     query r is at position r + Nk - Nq; entries with a column index above

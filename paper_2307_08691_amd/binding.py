@@ -43,6 +43,8 @@ SIGNATURES = {
     "fa_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_bwd_workspace_bytes": (_c_size_t, [_c_int] * 6),
     "fa_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_cross_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_cross_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
@@ -136,14 +138,15 @@ def fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d) -> int:
     return load().fa_varlen_bwd_workspace_bytes(total, Hq, Hkv, d)
 
 
-def fa_cross_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream=0) -> int:
-    return load().fa_cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), stream)
+def fa_cross_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream=0, f16=False) -> int:
+    fn = load().fa_cross_fwd_f16 if f16 else load().fa_cross_fwd
+    return fn(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), stream)
 
 
 def fa_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                     stream=0) -> int:
-    return load().fa_cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
-                               int(causal), stream)
+                     stream=0, f16=False) -> int:
+    fn = load().fa_cross_bwd_f16 if f16 else load().fa_cross_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), stream)
 
 
 def fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d) -> int:
@@ -281,11 +284,24 @@ def fa_varlen_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float
     return dQ, dK, dV
 
 
+def _elem_type(Q, *others):
+    """bfloat16 or float16 tensors, all alike; returns True for float16."""
+    import torch
+    if Q.dtype not in (torch.bfloat16, torch.float16):
+        raise ValueError("Q must be bfloat16 or float16")
+    for t in others:
+        if t.dtype != Q.dtype:
+            raise ValueError("all 16-bit tensors must have the element type of Q")
+    return Q.dtype == torch.float16
+
+
 def fa_cross_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None):
-    """Two lengths. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 -> O [B,Nq,Hq,d] bf16, LSE [B,Hq,Nq] fp32."""
+    """Two lengths. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 (fa_cross_fwd) or fp16 (fa_cross_fwd_f16)
+    -> O [B,Nq,Hq,d] of the same type, LSE [B,Hq,Nq] fp32."""
     import torch
     for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
+        _need(t, nm)
+    f16 = _elem_type(Q, K, V)
     B, Nq, Hq, d = Q.shape
     Nk, Hkv = K.shape[1], K.shape[2]
     if O is None:
@@ -293,15 +309,16 @@ def fa_cross_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None):
     if LSE is None:
         LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
     _check(fa_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                            _stream()))
+                            _stream(), f16))
     return O, LSE
 
 
 def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
-    """Two lengths, backward. Returns dQ [B,Nq,Hq,d], dK, dV [B,Nk,Hkv,d] bf16."""
+    """Two lengths, backward (bf16 or fp16 by the tensors' type). Returns dQ [B,Nq,Hq,d], dK, dV [B,Nk,Hkv,d]."""
     import torch
     for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
+        _need(t, nm)
+    f16 = _elem_type(Q, K, V, O, dO)
     _need(LSE, "LSE", torch.float32)
     B, Nq, Hq, d = Q.shape
     Nk, Hkv = K.shape[1], K.shape[2]
@@ -313,7 +330,7 @@ def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=No
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     _check(fa_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                             _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
-                            scale, causal, _stream()))
+                            scale, causal, _stream(), f16))
     return dQ, dK, dV
 
 

@@ -21,8 +21,9 @@ int check_common(int Hq, int Hkv, int d, float scale) {
 }
 
 fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int Hkv, long total, float scale,
-                         const int32_t* cu_k = nullptr) {
+                         const int32_t* cu_k = nullptr, int f16 = 0) {
   fa::Problem p;
+  p.f16 = f16;
   p.cu_seqlens = cu;
   p.cu_seqlens_k = cu_k;
   p.nseq = nseq;
@@ -46,12 +47,12 @@ size_t ws_bytes(long tokens, int Hq, int d) {
 
 int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
             int Nk, long total, int Hq, int Hkv, int d, float scale, int causal, void* stream, int nsplit = 0,
-            void* ws = nullptr, const int32_t* cu_k = nullptr) {
+            void* ws = nullptr, const int32_t* cu_k = nullptr, int f16 = 0) {
   fa::FwdArgs a;
   a.nsplit = nsplit;
   a.Opart = (float*)ws;  // [nsplit, tokens, Hq, d], then the partial logsumexps [nsplit, B, Hq, Nq]
   a.Lpart = ws ? (float*)ws + (size_t)nsplit * total * Hq * d : nullptr;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k, f16);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -67,9 +68,9 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
 
 int run_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE, void* dQ,
             void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, int Nk, long total, int Hq, int Hkv, int d,
-            float scale, int causal, int stages, void* stream, const int32_t* cu_k = nullptr) {
+            float scale, int causal, int stages, void* stream, const int32_t* cu_k = nullptr, int f16 = 0) {
   fa::BwdArgs a;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k, f16);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -195,13 +196,24 @@ static int check_cross(int B, int Nq, int Nk, int causal) {
   return FA_OK;
 }
 
-int fa_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
-                 int Nk, int d, float scale, int causal, void* stream) {
+static int cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                     int Nk, int d, float scale, int causal, void* stream, int f16) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
   if (int e = check_common(Hq, Hkv, d, scale)) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
-  return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream);
+  return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, 0, nullptr,
+                 nullptr, f16);
+}
+
+int fa_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                 int Nk, int d, float scale, int causal, void* stream) {
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, 0);
+}
+
+int fa_cross_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                     int Nk, int d, float scale, int causal, void* stream) {
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, 1);
 }
 
 size_t fa_cross_bwd_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int d) {
@@ -210,9 +222,9 @@ size_t fa_cross_bwd_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int 
   return ws_bytes((long)B * Nq, Hq, d);
 }
 
-int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
-                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
-                 int Nq, int Nk, int d, float scale, int causal, void* stream) {
+static int cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                     void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                     int Nq, int Nk, int d, float scale, int causal, void* stream, int f16) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
   if (int e = check_common(Hq, Hkv, d, scale)) return e;
@@ -221,7 +233,21 @@ int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, con
     return FA_ERR_ALIGN;
   if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
   return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
-                 causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
+                 causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream, nullptr, f16);
+}
+
+int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                 int Nq, int Nk, int d, float scale, int causal, void* stream) {
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, 0);
+}
+
+int fa_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                     void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                     int Nq, int Nk, int d, float scale, int causal, void* stream) {
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, 1);
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,

@@ -37,7 +37,7 @@ __device__ __forceinline__ long stat_index(const Problem& p, long tok, int h) {
   return b * p.lse_seq_stride + (long)h * p.lse_head_stride + r;
 }
 
-template <int D>
+template <int D, bool F16>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
   constexpr int LPR = D / 8;  // lanes per row, 8 elements each
   constexpr int RPB = 256 / LPR;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
     bf16x8 o = *(const bf16x8*)(a.O + row * D + 8 * c);
     bf16x8 g = *(const bf16x8*)(a.dO + row * D + 8 * c);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
+    for (int t = 0; t < 8; ++t) acc += widen<F16>(o, t) * widen<F16>(g, t);
   }
 #pragma unroll
   for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 #ifndef FA_DKDV_AHEAD
 #define FA_DKDV_AHEAD 4
 #endif
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool F16>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int BC = 128;               // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
@@ -271,8 +271,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   };
   auto mma_m = [&](int i, const OperandPair& o) {
     const int tq = i / (2 * KS), k = i % (2 * KS);
-    if (k & 1) dP[tq] = mfma32(o.a, o.b, dP[tq]);
-    else S[tq] = mfma32(o.a, o.b, k == 0 ? (f32x16){0} : S[tq]);
+    if (k & 1) dP[tq] = mfma32<F16>(o.a, o.b, dP[tq]);
+    else S[tq] = mfma32<F16>(o.a, o.b, k == 0 ? (f32x16){0} : S[tq]);
   };
   auto load_m2 = [&](const Cursor& c, int i) {  // Q_i^T (even i) or dO_i^T (odd i) operand of dK / dV
     const int tq = i / (4 * DT), k = i % (4 * DT), dt = k >> 2, s2 = (k >> 1) & 1;
@@ -281,8 +281,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   };
   auto mma_m2 = [&](int i, bf16x8 x) {
     const int tq = i / (4 * DT), k = i % (4 * DT), dt = k >> 2, s2 = (k >> 1) & 1;
-    if (i & 1) dVt[dt] = mfma32(x, Pf[tq][s2], dVt[dt]);
-    else dKt[dt] = mfma32(x, dSf[tq][s2], dKt[dt]);
+    if (i & 1) dVt[dt] = mfma32<F16>(x, Pf[tq][s2], dVt[dt]);
+    else dKt[dt] = mfma32<F16>(x, dSf[tq][s2], dKt[dt]);
   };
   auto phase_v = [&](const Cursor& c) {  // P, dS
     const int i0 = c.it * BR;
@@ -309,8 +309,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       for (int r = 0; r < 16; ++r) dP[tq][r] *= S[tq][r];  // dS = P o (dP - D)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        Pf[tq][s2] = pack8(S[tq], s2);
-        dSf[tq][s2] = pack8(dP[tq], s2);
+        Pf[tq][s2] = pack8<F16>(S[tq], s2);
+        dSf[tq][s2] = pack8<F16>(dP[tq], s2);
       }
     }
   };
@@ -426,8 +426,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
           for (int u = 0; u < 4; ++u)
             x[u] = (accs[dt][4 * r4 + u] + red[((kg * DT + dt) * 16 + 4 * r4 + u) * 64 + lane]) * mul;
           u32x2 o;
-          o[0] = pack_bf16(x[0], x[1]);
-          o[1] = pack_bf16(x[2], x[3]);
+          o[0] = pack2<F16>(x[0], x[1]);
+          o[1] = pack2<F16>(x[2], x[3]);
           *(u32x2*)(dst + 32 * dt + 8 * r4) = o;
         }
     }
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // structure as the forward kernel: a matrix phase (S^T, dP^T of block j and the dQ^T update
 // with block j - 1) and a vector phase (P and dS of block j), the two wave groups one phase
 // apart, K_j / V_j tiles streaming HBM -> LDS two blocks ahead into a ring of four buffers.
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool F16>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32;
@@ -546,8 +546,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
           },
           [&](int i, bf16x8 x) {
             const int ks = i >> 2, kt = (i >> 1) & 1;
-            if (i & 1) dP[kt] = mfma32(x, dOf[ks], dP[kt]);
-            else S[kt] = mfma32(x, Qf[ks], S[kt]);
+            if (i & 1) dP[kt] = mfma32<F16>(x, dOf[ks], dP[kt]);
+            else S[kt] = mfma32<F16>(x, Qf[ks], S[kt]);
           });
     }
     if (j >= 1 && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
@@ -559,7 +559,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
             const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
             return lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro);
           },
-          [&](int i, bf16x8 x) { dQt[i >> 2] = mfma32(x, dSf[(i >> 1) & 1][i & 1], dQt[i >> 2]); });
+          [&](int i, bf16x8 x) { dQt[i >> 2] = mfma32<F16>(x, dSf[(i >> 1) & 1][i & 1], dQt[i >> 2]); });
     }
     __builtin_amdgcn_s_setprio(0);
   };
@@ -581,8 +581,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) dP[kt][r] = S[kt][r] * (dP[kt][r] - Dq);
-      dSf[kt][0] = pack8(dP[kt], 0);
-      dSf[kt][1] = pack8(dP[kt], 1);
+      dSf[kt][0] = pack8<F16>(dP[kt], 0);
+      dSf[kt][1] = pack8<F16>(dP[kt], 1);
     }
   };
 
@@ -619,40 +619,40 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         u32x2 o;
-        o[0] = pack_bf16(dQt[dt][4 * r4 + 0] * sc, dQt[dt][4 * r4 + 1] * sc);
-        o[1] = pack_bf16(dQt[dt][4 * r4 + 2] * sc, dQt[dt][4 * r4 + 3] * sc);
+        o[0] = pack2<F16>(dQt[dt][4 * r4 + 0] * sc, dQt[dt][4 * r4 + 1] * sc);
+        o[1] = pack2<F16>(dQt[dt][4 * r4 + 2] * sc, dQt[dt][4 * r4 + 3] * sc);
         *(u32x2*)(op + 32 * dt + 8 * r4) = o;
       }
   }
 }
 
-template <int D>
+template <int D, bool F16>
 static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStream_t st) {
   const long nrows = (long)a.p.total_tokens * a.p.Hq;
   constexpr int RPB = 256 / (D / 8);
   hipError_t e = hipSuccess;
   if (stages & 1) {
-    hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((bwd_prep_kernel<D, F16>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 2) {
     dim3 grid(grid_size((a.p.Nk + 127) / 128, a.p.Hkv * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true>), grid, dim3(512), 0, st, a);
-    else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false>), grid, dim3(512), 0, st, a);
+    if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16>), grid, dim3(512), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 4) {
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true>), grid, dim3(512), 0, st, a);
-    else hipLaunchKernelGGL((bwd_dq_kernel<D, false>), grid, dim3(512), 0, st, a);
+    if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16>), grid, dim3(512), 0, st, a);
     e = hipGetLastError();
   }
   return e;
 }
 
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st) {
-  if (d == 64) return launch_bwd_d<64>(a, causal, stages, st);
-  return launch_bwd_d<128>(a, causal, stages, st);
+  if (a.p.f16) return d == 64 ? launch_bwd_d<64, true>(a, causal, stages, st) : launch_bwd_d<128, true>(a, causal, stages, st);
+  return d == 64 ? launch_bwd_d<64, false>(a, causal, stages, st) : launch_bwd_d<128, false>(a, causal, stages, st);
 }
 
 }  // namespace fa

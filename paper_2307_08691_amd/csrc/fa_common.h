@@ -35,6 +35,7 @@ struct Problem {
   long lse_head_stride;       // dense: N, ragged: total_tokens
   float scale;                // softmax scaling
   float scale_log2e;          // scale * log2(e)
+  int f16;                    // element type of the 16-bit tensors: 0 bfloat16, 1 IEEE half precision
 };
 
 struct SeqInfo {
@@ -104,11 +105,20 @@ __device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads, int nseq
   return c;
 }
 
-// D = A(32 x 16) * B(16 x 32) + C on one wavefront, bf16 inputs, fp32 accumulate.
+// D = A(32 x 16) * B(16 x 32) + C on one wavefront, 16-bit inputs, fp32 accumulate.
 // Lane l supplies A[l % 32][8 * (l / 32) + t] and B[8 * (l / 32) + t][l % 32], t = 0..7,
 // and owns C[8 * (r / 4) + 4 * (l / 32) + (r % 4)][l % 32] in register r = 0..15.
+// The kernels move 16-bit elements around as raw bits (bf16x8 is just 128 bits of them);
+// the element type only matters here, where they are multiplied, and in pack2 below, where
+// float32 results are rounded: F16 = false means bfloat16, F16 = true IEEE half precision.
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+template <bool F16 = false>
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
 // Row of the 32 x 32 accumulator tile that register r of lane-half hh holds.
@@ -136,20 +146,35 @@ __device__ __forceinline__ float sum_with_partner32(float x) {
   return __builtin_bit_cast(float, (int)sw[0]) + __builtin_bit_cast(float, (int)sw[1]);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+// Two float32 values rounded (to nearest even) to the 16-bit element type, packed low | high.
+template <bool F16 = false>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   f32x2 v = {lo, hi};
-  bf16x2 r = __builtin_convertvector(v, bf16x2);
-  return __builtin_bit_cast(uint32_t, r);
+  if constexpr (F16) {
+    f16x2 r = __builtin_convertvector(v, f16x2);
+    return __builtin_bit_cast(uint32_t, r);
+  } else {
+    bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, r);
+  }
 }
 
-// Registers 8s .. 8s+7 of an accumulator tile, rounded to bf16, as an MFMA operand.
+// Registers 8s .. 8s+7 of an accumulator tile, rounded to the element type, as an MFMA operand.
+template <bool F16 = false>
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int s) {
   u32x4 r;
-  r[0] = pack_bf16(v[8 * s + 0], v[8 * s + 1]);
-  r[1] = pack_bf16(v[8 * s + 2], v[8 * s + 3]);
-  r[2] = pack_bf16(v[8 * s + 4], v[8 * s + 5]);
-  r[3] = pack_bf16(v[8 * s + 6], v[8 * s + 7]);
+  r[0] = pack2<F16>(v[8 * s + 0], v[8 * s + 1]);
+  r[1] = pack2<F16>(v[8 * s + 2], v[8 * s + 3]);
+  r[2] = pack2<F16>(v[8 * s + 4], v[8 * s + 5]);
+  r[3] = pack2<F16>(v[8 * s + 6], v[8 * s + 7]);
   return __builtin_bit_cast(bf16x8, r);
+}
+
+// Element t of 8 raw 16-bit elements, widened to float32.
+template <bool F16>
+__device__ __forceinline__ float widen(bf16x8 v, int t) {
+  if constexpr (F16) return (float)__builtin_bit_cast(f16x8, v)[t];
+  else return (float)v[t];
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

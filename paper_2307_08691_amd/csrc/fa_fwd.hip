@@ -57,7 +57,7 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return __buil
 // between blocks, O = sum_k e^{L_k - L} O_k, L = logsumexp_k L_k (section 3.1.1). The G query
 // heads that share the key/value head are packed into the row block (row = query * G + head),
 // so K and V are read once for all of them.
-template <int D, bool CAUSAL, bool SPLIT>
+template <int D, bool CAUSAL, bool SPLIT, bool F16>
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
       S[0] = S[1] = (f32x16){0};
       mfma_stream<2 * KS, FA_FWD_AHEAD_QK, 1>(
           [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
-          [&](int i, bf16x8 x) { S[i & 1] = mfma32(x, Qf[i >> 1], S[i & 1]); });
+          [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, Qf[i >> 1], S[i & 1]); });
     }
     if (wave_on && j > jb && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
       // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10)
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
             const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
             return lds_tr_pair(smem, (zv0 ^ (64 * dt)) + ro, (zv1 ^ (64 * dt)) + ro);
           },
-          [&](int i, bf16x8 x) { O[i >> 2] = mfma32(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
+          [&](int i, bf16x8 x) { O[i >> 2] = mfma32<F16>(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
     }
     __builtin_amdgcn_s_setprio(0);
   };
@@ -250,8 +250,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         rs0 += e0;
         rs1 += e1;
       }
-      Pf[kt][0] = pack8(S[kt], 0);
-      Pf[kt][1] = pack8(S[kt], 1);
+      Pf[kt][0] = pack8<F16>(S[kt], 0);
+      Pf[kt][1] = pack8<F16>(S[kt], 1);
     }
     l += rs0 + rs1;
   };
@@ -315,8 +315,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         u32x2 o;
-        o[0] = pack_bf16(O[dt][4 * r4 + 0] * inv, O[dt][4 * r4 + 1] * inv);
-        o[1] = pack_bf16(O[dt][4 * r4 + 2] * inv, O[dt][4 * r4 + 3] * inv);
+        o[0] = pack2<F16>(O[dt][4 * r4 + 0] * inv, O[dt][4 * r4 + 1] * inv);
+        o[1] = pack2<F16>(O[dt][4 * r4 + 2] * inv, O[dt][4 * r4 + 3] * inv);
         *(u32x2*)(op + 32 * dt + 8 * r4) = o;
       }
     if (hh == 0)
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 }
 
 // Combine the partial results of the key shares: one thread per 4 output elements.
-template <int D>
+template <int D, bool F16>
 __global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
   constexpr int TPR = D / 4;  // threads per (token, head) row
   const Problem& p = a.p;
@@ -350,34 +350,35 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
   }
   const float inv = 1.f / z;  // at least one share holds a visible key
   u32x2 o;
-  o[0] = pack_bf16(acc[0] * inv, acc[1] * inv);
-  o[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
+  o[0] = pack2<F16>(acc[0] * inv, acc[1] * inv);
+  o[1] = pack2<F16>(acc[2] * inv, acc[3] * inv);
   *(u32x2*)(a.O + r * D + 4 * c) = o;
   if (c == 0) a.LSE[li] = mx + __logf(z);
 }
 
-template <int D>
+template <int D, bool F16>
 static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
   dim3 block(512);
   if (a.nsplit > 0) {
     const int nblk = (a.p.N * a.p.G + 255) / 256;
     dim3 grid(grid_size(nblk * a.nsplit, a.p.Hkv * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((fwd_kernel<D, false, true>), grid, block, 0, st, a);
+    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, true, F16>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fwd_kernel<D, false, true, F16>), grid, block, 0, st, a);
     if (hipError_t e = hipGetLastError()) return e;
     constexpr int RPB = 256 / (D / 4);
     const long nrows = (long)a.p.total_tokens * a.p.Hq;
-    hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fwd_merge_kernel<D, F16>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
     return hipGetLastError();
   }
   dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
-  if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((fwd_kernel<D, false, false>), grid, block, 0, st, a);
+  if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st) {
-  return d == 64 ? launch_fwd_d<64>(a, causal, st) : launch_fwd_d<128>(a, causal, st);
+  if (a.p.f16) return d == 64 ? launch_fwd_d<64, true>(a, causal, st) : launch_fwd_d<128, true>(a, causal, st);
+  return d == 64 ? launch_fwd_d<64, false>(a, causal, st) : launch_fwd_d<128, false>(a, causal, st);
 }
 
 }  // namespace fa

@@ -19,6 +19,7 @@ import numpy as np
 
 __all__ = [
     "f32_to_bf16_bits",
+    "f32_to_f16_bits",
     "bf16_bits_to_f32",
     "AttnProblem",
     "make_dense",
@@ -39,6 +40,11 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     if nan.any():
         out[nan] = 0x7FC0
     return out
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to IEEE half precision (RNE) and return the uint16 bit patterns."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
@@ -70,6 +76,7 @@ class AttnProblem:
     B: int = 0
     N: int = 0
     Nk: int = 0
+    dtype: str = "bf16"  # element type the 16-bit patterns encode: "bf16" or "f16"
     cu_seqlens: Optional[np.ndarray] = None
     seed: int = 0
     meta: dict = field(default_factory=dict)
@@ -109,11 +116,11 @@ class AttnProblem:
         return 2.5 * self.fwd_flops()
 
 
-def _draw(rng: np.random.Generator, shape, mult: float = 1.0) -> np.ndarray:
+def _draw(rng: np.random.Generator, shape, mult: float = 1.0, dtype: str = "bf16") -> np.ndarray:
     x = rng.standard_normal(size=shape, dtype=np.float32)
     if mult != 1.0:
         x = x * np.float32(mult)
-    return f32_to_bf16_bits(x)
+    return f32_to_f16_bits(x) if dtype == "f16" else f32_to_bf16_bits(x)
 
 
 def make_dense(B, N, Hq, Hkv, d, causal, seed, scale=None, qk_mult=1.0,
@@ -130,16 +137,17 @@ def make_dense(B, N, Hq, Hkv, d, causal, seed, scale=None, qk_mult=1.0,
                        causal=bool(causal), B=B, N=N, seed=seed)
 
 
-def make_cross(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="cross") -> AttnProblem:
-    """Two lengths: Nq query rows against Nk key/value rows; Q, K, V, dO drawn in that order."""
+def make_cross(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="cross", dtype="bf16") -> AttnProblem:
+    """Two lengths: Nq query rows against Nk key/value rows; Q, K, V, dO drawn in that order,
+    rounded to bfloat16 or (dtype="f16") to IEEE half precision."""
     rng = np.random.default_rng(seed)
-    Q = _draw(rng, (B, Nq, Hq, d))
-    K = _draw(rng, (B, Nk, Hkv, d))
-    V = _draw(rng, (B, Nk, Hkv, d))
-    dO = _draw(rng, (B, Nq, Hq, d))
+    Q = _draw(rng, (B, Nq, Hq, d), dtype=dtype)
+    K = _draw(rng, (B, Nk, Hkv, d), dtype=dtype)
+    V = _draw(rng, (B, Nk, Hkv, d), dtype=dtype)
+    dO = _draw(rng, (B, Nq, Hq, d), dtype=dtype)
     return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
                        scale=float(scale if scale is not None else d ** -0.5),
-                       causal=bool(causal), B=B, N=Nq, Nk=Nk, seed=seed)
+                       causal=bool(causal), B=B, N=Nq, Nk=Nk, seed=seed, dtype=dtype)
 
 
 def make_varlen(seqlens, Hq, Hkv, d, causal, seed, scale=None,
@@ -174,6 +182,9 @@ CONFIGS = {
     # decoding: one new token per sequence against a cache of 8192 keys, grouped heads (forward only)
     "decode_b8_on_8k": dict(kind="cross", B=8, Nq=1, Nk=8192, Hq=32, Hkv=8, d=128, causal=True, seed=1008),
     "decode_b1_on_128k": dict(kind="cross", B=1, Nq=1, Nk=131072, Hq=32, Hkv=8, d=128, causal=True, seed=1009),
+    # half precision elements, the shape of d128_n8k_causal
+    "f16_d128_n8k_causal": dict(kind="cross", B=2, Nq=8192, Nk=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1010,
+                                dtype="f16"),
 }
 
 

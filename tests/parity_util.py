@@ -39,9 +39,10 @@ def tolerance(name: str, expected: np.ndarray) -> float:
     return max(base, 2.0 * bf16_ulp(float(np.max(np.abs(expected))) if expected.size else 0.0))
 
 
-def to_gpu(bits: np.ndarray):
+def to_gpu(bits: np.ndarray, dtype: str = "bf16"):
     import torch
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(
+        torch.float16 if dtype == "f16" else torch.bfloat16)
 
 
 def to_f64(t) -> np.ndarray:
@@ -58,7 +59,7 @@ def bf16_ulp(maxabs: float) -> float:
 def run_hip(prob: AttnProblem, backward: bool = True):
     """Run the HIP path. Returns dict of torch tensors (O, LSE, dQ, dK, dV)."""
     import torch
-    Q, K, V, dO = (to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    Q, K, V, dO = (to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
     out = {}
     if prob.varlen:
         cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
@@ -85,7 +86,8 @@ def run_hip(prob: AttnProblem, backward: bool = True):
 
 
 def run_oracle(prob: AttnProblem, backward: bool = True):
-    Q, K, V, dO = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
+    Q, K, V, dO = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     out = {}
     if prob.varlen:
         out["O"], out["LSE"] = orc.varlen_forward(Q, K, V, prob.cu_seqlens, prob.scale, prob.causal)
@@ -104,7 +106,7 @@ def bf16_reference_head(q, k, v, do, scale, causal):
     GPU. Returns O, dQ, dK, dV as float64 numpy arrays. Test-side yardstick
     only: the HIP path must not be less accurate than this."""
     import torch
-    bf = torch.bfloat16
+    bf = q.dtype  # bfloat16 or float16: the element type under test
     s = ((q @ k.T).float() * scale).to(bf)
     sf = s.float()
     if causal:

@@ -16,7 +16,7 @@ HEADER = os.path.join(ROOT, "include", "fa.h")
 def declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(fa_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(fa_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_header_declares_the_entry_points():
@@ -131,6 +131,10 @@ def test_two_length_entry_points_reject_bad_arguments():
     ptrs = [P] * 9
     assert binding.fa_cross_bwd_raw(*ptrs, P, 0, 1, 2, 2, 8, 128, 64, 0.125, 0, 0) == binding.FA_ERR_WORKSPACE
     assert binding.fa_cross_bwd_raw(*ptrs, 0, 1 << 20, 1, 2, 2, 8, 128, 64, 0.125, 0, 0) == binding.FA_ERR_NULL
+    # the half-precision entry points validate alike
+    assert binding.fa_cross_fwd_raw(0, P, P, P, P, 1, 2, 2, 8, 128, 64, 0.125, 0, 0, f16=True) == binding.FA_ERR_NULL
+    assert binding.fa_cross_fwd_raw(P, P, P, P, P, 1, 2, 2, 129, 128, 64, 0.125, 1, 0, f16=True) == binding.FA_ERR_SHAPE
+    assert binding.fa_cross_bwd_raw(*ptrs, P, 0, 1, 2, 2, 8, 128, 64, 0.125, 0, 0, f16=True) == binding.FA_ERR_WORKSPACE
     # the workspace holds D: one float per query row and query head
     assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == 512
     assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == binding.fa_bwd_workspace_bytes(3, 4, 2, 10, 64)

@@ -20,15 +20,16 @@ def check_units(prob, got, units):
     """units: list of (b, kv_head). Compares O, LSE, dQ for every query head of
     the group and dK, dV of the kv head."""
     G = prob.Hq // prob.Hkv
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
     worst = {}
     for (b, g) in units:
-        k = orc.widen_bf16(prob.K[b, :, g])
-        v = orc.widen_bf16(prob.V[b, :, g])
+        k = widen(prob.K[b, :, g])
+        v = widen(prob.V[b, :, g])
         dk_sum = np.zeros_like(k)
         dv_sum = np.zeros_like(v)
         for h in range(g * G, (g + 1) * G):
-            q = orc.widen_bf16(prob.Q[b, :, h])
-            do = orc.widen_bf16(prob.dO[b, :, h])
+            q = widen(prob.Q[b, :, h])
+            do = widen(prob.dO[b, :, h])
             o, lse, _ = orc.head_forward(q, k, v, prob.scale, prob.causal)
             dq, dk, dv = orc.head_backward(q, k, v, do, prob.scale, prob.causal)
             dk_sum += dk

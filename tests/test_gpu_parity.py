@@ -32,7 +32,7 @@ def check(prob, backward=True, ref_compare=True):
         assert errs[nm] <= tol, f"{prob.name}: {nm} err {errs[nm]:.3e} > {tol:.3e}"
     if ref_compare and not prob.varlen:
         # yardstick: bf16 standard implementation, per (batch, head); GQA summed over the group
-        Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+        Q, K, V, dO = (pu.to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
         G = prob.Hq // prob.Hkv
         ref = {k: np.zeros_like(exp[k]) for k in ("O", "dQ", "dK", "dV")} if backward else {"O": np.zeros_like(exp["O"])}
         for b in range(prob.B):

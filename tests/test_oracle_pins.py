@@ -517,3 +517,18 @@ def test_ragged_two_lengths_equal_per_sequence_brute_force(causal):
     K2[cu_k[2]:] += 1.0
     O2, _ = orc.varlen_forward(Q, K2, V, cu_q, 0.6, causal, cu_seqlens_k=cu_k)
     np.testing.assert_array_equal(O2[:cu_q[2]], O[:cu_q[2]])
+
+
+def test_widen_f16_is_exact_on_every_bit_pattern():
+    """Against the format's definition: sign, 5 exponent bits (bias 15), 10 fraction bits."""
+    bits = np.arange(65536, dtype=np.uint16)
+    got = orc.widen_f16(bits)
+    sign = np.where(bits >> 15, -1.0, 1.0)
+    e = ((bits >> 10) & 31).astype(np.int64)
+    f = (bits & 1023).astype(np.float64)
+    normal = sign * (1.0 + f / 1024.0) * np.exp2(e - 15.0)
+    sub = sign * (f / 1024.0) * 2.0 ** -14
+    want = np.where(e == 0, sub, normal)
+    fin = e != 31
+    np.testing.assert_array_equal(got[fin], want[fin])
+    assert np.all(np.isinf(got[(e == 31) & (f == 0)])) and np.all(np.isnan(got[(e == 31) & (f != 0)]))
