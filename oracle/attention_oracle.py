@@ -41,6 +41,14 @@ Readings taken where the text is silent or inconsistent:
     c > r + Nk - Nq. Nq = Nk gives the printed mask. Causal with Nq > Nk would
     leave rows without any key and is rejected.
 
+  * dropout on P (the footnote of section 2.2 names it; no algorithm is given):
+    P_drop = keep o P / (1 - p) replaces P in O = P V and in its derivatives,
+    while the logsumexp stays that of the undropped scores. `keep` comes from
+    a counter-based generator of this build's own definition (dropout_keep
+    below): one 32-bit hash per (head, query, group of 4 keys), one byte per
+    key, kept when the byte is >= round(256 p). The drop probability is
+    therefore a multiple of 1/256.
+
 Layouts: dense Q,O,dO,dQ [B, Nq, Hq, d]; K,V,dK,dV [B, Nk, Hkv, d]; L [B, Hq, Nq]
 (Nq = Nk = N for self-attention).
 Packed: Q.. [T, Hq, d]; K.. [T, Hkv, d]; L [Hq, T].
@@ -198,3 +206,97 @@ def rows_forward(q_rows, row_idx, k, v, scale, causal, nq=None):
         s = np.where(c > pos, -np.inf, s)
     p, lse = softmax_rows(s)
     return p @ v, lse
+
+
+# ---------------------------------------------------------------------------
+# Dropout on P. The generator is defined here in plain integer arithmetic; the
+# GPU kernels implement the same function on their own.
+# ---------------------------------------------------------------------------
+
+_M32 = 0xFFFFFFFF
+
+
+def dropout_threshold(p_drop):
+    """The 8-bit threshold for a drop probability: round(256 p), at most 255."""
+    if not (0.0 <= p_drop < 1.0):
+        raise ValueError("drop probability must be in [0, 1)")
+    return min(255, int(round(256.0 * p_drop)))
+
+
+def dropout_keep(seed, bh, nq, nk, threshold):
+    """keep[r, c] for head index bh = b * Hq + h: boolean [nq, nk].
+
+    key = (seed mod 2^32) xor (bh * 0xC2B2AE3D) xor (seed >> 32) * 0x27D4EB2F   (mod 2^32)
+    x   = (c div 4) * 0x9E3779B1 + r * 0x85EBCA77 + key                        (mod 2^32)
+    x  ^= x >> 16;  x *= 0x7FEB352D;  x ^= x >> 15;  x *= 0x846CA68B;  x ^= x >> 16
+    keep = byte (c mod 4) of x  >=  threshold
+    """
+    seed = int(seed) & 0xFFFFFFFFFFFFFFFF
+    key = ((seed & _M32) ^ ((bh * 0xC2B2AE3D) & _M32) ^ (((seed >> 32) * 0x27D4EB2F) & _M32)) & _M32
+    r = np.arange(nq, dtype=np.uint64)[:, None]
+    c = np.arange(nk, dtype=np.uint64)[None, :]
+    x = ((c >> np.uint64(2)) * np.uint64(0x9E3779B1) + r * np.uint64(0x85EBCA77) + np.uint64(key)) & np.uint64(_M32)
+    x ^= x >> np.uint64(16)
+    x = (x * np.uint64(0x7FEB352D)) & np.uint64(_M32)
+    x ^= x >> np.uint64(15)
+    x = (x * np.uint64(0x846CA68B)) & np.uint64(_M32)
+    x ^= x >> np.uint64(16)
+    byte = (x >> (np.uint64(8) * (c & np.uint64(3)))) & np.uint64(255)
+    return byte >= np.uint64(threshold)
+
+
+def head_forward_dropout(q, k, v, scale, causal, keep, threshold):
+    """One head with dropout: O = (keep o P / (1 - t/256)) V; L as without dropout."""
+    p, lse = softmax_rows(scores(q, k, scale, causal))
+    rp = 256.0 / (256.0 - threshold)
+    return (np.where(keep, p, 0.0) * rp) @ v, lse, p
+
+
+def head_backward_dropout(q, k, v, do, scale, causal, keep, threshold):
+    """One head with dropout: the chain rule through P_drop = keep o P * rp.
+    dV = P_drop^T dO;  dP = keep o (dO V^T) * rp;  D = rowsum(dO o O) = rowsum(P o dP);
+    dS = P o (dP - D);  dQ = scale dS K;  dK = scale dS^T Q."""
+    o, _, p = head_forward_dropout(q, k, v, scale, causal, keep, threshold)
+    rp = 256.0 / (256.0 - threshold)
+    pd = np.where(keep, p, 0.0) * rp
+    dv = pd.T @ do
+    dp = np.where(keep, do @ v.T, 0.0) * rp
+    big_d = np.sum(do * o, axis=1, keepdims=True)
+    ds = p * (dp - big_d)
+    return scale * (ds @ k), scale * (ds.T @ q), dv
+
+
+def attention_forward_dropout(Q, K, V, scale, causal, p_drop, seed):
+    """Dense batch forward with dropout. Shapes as attention_forward."""
+    B, N, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    t = dropout_threshold(p_drop)
+    O = np.empty((B, N, Hq, d), dtype=np.float64)
+    L = np.empty((B, Hq, N), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            keep = dropout_keep(seed, b * Hq + h, N, K.shape[1], t)
+            o, lse, _ = head_forward_dropout(Q[b, :, h, :], K[b, :, h // G, :], V[b, :, h // G, :], scale, causal, keep, t)
+            O[b, :, h, :] = o
+            L[b, h, :] = lse
+    return O, L
+
+
+def attention_backward_dropout(Q, K, V, dO, scale, causal, p_drop, seed):
+    """Dense batch backward with dropout. Shapes as attention_backward."""
+    B, N, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    t = dropout_threshold(p_drop)
+    dQ = np.zeros(Q.shape, dtype=np.float64)
+    dK = np.zeros(K.shape, dtype=np.float64)
+    dV = np.zeros(V.shape, dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            keep = dropout_keep(seed, b * Hq + h, N, K.shape[1], t)
+            dq, dk, dv = head_backward_dropout(Q[b, :, h, :], K[b, :, g, :], V[b, :, g, :], dO[b, :, h, :],
+                                               scale, causal, keep, t)
+            dQ[b, :, h, :] = dq
+            dK[b, :, g, :] += dk
+            dV[b, :, g, :] += dv
+    return dQ, dK, dV

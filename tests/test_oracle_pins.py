@@ -532,3 +532,143 @@ def test_widen_f16_is_exact_on_every_bit_pattern():
     fin = e != 31
     np.testing.assert_array_equal(got[fin], want[fin])
     assert np.all(np.isinf(got[(e == 31) & (f == 0)])) and np.all(np.isnan(got[(e == 31) & (f != 0)]))
+
+
+# ----------------------------------------------------------------------------
+# dropout on P: the generator and the chain rule through P_drop = keep o P / (1 - p)
+# ----------------------------------------------------------------------------
+
+def keep_scalar(seed, bh, r, c, thr):
+    """The generator's definition in Python integers, one element at a time."""
+    M = 0xFFFFFFFF
+    key = ((seed & M) ^ ((bh * 0xC2B2AE3D) & M) ^ (((seed >> 32) * 0x27D4EB2F) & M)) & M
+    x = ((c >> 2) * 0x9E3779B1 + r * 0x85EBCA77 + key) & M
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & M
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & M
+    x ^= x >> 16
+    return ((x >> (8 * (c & 3))) & 255) >= thr
+
+
+def test_dropout_generator_matches_its_scalar_definition():
+    seed, bh, thr = 0x123456789ABCDEF, 37, 51
+    keep = orc.dropout_keep(seed, bh, 70, 130, thr)
+    for r in (0, 1, 2, 33, 69):
+        for c in range(130):
+            assert bool(keep[r, c]) == keep_scalar(seed, bh, r, c, thr)
+
+
+def test_dropout_threshold_quantises_to_256ths():
+    assert orc.dropout_threshold(0.0) == 0 and orc.dropout_threshold(0.1) == 26
+    assert orc.dropout_threshold(0.5) == 128 and orc.dropout_threshold(0.999) == 255
+    with pytest.raises(ValueError):
+        orc.dropout_threshold(1.0)
+
+
+def test_dropout_generator_statistics():
+    thr = orc.dropout_threshold(0.25)
+    keep = orc.dropout_keep(99, 5, 1024, 1024, thr)
+    n = keep.size
+    rate = keep.mean()
+    assert abs(rate - 0.75) < 4 * math.sqrt(0.75 * 0.25 / n)
+    # rows, columns and the four bytes of a hash are not visibly correlated
+    for a, b in ((keep[:-1], keep[1:]), (keep[:, :-1], keep[:, 1:]), (keep[:, 0::4], keep[:, 1::4])):
+        corr = np.corrcoef(a.ravel().astype(float), b.ravel().astype(float))[0, 1]
+        assert abs(corr) < 0.01
+    # other heads and other seeds give other masks
+    assert (orc.dropout_keep(99, 6, 64, 64, thr) != keep[:64, :64]).mean() > 0.2
+    assert (orc.dropout_keep(100, 5, 64, 64, thr) != keep[:64, :64]).mean() > 0.2
+    assert orc.dropout_keep(99, 5, 64, 64, 0).all()  # threshold 0 keeps everything
+
+
+def brute_forward_dropout(q, k, v, scale, causal, keep, thr):
+    n, nk, d = len(q), len(k), len(q[0])
+    rp = 256.0 / (256.0 - thr)
+    O = [[0.0] * d for _ in range(n)]
+    for r in range(n):
+        cols = range(r + nk - n + 1) if causal else range(nk)
+        w = {c: math.exp(scale * sum(q[r][t] * k[c][t] for t in range(d))) for c in cols}
+        z = sum(w.values())
+        for t in range(d):
+            O[r][t] = sum(w[c] * v[c][t] for c in cols if keep[r][c]) * rp / z
+    return O
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_dropout_forward_matches_scalar_brute_force(causal):
+    nq, nk, d, thr = 5, 9, 3, 77
+    q, k, v = rnd(110, nq, d), rnd(111, nk, d), rnd(112, nk, d)
+    keep = orc.dropout_keep(7, 2, nq, nk, thr)
+    o, lse, _ = orc.head_forward_dropout(q, k, v, 0.4, causal, keep, thr)
+    bo = brute_forward_dropout(q.tolist(), k.tolist(), v.tolist(), 0.4, causal, keep.tolist(), thr)
+    np.testing.assert_allclose(o, np.asarray(bo), rtol=1e-12, atol=1e-13)
+    # the logsumexp is that of the undropped scores
+    np.testing.assert_allclose(lse, orc.head_forward(q, k, v, 0.4, causal)[1], rtol=0, atol=0)
+
+
+def test_zero_drop_probability_is_plain_attention():
+    Q, K, V, dO = rnd(113, 1, 6, 2, 3), rnd(114, 1, 8, 1, 3), rnd(115, 1, 8, 1, 3), rnd(116, 1, 6, 2, 3)
+    a = orc.attention_forward_dropout(Q, K, V, 0.5, True, 0.0, 123)
+    b = orc.attention_forward(Q, K, V, 0.5, True)
+    np.testing.assert_array_equal(a[0], b[0])
+    for x, y in zip(orc.attention_backward_dropout(Q, K, V, dO, 0.5, True, 0.0, 123),
+                    orc.attention_backward(Q, K, V, dO, 0.5, True)):
+        np.testing.assert_array_equal(x, y)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_dropout_backward_matches_finite_differences(causal):
+    nq, nk, d, thr, scale = 4, 6, 3, 90, 0.45
+    q, k, v, do = rnd(120, nq, d), rnd(121, nk, d), rnd(122, nk, d), rnd(123, nq, d)
+    keep = orc.dropout_keep(11, 0, nq, nk, thr)
+
+    def loss(qq, kk, vv):
+        return float(np.sum(np.asarray(brute_forward_dropout(qq.tolist(), kk.tolist(), vv.tolist(), scale, causal,
+                                                              keep.tolist(), thr)) * do))
+
+    got = orc.head_backward_dropout(q, k, v, do, scale, causal, keep, thr)
+    arrs = [q.copy(), k.copy(), v.copy()]
+    for which in range(3):
+        x = arrs[which]
+        ref = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            old = x[idx]
+            x[idx] = old + 1e-5
+            fp = loss(*arrs)
+            x[idx] = old - 1e-5
+            fm = loss(*arrs)
+            x[idx] = old
+            ref[idx] = (fp - fm) / 2e-5
+        err = np.max(np.abs(got[which] - ref)) / max(1.0, np.max(np.abs(ref)))
+        assert err < 1e-6, (which, err)
+
+
+def test_dropout_is_unbiased_over_seeds():
+    nq, nk, d = 3, 40, 2
+    q, k, v = rnd(124, nq, d), rnd(125, nk, d), rnd(126, nk, d)
+    plain = orc.head_forward(q, k, v, 0.3, False)[0]
+    thr = orc.dropout_threshold(0.5)
+    acc = np.zeros_like(plain)
+    n = 4000
+    for s in range(n):
+        acc += orc.head_forward_dropout(q, k, v, 0.3, False, orc.dropout_keep(s, 1, nq, nk, thr), thr)[0]
+    assert np.max(np.abs(acc / n - plain)) < 0.05
+
+
+def test_dropout_batch_wrapper_uses_one_mask_per_head():
+    B, nq, nk, Hq, Hkv, d = 2, 4, 7, 4, 2, 2
+    Q, K, V, dO = rnd(127, B, nq, Hq, d), rnd(128, B, nk, Hkv, d), rnd(129, B, nk, Hkv, d), rnd(130, B, nq, Hq, d)
+    O, L = orc.attention_forward_dropout(Q, K, V, 0.5, True, 0.3, 2024)
+    dQ, dK, dV = orc.attention_backward_dropout(Q, K, V, dO, 0.5, True, 0.3, 2024)
+    thr = orc.dropout_threshold(0.3)
+    dk_ref = np.zeros_like(K)
+    for b in range(B):
+        for h in range(Hq):
+            keep = orc.dropout_keep(2024, b * Hq + h, nq, nk, thr)
+            bo = brute_forward_dropout(Q[b, :, h].tolist(), K[b, :, h // 2].tolist(), V[b, :, h // 2].tolist(), 0.5, True,
+                                       keep.tolist(), thr)
+            np.testing.assert_allclose(O[b, :, h], np.asarray(bo), rtol=1e-12, atol=1e-13)
+            dk_ref[b, :, h // 2] += orc.head_backward_dropout(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2], dO[b, :, h],
+                                                              0.5, True, keep, thr)[1]
+    np.testing.assert_allclose(dK, dk_ref, rtol=1e-12, atol=1e-13)
