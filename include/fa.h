@@ -167,6 +167,32 @@ int fa_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O,
                      int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, void* stream);
 
 /*
+ * Dropout on P (named, without an algorithm, in the footnote of section 2.2): the same two
+ * passes as fa_cross_fwd / fa_cross_bwd (bfloat16, dense layout, two lengths) with
+ *     P_drop = keep o P / (1 - p)
+ * in place of P in O = P V and in every derivative; LSE is that of the undropped scores and
+ * D = rowsum(dO o O) as in Algorithm 2. `keep` is a pure function of (seed, sequence, head,
+ * query, key), so the backward pass regenerates the mask of the forward pass from the same
+ * `seed` and `p_drop`; nothing is stored. Generator (this library's definition): with
+ * bh = sequence * Hq + head and 32-bit wrap-around arithmetic,
+ *     x = (key / 4) * 0x9E3779B1 + query * 0x85EBCA77
+ *         + ((seed mod 2^32) xor (seed >> 32) * 0x27D4EB2F xor bh * 0xC2B2AE3D)
+ *     x ^= x >> 16;  x *= 0x7FEB352D;  x ^= x >> 15;  x *= 0x846CA68B;  x ^= x >> 16
+ *     keep = byte (key mod 4) of x  >=  round(256 * p_drop)       (threshold capped at 255)
+ * so the effective drop probability is a multiple of 1/256, and 1 / (1 - p) uses that
+ * multiple. 0 <= p_drop < 1, otherwise FA_ERR_SHAPE; a threshold of 0 runs the plain kernels.
+ * Workspace: fa_cross_bwd_workspace_bytes.
+ */
+int fa_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                   int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                   float p_drop, uint64_t seed, void* stream);
+int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                   const float* LSE, void* dQ, void* dK, void* dV,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                   float p_drop, uint64_t seed, void* stream);
+
+/*
  * Two lengths in the packed ragged layout: sequence s owns query rows
  * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
  * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].

@@ -45,6 +45,9 @@ SIGNATURES = {
     "fa_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 +
+                       [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
@@ -151,6 +154,16 @@ def fa_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, 
 
 def fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d) -> int:
     return load().fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
+
+
+def fa_dropout_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop, seed, stream=0) -> int:
+    return load().fa_dropout_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), p_drop, seed, stream)
+
+
+def fa_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop,
+                       seed, stream=0) -> int:
+    return load().fa_dropout_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                                 int(causal), p_drop, seed, stream)
 
 
 def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
@@ -331,6 +344,43 @@ def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=No
     _check(fa_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                             _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
                             scale, causal, _stream(), f16))
+    return dQ, dK, dV
+
+
+def fa_dropout_fwd(Q, K, V, scale: float, causal: bool, p_drop: float, seed: int, O=None, LSE=None):
+    """Forward with dropout on P. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
+    _check(fa_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                              p_drop, seed, _stream()))
+    return O, LSE
+
+
+def fa_dropout_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, p_drop: float, seed: int, dQ=None, dK=None,
+                   dV=None, workspace=None):
+    """Backward with the dropout mask of fa_dropout_fwd for the same p_drop and seed."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    _need(LSE, "LSE", torch.float32)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    if workspace is None:
+        workspace = torch.empty(fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d), dtype=torch.uint8,
+                                device=Q.device)
+    _check(fa_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                              _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
+                              scale, causal, p_drop, seed, _stream()))
     return dQ, dK, dV
 
 

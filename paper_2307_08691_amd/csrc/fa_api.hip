@@ -24,6 +24,9 @@ fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int
                          const int32_t* cu_k = nullptr, int f16 = 0) {
   fa::Problem p;
   p.f16 = f16;
+  p.drop_thr = 0;
+  p.drop_seed = 0;
+  p.drop_rp = 1.f;
   p.cu_seqlens = cu;
   p.cu_seqlens_k = cu_k;
   p.nseq = nseq;
@@ -248,6 +251,72 @@ int fa_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O,
                      int Nq, int Nk, int d, float scale, int causal, void* stream) {
   return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
                    stream, 1);
+}
+
+// dropout: threshold round(256 p) in 0 .. 255 (0: nothing is dropped) and the mixed seed
+static int set_dropout(fa::Problem& p, float p_drop, uint64_t seed) {
+  if (!(p_drop >= 0.f) || !(p_drop < 1.f)) return FA_ERR_SHAPE;
+  long t = std::lround(256.0 * (double)p_drop);
+  if (t > 255) t = 255;
+  p.drop_thr = (uint32_t)t;
+  p.drop_seed = (uint32_t)seed ^ ((uint32_t)(seed >> 32) * 0x27D4EB2Fu);
+  p.drop_rp = 256.f / (256.f - (float)t);
+  return FA_OK;
+}
+
+int fa_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                   int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  fa::FwdArgs a;
+  a.nsplit = 0;
+  a.Opart = a.Lpart = nullptr;
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, (long)B * Nq, scale);
+  if (int e = set_dropout(a.p, p_drop, seed)) return e;
+  a.Q = (const __bf16*)Q;
+  a.K = (const __bf16*)K;
+  a.V = (const __bf16*)V;
+  a.O = (__bf16*)O;
+  a.LSE = LSE;
+  hipError_t e = fa::launch_fwd(a, d, causal, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
+int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                   void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                   int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
+  fa::BwdArgs a;
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, (long)B * Nq, scale);
+  if (int e = set_dropout(a.p, p_drop, seed)) return e;
+  a.Q = (const __bf16*)Q;
+  a.K = (const __bf16*)K;
+  a.V = (const __bf16*)V;
+  a.O = (const __bf16*)O;
+  a.dO = (const __bf16*)dO;
+  a.LSE = LSE;
+  a.dQ = (__bf16*)dQ;
+  a.dK = (__bf16*)dK;
+  a.dV = (__bf16*)dV;
+  a.Dvec = (float*)workspace;
+  hipError_t e = fa::launch_bwd(a, d, causal, 7, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 #ifndef FA_DKDV_AHEAD
 #define FA_DKDV_AHEAD 4
 #endif
-template <int D, bool CAUSAL, bool F16>
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int BC = 128;               // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       for (int r4 = 0; r4 < 4; ++r4) {
         const f32x4 Dn = *(const f32x4*)(smem + DV_OFF + c.slot * BR * 4 + (32 * tq + 8 * r4 + 4 * hh) * 4);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) dP[tq][4 * r4 + u] = Dn[u];
+        for (int u = 0; u < 4; ++u) dP[tq][4 * r4 + u] = DROPOUT ? 0.f : Dn[u];  // dropout: see phase_v
       }
       FA_SCHED_DSRD(4);
     }
@@ -305,8 +305,29 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
           if (!vis) S[tq][r] = 0.f;
         }
       }
+      if constexpr (DROPOUT) {
+        // dP = keep o (dO V^T) / (1 - p), then dS = P o (dP - D) with the true P; afterwards P
+        // itself is masked for dV += P_drop^T dO (its 1 / (1 - p) goes into the final scaling)
+        const uint32_t hq_key = p.drop_seed ^ (uint32_t)(s * p.Hq + c.hq) * kDropHead;
+        const uint32_t base = (uint32_t)(key >> 2) * kDropCol + hq_key;
+        const int sh = 8 * (key & 3);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dP[tq][r] *= S[tq][r];  // dS = P o (dP - D)
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 Dn = *(const f32x4*)(smem + DV_OFF + stat_off + (32 * tq + 8 * r4 + 4 * hh) * 4);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = 4 * r4 + u;
+            const uint32_t x = drop_mix(base + (uint32_t)(r0 + acc_row(e, hh)) * kDropRow);
+            const bool kept = ((x >> sh) & 255u) >= p.drop_thr;
+            const float pe = S[tq][e], dpe = kept ? dP[tq][e] * p.drop_rp : 0.f;
+            dP[tq][e] = pe * (dpe + Dn[u]);  // Dn = -D
+            S[tq][e] = kept ? pe : 0.f;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dP[tq][r] *= S[tq][r];  // dS = P o (dP - D)
+      }
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         Pf[tq][s2] = pack8<F16>(S[tq], s2);
@@ -416,7 +437,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     __syncthreads();
     if (grp == 0 && key_ok) {
       __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0k + key) * p.Hkv + g) * D + 4 * hh;
-      const float mul = which == 0 ? sc : 1.f;
+      const float mul = which == 0 ? sc : (DROPOUT ? p.drop_rp : 1.f);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -439,7 +460,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // structure as the forward kernel: a matrix phase (S^T, dP^T of block j and the dQ^T update
 // with block j - 1) and a vector phase (P and dS of block j), the two wave groups one phase
 // apart, K_j / V_j tiles streaming HBM -> LDS two blocks ahead into a ring of four buffers.
-template <int D, bool CAUSAL, bool F16>
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32;
@@ -564,6 +585,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     __builtin_amdgcn_s_setprio(0);
   };
 
+  const uint32_t drop_lane = DROPOUT ? (uint32_t)hh * kDropCol + (uint32_t)row * kDropRow +
+                                           (p.drop_seed ^ (uint32_t)(s * p.Hq + h) * kDropHead)
+                                     : 0u;
   // ================= vector phase j: P = exp(S - L) (line 11), dS = P o (dP - D) (line 14) =================
   auto vector_phase = [&](int j) {
     if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
@@ -578,6 +602,15 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[kt][r] = 0.f;
+      }
+      if constexpr (DROPOUT) {  // dP = keep o (dO V^T) / (1 - p)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {  // registers 4 q4 .. 4 q4 + 3: keys col0 + 32 kt + 8 q4 + 4 hh + 0..3
+          const uint32_t x = drop_mix(drop_lane + (uint32_t)(col0 / 4 + 8 * kt + 2 * q4) * kDropCol);
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            dP[kt][4 * q4 + u] = ((x >> (8 * u)) & 255u) >= p.drop_thr ? dP[kt][4 * q4 + u] * p.drop_rp : 0.f;
+        }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) dP[kt][r] = S[kt][r] * (dP[kt][r] - Dq);
@@ -637,13 +670,31 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   }
   if (stages & 2) {
     dim3 grid(grid_size((a.p.Nk + 127) / 128, a.p.Hkv * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16>), grid, dim3(512), 0, st, a);
+    bool done = false;
+    if constexpr (!F16) {
+      if (a.p.drop_thr) {
+        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, true>), grid, dim3(512), 0, st, a);
+        done = true;
+      }
+    }
+    if (done) {
+    } else if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16>), grid, dim3(512), 0, st, a);
     else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16>), grid, dim3(512), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 4) {
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16>), grid, dim3(512), 0, st, a);
+    bool done = false;
+    if constexpr (!F16) {
+      if (a.p.drop_thr) {
+        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, true>), grid, dim3(512), 0, st, a);
+        done = true;
+      }
+    }
+    if (done) {
+    } else if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16>), grid, dim3(512), 0, st, a);
     else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16>), grid, dim3(512), 0, st, a);
     e = hipGetLastError();
   }

@@ -36,6 +36,10 @@ struct Problem {
   float scale;                // softmax scaling
   float scale_log2e;          // scale * log2(e)
   int f16;                    // element type of the 16-bit tensors: 0 bfloat16, 1 IEEE half precision
+  // dropout on P (drop_thr = 0: none): an entry is kept when its byte of the hash is >= drop_thr
+  uint32_t drop_thr;          // round(256 p), 1 .. 255
+  uint32_t drop_seed;         // (seed mod 2^32) xor (seed >> 32) * 0x27D4EB2F
+  float drop_rp;              // 1 / (1 - drop_thr / 256)
 };
 
 struct SeqInfo {
@@ -175,6 +179,20 @@ template <bool F16>
 __device__ __forceinline__ float widen(bf16x8 v, int t) {
   if constexpr (F16) return (float)__builtin_bit_cast(f16x8, v)[t];
   else return (float)v[t];
+}
+
+// Dropout generator (defined by this library, the same function as the CPU checker's): for
+// head index bh = sequence * Hq + head, query r and key c,
+//   x = (c / 4) * 0x9E3779B1 + r * 0x85EBCA77 + (seed_mix xor bh * 0xC2B2AE3D), mixed by
+//   drop_mix; entry (r, c) is kept when byte c % 4 of x is >= the threshold.
+constexpr uint32_t kDropCol = 0x9E3779B1u, kDropRow = 0x85EBCA77u, kDropHead = 0xC2B2AE3Du;
+__device__ __forceinline__ uint32_t drop_mix(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -57,7 +57,7 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return __buil
 // between blocks, O = sum_k e^{L_k - L} O_k, L = logsumexp_k L_k (section 3.1.1). The G query
 // heads that share the key/value head are packed into the row block (row = query * G + head),
 // so K and V are read once for all of them.
-template <int D, bool CAUSAL, bool SPLIT, bool F16>
+template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false>
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
@@ -168,6 +168,10 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
   f32x16 S[2];
   bf16x8 Pf[2][2];
+  // dropout: this lane's part of the hash input (its query row, its lane half, its head)
+  const uint32_t drop_lane = DROPOUT ? (uint32_t)hh * kDropCol + (uint32_t)row * kDropRow +
+                                           (p.drop_seed ^ (uint32_t)(s * p.Hq + h) * kDropHead)
+                                     : 0u;
 
   // ================= matrix phase j: S^T of block j, O^T update with block j - 1 =================
   auto matrix_phase = [&](int j) {
@@ -250,6 +254,14 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         rs0 += e0;
         rs1 += e1;
       }
+      if constexpr (DROPOUT) {  // the row sum above is that of the undropped block; O only sees the kept entries
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {  // registers 4 q4 .. 4 q4 + 3: keys col0 + 32 kt + 8 q4 + 4 hh + 0..3
+          const uint32_t x = drop_mix(drop_lane + (uint32_t)(col0 / 4 + 8 * kt + 2 * q4) * kDropCol);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) S[kt][4 * q4 + u] = ((x >> (8 * u)) & 255u) >= p.drop_thr ? S[kt][4 * q4 + u] : 0.f;
+        }
+      }
       Pf[kt][0] = pack8<F16>(S[kt], 0);
       Pf[kt][1] = pack8<F16>(S[kt], 1);
     }
@@ -307,7 +319,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     }
     return;
   }
-  const float inv = 1.0f / lsum;
+  const float inv = (DROPOUT ? p.drop_rp : 1.0f) / lsum;
   if (row < n) {
     __bf16* op = a.O + ((si.tok0 + row) * p.Hq + h) * D + 4 * hh;
 #pragma unroll
@@ -371,6 +383,13 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     return hipGetLastError();
   }
   dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+  if constexpr (!F16) {
+    if (a.p.drop_thr) {
+      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((fwd_kernel<D, false, false, false, true>), grid, block, 0, st, a);
+      return hipGetLastError();
+    }
+  }
   if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16>), grid, block, 0, st, a);
   return hipGetLastError();

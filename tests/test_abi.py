@@ -140,6 +140,20 @@ def test_two_length_entry_points_reject_bad_arguments():
     assert binding.fa_cross_bwd_workspace_bytes(3, 4, 2, 10, 1000, 64) == binding.fa_bwd_workspace_bytes(3, 4, 2, 10, 64)
 
 
+def test_dropout_entry_points_reject_bad_arguments():
+    def run(Q=P, p_drop=0.1, Nq=8, Nk=128, causal=0, d=64):
+        return binding.fa_dropout_fwd_raw(Q, P, P, P, P, 1, 2, 2, Nq, Nk, d, 0.125, causal, p_drop, 99, 0)
+    assert run(Q=0) == binding.FA_ERR_NULL
+    assert run(p_drop=1.0) == binding.FA_ERR_SHAPE
+    assert run(p_drop=-0.1) == binding.FA_ERR_SHAPE
+    assert run(p_drop=float("nan")) == binding.FA_ERR_SHAPE
+    assert run(Nq=129, causal=1) == binding.FA_ERR_SHAPE
+    assert run(d=32) == binding.FA_ERR_UNSUPPORTED
+    ptrs = [P] * 9
+    assert binding.fa_dropout_bwd_raw(*ptrs, P, 0, 1, 2, 2, 8, 128, 64, 0.125, 0, 0.1, 99, 0) == binding.FA_ERR_WORKSPACE
+    assert binding.fa_dropout_bwd_raw(*ptrs, P, 1 << 20, 1, 2, 2, 8, 128, 64, 0.125, 0, 1.5, 99, 0) == binding.FA_ERR_SHAPE
+
+
 def test_ragged_two_length_entry_points_reject_bad_arguments():
     def run(Q=P, cu_q=P, cu_k=P, nseq=2, tq=10, tk=100, mq=8, mk=60, d=64):
         return binding.fa_varlen_cross_fwd_raw(Q, P, P, P, P, cu_q, cu_k, nseq, tq, tk, mq, mk, 2, 2, d, 0.125, 1, 0)

@@ -1,0 +1,81 @@
+"""GPU parity with dropout on P: fa_dropout_fwd / fa_dropout_bwd against the float64 oracle, which
+regenerates the same keep mask from the same (seed, head, query, key) function. The mask decision
+is integer arithmetic on both sides, so the comparison is as tight as without dropout, scaled by
+1 / (1 - p)."""
+import numpy as np
+import pytest
+
+from paper_2307_08691_amd import binding, inputs
+from oracle import attention_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import parity_util as pu  # noqa: E402
+
+
+def run(prob, p_drop, seed):
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    O, L = binding.fa_dropout_fwd(Q, K, V, prob.scale, prob.causal, p_drop, seed)
+    dQ, dK, dV = binding.fa_dropout_bwd(Q, K, V, O, dO, L, prob.scale, prob.causal, p_drop, seed)
+    torch.cuda.synchronize()
+    return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV)
+
+
+def check_dropout(prob, p_drop, seed):
+    got = run(prob, p_drop, seed)
+    Q, K, V, dO = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    exp = {}
+    exp["O"], exp["LSE"] = orc.attention_forward_dropout(Q, K, V, prob.scale, prob.causal, p_drop, seed)
+    exp["dQ"], exp["dK"], exp["dV"] = orc.attention_backward_dropout(Q, K, V, dO, prob.scale, prob.causal, p_drop, seed)
+    rp = 256.0 / (256.0 - orc.dropout_threshold(p_drop))
+    errs = {}
+    for nm in ("O", "LSE", "dQ", "dK", "dV"):
+        g = pu.to_f64(got[nm])
+        assert np.all(np.isfinite(g)), nm
+        errs[nm] = pu.maxdiff(g, exp[nm])
+        tol = pu.tolerance(nm, exp[nm]) * (1.0 if nm == "LSE" else rp)
+        assert errs[nm] <= tol, f"{prob.name} p={p_drop}: {nm} err {errs[nm]:.3e} > {tol:.3e}"
+    return errs
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("p_drop", [0.1, 0.5])
+@pytest.mark.parametrize("Nq,Nk,Hq,Hkv,d", [(1, 1, 2, 2, 64), (65, 65, 2, 2, 64), (128, 128, 2, 2, 128), (257, 300, 4, 2, 128),
+                                            (300, 515, 2, 1, 64), (33, 1000, 8, 2, 128)])
+def test_dropout_matches_the_oracle(Nq, Nk, Hq, Hkv, d, p_drop, causal):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=6000 + Nq + Nk)
+    check_dropout(prob, p_drop, seed=0x1234ABCD5678 + Nq)
+
+
+def test_zero_probability_reproduces_the_plain_entry_points_bitwise():
+    prob = inputs.make_cross(B=2, Nq=200, Nk=260, Hq=4, Hkv=2, d=128, causal=True, seed=6100)
+    got = run(prob, 0.0, 42)
+    ref = pu.run_hip(prob)
+    for nm in got:
+        assert torch.equal(got[nm], ref[nm]), nm
+
+
+def test_lse_does_not_depend_on_the_mask_and_the_mask_depends_on_the_seed():
+    prob = inputs.make_cross(B=1, Nq=129, Nk=129, Hq=2, Hkv=2, d=64, causal=False, seed=6200)
+    a, b, plain = run(prob, 0.25, 1), run(prob, 0.25, 2), pu.run_hip(prob)
+    assert torch.equal(a["LSE"], plain["LSE"]) and torch.equal(b["LSE"], plain["LSE"])
+    assert not torch.equal(a["O"], b["O"])
+    again = run(prob, 0.25, 1)
+    for nm in a:
+        assert torch.equal(a[nm], again[nm]), nm  # same seed, same bits
+
+
+def test_kept_fraction_seen_through_the_output():
+    """V = all ones: every output element is (number of kept keys) / ((1 - p) Nk) for uniform P."""
+    B, N, H, d = 1, 512, 2, 64
+    Q = torch.zeros(B, N, H, d, dtype=torch.bfloat16, device="cuda")  # uniform probabilities
+    K = torch.zeros_like(Q)
+    V = torch.ones_like(Q)
+    O, _ = binding.fa_dropout_fwd(Q, K, V, 0.125, False, 0.25, 7)
+    torch.cuda.synchronize()
+    thr = orc.dropout_threshold(0.25)
+    for h in range(H):
+        keep = orc.dropout_keep(7, h, N, N, thr)
+        want = keep.sum(axis=1) / (0.75 * N)
+        assert np.max(np.abs(pu.to_f64(O[0, :, h, 0]) - want)) <= 2 * pu.bf16_ulp(float(want.max()))
