@@ -183,3 +183,44 @@ def test_mfma_probe_runs_and_reports_a_plausible_rate():
         assert 0.5 < ghz < 2.6
         peak_at_clock = 256 * 4 * 1024 * ghz / 1e3  # TFLOP/s: 1024 FLOPs per SIMD and cycle
         assert 0.3 * peak_at_clock < tf < 1.05 * peak_at_clock
+
+
+@pytest.mark.gpu
+def test_forward_and_backward_replay_from_a_captured_graph():
+    """The library allocates nothing and enqueues plain kernel launches on the caller's stream, so a
+    whole step can be captured into a HIP graph. Replays (with other eager work and synchronisation
+    in between, and new input values in the same buffers) must reproduce the eager results bit for bit."""
+    import torch
+    prob = inputs.make_dense(B=2, N=300, Hq=4, Hkv=2, d=128, causal=True, seed=2900)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    B, N, Hq, d = Q.shape
+    O, L = torch.empty_like(Q), torch.empty(B, Hq, N, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    ws = torch.empty(binding.fa_bwd_workspace_bytes(B, Hq, prob.Hkv, N, d), dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.fa_fwd(Q, K, V, prob.scale, True, O=O, LSE=L)
+        binding.fa_bwd(Q, K, V, O, dO, L, prob.scale, True, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for trial in range(3):
+        if trial:  # new values in the captured buffers
+            Q.copy_(torch.randn_like(Q))
+            dO.copy_(torch.randn_like(dO))
+        step()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in (O, L, dQ, dK, dV)]
+        for t in (O, L, dQ, dK, dV):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, (O, L, dQ, dK, dV)):
+            assert torch.equal(a, b)
