@@ -208,6 +208,46 @@ def rows_forward(q_rows, row_idx, k, v, scale, causal, nq=None):
     return p @ v, lse
 
 
+def head_statistics_blockwise(q, k, v, do, scale, causal, block=2048):
+    """L [Nq], O [Nq, d] and D = rowsum(dO o O) [Nq] of one head, evaluated `block` query rows at a
+    time so that no Nq x Nk matrix is ever held: the same definition as head_forward, row by row."""
+    nq = q.shape[0]
+    L = np.empty(nq)
+    O = np.empty((nq, v.shape[1]))
+    for a in range(0, nq, block):
+        rows = np.arange(a, min(nq, a + block))
+        O[rows], L[rows] = rows_forward(q[rows], rows, k, v, scale, causal, nq=nq)
+    return L, O, np.sum(do * O, axis=1)
+
+
+def rows_backward_dq(q_rows, row_idx, k, v, do_rows, scale, causal, nq=None):
+    """dQ for selected query rows of one head (they need nothing from the other rows):
+    dS_r = P_r o (dO_r V^T - D_r), D_r = dO_r . O_r, dQ_r = scale dS_r K."""
+    s = scale * (q_rows @ k.T)
+    if causal:
+        nk = k.shape[0]
+        pos = np.asarray(row_idx)[:, None] + (nk - (nk if nq is None else nq))
+        s = np.where(np.arange(nk)[None, :] > pos, -np.inf, s)
+    p, _ = softmax_rows(s)
+    o = p @ v
+    ds = p * (do_rows @ v.T - np.sum(do_rows * o, axis=1, keepdims=True))
+    return scale * (ds @ k)
+
+
+def cols_backward_dkdv(q, k_cols, v_cols, col_idx, nk, do, L, big_d, scale, causal):
+    """dK and dV for selected key columns `col_idx` (of `nk` keys) of one head, given the row
+    statistics L and D = rowsum(dO o O) of ALL query rows (head_statistics_blockwise):
+    P[:, c] = exp(scale q . k_c - L) (0 where masked), dV_c = P[:, c]^T dO,
+    dS[:, c] = P[:, c] o (dO v_c - D), dK_c = scale dS[:, c]^T Q."""
+    nq = q.shape[0]
+    p = np.exp(scale * (q @ k_cols.T) - L[:, None])  # [Nq, C]
+    if causal:
+        pos = np.arange(nq)[:, None] + (nk - nq)
+        p = np.where(np.asarray(col_idx)[None, :] > pos, 0.0, p)
+    ds = p * (do @ v_cols.T - big_d[:, None])
+    return scale * (ds.T @ q), p.T @ do
+
+
 # ---------------------------------------------------------------------------
 # Dropout on P. The generator is defined here in plain integer arithmetic; the
 # GPU kernels implement the same function on their own.

@@ -108,3 +108,45 @@ def test_gqa_ragged_sampled_sequences():
             err = pu.maxdiff(pu.to_f64(gt), exp)
             tol = pu.tolerance(nm, exp)
             assert err <= tol, f"ragged seq {s} (len {e - a}) kv head {g}: {nm} err {err:.3e} > {tol:.3e}"
+
+
+@pytest.mark.timeout(900)
+def test_tensors_beyond_two_to_the_31_elements():
+    """Maximum sizes: 4 x 32768 x 128 heads x 128 = 2^31 elements (4 GiB) per tensor, so element
+    offsets of the last sequences and heads do not fit 32 bits. Inputs are drawn on the GPU from a
+    seeded generator (the host copy of a tensor this size would dominate the test); the last
+    (sequence, head) unit is checked against the oracle on sampled query rows (O, L, dQ) and
+    sampled key columns (dK, dV), whose row statistics the oracle computes blockwise for the whole
+    head; the first unit on sampled rows."""
+    from paper_2307_08691_amd import binding
+    B, N, H, d, scale = 4, 32768, 128, 128, 128 ** -0.5
+    gen = torch.Generator(device="cuda").manual_seed(7001)
+    draw = lambda: torch.randn(B, N, H, d, device="cuda", dtype=torch.float32, generator=gen).to(torch.bfloat16)  # noqa: E731
+    Q = draw()
+    K = draw()
+    V = draw()
+    dO = draw()
+    assert Q.numel() == 2 ** 31
+    O, L = binding.fa_fwd(Q, K, V, scale, True)
+    dQ, dK, dV = binding.fa_bwd(Q, K, V, O, dO, L, scale, True)
+    torch.cuda.synchronize()
+    rows = np.asarray([0, 1, 255, 256, 12345, 32766, 32767])
+    cols = [0, 127, 128, 20000, 32767]
+    f64 = lambda t: t.double().cpu().numpy()  # noqa: E731
+    for (b, h, full) in ((B - 1, H - 1, True), (0, 0, False)):
+        q, k, v, do = f64(Q[b, :, h]), f64(K[b, :, h]), f64(V[b, :, h]), f64(dO[b, :, h])
+        o, lse = orc.rows_forward(q[rows], rows, k, v, scale, True)
+        dq = orc.rows_backward_dq(q[rows], rows, k, v, do[rows], scale, True)
+        for nm, got, exp in (("O", O[b, rows, h], o), ("LSE", L[b, h, rows], lse), ("dQ", dQ[b, rows, h], dq)):
+            err = pu.maxdiff(f64(got), exp)
+            assert err <= pu.tolerance(nm, exp), f"unit ({b},{h}) {nm}: {err:.3e}"
+        if full:
+            Lall, _, Dall = orc.head_statistics_blockwise(q, k, v, do, scale, True, block=1024)
+            gk, gv = orc.cols_backward_dkdv(q, k[cols], v[cols], cols, N, do, Lall, Dall, scale, True)
+            for nm, got, exp in (("dK", dK[b, cols, h], gk), ("dV", dV[b, cols, h], gv)):
+                err = pu.maxdiff(f64(got), exp)
+                assert err <= pu.tolerance(nm, exp), f"unit ({b},{h}) {nm}: {err:.3e}"
+    for t in (O, L, dQ, dK, dV):
+        # finiteness of everything, in slices (a 4 GiB tensor widened at once would double the footprint)
+        for b in range(B):
+            assert torch.isfinite(t[b].float()).all()

@@ -672,3 +672,23 @@ def test_dropout_batch_wrapper_uses_one_mask_per_head():
             dk_ref[b, :, h // 2] += orc.head_backward_dropout(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2], dO[b, :, h],
                                                               0.5, True, keep, thr)[1]
     np.testing.assert_allclose(dK, dk_ref, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nq,nk", [(9, 9), (5, 11)])
+def test_sampled_backward_helpers_are_restrictions_of_the_full_backward(nq, nk, causal):
+    d = 3
+    q, k, v, do = rnd(140, nq, d), rnd(141, nk, d), rnd(142, nk, d), rnd(143, nq, d)
+    o, lse, _ = orc.head_forward(q, k, v, 0.55, causal)
+    dq, dk, dv = orc.head_backward(q, k, v, do, 0.55, causal)
+    L, O, D = orc.head_statistics_blockwise(q, k, v, do, 0.55, causal, block=4)
+    np.testing.assert_allclose(L, lse, rtol=1e-13)
+    np.testing.assert_allclose(O, o, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(D, np.sum(do * o, axis=1), rtol=1e-12, atol=1e-14)
+    rows = [0, nq // 2, nq - 1]
+    np.testing.assert_allclose(orc.rows_backward_dq(q[rows], rows, k, v, do[rows], 0.55, causal, nq=nq), dq[rows],
+                               rtol=1e-12, atol=1e-14)
+    cols = [0, 3, nk - 1]
+    gk, gv = orc.cols_backward_dkdv(q, k[cols], v[cols], cols, nk, do, L, D, 0.55, causal)
+    np.testing.assert_allclose(gk, dk[cols], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(gv, dv[cols], rtol=1e-12, atol=1e-14)
