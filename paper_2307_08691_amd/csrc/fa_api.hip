@@ -12,17 +12,20 @@ thread_local int g_last_hip_error = 0;
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int check_common(int Hq, int Hkv, int d, float scale) {
+// any_d: the entry point also takes head dimensions that the kernels pad on chip
+// (multiples of 8 up to 128); otherwise only the two tile widths themselves.
+int check_common(int Hq, int Hkv, int d, float scale, bool any_d = true) {
   if (Hq <= 0 || Hkv <= 0 || d <= 0) return FA_ERR_SHAPE;
   if (Hq % Hkv != 0) return FA_ERR_SHAPE;
   if (!(scale > 0.f) || !std::isfinite(scale)) return FA_ERR_SHAPE;
-  if (d != 64 && d != 128) return FA_ERR_UNSUPPORTED;
+  if (any_d ? (d % 8 != 0 || d > 128) : (d != 64 && d != 128)) return FA_ERR_UNSUPPORTED;
   return FA_OK;
 }
 
-fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int Hkv, long total, float scale,
+fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int Hkv, int d, long total, float scale,
                          const int32_t* cu_k = nullptr, int f16 = 0) {
   fa::Problem p;
+  p.d = d;
   p.f16 = f16;
   p.drop_thr = 0;
   p.drop_seed = 0;
@@ -55,7 +58,7 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
   a.nsplit = nsplit;
   a.Opart = (float*)ws;  // [nsplit, tokens, Hq, d], then the partial logsumexps [nsplit, B, Hq, Nq]
   a.Lpart = ws ? (float*)ws + (size_t)nsplit * total * Hq * d : nullptr;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k, f16);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, f16);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -73,7 +76,7 @@ int run_bwd(const void* Q, const void* K, const void* V, const void* O, const vo
             void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, int Nk, long total, int Hq, int Hkv, int d,
             float scale, int causal, int stages, void* stream, const int32_t* cu_k = nullptr, int f16 = 0) {
   fa::BwdArgs a;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, total, scale, cu_k, f16);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, f16);
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -103,7 +106,8 @@ const char* fa_status_string(int status) {
     case FA_OK: return "ok";
     case FA_ERR_NULL: return "a required pointer is NULL";
     case FA_ERR_SHAPE: return "invalid shape, head grouping, scale or ragged description";
-    case FA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are supported)";
+    case FA_ERR_UNSUPPORTED:
+      return "unsupported head dimension (multiples of 8 up to 128; dropout and split keys: 64 and 128 only)";
     case FA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
     case FA_ERR_WORKSPACE: return "workspace too small";
     case FA_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
@@ -268,12 +272,12 @@ int fa_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* 
                    int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
   fa::FwdArgs a;
   a.nsplit = 0;
   a.Opart = a.Lpart = nullptr;
-  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, (long)B * Nq, scale);
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
   if (int e = set_dropout(a.p, p_drop, seed)) return e;
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
@@ -293,13 +297,13 @@ int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, c
                    int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return FA_ERR_ALIGN;
   if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
   fa::BwdArgs a;
-  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, (long)B * Nq, scale);
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
   if (int e = set_dropout(a.p, p_drop, seed)) return e;
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
@@ -362,7 +366,7 @@ int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* 
                    int num_splits, void* stream) {
   if (!Q || !K || !V || !O || !LSE || !workspace) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
   if (num_splits < 1 || num_splits > FA_SPLITKV_MAX_SPLITS) return FA_ERR_SHAPE;
   if ((long)Nq * (Hq / Hkv) > 0x7fffffffL) return FA_ERR_SHAPE;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) || !aligned16(workspace))

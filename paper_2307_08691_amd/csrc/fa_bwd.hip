@@ -44,10 +44,11 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
   const long nrows = (long)a.p.total_tokens * a.p.Hq;
   const long row = (long)blockIdx.x * RPB + threadIdx.x / LPR;
   const int c = threadIdx.x % LPR;
+  const int dh = a.p.d;  // row length in memory, at most D
   float acc = 0.f;
-  if (row < nrows) {
-    bf16x8 o = *(const bf16x8*)(a.O + row * D + 8 * c);
-    bf16x8 g = *(const bf16x8*)(a.dO + row * D + 8 * c);
+  if (row < nrows && 8 * c < dh) {
+    bf16x8 o = *(const bf16x8*)(a.O + row * dh + 8 * c);
+    bf16x8 g = *(const bf16x8*)(a.dO + row * dh + 8 * c);
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc += widen<F16>(o, t) * widen<F16>(g, t);
   }
@@ -87,7 +88,10 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 #ifndef FA_DKDV_AHEAD
 #define FA_DKDV_AHEAD 4
 #endif
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false>
+//
+// PAD: head dimension p.d below the tile width D, rows padded with zeros on chip (see the
+// forward kernel); only the first p.d columns of dK, dV are stored.
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int BC = 128;               // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
@@ -121,7 +125,9 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int off = nk - n;          // position of query 0 among the keys (causal alignment)
   const int j0 = bc.blk * BC;
   if (j0 >= nk) return;
-  const long qstride = (long)p.Hq * D, kstride = (long)p.Hkv * D;
+  const int dh = PAD ? p.d : D;  // row length in memory
+  const long qstride = (long)p.Hq * dh, kstride = (long)p.Hkv * dh;
+  if (PAD) lds_zero<512>(smem, SMEM);
 
   const float c2 = p.scale_log2e;
   const int nrt = (n + BR - 1) / BR;         // row tiles of the sequence
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     int hq, it, slot;
     long qoff, soff;
   };
-  const long wrap_q = D - (long)(nrt - i_first) * BR * qstride;  // last row tile of a head -> first of the next
+  const long wrap_q = dh - (long)(nrt - i_first) * BR * qstride;  // last row tile of a head -> first of the next
   const long wrap_s = p.lse_head_stride - (long)(nrt - i_first) * BR;
   auto advance = [&](Cursor& c, int steps) {
     for (int k = 0; k < steps; ++k) {
@@ -153,7 +159,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       c.slot = c.slot + 1 == RING ? 0 : c.slot + 1;
     }
   };
-  const Cursor tile0 = {g * p.G, i_first, 0, ((si.tok0 + (long)i_first * BR) * p.Hq + g * p.G) * D,
+  const Cursor tile0 = {g * p.G, i_first, 0, ((si.tok0 + (long)i_first * BR) * p.Hq + g * p.G) * dh,
                         stat_base + (long)g * p.G * p.lse_head_stride + (long)i_first * BR};
 
   // Q_i, dO_i (line 9) go HBM -> LDS directly; L_i, D_i travel through two registers of the
@@ -162,8 +168,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // them, and with them for the copies in flight.
   float lraw = 0.f, draw = 0.f;
   bool stat_ok = false;
-  TileLoader<D, BR, 4> qloader;  // Q_i and dO_i tiles have the same shape and row pitch
-  qloader.init(qstride, kg, lane);
+  TileLoader<D, BR, 4, PAD> qloader;  // Q_i and dO_i tiles have the same shape and row pitch
+  qloader.init(qstride, kg, lane, dh / 8);
   auto issue_loads = [&](const Cursor& c) {
     char* dst = smem + QDO_OFF + c.slot * BUFB;
     if ((c.it + 1) * BR <= n) {  // all rows exist
@@ -177,8 +183,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     } else {  // the last rows of the sequence: rows past the end repeat row n - 1
       const int i0 = c.it * BR;
       const long first = c.qoff - (long)i0 * qstride;  // row 0 of this head
-      tile_load_async<D, BR, 4>(dst, a.Q + first, qstride, i0, n - 1, kg, lane);
-      tile_load_async<D, BR, 4>(dst + TILEB, a.dO + first, qstride, i0, n - 1, kg, lane);
+      tile_load_async<D, BR, 4, PAD>(dst, a.Q + first, qstride, i0, n - 1, kg, lane, dh / 8);
+      tile_load_async<D, BR, 4, PAD>(dst + TILEB, a.dO + first, qstride, i0, n - 1, kg, lane, dh / 8);
       if (gtid < BR) {
         stat_ok = i0 + gtid < n;
         const int r = stat_ok ? gtid : n - 1 - i0;
@@ -199,15 +205,15 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 
   // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop; tiles 0..2 are
   //      requested up front by all wavefronts
-  tile_load_async<D, BC, 8>(smem + KT_OFF, a.K + (si.tok0k * p.Hkv + g) * D, kstride, j0, nk - 1, v, lane);
-  tile_load_async<D, BC, 8>(smem + VT_OFF, a.V + (si.tok0k * p.Hkv + g) * D, kstride, j0, nk - 1, v, lane);
+  tile_load_async<D, BC, 8, PAD>(smem + KT_OFF, a.K + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
+  tile_load_async<D, BC, 8, PAD>(smem + VT_OFF, a.V + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
   {
     Cursor c = tile0;
     for (int t = 0; t < 3 && t < T; ++t) {
       const long first = c.qoff - (long)c.it * BR * qstride;  // row 0 of this head
       char* dst = smem + QDO_OFF + c.slot * BUFB;
-      tile_load_async<D, BR, 8>(dst, a.Q + first, qstride, c.it * BR, n - 1, v, lane);
-      tile_load_async<D, BR, 8>(dst + TILEB, a.dO + first, qstride, c.it * BR, n - 1, v, lane);
+      tile_load_async<D, BR, 8, PAD>(dst, a.Q + first, qstride, c.it * BR, n - 1, v, lane, dh / 8);
+      tile_load_async<D, BR, 8, PAD>(dst + TILEB, a.dO + first, qstride, c.it * BR, n - 1, v, lane, dh / 8);
       if (tid >= t * BR && tid < (t + 1) * BR) {  // 3 * BR <= 512 threads
         const int row = c.it * BR + tid - t * BR;
         const bool ok = row < n;
@@ -436,7 +442,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     }
     __syncthreads();
     if (grp == 0 && key_ok) {
-      __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0k + key) * p.Hkv + g) * D + 4 * hh;
+      __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0k + key) * p.Hkv + g) * dh + 4 * hh;
       const float mul = which == 0 ? sc : (DROPOUT ? p.drop_rp : 1.f);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -449,7 +455,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
           u32x2 o;
           o[0] = pack2<F16>(x[0], x[1]);
           o[1] = pack2<F16>(x[2], x[3]);
-          *(u32x2*)(dst + 32 * dt + 8 * r4) = o;
+          if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(dst + 32 * dt + 8 * r4) = o;
         }
     }
     __syncthreads();
@@ -460,7 +466,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // structure as the forward kernel: a matrix phase (S^T, dP^T of block j and the dQ^T update
 // with block j - 1) and a vector phase (P and dS of block j), the two wave groups one phase
 // apart, K_j / V_j tiles streaming HBM -> LDS two blocks ahead into a ring of four buffers.
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false>
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32;
@@ -484,9 +490,11 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const int i0 = rowblk * BR;
   if (i0 >= n) return;
   const int g = h / p.G;
-  const long kstride = (long)p.Hkv * D;
-  const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;
-  const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * D;
+  const int dh = PAD ? p.d : D;  // row length in memory
+  const long kstride = (long)p.Hkv * dh;
+  const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * dh;
+  const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * dh;
+  if (PAD) lds_zero<512>(smem, RING * BUFB);
 
   // ---- Q_i, dO_i operands and L_i, D_i of this lane's query row: registers for the whole kernel
   const int wrow0 = i0 + 32 * w;
@@ -494,12 +502,15 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const int rowc = row < n ? row : n - 1;
   bf16x8 Qf[KS], dOf[KS];
   {
-    const __bf16* qp = a.Q + ((si.tok0 + rowc) * p.Hq + h) * D + 8 * hh;
-    const __bf16* gp = a.dO + ((si.tok0 + rowc) * p.Hq + h) * D + 8 * hh;
+    const __bf16* qp = a.Q + ((si.tok0 + rowc) * p.Hq + h) * dh + 8 * hh;
+    const __bf16* gp = a.dO + ((si.tok0 + rowc) * p.Hq + h) * dh + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      Qf[ks] = *(const bf16x8*)(qp + 16 * ks);
-      dOf[ks] = *(const bf16x8*)(gp + 16 * ks);
+      Qf[ks] = dOf[ks] = (bf16x8){0};
+      if (!PAD || 16 * ks + 8 * hh < dh) {
+        Qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+        dOf[ks] = *(const bf16x8*)(gp + 16 * ks);
+      }
     }
   }
   const long stat = s * p.lse_seq_stride + (long)h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + rowc;
@@ -520,9 +531,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
 
   // tile copies: group 1 brings in the K tiles, group 0 the V tiles, each at the start of its
   // own vector phase (see the forward kernel)
-  TileLoader<D, BC, 4> loader;
-  loader.init(kstride, w & 3, lane);
-  constexpr int TPW = TileLoader<D, BC, 4>::PER;
+  TileLoader<D, BC, 4, PAD> loader;
+  loader.init(kstride, w & 3, lane, dh / 8);
+  constexpr int TPW = TileLoader<D, BC, 4, PAD>::PER;
   auto issue_tile = [&](int j) {
     char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
     loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
@@ -645,7 +656,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   }
 
   if (row < n) {
-    __bf16* op = a.dQ + ((si.tok0 + row) * p.Hq + h) * D + 4 * hh;
+    __bf16* op = a.dQ + ((si.tok0 + row) * p.Hq + h) * dh + 4 * hh;
     const float sc = p.scale;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -654,7 +665,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
         u32x2 o;
         o[0] = pack2<F16>(dQt[dt][4 * r4 + 0] * sc, dQt[dt][4 * r4 + 1] * sc);
         o[1] = pack2<F16>(dQt[dt][4 * r4 + 2] * sc, dQt[dt][4 * r4 + 3] * sc);
-        *(u32x2*)(op + 32 * dt + 8 * r4) = o;
+        if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(op + 32 * dt + 8 * r4) = o;
       }
   }
 }
@@ -671,8 +682,13 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   if (stages & 2) {
     dim3 grid(grid_size((a.p.Nk + 127) / 128, a.p.Hkv * a.p.nseq));
     bool done = false;
+    if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
+      if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
+      done = true;
+    }
     if constexpr (!F16) {
-      if (a.p.drop_thr) {
+      if (!done && a.p.drop_thr) {
         if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, false, true>), grid, dim3(512), 0, st, a);
         else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
@@ -686,8 +702,13 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   if (stages & 4) {
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
     bool done = false;
+    if (a.p.d != D) {
+      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
+      done = true;
+    }
     if constexpr (!F16) {
-      if (a.p.drop_thr) {
+      if (!done && a.p.drop_thr) {
         if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, false, true>), grid, dim3(512), 0, st, a);
         else hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
@@ -702,8 +723,8 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
 }
 
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st) {
-  if (a.p.f16) return d == 64 ? launch_bwd_d<64, true>(a, causal, stages, st) : launch_bwd_d<128, true>(a, causal, stages, st);
-  return d == 64 ? launch_bwd_d<64, false>(a, causal, stages, st) : launch_bwd_d<128, false>(a, causal, stages, st);
+  if (a.p.f16) return d <= 64 ? launch_bwd_d<64, true>(a, causal, stages, st) : launch_bwd_d<128, true>(a, causal, stages, st);
+  return d <= 64 ? launch_bwd_d<64, false>(a, causal, stages, st) : launch_bwd_d<128, false>(a, causal, stages, st);
 }
 
 }  // namespace fa

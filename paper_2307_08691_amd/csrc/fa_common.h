@@ -30,6 +30,7 @@ struct Problem {
   int N;                      // dense: number of query rows; ragged: upper bound on any length
   int Nk;                     // dense: number of key/value rows; ragged: same bound
   int Hq, Hkv, G;             // G = Hq / Hkv
+  int d;                      // head dimension in memory (a multiple of 8); kernels pad it to 64 or 128 on chip
   int total_tokens;
   long lse_seq_stride;        // dense: Hq * N, ragged: 0
   long lse_head_stride;       // dense: N, ragged: total_tokens

@@ -57,7 +57,11 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return __buil
 // between blocks, O = sum_k e^{L_k - L} O_k, L = logsumexp_k L_k (section 3.1.1). The G query
 // heads that share the key/value head are packed into the row block (row = query * G + head),
 // so K and V are read once for all of them.
-template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false>
+//
+// PAD: the head dimension in memory, p.d, is smaller than the tile width D. Rows are padded
+// with zeros on chip (registers for Q, never-written LDS chunks for K and V), which changes
+// no product, and only the first p.d columns of O are stored.
+template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false, bool PAD = false>
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
@@ -86,9 +90,11 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   const int i0 = rowblk * BR;
   if (i0 >= nrows) return;
   const int g = SPLIT ? bc.head : bc.head / p.G;
-  const long kstride = (long)p.Hkv * D;
-  const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;
-  const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * D;
+  const int dh = PAD ? p.d : D;  // row length in memory
+  const long kstride = (long)p.Hkv * dh;
+  const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * dh;
+  const __bf16* Vb = a.V + (si.tok0k * p.Hkv + g) * dh;
+  if (PAD) lds_zero<512>(smem, RING * BUFB);
 
   // ---- Q_i operands: registers for the whole kernel (Algorithm 1, line 4)
   // row: this lane's query (index into the sequence), h: its head. Packed rows interleave the
@@ -106,9 +112,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   const bool wave_on = !SPLIT || prow0 < nrows;  // a wavefront without rows only helps with the copies
   bf16x8 Qf[KS];
   {
-    const __bf16* qp = a.Q + ((si.tok0 + rowc) * p.Hq + h) * D + 8 * hh;
+    const __bf16* qp = a.Q + ((si.tok0 + rowc) * p.Hq + h) * dh + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) Qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+    for (int ks = 0; ks < KS; ++ks) {
+      Qf[ks] = (bf16x8){0};
+      if (!PAD || 16 * ks + 8 * hh < dh) Qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+    }
   }
 
   // ---- on-chip state (Algorithm 1, line 5)
@@ -138,9 +147,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   // busy: group 1 brings in the K tiles, group 0 the V tiles, each two blocks ahead. Every
   // wavefront issues exactly TPW copies per own vector phase, also past the last block (rows
   // are clamped, the data is never read), so the waits below can count instructions.
-  TileLoader<D, BC, 4> loader;
-  loader.init(kstride, w & 3, lane);
-  constexpr int TPW = TileLoader<D, BC, 4>::PER;  // copies per wavefront per tile
+  TileLoader<D, BC, 4, PAD> loader;
+  loader.init(kstride, w & 3, lane, dh / 8);
+  constexpr int TPW = TileLoader<D, BC, 4, PAD>::PER;  // copies per wavefront per tile
   auto issue_tile = [&](int j) {  // group 0: V_j, group 1: K_j
     char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
     loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
@@ -321,7 +330,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   }
   const float inv = (DROPOUT ? p.drop_rp : 1.0f) / lsum;
   if (row < n) {
-    __bf16* op = a.O + ((si.tok0 + row) * p.Hq + h) * D + 4 * hh;
+    __bf16* op = a.O + ((si.tok0 + row) * p.Hq + h) * dh + 4 * hh;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -329,7 +338,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         u32x2 o;
         o[0] = pack2<F16>(O[dt][4 * r4 + 0] * inv, O[dt][4 * r4 + 1] * inv);
         o[1] = pack2<F16>(O[dt][4 * r4 + 2] * inv, O[dt][4 * r4 + 3] * inv);
-        *(u32x2*)(op + 32 * dt + 8 * r4) = o;
+        if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(op + 32 * dt + 8 * r4) = o;
       }
     if (hh == 0)
       a.LSE[s * p.lse_seq_stride + h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + row] =
@@ -383,6 +392,11 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     return hipGetLastError();
   }
   dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+  if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
+    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, true>), grid, block, 0, st, a);
+    return hipGetLastError();
+  }
   if constexpr (!F16) {
     if (a.p.drop_thr) {
       if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, true>), grid, block, 0, st, a);
@@ -396,8 +410,9 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st) {
-  if (a.p.f16) return d == 64 ? launch_fwd_d<64, true>(a, causal, st) : launch_fwd_d<128, true>(a, causal, st);
-  return d == 64 ? launch_fwd_d<64, false>(a, causal, st) : launch_fwd_d<128, false>(a, causal, st);
+  // tile width: the head dimension padded up to 64 or 128
+  if (a.p.f16) return d <= 64 ? launch_fwd_d<64, true>(a, causal, st) : launch_fwd_d<128, true>(a, causal, st);
+  return d <= 64 ? launch_fwd_d<64, false>(a, causal, st) : launch_fwd_d<128, false>(a, causal, st);
 }
 
 }  // namespace fa

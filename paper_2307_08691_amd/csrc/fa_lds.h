@@ -61,9 +61,14 @@ __device__ __forceinline__ void dma16_uniform(const void* gbase, unsigned voff, 
 // swizzled LDS tile, 16 bytes per lane, without passing through registers. Each
 // wavefront instruction fills 1 KiB of consecutive LDS; the swizzle is applied by
 // choosing which global chunk each lane fetches.
-template <int D, int NROWS, int NW>
+//
+// PAD: the rows in memory hold only `nchunk` < D / 8 chunks (a head dimension below the
+// tile width D). Lanes whose chunk lies past the row end copy nothing; the kernel zeroes
+// the whole LDS block once before its first copy, and because a given LDS position always
+// receives the same chunk index those positions stay zero for every later tile.
+template <int D, int NROWS, int NW, bool PAD = false>
 __device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase, long gstride, int row_first,
-                                                int row_last, int wave, int lane) {
+                                                int row_last, int wave, int lane, int nchunk = D / 8) {
   constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI;
   static_assert(NI % NW == 0, "tile must divide over the wavefronts");
 #pragma unroll
@@ -73,8 +78,16 @@ __device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase,
     const int c = (lane % CPR) ^ swz<ROWB>(r);
     int grow = row_first + r;
     grow = grow < row_last ? grow : row_last;
-    dma16(gbase + (long)grow * gstride + 8 * c, tile + rb * ROWB);
+    if (!PAD || c < nchunk) dma16(gbase + (long)grow * gstride + 8 * c, tile + rb * ROWB);
   }
+}
+
+// Zero an LDS block (all threads of the workgroup), then a barrier: PAD kernels call this
+// before their first copy.
+template <int NTHREADS>
+__device__ __forceinline__ void lds_zero(char* smem, int bytes) {
+  for (int i = threadIdx.x * 16; i < bytes; i += NTHREADS * 16) *(u32x4*)(smem + i) = (u32x4){0, 0, 0, 0};
+  __syncthreads();
 }
 
 __device__ __forceinline__ bf16x8 lds_b128(const char* smem, int off) { return *(const bf16x8*)(smem + off); }
@@ -88,23 +101,29 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const char* smem, int off_lo, int 
 // of an interior tile are computed once (TileLoader::init) and every tile then costs one
 // scalar base-address update plus the load instructions. Tiles that reach past `row_last`
 // take the clamping path above.
-template <int D, int NROWS, int NW>
+template <int D, int NROWS, int NW, bool PAD = false>
 struct TileLoader {
   static constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI, PER = NI / NW;
   static_assert(NI % NW == 0, "tile must divide over the wavefronts");
   unsigned voff[PER];  // byte offset of this lane's chunk from the tile's first row
-  __device__ __forceinline__ void init(long gstride, int wave, int lane) {
+  unsigned on;         // PAD: bit u set when copy u of this lane fetches a chunk that exists
+  int nchunk;
+  __device__ __forceinline__ void init(long gstride, int wave, int lane, int nchunk_ = D / 8) {
+    on = 0;
+    nchunk = nchunk_;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
       const int r = (wave + NW * u) * RPI + lane / CPR;
       const int c = (lane % CPR) ^ swz<ROWB>(r);
       voff[u] = (unsigned)(r * gstride + 8 * c) * 2u;
+      if (c < nchunk_) on |= 1u << u;
     }
   }
   // an interior tile whose first row starts at `first_row` (wave-uniform)
   __device__ __forceinline__ void load_at(char* tile, const __bf16* first_row, int wave) const {
 #pragma unroll
-    for (int u = 0; u < PER; ++u) dma16_uniform(first_row, voff[u], tile + (wave + NW * u) * RPI * ROWB);
+    for (int u = 0; u < PER; ++u)
+      if (!PAD || ((on >> u) & 1)) dma16_uniform(first_row, voff[u], tile + (wave + NW * u) * RPI * ROWB);
   }
   __device__ __forceinline__ void load(char* tile, const __bf16* gbase, long gstride, int row_first, int row_last,
                                        int wave, int lane) const {
@@ -112,9 +131,9 @@ struct TileLoader {
       const char* base = (const char*)(gbase + (long)row_first * gstride);  // wave-uniform
 #pragma unroll
       for (int u = 0; u < PER; ++u)
-        dma16_uniform(base, voff[u], tile + (wave + NW * u) * RPI * ROWB);
+        if (!PAD || ((on >> u) & 1)) dma16_uniform(base, voff[u], tile + (wave + NW * u) * RPI * ROWB);
     } else {
-      tile_load_async<D, NROWS, NW>(tile, gbase, gstride, row_first, row_last, wave, lane);
+      tile_load_async<D, NROWS, NW, PAD>(tile, gbase, gstride, row_first, row_last, wave, lane, nchunk);
     }
   }
 };

@@ -185,6 +185,9 @@ CONFIGS = {
     # half precision elements, the shape of d128_n8k_causal
     "f16_d128_n8k_causal": dict(kind="cross", B=2, Nq=8192, Nk=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1010,
                                 dtype="f16"),
+    # head dimensions that the kernels pad on chip, 16k tokens and about 2048 hidden units
+    "d96_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=20, Hkv=20, d=96, causal=True, seed=1011),
+    "d32_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=64, Hkv=64, d=32, causal=True, seed=1012),
 }
 
 

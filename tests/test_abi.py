@@ -68,7 +68,8 @@ def test_fwd_rejects_bad_arguments():
     assert fwd(scale=-1.0) == binding.FA_ERR_SHAPE
     assert fwd(scale=float("nan")) == binding.FA_ERR_SHAPE
     assert fwd(scale=float("inf")) == binding.FA_ERR_SHAPE
-    assert fwd(d=96) == binding.FA_ERR_UNSUPPORTED
+    assert fwd(d=100) == binding.FA_ERR_UNSUPPORTED  # not a multiple of 8
+    assert fwd(d=136) == binding.FA_ERR_UNSUPPORTED
     assert fwd(d=256) == binding.FA_ERR_UNSUPPORTED
     assert fwd(K=P + 2) == binding.FA_ERR_ALIGN
     assert fwd(O=P + 8) == binding.FA_ERR_ALIGN
@@ -81,7 +82,7 @@ def test_bwd_rejects_bad_arguments():
         assert bwd(ptrs) == binding.FA_ERR_NULL
     assert bwd(ws=0) == binding.FA_ERR_NULL
     assert bwd(Hq=4, Hkv=3) == binding.FA_ERR_SHAPE
-    assert bwd(d=32) == binding.FA_ERR_UNSUPPORTED
+    assert bwd(d=36) == binding.FA_ERR_UNSUPPORTED
     ptrs = [P] * 9
     ptrs[6] = P + 4
     assert bwd(ptrs) == binding.FA_ERR_ALIGN
@@ -108,7 +109,7 @@ def test_varlen_rejects_bad_arguments():
     assert vf(mx=2000) == binding.FA_ERR_SHAPE      # longest sequence longer than the whole batch
     assert vf(mx=100) == binding.FA_ERR_SHAPE       # 4 sequences of at most 100 cannot hold 1000 tokens
     assert vf(Hq=5) == binding.FA_ERR_SHAPE
-    assert vf(d=80) == binding.FA_ERR_UNSUPPORTED
+    assert vf(d=84) == binding.FA_ERR_UNSUPPORTED
 
     def vb(ws_bytes=1 << 30, mx=400):
         return binding.fa_varlen_bwd_raw(*([P] * 9), P, ws_bytes, P, 4, 1000, mx, 4, 2, 128, 0.1, 1, 0)
@@ -125,7 +126,7 @@ def test_two_length_entry_points_reject_bad_arguments():
     assert cross(Nq=0) == binding.FA_ERR_SHAPE
     assert cross(Nk=0) == binding.FA_ERR_SHAPE
     assert cross(Nq=129, Nk=128, causal=1) == binding.FA_ERR_SHAPE  # a query row without keys
-    assert cross(d=96) == binding.FA_ERR_UNSUPPORTED
+    assert cross(d=192) == binding.FA_ERR_UNSUPPORTED
     assert cross(Q=P + 2) == binding.FA_ERR_ALIGN
     assert cross(Hq=3) == binding.FA_ERR_SHAPE
     ptrs = [P] * 9
@@ -148,7 +149,7 @@ def test_dropout_entry_points_reject_bad_arguments():
     assert run(p_drop=-0.1) == binding.FA_ERR_SHAPE
     assert run(p_drop=float("nan")) == binding.FA_ERR_SHAPE
     assert run(Nq=129, causal=1) == binding.FA_ERR_SHAPE
-    assert run(d=32) == binding.FA_ERR_UNSUPPORTED
+    assert run(d=32) == binding.FA_ERR_UNSUPPORTED  # dropout: the two tile widths only
     ptrs = [P] * 9
     assert binding.fa_dropout_bwd_raw(*ptrs, P, 0, 1, 2, 2, 8, 128, 64, 0.125, 0, 0.1, 99, 0) == binding.FA_ERR_WORKSPACE
     assert binding.fa_dropout_bwd_raw(*ptrs, P, 1 << 20, 1, 2, 2, 8, 128, 64, 0.125, 0, 1.5, 99, 0) == binding.FA_ERR_SHAPE
@@ -161,7 +162,7 @@ def test_ragged_two_length_entry_points_reject_bad_arguments():
     assert run(cu_k=0) == binding.FA_ERR_NULL
     assert run(mq=4) == binding.FA_ERR_SHAPE   # two sequences of at most 4 rows cannot hold 10
     assert run(mk=101) == binding.FA_ERR_SHAPE
-    assert run(d=80) == binding.FA_ERR_UNSUPPORTED
+    assert run(d=4) == binding.FA_ERR_UNSUPPORTED
     ptrs = [P] * 9
     assert binding.fa_varlen_cross_bwd_raw(*ptrs, P, 16, P, P, 2, 10, 100, 8, 60, 2, 2, 64, 0.125, 1, 0) == binding.FA_ERR_WORKSPACE
 
@@ -176,6 +177,7 @@ def test_split_key_entry_point_rejects_bad_arguments():
     assert run(Nq=1001) == binding.FA_ERR_SHAPE  # causal, more queries than keys
     assert run(ws=P + 4) == binding.FA_ERR_ALIGN
     assert run(d=256) == binding.FA_ERR_UNSUPPORTED
+    assert run(d=96) == binding.FA_ERR_UNSUPPORTED  # split keys: the two tile widths only
     need = binding.fa_splitkv_fwd_workspace_bytes(1, 4, 1, 128, 4)
     assert need == 4 * 1 * 1 * 4 * 129 * 4 + (-(4 * 4 * 129 * 4)) % 256
     assert run(ws_bytes=need - 1) == binding.FA_ERR_WORKSPACE
