@@ -49,6 +49,16 @@ Readings taken where the text is silent or inconsistent:
     key, kept when the byte is >= round(256 p). The drop probability is
     therefore a multiple of 1/256.
 
+  * elementwise mask on S (the same footnote; no algorithm is given): a tensor M
+    is ADDED to the scaled scores, S = scale * Q K^T + M, before the causal mask
+    and the softmax. Entries of M are finite or -inf; -inf removes an entry
+    (a boolean mask is M in {0, -inf}). M is a constant of the computation: it
+    receives no gradient, and dQ, dK, dV follow from the same equations with
+    the P of the masked scores. A row whose entries are all -inf has no
+    softmax; reading: P = 0 on that row, hence O = 0, L = -inf, and the row
+    contributes nothing to any gradient. M is [Bm, Hm, Nq, Nk] with Bm in
+    {1, B} and Hm in {1, Hq} (size 1 = shared).
+
 Layouts: dense Q,O,dO,dQ [B, Nq, Hq, d]; K,V,dK,dV [B, Nk, Hkv, d]; L [B, Hq, Nq]
 (Nq = Nk = N for self-attention).
 Packed: Q.. [T, Hq, d]; K.. [T, Hkv, d]; L [Hq, T].
@@ -336,6 +346,76 @@ def attention_backward_dropout(Q, K, V, dO, scale, causal, p_drop, seed):
             keep = dropout_keep(seed, b * Hq + h, N, K.shape[1], t)
             dq, dk, dv = head_backward_dropout(Q[b, :, h, :], K[b, :, g, :], V[b, :, g, :], dO[b, :, h, :],
                                                scale, causal, keep, t)
+            dQ[b, :, h, :] = dq
+            dK[b, :, g, :] += dk
+            dV[b, :, g, :] += dv
+    return dQ, dK, dV
+
+
+# ---------------------------------------------------------------------------
+# Elementwise mask added to S (footnote of section 2.2; reading in the header)
+# ---------------------------------------------------------------------------
+
+def softmax_rows_masked(s):
+    """softmax_rows for scores that may hold whole rows of -inf: such a row has
+    P = 0 and L = -inf; every other row is the ordinary softmax."""
+    m = np.max(s, axis=1, keepdims=True)
+    dead = np.isneginf(m)
+    e = np.exp(s - np.where(dead, 0.0, m))  # dead rows: exp(-inf) = 0 everywhere
+    l = np.sum(e, axis=1, keepdims=True)
+    p = e / np.where(dead, 1.0, l)
+    lse = np.where(dead, -np.inf, m + np.log(np.where(dead, 1.0, l)))
+    return p, lse[:, 0]
+
+
+def head_forward_masked(q, k, v, mask, scale, causal):
+    """One head with S = scale * Q K^T + mask (then the causal mask): O, L, P."""
+    p, lse = softmax_rows_masked(scores(q, k, scale, causal) + mask)
+    return p @ v, lse, p
+
+
+def head_backward_masked(q, k, v, mask, do, scale, causal):
+    """One head: dQ, dK, dV of section 2.2 / Algorithm 2 with the P of the masked scores."""
+    o, _, p = head_forward_masked(q, k, v, mask, scale, causal)
+    dv = p.T @ do
+    dp = do @ v.T
+    big_d = np.sum(do * o, axis=1, keepdims=True)
+    ds = p * (dp - big_d)
+    return scale * (ds @ k), scale * (ds.T @ q), dv
+
+
+def _mask_of(M, b, h):
+    return M[b if M.shape[0] > 1 else 0, h if M.shape[1] > 1 else 0]
+
+
+def attention_forward_masked(Q, K, V, M, scale, causal):
+    """Dense batch forward with an additive mask M [Bm, Hm, Nq, Nk] (Bm in {1, B}, Hm in {1, Hq})."""
+    B, Nq, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    O = np.empty((B, Nq, Hq, d), dtype=np.float64)
+    L = np.empty((B, Hq, Nq), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            o, lse, _ = head_forward_masked(Q[b, :, h, :], K[b, :, g, :], V[b, :, g, :], _mask_of(M, b, h),
+                                            scale, causal)
+            O[b, :, h, :] = o
+            L[b, h, :] = lse
+    return O, L
+
+
+def attention_backward_masked(Q, K, V, M, dO, scale, causal):
+    """Dense batch backward with an additive mask: dQ, dK, dV (the mask receives no gradient)."""
+    B, Nq, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    dQ = np.zeros(Q.shape, dtype=np.float64)
+    dK = np.zeros(K.shape, dtype=np.float64)
+    dV = np.zeros(V.shape, dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            dq, dk, dv = head_backward_masked(Q[b, :, h, :], K[b, :, g, :], V[b, :, g, :], _mask_of(M, b, h),
+                                              dO[b, :, h, :], scale, causal)
             dQ[b, :, h, :] = dq
             dK[b, :, g, :] += dk
             dV[b, :, g, :] += dv

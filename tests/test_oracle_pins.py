@@ -692,3 +692,167 @@ def test_sampled_backward_helpers_are_restrictions_of_the_full_backward(nq, nk, 
     gk, gv = orc.cols_backward_dkdv(q, k[cols], v[cols], cols, nk, do, L, D, 0.55, causal)
     np.testing.assert_allclose(gk, dk[cols], rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(gv, dv[cols], rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# elementwise mask added to S (footnote of section 2.2)
+# ----------------------------------------------------------------------------
+
+def brute_forward_masked(q, k, v, mask, scale, causal):
+    """Scalar loops from the definition: weights exp(scale q.k + mask) over the entries that are
+    neither removed by the causal rule nor by a -inf in the mask; a row with none is all zero."""
+    n, nk, d = len(q), len(k), len(q[0])
+    O = [[0.0] * d for _ in range(n)]
+    L = [-math.inf] * n
+    for r in range(n):
+        cols = [c for c in (range(r + nk - n + 1) if causal else range(nk)) if mask[r][c] != -math.inf]
+        if not cols:
+            continue
+        w = {c: math.exp(scale * sum(q[r][t] * k[c][t] for t in range(d)) + mask[r][c]) for c in cols}
+        z = sum(w.values())
+        L[r] = math.log(z)
+        for t in range(d):
+            O[r][t] = sum(w[c] * v[c][t] for c in cols) / z
+    return O, L
+
+
+def some_mask(seed, nq, nk, dead_row=None):
+    g = np.random.default_rng(seed)
+    m = g.standard_normal((nq, nk)) * 2.0
+    m[g.random((nq, nk)) < 0.3] = -np.inf
+    m[:, 0] = np.where(np.isneginf(m[:, 0]), 0.5, m[:, 0])  # keep one entry per row (also under the causal rule)
+    if dead_row is not None:
+        m[dead_row, :] = -np.inf
+    return m
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nq,nk,dead", [(5, 5, None), (3, 8, None), (6, 9, 2), (1, 4, 0)])
+def test_masked_forward_matches_scalar_brute_force(nq, nk, dead, causal):
+    d = 3
+    q, k, v = rnd(200, nq, d), rnd(201, nk, d), rnd(202, nk, d)
+    m = some_mask(203, nq, nk, dead)
+    o, lse, p = orc.head_forward_masked(q, k, v, m, 0.41, causal)
+    bo, bl = brute_forward_masked(q.tolist(), k.tolist(), v.tolist(), m.tolist(), 0.41, causal)
+    np.testing.assert_allclose(o, np.asarray(bo), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, np.asarray(bl), rtol=1e-12, atol=1e-13)
+    if dead is not None:
+        assert not p[dead].any() and not o[dead].any() and lse[dead] == -np.inf
+    assert np.all(np.isfinite(o)) and np.all(np.isfinite(p))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_zero_mask_is_plain_attention_and_the_causal_rule_is_a_mask(causal):
+    nq, nk, d = 5, 8, 4
+    q, k, v, do = rnd(210, nq, d), rnd(211, nk, d), rnd(212, nk, d), rnd(213, nq, d)
+    o, lse, _ = orc.head_forward(q, k, v, 0.3, causal)
+    om, lm, _ = orc.head_forward_masked(q, k, v, np.zeros((nq, nk)), 0.3, causal)
+    np.testing.assert_array_equal(om, o)
+    np.testing.assert_array_equal(lm, lse)
+    for a, b in zip(orc.head_backward_masked(q, k, v, np.zeros((nq, nk)), do, 0.3, causal),
+                    orc.head_backward(q, k, v, do, 0.3, causal)):
+        np.testing.assert_array_equal(a, b)
+    # the causal rule of section 3.1.1 written as a mask of 0 / -inf, with the flag off
+    tri = np.where(np.arange(nk)[None, :] > np.arange(nq)[:, None] + nk - nq, -np.inf, 0.0)
+    oc, lc, _ = orc.head_forward(q, k, v, 0.3, True)
+    ot, lt, _ = orc.head_forward_masked(q, k, v, tri, 0.3, False)
+    np.testing.assert_allclose(ot, oc, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(lt, lc, rtol=1e-13, atol=1e-14)
+
+
+def test_a_boolean_mask_is_attention_over_the_selected_keys():
+    """Removing keys with -inf equals plain attention on the remaining keys; their dK, dV rows are
+    those of the smaller problem and the removed keys get exactly zero."""
+    nq, nk, d = 6, 10, 4
+    q, k, v, do = rnd(220, nq, d), rnd(221, nk, d), rnd(222, nk, d), rnd(223, nq, d)
+    sel = np.asarray([0, 2, 3, 7, 9])
+    m = np.full((nq, nk), -np.inf)
+    m[:, sel] = 0.0
+    o, lse, _ = orc.head_forward_masked(q, k, v, m, 0.5, False)
+    o2, lse2, _ = orc.head_forward(q, k[sel], v[sel], 0.5, False)
+    np.testing.assert_allclose(o, o2, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(lse, lse2, rtol=1e-13, atol=1e-14)
+    dq, dk, dv = orc.head_backward_masked(q, k, v, m, do, 0.5, False)
+    dq2, dk2, dv2 = orc.head_backward(q, k[sel], v[sel], do, 0.5, False)
+    np.testing.assert_allclose(dq, dq2, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dk[sel], dk2, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dv[sel], dv2, rtol=1e-12, atol=1e-13)
+    gone = np.setdiff1d(np.arange(nk), sel)
+    assert not dk[gone].any() and not dv[gone].any()
+
+
+def test_a_row_constant_in_the_mask_shifts_L_and_nothing_else():
+    nq, nk, d = 4, 7, 3
+    q, k, v, do = rnd(230, nq, d), rnd(231, nk, d), rnd(232, nk, d), rnd(233, nq, d)
+    m = some_mask(234, nq, nk)
+    c = np.asarray([0.7, -1.3, 2.0, 0.0])[:, None]
+    o, lse, _ = orc.head_forward_masked(q, k, v, m, 0.6, False)
+    o2, lse2, _ = orc.head_forward_masked(q, k, v, m + c, 0.6, False)
+    np.testing.assert_allclose(o2, o, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse2, lse + c[:, 0], rtol=1e-12, atol=1e-13)
+    for a, b in zip(orc.head_backward_masked(q, k, v, m + c, do, 0.6, False),
+                    orc.head_backward_masked(q, k, v, m, do, 0.6, False)):
+        np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-12)
+
+
+def test_a_mask_is_a_bias_on_the_scores_not_on_the_probabilities():
+    """Two keys with equal scores: the bias b on one of them gives weights e^b / (1 + e^b) and
+    1 / (1 + e^b) - a planted mistake (mask multiplied in, or added after the softmax) fails this."""
+    q = np.zeros((1, 2))
+    k = np.zeros((2, 2))
+    v = np.asarray([[1.0, 0.0], [0.0, 1.0]])
+    b = 1.25
+    o, lse, _ = orc.head_forward_masked(q, k, v, np.asarray([[b, 0.0]]), 0.9, False)
+    w = math.exp(b) / (1.0 + math.exp(b))
+    np.testing.assert_allclose(o, [[w, 1.0 - w]], rtol=1e-14)
+    np.testing.assert_allclose(lse, [math.log(1.0 + math.exp(b))], rtol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_masked_backward_matches_finite_differences(causal):
+    nq, nk, d, scale = 4, 6, 3, 0.45
+    q, k, v, do = rnd(240, nq, d), rnd(241, nk, d), rnd(242, nk, d), rnd(243, nq, d)
+    m = some_mask(244, nq, nk, dead_row=None if causal else 1)
+
+    def loss(qq, kk, vv):
+        O, _ = brute_forward_masked(qq.tolist(), kk.tolist(), vv.tolist(), m.tolist(), scale, causal)
+        return float(np.sum(np.asarray(O) * do))
+
+    got = orc.head_backward_masked(q, k, v, m, do, scale, causal)
+    arrs = [q.copy(), k.copy(), v.copy()]
+    for which in range(3):
+        x = arrs[which]
+        ref = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            old = x[idx]
+            x[idx] = old + 1e-5
+            fp = loss(*arrs)
+            x[idx] = old - 1e-5
+            fm = loss(*arrs)
+            x[idx] = old
+            ref[idx] = (fp - fm) / 2e-5
+        err = np.max(np.abs(got[which] - ref)) / max(1.0, np.max(np.abs(ref)))
+        assert err < 1e-6, (which, err)
+    if not causal:
+        assert not got[0][1].any()  # the row without any key has no gradient
+
+
+def test_masked_batch_wrapper_shares_masks_over_batch_and_heads():
+    B, Nq, Nk, Hq, Hkv, d = 2, 3, 5, 4, 2, 2
+    Q, K, V, dO = rnd(250, B, Nq, Hq, d), rnd(251, B, Nk, Hkv, d), rnd(252, B, Nk, Hkv, d), rnd(253, B, Nq, Hq, d)
+    for shape in ((1, 1), (B, 1), (1, Hq), (B, Hq)):
+        M = np.stack([np.stack([some_mask(260 + 10 * b + h, Nq, Nk) for h in range(shape[1])]) for b in range(shape[0])])
+        O, L = orc.attention_forward_masked(Q, K, V, M, 0.7, False)
+        dQ, dK, dV = orc.attention_backward_masked(Q, K, V, M, dO, 0.7, False)
+        for b in range(B):
+            dk_sum = np.zeros((Nk, Hkv, d))
+            for h in range(Hq):
+                m = M[b if shape[0] > 1 else 0, h if shape[1] > 1 else 0]
+                o, lse, _ = orc.head_forward_masked(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2], m, 0.7, False)
+                np.testing.assert_array_equal(O[b, :, h], o)
+                np.testing.assert_array_equal(L[b, h], lse)
+                dq, dk, dv = orc.head_backward_masked(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2], m, dO[b, :, h],
+                                                      0.7, False)
+                np.testing.assert_array_equal(dQ[b, :, h], dq)
+                dk_sum[:, h // 2] += dk
+            np.testing.assert_allclose(dK[b], dk_sum, rtol=1e-13, atol=1e-14)
