@@ -198,6 +198,37 @@ int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, c
                    float p_drop, uint64_t seed, void* stream);
 
 /*
+ * Elementwise mask on S (section 2.2, the footnote to the definition of S, P, O, which names
+ * masking without giving an algorithm). Reading taken here: a tensor M is ADDED to the scaled
+ * scores, S = scale * Q K^T + M, before the causal rule (if any) and the softmax; the rest of
+ * Algorithms 1 and 2 is unchanged, with P = exp(S - L) taken from these scores. Entries of M
+ * are finite or -inf: -inf removes an entry (a boolean mask is M in {0, -inf}), finite values
+ * act as a bias on the scores (relative-position biases and the like). +inf and NaN are not
+ * allowed (not checked). A query row left without any entry gets O = 0 and L = -inf in the
+ * forward pass and contributes nothing to dQ, dK, dV. M is an input of both passes and
+ * receives no gradient.
+ *
+ * M (device, bfloat16, 16-byte aligned, never written) holds element (b, h, r, c) at
+ *     M[b * mask_batch_stride + h * mask_head_stride + r * mask_row_stride + c]
+ * (strides in elements). mask_batch_stride = 0 shares one mask over the sequences,
+ * mask_head_stride = 0 over the query heads. All three strides are multiples of 8 and
+ * mask_row_stride >= Nk rounded up to a multiple of 8 (rows are padded in memory; the pad is
+ * read but never used), otherwise FA_ERR_SHAPE. Layouts, lengths and the causal rule as for
+ * fa_cross_fwd / fa_cross_bwd; d in {64, 128}; bfloat16 elements; workspace as for
+ * fa_cross_bwd (fa_cross_bwd_workspace_bytes).
+ */
+int fa_mask_fwd(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE,
+                int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                void* stream);
+int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, const void* O,
+                const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                void* workspace, size_t workspace_bytes,
+                int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                void* stream);
+
+/*
  * Two lengths in the packed ragged layout: sequence s owns query rows
  * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
  * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].

@@ -48,6 +48,9 @@ SIGNATURES = {
     "fa_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 +
                        [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_mask_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
+    "fa_mask_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
+                    [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
@@ -164,6 +167,17 @@ def fa_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv
                        seed, stream=0) -> int:
     return load().fa_dropout_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
                                  int(causal), p_drop, seed, stream)
+
+
+def fa_mask_fwd_raw(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs, mask_hs, mask_rs, stream=0) -> int:
+    return load().fa_mask_fwd(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), mask_bs, mask_hs, mask_rs,
+                              stream)
+
+
+def fa_mask_bwd_raw(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs,
+                    mask_hs, mask_rs, stream=0) -> int:
+    return load().fa_mask_bwd(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                              int(causal), mask_bs, mask_hs, mask_rs, stream)
 
 
 def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
@@ -381,6 +395,65 @@ def fa_dropout_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, p_drop: floa
     _check(fa_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                               _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
                               scale, causal, p_drop, seed, _stream()))
+    return dQ, dK, dV
+
+
+def mask_buffer(Bm: int, Hm: int, Nq: int, Nk: int, device="cuda"):
+    """An elementwise mask [Bm, Hm, Nq, Nk] (bf16, zeros) whose rows are padded in memory to a
+    multiple of 8 elements, as fa_mask_fwd / fa_mask_bwd require; Bm, Hm = 1 shares the mask."""
+    import torch
+    rs = (Nk + 7) // 8 * 8
+    return torch.zeros((Bm, Hm, Nq, rs), dtype=torch.bfloat16, device=device)[..., :Nk]
+
+
+def _mask_strides(M, B, Hq, Nq, Nk):
+    import torch
+    _need_dtype = torch.bfloat16
+    if not M.is_cuda or M.dtype != _need_dtype:
+        raise ValueError("M must be a CUDA bfloat16 tensor")
+    if M.dim() != 4 or M.shape[0] not in (1, B) or M.shape[1] not in (1, Hq) or tuple(M.shape[2:]) != (Nq, Nk):
+        raise ValueError("M must be [1 or B, 1 or Hq, Nq, Nk]")
+    if M.stride(3) != 1:
+        raise ValueError("the key dimension of M must be contiguous")
+    return (M.stride(0) if M.shape[0] > 1 else 0, M.stride(1) if M.shape[1] > 1 else 0, M.stride(2))
+
+
+def fa_mask_fwd(Q, K, V, M, scale: float, causal: bool, O=None, LSE=None):
+    """Forward with the mask M added to the scaled scores. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16; M as
+    made by mask_buffer (entries finite or -inf)."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    bs, hs, rs = _mask_strides(M, B, Hq, Nq, Nk)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
+    _check(fa_mask_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                           bs, hs, rs, _stream()))
+    return O, LSE
+
+
+def fa_mask_bwd(Q, K, V, M, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
+    """Backward with the mask of fa_mask_fwd; M receives no gradient."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    _need(LSE, "LSE", torch.float32)
+    B, Nq, Hq, d = Q.shape
+    Nk, Hkv = K.shape[1], K.shape[2]
+    bs, hs, rs = _mask_strides(M, B, Hq, Nq, Nk)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    if workspace is None:
+        workspace = torch.empty(fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d), dtype=torch.uint8,
+                                device=Q.device)
+    _check(fa_mask_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                           _ptr(dV), _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk,
+                           d, scale, causal, bs, hs, rs, _stream()))
     return dQ, dK, dV
 
 

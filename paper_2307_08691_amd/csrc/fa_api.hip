@@ -30,6 +30,8 @@ fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int
   p.drop_thr = 0;
   p.drop_seed = 0;
   p.drop_rp = 1.f;
+  p.mask = nullptr;
+  p.mask_bs = p.mask_hs = p.mask_rs = 0;
   p.cu_seqlens = cu;
   p.cu_seqlens_k = cu_k;
   p.nseq = nseq;
@@ -107,7 +109,7 @@ const char* fa_status_string(int status) {
     case FA_ERR_NULL: return "a required pointer is NULL";
     case FA_ERR_SHAPE: return "invalid shape, head grouping, scale or ragged description";
     case FA_ERR_UNSUPPORTED:
-      return "unsupported head dimension (multiples of 8 up to 128; dropout and split keys: 64 and 128 only)";
+      return "unsupported head dimension (multiples of 8 up to 128; dropout, mask and split keys: 64 and 128 only)";
     case FA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
     case FA_ERR_WORKSPACE: return "workspace too small";
     case FA_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
@@ -305,6 +307,76 @@ int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, c
   fa::BwdArgs a;
   a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
   if (int e = set_dropout(a.p, p_drop, seed)) return e;
+  a.Q = (const __bf16*)Q;
+  a.K = (const __bf16*)K;
+  a.V = (const __bf16*)V;
+  a.O = (const __bf16*)O;
+  a.dO = (const __bf16*)dO;
+  a.LSE = LSE;
+  a.dQ = (__bf16*)dQ;
+  a.dK = (__bf16*)dK;
+  a.dV = (__bf16*)dV;
+  a.Dvec = (float*)workspace;
+  hipError_t e = fa::launch_bwd(a, d, causal, 7, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
+// elementwise mask: strides in elements, multiples of 8 (every 16-byte chunk of M aligned)
+static int set_mask(fa::Problem& p, const void* M, int Nk, long long bs, long long hs, long long rs) {
+  if (!M) return FA_ERR_NULL;
+  if (!aligned16(M)) return FA_ERR_ALIGN;
+  if (bs < 0 || hs < 0 || rs < (((long long)Nk + 7) & ~7LL)) return FA_ERR_SHAPE;
+  if (bs % 8 || hs % 8 || rs % 8) return FA_ERR_SHAPE;
+  p.mask = (const __bf16*)M;
+  p.mask_bs = (long)bs;
+  p.mask_hs = (long)hs;
+  p.mask_rs = (long)rs;
+  return FA_OK;
+}
+
+int fa_mask_fwd(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE, int B, int Hq, int Hkv,
+                int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
+                long long mask_head_stride, long long mask_row_stride, void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  fa::FwdArgs a;
+  a.nsplit = 0;
+  a.Opart = a.Lpart = nullptr;
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
+  if (int e = set_mask(a.p, M, Nk, mask_batch_stride, mask_head_stride, mask_row_stride)) return e;
+  a.Q = (const __bf16*)Q;
+  a.K = (const __bf16*)K;
+  a.V = (const __bf16*)V;
+  a.O = (__bf16*)O;
+  a.LSE = LSE;
+  hipError_t e = fa::launch_fwd(a, d, causal, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
+int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, const void* O, const void* dO,
+                const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq,
+                int Hkv, int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
+                long long mask_head_stride, long long mask_row_stride, void* stream) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
+  fa::BwdArgs a;
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
+  if (int e = set_mask(a.p, M, Nk, mask_batch_stride, mask_head_stride, mask_row_stride)) return e;
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;

@@ -91,8 +91,15 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 //
 // PAD: head dimension p.d below the tile width D, rows padded with zeros on chip (see the
 // forward kernel); only the first p.d columns of dK, dV are stored.
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false>
+//
+// MASK: a tensor M is added to the scaled scores (section 2.2, footnote). Here a lane holds one
+// key column and 16 query rows of a tile, and the LDS block is full, so each lane fetches its
+// 16 entries of M straight into registers, one tile ahead: requested at the end of the vector
+// phase before, complete at the wait that ends the matrix phase in between. The operand
+// prefetch distance is halved to make room for them.
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
+  static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   constexpr int BC = 128;               // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
   constexpr int BR = 32 * QTW;          // query rows of one tile
@@ -198,7 +205,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       const int o = (slot * BR + gtid) * 4;
       // L in the exponent's base; rows past the end get L = +inf so that P = exp2(. - inf) = 0.
       // D is stored negated: it is the initial value of the dP accumulator (line 14).
-      *(float*)(smem + LS_OFF + o) = stat_ok ? lraw * kLog2e : INFINITY;
+      // (mask: a row left without keys has L = -inf and, like a row past the end, P = 0)
+      *(float*)(smem + LS_OFF + o) = stat_ok && !(MASK && lraw == -INFINITY) ? lraw * kLog2e : INFINITY;
       *(float*)(smem + DV_OFF + o) = stat_ok ? -draw : 0.f;
     }
   };
@@ -220,7 +228,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         const long si_ = stat_base + (long)c.hq * p.lse_head_stride + (ok ? row : n - 1);
         const float l = a.LSE[si_], dd = a.Dvec[si_];
         const int o = (c.slot * BR + tid - t * BR) * 4;
-        *(float*)(smem + LS_OFF + o) = ok ? l * kLog2e : INFINITY;
+        *(float*)(smem + LS_OFF + o) = ok && !(MASK && l == -INFINITY) ? l * kLog2e : INFINITY;
         *(float*)(smem + DV_OFF + o) = ok ? -dd : 0.f;
       }
       advance(c, 1);
@@ -256,7 +264,31 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // ---- the MFMA work of a tile, as index -> (operand reads, MFMA) maps for mfma_stream_*
   constexpr int NM = QTW * 2 * KS;   // S and dP: 16 MFMAs
   constexpr int NM2 = QTW * 4 * DT;  // dV and dK: 16 MFMAs
-  constexpr int AH = FA_DKDV_AHEAD;
+  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : FA_DKDV_AHEAD;
+  // MASK: this lane's entries of M for the wavefront's next tile (raw bfloat16 bits), row by row
+  uint32_t mraw[MASK ? QTW * 16 : 1];
+  auto issue_mask_loads = [&](const Cursor& c) {
+    if constexpr (MASK) {
+      const int keyc = key < nk ? key : nk - 1;
+      // entry (row, key) of this head's M: a wave-uniform row address plus one per-lane offset
+      const char* m0 = (const char*)(p.mask + s * p.mask_bs + c.hq * p.mask_hs);
+      if ((c.it + 1) * BR <= n) {  // all rows exist
+        unsigned voff = (unsigned)((4 * hh * p.mask_rs + keyc) * 2);
+        asm volatile("" : "+v"(voff));  // (recomputed for every tile instead of held in registers)
+#pragma unroll
+        for (int e = 0; e < QTW * 16; ++e) {
+          const char* rowp = m0 + (long)(c.it * BR + 32 * (e / 16) + acc_row(e % 16, 0)) * p.mask_rs * 2;
+          mraw[e] = *(const unsigned short*)(rowp + voff);
+        }
+      } else {  // the last rows of the sequence: rows past the end repeat row n - 1
+#pragma unroll
+        for (int e = 0; e < QTW * 16; ++e) {
+          const int row = c.it * BR + 32 * (e / 16) + acc_row(e % 16, hh);
+          mraw[e] = *(const unsigned short*)(m0 + ((long)(row < n ? row : n - 1) * p.mask_rs + keyc) * 2);
+        }
+      }
+    }
+  };
   bf16x8 pre[AH];  // first operands of the next M', requested at the end of the vector phase before it
   auto load_m = [&](const Cursor& c, int i) {  // operands of S (even i) and dP (odd i)
     const int tq = i / (2 * KS), k = i % (2 * KS), x = 32 * (k >> 1);
@@ -301,7 +333,12 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       for (int r4 = 0; r4 < 4; ++r4) {
         const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * tq + 8 * r4 + 4 * hh) * 4);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) S[tq][4 * r4 + u] = fast_exp2(__builtin_fmaf(S[tq][4 * r4 + u], c2, -Lv[u]));
+        for (int u = 0; u < 4; ++u) {
+          float sub = -Lv[u];
+          if constexpr (MASK)
+            sub = __builtin_fmaf(__builtin_bit_cast(float, mraw[16 * tq + 4 * r4 + u] << 16), kLog2e, sub);
+          S[tq][4 * r4 + u] = fast_exp2(__builtin_fmaf(S[tq][4 * r4 + u], c2, sub));
+        }
       }
       if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
         asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
@@ -360,6 +397,10 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     wait_vmem();
     touch(lraw);
     touch(draw);
+    if constexpr (MASK) {
+#pragma unroll
+      for (int e = 0; e < QTW * 16; ++e) touch(mraw[e]);
+    }
     if (pending >= 0) {
       commit_stats(pending);
       pending = -1;
@@ -375,6 +416,11 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     }
     if (do_v) {
       phase_v(cur);
+      if (MASK && tau + 2 < T) {  // this wavefront's next tile
+        Cursor nxt = cur;
+        advance(nxt, 2);
+        issue_mask_loads(nxt);
+      }
       mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
     }
     lds_barrier();
@@ -384,6 +430,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   if (grp == 1) lds_barrier();
   // the group's first matrix phase: M only
   const bool have_first = tau < T;
+  if (MASK && have_first) issue_mask_loads(cur);
   if (have_first) {
     __builtin_amdgcn_s_setprio(2);
     mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
@@ -466,14 +513,19 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // structure as the forward kernel: a matrix phase (S^T, dP^T of block j and the dQ^T update
 // with block j - 1) and a vector phase (P and dS of block j), the two wave groups one phase
 // apart, K_j / V_j tiles streaming HBM -> LDS two blocks ahead into a ring of four buffers.
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false>
+// MASK: the tensor added to the scaled scores reaches the wavefronts as in the forward kernel
+// (a private 32 x 64 piece per block, copied HBM -> LDS one vector phase ahead).
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
+  static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
+  constexpr int MASKB = 32 * BC * 2;             // one wavefront's piece of M for one block
+  constexpr int MPW = MASK ? MASKB / 1024 : 0;  // copies per wavefront per block
 
-  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB];
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0)];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -514,7 +566,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     }
   }
   const long stat = s * p.lse_seq_stride + (long)h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + rowc;
-  const float Lq = row < n ? a.LSE[stat] * kLog2e : INFINITY;  // rows past the end: P = 0
+  float Lq = row < n ? a.LSE[stat] * kLog2e : INFINITY;  // rows past the end: P = 0
+  if (MASK && Lq == -INFINITY) Lq = INFINITY;            // a row that the mask left without keys: P = 0
   const float Dq = a.Dvec[stat];
 
   f32x16 dQt[DT];
@@ -538,8 +591,28 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
     loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
   };
+  char* mbuf = smem + RING * BUFB + w * MASKB;
+  const __bf16* Mb = MASK ? p.mask + s * p.mask_bs + h * p.mask_hs : nullptr;
+  const int nk8 = (nk + 7) & ~7;
+  auto issue_mask = [&](int j) {  // see the forward kernel
+    if constexpr (MASK) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      int ln = lane;  // hidden from the optimiser: otherwise it keeps all these addresses in registers across the loop
+      asm volatile("" : "+v"(ln));
+#pragma unroll
+      for (int u = 0; u < MPW; ++u) {
+        const int r = 8 * u + (ln >> 3);
+        const int qr = wrow0 + r < n ? wrow0 + r : n - 1;
+        const int c = (ln & 7) ^ (r & 7);
+        int col = j * BC + 8 * c;
+        col = col < nk8 ? col : 0;
+        dma16(Mb + (long)qr * p.mask_rs + col, mbuf + u * 1024);
+      }
+    }
+  };
   issue_tile(0);
   issue_tile(1);
+  issue_mask(0);
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     touch(Qf[ks]);
@@ -571,7 +644,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
       const int zk = zrow + (j % RING) * BUFB;
       S[0] = S[1] = dP[0] = dP[1] = (f32x16){0};
-      mfma_stream<4 * KS, 4, 1>(
+      mfma_stream<4 * KS, MASK && D == 128 ? 2 : 4, 1>(  // (mask, d = 128: shorter operand prefetch, the registers go to M)
           [&](int i) {
             const int ks = i >> 2, kt = (i >> 1) & 1;
             return lds_b128(smem, (zk ^ (32 * ks)) + 32 * kt * ROWB + (i & 1) * TILEB);
@@ -586,7 +659,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       // ---- dQ_i^T += K_{j-1}^T dS^T (line 15)
       const int kb = ((j - 1) % RING) * BUFB;
       const int zc0 = zcol[0] + kb, zc1 = zcol[1] + kb;
-      mfma_stream<4 * DT, 3, 2>(
+      mfma_stream<4 * DT, MASK && D == 128 ? 2 : 3, 2>(
           [&](int i) {
             const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
             return lds_tr_pair(smem, (zc0 ^ (64 * dt)) + ro, (zc1 ^ (64 * dt)) + ro);
@@ -604,10 +677,27 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
     const int col0 = j * BC;
     const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
+    int zm = lq * (2 * BC) + ((lq & 7) << 4) + 8 * hh;  // mask: chunk k of this lane's row at zm ^ 16 k
+    if constexpr (MASK) {
+      wait_vmem_upto<TPW>();  // this piece of M is older than this phase's tile copies
+      asm volatile("" : "+v"(zm));  // (recomputed every block instead of held in registers)
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
+      if constexpr (MASK) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) S[kt][r] = fast_exp2(__builtin_fmaf(S[kt][r], c2, -Lq));
+        for (int q4 = 0; q4 < 4; ++q4) {  // registers 4 q4 .. 4 q4 + 3: keys col0 + 32 kt + 8 q4 + 4 hh + 0..3
+          const u32x2 mv = *(const u32x2*)(mbuf + (zm ^ (16 * (4 * kt + q4))));
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float mf = __builtin_bit_cast(float, (u & 1) ? (mv[u >> 1] & 0xffff0000u) : (mv[u >> 1] << 16));
+            S[kt][4 * q4 + u] = fast_exp2(__builtin_fmaf(S[kt][4 * q4 + u], c2, __builtin_fmaf(mf, kLog2e, -Lq)));
+          }
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[kt][r] = fast_exp2(__builtin_fmaf(S[kt][r], c2, -Lq));
+      }
       if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
         asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
 #pragma unroll
@@ -637,7 +727,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       lds_barrier();
       issue_tile(j + 2);
       vector_phase(j);
-      wait_vmem_upto<TPW>();
+      issue_mask(j + 1);
+      wait_vmem_upto<TPW + MPW>();
       lds_barrier();
     }
   } else {
@@ -645,11 +736,12 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     lds_barrier();
     for (int j = 0; j <= ncol; ++j) {
       matrix_phase(j);
-      wait_vmem_upto<TPW>();
+      wait_vmem_upto<TPW + MPW>();
       lds_barrier();
       if (j < ncol) {
         issue_tile(j + 3);
         vector_phase(j);
+        issue_mask(j + 1);
         lds_barrier();
       }
     }
@@ -682,7 +774,15 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   if (stages & 2) {
     dim3 grid(grid_size((a.p.Nk + 127) / 128, a.p.Hkv * a.p.nseq));
     bool done = false;
-    if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
+    if constexpr (!F16) {
+      if (a.p.mask) {
+        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, false, false, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        done = true;
+      }
+    }
+    if (done) {
+    } else if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
       if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
       else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
       done = true;
@@ -702,7 +802,15 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   if (stages & 4) {
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
     bool done = false;
-    if (a.p.d != D) {
+    if constexpr (!F16) {
+      if (a.p.mask) {
+        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, false, false, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        done = true;
+      }
+    }
+    if (done) {
+    } else if (a.p.d != D) {
       if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
       else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
       done = true;

@@ -41,6 +41,11 @@ struct Problem {
   uint32_t drop_thr;          // round(256 p), 1 .. 255
   uint32_t drop_seed;         // (seed mod 2^32) xor (seed >> 32) * 0x27D4EB2F
   float drop_rp;              // 1 / (1 - drop_thr / 256)
+  // elementwise mask added to the scaled scores (nullptr: none): bfloat16, finite or -inf,
+  // element (s, h, r, c) at mask[s * mask_bs + h * mask_hs + r * mask_rs + c]; a stride of 0
+  // shares the mask over sequences or heads; mask_rs >= Nk rounded up to 8, a multiple of 8
+  const __bf16* mask;
+  long mask_bs, mask_hs, mask_rs;
 };
 
 struct SeqInfo {

@@ -61,15 +61,27 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return __buil
 // PAD: the head dimension in memory, p.d, is smaller than the tile width D. Rows are padded
 // with zeros on chip (registers for Q, never-written LDS chunks for K and V), which changes
 // no product, and only the first p.d columns of O are stored.
-template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false, bool PAD = false>
+//
+// MASK: a tensor M is added to the scaled scores before the softmax (section 2.2, footnote).
+// Each wavefront copies its own 32 x 64 piece of M for the next block HBM -> LDS at the end
+// of its vector phase (a private 4 KiB buffer, 16-byte chunks XOR-ed with the row so that the
+// 8-byte reads of 32 rows spread over all banks) and adds it, times log2(e), to the scores in
+// the exponent's base at the start of the next one. Entries of -inf remove a score; a row may
+// be left without any, so the running maximum can stay -inf (guards as for SPLIT) and such a
+// row ends with O = 0, L = -inf.
+template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
+  static_assert(!MASK || (!SPLIT && !F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
   constexpr int DT = D / 32;  // 32-row tiles of O^T
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
 
-  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB];
+  constexpr int MASKB = 32 * BC * 2;             // one wavefront's piece of M for one block
+  constexpr int MPW = MASK ? MASKB / 1024 : 0;  // copies per wavefront per block
+
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0)];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -124,7 +136,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   f32x16 O[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) O[dt] = (f32x16){0};
-  float m = -INFINITY;  // running row maximum, raw score units
+  float m = -INFINITY;  // running row maximum, raw score units (mask: scaled scores, M included)
   float l = 0.f;        // this lane's share of the row sum (the two lane halves are added at the end)
 
   // column blocks the workgroup visits: all of them, or (causal) those not entirely above the diagonal
@@ -154,9 +166,32 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
     loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
   };
+  // MASK: this wavefront's rows of M, columns of block j (rows and columns clamped into the
+  // tensor: what lies past the end is never used). Issued unconditionally, once per vector
+  // phase, like the tile copies, so that the waits can count instructions.
+  char* mbuf = smem + RING * BUFB + w * MASKB;
+  const __bf16* Mb = MASK ? p.mask + s * p.mask_bs + h * p.mask_hs : nullptr;
+  const int nk8 = (nk + 7) & ~7;
+  auto issue_mask = [&](int j) {
+    if constexpr (MASK) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the reads of the previous piece have returned
+      int ln = lane;  // hidden from the optimiser: otherwise it keeps all these addresses in registers across the loop
+      asm volatile("" : "+v"(ln));
+#pragma unroll
+      for (int u = 0; u < MPW; ++u) {
+        const int r = 8 * u + (ln >> 3);
+        const int qr = prow0 + r < n ? prow0 + r : n - 1;
+        const int c = (ln & 7) ^ (r & 7);
+        int col = j * BC + 8 * c;
+        col = col < nk8 ? col : 0;
+        dma16(Mb + (long)qr * p.mask_rs + col, mbuf + u * 1024);
+      }
+    }
+  };
   {  // blocks 0 and 1: both tiles, split over the two groups as above
     issue_tile(jb);
     issue_tile(jb + 1);
+    issue_mask(jb);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
     wait_vmem();
@@ -172,6 +207,10 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
 
   const float c2 = p.scale_log2e;
+  constexpr bool GUARD = SPLIT || MASK;  // a row may have seen no key yet
+  // MASK: the scores are scaled when M is added (one FMA); from there on the softmax works on
+  // scaled scores and the factor that remains is the change of base
+  const float cs = MASK ? kLog2e : c2;
   const int wrow_last = wq_last + off;  // position of the wavefront's last query among the keys
   const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;  // last visible column of this lane's row
 
@@ -212,6 +251,22 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
   auto vector_phase = [&](int j) {
     if (!wave_on || j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
     const int col0 = j * BC;
+    if constexpr (MASK) {
+      wait_vmem_upto<TPW>();  // the copies of this piece of M are older than this phase's tile copies
+      int zm = lq * (2 * BC) + ((lq & 7) << 4) + 8 * hh;  // chunk k of this lane's row: zm ^ 16 k
+      asm volatile("" : "+v"(zm));                        // (recomputed every block instead of held in registers)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {  // registers 4 q4 .. 4 q4 + 3: keys col0 + 32 kt + 8 q4 + 4 hh + 0..3
+          const u32x2 mv = *(const u32x2*)(mbuf + (zm ^ (16 * (4 * kt + q4))));
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float mf = __builtin_bit_cast(float, (u & 1) ? (mv[u >> 1] & 0xffff0000u) : (mv[u >> 1] << 16));
+            S[kt][4 * q4 + u] = __builtin_fmaf(S[kt][4 * q4 + u], p.scale, mf);
+          }
+        }
+    }
     // ---- mask: causal entries above the diagonal and columns past the end
     const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
     if (need_mask) {
@@ -237,9 +292,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // not for the result: O and l are relative to the same reference m whatever it is. The
     // reference is therefore advanced only when some row's maximum outgrew it by a factor
     // 2^FA_FWD_LAZY_LOG2, which after the first few blocks is rare.
-    if (__builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)FA_FWD_LAZY_LOG2) != 0) {
-      // (split: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
-      const float alpha = SPLIT && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * c2);
+    if (__builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)FA_FWD_LAZY_LOG2) != 0) {
+      // (split, mask: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
+      const float alpha = GUARD && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * cs);
       l *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -248,7 +303,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
       m = m_new;
     }
     // (split: a row may have seen no key yet; its scores are all -inf and must give P = 0)
-    const float mc = (SPLIT && m == -INFINITY ? 0.f : m) * c2;
+    const float mc = (GUARD && m == -INFINITY ? 0.f : m) * cs;
     // the row sum is taken from the float32 exponentials, not from their bf16 roundings:
     // rows that see only a few keys would otherwise miss the 1e-3 bound on L
     float rs0 = 0.f, rs1 = 0.f;
@@ -256,8 +311,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], c2, -mc));
-        const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -mc));
+        const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], cs, -mc));
+        const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], cs, -mc));
         S[kt][r] = e0;
         S[kt][r + 1] = e1;
         rs0 += e0;
@@ -288,7 +343,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
       lds_barrier();
       issue_tile(j + 2);
       vector_phase(j);
-      wait_vmem_upto<TPW>();
+      issue_mask(j + 1);
+      wait_vmem_upto<TPW + MPW>();
       lds_barrier();
     }
   } else {
@@ -296,11 +352,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     lds_barrier();
     for (int j = jb; j <= ncol; ++j) {
       matrix_phase(j);
-      wait_vmem_upto<TPW>();
+      wait_vmem_upto<TPW + MPW>();
       lds_barrier();
       if (j < ncol) {
         issue_tile(j + 3);
         vector_phase(j);
+        issue_mask(j + 1);
         lds_barrier();
       }
     }
@@ -328,7 +385,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     }
     return;
   }
-  const float inv = (DROPOUT ? p.drop_rp : 1.0f) / lsum;
+  // (mask: a row without any key ends with l = 0: O = 0, L = -inf)
+  const float inv = MASK && !(lsum > 0.f) ? 0.f : (DROPOUT ? p.drop_rp : 1.0f) / lsum;
   if (row < n) {
     __bf16* op = a.O + ((si.tok0 + row) * p.Hq + h) * dh + 4 * hh;
 #pragma unroll
@@ -342,7 +400,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
       }
     if (hh == 0)
       a.LSE[s * p.lse_seq_stride + h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + row] =
-          m * p.scale + fast_log2(lsum) * kLn2;
+          MASK ? (lsum > 0.f ? m + fast_log2(lsum) * kLn2 : -INFINITY) : m * p.scale + fast_log2(lsum) * kLn2;
   }
 }
 
@@ -392,6 +450,13 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     return hipGetLastError();
   }
   dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+  if constexpr (!F16) {
+    if (a.p.mask) {  // the entry points keep everything else away from it
+      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, false, false, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((fwd_kernel<D, false, false, false, false, false, true>), grid, block, 0, st, a);
+      return hipGetLastError();
+    }
+  }
   if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
     if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, false, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, true>), grid, block, 0, st, a);

@@ -155,6 +155,23 @@ def test_dropout_entry_points_reject_bad_arguments():
     assert binding.fa_dropout_bwd_raw(*ptrs, P, 1 << 20, 1, 2, 2, 8, 128, 64, 0.125, 0, 1.5, 99, 0) == binding.FA_ERR_SHAPE
 
 
+def test_mask_entry_points_reject_bad_arguments():
+    def run(Q=P, M=P, Nq=8, Nk=100, causal=0, d=64, bs=0, hs=0, rs=104):
+        return binding.fa_mask_fwd_raw(Q, P, P, M, P, P, 1, 2, 2, Nq, Nk, d, 0.125, causal, bs, hs, rs, 0)
+    assert run(Q=0) == binding.FA_ERR_NULL
+    assert run(M=0) == binding.FA_ERR_NULL
+    assert run(M=P + 8) == binding.FA_ERR_ALIGN
+    assert run(rs=96) == binding.FA_ERR_SHAPE    # shorter than a row of 100 keys padded to 104
+    assert run(rs=108) == binding.FA_ERR_SHAPE   # not a multiple of 8
+    assert run(bs=-8) == binding.FA_ERR_SHAPE
+    assert run(hs=12) == binding.FA_ERR_SHAPE
+    assert run(Nq=101, causal=1) == binding.FA_ERR_SHAPE
+    assert run(d=96) == binding.FA_ERR_UNSUPPORTED  # mask: the two tile widths only
+    ptrs = [P] * 10
+    assert binding.fa_mask_bwd_raw(*ptrs, P, 0, 1, 2, 2, 8, 100, 64, 0.125, 0, 0, 0, 104, 0) == binding.FA_ERR_WORKSPACE
+    assert binding.fa_mask_bwd_raw(*ptrs, P, 1 << 20, 1, 2, 2, 8, 100, 64, 0.125, 0, 0, 0, 100, 0) == binding.FA_ERR_SHAPE
+
+
 def test_ragged_two_length_entry_points_reject_bad_arguments():
     def run(Q=P, cu_q=P, cu_k=P, nseq=2, tq=10, tk=100, mq=8, mk=60, d=64):
         return binding.fa_varlen_cross_fwd_raw(Q, P, P, P, P, cu_q, cu_k, nseq, tq, tk, mq, mk, 2, 2, d, 0.125, 1, 0)

@@ -1,0 +1,153 @@
+"""GPU parity for the elementwise mask added to the scores (fa_mask_fwd / fa_mask_bwd) against
+the float64 oracle: biases, boolean masks, rows left without any key, masks shared over batch
+and heads, ragged lengths on both sides, with and without the causal rule."""
+import numpy as np
+import pytest
+
+from paper_2307_08691_amd import binding, inputs
+from oracle import attention_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import parity_util as pu  # noqa: E402
+
+
+def make_mask(seed, Bm, Hm, Nq, Nk, kind):
+    """Mask values as bfloat16 bit patterns [Bm, Hm, Nq, Nk]: 'bias' N(0, 2^2); 'bool' 0 / -inf with
+    30 % removed; 'mixed' bias with 30 % removed; key 0 always stays (every row keeps one entry,
+    also under the causal rule). 'dead' additionally removes whole rows."""
+    g = np.random.default_rng(seed)
+    m = np.zeros((Bm, Hm, Nq, Nk), dtype=np.float32) if kind == "bool" else \
+        (2.0 * g.standard_normal((Bm, Hm, Nq, Nk))).astype(np.float32)
+    if kind != "bias":
+        gone = g.random((Bm, Hm, Nq, Nk)) < 0.3
+        gone[..., 0] = False
+        m[gone] = -np.inf
+    if kind == "dead":
+        rows = g.random((Bm, Hm, Nq)) < 0.2
+        m[rows] = -np.inf
+    return inputs.f32_to_bf16_bits(m)
+
+
+def mask_to_gpu(bits):
+    Bm, Hm, Nq, Nk = bits.shape
+    M = binding.mask_buffer(Bm, Hm, Nq, Nk)
+    M.copy_(pu.to_gpu(bits))
+    return M
+
+
+def check_mask(prob, mbits, fwd_only=False):
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    M = mask_to_gpu(mbits)
+    O, L = binding.fa_mask_fwd(Q, K, V, M, prob.scale, prob.causal)
+    Qf, Kf, Vf, dOf, Mf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO, mbits))
+    eO, eL = orc.attention_forward_masked(Qf, Kf, Vf, Mf, prob.scale, prob.causal)
+    got = {"O": O, "LSE": L}
+    exp = {"O": eO, "LSE": eL}
+    if not fwd_only:
+        dQ, dK, dV = binding.fa_mask_bwd(Q, K, V, M, O, dO, L, prob.scale, prob.causal)
+        got.update(dQ=dQ, dK=dK, dV=dV)
+        exp.update(zip(("dQ", "dK", "dV"), orc.attention_backward_masked(Qf, Kf, Vf, Mf, dOf, prob.scale, prob.causal)))
+    torch.cuda.synchronize()
+    errs = {}
+    for nm in got:
+        g, e = pu.to_f64(got[nm]), exp[nm]
+        if nm == "LSE":  # rows without keys: -inf on both sides, compared apart
+            dead = np.isneginf(e)
+            assert np.array_equal(np.isneginf(g), dead), "rows without keys"
+            g, e = np.where(dead, 0.0, g), np.where(dead, 0.0, e)
+        assert np.all(np.isfinite(g)), nm
+        errs[nm] = pu.maxdiff(g, e)
+        assert errs[nm] <= pu.tolerance(nm, e), f"{nm}: {errs[nm]:.3e}"
+    return errs
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("kind", ["bias", "bool", "mixed"])
+@pytest.mark.parametrize("N", [1, 65, 300, 515])
+def test_masked_self_attention(N, kind, d, causal):
+    prob = inputs.make_dense(B=2, N=N, Hq=2, Hkv=2, d=d, causal=causal, seed=9000 + N)
+    check_mask(prob, make_mask(9100 + N, 2, 2, N, N, kind))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,Nk,Hq,Hkv,d", [(70, 333, 4, 2, 128), (1, 300, 8, 2, 64), (300, 301, 4, 1, 128),
+                                            (257, 1000, 2, 2, 64), (300, 129, 2, 2, 128)])
+def test_two_lengths_and_grouped_heads(Nq, Nk, Hq, Hkv, d, causal):
+    if causal and Nq > Nk:
+        pytest.skip("causal needs at least as many keys as queries")
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=9200 + Nq)
+    check_mask(prob, make_mask(9300 + Nq, 2, Hq, Nq, Nk, "mixed"))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_rows_left_without_any_key(d, causal):
+    prob = inputs.make_cross(B=2, Nq=200, Nk=330, Hq=4, Hkv=2, d=d, causal=causal, seed=9400 + d)
+    mbits = make_mask(9401, 2, 4, 200, 330, "dead")
+    check_mask(prob, mbits)
+    # the outputs of such rows are exactly zero
+    dead = np.all(np.isneginf(orc.widen_bf16(mbits)), axis=3)  # [B, Hq, Nq]
+    assert dead.any()
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    M = mask_to_gpu(mbits)
+    O, L = binding.fa_mask_fwd(Q, K, V, M, prob.scale, causal)
+    dQ, _, _ = binding.fa_mask_bwd(Q, K, V, M, O, dO, L, prob.scale, causal)
+    torch.cuda.synchronize()
+    sel = torch.from_numpy(dead.transpose(0, 2, 1).copy()).cuda()  # [B, Nq, Hq]
+    assert not bool(O[sel].any()) and not bool(dQ[sel].any())
+
+
+@pytest.mark.parametrize("Bm,Hm", [(1, 1), (2, 1), (1, 4)])
+def test_masks_shared_over_sequences_and_heads(Bm, Hm):
+    prob = inputs.make_cross(B=2, Nq=130, Nk=200, Hq=4, Hkv=2, d=128, causal=False, seed=9500)
+    check_mask(prob, make_mask(9501 + Bm + Hm, Bm, Hm, 130, 200, "mixed"))
+
+
+def test_a_zero_mask_reproduces_the_plain_entry_points():
+    prob = inputs.make_cross(B=2, Nq=300, Nk=301, Hq=4, Hkv=2, d=128, causal=True, seed=9600)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    M = binding.mask_buffer(1, 1, 300, 301)
+    O1, L1 = binding.fa_cross_fwd(Q, K, V, prob.scale, True)
+    O2, L2 = binding.fa_mask_fwd(Q, K, V, M, prob.scale, True)
+    g1 = binding.fa_cross_bwd(Q, K, V, O1, dO, L1, prob.scale, True)
+    g2 = binding.fa_mask_bwd(Q, K, V, M, O1, dO, L1, prob.scale, True)
+    torch.cuda.synchronize()
+    # same arithmetic up to the order of two roundings in the exponent
+    assert float((O1.float() - O2.float()).abs().max()) <= 2e-3
+    assert float((L1 - L2).abs().max()) <= 1e-5
+    for a, b in zip(g1, g2):
+        assert float((a.float() - b.float()).abs().max()) <= 4e-3 * max(1.0, float(a.float().abs().max()))
+
+
+def test_the_causal_rule_written_as_a_mask():
+    prob = inputs.make_dense(B=1, N=400, Hq=2, Hkv=2, d=64, causal=False, seed=9700)
+    Q, K, V = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V))
+    M = binding.mask_buffer(1, 1, 400, 400)
+    M.masked_fill_(torch.ones(400, 400, dtype=torch.bool, device="cuda").triu(1), float("-inf"))
+    O1, L1 = binding.fa_fwd(Q, K, V, prob.scale, True)
+    O2, L2 = binding.fa_mask_fwd(Q, K, V, M, prob.scale, False)
+    torch.cuda.synchronize()
+    assert float((O1.float() - O2.float()).abs().max()) <= 2e-3
+    assert float((L1 - L2).abs().max()) <= 1e-5
+
+
+def test_bad_mask_descriptions_are_rejected():
+    q = torch.zeros(1, 16, 2, 64, dtype=torch.bfloat16, device="cuda")
+    o = torch.empty_like(q)
+    lse = torch.empty(1, 2, 16, dtype=torch.float32, device="cuda")
+    m = torch.zeros(1, 1, 16, 16, dtype=torch.bfloat16, device="cuda")
+    args = (q.data_ptr(), q.data_ptr(), q.data_ptr())
+
+    def run(M=m.data_ptr(), bs=0, hs=0, rs=16, d=64):
+        return binding.fa_mask_fwd_raw(*args, M, o.data_ptr(), lse.data_ptr(), 1, 2, 2, 16, 16, d, 0.125, 0, bs, hs, rs, 0)
+    assert run() == binding.FA_OK
+    assert run(M=0) == binding.FA_ERR_NULL
+    assert run(M=m.data_ptr() + 2) == binding.FA_ERR_ALIGN
+    assert run(rs=8) == binding.FA_ERR_SHAPE     # shorter than a row
+    assert run(rs=20) == binding.FA_ERR_SHAPE    # not a multiple of 8
+    assert run(hs=-8) == binding.FA_ERR_SHAPE
+    assert run(bs=4) == binding.FA_ERR_SHAPE
+    torch.cuda.synchronize()
