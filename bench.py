@@ -17,7 +17,12 @@ Prints ONE JSON line. Besides the contract fields it carries
   roofline_fwd, roofline_dq - the same for the forward and the dQ kernels;
   mfma_loop    - TFLOP/s and shader clock of a register-resident loop of the same MFMA on
                  constant and on pseudo-random operands: what the pipe sustains on this box;
-  cpu_baseline - the float64 oracle timed on the host cores on a bounded sample.
+  cpu_baseline - the float64 oracle timed on the host cores on a bounded sample;
+  sweep        - (default workload only, after the timed region) the paper's benchmark grid
+                 (section 4.1: 16k tokens, hidden 2048, d = 64 with 32 heads and d = 128 with 16,
+                 N = 512 .. 16k, with and without the causal mask): forward and forward+backward
+                 TFLOPs/s of every point, so that one run carries the whole metric. The headline
+                 `value` stays the single workload named in `config`.
 """
 from __future__ import annotations
 
@@ -73,6 +78,45 @@ def cpu_baseline(prob, budget_s: float = 12.0):
         "sample": f"{len(units)} of {prob.B * prob.Hq} (sequence, head) units of {prob.name}, forward+backward, "
                   f"float64 numpy, {dt:.1f} s",
     }
+
+
+def paper_grid(binding, torch, iters: int = 8):
+    """Forward and forward+backward TFLOPs/s over the grid of section 4.1. Inputs are drawn on the
+    GPU (N(0,1) rounded to bf16, seeded): the values do not change the work."""
+    gen = torch.Generator(device="cuda").manual_seed(1002)
+    out = {}
+    for d, H in ((64, 32), (128, 16)):
+        for N in (512, 1024, 2048, 4096, 8192, 16384):
+            B = 16384 // N
+            Q, K, V, dO = (torch.randn(B, N, H, d, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
+            O = torch.empty_like(Q)
+            LSE = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+            dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+            ws = torch.empty(binding.fa_bwd_workspace_bytes(B, H, H, N, d), dtype=torch.uint8, device="cuda")
+            sc = d ** -0.5
+            for causal in (False, True):
+                def fwd():
+                    binding.fa_fwd(Q, K, V, sc, causal, O=O, LSE=LSE)
+
+                def both():
+                    fwd()
+                    binding.fa_bwd(Q, K, V, O, dO, LSE, sc, causal, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+                ms = []
+                for fn in (fwd, both):
+                    for _ in range(3):
+                        fn()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(iters):
+                        fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms.append(e0.elapsed_time(e1) / iters)
+                fl = 4.0 * B * H * N * N * d * (0.5 if causal else 1.0)
+                out[f"d{d}_n{N}_{'causal' if causal else 'full'}"] = {
+                    "fwd_tflops": round(fl / ms[0] / 1e9, 1), "fwd_bwd_tflops": round(3.5 * fl / ms[1] / 1e9, 1)}
+    return out
 
 
 def bench_decode(args, prob, binding) -> int:
@@ -143,6 +187,7 @@ def main() -> int:
     ap.add_argument("--workload", default="d128_n8k_causal")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true", help="profiling aid: time the forward alone")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the grid of section 4.1 after the timed region")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="profiling aid: instead of the benchmark, run 5 device-to-device copies of BYTES bytes; "
                          "under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE they give the counters' scale factors")
@@ -273,6 +318,9 @@ def main() -> int:
     for key, rnd in (("constant_operands", False), ("random_operands", True)):
         tf, ghz = binding.fa_mfma_probe(2000, rnd)
         out["mfma_loop"][key] = {"tflops": tf, "shader_clock_ghz": ghz}
+    if not args.no_sweep and not args.fwd_only and args.workload == "d128_n8k_causal":
+        del Q, K, V, dO, O, LSE, dQ, dK, dV, ws
+        out["sweep"] = paper_grid(binding, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(prob)
     print(json.dumps(out))
