@@ -88,6 +88,14 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 #ifndef FA_DKDV_AHEAD
 #define FA_DKDV_AHEAD 4
 #endif
+// K_j (and, at d = 64, V_j) operands of a wavefront's 32 keys held in registers instead of
+// being read from LDS for every tile
+#ifndef FA_DKDV_KREG
+#define FA_DKDV_KREG 1
+#endif
+#ifndef FA_DKDV_VREG
+#define FA_DKDV_VREG 1
+#endif
 //
 // PAD: head dimension p.d below the tile width D, rows padded with zeros on chip (see the
 // forward kernel); only the first p.d columns of dK, dV are stored.
@@ -262,9 +270,25 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   bf16x8 Pf[QTW][2], dSf[QTW][2];
 
   // ---- the MFMA work of a tile, as index -> (operand reads, MFMA) maps for mfma_stream_*
+  constexpr bool KREG = FA_DKDV_KREG && !MASK && !DROPOUT;
+  constexpr bool VREG = FA_DKDV_VREG && D == 64 && !MASK && !DROPOUT;
+  // The S and dP products take both operands from LDS, two 16-byte reads per MFMA: exactly what
+  // the LDS port delivers in the time the four SIMDs need for one MFMA each. K_j never changes,
+  // so its operands are read once (32 registers at d = 128; the prefetch ring shrinks by one
+  // entry to pay for them) and, at d = 64 where there is room, V_j's as well.
+  bf16x8 Kf[KREG ? KS : 1];  // this wavefront's K_j operands
+  if (KREG) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) Kf[ks] = lds_b128(smem, (zk ^ (32 * ks)) + KT_OFF);
+  }
+  bf16x8 Vf[VREG ? KS : 1];
+  if (VREG) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) Vf[ks] = lds_b128(smem, (zk ^ (32 * ks)) + VT_OFF);
+  }
   constexpr int NM = QTW * 2 * KS;   // S and dP: 16 MFMAs
   constexpr int NM2 = QTW * 4 * DT;  // dV and dK: 16 MFMAs
-  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : FA_DKDV_AHEAD;
+  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : (KREG && D == 128 && FA_DKDV_AHEAD > 3 ? 3 : FA_DKDV_AHEAD);
   // MASK: this lane's entries of M for the wavefront's next tile (raw bfloat16 bits), row by row
   uint32_t mraw[MASK ? QTW * 16 : 1];
   auto issue_mask_loads = [&](const Cursor& c) {
@@ -304,13 +328,14 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       }
       FA_SCHED_DSRD(4);
     }
-    return OperandPair{lds_b128(smem, (zq ^ x) + 32 * tq * ROWB + (i & 1) * TILEB),
-                       lds_b128(smem, (zk ^ x) + ((i & 1) ? VT_OFF : KT_OFF))};
+    const bf16x8 qa = lds_b128(smem, (zq ^ x) + 32 * tq * ROWB + (i & 1) * TILEB);
+    if ((i & 1) ? VREG : KREG) return OperandPair{qa, qa};
+    return OperandPair{qa, lds_b128(smem, (zk ^ x) + ((i & 1) ? VT_OFF : KT_OFF))};
   };
   auto mma_m = [&](int i, const OperandPair& o) {
     const int tq = i / (2 * KS), k = i % (2 * KS);
-    if (k & 1) dP[tq] = mfma32<F16>(o.a, o.b, dP[tq]);
-    else S[tq] = mfma32<F16>(o.a, o.b, k == 0 ? (f32x16){0} : S[tq]);
+    if (k & 1) dP[tq] = mfma32<F16>(o.a, VREG ? Vf[k >> 1] : o.b, dP[tq]);
+    else S[tq] = mfma32<F16>(o.a, KREG ? Kf[k >> 1] : o.b, k == 0 ? (f32x16){0} : S[tq]);
   };
   auto load_m2 = [&](const Cursor& c, int i) {  // Q_i^T (even i) or dO_i^T (odd i) operand of dK / dV
     const int tq = i / (4 * DT), k = i % (4 * DT), dt = k >> 2, s2 = (k >> 1) & 1;
@@ -341,12 +366,11 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         }
       }
       if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
-        asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
+        asm volatile("; keep this a branch: the mask costs two instructions per element" ::);
+        // visible: key < nk and (causal) key <= r0 + off + row of the tile, row = acc_row(r, hh)
+        const int kc = key_ok ? (CAUSAL ? key - (r0 + off) - 4 * hh : -1) : 0x7fffffff;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const bool vis = key_ok && (!CAUSAL || key <= r0 + off + acc_row(r, hh));
-          if (!vis) S[tq][r] = 0.f;
-        }
+        for (int r = 0; r < 16; ++r) S[tq][r] = kc <= acc_row(r, 0) ? S[tq][r] : 0.f;
       }
       if constexpr (DROPOUT) {
         // dP = keep o (dO V^T) / (1 - p), then dS = P o (dP - D) with the true P; afterwards P
