@@ -270,12 +270,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // ---- mask: causal entries above the diagonal and columns past the end
     const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
     if (need_mask) {
-      asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
+      asm volatile("; keep this a branch: the mask costs two instructions per element" ::);
+      const int lim = lim_row - col0 - 4 * hh;  // last visible column, relative to this lane's first
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[kt][r] = -INFINITY;
+        for (int r = 0; r < 16; ++r) S[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : S[kt][r];
     }
     float mx = max3(S[0][0], S[0][1], S[1][0]);
 #pragma unroll
