@@ -219,8 +219,9 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     }
   };
 
-  // ---- K_j, V_j (Algorithm 2, line 6) stay in LDS for the whole loop; tiles 0..2 are
-  //      requested up front by all wavefronts
+  // ---- K_j, V_j (Algorithm 2, line 6) are brought into LDS once (their MFMA operands are then
+  //      read from there, or from registers, see Kf / Vf below); tiles 0..2 are requested up
+  //      front by all wavefronts
   tile_load_async<D, BC, 8, PAD>(smem + KT_OFF, a.K + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
   tile_load_async<D, BC, 8, PAD>(smem + VT_OFF, a.V + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
   {
