@@ -151,3 +151,34 @@ def test_bad_mask_descriptions_are_rejected():
     assert run(hs=-8) == binding.FA_ERR_SHAPE
     assert run(bs=4) == binding.FA_ERR_SHAPE
     torch.cuda.synchronize()
+
+
+@pytest.mark.timeout(600)
+def test_full_size_masked_workload_sampled_units():
+    """The shape of the benchmark workload (B=2, N=8192, 16 heads of 128, causal) with one mask per
+    head shared by the two sequences: 30 % of the entries removed, a bias on the rest. The mask is
+    drawn on the GPU; whole (sequence, head) units are compared with the oracle."""
+    prob = inputs.make_config("d128_n8k_causal")
+    B, N, H = prob.B, prob.N, prob.Hq
+    gen = torch.Generator(device="cuda").manual_seed(9800)
+    M = binding.mask_buffer(1, H, N, N)
+    M.copy_(2.0 * torch.randn(1, H, N, N, device="cuda", generator=gen))
+    gone = torch.rand(1, H, N, N, device="cuda", generator=gen) < 0.3
+    gone[..., 0] = False
+    M.masked_fill_(gone, float("-inf"))
+    del gone
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    O, L = binding.fa_mask_fwd(Q, K, V, M, prob.scale, True)
+    dQ, dK, dV = binding.fa_mask_bwd(Q, K, V, M, O, dO, L, prob.scale, True)
+    torch.cuda.synchronize()
+    for t in (O, L, dQ, dK, dV):
+        assert torch.isfinite(t.float()).all()
+    for (b, h) in ((0, 0), (B - 1, H - 1)):
+        q, k, v, do = (orc.widen_bf16(x[b, :, h]) for x in (prob.Q, prob.K, prob.V, prob.dO))
+        m = M[0, h].double().cpu().numpy()
+        o, lse, _ = orc.head_forward_masked(q, k, v, m, prob.scale, True)
+        dq, dk, dv = orc.head_backward_masked(q, k, v, m, do, prob.scale, True)
+        for nm, got, exp in (("O", O[b, :, h], o), ("LSE", L[b, h], lse), ("dQ", dQ[b, :, h], dq),
+                             ("dK", dK[b, :, h], dk), ("dV", dV[b, :, h], dv)):
+            err = pu.maxdiff(pu.to_f64(got), exp)
+            assert err <= pu.tolerance(nm, exp), f"unit ({b},{h}) {nm}: {err:.3e}"
