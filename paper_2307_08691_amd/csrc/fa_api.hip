@@ -53,14 +53,58 @@ size_t ws_bytes(long tokens, int Hq, int d) {
   return round_up((size_t)tokens * Hq * sizeof(float), 256);  // D = rowsum(dO o O)
 }
 
+// dropout: threshold round(256 p) in 0 .. 255 (0: nothing is dropped) and the mixed seed
+int set_dropout(fa::Problem& p, float p_drop, uint64_t seed) {
+  if (!(p_drop >= 0.f) || !(p_drop < 1.f)) return FA_ERR_SHAPE;
+  long t = std::lround(256.0 * (double)p_drop);
+  if (t > 255) t = 255;
+  p.drop_thr = (uint32_t)t;
+  p.drop_seed = (uint32_t)seed ^ ((uint32_t)(seed >> 32) * 0x27D4EB2Fu);
+  p.drop_rp = 256.f / (256.f - (float)t);
+  return FA_OK;
+}
+
+// elementwise mask: strides in elements, multiples of 8 (every 16-byte chunk of M aligned)
+int set_mask(fa::Problem& p, const void* M, int Nk, long long bs, long long hs, long long rs) {
+  if (!M) return FA_ERR_NULL;
+  if (!aligned16(M)) return FA_ERR_ALIGN;
+  if (bs < 0 || hs < 0 || rs < (((long long)Nk + 7) & ~7LL)) return FA_ERR_SHAPE;
+  if (bs % 8 || hs % 8 || rs % 8) return FA_ERR_SHAPE;
+  p.mask = (const __bf16*)M;
+  p.mask_bs = (long)bs;
+  p.mask_hs = (long)hs;
+  p.mask_rs = (long)rs;
+  return FA_OK;
+}
+
+// What an entry point may ask for beyond the plain pass.
+struct Options {
+  int f16 = 0;                      // element type: 0 bfloat16, 1 IEEE half precision
+  bool dropout = false;             // dropout on P with p_drop, seed
+  float p_drop = 0.f;
+  uint64_t seed = 0;
+  bool mask = false;                // elementwise mask M with its three strides
+  const void* M = nullptr;
+  long long mask_bs = 0, mask_hs = 0, mask_rs = 0;
+};
+
+int apply_options(fa::Problem& p, const Options& o) {
+  if (o.dropout)
+    if (int e = set_dropout(p, o.p_drop, o.seed)) return e;
+  if (o.mask)
+    if (int e = set_mask(p, o.M, p.Nk, o.mask_bs, o.mask_hs, o.mask_rs)) return e;
+  return FA_OK;
+}
+
 int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu, int nseq, int N,
             int Nk, long total, int Hq, int Hkv, int d, float scale, int causal, void* stream, int nsplit = 0,
-            void* ws = nullptr, const int32_t* cu_k = nullptr, int f16 = 0) {
+            void* ws = nullptr, const int32_t* cu_k = nullptr, const Options& opt = Options()) {
   fa::FwdArgs a;
   a.nsplit = nsplit;
   a.Opart = (float*)ws;  // [nsplit, tokens, Hq, d], then the partial logsumexps [nsplit, B, Hq, Nq]
   a.Lpart = ws ? (float*)ws + (size_t)nsplit * total * Hq * d : nullptr;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, f16);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, opt.f16);
+  if (int e = apply_options(a.p, opt)) return e;
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -76,9 +120,11 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
 
 int run_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE, void* dQ,
             void* dK, void* dV, void* ws, const int32_t* cu, int nseq, int N, int Nk, long total, int Hq, int Hkv, int d,
-            float scale, int causal, int stages, void* stream, const int32_t* cu_k = nullptr, int f16 = 0) {
+            float scale, int causal, int stages, void* stream, const int32_t* cu_k = nullptr,
+            const Options& opt = Options()) {
   fa::BwdArgs a;
-  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, f16);
+  a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, opt.f16);
+  if (int e = apply_options(a.p, opt)) return e;
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -205,24 +251,62 @@ static int check_cross(int B, int Nq, int Nk, int causal) {
   return FA_OK;
 }
 
+// Dense entry points with two lengths: the plain ones, half precision, dropout and mask differ
+// only in the options.
 static int cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
-                     int Nk, int d, float scale, int causal, void* stream, int f16) {
+                     int Nk, int d, float scale, int causal, void* stream, const Options& opt) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
   return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, 0, nullptr,
-                 nullptr, f16);
+                 nullptr, opt);
+}
+
+static int cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                     void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                     int Nq, int Nk, int d, float scale, int causal, void* stream, const Options& opt) {
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask))) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
+  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
+                 causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream, nullptr, opt);
+}
+
+static Options half_precision(int f16) {
+  Options o;
+  o.f16 = f16;
+  return o;
+}
+static Options with_dropout(float p_drop, uint64_t seed) {
+  Options o;
+  o.dropout = true;
+  o.p_drop = p_drop;
+  o.seed = seed;
+  return o;
+}
+static Options with_mask(const void* M, long long bs, long long hs, long long rs) {
+  Options o;
+  o.mask = true;
+  o.M = M;
+  o.mask_bs = bs;
+  o.mask_hs = hs;
+  o.mask_rs = rs;
+  return o;
 }
 
 int fa_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
                  int Nk, int d, float scale, int causal, void* stream) {
-  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, 0);
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, half_precision(0));
 }
 
 int fa_cross_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
                      int Nk, int d, float scale, int causal, void* stream) {
-  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, 1);
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, half_precision(1));
 }
 
 size_t fa_cross_bwd_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int d) {
@@ -231,168 +315,45 @@ size_t fa_cross_bwd_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int 
   return ws_bytes((long)B * Nq, Hq, d);
 }
 
-static int cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
-                     void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
-                     int Nq, int Nk, int d, float scale, int causal, void* stream, int f16) {
-  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
-      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
-    return FA_ERR_ALIGN;
-  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
-  return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
-                 causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream, nullptr, f16);
-}
-
 int fa_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
                  void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
                  int Nq, int Nk, int d, float scale, int causal, void* stream) {
   return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                   stream, 0);
+                   stream, half_precision(0));
 }
 
 int fa_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
                      void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
                      int Nq, int Nk, int d, float scale, int causal, void* stream) {
   return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                   stream, 1);
-}
-
-// dropout: threshold round(256 p) in 0 .. 255 (0: nothing is dropped) and the mixed seed
-static int set_dropout(fa::Problem& p, float p_drop, uint64_t seed) {
-  if (!(p_drop >= 0.f) || !(p_drop < 1.f)) return FA_ERR_SHAPE;
-  long t = std::lround(256.0 * (double)p_drop);
-  if (t > 255) t = 255;
-  p.drop_thr = (uint32_t)t;
-  p.drop_seed = (uint32_t)seed ^ ((uint32_t)(seed >> 32) * 0x27D4EB2Fu);
-  p.drop_rp = 256.f / (256.f - (float)t);
-  return FA_OK;
+                   stream, half_precision(1));
 }
 
 int fa_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
                    int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
-  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
-  fa::FwdArgs a;
-  a.nsplit = 0;
-  a.Opart = a.Lpart = nullptr;
-  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
-  if (int e = set_dropout(a.p, p_drop, seed)) return e;
-  a.Q = (const __bf16*)Q;
-  a.K = (const __bf16*)K;
-  a.V = (const __bf16*)V;
-  a.O = (__bf16*)O;
-  a.LSE = LSE;
-  hipError_t e = fa::launch_fwd(a, d, causal, (hipStream_t)stream);
-  if (e != hipSuccess) {
-    g_last_hip_error = (int)e;
-    return FA_ERR_LAUNCH;
-  }
-  return FA_OK;
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, with_dropout(p_drop, seed));
 }
 
 int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
                    void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
                    int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
-  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
-      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
-    return FA_ERR_ALIGN;
-  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
-  fa::BwdArgs a;
-  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
-  if (int e = set_dropout(a.p, p_drop, seed)) return e;
-  a.Q = (const __bf16*)Q;
-  a.K = (const __bf16*)K;
-  a.V = (const __bf16*)V;
-  a.O = (const __bf16*)O;
-  a.dO = (const __bf16*)dO;
-  a.LSE = LSE;
-  a.dQ = (__bf16*)dQ;
-  a.dK = (__bf16*)dK;
-  a.dV = (__bf16*)dV;
-  a.Dvec = (float*)workspace;
-  hipError_t e = fa::launch_bwd(a, d, causal, 7, (hipStream_t)stream);
-  if (e != hipSuccess) {
-    g_last_hip_error = (int)e;
-    return FA_ERR_LAUNCH;
-  }
-  return FA_OK;
-}
-
-// elementwise mask: strides in elements, multiples of 8 (every 16-byte chunk of M aligned)
-static int set_mask(fa::Problem& p, const void* M, int Nk, long long bs, long long hs, long long rs) {
-  if (!M) return FA_ERR_NULL;
-  if (!aligned16(M)) return FA_ERR_ALIGN;
-  if (bs < 0 || hs < 0 || rs < (((long long)Nk + 7) & ~7LL)) return FA_ERR_SHAPE;
-  if (bs % 8 || hs % 8 || rs % 8) return FA_ERR_SHAPE;
-  p.mask = (const __bf16*)M;
-  p.mask_bs = (long)bs;
-  p.mask_hs = (long)hs;
-  p.mask_rs = (long)rs;
-  return FA_OK;
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, with_dropout(p_drop, seed));
 }
 
 int fa_mask_fwd(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE, int B, int Hq, int Hkv,
                 int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
                 long long mask_head_stride, long long mask_row_stride, void* stream) {
-  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
-  fa::FwdArgs a;
-  a.nsplit = 0;
-  a.Opart = a.Lpart = nullptr;
-  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
-  if (int e = set_mask(a.p, M, Nk, mask_batch_stride, mask_head_stride, mask_row_stride)) return e;
-  a.Q = (const __bf16*)Q;
-  a.K = (const __bf16*)K;
-  a.V = (const __bf16*)V;
-  a.O = (__bf16*)O;
-  a.LSE = LSE;
-  hipError_t e = fa::launch_fwd(a, d, causal, (hipStream_t)stream);
-  if (e != hipSuccess) {
-    g_last_hip_error = (int)e;
-    return FA_ERR_LAUNCH;
-  }
-  return FA_OK;
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream,
+                   with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride));
 }
 
 int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq,
                 int Hkv, int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
                 long long mask_head_stride, long long mask_row_stride, void* stream) {
-  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
-      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
-    return FA_ERR_ALIGN;
-  if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
-  fa::BwdArgs a;
-  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale);
-  if (int e = set_mask(a.p, M, Nk, mask_batch_stride, mask_head_stride, mask_row_stride)) return e;
-  a.Q = (const __bf16*)Q;
-  a.K = (const __bf16*)K;
-  a.V = (const __bf16*)V;
-  a.O = (const __bf16*)O;
-  a.dO = (const __bf16*)dO;
-  a.LSE = LSE;
-  a.dQ = (__bf16*)dQ;
-  a.dK = (__bf16*)dK;
-  a.dV = (__bf16*)dV;
-  a.Dvec = (float*)workspace;
-  hipError_t e = fa::launch_bwd(a, d, causal, 7, (hipStream_t)stream);
-  if (e != hipSuccess) {
-    g_last_hip_error = (int)e;
-    return FA_ERR_LAUNCH;
-  }
-  return FA_OK;
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride));
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,
