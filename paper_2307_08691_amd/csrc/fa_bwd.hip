@@ -62,9 +62,15 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 }
 
 
-// dK/dV kernel: 8 wavefronts in two groups of four. Wavefront (kg, grp) owns keys 32*kg..
-// of the column block; the groups take the 32*QTW-row query tiles alternately (group = tile
-// index mod 2) and accumulate partial dK_j^T, dV_j^T over their own tiles.
+// dK/dV kernel: 8 wavefronts in two groups of four. Two forms share the code below.
+// WIDE (the plain, half precision and padded instantiations): 256 keys per workgroup, wavefront
+// v owns keys 32*v.. and visits every tile; see the comment at `if constexpr (WIDE)`.
+// Otherwise (dropout, mask: their extra registers leave no room for K_j in registers, and K_j
+// plus V_j of 256 keys do not fit in LDS): 128 keys per workgroup, wavefront (kg, grp) owns
+// keys 32*kg.. of the column block; the groups take the 32*QTW-row query tiles alternately
+// (group = tile index mod 2) and accumulate partial dK_j^T, dV_j^T over their own tiles.
+// The description that follows is that of the second form; the first differs in who visits
+// which tile and in the ring depth, not in the phases.
 //
 // Phases. Tile T passes through three stages, one per global phase, a workgroup barrier
 // after every phase:
@@ -96,6 +102,15 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 #ifndef FA_DKDV_VREG
 #define FA_DKDV_VREG 1
 #endif
+// 256 keys per workgroup (see WIDE below)
+#ifndef FA_DKDV_WIDE
+#define FA_DKDV_WIDE 1
+#endif
+// keys per workgroup of the dK/dV kernel instantiation (the launch needs it for the grid)
+constexpr bool dkdv_wide(int D, bool dropout, bool mask) {
+  return FA_DKDV_WIDE && FA_DKDV_KREG && !dropout && !mask && (D == 128 || FA_DKDV_VREG);
+}
+constexpr int dkdv_block_keys(int D, bool dropout, bool mask) { return dkdv_wide(D, dropout, mask) ? 256 : 128; }
 //
 // PAD: head dimension p.d below the tile width D, rows padded with zeros on chip (see the
 // forward kernel); only the first p.d columns of dK, dV are stored.
@@ -108,20 +123,24 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
-  constexpr int BC = 128;               // keys per workgroup
+  constexpr bool KREG = FA_DKDV_KREG && !MASK && !DROPOUT;
+  constexpr bool VREG = FA_DKDV_VREG && D == 64 && !MASK && !DROPOUT;
+  constexpr bool WIDE = dkdv_wide(D, DROPOUT, MASK);
+  constexpr int BC = dkdv_block_keys(D, DROPOUT, MASK);  // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
   constexpr int BR = 32 * QTW;          // query rows of one tile
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int ROWB = 2 * D;           // row bytes of the Q_i, dO_i, K_j, V_j tiles
-  constexpr int RING = 5;
-  // byte offsets inside the LDS block
-  constexpr int KT_OFF = 0, VT_OFF = BC * ROWB, QDO_OFF = 2 * BC * ROWB;
+  constexpr int RING = WIDE ? 4 : 5;
+  // byte offsets inside the LDS block (WIDE: K_j never enters LDS, V_j only when it is not in registers)
+  constexpr bool K_IN_LDS = !WIDE, V_IN_LDS = !(WIDE && VREG);
+  constexpr int KT_OFF = 0, VT_OFF = K_IN_LDS ? BC * ROWB : 0, QDO_OFF = VT_OFF + (V_IN_LDS ? BC * ROWB : 0);
   constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one ring slot = Q_i | dO_i
   constexpr int LS_OFF = QDO_OFF + RING * BUFB;       // [slot][row] floats
   constexpr int DV_OFF = LS_OFF + RING * BR * 4;
   constexpr int SMEM = DV_OFF + RING * BR * 4;
   static_assert(VT_OFF + BC * ROWB <= 65536 && BUFB <= 32768, "immediate offsets must fit 16 bits");
-  static_assert(4 * DT * 16 * 64 * 4 <= RING * BUFB, "the final reduction reuses the ring");
+  static_assert(WIDE || 4 * DT * 16 * 64 * 4 <= RING * BUFB, "the final reduction reuses the ring");
   static_assert(SMEM <= 160 * 1024, "LDS of one compute unit");
 
   __shared__ __attribute__((aligned(1024))) char smem[SMEM];
@@ -130,6 +149,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int v = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = v & 3, grp = v >> 2;
+  const int kgi = WIDE ? v : kg;  // which 32 keys of the block this wavefront owns
   const int gtid = tid & 255;  // thread index inside the group
   const int lq = lane & 31, hh = lane >> 5;
   const BlockCoord bc = block_coord<CAUSAL>((p.Nk + BC - 1) / BC, p.Hkv, p.nseq);  // causal: block 0 is the longest
@@ -222,11 +242,31 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // ---- K_j, V_j (Algorithm 2, line 6) are brought into LDS once (their MFMA operands are then
   //      read from there, or from registers, see Kf / Vf below); tiles 0..2 are requested up
   //      front by all wavefronts
-  tile_load_async<D, BC, 8, PAD>(smem + KT_OFF, a.K + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
-  tile_load_async<D, BC, 8, PAD>(smem + VT_OFF, a.V + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
+  if (K_IN_LDS)
+    tile_load_async<D, BC, 8, PAD>(smem + KT_OFF, a.K + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
+  if (V_IN_LDS)
+    tile_load_async<D, BC, 8, PAD>(smem + VT_OFF, a.V + (si.tok0k * p.Hkv + g) * dh, kstride, j0, nk - 1, v, lane, dh / 8);
+  // this lane's key column, and (WIDE) its K_j / V_j operands straight from memory: the 8
+  // elements 16 ks + 8 hh .. of the key's row are exactly what lane (lq, hh) feeds to MFMA ks
+  const int key = j0 + 32 * kgi + lq;
+  const bool key_ok = key < nk;
+  bf16x8 Kf[KREG ? KS : 1];
+  bf16x8 Vf[VREG ? KS : 1];
+  if constexpr (WIDE) {
+    const long krow = ((si.tok0k + (key_ok ? key : nk - 1)) * p.Hkv + g) * dh + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      Kf[ks] = (bf16x8){0};
+      if (VREG) Vf[ks] = (bf16x8){0};
+      if (!PAD || 16 * ks + 8 * hh < dh) {
+        Kf[ks] = *(const bf16x8*)(a.K + krow + 16 * ks);
+        if (VREG) Vf[ks] = *(const bf16x8*)(a.V + krow + 16 * ks);
+      }
+    }
+  }
   {
     Cursor c = tile0;
-    for (int t = 0; t < 3 && t < T; ++t) {
+    for (int t = 0; t < (WIDE ? 2 : 3) && t < T; ++t) {
       const long first = c.qoff - (long)c.it * BR * qstride;  // row 0 of this head
       char* dst = smem + QDO_OFF + c.slot * BUFB;
       tile_load_async<D, BR, 8, PAD>(dst, a.Q + first, qstride, c.it * BR, n - 1, v, lane, dh / 8);
@@ -243,6 +283,13 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       advance(c, 1);
     }
   }
+  if constexpr (WIDE) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      touch(Kf[ks]);
+      if (VREG) touch(Vf[ks]);
+    }
+  }
   wait_vmem();
   lds_barrier();
 
@@ -256,7 +303,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
   for (int u = 0; u < 2; ++u)
     zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
-  const int zk = zrow + 32 * kg * ROWB;  // K_j / V_j row operands of this wavefront
+  const int zk = zrow + 32 * kgi * ROWB;  // K_j / V_j row operands of this wavefront
 
   // ---- dK_j^T, dV_j^T accumulators (line 7): rows = head dim, columns = this wavefront's
   //      32 keys; partial over this group's tiles
@@ -264,26 +311,19 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dKt[dt] = dVt[dt] = (f32x16){0};
 
-  const int key = j0 + 32 * kg + lq;  // this lane's key column
-  const bool key_ok = key < nk;
-
   f32x16 S[QTW], dP[QTW];
   bf16x8 Pf[QTW][2], dSf[QTW][2];
 
   // ---- the MFMA work of a tile, as index -> (operand reads, MFMA) maps for mfma_stream_*
-  constexpr bool KREG = FA_DKDV_KREG && !MASK && !DROPOUT;
-  constexpr bool VREG = FA_DKDV_VREG && D == 64 && !MASK && !DROPOUT;
   // The S and dP products take both operands from LDS, two 16-byte reads per MFMA: exactly what
   // the LDS port delivers in the time the four SIMDs need for one MFMA each. K_j never changes,
   // so its operands are read once (32 registers at d = 128; the prefetch ring shrinks by one
   // entry to pay for them) and, at d = 64 where there is room, V_j's as well.
-  bf16x8 Kf[KREG ? KS : 1];  // this wavefront's K_j operands
-  if (KREG) {
+  if (KREG && !WIDE) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) Kf[ks] = lds_b128(smem, (zk ^ (32 * ks)) + KT_OFF);
   }
-  bf16x8 Vf[VREG ? KS : 1];
-  if (VREG) {
+  if (VREG && !WIDE) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) Vf[ks] = lds_b128(smem, (zk ^ (32 * ks)) + VT_OFF);
   }
@@ -354,7 +394,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int tq = 0; tq < QTW; ++tq) {
       const int r0 = i0 + 32 * tq;  // first query row of this tile
-      const bool need_mask = (CAUSAL && j0 + 32 * kg + 31 > r0 + off) || (j0 + BC > nk);
+      const bool need_mask = (CAUSAL && j0 + 32 * kgi + 31 > r0 + off) || (j0 + BC > nk);
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * tq + 8 * r4 + 4 * hh) * 4);
@@ -410,8 +450,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // operand reads of M' are issued at the end of the vector phase before it: the tile they
   // read has been in LDS for two phases, so they need not wait for the barrier.
   Cursor cur = tile0, prev = tile0, ld = tile0;
-  advance(cur, grp);
-  advance(ld, 3 + grp);  // first refill: tile 3 in phase 1 (group 0), tile 4 in phase 2 (group 1)
   int pending = -1;      // ring slot whose statistics wait in lraw / draw
   auto end_matrix_phase = [&]() {
     __builtin_amdgcn_s_setprio(0);
@@ -451,21 +489,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     lds_barrier();
   };
 
-  int tau = grp;
-  if (grp == 1) lds_barrier();
-  // the group's first matrix phase: M only
-  const bool have_first = tau < T;
-  if (MASK && have_first) issue_mask_loads(cur);
-  if (have_first) {
-    __builtin_amdgcn_s_setprio(2);
-    mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
-  }
-  end_matrix_phase();
-  vector_phase(tau, have_first);
-  prev = cur;
-  advance(cur, 2);
-  // steady state: M' of the previous tile, then M of the current one
-  for (tau += 2; tau < T; tau += 2) {
+  // the two MFMA streams of the steady state as functions of (prev, cur)
+  auto fused_stream = [&]() {  // M' of the previous tile running into M of the current one
     __builtin_amdgcn_s_setprio(2);
     OperandPair ring[AH];
 #pragma unroll
@@ -483,6 +508,107 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
           if (i < NM2) mma_m2(i, o.a);
           else mma_m(i - NM2, o);
         });
+  };
+
+  if constexpr (WIDE) {
+    // 256 keys per workgroup: the eight wavefronts own eight different key groups, so every
+    // wavefront visits EVERY tile, nothing is left to add up at the end, and each Q_i / dO_i
+    // tile is copied once per 256 keys instead of once per 128 (the copy traffic L2 -> LDS
+    // costs about as much as the operand reads from LDS). Group 1 runs the same program one
+    // phase behind group 0: tile t is in M in phase 2t (group 0) / 2t + 1 (group 1), in V one
+    // phase later, in M' two phases later. Phases 0 .. 2T + 1, one barrier each.
+    // Copies: group 0 requests tile t + 2 at the start of its vector phase t (phase 2t + 1) into
+    // the slot of tile t - 2, whose last reader was group 1's M' in phase 2t - 1; they are
+    // complete and visible when the barrier of phase 2t + 2 falls, two phases before group 0
+    // reads the tile. A ring of four slots suffices.
+    advance(ld, 2);
+    if (grp == 1) lds_barrier();
+    auto vector_phase_w = [&](int t, bool do_v) {
+      if (grp == 0 && t + 2 < T) {
+        issue_loads(ld);
+        pending = ld.slot;
+        advance(ld, 1);
+      }
+      if (do_v) {
+        phase_v(cur);
+        mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
+      }
+      lds_barrier();
+    };
+    // Leading tiles in which every score of THIS wavefront's 32 keys is masked (its keys lie
+    // above the tile's last row, or past the end of the sequence): the wavefront only keeps up
+    // with the copies and the barriers. With several query heads per key/value head the
+    // masked tiles recur at the start of every head and are computed (they contribute zeros).
+    int skip = 0;
+    if (j0 + 32 * kgi >= nk) skip = T;
+    else if (CAUSAL && p.G == 1 && j0 + 32 * kgi > off) {
+      const int first_useful = (j0 + 32 * kgi - off) / BR;  // first row tile that reaches this wavefront's keys
+      skip = first_useful - i_first < T ? first_useful - i_first : T;
+    }
+    int t = 0;
+    for (; t < skip; ++t) {
+      end_matrix_phase();
+      vector_phase_w(t, false);
+      advance(cur, 1);
+    }
+    if (t < T) {
+      __builtin_amdgcn_s_setprio(2);
+      mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
+      end_matrix_phase();
+      vector_phase_w(t, true);
+      for (++t; t < T; ++t) {
+        prev = cur;
+        advance(cur, 1);
+        fused_stream();
+        end_matrix_phase();
+        vector_phase_w(t, true);
+      }
+      prev = cur;
+      __builtin_amdgcn_s_setprio(2);
+      mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
+    }
+    end_matrix_phase();
+    if (grp == 0) lds_barrier();  // group 1's last phase
+
+    // ---- write dK_j, dV_j (line 18); dK carries the scaling
+    if (key_ok) {
+#pragma unroll
+      for (int which = 0; which < 2; ++which) {
+        const f32x16* accs = which == 0 ? dKt : dVt;
+        __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0k + key) * p.Hkv + g) * dh + 4 * hh;
+        const float mul = which == 0 ? p.scale : 1.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            u32x2 o;
+            o[0] = pack2<F16>(accs[dt][4 * r4 + 0] * mul, accs[dt][4 * r4 + 1] * mul);
+            o[1] = pack2<F16>(accs[dt][4 * r4 + 2] * mul, accs[dt][4 * r4 + 3] * mul);
+            if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(dst + 32 * dt + 8 * r4) = o;
+          }
+      }
+    }
+    return;
+  }
+
+  advance(cur, grp);
+  advance(ld, 3 + grp);  // first refill: tile 3 in phase 1 (group 0), tile 4 in phase 2 (group 1)
+  int tau = grp;
+  if (grp == 1) lds_barrier();
+  // the group's first matrix phase: M only
+  const bool have_first = tau < T;
+  if (MASK && have_first) issue_mask_loads(cur);
+  if (have_first) {
+    __builtin_amdgcn_s_setprio(2);
+    mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
+  }
+  end_matrix_phase();
+  vector_phase(tau, have_first);
+  prev = cur;
+  advance(cur, 2);
+  // steady state: M' of the previous tile, then M of the current one
+  for (tau += 2; tau < T; tau += 2) {
+    fused_stream();
     end_matrix_phase();
     vector_phase(tau, true);
     prev = cur;
@@ -797,7 +923,10 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (stages & 2) {
-    dim3 grid(grid_size((a.p.Nk + 127) / 128, a.p.Hkv * a.p.nseq));
+    // keys per workgroup differ between the instantiations
+    const bool special = !F16 && (a.p.mask || a.p.drop_thr);
+    const int bck = special ? dkdv_block_keys(D, true, true) : dkdv_block_keys(D, false, false);
+    dim3 grid(grid_size((a.p.Nk + bck - 1) / bck, a.p.Hkv * a.p.nseq));
     bool done = false;
     if constexpr (!F16) {
       if (a.p.mask) {
