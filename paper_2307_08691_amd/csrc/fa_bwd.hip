@@ -2,7 +2,7 @@
 //
 // Three launches on the caller's stream:
 //   1. prep:  D = rowsum(dO o O) (Algorithm 2, line 4)
-//   2. dK/dV: one workgroup per block of 128 keys of one (sequence, key/value head)
+//   2. dK/dV: one workgroup per block of 256 keys of one (sequence, key/value head)
 //             (section 3.2 "Backward pass"); it loops over the query heads that share the
 //             key/value head and over the row blocks i, recomputes P from the saved
 //             logsumexp (line 11) and keeps dK_j, dV_j in MFMA accumulators for the whole
