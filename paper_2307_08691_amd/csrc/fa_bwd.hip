@@ -172,22 +172,25 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const int T = (nrt - i_first) * p.G;       // tiles this workgroup visits, over the group's query heads
   const long stat_base = s * p.lse_seq_stride + (p.cu_seqlens ? si.tok0 : 0);
 
-  // Position of a tile in the visiting order: query head, row tile, ring slot, and where the
-  // tile starts in Q / dO (elements) and in L / D. Advancing is a few scalar additions.
+  // Position of a tile in the visiting order: row tile, query head, ring slot, and where the
+  // tile starts in Q / dO (elements) and in L / D. Advancing is a few scalar additions. The
+  // query heads of the group are the inner loop: their rows of one token are neighbours in
+  // memory, and under the mask the tiles above a wavefront's keys then come first, all together.
   struct Cursor {
     int hq, it, slot;
     long qoff, soff;
   };
-  const long wrap_q = dh - (long)(nrt - i_first) * BR * qstride;  // last row tile of a head -> first of the next
-  const long wrap_s = p.lse_head_stride - (long)(nrt - i_first) * BR;
+  const int hq_end = (g + 1) * p.G;
+  const long wrap_q = BR * qstride - (long)p.G * dh;  // last head of a row tile -> first head of the next
+  const long wrap_s = BR - (long)p.G * p.lse_head_stride;
   auto advance = [&](Cursor& c, int steps) {
     for (int k = 0; k < steps; ++k) {
-      ++c.it;
-      c.qoff += BR * qstride;
-      c.soff += BR;
-      if (c.it == nrt) {
-        c.it = i_first;
-        ++c.hq;
+      ++c.hq;
+      c.qoff += dh;
+      c.soff += p.lse_head_stride;
+      if (c.hq == hq_end) {
+        c.hq = g * p.G;
+        ++c.it;
         c.qoff += wrap_q;
         c.soff += wrap_s;
       }
@@ -537,13 +540,12 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     };
     // Leading tiles in which every score of THIS wavefront's 32 keys is masked (its keys lie
     // above the tile's last row, or past the end of the sequence): the wavefront only keeps up
-    // with the copies and the barriers. With several query heads per key/value head the
-    // masked tiles recur at the start of every head and are computed (they contribute zeros).
+    // with the copies and the barriers.
     int skip = 0;
     if (j0 + 32 * kgi >= nk) skip = T;
-    else if (CAUSAL && p.G == 1 && j0 + 32 * kgi > off) {
+    else if (CAUSAL && j0 + 32 * kgi > off) {
       const int first_useful = (j0 + 32 * kgi - off) / BR;  // first row tile that reaches this wavefront's keys
-      skip = first_useful - i_first < T ? first_useful - i_first : T;
+      skip = (first_useful - i_first) * p.G < T ? (first_useful - i_first) * p.G : T;
     }
     int t = 0;
     for (; t < skip; ++t) {
