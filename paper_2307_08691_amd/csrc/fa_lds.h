@@ -71,6 +71,10 @@ __device__ __forceinline__ void tile_load_async(char* tile, const __bf16* gbase,
                                                 int row_last, int wave, int lane, int nchunk = D / 8) {
   constexpr int ROWB = 2 * D, CPR = ROWB / 16, RPI = 64 / CPR, NI = NROWS / RPI;
   static_assert(NI % NW == 0, "tile must divide over the wavefronts");
+  // The lane index is hidden from the optimiser: this is the rarely taken path of the streaming
+  // kernels (tiles at the end of a sequence), and otherwise the loop-invariant parts of its
+  // per-lane 64-bit addresses are kept in registers across the whole main loop.
+  asm volatile("" : "+v"(lane));
 #pragma unroll
   for (int u = 0; u < NI / NW; ++u) {
     const int rb = (wave + NW * u) * RPI;
