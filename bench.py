@@ -42,8 +42,8 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 # under profiles/pmc_<workload>_kernels.md, already scaled by the copy-kernel factors given there.
 # A counter pass cannot run inside this script; workloads without a recorded pass report null.
 MEASURED_TRAFFIC = {
-    "d128_n8k_causal": {"fwd_kernel": 638070081, "bwd_dkdv_kernel": 862573470, "bwd_dq_kernel": 686821742},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269848099, "bwd_dkdv_kernel": 405969185, "bwd_dq_kernel": 338143380},
+    "d128_n8k_causal": {"fwd_kernel": 644704547, "bwd_dkdv_kernel": 841273533, "bwd_dq_kernel": 739985828},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269992881, "bwd_dkdv_kernel": 417536429, "bwd_dq_kernel": 337870057},
     "decode_b8_on_8k": {"fwd_kernel": 288777216},  # split kernel + merge, profiles/bench_decode_b8_on_8k_kernel_stats.md
 }
 
