@@ -198,6 +198,25 @@ int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, c
                    float p_drop, uint64_t seed, void* stream);
 
 /*
+ * Dropout on P for packed ragged batches: fa_varlen_fwd / fa_varlen_bwd with the dropout of
+ * fa_dropout_fwd / fa_dropout_bwd (same reading of the footnote of section 2.2, same generator;
+ * the head index of the generator is bh = sequence * Hq + head, query and key are counted from
+ * the start of their sequence, so a ragged batch of equal lengths drops exactly what the dense
+ * batch drops). Layouts, arguments and workspace as for fa_varlen_fwd / fa_varlen_bwd
+ * (fa_varlen_bwd_workspace_bytes); d in {64, 128}; bfloat16 elements.
+ */
+int fa_varlen_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                          const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                          int Hq, int Hkv, int d, float scale, int causal,
+                          float p_drop, uint64_t seed, void* stream);
+int fa_varlen_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                          const float* LSE, void* dQ, void* dK, void* dV,
+                          void* workspace, size_t workspace_bytes,
+                          const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                          int Hq, int Hkv, int d, float scale, int causal,
+                          float p_drop, uint64_t seed, void* stream);
+
+/*
  * Elementwise mask on S (section 2.2, the footnote to the definition of S, P, O, which names
  * masking without giving an algorithm). Reading taken here: a tensor M is ADDED to the scaled
  * scores, S = scale * Q K^T + M, before the causal rule (if any) and the softmax; the rest of

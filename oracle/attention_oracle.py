@@ -352,6 +352,45 @@ def attention_backward_dropout(Q, K, V, dO, scale, causal, p_drop, seed):
     return dQ, dK, dV
 
 
+def varlen_forward_dropout(Q, K, V, cu_seqlens, scale, causal, p_drop, seed):
+    """Packed ragged forward with dropout: every sequence is its own attention problem; the head
+    index of the generator is sequence * Hq + head and rows and columns count from the start of
+    the sequence, as in a dense batch. Q [T,Hq,d], K,V [T,Hkv,d]; returns O [T,Hq,d], L [Hq,T]."""
+    T, Hq, d = Q.shape
+    G = _group(Hq, K.shape[1])
+    t = dropout_threshold(p_drop)
+    O = np.zeros((T, Hq, d), dtype=np.float64)
+    L = np.zeros((Hq, T), dtype=np.float64)
+    for s in range(len(cu_seqlens) - 1):
+        a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        for h in range(Hq if e > a else 0):
+            keep = dropout_keep(seed, s * Hq + h, e - a, e - a, t)
+            o, lse, _ = head_forward_dropout(Q[a:e, h], K[a:e, h // G], V[a:e, h // G], scale, causal, keep, t)
+            O[a:e, h] = o
+            L[h, a:e] = lse
+    return O, L
+
+
+def varlen_backward_dropout(Q, K, V, dO, cu_seqlens, scale, causal, p_drop, seed):
+    """Packed ragged backward with dropout. Returns dQ [T,Hq,d], dK, dV [T,Hkv,d]."""
+    T, Hq, d = Q.shape
+    G = _group(Hq, K.shape[1])
+    t = dropout_threshold(p_drop)
+    dQ = np.zeros(Q.shape, dtype=np.float64)
+    dK = np.zeros(K.shape, dtype=np.float64)
+    dV = np.zeros(V.shape, dtype=np.float64)
+    for s in range(len(cu_seqlens) - 1):
+        a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        for h in range(Hq if e > a else 0):
+            keep = dropout_keep(seed, s * Hq + h, e - a, e - a, t)
+            dq, dk, dv = head_backward_dropout(Q[a:e, h], K[a:e, h // G], V[a:e, h // G], dO[a:e, h], scale, causal,
+                                               keep, t)
+            dQ[a:e, h] = dq
+            dK[a:e, h // G] += dk
+            dV[a:e, h // G] += dv
+    return dQ, dK, dV
+
+
 # ---------------------------------------------------------------------------
 # Elementwise mask added to S (footnote of section 2.2; reading in the header)
 # ---------------------------------------------------------------------------

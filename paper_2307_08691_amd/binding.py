@@ -48,6 +48,10 @@ SIGNATURES = {
     "fa_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 +
                        [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_varlen_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 +
+                              [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_varlen_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
+                              [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_mask_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_mask_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
                     [ctypes.c_longlong] * 3 + [_c_void_p]),
@@ -167,6 +171,18 @@ def fa_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv
                        seed, stream=0) -> int:
     return load().fa_dropout_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
                                  int(causal), p_drop, seed, stream)
+
+
+def fa_varlen_dropout_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed,
+                              stream=0) -> int:
+    return load().fa_varlen_dropout_fwd(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, int(causal),
+                                        p_drop, seed, stream)
+
+
+def fa_varlen_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d,
+                              scale, causal, p_drop, seed, stream=0) -> int:
+    return load().fa_varlen_dropout_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq,
+                                        Hkv, d, scale, int(causal), p_drop, seed, stream)
 
 
 def fa_mask_fwd_raw(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs, mask_hs, mask_rs, stream=0) -> int:
@@ -395,6 +411,47 @@ def fa_dropout_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, p_drop: floa
     _check(fa_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                               _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
                               scale, causal, p_drop, seed, _stream()))
+    return dQ, dK, dV
+
+
+def fa_varlen_dropout_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, causal: bool, p_drop: float, seed: int,
+                          O=None, LSE=None):
+    """Packed ragged forward with dropout on P. Q [T,Hq,d], K,V [T,Hkv,d] bf16; cu_seqlens int32 on the GPU."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _need(t, nm, torch.bfloat16)
+    _need(cu_seqlens, "cu_seqlens", torch.int32)
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((Hq, T), dtype=torch.float32, device=Q.device)
+    _check(fa_varlen_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens),
+                                     cu_seqlens.numel() - 1, T, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed,
+                                     _stream()))
+    return O, LSE
+
+
+def fa_varlen_dropout_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, causal: bool, p_drop: float,
+                          seed: int, dQ=None, dK=None, dV=None, workspace=None):
+    """Packed ragged backward with the dropout mask of fa_varlen_dropout_fwd for the same p_drop and seed."""
+    import torch
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _need(t, nm, torch.bfloat16)
+    _need(LSE, "LSE", torch.float32)
+    _need(cu_seqlens, "cu_seqlens", torch.int32)
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    if workspace is None:
+        workspace = torch.empty(fa_varlen_bwd_workspace_bytes(T, Hq, Hkv, d), dtype=torch.uint8, device=Q.device)
+    _check(fa_varlen_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                                     _ptr(dV), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _ptr(cu_seqlens), cu_seqlens.numel() - 1, T, max_seqlen, Hq, Hkv, d, scale,
+                                     causal, p_drop, seed, _stream()))
     return dQ, dK, dV
 
 

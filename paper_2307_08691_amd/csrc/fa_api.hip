@@ -88,6 +88,28 @@ struct Options {
   long long mask_bs = 0, mask_hs = 0, mask_rs = 0;
 };
 
+Options half_precision(int f16) {
+  Options o;
+  o.f16 = f16;
+  return o;
+}
+Options with_dropout(float p_drop, uint64_t seed) {
+  Options o;
+  o.dropout = true;
+  o.p_drop = p_drop;
+  o.seed = seed;
+  return o;
+}
+Options with_mask(const void* M, long long bs, long long hs, long long rs) {
+  Options o;
+  o.mask = true;
+  o.M = M;
+  o.mask_bs = bs;
+  o.mask_hs = hs;
+  o.mask_rs = rs;
+  return o;
+}
+
 int apply_options(fa::Problem& p, const Options& o) {
   if (o.dropout)
     if (int e = set_dropout(p, o.p_drop, o.seed)) return e;
@@ -212,15 +234,29 @@ static int check_varlen(const int32_t* cu, int nseq, int total_tokens, int max_s
   return FA_OK;
 }
 
+static int varlen_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
+                      int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
+                      void* stream, const Options& opt) {
+  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !opt.dropout)) return e;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  return run_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, max_seqlen, max_seqlen, total_tokens, Hq, Hkv, d, scale, causal,
+                 stream, 0, nullptr, nullptr, opt);
+}
+
 int fa_varlen_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
                   int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
                   void* stream) {
-  if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
-  if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
-  return run_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, max_seqlen, max_seqlen, total_tokens, Hq, Hkv, d, scale, causal,
-                 stream);
+  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
+                    Options());
+}
+
+int fa_varlen_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
+                          int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
+                          float p_drop, uint64_t seed, void* stream) {
+  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
+                    with_dropout(p_drop, seed));
 }
 
 size_t fa_varlen_bwd_workspace_bytes(int total_tokens, int Hq, int Hkv, int d) {
@@ -229,19 +265,35 @@ size_t fa_varlen_bwd_workspace_bytes(int total_tokens, int Hq, int Hkv, int d) {
   return ws_bytes(total_tokens, Hq, d);
 }
 
-int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
-                  void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, const int32_t* cu_seqlens,
-                  int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
-                  void* stream) {
+static int varlen_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                      void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                      const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d,
+                      float scale, int causal, void* stream, const Options& opt) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
   if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !opt.dropout)) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return FA_ERR_ALIGN;
   if (workspace_bytes < ws_bytes(total_tokens, Hq, d)) return FA_ERR_WORKSPACE;
   return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, cu_seqlens, nseq, max_seqlen, max_seqlen, total_tokens, Hq,
-                 Hkv, d, scale, causal, 7, stream);
+                 Hkv, d, scale, causal, 7, stream, nullptr, opt);
+}
+
+int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                  void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, const int32_t* cu_seqlens,
+                  int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
+                  void* stream) {
+  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
+                    max_seqlen, Hq, Hkv, d, scale, causal, stream, Options());
+}
+
+int fa_varlen_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                          const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                          const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                          int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
+                    max_seqlen, Hq, Hkv, d, scale, causal, stream, with_dropout(p_drop, seed));
 }
 
 static int check_cross(int B, int Nq, int Nk, int causal) {
@@ -275,28 +327,6 @@ static int cross_bwd(const void* Q, const void* K, const void* V, const void* O,
   if (workspace_bytes < ws_bytes((long)B * Nq, Hq, d)) return FA_ERR_WORKSPACE;
   return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale,
                  causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream, nullptr, opt);
-}
-
-static Options half_precision(int f16) {
-  Options o;
-  o.f16 = f16;
-  return o;
-}
-static Options with_dropout(float p_drop, uint64_t seed) {
-  Options o;
-  o.dropout = true;
-  o.p_drop = p_drop;
-  o.seed = seed;
-  return o;
-}
-static Options with_mask(const void* M, long long bs, long long hs, long long rs) {
-  Options o;
-  o.mask = true;
-  o.M = M;
-  o.mask_bs = bs;
-  o.mask_hs = hs;
-  o.mask_rs = rs;
-  return o;
 }
 
 int fa_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,

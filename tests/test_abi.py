@@ -155,6 +155,18 @@ def test_dropout_entry_points_reject_bad_arguments():
     assert binding.fa_dropout_bwd_raw(*ptrs, P, 1 << 20, 1, 2, 2, 8, 128, 64, 0.125, 0, 1.5, 99, 0) == binding.FA_ERR_SHAPE
 
 
+def test_ragged_dropout_entry_points_reject_bad_arguments():
+    def run(Q=P, cu=P, p_drop=0.1, d=64, mx=8):
+        return binding.fa_varlen_dropout_fwd_raw(Q, P, P, P, P, cu, 2, 10, mx, 2, 2, d, 0.125, 1, p_drop, 5, 0)
+    assert run(Q=0) == binding.FA_ERR_NULL
+    assert run(cu=0) == binding.FA_ERR_NULL
+    assert run(p_drop=1.0) == binding.FA_ERR_SHAPE
+    assert run(mx=4) == binding.FA_ERR_SHAPE          # two sequences of at most 4 rows cannot hold 10
+    assert run(d=96) == binding.FA_ERR_UNSUPPORTED    # dropout: the two tile widths only
+    ptrs = [P] * 9
+    assert binding.fa_varlen_dropout_bwd_raw(*ptrs, P, 16, P, 2, 10, 8, 2, 2, 64, 0.125, 1, 0.1, 5, 0) == binding.FA_ERR_WORKSPACE
+
+
 def test_mask_entry_points_reject_bad_arguments():
     def run(Q=P, M=P, Nq=8, Nk=100, causal=0, d=64, bs=0, hs=0, rs=104):
         return binding.fa_mask_fwd_raw(Q, P, P, M, P, P, 1, 2, 2, Nq, Nk, d, 0.125, causal, bs, hs, rs, 0)

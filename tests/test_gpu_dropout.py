@@ -79,3 +79,24 @@ def test_kept_fraction_seen_through_the_output():
         keep = orc.dropout_keep(7, h, N, N, thr)
         want = keep.sum(axis=1) / (0.75 * N)
         assert np.max(np.abs(pu.to_f64(O[0, :, h, 0]) - want)) <= 2 * pu.bf16_ulp(float(want.max()))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 2, 2), (128, 4, 2)])
+def test_ragged_batches_with_dropout(d, Hq, Hkv, causal):
+    """fa_varlen_dropout_fwd / bwd against the oracle's ragged dropout: the generator counts rows and
+    columns from the start of each sequence and uses sequence * Hq + head as its head index."""
+    prob = inputs.make_varlen([100, 257, 1, 31, 300], Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=6100 + d)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
+    p_drop, seed = 0.25, 0x1234567890ABCDEF
+    O, L = binding.fa_varlen_dropout_fwd(Q, K, V, cu, 300, prob.scale, causal, p_drop, seed)
+    dQ, dK, dV = binding.fa_varlen_dropout_bwd(Q, K, V, O, dO, L, cu, 300, prob.scale, causal, p_drop, seed)
+    torch.cuda.synchronize()
+    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    eO, eL = orc.varlen_forward_dropout(Qf, Kf, Vf, prob.cu_seqlens, prob.scale, causal, p_drop, seed)
+    edQ, edK, edV = orc.varlen_backward_dropout(Qf, Kf, Vf, dOf, prob.cu_seqlens, prob.scale, causal, p_drop, seed)
+    rp = 1.0 / (1.0 - 0.25)
+    for nm, got, exp in (("O", O, eO), ("LSE", L, eL), ("dQ", dQ, edQ), ("dK", dK, edK), ("dV", dV, edV)):
+        err = pu.maxdiff(pu.to_f64(got), exp)
+        assert err <= pu.tolerance(nm, exp) * (1.0 if nm == "LSE" else rp), f"{nm}: {err:.3e}"

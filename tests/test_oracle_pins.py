@@ -856,3 +856,29 @@ def test_masked_batch_wrapper_shares_masks_over_batch_and_heads():
                 np.testing.assert_array_equal(dQ[b, :, h], dq)
                 dk_sum[:, h // 2] += dk
             np.testing.assert_allclose(dK[b], dk_sum, rtol=1e-13, atol=1e-14)
+
+
+def test_ragged_dropout_with_equal_lengths_is_the_dense_batch():
+    """The ragged wrappers reach the per-head functions by a different route than the dense ones;
+    with equal lengths both must drop the same entries (head index = sequence * Hq + head) and
+    agree everywhere. A different head index, or rows counted from the start of the packed batch,
+    would fail this."""
+    B, N, Hq, Hkv, d = 3, 7, 4, 2, 3
+    Q, K, V, dO = rnd(300, B, N, Hq, d), rnd(301, B, N, Hkv, d), rnd(302, B, N, Hkv, d), rnd(303, B, N, Hq, d)
+    cu = np.arange(B + 1) * N
+    flat = lambda x: x.reshape(B * N, x.shape[2], d)  # noqa: E731
+    for causal in (False, True):
+        O, L = orc.attention_forward_dropout(Q, K, V, 0.6, causal, 0.3, 77)
+        Or, Lr = orc.varlen_forward_dropout(flat(Q), flat(K), flat(V), cu, 0.6, causal, 0.3, 77)
+        np.testing.assert_array_equal(Or, flat(O))
+        np.testing.assert_array_equal(Lr, L.transpose(1, 0, 2).reshape(Hq, B * N))
+        g = orc.attention_backward_dropout(Q, K, V, dO, 0.6, causal, 0.3, 77)
+        gr = orc.varlen_backward_dropout(flat(Q), flat(K), flat(V), flat(dO), cu, 0.6, causal, 0.3, 77)
+        for x, y in zip(gr, g):
+            np.testing.assert_allclose(x, flat(y), rtol=1e-13, atol=1e-14)
+    # an empty sequence in the middle changes nothing for the others
+    cu2 = np.asarray([0, N, N, 2 * N, 3 * N])
+    O1, _ = orc.varlen_forward_dropout(flat(Q), flat(K), flat(V), cu, 0.6, False, 0.3, 77)
+    O2, _ = orc.varlen_forward_dropout(flat(Q), flat(K), flat(V), cu2, 0.6, False, 0.3, 77)
+    np.testing.assert_array_equal(O2[:N], O1[:N])
+    assert not np.array_equal(O2[N:2 * N], O1[N:2 * N])  # the later sequences moved on to other head indices
