@@ -44,6 +44,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 MEASURED_TRAFFIC = {
     "d128_n8k_causal": {"fwd_kernel": 644704547, "bwd_dkdv_kernel": 841273533, "bwd_dq_kernel": 739985828},
     "sweep_d128_n8192_full": {"fwd_kernel": 269992881, "bwd_dkdv_kernel": 417536429, "bwd_dq_kernel": 337870057},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 849614118, "bwd_dkdv_kernel": 884153408, "bwd_dq_kernel": 830965471},
     "decode_b8_on_8k": {"fwd_kernel": 288777216},  # split kernel + merge, profiles/bench_decode_b8_on_8k_kernel_stats.md
 }
 
