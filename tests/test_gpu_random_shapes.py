@@ -49,3 +49,15 @@ def test_random_ragged_batches(i):
     prob = inputs.make_varlen(lens, Hq=hkv * G, Hkv=hkv, d=int(g.choice([64, 128, 96])), causal=bool(i % 2),
                               seed=13100 + i)
     check(prob)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("qk_mult", [0.0, 8.0])
+def test_extreme_score_ranges(qk_mult, d, causal):
+    """Q = K = 0 (uniform attention: every exponent equal) and Q, K multiplied by 8 before the
+    rounding (scores of several hundred, a softmax that is almost one-hot, row maxima that keep
+    growing along the keys: the running reference is advanced many times)."""
+    prob = inputs.make_dense(B=1, N=700, Hq=2, Hkv=1, d=d, causal=causal, seed=14000 + d, qk_mult=qk_mult)
+    errs = check(prob, ref_compare=False)
+    assert errs["LSE"] <= 1e-3 * max(1.0, qk_mult)
