@@ -105,7 +105,7 @@ def test_packed_ragged_batch(d, Hq, Hkv, causal):
 
 def test_packed_ragged_equals_dense_calls_bitwise():
     """A packed batch of equal lengths must reproduce the dense entry point bit for bit
-    (forward and dK/dV are deterministic)."""
+    (every output is deterministic)."""
     prob = inputs.make_dense(B=3, N=200, Hq=4, Hkv=2, d=128, causal=True, seed=2600)
     dense = pu.run_hip(prob)
     packed = inputs.AttnProblem(name="packed", Q=prob.Q.reshape(600, 4, 128), K=prob.K.reshape(600, 2, 128),
@@ -117,16 +117,19 @@ def test_packed_ragged_equals_dense_calls_bitwise():
     assert torch.equal(dense["LSE"].permute(1, 0, 2).reshape(4, 600), rag["LSE"])
     assert torch.equal(dense["dK"].reshape(600, 2, 128), rag["dK"])
     assert torch.equal(dense["dV"].reshape(600, 2, 128), rag["dV"])
-    assert pu.maxdiff(pu.to_f64(dense["dQ"]).reshape(600, 4, 128), pu.to_f64(rag["dQ"])) <= 2e-2
+    assert torch.equal(dense["dQ"].reshape(600, 4, 128), rag["dQ"])
 
 
-def test_forward_and_dkdv_are_bit_reproducible():
-    prob = inputs.make_dense(B=2, N=333, Hq=4, Hkv=2, d=128, causal=True, seed=2700)
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_output_is_bit_reproducible(d):
+    """No output is accumulated by atomic adds (dQ comes from a row-block pass of its own instead
+    of section 3.2's atomic accumulation), so two runs on the same inputs agree bit for bit:
+    the deterministic backward."""
+    prob = inputs.make_dense(B=2, N=1333, Hq=4, Hkv=2, d=d, causal=True, seed=2700 + d)
     a = pu.run_hip(prob)
     b = pu.run_hip(prob)
-    for nm in ("O", "LSE", "dK", "dV"):
+    for nm in ("O", "LSE", "dQ", "dK", "dV"):
         assert torch.equal(a[nm], b[nm]), nm
-    assert pu.maxdiff(pu.to_f64(a["dQ"]), pu.to_f64(b["dQ"])) <= 1e-2
 
 
 def test_outputs_stay_inside_their_buffers():
