@@ -402,18 +402,21 @@ __global__ __launch_bounds__(512)
   }
   // (mask: a row without any key ends with l = 0: O = 0, L = -inf)
   const float inv = MASK && !(lsum > 0.f) ? 0.f : (DROPOUT ? p.drop_rp : 1.0f) / lsum;
-  if (row < n) {
-    __bf16* op = a.O + ((si.tok0 + row) * p.Hq + h) * dh + 4 * hh;
+  {
+    // O through the ring slot that neither holds a block still in use nor receives one of the
+    // copies issued past the last block (those fill the three slots after block ncol - 1)
+    static_assert(RING == 4 && BUFB / 8 == 32 * 32 * DT, "the staging area of a wavefront is an eighth of a ring slot");
+    char* stg = smem + ((ncol + 3) % RING) * BUFB + w * (BUFB / 8);
+    __bf16* op = a.O + ((si.tok0 + prow0) * p.Hq + h) * dh;
+    const long ostride = (long)p.Hq * dh;
+    int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop
+    asm volatile("" : "+v"(ln));
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        u32x2 o;
-        o[0] = pack2<F16>(O[dt][4 * r4 + 0] * inv, O[dt][4 * r4 + 1] * inv);
-        o[1] = pack2<F16>(O[dt][4 * r4 + 2] * inv, O[dt][4 * r4 + 3] * inv);
-        if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(op + 32 * dt + 8 * r4) = o;
-      }
-    if (hh == 0)
+    for (int half = 0; half < 2; ++half) {
+      store_rows_via_lds<DT / 2, F16>(stg, &O[half * (DT / 2)], inv, op + half * (D / 2), ostride, n - prow0,
+                                      dh - half * (D / 2), ln);
+    }
+    if (row < n && hh == 0)
       a.LSE[s * p.lse_seq_stride + h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + row] =
           MASK ? (lsum > 0.f ? m + fast_log2(lsum) * kLn2 : -INFINITY) : m * p.scale + fast_log2(lsum) * kLn2;
   }

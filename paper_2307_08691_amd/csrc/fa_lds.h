@@ -153,6 +153,41 @@ __device__ __forceinline__ void touch(const T& x) {
   asm volatile("" ::"v"(x));
 }
 
+// Write a wavefront's 32 rows x (32 NT) columns, held TRANSPOSED in accumulators (register r of
+// tile t in lane (lq, hh) is row lq, column 32 t + acc_row(r, hh)), to global memory as
+// 16-bit rows, scaled by the lane's row factor `mul`. Storing straight from that layout puts 16
+// bytes per row into every instruction (32 partly written cache lines each); going through a
+// wavefront-private LDS buffer `stg` (32 * 64 * NT bytes, chunks XOR-ed so that neither side
+// conflicts) turns it into whole rows: a quarter of the write requests. Rows >= nrows and columns >=
+// ncols (a multiple of 8) are not stored. Needs no barrier: only this wavefront touches `stg`.
+template <int NT, bool F16>
+__device__ __forceinline__ void store_rows_via_lds(char* stg, const f32x16* acc, float mul, __bf16* g, long gstride,
+                                                   int nrows, int ncols, int lane) {
+  constexpr int SROW = 64 * NT;      // bytes per staged row
+  constexpr int CPR = SROW / 16;     // 16-byte chunks per row
+  constexpr int RPB = 256 / SROW;    // rows per 256 bytes (one pass over the banks)
+  constexpr int RPI = 64 / CPR;      // rows per store instruction
+  const int lq = lane & 31, hh = lane >> 5;
+  char* wr = stg + lq * SROW + 8 * hh;
+  const int wx = (lq / RPB) & (CPR - 1);
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      u32x2 o;
+      o[0] = pack2<F16>(acc[t][4 * r4 + 0] * mul, acc[t][4 * r4 + 1] * mul);
+      o[1] = pack2<F16>(acc[t][4 * r4 + 2] * mul, acc[t][4 * r4 + 3] * mul);
+      *(u32x2*)(wr + 16 * ((4 * t + r4) ^ wx)) = o;
+    }
+  const int c = lane % CPR, rr = lane / CPR;
+#pragma unroll
+  for (int u = 0; u < 32 / RPI; ++u) {
+    const int row = RPI * u + rr;
+    const u32x4 v = *(const u32x4*)(stg + row * SROW + 16 * (c ^ ((row / RPB) & (CPR - 1))));
+    if (row < nrows && 8 * c < ncols) *(u32x4*)(g + row * gstride + 8 * c) = v;
+  }
+}
+
 // Issue-order hints for the machine scheduler (one scheduling group each, in program
 // order): without them the compiler tends to wait for every LDS operand right before
 // the MFMA that uses it, which exposes the LDS latency once per MFMA.
