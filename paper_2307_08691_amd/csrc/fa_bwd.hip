@@ -572,23 +572,17 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     end_matrix_phase();
     if (grp == 0) lds_barrier();  // group 1's last phase
 
-    // ---- write dK_j, dV_j (line 18); dK carries the scaling
-    if (key_ok) {
-#pragma unroll
-      for (int which = 0; which < 2; ++which) {
-        const f32x16* accs = which == 0 ? dKt : dVt;
-        __bf16* dst = (which == 0 ? a.dK : a.dV) + ((si.tok0k + key) * p.Hkv + g) * dh + 4 * hh;
-        const float mul = which == 0 ? p.scale : 1.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {
-            u32x2 o;
-            o[0] = pack2<F16>(accs[dt][4 * r4 + 0] * mul, accs[dt][4 * r4 + 1] * mul);
-            o[1] = pack2<F16>(accs[dt][4 * r4 + 2] * mul, accs[dt][4 * r4 + 3] * mul);
-            if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(dst + 32 * dt + 8 * r4) = o;
-          }
-      }
+    // ---- write dK_j, dV_j (line 18); dK carries the scaling. The ring is idle now (no copy is
+    // requested past the last tile): each wavefront stages its rows there and stores whole rows.
+    {
+      static_assert(RING * BUFB >= 8 * 32 * ROWB, "the ring holds one 32-key tile per wavefront");
+      char* stg = smem + QDO_OFF + v * (32 * ROWB);
+      const int key0 = j0 + 32 * kgi;
+      const long kvoff = ((si.tok0k + key0) * p.Hkv + g) * dh;
+      int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop
+      asm volatile("" : "+v"(ln));
+      store_rows_via_lds<DT, F16>(stg, dKt, p.scale, a.dK + kvoff, (long)p.Hkv * dh, nk - key0, dh, ln);
+      store_rows_via_lds<DT, F16>(stg, dVt, 1.f, a.dV + kvoff, (long)p.Hkv * dh, nk - key0, dh, ln);
     }
     return;
   }
@@ -908,18 +902,19 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     }
   }
 
-  if (row < n) {
-    __bf16* op = a.dQ + ((si.tok0 + row) * p.Hq + h) * dh + 4 * hh;
-    const float sc = p.scale;
+  {
+    // dQ_i through the one ring slot that is neither in use nor the target of a copy issued
+    // past the last block, as whole rows (see store_rows_via_lds)
+    static_assert(RING == 4 && BUFB / 8 == 32 * 32 * DT, "the staging area of a wavefront is an eighth of a ring slot");
+    char* stg = smem + ((ncol + 3) % RING) * BUFB + w * (BUFB / 8);
+    __bf16* op = a.dQ + ((si.tok0 + wrow0) * p.Hq + h) * dh;
+    const long ostride = (long)p.Hq * dh;
+    int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop
+    asm volatile("" : "+v"(ln));
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        u32x2 o;
-        o[0] = pack2<F16>(dQt[dt][4 * r4 + 0] * sc, dQt[dt][4 * r4 + 1] * sc);
-        o[1] = pack2<F16>(dQt[dt][4 * r4 + 2] * sc, dQt[dt][4 * r4 + 3] * sc);
-        if (!PAD || 32 * dt + 8 * r4 + 4 * hh < dh) *(u32x2*)(op + 32 * dt + 8 * r4) = o;
-      }
+    for (int half = 0; half < 2; ++half)
+      store_rows_via_lds<DT / 2, F16>(stg, &dQt[half * (DT / 2)], p.scale, op + half * (D / 2), ostride, n - wrow0,
+                                      dh - half * (D / 2), ln);
   }
 }
 
