@@ -26,6 +26,8 @@
 //
 // K_j and V_j travel HBM -> LDS directly (no registers), two blocks ahead, into a
 // ring of four swizzled (unpadded) buffers shared by all eight wavefronts.
+#include <type_traits>
+
 #include "fa_common.h"
 #include "fa_kernels.h"
 #include "fa_lds.h"
@@ -57,6 +59,11 @@ namespace fa {
 // registers) or the elementwise mask (more LDS).
 #ifndef FA_FWD_TWO_PER_CU
 #define FA_FWD_TWO_PER_CU 1
+#endif
+// d = 128: workgroups that take several items in a row and overlap an item's start-up with
+// the end of the one before (fwd_chain_kernel)
+#ifndef FA_FWD_CHAIN
+#define FA_FWD_CHAIN 1
 #endif
 constexpr bool fwd_two_per_cu(int D, bool dropout, bool mask) { return FA_FWD_TWO_PER_CU && D == 64 && !dropout && !mask; }
 
@@ -422,6 +429,309 @@ __global__ __launch_bounds__(512)
   }
 }
 
+// The same forward pass for a workgroup that takes `chain` items (row block, head, sequence)
+// one after the other, d = 128, dense batches, no options. A workgroup's start-up (Q_i and the
+// first two K/V tiles: a memory latency of several microseconds during which the matrix pipe
+// idles) cannot be overlapped by a second resident workgroup here (128 KiB of LDS, 190
+// registers), so the workgroup overlaps it with its own previous item: the three tile copies
+// that every wavefront issues past an item's last block anyway fetch the NEXT item's first two
+// tiles instead (the ring just keeps turning: an item's block j lives in slot (j + rb) % 4),
+// and the next Q_i is requested into spare registers two blocks before the end. When the last
+// barrier of an item falls, everything the next item's first phase reads is already in place.
+//
+// Items: an XCD's list is the one block_coord walks (under the mask heaviest row blocks
+// first); workgroup k of the XCD's W takes positions k, 2W-1-k, 2W+k, 4W-1-k, ...: every
+// workgroup gets the same amount of work whenever the chain length is even.
+template <int D, bool CAUSAL, bool F16>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_chain_kernel(FwdArgs a, int chain) {
+  constexpr int AHEAD_QK = FA_FWD_AHEAD_QK, AHEAD_PV = FA_FWD_AHEAD_PV;
+  constexpr int BR = 256, BC = 64, RING = 4;
+  constexpr int KS = D / 16, DT = D / 32, ROWB = 2 * D;
+  constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
+
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB];
+
+  const Problem& p = a.p;
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = w >> 2;
+  // Everything derived from the lane index is recomputed at the start of every item from a copy
+  // the optimiser cannot see through: it would otherwise hoist the loop invariants of BOTH
+  // groups' loops (LDS addresses by the dozen) out of the item loop, where they are all live at
+  // once, and run out of registers.
+  int lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+  // dense batch: every item has the same lengths
+  const int n = p.N, nk = p.Nk, off = nk - n;
+  const int nblk = (n + BR - 1) / BR;
+  const int ncol_all = (nk + BC - 1) / BC;
+  const long kstride = (long)p.Hkv * D, qstride = (long)p.Hq * D;
+
+  // ---- items of this workgroup
+  const int xcd = blockIdx.x % kXcds, kq = blockIdx.x / kXcds;
+  const int wpx = gridDim.x / kXcds;            // workgroups per XCD
+  const int ppx = p.Hq * p.nseq / kXcds;        // (head, sequence) pairs per XCD (the launch makes it exact)
+  struct Item {
+    const __bf16 *Kb, *Vb;
+    int h, s, prow0, ncol;
+  };
+  auto locate = [&](int i) {
+    const int pos = i * wpx + ((i & 1) ? wpx - 1 - kq : kq);
+    int blk, pl;
+    if (CAUSAL) {
+      blk = pos / ppx;
+      pl = pos % ppx;
+    } else {
+      blk = pos % nblk;
+      pl = pos / nblk;
+    }
+    const int pr = pl * kXcds + xcd;
+    Item it;
+    it.h = pr % p.Hq;
+    it.s = pr / p.Hq;
+    const int i0 = (nblk - 1 - blk) * BR;
+    it.prow0 = i0 + 32 * w;
+    it.ncol = ncol_all;
+    if (CAUSAL) {
+      const int last_pos = (i0 + BR < n ? i0 + BR : n) - 1 + off;
+      const int c = last_pos / BC + 1;
+      it.ncol = c < ncol_all ? c : ncol_all;
+    }
+    const long kv = ((long)it.s * nk * p.Hkv + it.h / p.G) * D;
+    it.Kb = a.K + kv;
+    it.Vb = a.V + kv;
+    return it;
+  };
+  auto q_address = [&](const Item& it) {
+    const int row = it.prow0 + lq;
+    const int rowc = row < n ? row : n - 1;  // rows past the end compute on a copy and are never stored
+    return a.Q + (((long)it.s * n + rowc) * p.Hq + it.h) * D + 8 * hh;
+  };
+
+  Item cur = locate(0), nxt = cur;
+  bool has_next = false;
+  int rb = 0;       // ring slot of the current item's block 0
+  int fwd_end = 0;  // blocks cur.ncol .. fwd_end - 1 of the current item are the next item's first blocks
+  int jq = -8;      // the block after whose score product the next Q_i is requested: the item's last, if it has a successor
+
+  u32x4 Qf[KS];
+  {
+    const __bf16* qp = q_address(cur);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) Qf[ks] = *(const u32x4*)(qp + 16 * ks);
+  }
+  // The next item's Q_i goes straight into the registers of the current one, as soon as the
+  // current item's last score product has been issued (its last matrix phase only updates O).
+  auto request_next_q = [&]() {
+    const __bf16* qp = q_address(nxt);
+    load16_async<0>(Qf[0], qp);
+    load16_async<32>(Qf[1], qp);
+    load16_async<64>(Qf[2], qp);
+    load16_async<96>(Qf[3], qp);
+    if constexpr (KS == 8) {
+      load16_async<128>(Qf[4], qp);
+      load16_async<160>(Qf[5], qp);
+      load16_async<192>(Qf[6], qp);
+      load16_async<224>(Qf[7], qp);
+    }
+  };
+
+  // Tile copies as in fwd_kernel (group 1 the K tiles, group 0 the V tiles, two blocks ahead,
+  // exactly TPW copies per wavefront and vector phase). Blocks ncol and ncol + 1 of an item that
+  // has a successor are the successor's blocks 0 and 1; block ncol + 2 (and every block past the
+  // end of the last item) is a clamped copy that nobody reads.
+  TileLoader<D, BC, 4, false> loader;
+  loader.init(kstride, w & 3, lane, D / 8);
+  int zrow, zcol[2];  // lane constants of the LDS addressing (see fa_lds.h)
+  auto lane_constants = [&]() {
+    lane = tid & 63;
+    asm volatile("" : "+v"(lane));
+    lq = lane & 31;
+    hh = lane >> 5;
+    loader.init(kstride, w & 3, lane, D / 8);
+    zrow = lq * ROWB + 16 * (hh ^ swz<ROWB>(lq));
+    const int p16 = lane & 15, g16 = (lane >> 4) & 1;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
+  };
+  constexpr int TPW = TileLoader<D, BC, 4, false>::PER;
+  auto issue_tile = [&](int j) {
+    char* dst = smem + ((j + rb) % RING) * BUFB + (grp == 0 ? TILEB : 0);
+    const bool fwd_ = j >= cur.ncol && j < fwd_end;
+    const __bf16* base = fwd_ ? (grp == 0 ? nxt.Vb : nxt.Kb) : (grp == 0 ? cur.Vb : cur.Kb);
+    loader.load(dst, base, kstride, (fwd_ ? j - cur.ncol : j) * BC, nk - 1, w & 3, lane);
+  };
+  issue_tile(0);
+  issue_tile(1);
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
+  wait_vmem();
+  lds_barrier();
+
+  const float c2 = p.scale_log2e;
+
+  // (one copy of the item loop per group, so that what the optimiser hoists out of one group's
+  // loops is not live in the other's)
+  auto run_items = [&](auto group) {
+  constexpr int GRP = decltype(group)::value;
+  for (int it = 0;; ++it) {
+  f32x16 O[DT];
+  float m, l;
+  f32x16 S[2];
+  bf16x8 Pf[2][2];
+  int wrow_last, lim_row;  // position of the wavefront's last query among the keys; last visible column of this lane's row
+
+  auto matrix_phase = [&](int j) {
+    __builtin_amdgcn_s_setprio(FA_FWD_MATRIX_PRIO);
+    if (j < cur.ncol && (!CAUSAL || j * BC <= wrow_last)) {  // S^T = K_j Q_i^T (Algorithm 1, line 8)
+      const int zk = zrow + ((j + rb) % RING) * BUFB;
+      S[0] = S[1] = (f32x16){0};
+      mfma_stream<2 * KS, AHEAD_QK, 1>(
+          [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
+          [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, __builtin_bit_cast(bf16x8, Qf[i >> 1]), S[i & 1]); });
+    }
+    if (j > 0 && (!CAUSAL || (j - 1) * BC <= wrow_last)) {  // O^T += V_{j-1}^T P^T (line 10)
+      const int vb = ((j - 1 + rb) % RING) * BUFB + TILEB;
+      const int zv0 = zcol[0] + vb, zv1 = zcol[1] + vb;
+      mfma_stream<4 * DT, AHEAD_PV, 2>(
+          [&](int i) {
+            const int dt = i >> 2, ro = (16 * (i & 3)) * ROWB;
+            return lds_tr_pair(smem, (zv0 ^ (64 * dt)) + ro, (zv1 ^ (64 * dt)) + ro);
+          },
+          [&](int i, bf16x8 x) { O[i >> 2] = mfma32<F16>(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+
+  auto vector_phase = [&](int j) {  // online softmax of block j (line 9), as in fwd_kernel
+    if (j >= cur.ncol || (CAUSAL && j * BC > wrow_last)) return;
+    const int col0 = j * BC;
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > cur.prow0 + off) || (col0 + BC > nk);
+    if (need_mask) {
+      asm volatile("; keep this a branch: the mask costs two instructions per element" ::);
+      const int lim = lim_row - col0 - 4 * hh;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : S[kt][r];
+    }
+    float mx = max3(S[0][0], S[0][1], S[1][0]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
+    mx = max3(mx, S[1][1], S[1][2]);
+    mx = fmaxf(mx, S[1][3]);
+#pragma unroll
+    for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
+    mx = max_with_partner32(mx);
+    const float m_new = fmaxf(m, mx);
+    if (__builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)FA_FWD_LAZY_LOG2) != 0) {  // lazy rescale, see fwd_kernel
+      const float alpha = fast_exp2((m - m_new) * c2);
+      l *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+      m = m_new;
+    }
+    const float mc = m * c2;
+    float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], c2, -mc));
+        const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -mc));
+        S[kt][r] = e0;
+        S[kt][r + 1] = e1;
+        rs0 += e0;
+        rs1 += e1;
+      }
+      Pf[kt][0] = pack8<F16>(S[kt], 0);
+      Pf[kt][1] = pack8<F16>(S[kt], 1);
+    }
+    l += rs0 + rs1;
+  };
+
+    lane_constants();
+    has_next = it + 1 < chain;
+    if (has_next) nxt = locate(it + 1);
+    const int ncol = cur.ncol;
+    // (kept as numbers compared with j rather than as flags, and opaque to the optimiser: it would
+    // otherwise build every loop twice, with and without a successor, and run out of registers)
+    fwd_end = has_next ? ncol + 2 : ncol;
+    jq = has_next ? ncol - 1 : -8;
+    asm volatile("" : "+s"(fwd_end), "+s"(jq));
+    {
+      const int row = cur.prow0 + lq;
+      wrow_last = cur.prow0 + 31 + off;
+      lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] = (f32x16){0};
+    m = -INFINITY;
+    l = 0.f;
+
+    // Phases as in fwd_kernel. Per wavefront the copies end in the order: block ncol + 1 (the
+    // next item's block 1), the KS loads of the next Q_i, block ncol + 2 (read by nobody). The
+    // waits of the last two blocks let the newer of these stay in flight; the wait after the last
+    // barrier completes all but the newest TPW, i.e. everything the next item reads.
+    constexpr int LATE = 2 * TPW + KS;
+    if constexpr (GRP == 0) {
+      for (int j = 0; j <= ncol; ++j) {
+        matrix_phase(j);
+        lds_barrier();
+        issue_tile(j + 2);
+        if (j == jq) request_next_q();
+        vector_phase(j);
+        if (j == jq) wait_vmem_upto<TPW + KS>();
+        else if (j == jq + 1) wait_vmem_upto<LATE>();
+        else wait_vmem_upto<TPW>();
+        lds_barrier();
+      }
+    } else {
+      issue_tile(2);
+      lds_barrier();
+      for (int j = 0; j <= ncol; ++j) {
+        matrix_phase(j);
+        if (j == jq + 1) wait_vmem_upto<LATE>();
+        else wait_vmem_upto<TPW>();
+        lds_barrier();
+        if (j < ncol) {
+          if (j == jq) request_next_q();
+          issue_tile(j + 3);
+          vector_phase(j);
+          lds_barrier();
+        }
+      }
+    }
+    wait_vmem_upto<TPW>();
+
+    // ---- epilogue of this item (lines 12-15); the next item's first tiles and Q_i are in place
+    {
+      const float lsum = sum_with_partner32(l);
+      const float inv = 1.0f / lsum;
+      char* stg = smem + ((ncol + 3 + rb) % RING) * BUFB + w * (BUFB / 8);
+      __bf16* op = a.O + (((long)cur.s * n + cur.prow0) * p.Hq + cur.h) * D;
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+        store_rows_via_lds<DT / 2, F16>(stg, &O[half * (DT / 2)], inv, op + half * (D / 2), qstride, n - cur.prow0, D / 2, lane);
+      const int row = cur.prow0 + lq;
+      if (row < n && hh == 0)
+        a.LSE[cur.s * p.lse_seq_stride + cur.h * p.lse_head_stride + row] = m * p.scale + fast_log2(lsum) * kLn2;
+    }
+    // (before the exit test, so that in the compiler's output every path from the loads of the
+    // next Q_i passes this point: that is what the host-side check of the assembly relies on)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) landed(Qf[ks]);
+    if (!has_next) break;
+    rb = (rb + ncol) % RING;
+    cur = nxt;
+  }
+  };
+  if (grp == 0) run_items(std::integral_constant<int, 0>{});
+  else run_items(std::integral_constant<int, 1>{});
+}
+
 // Combine the partial results of the key shares: one thread per 4 output elements.
 template <int D, bool F16>
 __global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
@@ -485,6 +795,25 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
       if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, true>), grid, block, 0, st, a);
       else hipLaunchKernelGGL((fwd_kernel<D, false, false, false, true>), grid, block, 0, st, a);
       return hipGetLastError();
+    }
+  }
+  if constexpr (D == 128 && FA_FWD_CHAIN) {
+    // chained items (fwd_chain_kernel): dense batches of short sequences (at most 16 key blocks:
+    // +15% at N = 512; from N = 2048 on the start-up no longer matters and the fixed assignment
+    // of items loses against the hardware's dynamic one, -5% at N = 8192 under the mask) whose
+    // items split evenly over the XCDs and into chains of even length, with at least one
+    // workgroup left per compute unit
+    const int pairs = a.p.Hq * a.p.nseq, nblk = (a.p.N + 255) / 256;
+    if (!a.p.cu_seqlens && pairs % kXcds == 0 && a.p.N >= 256 && a.p.Nk >= a.p.N && a.p.Nk <= 1024) {
+      const int items = pairs / kXcds * nblk;  // per XCD
+      int chain = items % 8 == 0 ? 8 : items % 4 == 0 ? 4 : items % 2 == 0 ? 2 : 1;
+      while (chain > 1 && items / chain < 32) chain /= 2;
+      if (chain > 1) {
+        dim3 cgrid((unsigned)(kXcds * (items / chain)));
+        if (causal) hipLaunchKernelGGL((fwd_chain_kernel<D, true, F16>), cgrid, block, 0, st, a, chain);
+        else hipLaunchKernelGGL((fwd_chain_kernel<D, false, F16>), cgrid, block, 0, st, a, chain);
+        return hipGetLastError();
+      }
     }
   }
   if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16>), grid, block, 0, st, a);

@@ -153,6 +153,21 @@ __device__ __forceinline__ void touch(const T& x) {
   asm volatile("" ::"v"(x));
 }
 
+// 16 bytes per lane from global memory into registers, hidden from the compiler's own
+// bookkeeping of loads in flight (it would wait for them with vmcnt(0), which also waits for
+// every direct-to-LDS copy in flight). The value may only be used after a hand-written wait
+// that covers the load, and only through landed(), which pins the first use behind that wait.
+// (dst is declared read-write so that the new value takes the old one's registers: reloading a
+// long-lived operand in place then costs neither registers nor copies.)
+template <int OFF>
+__device__ __forceinline__ void load16_async(u32x4& dst, const void* gaddr) {
+  asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "+v"(dst) : "v"(gaddr), "n"(OFF) : "memory");
+}
+template <class T>
+__device__ __forceinline__ void landed(T& x) {
+  asm volatile("; landed %0" : "+v"(x));  // (the comment lets a checker of the compiler's output find this place)
+}
+
 // Write a wavefront's 32 rows x (32 NT) columns, held TRANSPOSED in accumulators (register r of
 // tile t in lane (lq, hh) is row lq, column 32 t + acc_row(r, hh)), to global memory as
 // 16-bit rows, scaled by the lane's row factor `mul`. Storing straight from that layout puts 16

@@ -68,6 +68,24 @@ def test_dense_workloads_sampled_units(name):
     print(name, check_units(prob, got, units))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,Nq,Nk,Hq,Hkv", [(4, 512, 512, 64, 64), (2, 1000, 1000, 64, 16), (8, 512, 512, 64, 8),
+                                            (16, 300, 300, 64, 64), (2, 1024, 1024, 64, 64), (4, 512, 777, 64, 16)])
+def test_short_sequences_in_chained_workgroups(B, Nq, Nk, Hq, Hkv, causal, dtype):
+    """Dense d = 128 batches of short sequences whose forward pass runs in workgroups that take
+    2, 4 or 8 (row block, head, sequence) items in a row, fetching an item's Q_i and first tiles
+    while the previous one finishes: units from both ends and the middle of the batch, which sit
+    at different places of different chains; ragged last row blocks (N = 1000, 300); more keys
+    than queries."""
+    prob = inputs.make_cross(B=B, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=128, causal=causal, seed=15000 + Nq + Hkv, dtype=dtype)
+    got = pu.run_hip(prob)
+    for nm, t in got.items():
+        assert torch.isfinite(t.float()).all(), nm
+    units = [(0, 0), (B // 2, Hkv // 2), (B - 1, Hkv - 1), (B - 1, 0), (0, Hkv - 1)]
+    print(prob.name, check_units(prob, got, units))
+
+
 def test_long_context_wide_range_sampled_units():
     prob = inputs.make_config("long_n16k_causal_x3")
     got = pu.run_hip(prob)
