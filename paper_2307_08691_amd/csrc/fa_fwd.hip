@@ -65,6 +65,12 @@ namespace fa {
 #ifndef FA_FWD_CHAIN
 #define FA_FWD_CHAIN 1
 #endif
+#ifndef FA_FWD_CHAIN_MAXN
+#define FA_FWD_CHAIN_MAXN 1024
+#endif
+#ifndef FA_FWD_CHAIN_LONG
+#define FA_FWD_CHAIN_LONG 8
+#endif
 constexpr bool fwd_two_per_cu(int D, bool dropout, bool mask) { return FA_FWD_TWO_PER_CU && D == 64 && !dropout && !mask; }
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
@@ -804,9 +810,10 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     // items split evenly over the XCDs and into chains of even length, with at least one
     // workgroup left per compute unit
     const int pairs = a.p.Hq * a.p.nseq, nblk = (a.p.N + 255) / 256;
-    if (!a.p.cu_seqlens && pairs % kXcds == 0 && a.p.N >= 256 && a.p.Nk >= a.p.N && a.p.Nk <= 1024) {
+    if (!a.p.cu_seqlens && pairs % kXcds == 0 && a.p.N >= 256 && a.p.Nk >= a.p.N && a.p.Nk <= FA_FWD_CHAIN_MAXN) {
       const int items = pairs / kXcds * nblk;  // per XCD
       int chain = items % 8 == 0 ? 8 : items % 4 == 0 ? 4 : items % 2 == 0 ? 2 : 1;
+      if (a.p.Nk > 1024 && chain > FA_FWD_CHAIN_LONG) chain = FA_FWD_CHAIN_LONG;
       while (chain > 1 && items / chain < 32) chain /= 2;
       if (chain > 1) {
         dim3 cgrid((unsigned)(kXcds * (items / chain)));
