@@ -42,9 +42,9 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 # under profiles/pmc_<workload>_kernels.md, already scaled by the copy-kernel factors given there.
 # A counter pass cannot run inside this script; workloads without a recorded pass report null.
 MEASURED_TRAFFIC = {
-    "d128_n8k_causal": {"fwd_kernel": 644704547, "bwd_dkdv_kernel": 841273533, "bwd_dq_kernel": 739985828},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269992881, "bwd_dkdv_kernel": 417536429, "bwd_dq_kernel": 337870057},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 849614118, "bwd_dkdv_kernel": 884153408, "bwd_dq_kernel": 830965471},
+    "d128_n8k_causal": {"fwd_kernel": 647689454, "bwd_dkdv_kernel": 828062947, "bwd_dq_kernel": 740116376},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269784965, "bwd_dkdv_kernel": 405079995, "bwd_dq_kernel": 337935017},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 884646395, "bwd_dkdv_kernel": 879984373, "bwd_dq_kernel": 830892697},
     "decode_b8_on_8k": {"fwd_kernel": 288777216},  # split kernel + merge, profiles/bench_decode_b8_on_8k_kernel_stats.md
 }
 
