@@ -26,6 +26,10 @@
 //
 // K_j and V_j travel HBM -> LDS directly (no registers), two blocks ahead, into a
 // ring of four swizzled (unpadded) buffers shared by all eight wavefronts.
+//
+// Two kernels: fwd_kernel (every option: split keys, half precision, dropout, padded head
+// dimension, elementwise mask) and fwd_chain_kernel (d = 128, short dense sequences: several
+// row blocks per workgroup, each one's start-up hidden behind the previous one's last blocks).
 #include <type_traits>
 
 #include "fa_common.h"
