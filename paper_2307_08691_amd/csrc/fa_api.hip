@@ -13,12 +13,13 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // any_d: the entry point also takes head dimensions that the kernels pad on chip
-// (multiples of 8 up to 128); otherwise only the two tile widths themselves.
+// (multiples of 8 up to 128) and 256, which has kernels of its own; otherwise only the two
+// tile widths 64 and 128 themselves.
 int check_common(int Hq, int Hkv, int d, float scale, bool any_d = true) {
   if (Hq <= 0 || Hkv <= 0 || d <= 0) return FA_ERR_SHAPE;
   if (Hq % Hkv != 0) return FA_ERR_SHAPE;
   if (!(scale > 0.f) || !std::isfinite(scale)) return FA_ERR_SHAPE;
-  if (any_d ? (d % 8 != 0 || d > 128) : (d != 64 && d != 128)) return FA_ERR_UNSUPPORTED;
+  if (any_d ? ((d % 8 != 0 || d > 128) && d != 256) : (d != 64 && d != 128)) return FA_ERR_UNSUPPORTED;
   return FA_OK;
 }
 

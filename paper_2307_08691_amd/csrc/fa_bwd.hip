@@ -990,6 +990,16 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
 }
 
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st) {
+  if (d == 256) {  // the D pre-pass is the generic one, the two kernels live in fa_d256.hip
+    if (stages & 1) {
+      const long nrows = (long)a.p.total_tokens * a.p.Hq;
+      constexpr int RPB = 256 / (256 / 8);
+      if (a.p.f16) hipLaunchKernelGGL((bwd_prep_kernel<256, true>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((bwd_prep_kernel<256, false>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
+      if (hipError_t e = hipGetLastError()) return e;
+    }
+    return launch_bwd256(a, causal, stages, st);
+  }
   if (a.p.f16) return d <= 64 ? launch_bwd_d<64, true>(a, causal, stages, st) : launch_bwd_d<128, true>(a, causal, stages, st);
   return d <= 64 ? launch_bwd_d<64, false>(a, causal, stages, st) : launch_bwd_d<128, false>(a, causal, stages, st);
 }

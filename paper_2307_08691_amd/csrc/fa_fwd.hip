@@ -833,6 +833,7 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st) {
+  if (d == 256) return launch_fwd256(a, causal, st);
   // tile width: the head dimension padded up to 64 or 128
   if (a.p.f16) return d <= 64 ? launch_fwd_d<64, true>(a, causal, st) : launch_fwd_d<128, true>(a, causal, st);
   return d <= 64 ? launch_fwd_d<64, false>(a, causal, st) : launch_fwd_d<128, false>(a, causal, st);

@@ -70,7 +70,8 @@ def test_fwd_rejects_bad_arguments():
     assert fwd(scale=float("inf")) == binding.FA_ERR_SHAPE
     assert fwd(d=100) == binding.FA_ERR_UNSUPPORTED  # not a multiple of 8
     assert fwd(d=136) == binding.FA_ERR_UNSUPPORTED
-    assert fwd(d=256) == binding.FA_ERR_UNSUPPORTED
+    assert fwd(d=192) == binding.FA_ERR_UNSUPPORTED  # above 128 only 256 has kernels
+    assert fwd(d=264) == binding.FA_ERR_UNSUPPORTED
     assert fwd(K=P + 2) == binding.FA_ERR_ALIGN
     assert fwd(O=P + 8) == binding.FA_ERR_ALIGN
 

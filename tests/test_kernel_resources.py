@@ -4,7 +4,7 @@
 Spills are more than a speed matter here. The kernels order their direct-to-LDS copies by
 counting outstanding vector-memory instructions (s_waitcnt vmcnt(n)); a spill store completes
 out of order with respect to loads and would make such a count pass early, and a spill reload
-makes the compiler wait for every copy in flight. The check compiles the two kernel files for
+makes the compiler wait for every copy in flight. The check compiles the kernel files for
 gfx950 with the flags of the build and reads the compiler's resource remarks (no GPU needed)."""
 import concurrent.futures
 import os
@@ -35,14 +35,15 @@ def resource_remarks(source):
 
 @pytest.fixture(scope="module")
 def remarks():
-    with concurrent.futures.ThreadPoolExecutor(2) as ex:
-        a, b = ex.map(resource_remarks, ["fa_fwd.hip", "fa_bwd.hip"])
-    return {**a, **b}
+    with concurrent.futures.ThreadPoolExecutor(3) as ex:
+        a, b, c = ex.map(resource_remarks, ["fa_fwd.hip", "fa_bwd.hip", "fa_d256.hip"])
+    return {**a, **b, **c}
 
 
 def test_every_kernel_was_seen(remarks):
     names = " ".join(remarks)
-    for k in ("fwd_kernel", "fwd_merge_kernel", "bwd_prep_kernel", "bwd_dkdv_kernel", "bwd_dq_kernel"):
+    for k in ("fwd_kernel", "fwd_chain_kernel", "fwd_merge_kernel", "bwd_prep_kernel", "bwd_dkdv_kernel", "bwd_dq_kernel",
+              "fwd256_kernel", "dkdv256_kernel", "dq256_kernel"):
         assert k in names
     assert len(remarks) >= 60  # every instantiation reports
 
