@@ -24,10 +24,11 @@
  *         K, V, dK, dV : [T, Hkv, d]
  *         LSE          : [Hq, T]
  *   - Supported: d a multiple of 8, 8 <= d <= 128 (section 3.3 names 64-128 as the
- *     usual range). The kernels work on tiles 64 or 128 wide: other head dimensions
- *     are padded with zeros on chip (memory holds exactly d elements per row, nothing
- *     is read or written past them) and cost as much as the next tile width. The
- *     dropout and split-key entry points take d in {64, 128} only. Hq a positive
+ *     usual range), and d = 256. Up to 128 the kernels work on tiles 64 or 128 wide:
+ *     other head dimensions are padded with zeros on chip (memory holds exactly d
+ *     elements per row, nothing is read or written past them) and cost as much as the
+ *     next tile width. d = 256 has kernels of its own. The dropout, mask and split-key
+ *     entry points take d in {64, 128} only. Hq a positive
  *     multiple of Hkv (grouped-query
  *     attention: query head h reads key/value head h / (Hq/Hkv), paragraph
  *     "Multi-query attention and grouped-query attention" of section 3.1);
@@ -56,7 +57,7 @@ extern "C" {
 #define FA_ERR_NULL (-1)        /* a required pointer is NULL */
 #define FA_ERR_SHAPE (-2)       /* non-positive dimension, Hq % Hkv != 0, scale <= 0 or not finite,
                                    inconsistent ragged description */
-#define FA_ERR_UNSUPPORTED (-3) /* head dim not a multiple of 8 in 8 .. 128 (dropout, split keys: not 64 or 128) */
+#define FA_ERR_UNSUPPORTED (-3) /* head dim neither a multiple of 8 in 8 .. 128 nor 256 (dropout, mask, split keys: not 64 or 128) */
 #define FA_ERR_ALIGN (-4)       /* a tensor pointer is not 16-byte aligned */
 #define FA_ERR_WORKSPACE (-5)   /* workspace smaller than fa_*_workspace_bytes() */
 #define FA_ERR_LAUNCH (-6)      /* the HIP runtime refused a launch; see fa_last_hip_error() */

@@ -188,6 +188,9 @@ CONFIGS = {
     # head dimensions that the kernels pad on chip, 16k tokens and about 2048 hidden units
     "d96_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=20, Hkv=20, d=96, causal=True, seed=1011),
     "d32_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=64, Hkv=64, d=32, causal=True, seed=1012),
+    "d256_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=8, Hkv=8, d=256, causal=True, seed=1014),
+    "d256_n8k_full": dict(kind="dense", B=2, N=8192, Hq=8, Hkv=8, d=256, causal=False, seed=1015),
+    "d256_n2k_causal": dict(kind="dense", B=8, N=2048, Hq=8, Hkv=8, d=256, causal=True, seed=1016),
 }
 
 
