@@ -47,8 +47,9 @@ struct LaneAddr {
 template <bool CAUSAL, bool F16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void fwd256_kernel(FwdArgs a) {
   constexpr int D = 256, BR = 128, BC = 64, KS = D / 16, DT = D / 32;
-  constexpr int HALFB = BC * kRowB, STAGEB = 4 * HALFB;
-  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGEB];
+  constexpr int HALFB = BC * kRowB, TILEB = 2 * HALFB;  // one K_j or V_j: left | right
+  constexpr int KSTAGES = 3, V_OFF = KSTAGES * TILEB;     // K_j: three stages, V_j: two (160 KiB in all)
+  __shared__ __attribute__((aligned(1024))) char smem[V_OFF + 2 * TILEB];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -93,16 +94,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   TileLoader<kHalf, BC, 4, false> loader;
   loader.init(kstride, w, lane, kHalf / 8);
-  constexpr int CPB = 4 * TileLoader<kHalf, BC, 4, false>::PER;  // copies per wavefront and block
-  auto issue_block = [&](int j) {
-    char* st = smem + (j & 1) * STAGEB;
+  // Copies: K_j is requested two blocks ahead, V_j one (it is needed only after the softmax).
+  // Every iteration issues the same number of copies, past the end too (rows are clamped, the
+  // data is never read), in the order V_{j+1}, K_{j+2}, so that the waits can count.
+  constexpr int CPT = 2 * TileLoader<kHalf, BC, 4, false>::PER;  // copies per wavefront and tile
+  auto issue_k = [&](int j) {
+    char* st = smem + (j % KSTAGES) * TILEB;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      loader.load(st + half * HALFB, Kb + half * kHalf, kstride, j * BC, nk - 1, w, lane);
-      loader.load(st + (2 + half) * HALFB, Vb + half * kHalf, kstride, j * BC, nk - 1, w, lane);
-    }
+    for (int half = 0; half < 2; ++half) loader.load(st + half * HALFB, Kb + half * kHalf, kstride, j * BC, nk - 1, w, lane);
   };
-  issue_block(0);
+  auto issue_v = [&](int j) {
+    char* st = smem + V_OFF + (j & 1) * TILEB;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) loader.load(st + half * HALFB, Vb + half * kHalf, kstride, j * BC, nk - 1, w, lane);
+  };
+  issue_k(0);
+  issue_v(0);
+  issue_k(1);
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
 
@@ -115,16 +123,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   bf16x8 Pf[2][2];
 
   for (int j = 0; j < ncol; ++j) {
-    if (j + 1 < ncol) {
-      issue_block(j + 1);
-      wait_vmem_upto<CPB>();
-    } else {
-      wait_vmem();
-    }
-    lds_barrier();  // block j of every wavefront has landed
+    issue_v(j + 1);  // in flight, oldest first: K_j, V_j, K_{j+1}, V_{j+1}, K_{j+2}
+    issue_k(j + 2);
+    wait_vmem_upto<4 * CPT>();
+    lds_barrier();  // K_j of every wavefront has landed
     const bool active = !CAUSAL || j * BC <= wrow_last;  // else every score of this wavefront is masked
     if (active) {
-      const int st = (j & 1) * STAGEB;
+      const int st = (j % KSTAGES) * TILEB;
       // ---- S^T = K_j Q_i^T (line 8)
       S[0] = S[1] = (f32x16){0};
       mfma_stream<2 * KS, 4, 1>(
@@ -133,6 +138,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             return lds_b128(smem, ((la.zrow + st + (ks >> 3) * HALFB) ^ (32 * (ks & 7))) + (i & 1) * 32 * kRowB);
           },
           [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, Qf[i >> 1], S[i & 1]); });
+    }
+    if (active) {
       // ---- online softmax (line 9), as in fwd_kernel
       const int col0 = j * BC;
       if ((CAUSAL && col0 + BC - 1 > prow0 + off) || col0 + BC > nk) {
@@ -177,19 +184,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         Pf[kt][1] = pack8<F16>(S[kt], 1);
       }
       l += rs0 + rs1;
+    }
+    wait_vmem_upto<3 * CPT>();
+    lds_barrier();  // V_j has landed
+    if (active) {
       // ---- O^T += V_j^T P^T (line 10)
+      const int vst = V_OFF + (j & 1) * TILEB;
       mfma_stream<4 * DT, 3, 2>(
           [&](int i) {
             const int dt = i >> 2, ro = (16 * (i & 3)) * kRowB;
-            const int vb = st + (2 + (dt >> 2)) * HALFB;
+            const int vb = vst + (dt >> 2) * HALFB;
             return lds_tr_pair(smem, ((la.zcol[0] + vb) ^ (64 * (dt & 3))) + ro, ((la.zcol[1] + vb) ^ (64 * (dt & 3))) + ro);
           },
           [&](int i, bf16x8 x) { O[i >> 2] = mfma32<F16>(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
     }
-    lds_barrier();  // block j has been read by everyone: its stage may be overwritten
+    lds_barrier();  // block j has been read by everyone: its stages may be overwritten
   }
 
   // ---- epilogue (lines 12-15): whole rows through LDS, see store_rows_via_lds
+  wait_vmem();  // (the copies past the last block)
+  lds_barrier();
   const float lsum = sum_with_partner32(l);
   const float inv = 1.0f / lsum;
   char* stg = smem + w * (32 * kRowB);
