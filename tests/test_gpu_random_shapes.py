@@ -52,7 +52,7 @@ def test_random_ragged_batches(i):
 
 
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 @pytest.mark.parametrize("qk_mult", [0.0, 8.0])
 def test_extreme_score_ranges(qk_mult, d, causal):
     """Q = K = 0 (uniform attention: every exponent equal) and Q, K multiplied by 8 before the
