@@ -59,7 +59,7 @@ def global_properties(prob, got):
 
 
 @pytest.mark.parametrize("name", ["d128_n8k_causal", "sweep_d64_n8192_full", "sweep_d64_n2048_causal",
-                                  "sweep_d128_n512_full", "d96_n8k_causal", "d32_n8k_causal"])
+                                  "sweep_d128_n512_full", "d96_n8k_causal", "d32_n8k_causal", "d256_n8k_causal"])
 def test_dense_workloads_sampled_units(name):
     prob = inputs.make_config(name)
     got = pu.run_hip(prob)
