@@ -4,9 +4,10 @@
 // operands another 64 to 128, so a wavefront needs the whole register file of its SIMD (512
 // registers, one wavefront per SIMD): workgroups of FOUR wavefronts, 128 query rows (forward,
 // dQ) or 128 keys (dK/dV) each, and no second wavefront on the SIMD to run the softmax
-// while the first one multiplies. The loops are therefore plain: wait for the block's tiles,
-// barrier, products, softmax, products, barrier, with the next block's tiles in flight
-// meanwhile (two LDS stages).
+// while the first one multiplies. The backward loops are plain: wait for the tile, barrier,
+// products, P and dS, products, barrier, with the next tile in flight meanwhile (two LDS
+// stages); the forward kernel interleaves the exponentials of one block with the MFMAs of its
+// neighbours inside its single instruction stream.
 //
 // A 256-wide tile is kept in LDS as two 128-wide halves side by side (columns 0..127 and
 // 128..255 of every row), each in the swizzled layout of fa_lds.h, so the operand addressing
@@ -94,9 +95,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   TileLoader<kHalf, BC, 4, false> loader;
   loader.init(kstride, w, lane, kHalf / 8);
-  // Copies: K_j is requested two blocks ahead, V_j one (it is needed only after the softmax).
-  // Every iteration issues the same number of copies, past the end too (rows are clamped, the
-  // data is never read), in the order V_{j+1}, K_{j+2}, so that the waits can count.
+  // One wavefront per SIMD has to overlap its own matrix and vector work: iteration j issues
+  // the MFMAs of O^T += V_{j-1}^T P_{j-1}^T and of S_{j+1}^T while it takes the exponentials of block j
+  // (whose maximum it has found just before). The scheduler interleaves the two instruction
+  // kinds inside one basic block (sched_group_barrier below).
+  //
+  // Copies: iteration j requests V_j (two LDS stages; read in iteration j + 1) and K_{j+3}
+  // (three stages; read in iteration j + 2), always the same number of copies, past the end too
+  // (rows are clamped, the data is never used), so that the waits can count.
   constexpr int CPT = 2 * TileLoader<kHalf, BC, 4, false>::PER;  // copies per wavefront and tile
   auto issue_k = [&](int j) {
     char* st = smem + (j % KSTAGES) * TILEB;
@@ -109,101 +115,137 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int half = 0; half < 2; ++half) loader.load(st + half * HALFB, Vb + half * kHalf, kstride, j * BC, nk - 1, w, lane);
   };
   issue_k(0);
-  issue_v(0);
   issue_k(1);
+  issue_k(2);
+  // (iteration 0 multiplies a P of zeros with whatever the V stage of "block -1" holds: zeros)
+  for (int o = tid * 16; o < TILEB; o += 256 * 16) *(u32x4*)(smem + V_OFF + TILEB + o) = (u32x4){0, 0, 0, 0};
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
 
   LaneAddr la;
   la.init(lane);
   const float c2 = p.scale_log2e;
-  const int wrow_last = prow0 + 31 + off;
   const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;
-  f32x16 S[2];
-  bf16x8 Pf[2][2];
+  f32x16 Sc[2], Sn[2];   // scores of the current block (turned into P in place) and of the next
+  bf16x8 Pp[2][2];       // P of the previous block, rounded: the operand of its O update
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) Pp[kt][0] = Pp[kt][1] = (bf16x8){0};
+  auto k_operand = [&](int st, int i) {
+    const int ks = i >> 1;
+    return lds_b128(smem, ((la.zrow + st + (ks >> 3) * HALFB) ^ (32 * (ks & 7))) + (i & 1) * 32 * kRowB);
+  };
+  auto v_operand = [&](int vst, int i) {
+    const int dt = i >> 2, ro = (16 * (i & 3)) * kRowB;
+    const int vb = vst + (dt >> 2) * HALFB;
+    return lds_tr_pair(smem, ((la.zcol[0] + vb) ^ (64 * (dt & 3))) + ro, ((la.zcol[1] + vb) ^ (64 * (dt & 3))) + ro);
+  };
+
+  wait_vmem_upto<2 * CPT>();
+  lds_barrier();  // K_0 has landed
+  Sc[0] = Sc[1] = (f32x16){0};
+  mfma_stream<2 * KS, 4, 1>([&](int i) { return k_operand(0, i); },
+                            [&](int i, bf16x8 x) { Sc[i & 1] = mfma32<F16>(x, Qf[i >> 1], Sc[i & 1]); });
+  lds_barrier();  // K_0 has been read by everyone (and the zeros above are in place)
 
   for (int j = 0; j < ncol; ++j) {
-    issue_v(j + 1);  // in flight, oldest first: K_j, V_j, K_{j+1}, V_{j+1}, K_{j+2}
-    issue_k(j + 2);
-    wait_vmem_upto<4 * CPT>();
-    lds_barrier();  // K_j of every wavefront has landed
-    const bool active = !CAUSAL || j * BC <= wrow_last;  // else every score of this wavefront is masked
-    if (active) {
-      const int st = (j % KSTAGES) * TILEB;
-      // ---- S^T = K_j Q_i^T (line 8)
-      S[0] = S[1] = (f32x16){0};
-      mfma_stream<2 * KS, 4, 1>(
-          [&](int i) {
-            const int ks = i >> 1;
-            return lds_b128(smem, ((la.zrow + st + (ks >> 3) * HALFB) ^ (32 * (ks & 7))) + (i & 1) * 32 * kRowB);
-          },
-          [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, Qf[i >> 1], S[i & 1]); });
+    issue_v(j);
+    issue_k(j + 3);  // in flight, oldest first: .. K_{j+1}, V_{j-1} | K_{j+2}, V_j, K_{j+3}
+    // ---- the maximum of block j and the reference it is measured against (line 9)
+    const int col0 = j * BC;
+    if ((CAUSAL && col0 + BC - 1 > prow0 + off) || col0 + BC > nk) {
+      const int lim = lim_row - col0 - 4 * hh;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Sc[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : Sc[kt][r];
     }
-    if (active) {
-      // ---- online softmax (line 9), as in fwd_kernel
-      const int col0 = j * BC;
-      if ((CAUSAL && col0 + BC - 1 > prow0 + off) || col0 + BC > nk) {
-        const int lim = lim_row - col0 - 4 * hh;
+    float mx = max3f(Sc[0][0], Sc[0][1], Sc[1][0]);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+    for (int r = 2; r < 16; r += 2) mx = max3f(mx, Sc[0][r], Sc[0][r + 1]);
+    mx = max3f(mx, Sc[1][1], Sc[1][2]);
+    mx = fmaxf(mx, Sc[1][3]);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) S[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : S[kt][r];
-      }
-      float mx = max3f(S[0][0], S[0][1], S[1][0]);
+    for (int r = 4; r < 16; r += 2) mx = max3f(mx, Sc[1][r], Sc[1][r + 1]);
+    mx = max_with_partner32(mx);
+    const float m_new = fmaxf(m, mx);
+    // (lazy: the reference only moves when some row outgrew it by 2^kLazyLog2; O then is rescaled
+    // AFTER this iteration's MFMAs, which still add a block measured against the old reference)
+    const bool moved = __builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)kLazyLog2) != 0;
+    float alpha = 1.f;
+    if (moved) {
+      alpha = fast_exp2((m - m_new) * c2);
+      l *= alpha;
+      m = m_new;
+    }
+    const float mc = m * c2;
+    wait_vmem_upto<3 * CPT>();
+    lds_barrier();  // K_{j+1} and V_{j-1} have landed
+    // ---- one basic block: 64 MFMAs (O^T += V_{j-1}^T P_{j-1}^T, line 10; S_{j+1}^T = K_{j+1} Q_i^T, line 8)
+    //      with the exponentials of block j between them
+    {
+      const int vst = V_OFF + ((j + 1) & 1) * TILEB, kst = ((j + 1) % KSTAGES) * TILEB;
+      constexpr int NPV = 4 * DT, NS = 2 * KS, AH = 3;
+      bf16x8 ring[AH];
+      auto operand = [&](int i) { return i < NPV ? v_operand(vst, i) : k_operand(kst, i - NPV); };
 #pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = max3f(mx, S[0][r], S[0][r + 1]);
-      mx = max3f(mx, S[1][1], S[1][2]);
-      mx = fmaxf(mx, S[1][3]);
-#pragma unroll
-      for (int r = 4; r < 16; r += 2) mx = max3f(mx, S[1][r], S[1][r + 1]);
-      mx = max_with_partner32(mx);
-      const float m_new = fmaxf(m, mx);
-      if (__builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)kLazyLog2) != 0) {
-        const float alpha = fast_exp2((m - m_new) * c2);
-        l *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-        m = m_new;
-      }
-      const float mc = m * c2;
+      for (int i = 0; i < AH; ++i) ring[i] = operand(i);
+      __builtin_amdgcn_sched_barrier(0);
+      Sn[0] = Sn[1] = (f32x16){0};
       float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], c2, -mc));
-          const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -mc));
-          S[kt][r] = e0;
-          S[kt][r + 1] = e1;
-          rs0 += e0;
-          rs1 += e1;
+      for (int i = 0; i < NPV + NS; ++i) {
+        const bf16x8 cur = ring[i % AH];
+        if (i + AH < NPV + NS) ring[i % AH] = operand(i + AH);
+        if (i < NPV) {
+          O[i >> 2] = mfma32<F16>(cur, Pp[(i >> 1) & 1][i & 1], O[i >> 2]);
+        } else {
+          const int k = i - NPV;
+          Sn[k & 1] = mfma32<F16>(cur, Qf[k >> 1], Sn[k & 1]);
         }
-        Pf[kt][0] = pack8<F16>(S[kt], 0);
-        Pf[kt][1] = pack8<F16>(S[kt], 1);
+        {  // one exponential of block j behind every second MFMA
+          const int e = i / 2, kt = e / 16, r = e % 16;
+          if (i & 1) {
+            // (the two empty statements tie the exponential to this place: instruction selection
+            // would otherwise sink all of them behind the last MFMA, next to their uses)
+            float x = Sc[kt][r];
+            asm volatile("" : "+v"(x));
+            float ex = fast_exp2(__builtin_fmaf(x, c2, -mc));
+            asm volatile("" : "+v"(ex));
+            Sc[kt][r] = ex;
+            if (r & 1) rs1 += ex;
+            else rs0 += ex;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep this order: the two kinds of work alternate
       }
       l += rs0 + rs1;
     }
-    wait_vmem_upto<3 * CPT>();
-    lds_barrier();  // V_j has landed
-    if (active) {
-      // ---- O^T += V_j^T P^T (line 10)
-      const int vst = V_OFF + (j & 1) * TILEB;
-      mfma_stream<4 * DT, 3, 2>(
-          [&](int i) {
-            const int dt = i >> 2, ro = (16 * (i & 3)) * kRowB;
-            const int vb = vst + (dt >> 2) * HALFB;
-            return lds_tr_pair(smem, ((la.zcol[0] + vb) ^ (64 * (dt & 3))) + ro, ((la.zcol[1] + vb) ^ (64 * (dt & 3))) + ro);
-          },
-          [&](int i, bf16x8 x) { O[i >> 2] = mfma32<F16>(x, Pf[(i >> 1) & 1][i & 1], O[i >> 2]); });
+    if (moved) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
     }
-    lds_barrier();  // block j has been read by everyone: its stages may be overwritten
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      Pp[kt][0] = pack8<F16>(Sc[kt], 0);
+      Pp[kt][1] = pack8<F16>(Sc[kt], 1);
+      Sc[kt] = Sn[kt];
+    }
+    lds_barrier();  // K_{j+1} and V_{j-1} have been read by everyone: their stages may be overwritten
   }
 
-  // ---- epilogue (lines 12-15): whole rows through LDS, see store_rows_via_lds
-  wait_vmem();  // (the copies past the last block)
+  // ---- the last block's O update
+  wait_vmem();
   lds_barrier();
+  {
+    const int vst = V_OFF + ((ncol - 1) & 1) * TILEB;
+    mfma_stream<4 * DT, 3, 2>([&](int i) { return v_operand(vst, i); },
+                              [&](int i, bf16x8 x) { O[i >> 2] = mfma32<F16>(x, Pp[(i >> 1) & 1][i & 1], O[i >> 2]); });
+  }
+  lds_barrier();
+
+  // ---- epilogue (lines 12-15): whole rows through LDS, see store_rows_via_lds
   const float lsum = sum_with_partner32(l);
   const float inv = 1.0f / lsum;
   char* stg = smem + w * (32 * kRowB);
