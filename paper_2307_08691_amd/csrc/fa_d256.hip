@@ -44,7 +44,7 @@ struct LaneAddr {
 
 // ---------------------------------------------------------------------------------------------
 // Forward (Algorithm 1). Wavefront w owns rows 32 w .. 32 w + 31 of a 128-row block; key blocks
-// of 64. One LDS stage = K_j left | K_j right | V_j left | V_j right, 16 KiB each.
+// of 64. LDS: three stages of K_j (left | right half, 16 KiB each) and two of V_j.
 template <bool CAUSAL, bool F16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void fwd256_kernel(FwdArgs a) {
   constexpr int D = 256, BR = 128, BC = 64, KS = D / 16, DT = D / 32;
@@ -97,8 +97,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   loader.init(kstride, w, lane, kHalf / 8);
   // One wavefront per SIMD has to overlap its own matrix and vector work: iteration j issues
   // the MFMAs of O^T += V_{j-1}^T P_{j-1}^T and of S_{j+1}^T while it takes the exponentials of block j
-  // (whose maximum it has found just before). The scheduler interleaves the two instruction
-  // kinds inside one basic block (sched_group_barrier below).
+  // (whose maximum it has found just before): one basic block in which the two kinds of
+  // instruction alternate in source order, held there by scheduling fences.
   //
   // Copies: iteration j requests V_j (two LDS stages; read in iteration j + 1) and K_{j+3}
   // (three stages; read in iteration j + 2), always the same number of copies, past the end too
