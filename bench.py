@@ -81,9 +81,12 @@ def cpu_baseline(prob, budget_s: float = 12.0):
     }
 
 
-def paper_grid(binding, torch, iters: int = 8):
+def paper_grid(binding, torch, samples: int = 20, warmup: int = 5):
     """Forward and forward+backward TFLOPs/s over the grid of section 4.1. Inputs are drawn on the
-    GPU (N(0,1) rounded to bf16, seeded): the values do not change the work."""
+    GPU (N(0,1) rounded to bf16, seeded): the values do not change the work. Per point: `warmup`
+    calls, then the median of `samples` timed batches (short calls are timed several at a time:
+    a batch lasts about a millisecond)."""
+    import statistics
     gen = torch.Generator(device="cuda").manual_seed(1002)
     out = {}
     for d, H in ((64, 32), (128, 16)):
@@ -105,15 +108,18 @@ def paper_grid(binding, torch, iters: int = 8):
 
                 ms = []
                 for fn in (fwd, both):
-                    for _ in range(3):
+                    def timed(k):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        for _ in range(k):
+                            fn()
+                        e1.record()
+                        torch.cuda.synchronize()
+                        return e0.elapsed_time(e1) / k
+                    for _ in range(warmup):
                         fn()
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(iters):
-                        fn()
-                    e1.record()
-                    torch.cuda.synchronize()
-                    ms.append(e0.elapsed_time(e1) / iters)
+                    k = max(1, min(16, int(1.0 / max(timed(1), 1e-3))))
+                    ms.append(statistics.median(timed(k) for _ in range(samples)))
                 fl = 4.0 * B * H * N * N * d * (0.5 if causal else 1.0)
                 out[f"d{d}_n{N}_{'causal' if causal else 'full'}"] = {
                     "fwd_tflops": round(fl / ms[0] / 1e9, 1), "fwd_bwd_tflops": round(3.5 * fl / ms[1] / 1e9, 1)}
