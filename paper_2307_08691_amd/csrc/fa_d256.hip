@@ -506,30 +506,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (t + 1 < T) issue_tile(t + 1);  // into the other stage, which everyone left at the last barrier
     const int st = (t & 1) * STAGEB;
     const int r0 = (i_first + t % per_head) * BR;  // first query row of the tile
-    // ---- S = Q_i K_j^T (line 10), dP - D = dO_i V_j^T - D (lines 13, 14)
+    // ---- S = Q_i K_j^T (line 10)
+    S = (f32x16){0};
+    mfma_stream<KS, 4, 1>(
+        [&](int i) { return lds_b128(smem, (la.zrow + st + (i >> 3) * HALFB) ^ (32 * (i & 7))); },
+        [&](int i, bf16x8 x) { S = mfma32<F16>(x, Kf[i], S); });
+    // ---- dP - D = dO_i V_j^T - D (lines 13, 14; -D is where the accumulator starts) with
+    //      P = exp(S - L) (line 11) between its MFMAs: one instruction stream per SIMD has to
+    //      overlap its own matrix and vector work (see the forward kernel)
+    f32x4 Lv[4];
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const f32x4 Dn = *(const f32x4*)(smem + DV_OFF + ((t & 1) * BR + 8 * r4 + 4 * hh) * 4);
+      Lv[r4] = *(const f32x4*)(smem + LS_OFF + ((t & 1) * BR + 8 * r4 + 4 * hh) * 4);
 #pragma unroll
       for (int u = 0; u < 4; ++u) dP[4 * r4 + u] = Dn[u];
     }
-    S = (f32x16){0};
-    mfma_stream<2 * KS, 4, 1>(
-        [&](int i) {
-          const int ks = i >> 1;
-          const int base = st + ((i & 1) ? 2 : 0) * HALFB + (ks >> 3) * HALFB;
-          return lds_b128(smem, (la.zrow + base) ^ (32 * (ks & 7)));
-        },
-        [&](int i, bf16x8 x) {
-          if (i & 1) dP = mfma32<F16>(x, Vf[i >> 1], dP);
-          else S = mfma32<F16>(x, Kf[i >> 1], S);
-        });
-    // ---- P = exp(S - L) (line 11), dS = P o (dP - D)
+    {
+      constexpr int AH = 4;
+      bf16x8 ring[AH];
+      auto operand = [&](int i) { return lds_b128(smem, (la.zrow + st + 2 * HALFB + (i >> 3) * HALFB) ^ (32 * (i & 7))); };
 #pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + ((t & 1) * BR + 8 * r4 + 4 * hh) * 4);
+      for (int i = 0; i < AH; ++i) ring[i] = operand(i);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) S[4 * r4 + u] = fast_exp2(__builtin_fmaf(S[4 * r4 + u], c2, -Lv[u]));
+      for (int i = 0; i < KS; ++i) {
+        const bf16x8 cur = ring[i % AH];
+        if (i + AH < KS) ring[i % AH] = operand(i + AH);
+        dP = mfma32<F16>(cur, Vf[i], dP);
+        float x = S[i];  // (tied in place, see the forward kernel)
+        asm volatile("" : "+v"(x));
+        float ex = fast_exp2(__builtin_fmaf(x, c2, -Lv[i >> 2][i & 3]));
+        asm volatile("" : "+v"(ex));
+        S[i] = ex;
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     if ((CAUSAL && key0 + 31 > r0 + off) || j0 + BC > nk) {
       // visible: key < nk and (causal) key <= r0 + off + row of the tile, row = acc_row(r, hh)
