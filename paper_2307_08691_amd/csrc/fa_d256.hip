@@ -363,26 +363,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     lds_barrier();
     if (!CAUSAL || j * BC <= wrow_last) {
       const int st = (j & 1) * STAGEB;
-      // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
+      // ---- S^T = K_j Q_i^T (line 10)
       S[0] = S[1] = dP[0] = dP[1] = (f32x16){0};
-      mfma_stream<4 * KS, 4, 1>(
+      mfma_stream<2 * KS, 4, 1>(
           [&](int i) {
-            const int ks = i >> 2, kt = (i >> 1) & 1;
-            const int base = st + ((i & 1) ? 2 : 0) * HALFB + (ks >> 3) * HALFB;
-            return lds_b128(smem, ((la.zrow + base) ^ (32 * (ks & 7))) + 32 * kt * kRowB);
+            const int ks = i >> 1;
+            return lds_b128(smem, ((la.zrow + st + (ks >> 3) * HALFB) ^ (32 * (ks & 7))) + (i & 1) * 32 * kRowB);
           },
-          [&](int i, bf16x8 x) {
-            const int ks = i >> 2, kt = (i >> 1) & 1;
-            if (i & 1) dP[kt] = mfma32<F16>(x, dOf[ks], dP[kt]);
-            else S[kt] = mfma32<F16>(x, Qf[ks], S[kt]);
-          });
-      // ---- P = exp(S - L) (line 11), dS = P o (dP - D) (line 14)
+          [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, Qf[i >> 1], S[i & 1]); });
+      // ---- dP^T = V_j dO_i^T (line 13) with P = exp(S - L) (line 11) between its MFMAs (one
+      //      instruction stream per SIMD has to overlap its own matrix and vector work)
+      {
+        constexpr int AH = 4;
+        bf16x8 ring[AH];
+        auto operand = [&](int i) {
+          const int ks = i >> 1;
+          return lds_b128(smem, ((la.zrow + st + 2 * HALFB + (ks >> 3) * HALFB) ^ (32 * (ks & 7))) + (i & 1) * 32 * kRowB);
+        };
+#pragma unroll
+        for (int i = 0; i < AH; ++i) ring[i] = operand(i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 2 * KS; ++i) {
+          const bf16x8 cur = ring[i % AH];
+          if (i + AH < 2 * KS) ring[i % AH] = operand(i + AH);
+          dP[i & 1] = mfma32<F16>(cur, dOf[i >> 1], dP[i & 1]);
+          float x = S[i >> 4][i & 15];  // (tied in place, see the forward kernel)
+          asm volatile("" : "+v"(x));
+          float ex = fast_exp2(__builtin_fmaf(x, c2, -Lq));
+          asm volatile("" : "+v"(ex));
+          S[i >> 4][i & 15] = ex;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      // ---- dS = P o (dP - D) (line 14)
       const int col0 = j * BC;
       const bool need_mask = (CAUSAL && col0 + BC - 1 > prow0 + off) || (col0 + BC > nk);
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[kt][r] = fast_exp2(__builtin_fmaf(S[kt][r], c2, -Lq));
         if (need_mask) {
 #pragma unroll
           for (int r = 0; r < 16; ++r)
