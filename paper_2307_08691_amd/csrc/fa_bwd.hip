@@ -680,7 +680,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const int grp = w >> 2;  // 0: matrix phase on even phases, 1: on odd phases
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq);
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq, p.G);
   if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;

@@ -94,8 +94,12 @@ struct BlockCoord {
 __host__ __device__ inline unsigned grid_size(int nblk, int pairs) {
   return (unsigned)(((pairs + kXcds - 1) / kXcds) * kXcds * nblk);
 }
+// `group` > 1 (kernels whose grid runs over QUERY heads that share key/value heads in groups of
+// that size): heads are handed out so that the heads of one group follow each other at a
+// distance of nheads / group pairs. With a multiple of 8 key/value heads they then land on the
+// same XCD, whose L2 holds the group's K and V once instead of every XCD holding them all.
 template <bool WORK_SORTED>
-__device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads, int nseq) {
+__device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads, int nseq, int group = 1) {
   const int L = blockIdx.x;
   const int x = L % kXcds, k = L / kXcds;
   const int ppx = gridDim.x / (kXcds * nblk);  // pairs per XCD
@@ -109,7 +113,8 @@ __device__ __forceinline__ BlockCoord block_coord(int nblk, int nheads, int nseq
     pl = k / nblk;
   }
   const int pr = pl * kXcds + x;
-  c.head = pr % nheads;
+  const int hp = pr % nheads, nkv = nheads / group;
+  c.head = (hp % nkv) * group + hp / nkv;
   c.seq = pr / nheads;
   c.valid = pr < nheads * nseq;
   return c;

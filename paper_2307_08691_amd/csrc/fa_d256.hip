@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq);
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq, p.G);
   if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;  // longest causal rows first
   const int h = bc.head, s = bc.seq;
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, hh = lane >> 5;
   const int nblk = (p.N + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq);
+  const BlockCoord bc = block_coord<CAUSAL>(nblk, p.Hq, p.nseq, p.G);
   if (!bc.valid) return;
   const int rowblk = nblk - 1 - bc.blk;
   const int h = bc.head, s = bc.seq;

@@ -122,7 +122,7 @@ __global__ __launch_bounds__(512)
   const int lq = lane & 31, hh = lane >> 5;
   const int nsplit = SPLIT ? a.nsplit : 1;
   const int nblk = ((SPLIT ? p.N * p.G : p.N) + BR - 1) / BR;
-  const BlockCoord bc = block_coord<CAUSAL && !SPLIT>(nblk * nsplit, SPLIT ? p.Hkv : p.Hq, p.nseq);
+  const BlockCoord bc = block_coord<CAUSAL && !SPLIT>(nblk * nsplit, SPLIT ? p.Hkv : p.Hq, p.nseq, SPLIT ? 1 : p.G);
   if (!bc.valid) return;
   const int split = SPLIT ? bc.blk % nsplit : 0;
   const int rowblk = SPLIT ? bc.blk / nsplit : nblk - 1 - bc.blk;  // not split: longest causal rows first
@@ -496,7 +496,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     const int pr = pl * kXcds + xcd;
     Item it;
-    it.h = pr % p.Hq;
+    const int hp = pr % p.Hq, nkv = p.Hq / p.G;  // heads of one group on one XCD (see block_coord)
+    it.h = (hp % nkv) * p.G + hp / nkv;
     it.s = pr / p.Hq;
     const int i0 = (nblk - 1 - blk) * BR;
     it.prow0 = i0 + 32 * w;
