@@ -134,7 +134,8 @@ def make_dense(B, N, Hq, Hkv, d, causal, seed, scale=None, qk_mult=1.0,
     dO = _draw(rng, (B, N, Hq, d))
     return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
                        scale=float(scale if scale is not None else d ** -0.5),
-                       causal=bool(causal), B=B, N=N, seed=seed)
+                       causal=bool(causal), B=B, N=N, seed=seed,
+                       meta={"qk_mult": float(qk_mult), "standard_normal": qk_mult <= 1.0})
 
 
 def make_cross(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="cross", dtype="bf16") -> AttnProblem:

@@ -92,9 +92,8 @@ def test_guard_values_around_outputs_survive():
     torch.cuda.synchronize()
     for buf in (bO, bQ, bK, bV):
         assert bool((buf[:pad] == 7.0).all()) and bool((buf[-pad:] == 7.0).all())
-    exp = pu.run_oracle(prob)
-    for nm, t in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
-        assert pu.maxdiff(pu.to_f64(t), exp[nm]) <= pu.tolerance(nm, exp[nm])
+    pu.judge("guarded outputs, two lengths", {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
+             pu.run_oracle(prob), pu.run_reference(prob), d=prob.d)
 
 
 @pytest.mark.parametrize("name", ["chunk_512_on_8k", "cross_2k_on_8k"])
@@ -116,11 +115,8 @@ def check_splitkv(prob, num_splits):
     Q, K, V = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V))
     O, L = binding.fa_splitkv_fwd(Q, K, V, prob.scale, prob.causal, num_splits)
     torch.cuda.synchronize()
-    exp = pu.run_oracle(prob, backward=False)
-    assert torch.isfinite(O.float()).all() and torch.isfinite(L).all()
-    eo, el = pu.maxdiff(pu.to_f64(O), exp["O"]), pu.maxdiff(pu.to_f64(L), exp["LSE"])
-    assert eo <= pu.tolerance("O", exp["O"]), f"{prob.name} splits={num_splits}: O err {eo:.3e}"
-    assert el <= pu.TOL_LSE, f"{prob.name} splits={num_splits}: LSE err {el:.3e}"
+    pu.judge(f"split keys {pu.describe(prob)} shares={num_splits}", {"O": pu.to_f64(O), "LSE": pu.to_f64(L)},
+             pu.run_oracle(prob, backward=False), pu.run_reference(prob, backward=False), d=prob.d)
     return O, L
 
 
@@ -176,11 +172,10 @@ def test_ragged_batches_with_two_lengths(d, Hq, Hkv, causal):
     Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (Qb, Kb, Vb, dOb))
     eO, eL = orc.varlen_forward(Qf, Kf, Vf, cu_q, scale, causal, cu_seqlens_k=cu_k)
     edQ, edK, edV = orc.varlen_backward(Qf, Kf, Vf, dOf, cu_q, scale, causal, cu_seqlens_k=cu_k)
-    for nm, got, exp in (("O", O, eO), ("LSE", L, eL), ("dQ", dQ, edQ), ("dK", dK, edK), ("dV", dV, edV)):
-        g = pu.to_f64(got)
-        assert np.all(np.isfinite(g)), nm
-        err = pu.maxdiff(g, exp)
-        assert err <= pu.tolerance(nm, exp), f"{nm}: {err:.3e}"
+    ref = pu.reference_batch(Q, K, V, dO, scale, causal, cu_q=cu_q, cu_k=cu_k)
+    pu.judge(f"ragged, two lengths, d{d} H{Hq}/{Hkv} causal={causal}",
+             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
+             dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, d=d)
     # the keys of the sequence without queries receive exactly zero
     assert not bool(dK[cu_k[2]:cu_k[3]].any()) and not bool(dV[cu_k[2]:cu_k[3]].any())
 

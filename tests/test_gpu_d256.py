@@ -49,12 +49,12 @@ def test_more_queries_than_keys_without_mask():
 @pytest.mark.parametrize("causal", [False, True])
 def test_half_precision(causal):
     prob = inputs.make_cross(B=2, Nq=300, Nk=300, Hq=4, Hkv=2, d=256, causal=causal, seed=18500, dtype="f16")
-    check(prob, ref_compare=False)
+    check(prob)
 
 
 def test_wide_score_range():
     prob = inputs.make_dense(B=1, N=700, Hq=2, Hkv=1, d=256, causal=True, seed=18600, qk_mult=3.0)
-    check(prob, ref_compare=False)
+    check(prob)
 
 
 def test_full_size_sampled_units():

@@ -1,7 +1,8 @@
 """GPU parity with dropout on P: fa_dropout_fwd / fa_dropout_bwd against the float64 oracle, which
 regenerates the same keep mask from the same (seed, head, query, key) function. The mask decision
-is integer arithmetic on both sides, so the comparison is as tight as without dropout, scaled by
-1 / (1 - p)."""
+is integer arithmetic on both sides. The outputs carry the factor 1 / (1 - p), so what is asserted is
+the yardstick clause: no worse than a bf16 implementation of the standard algorithm with the same
+keep mask that materialises S and P (parity_util.judge with standard=False)."""
 import numpy as np
 import pytest
 
@@ -22,21 +23,24 @@ def run(prob, p_drop, seed):
     return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV)
 
 
+def keep_masks(seed, p_drop, Hq):
+    """keep_of(sequence, head, nq, nk) for parity_util.reference_batch, from the oracle's generator."""
+    thr = orc.dropout_threshold(p_drop)
+    return (lambda s, h, nq, nk: torch.from_numpy(orc.dropout_keep(seed, s * Hq + h, nq, nk, thr)).cuda()), 256.0 / (256.0 - thr)
+
+
 def check_dropout(prob, p_drop, seed):
     got = run(prob, p_drop, seed)
     Q, K, V, dO = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     exp = {}
     exp["O"], exp["LSE"] = orc.attention_forward_dropout(Q, K, V, prob.scale, prob.causal, p_drop, seed)
     exp["dQ"], exp["dK"], exp["dV"] = orc.attention_backward_dropout(Q, K, V, dO, prob.scale, prob.causal, p_drop, seed)
-    rp = 256.0 / (256.0 - orc.dropout_threshold(p_drop))
-    errs = {}
-    for nm in ("O", "LSE", "dQ", "dK", "dV"):
-        g = pu.to_f64(got[nm])
-        assert np.all(np.isfinite(g)), nm
-        errs[nm] = pu.maxdiff(g, exp[nm])
-        tol = pu.tolerance(nm, exp[nm]) * (1.0 if nm == "LSE" else rp)
-        assert errs[nm] <= tol, f"{prob.name} p={p_drop}: {nm} err {errs[nm]:.3e} > {tol:.3e}"
-    return errs
+    keep_of, rp = keep_masks(seed, p_drop, prob.Hq)
+    ref = pu.reference_batch(*(pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO)), prob.scale, prob.causal,
+                             keep_of=keep_of, rp=rp)
+    res = pu.judge(f"dropout p={p_drop} {pu.describe(prob)}", {k: pu.to_f64(v) for k, v in got.items()}, exp, ref,
+                   standard=False, d=prob.d)
+    return {k: v[0] for k, v in res.items()}
 
 
 @pytest.mark.parametrize("causal", [False, True])
@@ -96,7 +100,8 @@ def test_ragged_batches_with_dropout(d, Hq, Hkv, causal):
     Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     eO, eL = orc.varlen_forward_dropout(Qf, Kf, Vf, prob.cu_seqlens, prob.scale, causal, p_drop, seed)
     edQ, edK, edV = orc.varlen_backward_dropout(Qf, Kf, Vf, dOf, prob.cu_seqlens, prob.scale, causal, p_drop, seed)
-    rp = 1.0 / (1.0 - 0.25)
-    for nm, got, exp in (("O", O, eO), ("LSE", L, eL), ("dQ", dQ, edQ), ("dK", dK, edK), ("dV", dV, edV)):
-        err = pu.maxdiff(pu.to_f64(got), exp)
-        assert err <= pu.tolerance(nm, exp) * (1.0 if nm == "LSE" else rp), f"{nm}: {err:.3e}"
+    keep_of, rp = keep_masks(seed, p_drop, Hq)
+    ref = pu.reference_batch(Q, K, V, dO, prob.scale, causal, cu_q=prob.cu_seqlens, keep_of=keep_of, rp=rp)
+    pu.judge(f"ragged dropout d{d} H{Hq}/{Hkv} causal={causal}",
+             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
+             dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, standard=False, d=d)

@@ -16,35 +16,7 @@ torch = pytest.importorskip("torch")
 import parity_util as pu  # noqa: E402
 
 
-def check_units(prob, got, units):
-    """units: list of (b, kv_head). Compares O, LSE, dQ for every query head of
-    the group and dK, dV of the kv head."""
-    G = prob.Hq // prob.Hkv
-    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
-    worst = {}
-    for (b, g) in units:
-        k = widen(prob.K[b, :, g])
-        v = widen(prob.V[b, :, g])
-        dk_sum = np.zeros_like(k)
-        dv_sum = np.zeros_like(v)
-        for h in range(g * G, (g + 1) * G):
-            q = widen(prob.Q[b, :, h])
-            do = widen(prob.dO[b, :, h])
-            o, lse, _ = orc.head_forward(q, k, v, prob.scale, prob.causal)
-            dq, dk, dv = orc.head_backward(q, k, v, do, prob.scale, prob.causal)
-            dk_sum += dk
-            dv_sum += dv
-            for nm, e, gt in (("O", o, got["O"][b, :, h]), ("LSE", lse, got["LSE"][b, h]), ("dQ", dq, got["dQ"][b, :, h])):
-                err = pu.maxdiff(pu.to_f64(gt), e)
-                tol = pu.tolerance(nm, e)
-                assert err <= tol, f"{prob.name} unit (b={b}, h={h}): {nm} err {err:.3e} > {tol:.3e}"
-                worst[nm] = max(worst.get(nm, 0.0), err)
-        for nm, e, gt in (("dK", dk_sum, got["dK"][b, :, g]), ("dV", dv_sum, got["dV"][b, :, g])):
-            err = pu.maxdiff(pu.to_f64(gt), e)
-            tol = pu.tolerance(nm, e)
-            assert err <= tol, f"{prob.name} unit (b={b}, g={g}): {nm} err {err:.3e} > {tol:.3e}"
-            worst[nm] = max(worst.get(nm, 0.0), err)
-    return worst
+check_units = pu.check_units
 
 
 def global_properties(prob, got):
@@ -97,8 +69,11 @@ def test_long_context_wide_range_sampled_units():
     v = orc.widen_bf16(prob.V[0, :, 3])
     q = orc.widen_bf16(prob.Q[0, rows, 3])
     o, lse = orc.rows_forward(q, rows, k, v, prob.scale, True)
-    assert pu.maxdiff(pu.to_f64(got["O"][0, rows, 3]), o) <= pu.tolerance("O", o)
-    assert pu.maxdiff(pu.to_f64(got["LSE"][0, 3, rows]), lse) <= pu.TOL_LSE
+    Qg, Kg, Vg, dOg = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    ref = pu.reference_head(Qg[0, rows, 3], Kg[0, :, 3], Vg[0, :, 3], dOg[0, rows, 3], prob.scale, True, backward=False,
+                            pos=rows)
+    pu.judge(f"{prob.name} sampled rows of head 3", {"O": pu.to_f64(got["O"][0, rows, 3]), "LSE": pu.to_f64(got["LSE"][0, 3, rows])},
+             {"O": o, "LSE": lse}, ref, standard=False, d=prob.d)
 
 
 def test_gqa_ragged_sampled_sequences():
@@ -110,6 +85,7 @@ def test_gqa_ragged_sampled_sequences():
     cu = prob.cu_seqlens
     picks = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 0, len(lens) - 1})
     G = prob.Hq // prob.Hkv
+    Qg, Kg, Vg, dOg = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     for s in picks:
         a, e = int(cu[s]), int(cu[s + 1])
         g = s % prob.Hkv
@@ -118,14 +94,15 @@ def test_gqa_ragged_sampled_sequences():
         dO = orc.widen_bf16(prob.dO[a:e, hs])[None]
         K = orc.widen_bf16(prob.K[a:e, g:g + 1])[None]
         V = orc.widen_bf16(prob.V[a:e, g:g + 1])[None]
-        O, L = orc.attention_forward(Q, K, V, prob.scale, True)
-        dQ, dK, dV = orc.attention_backward(Q, K, V, dO, prob.scale, True)
-        for nm, exp, gt in (("O", O[0], got["O"][a:e, hs]), ("LSE", L[0], got["LSE"][hs, a:e]),
-                            ("dQ", dQ[0], got["dQ"][a:e, hs]), ("dK", dK[0], got["dK"][a:e, g:g + 1]),
-                            ("dV", dV[0], got["dV"][a:e, g:g + 1])):
-            err = pu.maxdiff(pu.to_f64(gt), exp)
-            tol = pu.tolerance(nm, exp)
-            assert err <= tol, f"ragged seq {s} (len {e - a}) kv head {g}: {nm} err {err:.3e} > {tol:.3e}"
+        exp = {}
+        exp["O"], exp["LSE"] = orc.attention_forward(Q, K, V, prob.scale, True)
+        exp["dQ"], exp["dK"], exp["dV"] = orc.attention_backward(Q, K, V, dO, prob.scale, True)
+        ref = pu.reference_batch(Qg[a:e, hs][None], Kg[a:e, g:g + 1][None], Vg[a:e, g:g + 1][None], dOg[a:e, hs][None],
+                                 prob.scale, True)
+        gotu = {"O": got["O"][a:e, hs][None], "LSE": got["LSE"][hs, a:e][None], "dQ": got["dQ"][a:e, hs][None],
+                "dK": got["dK"][a:e, g:g + 1][None], "dV": got["dV"][a:e, g:g + 1][None]}
+        pu.judge(f"{prob.name} sequence {s} (len {e - a}) kv head {g}", {k: pu.to_f64(v) for k, v in gotu.items()}, exp, ref,
+                 standard=True, d=prob.d)
 
 
 @pytest.mark.timeout(900)
@@ -153,17 +130,19 @@ def test_tensors_beyond_two_to_the_31_elements():
     f64 = lambda t: t.double().cpu().numpy()  # noqa: E731
     for (b, h, full) in ((B - 1, H - 1, True), (0, 0, False)):
         q, k, v, do = f64(Q[b, :, h]), f64(K[b, :, h]), f64(V[b, :, h]), f64(dO[b, :, h])
-        o, lse = orc.rows_forward(q[rows], rows, k, v, scale, True)
-        dq = orc.rows_backward_dq(q[rows], rows, k, v, do[rows], scale, True)
-        for nm, got, exp in (("O", O[b, rows, h], o), ("LSE", L[b, h, rows], lse), ("dQ", dQ[b, rows, h], dq)):
-            err = pu.maxdiff(f64(got), exp)
-            assert err <= pu.tolerance(nm, exp), f"unit ({b},{h}) {nm}: {err:.3e}"
+        exp, gotu = {}, {"O": f64(O[b, rows, h]), "LSE": f64(L[b, h, rows]), "dQ": f64(dQ[b, rows, h])}
+        exp["O"], exp["LSE"] = orc.rows_forward(q[rows], rows, k, v, scale, True)
+        exp["dQ"] = orc.rows_backward_dq(q[rows], rows, k, v, do[rows], scale, True)
+        ref = pu.reference_head(Q[b, rows, h], K[b, :, h], V[b, :, h], dO[b, rows, h], scale, True, pos=rows)
+        ref = {nm: ref[nm] for nm in gotu}
         if full:
             Lall, _, Dall = orc.head_statistics_blockwise(q, k, v, do, scale, True, block=1024)
-            gk, gv = orc.cols_backward_dkdv(q, k[cols], v[cols], cols, N, do, Lall, Dall, scale, True)
-            for nm, got, exp in (("dK", dK[b, cols, h], gk), ("dV", dV[b, cols, h], gv)):
-                err = pu.maxdiff(f64(got), exp)
-                assert err <= pu.tolerance(nm, exp), f"unit ({b},{h}) {nm}: {err:.3e}"
+            exp["dK"], exp["dV"] = orc.cols_backward_dkdv(q, k[cols], v[cols], cols, N, do, Lall, Dall, scale, True)
+            whole = pu.reference_head(Q[b, :, h], K[b, :, h], V[b, :, h], dO[b, :, h], scale, True)
+            ref.update(dK=whole["dK"][cols], dV=whole["dV"][cols])
+            gotu.update(dK=f64(dK[b, cols, h]), dV=f64(dV[b, cols, h]))
+            del whole
+        pu.judge(f"2^31 elements, unit ({b},{h}), sampled rows and columns", gotu, exp, ref, standard=True, d=d)
     for t in (O, L, dQ, dK, dV):
         # finiteness of everything, in slices (a 4 GiB tensor widened at once would double the footprint)
         for b in range(B):

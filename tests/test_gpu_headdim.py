@@ -52,9 +52,9 @@ def test_packed_ragged_batches_with_two_lengths(d):
     Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (Qb, Kb, Vb, dOb))
     eO, eL = orc.varlen_forward(Qf, Kf, Vf, cu_q, scale, True, cu_seqlens_k=cu_k)
     edQ, edK, edV = orc.varlen_backward(Qf, Kf, Vf, dOf, cu_q, scale, True, cu_seqlens_k=cu_k)
-    for nm, got, exp in (("O", O, eO), ("LSE", L, eL), ("dQ", dQ, edQ), ("dK", dK, edK), ("dV", dV, edV)):
-        err = pu.maxdiff(pu.to_f64(got), exp)
-        assert err <= pu.tolerance(nm, exp), f"{nm}: {err:.3e}"
+    ref = pu.reference_batch(Q, K, V, dO, scale, True, cu_q=cu_q, cu_k=cu_k)
+    pu.judge(f"ragged, two lengths, d{d}", {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
+             dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, d=d)
 
 
 @pytest.mark.parametrize("d", [24, 96])
@@ -78,10 +78,8 @@ def test_nothing_is_written_past_a_rows_real_length(d):
     torch.cuda.synchronize()
     for buf in (bO, bQ, bK, bV):
         assert bool((buf[:pad] == 7.0).all()) and bool((buf[-pad:] == 7.0).all())
-    exp = pu.run_oracle(prob)
-    for nm, got in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
-        err = pu.maxdiff(pu.to_f64(got), exp[nm])
-        assert err <= pu.tolerance(nm, exp[nm]), f"{nm}: {err:.3e}"
+    pu.judge(f"guarded outputs, d{d}", {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
+             pu.run_oracle(prob), pu.run_reference(prob), d=d)
 
 
 def test_dropout_and_split_keys_keep_to_the_tile_widths():

@@ -50,17 +50,10 @@ def check_mask(prob, mbits, fwd_only=False):
         got.update(dQ=dQ, dK=dK, dV=dV)
         exp.update(zip(("dQ", "dK", "dV"), orc.attention_backward_masked(Qf, Kf, Vf, Mf, dOf, prob.scale, prob.causal)))
     torch.cuda.synchronize()
-    errs = {}
-    for nm in got:
-        g, e = pu.to_f64(got[nm]), exp[nm]
-        if nm == "LSE":  # rows without keys: -inf on both sides, compared apart
-            dead = np.isneginf(e)
-            assert np.array_equal(np.isneginf(g), dead), "rows without keys"
-            g, e = np.where(dead, 0.0, g), np.where(dead, 0.0, e)
-        assert np.all(np.isfinite(g)), nm
-        errs[nm] = pu.maxdiff(g, e)
-        assert errs[nm] <= pu.tolerance(nm, e), f"{nm}: {errs[nm]:.3e}"
-    return errs
+    Bm, Hm, Nq, Nk = mbits.shape
+    ref = pu.reference_batch(Q, K, V, dO, prob.scale, prob.causal, backward=not fwd_only, M=M[:, :, :, :Nk])
+    res = pu.judge(f"mask {pu.describe(prob)} shared {Bm}x{Hm}", {k: pu.to_f64(v) for k, v in got.items()}, exp, ref, d=prob.d)
+    return {k: v[0] for k, v in res.items()}
 
 
 @pytest.mark.parametrize("causal", [False, True])
@@ -178,7 +171,8 @@ def test_full_size_masked_workload_sampled_units():
         m = M[0, h].double().cpu().numpy()
         o, lse, _ = orc.head_forward_masked(q, k, v, m, prob.scale, True)
         dq, dk, dv = orc.head_backward_masked(q, k, v, m, do, prob.scale, True)
-        for nm, got, exp in (("O", O[b, :, h], o), ("LSE", L[b, h], lse), ("dQ", dQ[b, :, h], dq),
-                             ("dK", dK[b, :, h], dk), ("dV", dV[b, :, h], dv)):
-            err = pu.maxdiff(pu.to_f64(got), exp)
-            assert err <= pu.tolerance(nm, exp), f"unit ({b},{h}) {nm}: {err:.3e}"
+        ref = pu.reference_head(Q[b, :, h], K[b, :, h], V[b, :, h], dO[b, :, h], prob.scale, True, M=M[0, h, :, :N])
+        pu.judge(f"masked {prob.name} unit ({b},{h})",
+                 {nm: pu.to_f64(t) for nm, t in (("O", O[b, :, h]), ("LSE", L[b, h]), ("dQ", dQ[b, :, h]), ("dK", dK[b, :, h]),
+                                                 ("dV", dV[b, :, h]))},
+                 dict(O=o, LSE=lse, dQ=dq, dK=dk, dV=dv), ref, d=prob.d)

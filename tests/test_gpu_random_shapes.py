@@ -59,5 +59,4 @@ def test_extreme_score_ranges(qk_mult, d, causal):
     rounding (scores of several hundred, a softmax that is almost one-hot, row maxima that keep
     growing along the keys: the running reference is advanced many times)."""
     prob = inputs.make_dense(B=1, N=700, Hq=2, Hkv=1, d=d, causal=causal, seed=14000 + d, qk_mult=qk_mult)
-    errs = check(prob, ref_compare=False)
-    assert errs["LSE"] <= 1e-3 * max(1.0, qk_mult)
+    check(prob)
