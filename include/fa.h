@@ -115,6 +115,25 @@ int fa_bwd_stages(const void* Q, const void* K, const void* V, const void* O, co
                   void* stream);
 
 /*
+ * fa_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, results
+ * (bit for bit) and errors as fa_bwd, without `workspace`: D = rowsum(dO o O) goes to a
+ * file-scope device array of FA_NOALLOC_MAX_ROWS floats (8 MiB) inside the library, which
+ * every GPU the library has run on holds until the process ends. The call itself allocates
+ * and frees nothing. B * N * Hq above FA_NOALLOC_MAX_ROWS returns FA_ERR_WORKSPACE and nothing
+ * runs. The first call on a device looks the array's address up (hipGetSymbolAddress, with
+ * that device current; a failure returns FA_ERR_LAUNCH, see fa_last_hip_error()): make that
+ * first call outside graph capture. All calls on one GPU share the one array: calls that may
+ * overlap on a GPU (different streams, or graphs replayed concurrently) race on it and must be
+ * ordered by the caller; nothing in it needs clearing between calls (every call first
+ * overwrites the part it then reads).
+ */
+#define FA_NOALLOC_MAX_ROWS (2 * 1024 * 1024)
+int fa_bwd_noalloc(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                   const float* LSE, void* dQ, void* dK, void* dV,
+                   int B, int Hq, int Hkv, int N, int d, float scale, int causal, void* stream);
+
+/*
  * Packed ragged batch (not in the paper; each sequence is an independent
  * attention problem of Algorithm 1 / Algorithm 2). `cu_seqlens` is a DEVICE
  * array of nseq + 1 non-decreasing int32 offsets starting at 0;

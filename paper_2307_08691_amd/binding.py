@@ -34,6 +34,7 @@ SIGNATURES = {
     "fa_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_float, _c_int, _c_void_p]),
     "fa_bwd_workspace_bytes": (_c_size_t, [_c_int] * 5),
     "fa_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 5 + [_c_float, _c_int, _c_void_p]),
+    "fa_bwd_noalloc": (_c_int, [_c_void_p] * 9 + [_c_int] * 5 + [_c_float, _c_int, _c_void_p]),
     "fa_bwd_stages": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 5 +
                       [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_varlen_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
@@ -122,6 +123,10 @@ def fa_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, N, d, scale, causal, stream=0) -> in
 
 def fa_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, causal, stream=0) -> int:
     return load().fa_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, int(causal), stream)
+
+
+def fa_bwd_noalloc_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, B, Hq, Hkv, N, d, scale, causal, stream=0) -> int:
+    return load().fa_bwd_noalloc(Q, K, V, O, dO, LSE, dQ, dK, dV, B, Hq, Hkv, N, d, scale, int(causal), stream)
 
 
 def fa_bwd_stages_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, N, d, scale, causal, stages,
@@ -274,6 +279,19 @@ def fa_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV
                       _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, N, d, scale, causal,
                       _stream()))
     return dQ, dK, dV
+
+
+FA_NOALLOC_MAX_ROWS = 2 * 1024 * 1024  # (query row, head) pairs that fa_bwd_noalloc's static scratch holds
+
+
+def fa_bwd_noalloc(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ, dK, dV) -> None:
+    """Dense backward into caller-supplied dQ, dK, dV without a workspace: nothing is allocated,
+    here or in the library (D lives in a static device array; at most FA_NOALLOC_MAX_ROWS
+    (query row, head) pairs). Calls on one GPU must not overlap."""
+    B, N, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    _check(fa_bwd_noalloc_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                              B, Hq, Hkv, N, d, scale, causal, _stream()))
 
 
 def fa_bwd_stages(Q, K, V, O, dO, LSE, scale: float, causal: bool, stages: int, dQ, dK, dV, workspace) -> None:

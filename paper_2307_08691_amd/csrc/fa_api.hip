@@ -2,10 +2,45 @@
 #include "../../include/fa.h"
 #include "fa_kernels.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 
+// Scratch of fa_bwd_noalloc: D = rowsum(dO o O) for up to FA_NOALLOC_MAX_ROWS (query row, head)
+// pairs. Every GPU the library runs on holds its own copy of this array, at its own address,
+// until the process ends. In host code the name below is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) float scratch[FA_NOALLOC_MAX_ROWS];
+
 namespace {
+
+// device address of `scratch` on each GPU, looked up once per device
+constexpr int kMaxDevices = 64;
+std::atomic<float*> g_scratch[kMaxDevices];
+
+// 0 and the address, or a negative status (and the HIP error kept for fa_last_hip_error)
+int scratch_on_current_device(float** out, int* hip_error) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  if (e == hipSuccess) {
+    float* p = g_scratch[dev].load(std::memory_order_acquire);
+    if (!p) {  // first call on this device (two threads racing here look up the same address)
+      void* sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e == hipSuccess && !sym) e = hipErrorInvalidSymbol;
+      if (e == hipSuccess) {
+        p = (float*)sym;
+        g_scratch[dev].store(p, std::memory_order_release);
+      }
+    }
+    if (e == hipSuccess) {
+      *out = p;
+      return FA_OK;
+    }
+  }
+  *hip_error = (int)e;
+  return FA_ERR_LAUNCH;
+}
 
 thread_local int g_last_hip_error = 0;
 
@@ -180,7 +215,8 @@ const char* fa_status_string(int status) {
     case FA_ERR_UNSUPPORTED:
       return "unsupported head dimension (multiples of 8 up to 128; dropout, mask and split keys: 64 and 128 only)";
     case FA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
-    case FA_ERR_WORKSPACE: return "workspace too small";
+    case FA_ERR_WORKSPACE:
+      return "workspace too small (fa_bwd_noalloc: more than FA_NOALLOC_MAX_ROWS (query row, head) pairs)";
     case FA_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
     default: return "unknown status";
   }
@@ -225,6 +261,17 @@ int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const voi
            float scale, int causal, void* stream) {
   return fa_bwd_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, N, d, scale, causal,
                        FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
+}
+
+int fa_bwd_noalloc(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                   void* dQ, void* dK, void* dV, int B, int Hq, int Hkv, int N, int d, float scale, int causal,
+                   void* stream) {
+  // sizes first: a problem that does not fit the static array is refused before anything else happens
+  if (B > 0 && Hq > 0 && N > 0 && (long long)B * N * Hq > (long long)FA_NOALLOC_MAX_ROWS) return FA_ERR_WORKSPACE;
+  float* ws = nullptr;
+  if (int e = scratch_on_current_device(&ws, &g_last_hip_error)) return e;
+  return fa_bwd_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, sizeof(float) * (size_t)FA_NOALLOC_MAX_ROWS, B, Hq, Hkv, N,
+                       d, scale, causal, FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ, stream);
 }
 
 static int check_varlen(const int32_t* cu, int nseq, int total_tokens, int max_seqlen) {
