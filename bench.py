@@ -1,34 +1,45 @@
 #!/usr/bin/env python3
 """Benchmark of the attention hot path on one MI355X.
 
-One "step" is one pass of the whole hot path over one batch of synthetic input:
-fa_fwd (Algorithm 1) followed by fa_bwd (Algorithm 2: D pre-pass, dK/dV kernel, dQ
-kernel) on the workload named in `config.workload`, inputs resident in HBM.
-Workloads with two lengths run fa_cross_fwd + fa_cross_bwd; workloads with a
-handful of query rows against a long cache run fa_splitkv_fwd alone and report
-GB/s of compulsory traffic against the HBM roofline. Throughput is
-counted with the paper's formula (section 4.1): forward 4*N^2*d FLOPs per head
-and sequence, halved under the causal mask, backward 2.5x that.
+One "step" is one pass of the whole hot path over one batch of synthetic input, through the
+entry points a user calls: the forward (Algorithm 1) followed by the backward (Algorithm 2: D
+pre-pass, dK/dV kernel, dQ kernel) of the workload named in `config.workload`, inputs resident
+in HBM. Dense workloads run fa_fwd + fa_bwd, packed ragged ones fa_varlen_fwd + fa_varlen_bwd,
+workloads with two lengths fa_cross_*, half precision fa_cross_*_f16, dropout and mask workloads
+their own entry points; a handful of query rows against a long cache runs fa_splitkv_fwd alone
+and reports GB/s of compulsory traffic against the HBM roofline. Throughput is counted with the
+paper's formula (section 4.1): forward 4*N^2*d FLOPs per head and sequence, halved under the
+causal mask, backward 2.5x that.
+
+The timed region holds exactly `--steps` steps and nothing else (no events inside). After it,
+outside the timed region, the same number of forward calls and of backward calls are timed
+apart with HIP events, and (dense bf16 workloads) every backward kernel on its own through
+fa_bwd_stages: those per-kernel durations feed the roofline objects.
 
 Prints ONE JSON line. Besides the contract fields it carries
-  roofline     - the dominant kernel (backward dK/dV) against the bf16 MFMA peak: the
-                 FLOPs of the four products it performs divided by its duration, which
-                 is measured with HIP events inside the timed loop;
+  fwd, bwd     - TFLOPs/s, ms and fraction of the bf16 MFMA peak of the two passes timed apart;
+  roofline     - the dominant kernel (backward dK/dV) against the bf16 MFMA peak: the FLOPs of
+                 the four products it performs divided by its average duration;
   roofline_fwd, roofline_dq - the same for the forward and the dQ kernels;
   mfma_loop    - TFLOP/s and shader clock of a register-resident loop of the same MFMA on
                  constant and on pseudo-random operands: what the pipe sustains on this machine;
   cpu_baseline - the float64 oracle timed on the host cores on a bounded sample;
-  sweep        - (default workload only, after the timed region) the paper's benchmark grid
-                 (section 4.1: 16k tokens, hidden 2048, d = 64 with 32 heads and d = 128 with 16,
-                 N = 512 .. 16k, with and without the causal mask): forward and forward+backward
-                 TFLOPs/s of every point, so that one run carries the whole metric. The headline
-                 `value` stays the single workload named in `config`.
+  configs      - (default workload only) forward / backward / both for the three single
+                 workloads of the metric: d = 128 N = 8192 causal, the long x3 sequence, the
+                 grouped-head ragged batch;
+  sweep        - (default workload only) the paper's benchmark grid (section 4.1: 16k tokens,
+                 hidden 2048, d = 64 with 32 heads and d = 128 with 16, N = 512 .. 16k, with and
+                 without the causal mask): forward, backward and forward+backward TFLOPs/s and the
+                 fractions of peak at every point, so that one run carries the whole metric. The
+                 headline `value` stays the single workload named in `config`.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -36,12 +47,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA peak
 
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes recorded
 # under profiles/pmc_<workload>_kernels.md, already scaled by the copy-kernel factors given there.
-# A counter pass cannot run inside this script; workloads without a recorded pass report null.
+# A counter pass cannot run inside this script, so the figures are only reported as `traffic` while
+# the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
+# of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
+    "sources": "unset",
     "d128_n8k_causal": {"fwd_kernel": 647689454, "bwd_dkdv_kernel": 828062947, "bwd_dq_kernel": 740116376},
     "sweep_d128_n8192_full": {"fwd_kernel": 269784965, "bwd_dkdv_kernel": 405079995, "bwd_dq_kernel": 337935017},
     "sweep_d64_n8192_causal": {"fwd_kernel": 884646395, "bwd_dkdv_kernel": 879984373, "bwd_dq_kernel": 830892697},
@@ -50,80 +64,225 @@ MEASURED_TRAFFIC = {
 }
 
 
+def kernel_sources_id() -> str:
+    """Short hash of the kernel sources (csrc/*.hip, *.h): identifies what a counter pass measured."""
+    d = os.path.join(ROOT, "paper_2307_08691_amd", "csrc")
+    h = hashlib.sha1()
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def traffic_fields(workload: str, kernel: str) -> dict:
+    rec = MEASURED_TRAFFIC.get(workload, {}).get(kernel)
+    if rec is None:
+        return {"traffic": None}
+    if MEASURED_TRAFFIC["sources"] == kernel_sources_id():
+        return {"traffic": rec, "traffic_from": f"profiles/pmc_{workload}_kernels.md"}
+    return {"traffic": None, "traffic_recorded": {"bytes": rec, "profile": f"profiles/pmc_{workload}_kernels.md",
+                                                  "kernel_sources": MEASURED_TRAFFIC["sources"],
+                                                  "note": "measured on other kernel sources than this run's"}}
+
+
+# ---------------------------------------------------------------------------------------------
+# one workload on the GPU: its buffers and the calls of one step
+# ---------------------------------------------------------------------------------------------
+
+class Runner:
+    """Buffers of one workload and the forward / backward calls of its entry points."""
+
+    def __init__(self, prob, binding, torch, on_device=None):
+        import numpy as np
+        self.prob, self.b, self.torch = prob, binding, torch
+        et = torch.float16 if prob.dtype == "f16" else torch.bfloat16
+
+        def gpu(bits):
+            return torch.from_numpy(bits.view(np.int16)).cuda().view(et)
+
+        self.Q, self.K, self.V, self.dO = on_device if on_device is not None else (gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+        Q, K = self.Q, self.K
+        self.O = torch.empty_like(Q)
+        self.dQ, self.dK, self.dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(self.V)
+        self.sc, self.ca = prob.scale, prob.causal
+        self.stages = None
+        self.drop = prob.meta.get("dropout")     # (p, seed) or None
+        self.M = None
+        if prob.varlen:
+            T, Hq, d = Q.shape
+            self.cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
+            self.mx = int(prob.seqlens.max())
+            self.LSE = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+            self.ws = torch.empty(binding.fa_varlen_bwd_workspace_bytes(T, Hq, prob.Hkv, d), dtype=torch.uint8, device="cuda")
+            self.kind = "varlen_dropout" if self.drop else "varlen"
+        else:
+            B, N, Hq, d = Q.shape
+            self.LSE = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
+            self.ws = torch.empty(binding.fa_cross_bwd_workspace_bytes(B, Hq, prob.Hkv, N, prob.keys, d), dtype=torch.uint8,
+                                  device="cuda")
+            if prob.meta.get("mask"):
+                mk = prob.meta["mask"]
+                gen = torch.Generator(device="cuda").manual_seed(mk["seed"])
+                Hm = Hq if mk.get("per_head", True) else 1
+                Bm = B if mk.get("per_sequence", True) else 1
+                self.M = binding.mask_buffer(Bm, Hm, N, prob.keys)
+                self.M.copy_(2.0 * torch.randn(Bm, Hm, N, prob.keys, device="cuda", generator=gen))
+                gone = torch.rand(Bm, Hm, N, prob.keys, device="cuda", generator=gen) < mk.get("removed", 0.3)
+                gone[..., 0] = False
+                self.M.masked_fill_(gone, float("-inf"))
+                del gone
+                self.kind = "mask"
+            elif self.drop:
+                self.kind = "dropout"
+            elif prob.Nk or prob.dtype == "f16":
+                self.kind = "cross"
+            else:
+                self.kind = "dense"
+                self.stages = lambda st: binding.fa_bwd_stages(self.Q, self.K, self.V, self.O, self.dO, self.LSE, self.sc,
+                                                               self.ca, st, self.dQ, self.dK, self.dV, self.ws)
+
+    def entry_points(self):
+        return {"dense": "fa_fwd + fa_bwd", "cross": "fa_cross_fwd + fa_cross_bwd" + ("_f16" if self.prob.dtype == "f16" else ""),
+                "varlen": "fa_varlen_fwd + fa_varlen_bwd", "dropout": "fa_dropout_fwd + fa_dropout_bwd",
+                "varlen_dropout": "fa_varlen_dropout_fwd + fa_varlen_dropout_bwd", "mask": "fa_mask_fwd + fa_mask_bwd"}[self.kind]
+
+    def fwd(self):
+        b, k = self.b, self.kind
+        a = (self.Q, self.K, self.V)
+        if k == "dense":
+            b.fa_fwd(*a, self.sc, self.ca, O=self.O, LSE=self.LSE)
+        elif k == "cross":
+            b.fa_cross_fwd(*a, self.sc, self.ca, O=self.O, LSE=self.LSE)
+        elif k == "varlen":
+            b.fa_varlen_fwd(*a, self.cu, self.mx, self.sc, self.ca, O=self.O, LSE=self.LSE)
+        elif k == "dropout":
+            b.fa_dropout_fwd(*a, self.sc, self.ca, *self.drop, O=self.O, LSE=self.LSE)
+        elif k == "varlen_dropout":
+            b.fa_varlen_dropout_fwd(*a, self.cu, self.mx, self.sc, self.ca, *self.drop, O=self.O, LSE=self.LSE)
+        else:
+            b.fa_mask_fwd(*a, self.M, self.sc, self.ca, O=self.O, LSE=self.LSE)
+
+    def bwd(self):
+        b, k = self.b, self.kind
+        a = (self.Q, self.K, self.V)
+        out = dict(dQ=self.dQ, dK=self.dK, dV=self.dV, workspace=self.ws)
+        if k == "dense":
+            b.fa_bwd(*a, self.O, self.dO, self.LSE, self.sc, self.ca, **out)
+        elif k == "cross":
+            b.fa_cross_bwd(*a, self.O, self.dO, self.LSE, self.sc, self.ca, **out)
+        elif k == "varlen":
+            b.fa_varlen_bwd(*a, self.O, self.dO, self.LSE, self.cu, self.mx, self.sc, self.ca, **out)
+        elif k == "dropout":
+            b.fa_dropout_bwd(*a, self.O, self.dO, self.LSE, self.sc, self.ca, *self.drop, **out)
+        elif k == "varlen_dropout":
+            b.fa_varlen_dropout_bwd(*a, self.O, self.dO, self.LSE, self.cu, self.mx, self.sc, self.ca, *self.drop, **out)
+        else:
+            b.fa_mask_bwd(*a, self.M, self.O, self.dO, self.LSE, self.sc, self.ca, **out)
+
+    def both(self):
+        self.fwd()
+        self.bwd()
+
+    def event_ms(self, fn, calls: int) -> float:
+        """Average duration of `calls` back-to-back calls of fn, by HIP events on torch's current
+        stream (the one the library launches on)."""
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(calls):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / calls
+
+
+def three_rates(prob, fwd_ms, bwd_ms, both_ms):
+    fl = prob.fwd_flops()
+    r = {"fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "fwd_bwd_ms": round(both_ms, 4),
+         "fwd_tflops": round(fl / fwd_ms / 1e9, 1), "bwd_tflops": round(2.5 * fl / bwd_ms / 1e9, 1),
+         "fwd_bwd_tflops": round(3.5 * fl / both_ms / 1e9, 1)}
+    for k in ("fwd", "bwd", "fwd_bwd"):
+        r[k + "_frac_of_peak"] = round(r[k + "_tflops"] / PEAK_BF16_TFLOPS, 4)
+    return r
+
+
+def measure_config(name, binding, torch, inputs, calls=10, warmup=3):
+    """Forward / backward / both of one named workload: `warmup` steps, then `calls` calls of each."""
+    prob = inputs.make_config(name)
+    r = Runner(prob, binding, torch)
+    for _ in range(warmup):
+        r.both()
+    torch.cuda.synchronize()
+    out = three_rates(prob, r.event_ms(r.fwd, calls), r.event_ms(r.bwd, calls), r.event_ms(r.both, calls))
+    out["entry_points"] = r.entry_points()
+    return out
+
+
 def cpu_baseline(prob, budget_s: float = 12.0):
     """Time the float64 oracle (forward + backward) on as many (sequence, head)
     units of the workload as fit in about `budget_s` seconds, all host cores,
     and scale to the metric's unit with the same FLOP formula."""
-    import numpy as np
     from oracle import attention_oracle as orc
 
     cores = len(os.sched_getaffinity(0))
     G = prob.Hq // prob.Hkv
-    units = []
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
+    if prob.varlen:
+        cu = prob.cu_seqlens
+        todo = [(s, h) for s in range(len(cu) - 1) for h in range(prob.Hq)]
+    else:
+        todo = [(b, h) for b in range(prob.B) for h in range(prob.Hq)]
+    done, pairs = 0, 0.0  # pairs: visible (query, key) pairs of the units done, as the metric counts them
     t0 = time.perf_counter()
-    for (b, h) in [(b, h) for b in range(prob.B) for h in range(prob.Hq)]:
-        if units and time.perf_counter() - t0 > budget_s:
+    for (s, h) in todo:
+        if done and time.perf_counter() - t0 > budget_s:
             break
-        units.append((b, h))
-        q = orc.widen_bf16(prob.Q[b, :, h])
-        k = orc.widen_bf16(prob.K[b, :, h // G])
-        v = orc.widen_bf16(prob.V[b, :, h // G])
-        do = orc.widen_bf16(prob.dO[b, :, h])
+        rows = slice(int(cu[s]), int(cu[s + 1])) if prob.varlen else (s, slice(None))
+        q, k, v, do = (widen(x) for x in (prob.Q[rows][..., h, :], prob.K[rows][..., h // G, :], prob.V[rows][..., h // G, :],
+                                          prob.dO[rows][..., h, :]))
+        nq, nk = q.shape[0], k.shape[0]
+        if nq == 0:
+            continue
         orc.head_backward(q, k, v, do, prob.scale, prob.causal)  # recomputes the forward inside
+        pairs += float(nq) * nk - (0.5 * float(nq) ** 2 if prob.causal else 0.0)
+        done += 1
+    flops = 3.5 * 4.0 * prob.d * pairs
     dt = time.perf_counter() - t0
-    per_unit = 3.5 * prob.fwd_flops() / (prob.B * prob.Hq)  # the metric's forward + backward FLOPs of one unit
     return {
-        "value": per_unit * len(units) / dt / 1e12,
+        "value": flops / dt / 1e12,
         "unit": "TFLOPs/s",
         "cores": cores,
         "kind": "oracle",
-        "sample": f"{len(units)} of {prob.B * prob.Hq} (sequence, head) units of {prob.name}, forward+backward, "
+        "sample": f"{done} of {len(todo)} (sequence, head) units of {prob.name}, forward+backward, "
                   f"float64 numpy, {dt:.1f} s",
     }
 
 
-def paper_grid(binding, torch, samples: int = 20, warmup: int = 5):
-    """Forward and forward+backward TFLOPs/s over the grid of section 4.1. Inputs are drawn on the
-    GPU (N(0,1) rounded to bf16, seeded): the values do not change the work. Per point: `warmup`
+def paper_grid(binding, torch, inputs, samples: int = 20, warmup: int = 5):
+    """Forward, backward and forward+backward TFLOPs/s over the grid of section 4.1. Inputs are drawn on
+    the GPU (N(0,1) rounded to bf16, seeded): the values do not change the work. Per point: `warmup`
     calls, then the median of `samples` timed batches (short calls are timed several at a time:
     a batch lasts about a millisecond)."""
-    import statistics
     gen = torch.Generator(device="cuda").manual_seed(1002)
     out = {}
     for d, H in ((64, 32), (128, 16)):
         for N in (512, 1024, 2048, 4096, 8192, 16384):
             B = 16384 // N
-            Q, K, V, dO = (torch.randn(B, N, H, d, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
-            O = torch.empty_like(Q)
-            LSE = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
-            dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-            ws = torch.empty(binding.fa_bwd_workspace_bytes(B, H, H, N, d), dtype=torch.uint8, device="cuda")
-            sc = d ** -0.5
+            dev = tuple(torch.randn(B, N, H, d, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
             for causal in (False, True):
-                def fwd():
-                    binding.fa_fwd(Q, K, V, sc, causal, O=O, LSE=LSE)
-
-                def both():
-                    fwd()
-                    binding.fa_bwd(Q, K, V, O, dO, LSE, sc, causal, dQ=dQ, dK=dK, dV=dV, workspace=ws)
-
+                prob = inputs.shape_only(B=B, N=N, Hq=H, Hkv=H, d=d, causal=causal, name=inputs.sweep_name(d, N, causal))
+                r = Runner(prob, binding, torch, on_device=dev)
                 ms = []
-                for fn in (fwd, both):
-                    def timed(k):
-                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                        e0.record()
-                        for _ in range(k):
-                            fn()
-                        e1.record()
-                        torch.cuda.synchronize()
-                        return e0.elapsed_time(e1) / k
+                for fn in (r.fwd, r.bwd, r.both):
                     for _ in range(warmup):
                         fn()
-                    k = max(1, min(16, int(1.0 / max(timed(1), 1e-3))))
-                    ms.append(statistics.median(timed(k) for _ in range(samples)))
-                fl = 4.0 * B * H * N * N * d * (0.5 if causal else 1.0)
-                out[f"d{d}_n{N}_{'causal' if causal else 'full'}"] = {
-                    "fwd_tflops": round(fl / ms[0] / 1e9, 1), "fwd_bwd_tflops": round(3.5 * fl / ms[1] / 1e9, 1)}
+                    torch.cuda.synchronize()
+                    k = max(1, min(16, int(1.0 / max(r.event_ms(fn, 1), 1e-3))))
+                    ms.append(statistics.median(r.event_ms(fn, k) for _ in range(samples)))
+                out[f"d{d}_n{N}_{'causal' if causal else 'full'}"] = three_rates(prob, *ms)
+                del r
+            del dev
     return out
 
 
@@ -168,7 +327,7 @@ def bench_decode(args, prob, binding) -> int:
         "config": {"workload": prob.name, "B": B, "Nq": Nq, "Nk": prob.Nk, "Hq": Hq, "Hkv": prob.Hkv, "d": d,
                    "causal": prob.causal, "num_splits": splits, "algorithmic_bytes": alg_bytes},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
-                     "traffic": MEASURED_TRAFFIC.get(prob.name, {}).get("fwd_kernel"), "avg_kernel_ms": kern_ms,
+                     **traffic_fields(prob.name, "fwd_kernel"), "avg_kernel_ms": kern_ms,
                      "kernel": "fwd_kernel<.., split> + fwd_merge_kernel"},
     }
     if not args.no_cpu_baseline:
@@ -194,8 +353,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="d128_n8k_causal")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--fwd-only", action="store_true", help="profiling aid: time the forward alone")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the grid of section 4.1 after the timed region")
+    ap.add_argument("--fwd-only", action="store_true", help="profiling aid: a step is the forward alone")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the grid of section 4.1 and the other configs after the timed region")
+    ap.add_argument("--list-workloads", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="profiling aid: instead of the benchmark, run 5 device-to-device copies of BYTES bytes; "
                          "under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE they give the counters' scale factors")
@@ -204,9 +365,12 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
 
-    import numpy as np
+    from paper_2307_08691_amd import inputs
+    if args.list_workloads:
+        print("\n".join(sorted(inputs.CONFIGS)))
+        return 0
     import torch
-    from paper_2307_08691_amd import binding, inputs
+    from paper_2307_08691_amd import binding
 
     binding.load()
     torch.cuda.set_device(0)
@@ -220,76 +384,36 @@ def main() -> int:
         print(json.dumps({"copy_calibration_bytes": args.copy_calibration, "copies": 5}))
         return 0
     prob = inputs.make_config(args.workload)
-    if prob.varlen:
-        print("bench.py: pick a dense workload", file=sys.stderr)
-        return 2
-    if prob.Nk and prob.N * (prob.Hq // prob.Hkv) <= 256:
+    if prob.Nk and not prob.varlen and prob.N * (prob.Hq // prob.Hkv) <= 256:
         return bench_decode(args, prob, binding)
 
-    def gpu(bits):
-        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-
-    Q, K, V, dO = (gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
-    B, N, Hq, d = Q.shape
-    O = torch.empty_like(Q)
-    LSE = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
-    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-    ws = torch.empty(binding.fa_bwd_workspace_bytes(B, Hq, prob.Hkv, N, d), dtype=torch.uint8, device="cuda")
-    sc, ca = prob.scale, prob.causal
-
-    def step(ev=None):
-        """fa_fwd + the three backward launches, in the order fa_bwd issues them; with `ev`
-        the forward, dK/dV and dQ kernels are bracketed by events."""
-        if ev:
-            ev[0].record()
-        if prob.Nk:  # two lengths: one call per pass, the backward is not taken apart
-            binding.fa_cross_fwd(Q, K, V, sc, ca, O=O, LSE=LSE)
-            if ev:
-                ev[1].record()
-            if not args.fwd_only:
-                binding.fa_cross_bwd(Q, K, V, O, dO, LSE, sc, ca, dQ=dQ, dK=dK, dV=dV, workspace=ws)
-            if ev:
-                for e in ev[2:]:
-                    e.record()
-            return
-        binding.fa_fwd(Q, K, V, sc, ca, O=O, LSE=LSE)
-        if ev:
-            ev[1].record()
-        if args.fwd_only:
-            return
-        binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 1, dQ, dK, dV, ws)
-        if ev:
-            ev[2].record()
-        binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 2, dQ, dK, dV, ws)
-        if ev:
-            ev[3].record()
-        binding.fa_bwd_stages(Q, K, V, O, dO, LSE, sc, ca, 4, dQ, dK, dV, ws)
-        if ev:
-            ev[4].record()
-
+    r = Runner(prob, binding, torch)
+    step = r.fwd if args.fwd_only else r.both
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # events are recorded on torch's current stream, the one the kernels are launched on
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
+    # ---- the timed region: exactly `steps` steps of the entry points, nothing else
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(evs[i])
+    for _ in range(args.steps):
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
     fwd_fl, bwd_fl = prob.fwd_flops(), prob.bwd_flops()
     total_fl = fwd_fl if args.fwd_only else fwd_fl + bwd_fl
     value = total_fl / (ms_per_step * 1e-3) / 1e12
 
+    # ---- after it: the two passes apart, and each backward kernel on its own (HIP events)
+    fwd_ms = r.event_ms(r.fwd, args.steps)
+    bwd_ms = None if args.fwd_only else r.event_ms(r.bwd, args.steps)
+
     def roof(flops, ms, kernel):
         ach = flops / (ms * 1e-3) / 1e12
         return {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(prob.name, {}).get(kernel),
-                "avg_kernel_ms": ms, "kernel": kernel}
+                "frac": ach / PEAK_BF16_TFLOPS, **traffic_fields(prob.name, kernel), "avg_kernel_ms": ms, "kernel": kernel}
 
+    shape = {"T": prob.total_tokens, "nseq": len(prob.seqlens), "max_seqlen": int(prob.seqlens.max())} if prob.varlen else \
+        {"B": prob.B, "N": prob.N, **({"Nk": prob.Nk} if prob.Nk else {})}
     out = {
         "metric": "attention fwd+bwd TFLOPs/s (bf16)" if not args.fwd_only else "attention fwd TFLOPs/s (bf16)",
         "value": value,
@@ -301,34 +425,45 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": prob.dtype,  # the arithmetic type of the MFMA operands; accumulation is float32
         "data": "synthetic",
-        "config": {"workload": prob.name, "B": B, "N": N, "Hq": Hq, "Hkv": prob.Hkv, "d": d, "causal": ca,
-                   "scale": sc, "fwd_flops": fwd_fl, "bwd_flops": bwd_fl},
+        "config": {"workload": prob.name, **shape, "Hq": prob.Hq, "Hkv": prob.Hkv, "d": prob.d, "causal": prob.causal,
+                   "scale": prob.scale, "fwd_flops": fwd_fl, "bwd_flops": bwd_fl, "entry_points": r.entry_points(),
+                   **{k: v for k, v in prob.meta.items() if k in ("dropout", "mask", "qk_mult")}},
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
+        "kernel_sources": kernel_sources_id(),
+        "fwd": {"ms": fwd_ms, "tflops": fwd_fl / fwd_ms / 1e9, "frac_of_peak": fwd_fl / fwd_ms / 1e9 / PEAK_BF16_TFLOPS},
         "roofline_fwd": roof(fwd_fl, fwd_ms, "fwd_kernel"),
     }
-    if prob.Nk and not args.fwd_only:
-        bwd_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-        out["roofline"] = roof(3.5 * fwd_fl, bwd_ms, "bwd_prep_kernel + bwd_dkdv_kernel + bwd_dq_kernel")
-        out["config"]["Nk"] = prob.Nk
-    elif not args.fwd_only:
+    if bwd_ms is not None:
+        out["bwd"] = {"ms": bwd_ms, "tflops": bwd_fl / bwd_ms / 1e9, "frac_of_peak": bwd_fl / bwd_ms / 1e9 / PEAK_BF16_TFLOPS}
+    if args.fwd_only:
+        out["roofline"] = out["roofline_fwd"]
+    elif r.stages is not None:
         # metric FLOPs count 5 products (2.5 x forward); the dK/dV kernel performs 4 of them
         # (S, dP, dV, dK) and the dQ kernel 3 (S, dP recomputed, dQ): 2 x and 1.5 x forward
-        dkdv_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
-        dq_ms = sum(e[3].elapsed_time(e[4]) for e in evs) / args.steps
+        prep_ms = r.event_ms(lambda: r.stages(1), args.steps)
+        dkdv_ms = r.event_ms(lambda: r.stages(2), args.steps)
+        dq_ms = r.event_ms(lambda: r.stages(4), args.steps)
         out["roofline"] = roof(2.0 * fwd_fl, dkdv_ms, "bwd_dkdv_kernel")
         out["roofline_dq"] = roof(1.5 * fwd_fl, dq_ms, "bwd_dq_kernel")
+        out["bwd"]["prep_ms"] = prep_ms
     else:
-        out["roofline"] = out["roofline_fwd"]
+        # no per-kernel entry point for this workload: the three backward launches together, against
+        # the 3.5 x forward FLOPs they execute (7 products)
+        out["roofline"] = roof(3.5 * fwd_fl, bwd_ms, "bwd_prep_kernel + bwd_dkdv_kernel + bwd_dq_kernel")
     # what the matrix pipe sustains on this machine with every operand in registers (outside the timed region)
     out["mfma_loop"] = {}
     for key, rnd in (("constant_operands", False), ("random_operands", True)):
         tf, ghz = binding.fa_mfma_probe(2000, rnd)
         out["mfma_loop"][key] = {"tflops": tf, "shader_clock_ghz": ghz}
     if not args.no_sweep and not args.fwd_only and args.workload == "d128_n8k_causal":
-        del Q, K, V, dO, O, LSE, dQ, dK, dV, ws
-        out["sweep"] = paper_grid(binding, torch)
+        out["configs"] = {prob.name: three_rates(prob, fwd_ms, bwd_ms, ms_per_step)}
+        out["configs"][prob.name]["entry_points"] = r.entry_points()
+        del r
+        for name in ("long_n16k_causal_x3", "gqa_ragged"):
+            out["configs"][name] = measure_config(name, binding, torch, inputs)
+        out["sweep"] = paper_grid(binding, torch, inputs)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(prob)
     print(json.dumps(out))

@@ -309,57 +309,79 @@ __global__ __launch_bounds__(512)
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : S[kt][r];
     }
-    float mx = max3(S[0][0], S[0][1], S[1][0]);
+    // The exponentials of the block against reference `ref` (already in the exponent's base),
+    // rounded into the operand registers of the second product; the row sum is taken from the
+    // float32 exponentials, not from their bf16 roundings: rows that see only a few keys would
+    // otherwise miss the 1e-3 bound on L. On the fast path S itself stays intact.
+    constexpr bool FAST = !GUARD && !(PAD && TWO);  // (see below)
+    float rs0, rs1;
+    auto exponentials = [&](float ref) {
+      rs0 = rs1 = 0.f;
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
-    mx = max3(mx, S[1][1], S[1][2]);
-    mx = fmaxf(mx, S[1][3]);
+      for (int kt = 0; kt < 2; ++kt) {
+        f32x16 Etmp;
+        f32x16& E = FAST ? Etmp : S[kt];  // without the fast path nobody needs S again: in place
 #pragma unroll
-    for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
-    mx = max_with_partner32(mx);
-    const float m_new = fmaxf(m, mx);
-    // column 0 is visible to every row and blocks are walked in ascending order,
-    // so m_new is finite from the first block on and exp2(-inf) = 0 covers the start.
-    // Rescaling O (line 10) by exp(m_old - m_new) only matters for the range of the numbers,
-    // not for the result: O and l are relative to the same reference m whatever it is. The
-    // reference is therefore advanced only when some row's maximum outgrew it by a factor
-    // 2^FA_FWD_LAZY_LOG2, which after the first few blocks is rare.
-    if (__builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)FA_FWD_LAZY_LOG2) != 0) {
-      // (split, mask: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
-      const float alpha = GUARD && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * cs);
-      l *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-      m = m_new;
-    }
-    // (split: a row may have seen no key yet; its scores are all -inf and must give P = 0)
-    const float mc = (GUARD && m == -INFINITY ? 0.f : m) * cs;
-    // the row sum is taken from the float32 exponentials, not from their bf16 roundings:
-    // rows that see only a few keys would otherwise miss the 1e-3 bound on L
-    float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], cs, -mc));
-        const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], cs, -mc));
-        S[kt][r] = e0;
-        S[kt][r + 1] = e1;
-        rs0 += e0;
-        rs1 += e1;
-      }
-      if constexpr (DROPOUT) {  // the row sum above is that of the undropped block; O only sees the kept entries
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {  // registers 4 q4 .. 4 q4 + 3: keys col0 + 32 kt + 8 q4 + 4 hh + 0..3
-          const uint32_t x = drop_mix(drop_lane + (uint32_t)(col0 / 4 + 8 * kt + 2 * q4) * kDropCol);
-#pragma unroll
-          for (int u = 0; u < 4; ++u) S[kt][4 * q4 + u] = ((x >> (8 * u)) & 255u) >= p.drop_thr ? S[kt][4 * q4 + u] : 0.f;
+        for (int r = 0; r < 16; r += 2) {
+          E[r] = fast_exp2(__builtin_fmaf(S[kt][r], cs, -ref));
+          E[r + 1] = fast_exp2(__builtin_fmaf(S[kt][r + 1], cs, -ref));
+          rs0 += E[r];
+          rs1 += E[r + 1];
         }
+        if constexpr (DROPOUT) {  // the row sum above is that of the undropped block; O only sees the kept entries
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {  // registers 4 q4 .. 4 q4 + 3: keys col0 + 32 kt + 8 q4 + 4 hh + 0..3
+            const uint32_t x = drop_mix(drop_lane + (uint32_t)(col0 / 4 + 8 * kt + 2 * q4) * kDropCol);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) E[4 * q4 + u] = ((x >> (8 * u)) & 255u) >= p.drop_thr ? E[4 * q4 + u] : 0.f;
+          }
+        }
+        Pf[kt][0] = pack8<F16>(E, 0);
+        Pf[kt][1] = pack8<F16>(E, 1);
       }
-      Pf[kt][0] = pack8<F16>(S[kt], 0);
-      Pf[kt][1] = pack8<F16>(S[kt], 1);
+    };
+    // The reference m of the running softmax need not be the row maximum: O and l are relative to
+    // the same reference whatever it is, and rescaling O (line 10) by exp(m_old - m_new) only
+    // matters for the range of the numbers. So the row maximum is NOT computed for every block.
+    // The block's exponentials are taken against the reference as it stands; only if some lane's
+    // share of a row sum then exceeds 2^FA_FWD_LAZY_LOG2 (which also catches an overflow to inf)
+    // is the maximum of the block found, the reference advanced to it, O and l rescaled, and the
+    // exponentials taken again. After the first few blocks that is rare: the fast path saves the
+    // 16 three-way maxima, the exchange with the partner lane and the comparison per block.
+    // The first block of a row (m = -inf) always takes the second path, and so do the
+    // instantiations in which a row may still have seen no key (split keys, elementwise mask)
+    // and the one that has no registers left to keep S beside the exponentials.
+    bool advance = !FAST || j == jb;
+    if (!advance) {
+      exponentials(m * cs);
+      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << FA_FWD_LAZY_LOG2)) != 0;
+    }
+    if (advance) {
+      float mx = max3(S[0][0], S[0][1], S[1][0]);
+#pragma unroll
+      for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
+      mx = max3(mx, S[1][1], S[1][2]);
+      mx = fmaxf(mx, S[1][3]);
+#pragma unroll
+      for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
+      mx = max_with_partner32(mx);
+      const float m_new = fmaxf(m, mx);
+      // column 0 is visible to every row and blocks are walked in ascending order, so m_new is
+      // finite from the first block on and exp2(-inf) = 0 covers the start (not so with split
+      // keys or a mask: GUARD). Without the fast path the reference is advanced only when some
+      // row's maximum outgrew it by a factor 2^FA_FWD_LAZY_LOG2.
+      if (FAST || __builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)FA_FWD_LAZY_LOG2) != 0) {
+        // (split, mask: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
+        const float alpha = GUARD && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * cs);
+        l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+        m = m_new;
+      }
+      // (split, mask: a row may have seen no key yet; its scores are all -inf and must give P = 0)
+      exponentials((GUARD && m == -INFINITY ? 0.f : m) * cs);
     }
     l += rs0 + rs1;
   };
@@ -626,16 +648,39 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : S[kt][r];
     }
-    float mx = max3(S[0][0], S[0][1], S[1][0]);
+    // (fast path without the row maximum, see fwd_kernel)
+    float rs0, rs1;
+    auto exponentials = [&](float ref) {
+      rs0 = rs1 = 0.f;
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
-    mx = max3(mx, S[1][1], S[1][2]);
-    mx = fmaxf(mx, S[1][3]);
+      for (int kt = 0; kt < 2; ++kt) {
+        f32x16 E;
 #pragma unroll
-    for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
-    mx = max_with_partner32(mx);
-    const float m_new = fmaxf(m, mx);
-    if (__builtin_amdgcn_ballot_w64((m_new - m) * c2 > (float)FA_FWD_LAZY_LOG2) != 0) {  // lazy rescale, see fwd_kernel
+        for (int r = 0; r < 16; r += 2) {
+          E[r] = fast_exp2(__builtin_fmaf(S[kt][r], c2, -ref));
+          E[r + 1] = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -ref));
+          rs0 += E[r];
+          rs1 += E[r + 1];
+        }
+        Pf[kt][0] = pack8<F16>(E, 0);
+        Pf[kt][1] = pack8<F16>(E, 1);
+      }
+    };
+    bool advance = j == 0;
+    if (!advance) {
+      exponentials(m * c2);
+      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << FA_FWD_LAZY_LOG2)) != 0;
+    }
+    if (advance) {
+      float mx = max3(S[0][0], S[0][1], S[1][0]);
+#pragma unroll
+      for (int r = 2; r < 16; r += 2) mx = max3(mx, S[0][r], S[0][r + 1]);
+      mx = max3(mx, S[1][1], S[1][2]);
+      mx = fmaxf(mx, S[1][3]);
+#pragma unroll
+      for (int r = 4; r < 16; r += 2) mx = max3(mx, S[1][r], S[1][r + 1]);
+      mx = max_with_partner32(mx);
+      const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2((m - m_new) * c2);
       l *= alpha;
 #pragma unroll
@@ -643,22 +688,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
       m = m_new;
-    }
-    const float mc = m * c2;
-    float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const float e0 = fast_exp2(__builtin_fmaf(S[kt][r], c2, -mc));
-        const float e1 = fast_exp2(__builtin_fmaf(S[kt][r + 1], c2, -mc));
-        S[kt][r] = e0;
-        S[kt][r + 1] = e1;
-        rs0 += e0;
-        rs1 += e1;
-      }
-      Pf[kt][0] = pack8<F16>(S[kt], 0);
-      Pf[kt][1] = pack8<F16>(S[kt], 1);
+      exponentials(m * c2);
     }
     l += rs0 + rs1;
   };

@@ -25,6 +25,7 @@ __all__ = [
     "make_dense",
     "make_cross",
     "make_varlen",
+    "shape_only",
     "CONFIGS",
     "make_config",
 ]
@@ -192,6 +193,20 @@ CONFIGS = {
     "d256_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=8, Hkv=8, d=256, causal=True, seed=1014),
     "d256_n8k_full": dict(kind="dense", B=2, N=8192, Hq=8, Hkv=8, d=256, causal=False, seed=1015),
     "d256_n2k_causal": dict(kind="dense", B=8, N=2048, Hq=8, Hkv=8, d=256, causal=True, seed=1016),
+    # dropout on P (p = 0.1) and an elementwise mask (a bias on 70 % of the entries, 30 % removed,
+    # one mask per sequence and head, drawn on the GPU from the given seed) on the benchmark shape
+    "dropout_d128_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1017,
+                                    dropout=(0.1, 0x5EED0D12)),
+    "dropout_d128_n8k_full": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1018,
+                                  dropout=(0.1, 0x5EED0D12)),
+    "dropout_gqa_ragged": dict(kind="varlen", nseq=16, lo=256, hi=4096, Hq=32, Hkv=8, d=128, causal=True, seed=1005,
+                               dropout=(0.1, 0x5EED0D12)),
+    "mask_d128_n8k_causal": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1019,
+                                 mask=dict(seed=9800, removed=0.3)),
+    "mask_d128_n8k_full": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1020,
+                               mask=dict(seed=9801, removed=0.3)),
+    "mask_d64_n8k_full": dict(kind="dense", B=2, N=8192, Hq=32, Hkv=32, d=64, causal=False, seed=1021,
+                              mask=dict(seed=9802, removed=0.3)),
 }
 
 
@@ -212,12 +227,23 @@ def ragged_lengths(seed: int, nseq: int, lo: int, hi: int) -> np.ndarray:
     return np.random.default_rng(seed + 7919).integers(lo, hi + 1, nseq)
 
 
+def shape_only(B, N, Hq, Hkv, d, causal, name, scale=None) -> AttnProblem:
+    """A dense problem without host tensors, for callers that draw their inputs on the GPU and only
+    need the shape and the FLOP count."""
+    return AttnProblem(name=name, Q=None, K=None, V=None, dO=None, Hq=Hq, Hkv=Hkv, d=d,
+                       scale=float(scale if scale is not None else d ** -0.5), causal=bool(causal), B=B, N=N)
+
+
 def make_config(name: str) -> AttnProblem:
     c = dict(CONFIGS[name])
     kind = c.pop("kind")
+    options = {k: c.pop(k) for k in ("dropout", "mask") if k in c}  # entry-point options, not part of the draw
     if kind == "dense":
-        return make_dense(name=name, **c)
-    if kind == "cross":
-        return make_cross(name=name, **c)
-    lens = ragged_lengths(c["seed"], c.pop("nseq"), c.pop("lo"), c.pop("hi"))
-    return make_varlen(lens, name=name, **c)
+        prob = make_dense(name=name, **c)
+    elif kind == "cross":
+        prob = make_cross(name=name, **c)
+    else:
+        lens = ragged_lengths(c["seed"], c.pop("nseq"), c.pop("lo"), c.pop("hi"))
+        prob = make_varlen(lens, name=name, **c)
+    prob.meta.update(options)
+    return prob
