@@ -277,8 +277,11 @@ int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, cons
  * fa_cross_fwd / fa_cross_bwd, with the same causal alignment. Under the causal mask every
  * sequence must have at least as many keys as queries: the library cannot see the device
  * arrays, so for a sequence that breaks this the outputs of that sequence are unspecified
- * (nothing outside the output tensors is touched). The backward workspace is that of
- * fa_varlen_bwd for total_q tokens (fa_varlen_bwd_workspace_bytes).
+ * (nothing outside the output tensors is touched). A sequence with queries but no keys at all
+ * (either setting of `causal`) has no softmax: its rows get O = 0, LSE = -inf and dQ = 0, as rows
+ * that an elementwise mask leaves without entries do, and nothing is read from K or V for it.
+ * The backward workspace is that of fa_varlen_bwd for total_q tokens
+ * (fa_varlen_bwd_workspace_bytes).
  */
 int fa_varlen_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                         const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq,

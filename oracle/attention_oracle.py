@@ -32,6 +32,9 @@ Readings taken where the text is silent or inconsistent:
     heads of a group;
   * packed ragged batches are not in the paper: each sequence, delimited by
     cumulative offsets, is an independent attention problem;
+  * a sequence of a ragged batch with queries but no keys has no softmax. Reading, the same
+    as for a row that the elementwise mask leaves without entries (below): P = 0 on those rows,
+    hence O = 0, L = -inf, and they contribute to no gradient;
   * two lengths (Nq queries against Nk keys; cross-attention, or the newest Nq
     tokens against a key/value cache, the inference setting the MQA/GQA
     paragraph of section 3.1.2 has in mind): section 2.2 defines S = QK^T for
@@ -175,6 +178,9 @@ def varlen_forward(Q, K, V, cu_seqlens, scale, causal, cu_seqlens_k=None):
         ak, ek = int(cu_k[s]), int(cu_k[s + 1])
         if e == a:
             continue
+        if ek == ak:  # queries without any key: no softmax; P = 0, so O = 0 and L = -inf
+            L[:, a:e] = -np.inf
+            continue
         o, lse = attention_forward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek], scale, causal)
         O[a:e] = o[0]
         L[:, a:e] = lse[0]
@@ -190,7 +196,7 @@ def varlen_backward(Q, K, V, dO, cu_seqlens, scale, causal, cu_seqlens_k=None):
     for s in range(len(cu_seqlens) - 1):
         a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
         ak, ek = int(cu_k[s]), int(cu_k[s + 1])
-        if e == a:
+        if e == a or ek == ak:  # no queries: nothing flows to the keys; no keys: P = 0, dQ = 0
             continue
         dq, dk, dv = attention_backward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek],
                                         dO[None, a:e], scale, causal)

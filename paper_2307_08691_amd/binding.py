@@ -11,7 +11,7 @@ import os
 from typing import Optional, Tuple
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("FA_LIB_PATH") or os.path.join(HERE, "libfa_gfx950.so")  # override: tuning builds
+LIB_PATH = os.path.join(HERE, "libfa_gfx950.so")
 
 FA_OK = 0
 FA_ERR_NULL = -1
@@ -101,7 +101,12 @@ def _check(status: int) -> None:
 
 
 def _ptr(t) -> int:
-    return 0 if t is None else t.data_ptr()
+    """Device address of a tensor for the C ABI (None -> NULL). Host tensors stop here."""
+    if t is None:
+        return 0
+    if not t.is_cuda:
+        raise ValueError("every tensor must live on the GPU")
+    return t.data_ptr()
 
 
 def _stream() -> int:
@@ -232,52 +237,135 @@ def fa_mfma_probe_raw(iters, random_operands, scratch, stream=0) -> int:
 
 # ---------------------------------------------------------------------------
 # tensor-level wrappers: same names as the C entry points
+#
+# The C ABI sees raw pointers and sizes; a tensor of the wrong shape, type or device would become
+# an out-of-bounds device access there. Every tensor is therefore checked here, before the call:
+# device, contiguity, element type and the exact shape its role implies.
 # ---------------------------------------------------------------------------
 
-def _need(t, name, dtype=None):
-    import torch
-    if not t.is_cuda:
-        raise ValueError(f"{name} must live on the GPU")
+def _need(t, name, dtype=None, shape=None, device=None):
+    # (type and shape first, so that these checks can be exercised with host tensors)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, not {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, not {tuple(t.shape)}")
     if not t.is_contiguous():
         raise ValueError(f"{name} must be contiguous")
-    if dtype is not None and t.dtype != dtype:
-        raise ValueError(f"{name} must be {dtype}")
+    if device is not None and t.device != device:
+        raise ValueError(f"{name} must be on {device}, like Q")
+    # (that the common device is a GPU is checked where the pointers are taken, in _ptr)
+
+
+def _elem_type(Q, allowed=None):
+    import torch
+    allowed = allowed or (torch.bfloat16, torch.float16)
+    if Q.dtype not in allowed:
+        raise ValueError("Q must be " + " or ".join(str(a) for a in allowed))
+    return Q.dtype
+
+
+def _out(t, name, shape, dtype, device):
+    """An output tensor: allocated when the caller passed none, checked otherwise."""
+    import torch
+    if t is None:
+        return torch.empty(tuple(shape), dtype=dtype, device=device)
+    _need(t, name, dtype, shape, device)
+    return t
+
+
+def _workspace(ws, nbytes, device):
+    import torch
+    if ws is None:
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _need(ws, "workspace", None, None, device)
+    if ws.numel() * ws.element_size() < nbytes:
+        raise ValueError(f"workspace holds {ws.numel() * ws.element_size()} bytes, {nbytes} are needed")
+    return ws
+
+
+def _wsbytes(ws) -> int:
+    return ws.numel() * ws.element_size()
+
+
+class _Dims:
+    pass
+
+
+def _dense(Q, K, V, allowed=None, one_length=False):
+    """Q [B,Nq,Hq,d], K, V [B,Nk,Hkv,d] of one element type on one device -> their dimensions."""
+    et = _elem_type(Q, allowed)
+    _need(Q, "Q", et)
+    if Q.dim() != 4 or K.dim() != 4:
+        raise ValueError("Q must be [B, Nq, Hq, d] and K, V [B, Nk, Hkv, d]")
+    x = _Dims()
+    x.B, x.Nq, x.Hq, x.d = Q.shape
+    x.Nk, x.Hkv = K.shape[1], K.shape[2]
+    x.et, x.dev = et, Q.device
+    if one_length and x.Nk != x.Nq:
+        raise ValueError("K, V must be [B, N, Hkv, d] with the N of Q (two lengths: the fa_cross_* entry points)")
+    _need(K, "K", et, (x.B, x.Nk, x.Hkv, x.d), x.dev)
+    _need(V, "V", et, (x.B, x.Nk, x.Hkv, x.d), x.dev)
+    x.q_shape, x.k_shape, x.l_shape = (x.B, x.Nq, x.Hq, x.d), (x.B, x.Nk, x.Hkv, x.d), (x.B, x.Hq, x.Nq)
+    return x
+
+
+def _packed(Q, K, V, cu_q, cu_k=None):
+    """Q [Tq,Hq,d], K, V [Tk,Hkv,d] bf16 and the int32 offset arrays (one for one length) -> dimensions."""
+    import torch
+    _need(Q, "Q", torch.bfloat16)
+    if Q.dim() != 3 or K.dim() != 3:
+        raise ValueError("Q must be [T, Hq, d] and K, V [T, Hkv, d]")
+    x = _Dims()
+    x.Tq, x.Hq, x.d = Q.shape
+    x.Tk, x.Hkv = K.shape[0], K.shape[1]
+    x.et, x.dev = torch.bfloat16, Q.device
+    if cu_k is None and x.Tk != x.Tq:
+        raise ValueError("K, V must hold as many tokens as Q (two lengths: the fa_varlen_cross_* entry points)")
+    _need(K, "K", x.et, (x.Tk, x.Hkv, x.d), x.dev)
+    _need(V, "V", x.et, (x.Tk, x.Hkv, x.d), x.dev)
+    for t, nm in ((cu_q, "cu_seqlens"), (cu_k, "cu_seqlens_k")):
+        if t is not None:
+            _need(t, nm, torch.int32, None, x.dev)
+            if t.dim() != 1 or t.numel() < 2:
+                raise ValueError(f"{nm} must be a vector of nseq + 1 offsets")
+    x.nseq = cu_q.numel() - 1
+    if cu_k is not None and cu_k.numel() != cu_q.numel():
+        raise ValueError("the two offset arrays must have nseq + 1 entries each")
+    x.q_shape, x.k_shape, x.l_shape = (x.Tq, x.Hq, x.d), (x.Tk, x.Hkv, x.d), (x.Hq, x.Tq)
+    return x
+
+
+def _fwd_outputs(x, O, LSE):
+    import torch
+    return _out(O, "O", x.q_shape, x.et, x.dev), _out(LSE, "LSE", x.l_shape, torch.float32, x.dev)
+
+
+def _bwd_tensors(x, O, dO, LSE, dQ, dK, dV):
+    import torch
+    _need(O, "O", x.et, x.q_shape, x.dev)
+    _need(dO, "dO", x.et, x.q_shape, x.dev)
+    _need(LSE, "LSE", torch.float32, x.l_shape, x.dev)
+    return (_out(dQ, "dQ", x.q_shape, x.et, x.dev), _out(dK, "dK", x.k_shape, x.et, x.dev),
+            _out(dV, "dV", x.k_shape, x.et, x.dev))
 
 
 def fa_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None) -> Tuple["torch.Tensor", "torch.Tensor"]:
     """Dense forward. Q [B,N,Hq,d], K,V [B,N,Hkv,d] bf16 -> O [B,N,Hq,d] bf16, LSE [B,Hq,N] fp32."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    B, N, Hq, d = Q.shape
-    Hkv = K.shape[2]
-    if K.shape != (B, N, Hkv, d) or V.shape != K.shape:
-        raise ValueError("K, V must be [B, N, Hkv, d]")
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((B, Hq, N), dtype=torch.float32, device=Q.device)
-    _check(fa_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, N, d, scale, causal, _stream()))
+    x = _dense(Q, K, V, (torch.bfloat16,), one_length=True)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.d, scale, causal, _stream()))
     return O, LSE
 
 
 def fa_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
     """Dense backward. Returns dQ [B,N,Hq,d], dK, dV [B,N,Hkv,d] (bf16)."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
-    _need(LSE, "LSE", torch.float32)
-    B, N, Hq, d = Q.shape
-    Hkv = K.shape[2]
-    nbytes = fa_bwd_workspace_bytes(B, Hq, Hkv, N, d)
-    if workspace is None:
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
+    x = _dense(Q, K, V, (torch.bfloat16,), one_length=True)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.d), x.dev)
     _check(fa_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                      _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, N, d, scale, causal,
-                      _stream()))
+                      _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.d, scale, causal, _stream()))
     return dQ, dK, dV
 
 
@@ -288,126 +376,77 @@ def fa_bwd_noalloc(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ, dK, dV) 
     """Dense backward into caller-supplied dQ, dK, dV without a workspace: nothing is allocated,
     here or in the library (D lives in a static device array; at most FA_NOALLOC_MAX_ROWS
     (query row, head) pairs). Calls on one GPU must not overlap."""
-    B, N, Hq, d = Q.shape
-    Hkv = K.shape[2]
+    import torch
+    x = _dense(Q, K, V, (torch.bfloat16,), one_length=True)
+    if dQ is None or dK is None or dV is None:
+        raise ValueError("fa_bwd_noalloc allocates nothing: pass dQ, dK and dV")
+    _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     _check(fa_bwd_noalloc_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                              B, Hq, Hkv, N, d, scale, causal, _stream()))
+                              x.B, x.Hq, x.Hkv, x.Nq, x.d, scale, causal, _stream()))
 
 
 def fa_bwd_stages(Q, K, V, O, dO, LSE, scale: float, causal: bool, stages: int, dQ, dK, dV, workspace) -> None:
     """Profiling aid: run the selected stages (1 D pre-pass | 2 dK/dV | 4 dQ) of the dense backward."""
-    B, N, Hq, d = Q.shape
-    Hkv = K.shape[2]
+    import torch
+    x = _dense(Q, K, V, (torch.bfloat16,), one_length=True)
+    _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.d), x.dev)
     _check(fa_bwd_stages_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                             _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, N, d, scale,
-                             causal, stages, _stream()))
+                             _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.d, scale, causal, stages, _stream()))
 
 
 def fa_varlen_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, causal: bool, O=None, LSE=None):
     """Packed ragged forward. Q [T,Hq,d], K,V [T,Hkv,d] bf16, cu_seqlens int32 on the GPU.
     Returns O [T,Hq,d] bf16 and LSE [Hq,T] fp32."""
-    import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    _need(cu_seqlens, "cu_seqlens", torch.int32)
-    T, Hq, d = Q.shape
-    Hkv = K.shape[1]
-    nseq = cu_seqlens.numel() - 1
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((Hq, T), dtype=torch.float32, device=Q.device)
-    _check(fa_varlen_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), nseq, T, max_seqlen,
-                             Hq, Hkv, d, scale, causal, _stream()))
+    x = _packed(Q, K, V, cu_seqlens)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_varlen_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen,
+                             x.Hq, x.Hkv, x.d, scale, causal, _stream()))
     return O, LSE
 
 
 def fa_varlen_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, causal: bool,
                   dQ=None, dK=None, dV=None, workspace=None):
     """Packed ragged backward. Returns dQ [T,Hq,d], dK, dV [T,Hkv,d] (bf16)."""
-    import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
-    _need(LSE, "LSE", torch.float32)
-    _need(cu_seqlens, "cu_seqlens", torch.int32)
-    T, Hq, d = Q.shape
-    Hkv = K.shape[1]
-    nseq = cu_seqlens.numel() - 1
-    nbytes = fa_varlen_bwd_workspace_bytes(T, Hq, Hkv, d)
-    if workspace is None:
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
+    x = _packed(Q, K, V, cu_seqlens)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                             _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(cu_seqlens), nseq, T,
-                             max_seqlen, Hq, Hkv, d, scale, causal, _stream()))
+                             _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen, x.Hq, x.Hkv, x.d, scale,
+                             causal, _stream()))
     return dQ, dK, dV
-
-
-def _elem_type(Q, *others):
-    """bfloat16 or float16 tensors, all alike; returns True for float16."""
-    import torch
-    if Q.dtype not in (torch.bfloat16, torch.float16):
-        raise ValueError("Q must be bfloat16 or float16")
-    for t in others:
-        if t.dtype != Q.dtype:
-            raise ValueError("all 16-bit tensors must have the element type of Q")
-    return Q.dtype == torch.float16
 
 
 def fa_cross_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None):
     """Two lengths. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 (fa_cross_fwd) or fp16 (fa_cross_fwd_f16)
     -> O [B,Nq,Hq,d] of the same type, LSE [B,Hq,Nq] fp32."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm)
-    f16 = _elem_type(Q, K, V)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
-    _check(fa_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                            _stream(), f16))
+    x = _dense(Q, K, V)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal,
+                            _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
     """Two lengths, backward (bf16 or fp16 by the tensors' type). Returns dQ [B,Nq,Hq,d], dK, dV [B,Nk,Hkv,d]."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm)
-    f16 = _elem_type(Q, K, V, O, dO)
-    _need(LSE, "LSE", torch.float32)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
-    need = fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    x = _dense(Q, K, V)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                            _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
-                            scale, causal, _stream(), f16))
+                            _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, _stream(),
+                            x.et == torch.float16))
     return dQ, dK, dV
 
 
 def fa_dropout_fwd(Q, K, V, scale: float, causal: bool, p_drop: float, seed: int, O=None, LSE=None):
     """Forward with dropout on P. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
-    _check(fa_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                              p_drop, seed, _stream()))
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
+                              causal, p_drop, seed, _stream()))
     return O, LSE
 
 
@@ -415,61 +454,34 @@ def fa_dropout_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, p_drop: floa
                    dV=None, workspace=None):
     """Backward with the dropout mask of fa_dropout_fwd for the same p_drop and seed."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
-    _need(LSE, "LSE", torch.float32)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
-    if workspace is None:
-        workspace = torch.empty(fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d), dtype=torch.uint8,
-                                device=Q.device)
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                              _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d,
-                              scale, causal, p_drop, seed, _stream()))
+                              _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, p_drop, seed,
+                              _stream()))
     return dQ, dK, dV
 
 
 def fa_varlen_dropout_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, causal: bool, p_drop: float, seed: int,
                           O=None, LSE=None):
     """Packed ragged forward with dropout on P. Q [T,Hq,d], K,V [T,Hkv,d] bf16; cu_seqlens int32 on the GPU."""
-    import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    _need(cu_seqlens, "cu_seqlens", torch.int32)
-    T, Hq, d = Q.shape
-    Hkv = K.shape[1]
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((Hq, T), dtype=torch.float32, device=Q.device)
-    _check(fa_varlen_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens),
-                                     cu_seqlens.numel() - 1, T, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed,
-                                     _stream()))
+    x = _packed(Q, K, V, cu_seqlens)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_varlen_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), x.nseq, x.Tq,
+                                     max_seqlen, x.Hq, x.Hkv, x.d, scale, causal, p_drop, seed, _stream()))
     return O, LSE
 
 
 def fa_varlen_dropout_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, causal: bool, p_drop: float,
                           seed: int, dQ=None, dK=None, dV=None, workspace=None):
     """Packed ragged backward with the dropout mask of fa_varlen_dropout_fwd for the same p_drop and seed."""
-    import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
-    _need(LSE, "LSE", torch.float32)
-    _need(cu_seqlens, "cu_seqlens", torch.int32)
-    T, Hq, d = Q.shape
-    Hkv = K.shape[1]
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
-    if workspace is None:
-        workspace = torch.empty(fa_varlen_bwd_workspace_bytes(T, Hq, Hkv, d), dtype=torch.uint8, device=Q.device)
+    x = _packed(Q, K, V, cu_seqlens)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
-                                     _ptr(dV), _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                     _ptr(cu_seqlens), cu_seqlens.numel() - 1, T, max_seqlen, Hq, Hkv, d, scale,
-                                     causal, p_drop, seed, _stream()))
+                                     _ptr(dV), _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen, x.Hq,
+                                     x.Hkv, x.d, scale, causal, p_drop, seed, _stream()))
     return dQ, dK, dV
 
 
@@ -481,12 +493,11 @@ def mask_buffer(Bm: int, Hm: int, Nq: int, Nk: int, device="cuda"):
     return torch.zeros((Bm, Hm, Nq, rs), dtype=torch.bfloat16, device=device)[..., :Nk]
 
 
-def _mask_strides(M, B, Hq, Nq, Nk):
+def _mask_strides(M, x):
     import torch
-    _need_dtype = torch.bfloat16
-    if not M.is_cuda or M.dtype != _need_dtype:
-        raise ValueError("M must be a CUDA bfloat16 tensor")
-    if M.dim() != 4 or M.shape[0] not in (1, B) or M.shape[1] not in (1, Hq) or tuple(M.shape[2:]) != (Nq, Nk):
+    if M.dtype != torch.bfloat16 or M.device != x.dev:
+        raise ValueError("M must be a bfloat16 tensor on the device of Q")
+    if M.dim() != 4 or M.shape[0] not in (1, x.B) or M.shape[1] not in (1, x.Hq) or tuple(M.shape[2:]) != (x.Nq, x.Nk):
         raise ValueError("M must be [1 or B, 1 or Hq, Nq, Nk]")
     if M.stride(3) != 1:
         raise ValueError("the key dimension of M must be contiguous")
@@ -497,79 +508,47 @@ def fa_mask_fwd(Q, K, V, M, scale: float, causal: bool, O=None, LSE=None):
     """Forward with the mask M added to the scaled scores. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16; M as
     made by mask_buffer (entries finite or -inf)."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
-    bs, hs, rs = _mask_strides(M, B, Hq, Nq, Nk)
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
-    _check(fa_mask_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                           bs, hs, rs, _stream()))
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    bs, hs, rs = _mask_strides(M, x)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_mask_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d,
+                           scale, causal, bs, hs, rs, _stream()))
     return O, LSE
 
 
 def fa_mask_bwd(Q, K, V, M, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
     """Backward with the mask of fa_mask_fwd; M receives no gradient."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
-    _need(LSE, "LSE", torch.float32)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
-    bs, hs, rs = _mask_strides(M, B, Hq, Nq, Nk)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
-    if workspace is None:
-        workspace = torch.empty(fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d), dtype=torch.uint8,
-                                device=Q.device)
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    bs, hs, rs = _mask_strides(M, x)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_mask_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
-                           _ptr(dV), _ptr(workspace), workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk,
-                           d, scale, causal, bs, hs, rs, _stream()))
+                           _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, bs, hs, rs,
+                           _stream()))
     return dQ, dK, dV
 
 
 def fa_varlen_cross_fwd(Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int, scale: float,
                         causal: bool, O=None, LSE=None):
     """Packed ragged forward with two lengths. Q [Tq,Hq,d], K,V [Tk,Hkv,d] bf16; offsets int32 on the GPU."""
-    import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    _need(cu_seqlens_q, "cu_seqlens_q", torch.int32)
-    _need(cu_seqlens_k, "cu_seqlens_k", torch.int32)
-    Tq, Hq, d = Q.shape
-    Tk, Hkv = K.shape[0], K.shape[1]
-    nseq = cu_seqlens_q.numel() - 1
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((Hq, Tq), dtype=torch.float32, device=Q.device)
+    x = _packed(Q, K, V, cu_seqlens_q, cu_seqlens_k)
+    O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_varlen_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens_q), _ptr(cu_seqlens_k),
-                                   nseq, Tq, Tk, max_seqlen_q, max_seqlen_k, Hq, Hkv, d, scale, causal, _stream()))
+                                   x.nseq, x.Tq, x.Tk, max_seqlen_q, max_seqlen_k, x.Hq, x.Hkv, x.d, scale, causal,
+                                   _stream()))
     return O, LSE
 
 
 def fa_varlen_cross_bwd(Q, K, V, O, dO, LSE, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int,
                         scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
     """Packed ragged backward with two lengths. Returns dQ [Tq,Hq,d], dK, dV [Tk,Hkv,d] bf16."""
-    import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
-        _need(t, nm, torch.bfloat16)
-    Tq, Hq, d = Q.shape
-    Tk, Hkv = K.shape[0], K.shape[1]
-    nseq = cu_seqlens_q.numel() - 1
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
-    if workspace is None:
-        workspace = torch.empty(fa_varlen_bwd_workspace_bytes(Tq, Hq, Hkv, d), dtype=torch.uint8, device=Q.device)
+    x = _packed(Q, K, V, cu_seqlens_q, cu_seqlens_k)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
-                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(cu_seqlens_q),
-                                   _ptr(cu_seqlens_k), nseq, Tq, Tk, max_seqlen_q, max_seqlen_k, Hq, Hkv, d, scale,
-                                   causal, _stream()))
+                                   _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens_q), _ptr(cu_seqlens_k), x.nseq, x.Tq, x.Tk,
+                                   max_seqlen_q, max_seqlen_k, x.Hq, x.Hkv, x.d, scale, causal, _stream()))
     return dQ, dK, dV
 
 
@@ -587,22 +566,13 @@ def splitkv_default_splits(B, Hq, Hkv, Nq, Nk) -> int:
 def fa_splitkv_fwd(Q, K, V, scale: float, causal: bool, num_splits: int = 0, O=None, LSE=None, workspace=None):
     """Few query rows against many keys; layouts and results as fa_cross_fwd. num_splits = 0 picks a default."""
     import torch
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
-        _need(t, nm, torch.bfloat16)
-    B, Nq, Hq, d = Q.shape
-    Nk, Hkv = K.shape[1], K.shape[2]
+    x = _dense(Q, K, V, (torch.bfloat16,))
     if num_splits <= 0:
-        num_splits = splitkv_default_splits(B, Hq, Hkv, Nq, Nk)
-    if O is None:
-        O = torch.empty_like(Q)
-    if LSE is None:
-        LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device=Q.device)
-    if workspace is None:
-        workspace = torch.empty(fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits), dtype=torch.uint8,
-                                device=Q.device)
-    _check(fa_splitkv_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(workspace),
-                              workspace.numel() * workspace.element_size(), B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                              num_splits, _stream()))
+        num_splits = splitkv_default_splits(x.B, x.Hq, x.Hkv, x.Nq, x.Nk)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    ws = _workspace(workspace, fa_splitkv_fwd_workspace_bytes(x.B, x.Hq, x.Nq, x.d, num_splits), x.dev)
+    _check(fa_splitkv_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv,
+                              x.Nq, x.Nk, x.d, scale, causal, num_splits, _stream()))
     return O, LSE
 
 

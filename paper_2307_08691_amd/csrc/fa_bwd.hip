@@ -91,25 +91,9 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(BwdArgs a) {
 // operand is (lane constant) ^ (compile-time constant) + (immediate): the lane
 // constants are a handful of registers computed once, instead of one register per
 // distinct operand.
-#ifndef FA_DKDV_AHEAD
-#define FA_DKDV_AHEAD 4
-#endif
-// K_j (and, at d = 64, V_j) operands of a wavefront's 32 keys held in registers instead of
-// being read from LDS for every tile
-#ifndef FA_DKDV_KREG
-#define FA_DKDV_KREG 1
-#endif
-#ifndef FA_DKDV_VREG
-#define FA_DKDV_VREG 1
-#endif
-// 256 keys per workgroup (see WIDE below)
-#ifndef FA_DKDV_WIDE
-#define FA_DKDV_WIDE 1
-#endif
+constexpr int kDkdvAhead = 4;  // how many MFMAs ahead the LDS operands are requested (3 where K_j takes the registers)
 // keys per workgroup of the dK/dV kernel instantiation (the launch needs it for the grid)
-constexpr bool dkdv_wide(int D, bool dropout, bool mask) {
-  return FA_DKDV_WIDE && FA_DKDV_KREG && !dropout && !mask && (D == 128 || FA_DKDV_VREG);
-}
+constexpr bool dkdv_wide(int D, bool dropout, bool mask) { return !dropout && !mask; }
 constexpr int dkdv_block_keys(int D, bool dropout, bool mask) { return dkdv_wide(D, dropout, mask) ? 256 : 128; }
 //
 // PAD: head dimension p.d below the tile width D, rows padded with zeros on chip (see the
@@ -123,8 +107,8 @@ constexpr int dkdv_block_keys(int D, bool dropout, bool mask) { return dkdv_wide
 template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
-  constexpr bool KREG = FA_DKDV_KREG && !MASK && !DROPOUT;
-  constexpr bool VREG = FA_DKDV_VREG && D == 64 && !MASK && !DROPOUT;
+  constexpr bool KREG = !MASK && !DROPOUT;  // K_j operands of the wavefront's 32 keys in registers
+  constexpr bool VREG = D == 64 && !MASK && !DROPOUT;  // at d = 64 V_j's as well
   constexpr bool WIDE = dkdv_wide(D, DROPOUT, MASK);
   constexpr int BC = dkdv_block_keys(D, DROPOUT, MASK);  // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
@@ -332,7 +316,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   }
   constexpr int NM = QTW * 2 * KS;   // S and dP: 16 MFMAs
   constexpr int NM2 = QTW * 4 * DT;  // dV and dK: 16 MFMAs
-  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : (KREG && D == 128 && FA_DKDV_AHEAD > 3 ? 3 : FA_DKDV_AHEAD);
+  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : (KREG && D == 128 ? 3 : kDkdvAhead);
   // MASK: this lane's entries of M for the wavefront's next tile (raw bfloat16 bits), row by row
   uint32_t mraw[MASK ? QTW * 16 : 1];
   auto issue_mask_loads = [&](const Cursor& c) {
@@ -687,7 +671,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const SeqInfo si = seq_info(p, s);
   const int n = si.n, nk = si.nk, off = nk - n;  // query rows, key rows, position of query 0
   const int i0 = rowblk * BR;
-  if (i0 >= n) return;
+  if (i0 >= n || nk == 0) return;  // (a sequence without keys: dQ = 0 comes from keyless_rows_kernel)
   const int g = h / p.G;
   const int dh = PAD ? p.d : D;  // row length in memory
   const long kstride = (long)p.Hkv * dh;
@@ -990,6 +974,8 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
 }
 
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st) {
+  if (stages & 4)
+    if (hipError_t e = launch_keyless_rows(a.p, a.dQ, nullptr, st)) return e;
   if (d == 256) {  // the D pre-pass is the generic one, the two kernels live in fa_d256.hip
     if (stages & 1) {
       const long nrows = (long)a.p.total_tokens * a.p.Hq;

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const SeqInfo si = seq_info(p, s);
   const int n = si.n, nk = si.nk, off = nk - n;
   const int i0 = rowblk * BR;
-  if (i0 >= n) return;
+  if (i0 >= n || nk == 0) return;  // (a sequence without keys: see keyless_rows_kernel)
   const int g = h / p.G;
   const long kstride = (long)p.Hkv * D;
   const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const SeqInfo si = seq_info(p, s);
   const int n = si.n, nk = si.nk, off = nk - n;
   const int i0 = rowblk * BR;
-  if (i0 >= n) return;
+  if (i0 >= n || nk == 0) return;  // (a sequence without keys: see keyless_rows_kernel)
   const int g = h / p.G;
   const long kstride = (long)p.Hkv * D;
   const __bf16* Kb = a.K + (si.tok0k * p.Hkv + g) * D;

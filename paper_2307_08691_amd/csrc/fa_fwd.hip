@@ -36,24 +36,21 @@
 #include "fa_kernels.h"
 #include "fa_lds.h"
 
-// How many MFMAs ahead the LDS operands of the two products are requested.
-#ifndef FA_FWD_AHEAD_QK
-#define FA_FWD_AHEAD_QK 4
-#endif
-#ifndef FA_FWD_AHEAD_PV
-#define FA_FWD_AHEAD_PV 3
-#endif
-#ifndef FA_FWD_MATRIX_PRIO
-#define FA_FWD_MATRIX_PRIO 2
-#endif
-// The running maximum is only advanced (and O, l rescaled) when some row's maximum grew by
-// more than 2^FA_FWD_LAZY_LOG2; until then exponentials are taken against the older
-// reference and may reach 2^FA_FWD_LAZY_LOG2. 0 = advance on every change.
-#ifndef FA_FWD_LAZY_LOG2
-#define FA_FWD_LAZY_LOG2 8
-#endif
-
 namespace fa {
+
+// How many MFMAs ahead the LDS operands of the two products are requested.
+constexpr int kFwdAheadQK = 4, kFwdAheadPV = 3;
+// Wave priority of a matrix phase: the MFMA stream must not wait behind the other group's
+// vector work (measured: 3-5% slower at d = 128 without it).
+#define FA_FWD_MATRIX_PRIO 2
+// The reference of the running softmax is only advanced (and O, l rescaled) when a lane's share
+// of a block's row sum exceeds 2^kFwdLazyLog2 (instantiations without the fast path: when some
+// row's maximum outgrew the reference by that factor); until then exponentials are taken against
+// the older reference and may reach 2^kFwdLazyLog2.
+constexpr int kFwdLazyLog2 = 8;
+// d = 128: workgroups that take several items in a row and overlap an item's start-up with the
+// end of the one before (fwd_chain_kernel), for sequences of at most kFwdChainMaxN keys
+constexpr int kFwdChainMaxN = 1024;
 
 // At d = 64 the kernel needs 64 KiB of LDS, so two workgroups fit on a compute unit if their
 // 16 wavefronts do, i.e. with at most 128 registers each. Two resident workgroups overlap one's
@@ -61,21 +58,7 @@ namespace fa {
 // which a single workgroup per compute unit cannot: 10% faster at N = 8192, 27% at N = 512.
 // The price is the shortest operand prefetch (one MFMA ahead). Not for dropout (more
 // registers) or the elementwise mask (more LDS).
-#ifndef FA_FWD_TWO_PER_CU
-#define FA_FWD_TWO_PER_CU 1
-#endif
-// d = 128: workgroups that take several items in a row and overlap an item's start-up with
-// the end of the one before (fwd_chain_kernel)
-#ifndef FA_FWD_CHAIN
-#define FA_FWD_CHAIN 1
-#endif
-#ifndef FA_FWD_CHAIN_MAXN
-#define FA_FWD_CHAIN_MAXN 1024
-#endif
-#ifndef FA_FWD_CHAIN_LONG
-#define FA_FWD_CHAIN_LONG 8
-#endif
-constexpr bool fwd_two_per_cu(int D, bool dropout, bool mask) { return FA_FWD_TWO_PER_CU && D == 64 && !dropout && !mask; }
+constexpr bool fwd_two_per_cu(int D, bool dropout, bool mask) { return D == 64 && !dropout && !mask; }
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
@@ -102,7 +85,7 @@ __global__ __launch_bounds__(512)
     __attribute__((amdgpu_waves_per_eu(fwd_two_per_cu(D, DROPOUT, MASK) ? 4 : 2, fwd_two_per_cu(D, DROPOUT, MASK) ? 4 : 2))) void
     fwd_kernel(FwdArgs a) {
   constexpr bool TWO = fwd_two_per_cu(D, DROPOUT, MASK);
-  constexpr int AHEAD_QK = TWO ? 1 : FA_FWD_AHEAD_QK, AHEAD_PV = TWO ? 1 : FA_FWD_AHEAD_PV;
+  constexpr int AHEAD_QK = TWO ? 1 : kFwdAheadQK, AHEAD_PV = TWO ? 1 : kFwdAheadPV;
   static_assert(!MASK || (!SPLIT && !F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16;  // contraction steps of the first product
@@ -132,7 +115,7 @@ __global__ __launch_bounds__(512)
   const int off = nk - n;          // position of query 0 among the keys (causal alignment)
   const int nrows = SPLIT ? n * p.G : n;  // rows of the (packed) row dimension
   const int i0 = rowblk * BR;
-  if (i0 >= nrows) return;
+  if (i0 >= nrows || nk == 0) return;  // (a sequence without keys: see keyless_rows_kernel)
   const int g = SPLIT ? bc.head : bc.head / p.G;
   const int dh = PAD ? p.d : D;  // row length in memory
   const long kstride = (long)p.Hkv * dh;
@@ -344,7 +327,7 @@ __global__ __launch_bounds__(512)
     // the same reference whatever it is, and rescaling O (line 10) by exp(m_old - m_new) only
     // matters for the range of the numbers. So the row maximum is NOT computed for every block.
     // The block's exponentials are taken against the reference as it stands; only if some lane's
-    // share of a row sum then exceeds 2^FA_FWD_LAZY_LOG2 (which also catches an overflow to inf)
+    // share of a row sum then exceeds 2^kFwdLazyLog2 (which also catches an overflow to inf)
     // is the maximum of the block found, the reference advanced to it, O and l rescaled, and the
     // exponentials taken again. After the first few blocks that is rare: the fast path saves the
     // 16 three-way maxima, the exchange with the partner lane and the comparison per block.
@@ -354,7 +337,7 @@ __global__ __launch_bounds__(512)
     bool advance = !FAST || j == jb;
     if (!advance) {
       exponentials(m * cs);
-      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << FA_FWD_LAZY_LOG2)) != 0;
+      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << kFwdLazyLog2)) != 0;
     }
     if (advance) {
       float mx = max3(S[0][0], S[0][1], S[1][0]);
@@ -369,8 +352,8 @@ __global__ __launch_bounds__(512)
       // column 0 is visible to every row and blocks are walked in ascending order, so m_new is
       // finite from the first block on and exp2(-inf) = 0 covers the start (not so with split
       // keys or a mask: GUARD). Without the fast path the reference is advanced only when some
-      // row's maximum outgrew it by a factor 2^FA_FWD_LAZY_LOG2.
-      if (FAST || __builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)FA_FWD_LAZY_LOG2) != 0) {
+      // row's maximum outgrew it by a factor 2^kFwdLazyLog2.
+      if (FAST || __builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)kFwdLazyLog2) != 0) {
         // (split, mask: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
         const float alpha = GUARD && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * cs);
         l *= alpha;
@@ -476,7 +459,7 @@ __global__ __launch_bounds__(512)
 // workgroup gets the same amount of work whenever the chain length is even.
 template <int D, bool CAUSAL, bool F16>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_chain_kernel(FwdArgs a, int chain) {
-  constexpr int AHEAD_QK = FA_FWD_AHEAD_QK, AHEAD_PV = FA_FWD_AHEAD_PV;
+  constexpr int AHEAD_QK = kFwdAheadQK, AHEAD_PV = kFwdAheadPV;
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32, ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
@@ -669,7 +652,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     bool advance = j == 0;
     if (!advance) {
       exponentials(m * c2);
-      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << FA_FWD_LAZY_LOG2)) != 0;
+      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << kFwdLazyLog2)) != 0;
     }
     if (advance) {
       float mx = max3(S[0][0], S[0][1], S[1][0]);
@@ -804,6 +787,27 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
   if (c == 0) a.LSE[li] = mx + __logf(z);
 }
 
+// A sequence without any key (possible in ragged batches with two lengths) has no softmax. Its
+// query rows get what rows emptied by an elementwise mask get: P = 0, hence O = 0 (and dQ = 0)
+// and L = -inf. The attention kernels skip such sequences; this one, launched beside them for
+// ragged batches with two lengths, fills their rows: one workgroup per sequence, the rows of a
+// sequence being one contiguous piece of the token-major tensor. `lse` may be nullptr (dQ).
+__global__ __launch_bounds__(256) void keyless_rows_kernel(Problem p, __bf16* out, float* lse) {
+  const SeqInfo si = seq_info(p, blockIdx.x);
+  if (si.nk != 0 || si.n == 0) return;
+  u32x4* o = (u32x4*)(out + si.tok0 * p.Hq * p.d);
+  const long chunks = (long)si.n * p.Hq * p.d / 8;
+  for (long i = threadIdx.x; i < chunks; i += 256) o[i] = (u32x4){0, 0, 0, 0};
+  if (lse)
+    for (long i = threadIdx.x; i < (long)si.n * p.Hq; i += 256)
+      lse[(i / si.n) * p.lse_head_stride + si.tok0 + i % si.n] = -INFINITY;
+}
+hipError_t launch_keyless_rows(const Problem& p, __bf16* out, float* lse, hipStream_t st) {
+  if (!p.cu_seqlens_k) return hipSuccess;  // one length per sequence: a sequence with queries has keys
+  hipLaunchKernelGGL(keyless_rows_kernel, dim3(p.nseq), dim3(256), 0, st, p, out, lse);
+  return hipGetLastError();
+}
+
 template <int D, bool F16>
 static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
   dim3 block(512);
@@ -838,17 +842,16 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
       return hipGetLastError();
     }
   }
-  if constexpr (D == 128 && FA_FWD_CHAIN) {
+  if constexpr (D == 128) {
     // chained items (fwd_chain_kernel): dense batches of short sequences (at most 16 key blocks:
     // +15% at N = 512; from N = 2048 on the start-up no longer matters and the fixed assignment
     // of items loses against the hardware's dynamic one, -5% at N = 8192 under the mask) whose
     // items split evenly over the XCDs and into chains of even length, with at least one
     // workgroup left per compute unit
     const int pairs = a.p.Hq * a.p.nseq, nblk = (a.p.N + 255) / 256;
-    if (!a.p.cu_seqlens && pairs % kXcds == 0 && a.p.N >= 256 && a.p.Nk >= a.p.N && a.p.Nk <= FA_FWD_CHAIN_MAXN) {
+    if (!a.p.cu_seqlens && pairs % kXcds == 0 && a.p.N >= 256 && a.p.Nk >= a.p.N && a.p.Nk <= kFwdChainMaxN) {
       const int items = pairs / kXcds * nblk;  // per XCD
       int chain = items % 8 == 0 ? 8 : items % 4 == 0 ? 4 : items % 2 == 0 ? 2 : 1;
-      if (a.p.Nk > 1024 && chain > FA_FWD_CHAIN_LONG) chain = FA_FWD_CHAIN_LONG;
       while (chain > 1 && items / chain < 32) chain /= 2;
       if (chain > 1) {
         dim3 cgrid((unsigned)(kXcds * (items / chain)));
@@ -864,6 +867,7 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st) {
+  if (hipError_t e = launch_keyless_rows(a.p, a.O, a.LSE, st)) return e;
   if (d == 256) return launch_fwd256(a, causal, st);
   // tile width: the head dimension padded up to 64 or 128
   if (a.p.f16) return d <= 64 ? launch_fwd_d<64, true>(a, causal, st) : launch_fwd_d<128, true>(a, causal, st);

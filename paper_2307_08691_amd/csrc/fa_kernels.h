@@ -35,6 +35,8 @@ struct BwdArgs {
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st);
 // stages: bit 0 D pre-pass, bit 1 dK/dV kernel, bit 2 dQ kernel
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st);
+// ragged batches with two lengths: O (or dQ) = 0 and L = -inf for the query rows of sequences without keys
+hipError_t launch_keyless_rows(const Problem& p, __bf16* out, float* lse, hipStream_t st);
 // head dimension 256 (fa_d256.hip): plain problems only (no split, dropout, mask)
 hipError_t launch_fwd256(const FwdArgs& a, int causal, hipStream_t st);
 hipError_t launch_bwd256(const BwdArgs& a, int causal, int stages, hipStream_t st);

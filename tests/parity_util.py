@@ -258,7 +258,7 @@ def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=N
     for s in range(nseq):
         if packed:
             a, e, ak, ek = int(cu_q[s]), int(cu_q[s + 1]), int(cu_k[s]), int(cu_k[s + 1])
-            if e == a:
+            if e == a or ek == ak:  # (a sequence without keys has no softmax to materialise: zeros)
                 continue
             qs, ks, vs, gs = Q[a:e], K[ak:ek], V[ak:ek], dO[a:e]
         else:

@@ -229,3 +229,43 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         binding.load()
+
+
+# ---- the tensor-level wrappers check every tensor before a pointer reaches the library
+
+def _host(*shape, dtype=None):
+    import torch
+    return torch.zeros(*shape, dtype=dtype or torch.bfloat16)
+
+
+def test_wrappers_reject_wrong_shapes_types_and_host_tensors_before_any_call():
+    import torch
+    B, N, Hq, Hkv, d = 2, 16, 4, 2, 64
+    q, k = _host(B, N, Hq, d), _host(B, N, Hkv, d)
+    lse = _host(B, Hq, N, dtype=torch.float32)
+    cases = [
+        (lambda: binding.fa_fwd(q, _host(B, N + 1, Hkv, d), k, 0.1, False), "two lengths"),
+        (lambda: binding.fa_fwd(q, k, _host(B, N, Hkv, d + 8), 0.1, False), "V must have shape"),
+        (lambda: binding.fa_fwd(q.float(), k, k, 0.1, False), "Q must be"),
+        (lambda: binding.fa_fwd(q, k, k, 0.1, False, O=_host(B, N, Hq, d + 8)), "O must have shape"),
+        (lambda: binding.fa_fwd(q, k, k, 0.1, False, LSE=_host(B, N, Hq, dtype=torch.float32)), "LSE must have shape"),
+        (lambda: binding.fa_bwd(q, k, k, _host(B, N, Hkv, d), q, lse, 0.1, False), "O must have shape"),
+        (lambda: binding.fa_bwd(q, k, k, q, q, lse.double(), 0.1, False), "LSE must be"),
+        (lambda: binding.fa_bwd(q, k, k, q, q, lse, 0.1, False, dK=_host(B, N, Hq, d)), "dK must have shape"),
+        (lambda: binding.fa_cross_bwd(q, k, k, q, q.half(), lse, 0.1, False), "dO must be"),
+        (lambda: binding.fa_bwd_noalloc(q, k, k, q, q, lse, 0.1, False, None, None, None), "allocates nothing"),
+        (lambda: binding.fa_varlen_fwd(_host(32, Hq, d), _host(31, Hkv, d), _host(31, Hkv, d),
+                                       torch.zeros(3, dtype=torch.int32), 16, 0.1, False), "as many tokens"),
+        (lambda: binding.fa_varlen_fwd(_host(32, Hq, d), _host(32, Hkv, d), _host(32, Hkv, d),
+                                       torch.zeros(3, dtype=torch.int64), 16, 0.1, False), "cu_seqlens must be"),
+        (lambda: binding.fa_varlen_cross_fwd(_host(32, Hq, d), _host(40, Hkv, d), _host(40, Hkv, d),
+                                             torch.zeros(3, dtype=torch.int32), torch.zeros(4, dtype=torch.int32),
+                                             16, 20, 0.1, False), "nseq + 1 entries each"),
+        # everything right but the device: refused as well, before the library sees a pointer
+        (lambda: binding.fa_fwd(q, k, k, 0.1, False), "must live on the GPU"),
+        (lambda: binding.fa_bwd(q, k, k, q, q, lse, 0.1, False), "must live on the GPU"),
+    ]
+    for call, needle in cases:
+        with pytest.raises(ValueError) as e:
+            call()
+        assert needle in str(e.value), (needle, str(e.value))

@@ -180,6 +180,31 @@ def test_ragged_batches_with_two_lengths(d, Hq, Hkv, causal):
     assert not bool(dK[cu_k[2]:cu_k[3]].any()) and not bool(dV[cu_k[2]:cu_k[3]].any())
 
 
+@pytest.mark.parametrize("d", [64, 128, 256, 96])
+def test_a_sequence_with_queries_but_no_keys(d):
+    """Ragged batch with two lengths, no mask: the first and a middle sequence have no key at all.
+    Their rows get O = 0, L = -inf, dQ = 0 (nothing is read before the key/value base), the
+    other sequences are unaffected."""
+    lq, lk, Hq, Hkv = [300, 70, 5, 64], [0, 257, 0, 65], 4, 2
+    cu_q, cu_k, Qb, Kb, Vb, dOb = ragged_cross(lq, lk, Hq, Hkv, d, 4200 + d)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (Qb, Kb, Vb, dOb))
+    cq, ck = torch.from_numpy(cu_q).cuda(), torch.from_numpy(cu_k).cuda()
+    scale = d ** -0.5
+    O, L = binding.fa_varlen_cross_fwd(Q, K, V, cq, ck, max(lq), max(lk), scale, False)
+    dQ, dK, dV = binding.fa_varlen_cross_bwd(Q, K, V, O, dO, L, cq, ck, max(lq), max(lk), scale, False)
+    torch.cuda.synchronize()
+    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (Qb, Kb, Vb, dOb))
+    eO, eL = orc.varlen_forward(Qf, Kf, Vf, cu_q, scale, False, cu_seqlens_k=cu_k)
+    edQ, edK, edV = orc.varlen_backward(Qf, Kf, Vf, dOf, cu_q, scale, False, cu_seqlens_k=cu_k)
+    ref = pu.reference_batch(Q, K, V, dO, scale, False, cu_q=cu_q, cu_k=cu_k)
+    ref["LSE"][:, :300] = -np.inf   # (the reference skips sequences it cannot run)
+    ref["LSE"][:, 370:375] = -np.inf
+    pu.judge(f"ragged with keyless sequences, d{d}", {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
+             dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, d=d)
+    for a, e in ((0, 300), (370, 375)):
+        assert not bool(O[a:e].any()) and not bool(dQ[a:e].any()) and bool(torch.isneginf(L[:, a:e]).all())
+
+
 def test_ragged_two_lengths_with_equal_offsets_reproduce_the_one_length_entry_points():
     prob = inputs.make_varlen([100, 257, 31], Hq=4, Hkv=2, d=128, causal=True, seed=4100)
     Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))

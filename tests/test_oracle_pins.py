@@ -882,3 +882,31 @@ def test_ragged_dropout_with_equal_lengths_is_the_dense_batch():
     O2, _ = orc.varlen_forward_dropout(flat(Q), flat(K), flat(V), cu2, 0.6, False, 0.3, 77)
     np.testing.assert_array_equal(O2[:N], O1[:N])
     assert not np.array_equal(O2[N:2 * N], O1[N:2 * N])  # the later sequences moved on to other head indices
+
+
+def test_a_sequence_with_queries_but_no_keys_is_a_row_block_the_mask_emptied():
+    """Ragged batch with two lengths in which one sequence has no key at all: its rows get what the
+    masked definition gives rows whose every entry is -inf (O = 0, L = -inf, dQ = 0), and the
+    other sequences are what they are on their own."""
+    rng = np.random.default_rng(77)
+    lq, lk, Hq, Hkv, d = [2, 4, 1], [3, 0, 5], 2, 1, 4
+    cu_q = np.concatenate([[0], np.cumsum(lq)])
+    cu_k = np.concatenate([[0], np.cumsum(lk)])
+    Q, dO = rng.standard_normal((7, Hq, d)), rng.standard_normal((7, Hq, d))
+    K, V = rng.standard_normal((8, Hkv, d)), rng.standard_normal((8, Hkv, d))
+    O, L = orc.varlen_forward(Q, K, V, cu_q, 0.5, False, cu_seqlens_k=cu_k)
+    dQ, dK, dV = orc.varlen_backward(Q, K, V, dO, cu_q, 0.5, False, cu_seqlens_k=cu_k)
+    # the keyless sequence against one dummy key that the mask removes
+    for h in range(Hq):
+        q, do = Q[2:6, h], dO[2:6, h]
+        k1, v1 = rng.standard_normal((1, d)), rng.standard_normal((1, d))
+        om, lm, _ = orc.head_forward_masked(q, k1, v1, np.full((4, 1), -np.inf), 0.5, False)
+        dqm, _, _ = orc.head_backward_masked(q, k1, v1, np.full((4, 1), -np.inf), do, 0.5, False)
+        assert np.array_equal(O[2:6, h], om) and np.array_equal(L[h, 2:6], lm) and np.array_equal(dQ[2:6, h], dqm)
+        assert not O[2:6, h].any() and np.all(np.isneginf(L[h, 2:6])) and not dQ[2:6, h].any()
+    # the others: each on its own
+    for (a, e, ak, ek) in ((0, 2, 0, 3), (6, 7, 3, 8)):
+        o, l = orc.attention_forward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek], 0.5, False)
+        dq, dk, dv = orc.attention_backward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek], dO[None, a:e], 0.5, False)
+        assert np.array_equal(O[a:e], o[0]) and np.array_equal(L[:, a:e], l[0])
+        assert np.array_equal(dQ[a:e], dq[0]) and np.array_equal(dK[ak:ek], dk[0]) and np.array_equal(dV[ak:ek], dv[0])
