@@ -62,6 +62,19 @@ Readings taken where the text is silent or inconsistent:
     contributes nothing to any gradient. M is [Bm, Hm, Nq, Nk] with Bm in
     {1, B} and Hm in {1, Hq} (size 1 = shared).
 
+  * local (sliding-window) and block-sparse attention (section 5 names them as patterns the
+    method combines with; no definition is given). Reading: both only REMOVE entries of S
+    before the softmax, exactly as the causal rule of section 3.1.1 does, and everything else
+    is the standard definition on what is left.
+      - window (left, right): query r stands at position p = r + Nk - Nq among the keys (the
+        alignment of the causal rule) and sees the keys c with p - left <= c <= p + right;
+        a negative bound means "unbounded on that side". right = 0, left < 0 is the causal
+        rule; left = W - 1, right = 0 is a causal sliding window over the W newest keys.
+      - block-sparse: a boolean matrix over (row block, key block) pairs of `block` x `block`
+        entries, rows counted from query 0 and keys from key 0; an entry of S is kept iff
+        its block is set (and the causal rule, if asked for, keeps it).
+    A row left without entries has P = 0, O = 0, L = -inf, as with the elementwise mask.
+
 Layouts: dense Q,O,dO,dQ [B, Nq, Hq, d]; K,V,dK,dV [B, Nk, Hkv, d]; L [B, Hq, Nq]
 (Nq = Nk = N for self-attention).
 Packed: Q.. [T, Hq, d]; K.. [T, Hkv, d]; L [Hq, T].
@@ -465,3 +478,92 @@ def attention_backward_masked(Q, K, V, M, dO, scale, causal):
             dK[b, :, g, :] += dk
             dV[b, :, g, :] += dv
     return dQ, dK, dV
+
+
+# ---------------------------------------------------------------------------
+# Local (sliding-window) and block-sparse patterns (section 5; reading in the header)
+# ---------------------------------------------------------------------------
+
+def window_visible(nq, nk, left, right):
+    """[nq, nk] booleans: key c is visible to query r iff p - left <= c <= p + right with
+    p = r + nk - nq; a negative bound is no bound."""
+    p = np.arange(nq)[:, None] + (nk - nq)
+    c = np.arange(nk)[None, :]
+    vis = np.ones((nq, nk), dtype=bool)
+    if left >= 0:
+        vis &= c >= p - left
+    if right >= 0:
+        vis &= c <= p + right
+    return vis
+
+
+def block_visible(nq, nk, block_mask, block):
+    """[nq, nk] booleans from a [ceil(nq/block), ceil(nk/block)] block mask."""
+    bm = np.asarray(block_mask, dtype=bool)
+    if bm.shape != (-(-nq // block), -(-nk // block)):
+        raise ValueError("block mask must be [ceil(Nq/block), ceil(Nk/block)]")
+    return np.repeat(np.repeat(bm, block, axis=0), block, axis=1)[:nq, :nk]
+
+
+def head_forward_pattern(q, k, v, visible, scale, causal=False):
+    """One head with the entries of S outside `visible` ([Nq, Nk] booleans) removed: O, L, P."""
+    s = np.where(visible, scores(q, k, scale, causal), -np.inf)
+    p, lse = softmax_rows_masked(s)
+    return p @ v, lse, p
+
+
+def head_backward_pattern(q, k, v, visible, do, scale, causal=False):
+    """One head: dQ, dK, dV of section 2.2 / Algorithm 2 with the P of the remaining entries."""
+    o, _, p = head_forward_pattern(q, k, v, visible, scale, causal)
+    dv = p.T @ do
+    dp = do @ v.T
+    big_d = np.sum(do * o, axis=1, keepdims=True)
+    ds = p * (dp - big_d)
+    return scale * (ds @ k), scale * (ds.T @ q), dv
+
+
+def _pattern_batch(Q, K, V, dO, scale, causal, visible_of):
+    B, Nq, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    O = np.empty((B, Nq, Hq, d), dtype=np.float64)
+    L = np.empty((B, Hq, Nq), dtype=np.float64)
+    dQ, dK, dV = np.zeros(Q.shape), np.zeros(K.shape), np.zeros(V.shape)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            vis = visible_of(b, h)
+            o, lse, _ = head_forward_pattern(Q[b, :, h], K[b, :, g], V[b, :, g], vis, scale, causal)
+            O[b, :, h], L[b, h] = o, lse
+            if dO is not None:
+                dq, dk, dv = head_backward_pattern(Q[b, :, h], K[b, :, g], V[b, :, g], vis, dO[b, :, h], scale, causal)
+                dQ[b, :, h] = dq
+                dK[b, :, g] += dk
+                dV[b, :, g] += dv
+    return O, L, dQ, dK, dV
+
+
+def attention_forward_local(Q, K, V, scale, left, right):
+    """Dense batch forward with the window (left, right): O [B,Nq,Hq,d], L [B,Hq,Nq]."""
+    vis = window_visible(Q.shape[1], K.shape[1], left, right)
+    return _pattern_batch(Q, K, V, None, scale, False, lambda b, h: vis)[:2]
+
+
+def attention_backward_local(Q, K, V, dO, scale, left, right):
+    """Dense batch backward with the window (left, right): dQ, dK, dV."""
+    vis = window_visible(Q.shape[1], K.shape[1], left, right)
+    return _pattern_batch(Q, K, V, dO, scale, False, lambda b, h: vis)[2:]
+
+
+def attention_forward_blocksparse(Q, K, V, scale, causal, block_mask, block):
+    """Dense batch forward with a block mask [Bm, Hm, ceil(Nq/block), ceil(Nk/block)]
+    (Bm in {1, B}, Hm in {1, Hq}): O, L."""
+    nq, nk = Q.shape[1], K.shape[1]
+    return _pattern_batch(Q, K, V, None, scale, causal,
+                          lambda b, h: block_visible(nq, nk, _mask_of(block_mask, b, h), block))[:2]
+
+
+def attention_backward_blocksparse(Q, K, V, dO, scale, causal, block_mask, block):
+    """Dense batch backward with a block mask: dQ, dK, dV."""
+    nq, nk = Q.shape[1], K.shape[1]
+    return _pattern_batch(Q, K, V, dO, scale, causal,
+                          lambda b, h: block_visible(nq, nk, _mask_of(block_mask, b, h), block))[2:]

@@ -910,3 +910,159 @@ def test_a_sequence_with_queries_but_no_keys_is_a_row_block_the_mask_emptied():
         dq, dk, dv = orc.attention_backward(Q[None, a:e], K[None, ak:ek], V[None, ak:ek], dO[None, a:e], 0.5, False)
         assert np.array_equal(O[a:e], o[0]) and np.array_equal(L[:, a:e], l[0])
         assert np.array_equal(dQ[a:e], dq[0]) and np.array_equal(dK[ak:ek], dk[0]) and np.array_equal(dV[ak:ek], dv[0])
+
+
+# ---------------------------------------------------------------------------
+# local (sliding-window) and block-sparse patterns
+# ---------------------------------------------------------------------------
+
+def _brute_pattern(q, k, v, scale, keep):
+    """Scalar loops over the kept entries only: O, L per row (rows without entries: 0, -inf)."""
+    nq, nk, d = q.shape[0], k.shape[0], q.shape[1]
+    O, L = np.zeros((nq, d)), np.full(nq, -np.inf)
+    for r in range(nq):
+        cols = [c for c in range(nk) if keep(r, c)]
+        if not cols:
+            continue
+        sc = [scale * sum(q[r, t] * k[c, t] for t in range(d)) for c in cols]
+        mx = max(sc)
+        w = [math.exp(x - mx) for x in sc]
+        tot = sum(w)
+        L[r] = mx + math.log(tot)
+        for wi, c in zip(w, cols):
+            O[r] += wi / tot * v[c]
+    return O, L
+
+
+@pytest.mark.parametrize("nq,nk,left,right", [(6, 6, 2, 0), (4, 9, 3, 0), (7, 7, 1, 2), (5, 8, -1, 1), (6, 6, 0, 0), (3, 10, 2, -1)])
+def test_window_forward_against_scalar_loops(nq, nk, left, right):
+    rng = np.random.default_rng(500 + nq + nk)
+    q, k, v = rng.standard_normal((nq, 3)), rng.standard_normal((nk, 3)), rng.standard_normal((nk, 3))
+    off = nk - nq
+    keep = lambda r, c: (left < 0 or c >= r + off - left) and (right < 0 or c <= r + off + right)  # noqa: E731
+    o, lse, p = orc.head_forward_pattern(q, k, v, orc.window_visible(nq, nk, left, right), 0.7)
+    bo, bl = _brute_pattern(q, k, v, 0.7, keep)
+    assert np.allclose(o, bo, atol=1e-12) and np.allclose(lse, bl, atol=1e-12)
+    assert np.allclose(p.sum(axis=1), 1.0, atol=1e-12)
+
+
+def test_window_special_cases_reduce_to_known_results():
+    rng = np.random.default_rng(510)
+    nq, nk, d = 5, 9, 4
+    q, k, v, do = (rng.standard_normal(s) for s in ((nq, d), (nk, d), (nk, d), (nq, d)))
+    # no bounds: plain attention; right = 0 alone: the causal rule
+    for (left, right, causal) in ((-1, -1, False), (-1, 0, True), (nk, nk, False), (nk + 3, 0, True)):
+        vis = orc.window_visible(nq, nk, left, right)
+        a = orc.head_forward_pattern(q, k, v, vis, 0.3)
+        b = orc.head_forward(q, k, v, 0.3, causal)
+        assert np.allclose(a[0], b[0], atol=1e-13) and np.allclose(a[1], b[1], atol=1e-13)
+        for x, y in zip(orc.head_backward_pattern(q, k, v, vis, do, 0.3), orc.head_backward(q, k, v, do, 0.3, causal)):
+            assert np.allclose(x, y, atol=1e-13)
+    # a window of one key: O is that key's value row, L its score, and nothing depends on the others
+    o, lse, _ = orc.head_forward_pattern(q, k, v, orc.window_visible(nq, nk, 0, 0), 0.3)
+    assert np.allclose(o, v[nk - nq:], atol=1e-14)
+    assert np.allclose(lse, 0.3 * np.sum(q * k[nk - nq:], axis=1), atol=1e-13)
+    dq, dk, dv = orc.head_backward_pattern(q, k, v, orc.window_visible(nq, nk, 0, 0), do, 0.3)
+    assert np.allclose(dq, 0, atol=1e-14) and np.allclose(dk, 0, atol=1e-14)  # P = 1 is constant
+    assert np.allclose(dv[nk - nq:], do, atol=1e-14) and np.allclose(dv[:nk - nq], 0)
+    # Q = 0: the mean over the window, L = log(number of keys in it)
+    left, right = 2, 1
+    o, lse, _ = orc.head_forward_pattern(np.zeros((nq, d)), k, v, orc.window_visible(nq, nk, left, right), 0.3)
+    for r in range(nq):
+        lo, hi = max(0, r + nk - nq - left), min(nk - 1, r + nk - nq + right)
+        assert np.allclose(o[r], v[lo:hi + 1].mean(axis=0), atol=1e-14)
+        assert abs(lse[r] - math.log(hi - lo + 1)) < 1e-14
+
+
+def test_window_and_block_patterns_equal_the_same_pattern_written_as_an_additive_mask():
+    rng = np.random.default_rng(520)
+    nq, nk, d = 7, 10, 3
+    q, k, v, do = (rng.standard_normal(s) for s in ((nq, d), (nk, d), (nk, d), (nq, d)))
+    bm = rng.random((2, 3)) < 0.6
+    bm[0, 0] = True
+    for vis, causal in ((orc.window_visible(nq, nk, 3, 1), False), (orc.block_visible(nq, nk, bm, 4), False),
+                        (orc.block_visible(nq, nk, bm, 4), True)):
+        mask = np.zeros((nq, nk))
+        for r in range(nq):
+            for c in range(nk):
+                if not vis[r, c]:
+                    mask[r, c] = -np.inf
+        a = orc.head_forward_pattern(q, k, v, vis, 0.4, causal)
+        b = orc.head_forward_masked(q, k, v, mask, 0.4, causal)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        for x, y in zip(orc.head_backward_pattern(q, k, v, vis, do, 0.4, causal),
+                        orc.head_backward_masked(q, k, v, mask, do, 0.4, causal)):
+            assert np.array_equal(x, y)
+
+
+def test_block_mask_expansion_and_scalar_loops():
+    rng = np.random.default_rng(530)
+    nq, nk, d, bs = 9, 11, 2, 4
+    bm = np.array([[1, 0, 1], [0, 0, 0], [1, 1, 0]], dtype=bool)   # the middle row block sees nothing
+    vis = orc.block_visible(nq, nk, bm, bs)
+    assert vis.shape == (nq, nk)
+    for r in range(nq):
+        for c in range(nk):
+            assert vis[r, c] == bm[r // bs, c // bs]
+    q, k, v = rng.standard_normal((nq, d)), rng.standard_normal((nk, d)), rng.standard_normal((nk, d))
+    o, lse, _ = orc.head_forward_pattern(q, k, v, vis, 0.9)
+    bo, bl = _brute_pattern(q, k, v, 0.9, lambda r, c: bm[r // bs, c // bs])
+    assert np.allclose(o, bo, atol=1e-12)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(bl)) and np.all(np.isneginf(lse[4:8]))
+    assert np.allclose(lse[~np.isneginf(lse)], bl[~np.isneginf(bl)], atol=1e-12)
+    assert not o[4:8].any()
+    with pytest.raises(ValueError):
+        orc.block_visible(nq, nk, bm[:2], bs)
+
+
+@pytest.mark.parametrize("pattern", ["window", "blocks"])
+def test_pattern_backward_against_finite_differences(pattern):
+    rng = np.random.default_rng(540)
+    B, nq, nk, Hq, Hkv, d = 1, 5, 7, 2, 1, 3
+    Q, K, V, dO = (rng.standard_normal(s) for s in ((B, nq, Hq, d), (B, nk, Hkv, d), (B, nk, Hkv, d), (B, nq, Hq, d)))
+    if pattern == "window":
+        fwd = lambda Q, K, V: orc.attention_forward_local(Q, K, V, 0.6, 2, 1)[0]  # noqa: E731
+        grads = orc.attention_backward_local(Q, K, V, dO, 0.6, 2, 1)
+    else:
+        bm = np.array([[[[1, 1, 0, 1], [0, 1, 1, 0], [1, 0, 1, 1]]]], dtype=bool)
+        fwd = lambda Q, K, V: orc.attention_forward_blocksparse(Q, K, V, 0.6, True, bm, 2)[0]  # noqa: E731
+        grads = orc.attention_backward_blocksparse(Q, K, V, dO, 0.6, True, bm, 2)
+    f = lambda Q, K, V: float(np.sum(fwd(Q, K, V) * dO))  # noqa: E731
+    h = 1e-6
+    for which, (X, G) in enumerate(zip((Q, K, V), grads)):
+        num = np.zeros_like(X)
+        it = np.nditer(X, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = X[i]
+            X[i] = old + h
+            fp = f(Q, K, V)
+            X[i] = old - h
+            fm = f(Q, K, V)
+            X[i] = old
+            num[i] = (fp - fm) / (2 * h)
+        assert np.allclose(num, G, atol=1e-7), which
+
+
+def test_pattern_batch_wrappers_map_heads_and_shared_masks():
+    rng = np.random.default_rng(550)
+    B, nq, nk, Hq, Hkv, d = 2, 6, 8, 4, 2, 3
+    Q, K, V, dO = (rng.standard_normal(s) for s in ((B, nq, Hq, d), (B, nk, Hkv, d), (B, nk, Hkv, d), (B, nq, Hq, d)))
+    bm = rng.random((1, Hq, 2, 2)) < 0.7
+    bm[..., 0] = True
+    O, L = orc.attention_forward_blocksparse(Q, K, V, 0.5, False, bm, 4)
+    dQ, dK, dV = orc.attention_backward_blocksparse(Q, K, V, dO, 0.5, False, bm, 4)
+    dk_sum, dv_sum = np.zeros_like(K), np.zeros_like(V)
+    for b in range(B):
+        for h in range(Hq):
+            vis = orc.block_visible(nq, nk, bm[0, h], 4)
+            o, lse, _ = orc.head_forward_pattern(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2], vis, 0.5)
+            dq, dk, dv = orc.head_backward_pattern(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2], vis, dO[b, :, h], 0.5)
+            assert np.array_equal(O[b, :, h], o) and np.array_equal(L[b, h], lse) and np.array_equal(dQ[b, :, h], dq)
+            dk_sum[b, :, h // 2] += dk
+            dv_sum[b, :, h // 2] += dv
+    assert np.allclose(dK, dk_sum, atol=1e-14) and np.allclose(dV, dv_sum, atol=1e-14)
+    Ol, Ll = orc.attention_forward_local(Q, K, V, 0.5, 1, 0)
+    for h in range(Hq):
+        o, lse, _ = orc.head_forward_pattern(Q[1, :, h], K[1, :, h // 2], V[1, :, h // 2], orc.window_visible(nq, nk, 1, 0), 0.5)
+        assert np.array_equal(Ol[1, :, h], o) and np.array_equal(Ll[1, h], lse)
