@@ -268,6 +268,30 @@ int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, cons
                 void* stream);
 
 /*
+ * Local (sliding-window) attention (section 5, "Discussion and Future Directions", names local
+ * attention as a pattern the method combines with; the block skipping of section 3.1.1,
+ * "Causal masking", is what makes it cheap). Reading: with query r standing at position
+ * q = r + Nk - Nq among the keys (the alignment of the causal rule), key c is visible to it iff
+ *     q - window_left <= c <= q + window_right ;
+ * a negative bound means no bound on that side. window_right = 0 with window_left < 0 is the
+ * causal rule; window_left = W - 1, window_right = 0 is a causal window over the W newest keys.
+ * Everything else is fa_cross_fwd / fa_cross_bwd: same layouts, workspace
+ * (fa_cross_bwd_workspace_bytes), grouped heads, errors. Only blocks inside the band are
+ * visited, so time is proportional to the band's area. Needs Nq <= Nk (FA_ERR_SHAPE otherwise:
+ * a query would stand before the first key); every row then sees at least its own position.
+ * bfloat16, d in {64, 128} (FA_ERR_UNSUPPORTED otherwise) unless the bounds reduce to plain or
+ * causal attention.
+ */
+int fa_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                 int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                 int window_left, int window_right, void* stream);
+int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                 const float* LSE, void* dQ, void* dK, void* dV,
+                 void* workspace, size_t workspace_bytes,
+                 int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                 int window_left, int window_right, void* stream);
+
+/*
  * Two lengths in the packed ragged layout: sequence s owns query rows
  * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
  * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].

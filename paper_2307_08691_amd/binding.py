@@ -56,6 +56,8 @@ SIGNATURES = {
     "fa_mask_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_mask_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
                     [ctypes.c_longlong] * 3 + [_c_void_p]),
+    "fa_local_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
@@ -204,6 +206,15 @@ def fa_mask_bwd_raw(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv
                     mask_hs, mask_rs, stream=0) -> int:
     return load().fa_mask_bwd(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
                               int(causal), mask_bs, mask_hs, mask_rs, stream)
+
+
+def fa_local_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0) -> int:
+    return load().fa_local_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream)
+
+
+def fa_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0) -> int:
+    return load().fa_local_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right,
+                               stream)
 
 
 def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
@@ -526,6 +537,30 @@ def fa_mask_bwd(Q, K, V, M, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=
     _check(fa_mask_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
                            _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, bs, hs, rs,
                            _stream()))
+    return dQ, dK, dV
+
+
+def fa_local_fwd(Q, K, V, scale: float, window_left: int, window_right: int, O=None, LSE=None):
+    """Sliding window: the query at position q = r + Nk - Nq sees keys q - window_left .. q + window_right
+    (a negative bound: none). Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
+    import torch
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_local_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
+                            window_left, window_right, _stream()))
+    return O, LSE
+
+
+def fa_local_bwd(Q, K, V, O, dO, LSE, scale: float, window_left: int, window_right: int, dQ=None, dK=None, dV=None,
+                 workspace=None):
+    """Backward of fa_local_fwd for the same window."""
+    import torch
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
+    _check(fa_local_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
+                            _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, window_left, window_right,
+                            _stream()))
     return dQ, dK, dV
 
 

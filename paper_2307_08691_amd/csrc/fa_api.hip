@@ -68,6 +68,7 @@ fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int
   p.drop_rp = 1.f;
   p.mask = nullptr;
   p.mask_bs = p.mask_hs = p.mask_rs = 0;
+  p.win_left = p.win_right = -1;
   p.cu_seqlens = cu;
   p.cu_seqlens_k = cu_k;
   p.nseq = nseq;
@@ -122,6 +123,8 @@ struct Options {
   bool mask = false;                // elementwise mask M with its three strides
   const void* M = nullptr;
   long long mask_bs = 0, mask_hs = 0, mask_rs = 0;
+  bool window = false;              // sliding window (win_left, win_right); a negative bound is no bound
+  int win_left = -1, win_right = -1;
 };
 
 Options half_precision(int f16) {
@@ -146,7 +149,19 @@ Options with_mask(const void* M, long long bs, long long hs, long long rs) {
   return o;
 }
 
+Options with_window(int left, int right) {
+  Options o;
+  o.window = true;
+  o.win_left = left < 0 ? -1 : left;
+  o.win_right = right < 0 ? -1 : right;
+  return o;
+}
+
 int apply_options(fa::Problem& p, const Options& o) {
+  if (o.window) {
+    p.win_left = o.win_left;
+    p.win_right = o.win_right;
+  }
   if (o.dropout)
     if (int e = set_dropout(p, o.p_drop, o.seed)) return e;
   if (o.mask)
@@ -357,7 +372,7 @@ static int cross_fwd(const void* Q, const void* K, const void* V, void* O, float
                      int Nk, int d, float scale, int causal, void* stream, const Options& opt) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask))) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask || opt.window))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
   return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, 0, nullptr,
                  nullptr, opt);
@@ -368,7 +383,7 @@ static int cross_bwd(const void* Q, const void* K, const void* V, const void* O,
                      int Nq, int Nk, int d, float scale, int causal, void* stream, const Options& opt) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask))) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask || opt.window))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return FA_ERR_ALIGN;
@@ -432,6 +447,38 @@ int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, cons
                 long long mask_head_stride, long long mask_row_stride, void* stream) {
   return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
                    stream, with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride));
+}
+
+// Sliding window. Without any bound this is plain attention and with win_right = 0 alone the
+// causal rule: both go to the kernels built for them. Otherwise the window instantiations run.
+static int window_route(int Nq, int Nk, int& left, int& right, int& causal) {
+  if (Nq > Nk) return FA_ERR_SHAPE;  // some query would stand before the first key
+  if (left < 0) left = -1;
+  if (right < 0) right = -1;
+  if (left >= Nk) left = -1;    // a bound no row can reach is no bound
+  if (right >= Nk) right = -1;
+  causal = left < 0 && right == 0;
+  if (causal) right = -1;
+  return FA_OK;
+}
+
+int fa_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                 int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+  int causal = 0;
+  if (B > 0 && Nq > 0 && Nk > 0)
+    if (int e = window_route(Nq, Nk, window_left, window_right, causal)) return e;
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream,
+                   window_left < 0 && window_right < 0 ? half_precision(0) : with_window(window_left, window_right));
+}
+
+int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                 int Nq, int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+  int causal = 0;
+  if (B > 0 && Nq > 0 && Nk > 0)
+    if (int e = window_route(Nq, Nk, window_left, window_right, causal)) return e;
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, window_left < 0 && window_right < 0 ? half_precision(0) : with_window(window_left, window_right));
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,

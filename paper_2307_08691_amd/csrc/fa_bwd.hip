@@ -104,9 +104,15 @@ constexpr int dkdv_block_keys(int D, bool dropout, bool mask) { return dkdv_wide
 // 16 entries of M straight into registers, one tile ahead: requested at the end of the vector
 // phase before, complete at the wait that ends the matrix phase in between. The operand
 // prefetch distance is halved to make room for them.
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
+//
+// LOCAL: sliding window (see the forward kernel). The workgroup visits only the row tiles whose
+// window reaches its 256 keys, a wavefront computes only on those that reach its own 32 keys
+// (leading and trailing tiles are sat out), and the element mask is applied on the tiles that
+// straddle an edge of the band.
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
+  static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
   constexpr bool KREG = !MASK && !DROPOUT;  // K_j operands of the wavefront's 32 keys in registers
   constexpr bool VREG = D == 64 && !MASK && !DROPOUT;  // at d = 64 V_j's as well
   constexpr bool WIDE = dkdv_wide(D, DROPOUT, MASK);
@@ -151,9 +157,17 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const float c2 = p.scale_log2e;
   const int nrt = (n + BR - 1) / BR;         // row tiles of the sequence
   // row tiles entirely above the diagonal are skipped; past the last row tile there is nothing to do
+  const int wl = LOCAL ? p.win_left : -1, wr = LOCAL ? p.win_right : -1;  // window bounds (negative: none)
   int i_first = CAUSAL && j0 > off ? (j0 - off) / BR : 0;
+  if (LOCAL && wr >= 0 && j0 > off + wr) i_first = (j0 - off - wr) / BR;  // the first row whose window reaches key j0
   if (i_first > nrt) i_first = nrt;
-  const int T = (nrt - i_first) * p.G;       // tiles this workgroup visits, over the group's query heads
+  int i_end = nrt;  // (window: one past the last row tile whose rows still see the block's last key)
+  if (LOCAL && wl >= 0) {
+    const long last_row = (long)j0 + BC - 1 - off + wl;
+    if (last_row / BR + 1 < i_end) i_end = (int)(last_row / BR) + 1;
+    if (i_end < i_first) i_end = i_first;
+  }
+  const int T = (i_end - i_first) * p.G;     // tiles this workgroup visits, over the group's query heads
   const long stat_base = s * p.lse_seq_stride + (p.cu_seqlens ? si.tok0 : 0);
 
   // Position of a tile in the visiting order: row tile, query head, ring slot, and where the
@@ -381,7 +395,9 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int tq = 0; tq < QTW; ++tq) {
       const int r0 = i0 + 32 * tq;  // first query row of this tile
-      const bool need_mask = (CAUSAL && j0 + 32 * kgi + 31 > r0 + off) || (j0 + BC > nk);
+      const bool need_mask = (CAUSAL && j0 + 32 * kgi + 31 > r0 + off) || (j0 + BC > nk) ||
+                             (LOCAL && ((wr >= 0 && j0 + 32 * kgi + 31 > r0 + off + wr) ||
+                                        (wl >= 0 && j0 + 32 * kgi < r0 + 31 + off - wl)));
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const f32x4 Lv = *(const f32x4*)(smem + LS_OFF + stat_off + (32 * tq + 8 * r4 + 4 * hh) * 4);
@@ -396,9 +412,11 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
         asm volatile("; keep this a branch: the mask costs two instructions per element" ::);
         // visible: key < nk and (causal) key <= r0 + off + row of the tile, row = acc_row(r, hh)
-        const int kc = key_ok ? (CAUSAL ? key - (r0 + off) - 4 * hh : -1) : 0x7fffffff;
+        // (window: key <= position + win_right and key >= position - win_left)
+        const int kc = key_ok ? (CAUSAL ? key - (r0 + off) - 4 * hh : (wr >= 0 ? key - (r0 + off) - 4 * hh - wr : -1)) : 0x7fffffff;
+        const int kb = wl >= 0 ? key - (r0 + off) - 4 * hh + wl : 0x7fffffff;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) S[tq][r] = kc <= acc_row(r, 0) ? S[tq][r] : 0.f;
+        for (int r = 0; r < 16; ++r) S[tq][r] = kc <= acc_row(r, 0) && (!LOCAL || acc_row(r, 0) <= kb) ? S[tq][r] : 0.f;
       }
       if constexpr (DROPOUT) {
         // dP = keep o (dO V^T) / (1 - p), then dS = P o (dP - D) with the true P; afterwards P
@@ -525,24 +543,30 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     // Leading tiles in which every score of THIS wavefront's 32 keys is masked (its keys lie
     // above the tile's last row, or past the end of the sequence): the wavefront only keeps up
     // with the copies and the barriers.
-    int skip = 0;
+    int skip = 0, t_stop = T;  // this wavefront computes on tiles skip .. t_stop - 1
     if (j0 + 32 * kgi >= nk) skip = T;
-    else if (CAUSAL && j0 + 32 * kgi > off) {
-      const int first_useful = (j0 + 32 * kgi - off) / BR;  // first row tile that reaches this wavefront's keys
+    else if ((CAUSAL || wr >= 0) && j0 + 32 * kgi > off + (LOCAL ? wr : 0)) {
+      const int first_useful = (j0 + 32 * kgi - off - (LOCAL ? wr : 0)) / BR;  // first row tile that reaches this wavefront's keys
       skip = (first_useful - i_first) * p.G < T ? (first_useful - i_first) * p.G : T;
     }
+    if (LOCAL && wl >= 0) {  // one past the last row tile whose rows still see this wavefront's last key
+      const long last_row = (long)j0 + 32 * kgi + 31 - off + wl;
+      const long stop = (last_row / BR + 1 - i_first) * p.G;
+      if (stop < t_stop) t_stop = (int)stop;
+    }
+    if (t_stop < skip) t_stop = skip;
     int t = 0;
     for (; t < skip; ++t) {
       end_matrix_phase();
       vector_phase_w(t, false);
       advance(cur, 1);
     }
-    if (t < T) {
+    if (t < t_stop) {
       __builtin_amdgcn_s_setprio(2);
       mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
       end_matrix_phase();
       vector_phase_w(t, true);
-      for (++t; t < T; ++t) {
+      for (++t; t < t_stop; ++t) {
         prev = cur;
         advance(cur, 1);
         fused_stream();
@@ -552,6 +576,12 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       prev = cur;
       __builtin_amdgcn_s_setprio(2);
       mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
+    }
+    if constexpr (LOCAL) {  // trailing tiles below this wavefront's band: keep up with the copies and the barriers
+      for (; t < T; ++t) {
+        end_matrix_phase();
+        vector_phase_w(t, false);
+      }
     }
     end_matrix_phase();
     if (grp == 0) lds_barrier();  // group 1's last phase
@@ -646,9 +676,12 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // apart, K_j / V_j tiles streaming HBM -> LDS two blocks ahead into a ring of four buffers.
 // MASK: the tensor added to the scaled scores reaches the wavefronts as in the forward kernel
 // (a private 32 x 64 piece per block, copied HBM -> LDS one vector phase ahead).
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
+// LOCAL: sliding window, as in the forward kernel (only the column blocks inside the band are
+// walked; the element mask on the blocks that straddle an edge of it).
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
+  static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int ROWB = 2 * D;
@@ -711,12 +744,15 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   f32x16 negD;  // filled once D_i has arrived, below
 
   const int ncol_all = (nk + BC - 1) / BC;
-  int ncol = ncol_all;
-  if (CAUSAL) {
+  int ncol = ncol_all, jb = 0;  // column blocks jb .. ncol - 1
+  const int wl = LOCAL ? p.win_left : -1, wr = LOCAL ? p.win_right : -1;  // window bounds (negative: none)
+  if (CAUSAL || wr >= 0) {
     const int last_pos = (i0 + BR < n ? i0 + BR : n) - 1 + off;
-    const int c = last_pos / BC + 1;
+    const int c = (last_pos + (LOCAL ? wr : 0)) / BC + 1;
     ncol = c < ncol_all ? c : ncol_all;
   }
+  if (LOCAL && wl >= 0 && i0 + off > wl) jb = (i0 + off - wl) / BC;
+  if (ncol < jb) ncol = jb;
 
   // tile copies: group 1 brings in the K tiles, group 0 the V tiles, each at the start of its
   // own vector phase (see the forward kernel)
@@ -746,9 +782,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       }
     }
   };
-  issue_tile(0);
-  issue_tile(1);
-  issue_mask(0);
+  issue_tile(jb);
+  issue_tile(jb + 1);
+  issue_mask(jb);
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     touch(Qf[ks]);
@@ -770,7 +806,15 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
 
   const float c2 = p.scale_log2e;
   const int wrow_last = wrow0 + 31 + off;  // position of the last row among the keys
-  const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;  // last visible column of this lane's row
+  // last and (window) first visible column of this lane's row
+  const int lim_row = CAUSAL || wr >= 0 ? (row + off + (LOCAL ? wr : 0) < nk - 1 ? row + off + (LOCAL ? wr : 0) : nk - 1) : nk - 1;
+  const int lo_row = wl >= 0 ? row + off - wl : 0;
+  // a block is skipped by a wavefront when every score it would produce is masked
+  auto wave_sees = [&](int j) {
+    if (CAUSAL) return j * BC <= wrow_last;
+    if (LOCAL) return (wr < 0 || j * BC <= wrow_last + wr) && (wl < 0 || j * BC + BC - 1 >= wrow0 + off - wl);
+    return true;
+  };
 
   f32x16 S[2], dP[2];
   bf16x8 dSf[2][2];
@@ -778,7 +822,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   // ================= matrix phase j =================
   auto matrix_phase = [&](int j) {
     __builtin_amdgcn_s_setprio(2);
-    if (j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
+    if (j < ncol && wave_sees(j)) {
       // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
       const int zk = zrow + (j % RING) * BUFB;
       S[0] = S[1] = dP[0] = dP[1] = (f32x16){0};
@@ -794,7 +838,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
             else S[kt] = mfma32<F16>(x, Qf[ks], S[kt]);
           });
     }
-    if (j >= 1 && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
+    if (j > jb && wave_sees(j - 1)) {
       // ---- dQ_i^T += K_{j-1}^T dS^T (line 15)
       const int kb = ((j - 1) % RING) * BUFB;
       const int zc0 = zcol[0] + kb, zc1 = zcol[1] + kb;
@@ -813,9 +857,10 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
                                      : 0u;
   // ================= vector phase j: P = exp(S - L) (line 11), dS = P o (dP - D) (line 14) =================
   auto vector_phase = [&](int j) {
-    if (j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
+    if (j >= ncol || !wave_sees(j)) return;
     const int col0 = j * BC;
-    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk) ||
+                           (LOCAL && ((wr >= 0 && col0 + BC - 1 > wrow0 + off + wr) || (wl >= 0 && col0 < wrow_last - wl)));
     int zm = lq * (2 * BC) + ((lq & 7) << 4) + 8 * hh;  // mask: chunk k of this lane's row at zm ^ 16 k
     if constexpr (MASK) {
       wait_vmem_upto<TPW>();  // this piece of M is older than this phase's tile copies
@@ -840,8 +885,10 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       if (need_mask) {  // tiles on the diagonal or at the end of the sequence only
         asm volatile("; keep this a branch: the mask costs three instructions per element" ::);
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (col0 + 32 * kt + acc_row(r, hh) > lim_row) S[kt][r] = 0.f;
+        for (int r = 0; r < 16; ++r) {
+          const int c = col0 + 32 * kt + acc_row(r, hh);
+          if (c > lim_row || (LOCAL && c < lo_row)) S[kt][r] = 0.f;
+        }
       }
       if constexpr (DROPOUT) {  // dP = keep o (dO V^T) / (1 - p)
 #pragma unroll
@@ -861,7 +908,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
 
   // phases: see the forward kernel
   if (grp == 0) {
-    for (int j = 0; j <= ncol; ++j) {
+    for (int j = jb; j <= ncol; ++j) {
       matrix_phase(j);
       lds_barrier();
       issue_tile(j + 2);
@@ -871,9 +918,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       lds_barrier();
     }
   } else {
-    issue_tile(2);
+    issue_tile(jb + 2);
     lds_barrier();
-    for (int j = 0; j <= ncol; ++j) {
+    for (int j = jb; j <= ncol; ++j) {
       matrix_phase(j);
       wait_vmem_upto<TPW + MPW>();
       lds_barrier();
@@ -918,6 +965,10 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     dim3 grid(grid_size((a.p.Nk + bck - 1) / bck, a.p.Hkv * a.p.nseq));
     bool done = false;
     if constexpr (!F16) {
+      if (a.p.win_left >= 0 || a.p.win_right >= 0) {  // sliding window
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        done = true;
+      } else
       if (a.p.mask) {
         if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, false, false, false, true>), grid, dim3(512), 0, st, a);
         else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, false, false, true>), grid, dim3(512), 0, st, a);
@@ -946,6 +997,10 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
     bool done = false;
     if constexpr (!F16) {
+      if (a.p.win_left >= 0 || a.p.win_right >= 0) {  // sliding window
+        hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        done = true;
+      } else
       if (a.p.mask) {
         if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, false, false, false, true>), grid, dim3(512), 0, st, a);
         else hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, false, false, true>), grid, dim3(512), 0, st, a);

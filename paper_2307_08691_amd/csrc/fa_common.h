@@ -46,6 +46,11 @@ struct Problem {
   // shares the mask over sequences or heads; mask_rs >= Nk rounded up to 8, a multiple of 8
   const __bf16* mask;
   long mask_bs, mask_hs, mask_rs;
+  // sliding window (local attention): with query r at position q = r + nk - nq among the keys, key c
+  // is visible iff q - win_left <= c <= q + win_right; a negative bound is no bound. Only read
+  // by the LOCAL instantiations (the entry points send "no bound at all" and "win_right = 0
+  // alone" to the plain and the causal kernels).
+  int win_left, win_right;
 };
 
 struct SeqInfo {

@@ -80,11 +80,21 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return __buil
 // the exponent's base at the start of the next one. Entries of -inf remove a score; a row may
 // be left without any, so the running maximum can stay -inf (guards as for SPLIT) and such a
 // row ends with O = 0, L = -inf.
-template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false>
+//
+// LOCAL: a sliding window (section 5 names local attention as a pattern to combine with; the
+// block skipping of section 3.1.1 carries over): key c is visible to the query at position q
+// iff q - win_left <= c <= q + win_right. The workgroup walks only the column blocks its rows
+// can see, a wavefront sits out the blocks none of its 32 rows can see, and the element mask
+// is applied on the blocks that straddle an edge of the band. A row's first visible key may
+// lie in a later block than its wavefront's first one, so the guards for "no key seen yet"
+// of the split-key kernel apply. Instantiated with CAUSAL = false (win_right = 0 is the rule).
+template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false,
+          bool LOCAL = false>
 __global__ __launch_bounds__(512)
-    __attribute__((amdgpu_waves_per_eu(fwd_two_per_cu(D, DROPOUT, MASK) ? 4 : 2, fwd_two_per_cu(D, DROPOUT, MASK) ? 4 : 2))) void
+    __attribute__((amdgpu_waves_per_eu(fwd_two_per_cu(D, DROPOUT, MASK || LOCAL) ? 4 : 2, fwd_two_per_cu(D, DROPOUT, MASK || LOCAL) ? 4 : 2))) void
     fwd_kernel(FwdArgs a) {
-  constexpr bool TWO = fwd_two_per_cu(D, DROPOUT, MASK);
+  constexpr bool TWO = fwd_two_per_cu(D, DROPOUT, MASK || LOCAL);
+  static_assert(!LOCAL || (!CAUSAL && !SPLIT && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
   constexpr int AHEAD_QK = TWO ? 1 : kFwdAheadQK, AHEAD_PV = TWO ? 1 : kFwdAheadPV;
   static_assert(!MASK || (!SPLIT && !F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
@@ -158,13 +168,17 @@ __global__ __launch_bounds__(512)
   // (split: this workgroup's share jb .. of them)
   const int ncol_all = (nk + BC - 1) / BC;
   const int per_split = (ncol_all + nsplit - 1) / nsplit;
-  const int jb = split * per_split;
+  int jb = split * per_split;
   int ncol = jb + per_split < ncol_all ? jb + per_split : ncol_all;
-  if (CAUSAL) {
+  const int wl = LOCAL ? p.win_left : -1, wr = LOCAL ? p.win_right : -1;  // window bounds (negative: none)
+  if (CAUSAL || LOCAL) {
     const int last_prow = (i0 + BR < nrows ? i0 + BR : nrows) - 1;
     const int last_pos = (SPLIT ? last_prow / p.G : last_prow) + off;
-    const int c = last_pos / BC + 1;
-    ncol = c < ncol ? c : ncol;
+    if (CAUSAL || wr >= 0) {
+      const int c = (last_pos + (LOCAL ? wr : 0)) / BC + 1;
+      ncol = c < ncol ? c : ncol;
+    }
+    if (LOCAL && wl >= 0 && i0 + off > wl) jb = (i0 + off - wl) / BC;  // the first block the first row sees
   }
   if (ncol < jb) ncol = jb;  // nothing visible in this share: the loops below still run once
 
@@ -222,12 +236,20 @@ __global__ __launch_bounds__(512)
     zcol[u] = swz_off<ROWB>(4 * hh + (p16 >> 2) + 8 * u, 2 * g16 + ((p16 & 3) >> 1)) + 8 * (p16 & 1);
 
   const float c2 = p.scale_log2e;
-  constexpr bool GUARD = SPLIT || MASK;  // a row may have seen no key yet
+  constexpr bool GUARD = SPLIT || MASK || LOCAL;  // a row may have seen no key yet
   // MASK: the scores are scaled when M is added (one FMA); from there on the softmax works on
   // scaled scores and the factor that remains is the change of base
   const float cs = MASK ? kLog2e : c2;
   const int wrow_last = wq_last + off;  // position of the wavefront's last query among the keys
-  const int lim_row = CAUSAL ? (row + off < nk - 1 ? row + off : nk - 1) : nk - 1;  // last visible column of this lane's row
+  // last and (window) first visible column of this lane's row
+  const int lim_row = CAUSAL || wr >= 0 ? (row + off + (LOCAL ? wr : 0) < nk - 1 ? row + off + (LOCAL ? wr : 0) : nk - 1) : nk - 1;
+  const int lo_row = wl >= 0 ? row + off - wl : 0;
+  // a block is skipped by a wavefront when every score it would produce is masked
+  auto wave_sees = [&](int j) {
+    if (CAUSAL) return j * BC <= wrow_last;
+    if (LOCAL) return (wr < 0 || j * BC <= wrow_last + wr) && (wl < 0 || j * BC + BC - 1 >= wrow0 + off - wl);
+    return true;
+  };
 
   f32x16 S[2];
   bf16x8 Pf[2][2];
@@ -239,8 +261,7 @@ __global__ __launch_bounds__(512)
   // ================= matrix phase j: S^T of block j, O^T update with block j - 1 =================
   auto matrix_phase = [&](int j) {
     __builtin_amdgcn_s_setprio(FA_FWD_MATRIX_PRIO);  // the MFMA stream must not wait behind the other group's VALU work
-    // a block is skipped by a wavefront when every score it would produce is masked
-    if (wave_on && j < ncol && (!CAUSAL || j * BC <= wrow_last)) {
+    if (wave_on && j < ncol && wave_sees(j)) {
       // ---- S^T = K_j Q_i^T (Algorithm 1, line 8)
       const int zk = zrow + (j % RING) * BUFB;
       S[0] = S[1] = (f32x16){0};
@@ -248,7 +269,7 @@ __global__ __launch_bounds__(512)
           [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
           [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, Qf[i >> 1], S[i & 1]); });
     }
-    if (wave_on && j > jb && (!CAUSAL || (j - 1) * BC <= wrow_last)) {
+    if (wave_on && j > jb && wave_sees(j - 1)) {
       // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10)
       const int vb = ((j - 1) % RING) * BUFB + TILEB;
       const int zv0 = zcol[0] + vb, zv1 = zcol[1] + vb;
@@ -264,7 +285,7 @@ __global__ __launch_bounds__(512)
 
   // ================= vector phase j: online softmax of block j (Algorithm 1, line 9) =================
   auto vector_phase = [&](int j) {
-    if (!wave_on || j >= ncol || (CAUSAL && j * BC > wrow_last)) return;
+    if (!wave_on || j >= ncol || !wave_sees(j)) return;
     const int col0 = j * BC;
     if constexpr (MASK) {
       wait_vmem_upto<TPW>();  // the copies of this piece of M are older than this phase's tile copies
@@ -283,14 +304,19 @@ __global__ __launch_bounds__(512)
         }
     }
     // ---- mask: causal entries above the diagonal and columns past the end
-    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk);
+    const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk) ||
+                           (LOCAL && ((wr >= 0 && col0 + BC - 1 > wrow0 + off + wr) || (wl >= 0 && col0 < wrow_last - wl)));
     if (need_mask) {
       asm volatile("; keep this a branch: the mask costs two instructions per element" ::);
       const int lim = lim_row - col0 - 4 * hh;  // last visible column, relative to this lane's first
+      const int lo = lo_row - col0 - 4 * hh;    // (window) first visible column, likewise
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) S[kt][r] = 32 * kt + acc_row(r, 0) > lim ? -INFINITY : S[kt][r];
+        for (int r = 0; r < 16; ++r) {
+          const int x = 32 * kt + acc_row(r, 0);
+          S[kt][r] = x > lim || (LOCAL && x < lo) ? -INFINITY : S[kt][r];
+        }
     }
     // The exponentials of the block against reference `ref` (already in the exponent's base),
     // rounded into the operand registers of the second product; the row sum is taken from the
@@ -422,8 +448,8 @@ __global__ __launch_bounds__(512)
     }
     return;
   }
-  // (mask: a row without any key ends with l = 0: O = 0, L = -inf)
-  const float inv = MASK && !(lsum > 0.f) ? 0.f : (DROPOUT ? p.drop_rp : 1.0f) / lsum;
+  // (mask, window: a row without any key ends with l = 0: O = 0, L = -inf)
+  const float inv = (MASK || LOCAL) && !(lsum > 0.f) ? 0.f : (DROPOUT ? p.drop_rp : 1.0f) / lsum;
   {
     // O through the ring slot that neither holds a block still in use nor receives one of the
     // copies issued past the last block (those fill the three slots after block ncol - 1)
@@ -440,7 +466,9 @@ __global__ __launch_bounds__(512)
     }
     if (row < n && hh == 0)
       a.LSE[s * p.lse_seq_stride + h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + row] =
-          MASK ? (lsum > 0.f ? m + fast_log2(lsum) * kLn2 : -INFINITY) : m * p.scale + fast_log2(lsum) * kLn2;
+          MASK    ? (lsum > 0.f ? m + fast_log2(lsum) * kLn2 : -INFINITY)
+          : LOCAL ? (lsum > 0.f ? m * p.scale + fast_log2(lsum) * kLn2 : -INFINITY)
+                  : m * p.scale + fast_log2(lsum) * kLn2;
   }
 }
 
@@ -827,6 +855,12 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     if (a.p.mask) {  // the entry points keep everything else away from it
       if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, false, false, true>), grid, block, 0, st, a);
       else hipLaunchKernelGGL((fwd_kernel<D, false, false, false, false, false, true>), grid, block, 0, st, a);
+      return hipGetLastError();
+    }
+  }
+  if constexpr (!F16) {
+    if (a.p.win_left >= 0 || a.p.win_right >= 0) {  // sliding window (the entry point keeps everything else away from it)
+      hipLaunchKernelGGL((fwd_kernel<D, false, false, false, false, false, false, true>), grid, block, 0, st, a);
       return hipGetLastError();
     }
   }

@@ -106,6 +106,14 @@ class AttnProblem:
         sequence, halved under the causal mask (the paper's benchmark formula).
         Two lengths: 4*d per visible (query, key) pair, Nq*Nk of them without
         the mask and Nq*Nk - Nq^2/2 with it (the same count for Nq = Nk)."""
+        if self.meta.get("window") and not self.varlen:
+            # sliding window: 4*d per visible (query, key) pair, counted exactly
+            left, right = self.meta["window"]
+            nk = self.keys
+            pos = np.arange(self.N, dtype=np.int64) + (nk - self.N)
+            lo = np.maximum(0, pos - left) if left >= 0 else np.zeros_like(pos)
+            hi = np.minimum(nk - 1, pos + right) if right >= 0 else np.full_like(pos, nk - 1)
+            return 4.0 * self.B * self.Hq * self.d * float(np.sum(hi - lo + 1))
         if self.Nk and not self.varlen:
             pairs = float(self.N) * self.Nk - (0.5 * float(self.N) ** 2 if self.causal else 0.0)
             return 4.0 * self.B * self.Hq * self.d * pairs
@@ -205,6 +213,10 @@ CONFIGS = {
                                  mask=dict(seed=9800, removed=0.3)),
     "mask_d128_n8k_full": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1020,
                                mask=dict(seed=9801, removed=0.3)),
+    # local attention: a causal window over the newest 1024 (2048) keys, and a two-sided window
+    "local_d128_n8k_w1024": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1022, window=(1023, 0)),
+    "local_d128_n16k_w2048": dict(kind="dense", B=1, N=16384, Hq=16, Hkv=16, d=128, causal=False, seed=1023, window=(2047, 0)),
+    "local_d64_n8k_w512x2": dict(kind="dense", B=2, N=8192, Hq=32, Hkv=32, d=64, causal=False, seed=1024, window=(512, 512)),
     "mask_d64_n8k_full": dict(kind="dense", B=2, N=8192, Hq=32, Hkv=32, d=64, causal=False, seed=1021,
                               mask=dict(seed=9802, removed=0.3)),
 }
@@ -237,7 +249,7 @@ def shape_only(B, N, Hq, Hkv, d, causal, name, scale=None) -> AttnProblem:
 def make_config(name: str) -> AttnProblem:
     c = dict(CONFIGS[name])
     kind = c.pop("kind")
-    options = {k: c.pop(k) for k in ("dropout", "mask") if k in c}  # entry-point options, not part of the draw
+    options = {k: c.pop(k) for k in ("dropout", "mask", "window") if k in c}  # entry-point options, not part of the draw
     if kind == "dense":
         prob = make_dense(name=name, **c)
     elif kind == "cross":
