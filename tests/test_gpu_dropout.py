@@ -105,3 +105,57 @@ def test_ragged_batches_with_dropout(d, Hq, Hkv, causal):
     pu.judge(f"ragged dropout d{d} H{Hq}/{Hkv} causal={causal}",
              {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
              dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, standard=False, d=d)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["dropout_d128_n8k_causal", "dropout_gqa_ragged"])
+def test_full_size_dropout_workloads_sampled_units(name):
+    """The benchmark shapes with dropout (p = 0.1): whole (sequence, head) units against the oracle
+    and the 16-bit reference with the same keep mask; the ragged one on its shortest and longest
+    sequence (grouped heads: dK, dV of a key/value head over its four query heads)."""
+    prob = inputs.make_config(name)
+    p_drop, seed = prob.meta["dropout"]
+    thr = orc.dropout_threshold(p_drop)
+    rp = 256.0 / (256.0 - thr)
+    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    G = prob.Hq // prob.Hkv
+    if prob.varlen:
+        cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
+        mx = int(prob.seqlens.max())
+        O, L = binding.fa_varlen_dropout_fwd(Q, K, V, cu, mx, prob.scale, True, p_drop, seed)
+        dQ, dK, dV = binding.fa_varlen_dropout_bwd(Q, K, V, O, dO, L, cu, mx, prob.scale, True, p_drop, seed)
+        units = [(s, s % prob.Hkv, int(prob.cu_seqlens[s]), int(prob.cu_seqlens[s + 1]))
+                 for s in sorted({int(np.argmin(prob.seqlens)), int(np.argmax(prob.seqlens))})]
+    else:
+        O, L = binding.fa_dropout_fwd(Q, K, V, prob.scale, True, p_drop, seed)
+        dQ, dK, dV = binding.fa_dropout_bwd(Q, K, V, O, dO, L, prob.scale, True, p_drop, seed)
+        units = [(0, 0, 0, prob.N), (prob.B - 1, prob.Hkv - 1, 0, prob.N)]
+    torch.cuda.synchronize()
+    for t in (O, L, dQ, dK, dV):
+        assert torch.isfinite(t.float()).all()
+    for (s, g, a, e) in units:
+        n = e - a
+        sel = (slice(a, e),) if prob.varlen else (s,)
+        k, v = orc.widen_bf16(prob.K[sel][:, g]), orc.widen_bf16(prob.V[sel][:, g])
+        exp = {"O": [], "LSE": [], "dQ": [], "dK": np.zeros_like(k), "dV": np.zeros_like(v)}
+        ref = {"O": [], "LSE": [], "dQ": [], "dK": np.zeros_like(k), "dV": np.zeros_like(v)}
+        for h in range(g * G, (g + 1) * G):
+            keep = orc.dropout_keep(seed, s * prob.Hq + h, n, n, thr)
+            q, do = orc.widen_bf16(prob.Q[sel][:, h]), orc.widen_bf16(prob.dO[sel][:, h])
+            o, lse, _ = orc.head_forward_dropout(q, k, v, prob.scale, True, keep, thr)
+            dq, dk, dv = orc.head_backward_dropout(q, k, v, do, prob.scale, True, keep, thr)
+            r = pu.reference_head(Q[sel][:, h], K[sel][:, g], V[sel][:, g], dO[sel][:, h], prob.scale, True,
+                                  keep=torch.from_numpy(keep).cuda(), rp=rp)
+            for nm, x in (("O", o), ("LSE", lse), ("dQ", dq)):
+                exp[nm].append(x)
+                ref[nm].append(r[nm])
+            exp["dK"] += dk
+            exp["dV"] += dv
+            ref["dK"] += r["dK"]
+            ref["dV"] += r["dV"]
+        hs = slice(g * G, (g + 1) * G)
+        got = {"O": pu.to_f64(O[sel][:, hs]).transpose(1, 0, 2), "LSE": pu.to_f64(L[hs, a:e] if prob.varlen else L[s, hs]),
+               "dQ": pu.to_f64(dQ[sel][:, hs]).transpose(1, 0, 2), "dK": pu.to_f64(dK[sel][:, g]), "dV": pu.to_f64(dV[sel][:, g])}
+        for nm in ("O", "LSE", "dQ"):
+            exp[nm], ref[nm] = np.stack(exp[nm]), np.stack(ref[nm])
+        pu.judge(f"{name} unit (s={s}, g={g}, n={n})", got, exp, ref, standard=False, d=prob.d)
