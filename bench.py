@@ -138,6 +138,13 @@ class Runner:
             elif prob.meta.get("window"):
                 self.kind = "local"
                 self.win = prob.meta["window"]
+            elif prob.meta.get("block_pattern"):
+                from paper_2307_08691_amd import inputs
+                bp = prob.meta["block_pattern"]
+                self.kind = "blocksparse"
+                self.block = bp["block"]
+                self.BM = torch.from_numpy(inputs.block_pattern(bp["seed"], 1, Hq, N, prob.keys, bp["block"], bp["density"],
+                                                                prob.causal).astype(np.uint8)).cuda()
             elif prob.Nk or prob.dtype == "f16":
                 self.kind = "cross"
             else:
@@ -148,7 +155,8 @@ class Runner:
     def entry_points(self):
         return {"dense": "fa_fwd + fa_bwd", "cross": "fa_cross_fwd + fa_cross_bwd" + ("_f16" if self.prob.dtype == "f16" else ""),
                 "varlen": "fa_varlen_fwd + fa_varlen_bwd", "dropout": "fa_dropout_fwd + fa_dropout_bwd",
-                "varlen_dropout": "fa_varlen_dropout_fwd + fa_varlen_dropout_bwd", "mask": "fa_mask_fwd + fa_mask_bwd", "local": "fa_local_fwd + fa_local_bwd"}[self.kind]
+                "varlen_dropout": "fa_varlen_dropout_fwd + fa_varlen_dropout_bwd", "mask": "fa_mask_fwd + fa_mask_bwd", "local": "fa_local_fwd + fa_local_bwd",
+                "blocksparse": "fa_blocksparse_fwd + fa_blocksparse_bwd"}[self.kind]
 
     def fwd(self):
         b, k = self.b, self.kind
@@ -165,6 +173,8 @@ class Runner:
             b.fa_varlen_dropout_fwd(*a, self.cu, self.mx, self.sc, self.ca, *self.drop, O=self.O, LSE=self.LSE)
         elif k == "local":
             b.fa_local_fwd(*a, self.sc, *self.win, O=self.O, LSE=self.LSE)
+        elif k == "blocksparse":
+            b.fa_blocksparse_fwd(*a, self.BM, self.block, self.sc, self.ca, O=self.O, LSE=self.LSE)
         else:
             b.fa_mask_fwd(*a, self.M, self.sc, self.ca, O=self.O, LSE=self.LSE)
 
@@ -184,6 +194,8 @@ class Runner:
             b.fa_varlen_dropout_bwd(*a, self.O, self.dO, self.LSE, self.cu, self.mx, self.sc, self.ca, *self.drop, **out)
         elif k == "local":
             b.fa_local_bwd(*a, self.O, self.dO, self.LSE, self.sc, *self.win, **out)
+        elif k == "blocksparse":
+            b.fa_blocksparse_bwd(*a, self.BM, self.block, self.O, self.dO, self.LSE, self.sc, self.ca, **out)
         else:
             b.fa_mask_bwd(*a, self.M, self.O, self.dO, self.LSE, self.sc, self.ca, **out)
 
@@ -436,7 +448,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": prob.name, **shape, "Hq": prob.Hq, "Hkv": prob.Hkv, "d": prob.d, "causal": prob.causal,
                    "scale": prob.scale, "fwd_flops": fwd_fl, "bwd_flops": bwd_fl, "entry_points": r.entry_points(),
-                   **{k: v for k, v in prob.meta.items() if k in ("dropout", "mask", "window", "qk_mult")}},
+                   **{k: v for k, v in prob.meta.items() if k in ("dropout", "mask", "window", "block_pattern", "qk_mult")}},
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
         "kernel_sources": kernel_sources_id(),
         "fwd": {"ms": fwd_ms, "tflops": fwd_fl / fwd_ms / 1e9, "frac_of_peak": fwd_fl / fwd_ms / 1e9 / PEAK_BF16_TFLOPS},

@@ -292,6 +292,32 @@ int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, con
                  int window_left, int window_right, void* stream);
 
 /*
+ * Block-sparse attention (section 5 names it beside local attention). Reading: `block_mask` holds
+ * one byte per block of `block` x `block` entries of S, row blocks counted from query 0 and key
+ * blocks from key 0; an entry of S takes part in the softmax iff its block's byte is non-zero
+ * (and, if `causal`, the causal rule with the alignment of fa_cross_fwd keeps it). A row left
+ * without entries gets O = 0, LSE = -inf and contributes to no gradient. `block_mask` is a DEVICE
+ * array of bytes [Bm, Hm, ceil(Nq/block), ceil(Nk/block)], rows dense, addressed through the two
+ * strides in bytes (0 shares the pattern over sequences or heads); it is read, never written.
+ * `block` is a power of two, at least 64 (FA_ERR_SHAPE otherwise). Wavefronts skip the blocks
+ * that the pattern removes from their rows (or keys); a workgroup still brings in every key
+ * block (row tile) inside its causal range, so time falls with the density but not to zero.
+ * Otherwise as fa_cross_fwd / fa_cross_bwd (layouts, workspace, grouped heads, errors).
+ * bfloat16, d in {64, 128}; at most 262144 keys and ceil(Nq/32) * (Hq/Hkv) <= 4096
+ * (FA_ERR_UNSUPPORTED beyond).
+ */
+int fa_blocksparse_fwd(const void* Q, const void* K, const void* V, const void* block_mask,
+                       void* O, float* LSE, int B, int Hq, int Hkv, int Nq, int Nk, int d,
+                       float scale, int causal, int block,
+                       long long mask_batch_stride, long long mask_head_stride, void* stream);
+int fa_blocksparse_bwd(const void* Q, const void* K, const void* V, const void* block_mask,
+                       const void* O, const void* dO, const float* LSE,
+                       void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                       int block, long long mask_batch_stride, long long mask_head_stride,
+                       void* stream);
+
+/*
  * Two lengths in the packed ragged layout: sequence s owns query rows
  * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
  * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].

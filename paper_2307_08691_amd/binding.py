@@ -58,6 +58,9 @@ SIGNATURES = {
                     [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_local_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_blocksparse_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
+    "fa_blocksparse_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int] +
+                           [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
@@ -215,6 +218,16 @@ def fa_local_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right,
 def fa_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0) -> int:
     return load().fa_local_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right,
                                stream)
+
+
+def fa_blocksparse_fwd_raw(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block, bs, hs, stream=0) -> int:
+    return load().fa_blocksparse_fwd(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), block, bs, hs, stream)
+
+
+def fa_blocksparse_bwd_raw(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, block,
+                           bs, hs, stream=0) -> int:
+    return load().fa_blocksparse_bwd(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                                     int(causal), block, bs, hs, stream)
 
 
 def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
@@ -561,6 +574,42 @@ def fa_local_bwd(Q, K, V, O, dO, LSE, scale: float, window_left: int, window_rig
     _check(fa_local_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                             _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, window_left, window_right,
                             _stream()))
+    return dQ, dK, dV
+
+
+def _block_mask_strides(BM, x, block):
+    import torch
+    nrb, ncb = -(-x.Nq // block), -(-x.Nk // block)
+    if BM.dtype != torch.uint8 or BM.device != x.dev or not BM.is_contiguous():
+        raise ValueError("block_mask must be a contiguous uint8 tensor on the device of Q")
+    if BM.dim() != 4 or BM.shape[0] not in (1, x.B) or BM.shape[1] not in (1, x.Hq) or tuple(BM.shape[2:]) != (nrb, ncb):
+        raise ValueError(f"block_mask must be [1 or B, 1 or Hq, {nrb}, {ncb}]")
+    return (BM.stride(0) if BM.shape[0] > 1 else 0, BM.stride(1) if BM.shape[1] > 1 else 0)
+
+
+def fa_blocksparse_fwd(Q, K, V, block_mask, block: int, scale: float, causal: bool, O=None, LSE=None):
+    """Block-sparse forward: block_mask uint8 [1 or B, 1 or Hq, ceil(Nq/block), ceil(Nk/block)], non-zero = the
+    block of `block` x `block` scores takes part. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
+    import torch
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    bs, hs = _block_mask_strides(block_mask, x, block)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_blocksparse_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(block_mask), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq,
+                                  x.Nk, x.d, scale, causal, block, bs, hs, _stream()))
+    return O, LSE
+
+
+def fa_blocksparse_bwd(Q, K, V, block_mask, block: int, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None,
+                       workspace=None):
+    """Backward of fa_blocksparse_fwd for the same pattern."""
+    import torch
+    x = _dense(Q, K, V, (torch.bfloat16,))
+    bs, hs = _block_mask_strides(block_mask, x, block)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
+    _check(fa_blocksparse_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(block_mask), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ),
+                                  _ptr(dK), _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
+                                  causal, block, bs, hs, _stream()))
     return dQ, dK, dV
 
 

@@ -69,6 +69,9 @@ fa::Problem make_problem(const int32_t* cu, int nseq, int N, int Nk, int Hq, int
   p.mask = nullptr;
   p.mask_bs = p.mask_hs = p.mask_rs = 0;
   p.win_left = p.win_right = -1;
+  p.bmask = nullptr;
+  p.bmask_bs = p.bmask_hs = 0;
+  p.bmask_cols = p.bmask_log2 = 0;
   p.cu_seqlens = cu;
   p.cu_seqlens_k = cu_k;
   p.nseq = nseq;
@@ -125,6 +128,9 @@ struct Options {
   long long mask_bs = 0, mask_hs = 0, mask_rs = 0;
   bool window = false;              // sliding window (win_left, win_right); a negative bound is no bound
   int win_left = -1, win_right = -1;
+  const void* bmask = nullptr;      // block-sparse pattern (with window = true): bytes, two strides, block size
+  long long bmask_bs = 0, bmask_hs = 0;
+  int block = 0;
 };
 
 Options half_precision(int f16) {
@@ -157,10 +163,28 @@ Options with_window(int left, int right) {
   return o;
 }
 
+// block-sparse pattern: block a power of two >= 64; the wavefronts' activity bitmaps hold
+// kPatternWords * 64 key blocks (forward, dQ) and row tiles (dK/dV: tiles of 32 rows, one per
+// query head of a group)
+int set_block_pattern(fa::Problem& p, const Options& o) {
+  if (!o.bmask) return FA_ERR_NULL;
+  if (o.block < 64 || (o.block & (o.block - 1)) || o.bmask_bs < 0 || o.bmask_hs < 0) return FA_ERR_SHAPE;
+  const long words = 64L * fa::kPatternWords;
+  if (((long)p.Nk + 63) / 64 > words || (((long)p.N + 31) / 32) * p.G > words) return FA_ERR_UNSUPPORTED;
+  p.bmask = (const uint8_t*)o.bmask;
+  p.bmask_bs = (long)o.bmask_bs;
+  p.bmask_hs = (long)o.bmask_hs;
+  p.bmask_cols = (p.Nk + o.block - 1) / o.block;
+  p.bmask_log2 = __builtin_ctz((unsigned)o.block);
+  return FA_OK;
+}
+
 int apply_options(fa::Problem& p, const Options& o) {
   if (o.window) {
     p.win_left = o.win_left;
     p.win_right = o.win_right;
+    if (o.block)
+      if (int e = set_block_pattern(p, o)) return e;
   }
   if (o.dropout)
     if (int e = set_dropout(p, o.p_drop, o.seed)) return e;
@@ -368,10 +392,11 @@ static int check_cross(int B, int Nq, int Nk, int causal) {
 
 // Dense entry points with two lengths: the plain ones, half precision, dropout and mask differ
 // only in the options.
+// (`rule`: the causal rule is in force although `causal` is 0, because a window instantiation applies it)
 static int cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
-                     int Nk, int d, float scale, int causal, void* stream, const Options& opt) {
+                     int Nk, int d, float scale, int causal, void* stream, const Options& opt, int rule = 0) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_cross(B, Nq, Nk, causal || rule)) return e;
   if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask || opt.window))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
   return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, 0, nullptr,
@@ -380,9 +405,9 @@ static int cross_fwd(const void* Q, const void* K, const void* V, void* O, float
 
 static int cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
                      void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
-                     int Nq, int Nk, int d, float scale, int causal, void* stream, const Options& opt) {
+                     int Nq, int Nk, int d, float scale, int causal, void* stream, const Options& opt, int rule = 0) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
-  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_cross(B, Nq, Nk, causal || rule)) return e;
   if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.mask || opt.window))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
@@ -479,6 +504,32 @@ int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, con
     if (int e = window_route(Nq, Nk, window_left, window_right, causal)) return e;
   return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
                    stream, window_left < 0 && window_right < 0 ? half_precision(0) : with_window(window_left, window_right));
+}
+
+static Options with_block_pattern(const void* block_mask, int block, long long bs, long long hs, int causal) {
+  Options o = with_window(-1, causal ? 0 : -1);  // the causal rule is the window (none, 0)
+  o.bmask = block_mask;
+  o.bmask_bs = bs;
+  o.bmask_hs = hs;
+  o.block = block ? block : -1;  // (0 would read as "no pattern")
+  return o;
+}
+
+int fa_blocksparse_fwd(const void* Q, const void* K, const void* V, const void* block_mask, void* O, float* LSE, int B,
+                       int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, int block,
+                       long long mask_batch_stride, long long mask_head_stride, void* stream) {
+  if (!block_mask) return FA_ERR_NULL;
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, 0, stream,
+                   with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), causal);
+}
+
+int fa_blocksparse_bwd(const void* Q, const void* K, const void* V, const void* block_mask, const void* O,
+                       const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                       size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                       int block, long long mask_batch_stride, long long mask_head_stride, void* stream) {
+  if (!block_mask) return FA_ERR_NULL;
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, 0, stream,
+                   with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), causal);
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,

@@ -128,7 +128,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one ring slot = Q_i | dO_i
   constexpr int LS_OFF = QDO_OFF + RING * BUFB;       // [slot][row] floats
   constexpr int DV_OFF = LS_OFF + RING * BR * 4;
-  constexpr int SMEM = DV_OFF + RING * BR * 4;
+  constexpr int BITS_OFF = DV_OFF + RING * BR * 4;  // LOCAL: one activity bitmap per wavefront (over the tiles it visits)
+  constexpr int SMEM = BITS_OFF + (LOCAL ? 8 * 8 * kPatternWords : 0);
   static_assert(VT_OFF + BC * ROWB <= 65536 && BUFB <= 32768, "immediate offsets must fit 16 bits");
   static_assert(WIDE || 4 * DT * 16 * 64 * 4 <= RING * BUFB, "the final reduction reuses the ring");
   static_assert(SMEM <= 160 * 1024, "LDS of one compute unit");
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       // L in the exponent's base; rows past the end get L = +inf so that P = exp2(. - inf) = 0.
       // D is stored negated: it is the initial value of the dP accumulator (line 14).
       // (mask: a row left without keys has L = -inf and, like a row past the end, P = 0)
-      *(float*)(smem + LS_OFF + o) = stat_ok && !(MASK && lraw == -INFINITY) ? lraw * kLog2e : INFINITY;
+      *(float*)(smem + LS_OFF + o) = stat_ok && !((MASK || LOCAL) && lraw == -INFINITY) ? lraw * kLog2e : INFINITY;
       *(float*)(smem + DV_OFF + o) = stat_ok ? -draw : 0.f;
     }
   };
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         const long si_ = stat_base + (long)c.hq * p.lse_head_stride + (ok ? row : n - 1);
         const float l = a.LSE[si_], dd = a.Dvec[si_];
         const int o = (c.slot * BR + tid - t * BR) * 4;
-        *(float*)(smem + LS_OFF + o) = ok && !(MASK && l == -INFINITY) ? l * kLog2e : INFINITY;
+        *(float*)(smem + LS_OFF + o) = ok && !((MASK || LOCAL) && l == -INFINITY) ? l * kLog2e : INFINITY;
         *(float*)(smem + DV_OFF + o) = ok ? -dd : 0.f;
       }
       advance(c, 1);
@@ -330,7 +331,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   }
   constexpr int NM = QTW * 2 * KS;   // S and dP: 16 MFMAs
   constexpr int NM2 = QTW * 4 * DT;  // dV and dK: 16 MFMAs
-  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : (KREG && D == 128 ? 3 : kDkdvAhead);
+  // (mask, window / pattern: a shorter prefetch, their bookkeeping needs the registers)
+  constexpr int AH = MASK ? (D == 128 ? 1 : 2) : LOCAL && D == 128 ? 1 : (KREG && D == 128 ? 3 : kDkdvAhead);
   // MASK: this lane's entries of M for the wavefront's next tile (raw bfloat16 bits), row by row
   uint32_t mraw[MASK ? QTW * 16 : 1];
   auto issue_mask_loads = [&](const Cursor& c) {
@@ -555,18 +557,86 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       if (stop < t_stop) t_stop = (int)stop;
     }
     if (t_stop < skip) t_stop = skip;
+    if constexpr (LOCAL) {
+      // Window and block-sparse pattern: tile by tile. Whether this wavefront has anything to do on
+      // tile t (row tile i_first + t / G of query head g G + t % G; its rows lie in one row block of
+      // the pattern, its 32 keys in one key block) is one bit of the wavefront's bitmap, gathered
+      // here for every t.
+      const bool sparse = p.bmask != nullptr;
+      unsigned long long* bits = (unsigned long long*)(smem + BITS_OFF) + v * kPatternWords;
+      if (sparse) {
+        const uint8_t* bm0 = p.bmask + s * p.bmask_bs + (long)((j0 + 32 * kgi < nk ? j0 + 32 * kgi : nk - 1) >> p.bmask_log2);
+        for (int q = 0; q * 64 < T; ++q) {
+          const int tt = q * 64 + lane;
+          const int it = i_first + tt / p.G, hq = g * p.G + tt % p.G;
+          const bool on = tt < T && bm0[hq * p.bmask_hs + (long)((it * BR) >> p.bmask_log2) * p.bmask_cols] != 0;
+          const unsigned long long m = __builtin_amdgcn_ballot_w64(on);
+          if (lane == 0) bits[q] = m;
+        }
+      }
+      int word_q = -1;
+      unsigned long long word = 0;
+      auto active = [&](int t) {
+        if (t < skip || t >= t_stop) return false;
+        if (!sparse) return true;
+        if ((t >> 6) != word_q) {
+          word_q = t >> 6;
+          word = bits[word_q];
+          word = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(word >> 32)) << 32) |
+                 (unsigned)__builtin_amdgcn_readfirstlane((unsigned)word);
+        }
+        return ((word >> (t & 63)) & 1) != 0;
+      };
+      // One loop body for every tile, the steady-state stream of the plain kernel (M' of tile t - 1
+      // running into M of tile t) whenever one of the two tiles is active. At the start of a run of
+      // active tiles its M' half multiplies by zero operands (P = dS = 0 stand for the inactive
+      // tile before), at the end of a run its M half computes scores nobody uses: half a tile of
+      // matrix work per end of a run, the price of keeping a single instruction stream (three
+      // streams side by side in one loop spill hundreds of registers). Between runs the wavefront
+      // only keeps up with the copies and the barriers.
+#pragma unroll
+      for (int i = 0; i < AH; ++i) pre[i] = (bf16x8){0};
+#pragma unroll
+      for (int tq = 0; tq < QTW; ++tq) Pf[tq][0] = Pf[tq][1] = dSf[tq][0] = dSf[tq][1] = (bf16x8){0};
+      bool was = false;  // tile t - 1 was active
+      for (int t = 0; t < T; ++t) {
+        const bool now = active(t);
+        if (was || now) fused_stream();
+        end_matrix_phase();
+        if (grp == 0 && t + 2 < T) {
+          issue_loads(ld);
+          pending = ld.slot;
+          advance(ld, 1);
+        }
+        if (now) {
+          phase_v(cur);
+          mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
+        } else if (was) {
+#pragma unroll
+          for (int tq = 0; tq < QTW; ++tq) Pf[tq][0] = Pf[tq][1] = dSf[tq][0] = dSf[tq][1] = (bf16x8){0};
+        }
+        lds_barrier();
+        prev = cur;
+        advance(cur, 1);
+        was = now;
+      }
+      if (was) {
+        __builtin_amdgcn_s_setprio(2);
+        mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
+      }
+    } else {
     int t = 0;
     for (; t < skip; ++t) {
       end_matrix_phase();
       vector_phase_w(t, false);
       advance(cur, 1);
     }
-    if (t < t_stop) {
+    if (t < T) {
       __builtin_amdgcn_s_setprio(2);
       mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
       end_matrix_phase();
       vector_phase_w(t, true);
-      for (++t; t < t_stop; ++t) {
+      for (++t; t < T; ++t) {
         prev = cur;
         advance(cur, 1);
         fused_stream();
@@ -577,11 +647,6 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       __builtin_amdgcn_s_setprio(2);
       mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
     }
-    if constexpr (LOCAL) {  // trailing tiles below this wavefront's band: keep up with the copies and the barriers
-      for (; t < T; ++t) {
-        end_matrix_phase();
-        vector_phase_w(t, false);
-      }
     }
     end_matrix_phase();
     if (grp == 0) lds_barrier();  // group 1's last phase
@@ -689,7 +754,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   constexpr int MASKB = 32 * BC * 2;             // one wavefront's piece of M for one block
   constexpr int MPW = MASK ? MASKB / 1024 : 0;  // copies per wavefront per block
 
-  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0)];
+  // (LOCAL: behind the ring, one activity bitmap per wavefront, as in the forward kernel)
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0) + (LOCAL ? 8 * 8 * kPatternWords : 0)];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -731,7 +797,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   }
   const long stat = s * p.lse_seq_stride + (long)h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + rowc;
   float Lq = row < n ? a.LSE[stat] * kLog2e : INFINITY;  // rows past the end: P = 0
-  if (MASK && Lq == -INFINITY) Lq = INFINITY;            // a row that the mask left without keys: P = 0
+  if ((MASK || LOCAL) && Lq == -INFINITY) Lq = INFINITY;  // a row that the mask (the pattern) left without keys: P = 0
   const float Dq = a.Dvec[stat];
 
   f32x16 dQt[DT];
@@ -809,10 +875,35 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   // last and (window) first visible column of this lane's row
   const int lim_row = CAUSAL || wr >= 0 ? (row + off + (LOCAL ? wr : 0) < nk - 1 ? row + off + (LOCAL ? wr : 0) : nk - 1) : nk - 1;
   const int lo_row = wl >= 0 ? row + off - wl : 0;
+  // block-sparse pattern: the wavefront's bitmap over the key blocks (see the forward kernel)
+  const unsigned long long* pattern_bits = (const unsigned long long*)(smem + RING * BUFB) + w * kPatternWords;
+  const bool sparse = LOCAL && p.bmask != nullptr;
+  if (LOCAL && sparse) {
+    const int r0 = wrow0 < n ? wrow0 : n - 1;
+    const uint8_t* bm_row = p.bmask + s * p.bmask_bs + h * p.bmask_hs + (long)(r0 >> p.bmask_log2) * p.bmask_cols;
+    for (int q = 0; q * 64 < ncol_all; ++q) {
+      const int jj = q * 64 + lane;
+      const bool on = jj < ncol_all && bm_row[(jj * BC) >> p.bmask_log2] != 0;
+      const unsigned long long bits = __builtin_amdgcn_ballot_w64(on);
+      if (lane == 0) ((unsigned long long*)pattern_bits)[q] = bits;
+    }
+  }
+  int pattern_q = -1;                 // which word of the bitmap `pattern_word` holds
+  unsigned long long pattern_word = 0;
   // a block is skipped by a wavefront when every score it would produce is masked
   auto wave_sees = [&](int j) {
     if (CAUSAL) return j * BC <= wrow_last;
-    if (LOCAL) return (wr < 0 || j * BC <= wrow_last + wr) && (wl < 0 || j * BC + BC - 1 >= wrow0 + off - wl);
+    if (LOCAL) {
+      if (!((wr < 0 || j * BC <= wrow_last + wr) && (wl < 0 || j * BC + BC - 1 >= wrow0 + off - wl))) return false;
+      if (!sparse) return true;
+      if ((j >> 6) != pattern_q) {
+        pattern_q = j >> 6;
+        pattern_word = pattern_bits[pattern_q];
+        pattern_word = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(pattern_word >> 32)) << 32) |
+                       (unsigned)__builtin_amdgcn_readfirstlane((unsigned)pattern_word);
+      }
+      return ((pattern_word >> (j & 63)) & 1) != 0;
+    }
     return true;
   };
 
@@ -965,7 +1056,7 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     dim3 grid(grid_size((a.p.Nk + bck - 1) / bck, a.p.Hkv * a.p.nseq));
     bool done = false;
     if constexpr (!F16) {
-      if (a.p.win_left >= 0 || a.p.win_right >= 0) {  // sliding window
+      if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern
         hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, false, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
       } else
@@ -997,7 +1088,7 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
     bool done = false;
     if constexpr (!F16) {
-      if (a.p.win_left >= 0 || a.p.win_right >= 0) {  // sliding window
+      if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern
         hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, false, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
       } else

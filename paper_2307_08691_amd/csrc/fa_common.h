@@ -51,7 +51,16 @@ struct Problem {
   // by the LOCAL instantiations (the entry points send "no bound at all" and "win_right = 0
   // alone" to the plain and the causal kernels).
   int win_left, win_right;
+  // block-sparse pattern (nullptr: none; LOCAL instantiations only): one byte per block of
+  // 2^bmask_log2 x 2^bmask_log2 entries of S (a power of two, at least 64), row blocks counted
+  // from query 0 and key blocks from key 0; byte (s, h, rb, cb) at
+  // bmask[s * bmask_bs + h * bmask_hs + rb * bmask_cols + cb], 0 = the block is removed;
+  // a stride of 0 shares the pattern over sequences or heads
+  const uint8_t* bmask;
+  long bmask_bs, bmask_hs;
+  int bmask_cols, bmask_log2;
 };
+constexpr int kPatternWords = 64;  // 64-bit words of a wavefront's activity bitmap in LDS: 4096 blocks or tiles
 
 struct SeqInfo {
   long tok0;   // first query row of the sequence in the packed [tokens, H, d] view

@@ -106,7 +106,9 @@ __global__ __launch_bounds__(512)
   constexpr int MASKB = 32 * BC * 2;             // one wavefront's piece of M for one block
   constexpr int MPW = MASK ? MASKB / 1024 : 0;  // copies per wavefront per block
 
-  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0)];
+  // (LOCAL: behind the ring, one bitmap of kPatternWords 64-bit words per wavefront: which key blocks
+  // the block-sparse pattern leaves to its rows)
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0) + (LOCAL ? 8 * 8 * kPatternWords : 0)];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -244,10 +246,38 @@ __global__ __launch_bounds__(512)
   // last and (window) first visible column of this lane's row
   const int lim_row = CAUSAL || wr >= 0 ? (row + off + (LOCAL ? wr : 0) < nk - 1 ? row + off + (LOCAL ? wr : 0) : nk - 1) : nk - 1;
   const int lo_row = wl >= 0 ? row + off - wl : 0;
+  // Block-sparse pattern: the wavefront's 32 rows lie in one row block of the pattern (blocks are
+  // at least 64 rows and the wavefront starts at a multiple of 32), so whether it has anything to
+  // do in key block j is one bit, gathered here for every j (one byte per lane and ballot) into
+  // the wavefront's bitmap. It is read back a word at a time.
+  const unsigned long long* pattern_bits = (const unsigned long long*)(smem + RING * BUFB) + w * kPatternWords;
+  const bool sparse = LOCAL && p.bmask != nullptr;
+  if (LOCAL && sparse) {
+    const int r0 = prow0 < n ? prow0 : n - 1;
+    const uint8_t* bm_row = p.bmask + s * p.bmask_bs + bc.head * p.bmask_hs + (long)(r0 >> p.bmask_log2) * p.bmask_cols;
+    for (int q = 0; q * 64 < ncol_all; ++q) {
+      const int jj = q * 64 + lane;
+      const bool on = jj < ncol_all && bm_row[(jj * BC) >> p.bmask_log2] != 0;
+      const unsigned long long bits = __builtin_amdgcn_ballot_w64(on);
+      if (lane == 0) ((unsigned long long*)pattern_bits)[q] = bits;
+    }
+  }
+  int pattern_q = -1;                 // which word of the bitmap `pattern_word` holds
+  unsigned long long pattern_word = 0;
   // a block is skipped by a wavefront when every score it would produce is masked
   auto wave_sees = [&](int j) {
     if (CAUSAL) return j * BC <= wrow_last;
-    if (LOCAL) return (wr < 0 || j * BC <= wrow_last + wr) && (wl < 0 || j * BC + BC - 1 >= wrow0 + off - wl);
+    if (LOCAL) {
+      if (!((wr < 0 || j * BC <= wrow_last + wr) && (wl < 0 || j * BC + BC - 1 >= wrow0 + off - wl))) return false;
+      if (!sparse) return true;
+      if ((j >> 6) != pattern_q) {
+        pattern_q = j >> 6;
+        pattern_word = pattern_bits[pattern_q];
+        pattern_word = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(pattern_word >> 32)) << 32) |
+                       (unsigned)__builtin_amdgcn_readfirstlane((unsigned)pattern_word);
+      }
+      return ((pattern_word >> (j & 63)) & 1) != 0;
+    }
     return true;
   };
 
@@ -859,7 +889,7 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     }
   }
   if constexpr (!F16) {
-    if (a.p.win_left >= 0 || a.p.win_right >= 0) {  // sliding window (the entry point keeps everything else away from it)
+    if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern (the entry points keep everything else away from them)
       hipLaunchKernelGGL((fwd_kernel<D, false, false, false, false, false, false, true>), grid, block, 0, st, a);
       return hipGetLastError();
     }

@@ -26,6 +26,7 @@ __all__ = [
     "make_cross",
     "make_varlen",
     "shape_only",
+    "block_pattern",
     "CONFIGS",
     "make_config",
 ]
@@ -114,6 +115,20 @@ class AttnProblem:
             lo = np.maximum(0, pos - left) if left >= 0 else np.zeros_like(pos)
             hi = np.minimum(nk - 1, pos + right) if right >= 0 else np.full_like(pos, nk - 1)
             return 4.0 * self.B * self.Hq * self.d * float(np.sum(hi - lo + 1))
+        if self.meta.get("block_pattern") and not self.varlen:
+            # block-sparse: 4*d per (query, key) pair of the kept blocks that the causal rule keeps too
+            bp = self.meta["block_pattern"]
+            bm = block_pattern(bp["seed"], 1, self.Hq, self.N, self.keys, bp["block"], bp["density"], self.causal)
+            blk, nk = bp["block"], self.keys
+            rows = np.arange(self.N, dtype=np.int64)
+            pairs = 0.0
+            for cb in range(bm.shape[3]):
+                c0, c1 = cb * blk, min(nk, (cb + 1) * blk) - 1
+                hi = np.minimum(c1, rows + (nk - self.N)) if self.causal else np.full_like(rows, c1)
+                per_row = np.maximum(0, hi - c0 + 1)                       # visible keys of this key block per row
+                per_rb = np.add.reduceat(per_row, np.arange(0, self.N, blk))  # ... per row block
+                pairs += float(np.sum(bm[0, :, :, cb] * per_rb[None, :]))
+            return 4.0 * self.B * self.d * pairs
         if self.Nk and not self.varlen:
             pairs = float(self.N) * self.Nk - (0.5 * float(self.N) ** 2 if self.causal else 0.0)
             return 4.0 * self.B * self.Hq * self.d * pairs
@@ -217,6 +232,11 @@ CONFIGS = {
     "local_d128_n8k_w1024": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1022, window=(1023, 0)),
     "local_d128_n16k_w2048": dict(kind="dense", B=1, N=16384, Hq=16, Hkv=16, d=128, causal=False, seed=1023, window=(2047, 0)),
     "local_d64_n8k_w512x2": dict(kind="dense", B=2, N=8192, Hq=32, Hkv=32, d=64, causal=False, seed=1024, window=(512, 512)),
+    # block-sparse: blocks of 128 x 128, half of them kept (one pattern per head), under the causal rule
+    "blocksparse_d128_n8k_causal_half": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1025,
+                                             block_pattern=dict(seed=17600, block=128, density=0.5)),
+    "blocksparse_d128_n8k_causal_eighth": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1026,
+                                               block_pattern=dict(seed=17601, block=128, density=0.125)),
     "mask_d64_n8k_full": dict(kind="dense", B=2, N=8192, Hq=32, Hkv=32, d=64, causal=False, seed=1021,
                               mask=dict(seed=9802, removed=0.3)),
 }
@@ -231,6 +251,19 @@ for _d, _H in ((64, 32), (128, 16)):
         for _c in (False, True):
             CONFIGS[sweep_name(_d, _N, _c)] = dict(kind="dense", B=16384 // _N, N=_N, Hq=_H, Hkv=_H,
                                                    d=_d, causal=_c, seed=1002)
+
+
+def block_pattern(seed: int, Bm: int, Hm: int, nq: int, nk: int, block: int, density: float, causal: bool) -> np.ndarray:
+    """A seeded block-sparse pattern [Bm, Hm, ceil(nq/block), ceil(nk/block)] of booleans: every block
+    kept with probability `density`; the first key block and (causal) the diagonal block of every row
+    block always, so that no row is left without keys."""
+    g = np.random.default_rng(seed)
+    bm = g.random((Bm, Hm, -(-nq // block), -(-nk // block))) < density
+    bm[..., 0] = True
+    if causal:
+        for rb in range(bm.shape[2]):
+            bm[:, :, rb, min((rb * block + nk - nq) // block, bm.shape[3] - 1)] = True
+    return bm
 
 
 def ragged_lengths(seed: int, nseq: int, lo: int, hi: int) -> np.ndarray:
@@ -249,7 +282,7 @@ def shape_only(B, N, Hq, Hkv, d, causal, name, scale=None) -> AttnProblem:
 def make_config(name: str) -> AttnProblem:
     c = dict(CONFIGS[name])
     kind = c.pop("kind")
-    options = {k: c.pop(k) for k in ("dropout", "mask", "window") if k in c}  # entry-point options, not part of the draw
+    options = {k: c.pop(k) for k in ("dropout", "mask", "window", "block_pattern") if k in c}  # entry-point options, not part of the draw
     if kind == "dense":
         prob = make_dense(name=name, **c)
     elif kind == "cross":
