@@ -75,6 +75,13 @@ Readings taken where the text is silent or inconsistent:
         its block is set (and the causal rule, if asked for, keeps it).
     A row left without entries has P = 0, O = 0, L = -inf, as with the elementwise mask.
 
+  * FP8 operands (section 5 names FP8 as a direction; no algorithm is given). Reading: Q, K, V
+    arrive quantised to OCP FP8 E4M3 (1 sign, 4 exponent, 3 significand bits, bias 7, largest
+    finite value 448, no infinities) with one float scale per tensor, x = descale * x8; the
+    computation is the standard definition on those dequantised values. What an
+    implementation does with P on chip (the HIP path rounds it to E4M3 as an operand of the
+    second product) is its own error, bounded in the tests, and no part of the definition.
+
 Layouts: dense Q,O,dO,dQ [B, Nq, Hq, d]; K,V,dK,dV [B, Nk, Hkv, d]; L [B, Hq, Nq]
 (Nq = Nk = N for self-attention).
 Packed: Q.. [T, Hq, d]; K.. [T, Hkv, d]; L [Hq, T].
@@ -92,6 +99,23 @@ def widen_bf16(bits):
 def widen_f16(bits):
     """IEEE half precision bit patterns (uint16) -> float64, exactly."""
     return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def widen_e4m3(bits):
+    """OCP FP8 E4M3 bit patterns (uint8) -> float64, exactly: S EEEE MMM, bias 7;
+    E = 0: subnormal M/8 * 2^-6; E = 15, M = 7: NaN; every other pattern a finite number."""
+    b = np.ascontiguousarray(bits, dtype=np.uint8).astype(np.int64)
+    sign = np.where(b & 0x80, -1.0, 1.0)
+    e, m = (b >> 3) & 0xF, b & 0x7
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    return sign * np.where((e == 15) & (m == 7), np.nan, val)
+
+
+def attention_forward_fp8(Q8, K8, V8, descale_q, descale_k, descale_v, scale, causal):
+    """Dense forward on E4M3 inputs with per-tensor scales: the definition on the dequantised
+    values. Q8 [B,Nq,Hq,d], K8, V8 [B,Nk,Hkv,d] uint8. Returns O [B,Nq,Hq,d], L [B,Hq,Nq]."""
+    return attention_forward(descale_q * widen_e4m3(Q8), descale_k * widen_e4m3(K8), descale_v * widen_e4m3(V8),
+                             scale, causal)
 
 
 def scores(q, k, scale, causal):

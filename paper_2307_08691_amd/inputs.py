@@ -20,6 +20,8 @@ import numpy as np
 __all__ = [
     "f32_to_bf16_bits",
     "f32_to_f16_bits",
+    "f32_to_e4m3_bits",
+    "make_fp8",
     "bf16_bits_to_f32",
     "AttnProblem",
     "make_dense",
@@ -47,6 +49,27 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
 def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
     """Round float32 to IEEE half precision (RNE) and return the uint16 bit patterns."""
     return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to OCP FP8 E4M3 (round to nearest, ties to even; magnitudes beyond 448 saturate
+    to 448) and return the uint8 bit patterns. Pure bit arithmetic: the spacing of E4M3 numbers at
+    |x| in [2^e, 2^(e+1)) is 2^(e-3), and 2^-9 below 2^-6 (subnormals)."""
+    x = np.ascontiguousarray(x, dtype=np.float32).astype(np.float64)
+    a = np.minimum(np.abs(x), 448.0)
+    e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.maximum(e, -6.0)
+    step = np.exp2(e - 3)
+    q = np.rint(a / step) * step  # numpy rounds halves to even
+    q = np.minimum(q, 448.0)
+    # encode
+    eq = np.floor(np.log2(np.where(q > 0, q, 1.0)))
+    sub = q < 2.0 ** -6
+    expo = np.where(sub, 0, eq + 7).astype(np.int64)
+    mant = np.where(sub, np.rint(q / 2.0 ** -9), np.rint((q / np.exp2(eq) - 1.0) * 8.0)).astype(np.int64)
+    out = ((expo << 3) | mant).astype(np.uint8)
+    out[np.signbit(x)] |= 0x80
+    return out
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
@@ -173,6 +196,22 @@ def make_cross(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="cross", dt
     return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
                        scale=float(scale if scale is not None else d ** -0.5),
                        causal=bool(causal), B=B, N=Nq, Nk=Nk, seed=seed, dtype=dtype)
+
+
+def make_fp8(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="fp8") -> AttnProblem:
+    """FP8 forward problem: Q, K, V drawn i.i.d. N(0,1) (in that order), each divided by its scale
+    descale = max|x| / 448 (the usual amax scaling) and rounded to E4M3. The patterns are in
+    Q, K, V (uint8); meta holds the three scales."""
+    rng = np.random.default_rng(seed)
+    out, scales = [], []
+    for shape in ((B, Nq, Hq, d), (B, Nk, Hkv, d), (B, Nk, Hkv, d)):
+        x = rng.standard_normal(size=shape, dtype=np.float32)
+        ds = float(np.max(np.abs(x))) / 448.0
+        out.append(f32_to_e4m3_bits(x / np.float32(ds)))
+        scales.append(ds)
+    return AttnProblem(name=name, Q=out[0], K=out[1], V=out[2], dO=None, Hq=Hq, Hkv=Hkv, d=d,
+                       scale=float(scale if scale is not None else d ** -0.5), causal=bool(causal), B=B, N=Nq,
+                       Nk=Nk if Nk != Nq else 0, seed=seed, dtype="e4m3", meta={"descale": tuple(scales)})
 
 
 def make_varlen(seqlens, Hq, Hkv, d, causal, seed, scale=None,

@@ -1066,3 +1066,64 @@ def test_pattern_batch_wrappers_map_heads_and_shared_masks():
     for h in range(Hq):
         o, lse, _ = orc.head_forward_pattern(Q[1, :, h], K[1, :, h // 2], V[1, :, h // 2], orc.window_visible(nq, nk, 1, 0), 0.5)
         assert np.array_equal(Ol[1, :, h], o) and np.array_equal(Ll[1, h], lse)
+
+
+# ---------------------------------------------------------------------------
+# FP8 (E4M3) inputs
+# ---------------------------------------------------------------------------
+
+def test_e4m3_decoding_on_all_256_patterns_against_the_format_and_a_library():
+    bits = np.arange(256, dtype=np.uint8)
+    got = orc.widen_e4m3(bits)
+    # the format, value by value
+    for b in range(256):
+        s, e, m = b >> 7, (b >> 3) & 15, b & 7
+        if e == 15 and m == 7:
+            assert np.isnan(got[b])
+            continue
+        want = (m / 8) * 2.0 ** -6 if e == 0 else (1 + m / 8) * 2.0 ** (e - 7)
+        assert got[b] == (-want if s else want)
+    assert got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+    # a library's decoder of the same format
+    torch = pytest.importorskip("torch")
+    lib = torch.from_numpy(bits.copy()).view(torch.float8_e4m3fn).double().numpy()
+    ok = ~np.isnan(got)
+    assert np.array_equal(np.isnan(lib), ~ok) and np.array_equal(lib[ok], got[ok])
+
+
+def test_e4m3_rounding_of_the_input_recipe_against_a_library_and_by_brute_force():
+    from paper_2307_08691_amd import inputs
+    rng = np.random.default_rng(600)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 100, rng.standard_normal(20000).astype(np.float32) * 0.01,
+                        np.float32([0.0, -0.0, 448.0, 449.0, 1e6, -1e6, 2.0 ** -9, 2.0 ** -10, 0.75 * 2.0 ** -9, 17.0, 18.0, 19.0])])
+    bits = inputs.f32_to_e4m3_bits(x)
+    val = orc.widen_e4m3(bits)
+    # brute force: the nearest of the 254 finite values (ties: even significand), saturating
+    table = orc.widen_e4m3(np.arange(256, dtype=np.uint8))
+    finite = np.where(np.isnan(table), np.inf, table)
+    for xi, vi, bi in zip(x[::37], val[::37], bits[::37]):
+        d = np.abs(finite - np.clip(float(xi), -448.0, 448.0))
+        best = np.flatnonzero(d == d.min())
+        assert vi in finite[best]
+        if len(best) > 1 and xi != 0:  # a tie: the even significand wins
+            assert bi % 2 == 0
+    torch = pytest.importorskip("torch")
+    lib = torch.from_numpy(np.clip(x, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(lib & 0x7F, bits & 0x7F)  # (the sign of a rounded-away negative may differ: -0)
+    prob = inputs.make_fp8(B=1, Nq=8, Nk=8, Hq=1, Hkv=1, d=16, causal=False, seed=1)
+    for t, ds in zip((prob.Q, prob.K, prob.V), prob.meta["descale"]):
+        assert np.abs(orc.widen_e4m3(t)).max() == 448.0 and ds > 0
+
+
+def test_fp8_forward_is_the_definition_on_the_dequantised_values():
+    from paper_2307_08691_amd import inputs
+    prob = inputs.make_fp8(B=2, Nq=5, Nk=7, Hq=2, Hkv=1, d=8, causal=True, seed=2)
+    dq, dk, dv = prob.meta["descale"]
+    O, L = orc.attention_forward_fp8(prob.Q, prob.K, prob.V, dq, dk, dv, prob.scale, True)
+    for b in range(2):
+        for h in range(2):
+            q = dq * orc.widen_e4m3(prob.Q[b, :, h])
+            k = dk * orc.widen_e4m3(prob.K[b, :, 0])
+            v = dv * orc.widen_e4m3(prob.V[b, :, 0])
+            bo = brute_forward(q, k, v, prob.scale, True)
+            assert np.allclose(O[b, :, h], bo[0], atol=1e-12) and np.allclose(L[b, h], bo[1], atol=1e-12)
