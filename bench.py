@@ -305,6 +305,60 @@ def paper_grid(binding, torch, inputs, samples: int = 20, warmup: int = 5):
     return out
 
 
+def bench_fp8(args, prob, binding) -> int:
+    """Forward on FP8 (E4M3) operands: one step is one fa_fp8_fwd call; roofline against the fp8 MFMA peak."""
+    import torch
+    dq, dk, dv = prob.meta["descale"]
+    Q8, K8, V8 = (torch.from_numpy(x).cuda() for x in (prob.Q, prob.K, prob.V))
+    Vt8 = binding.fp8_key_major(V8)
+    B, Nq, Hq, d = Q8.shape
+    O = torch.empty((B, Nq, Hq, d), dtype=torch.bfloat16, device="cuda")
+    LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device="cuda")
+
+    def step():
+        binding.fa_fp8_fwd(Q8, K8, Vt8, prob.keys, prob.scale, dq, dk, dv, prob.causal, O=O, LSE=LSE)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = e0.elapsed_time(e1) / args.steps
+    fl = prob.fwd_flops()
+    ach = fl / kern_ms / 1e9
+    out = {
+        "metric": "attention fwd TFLOPs/s (fp8 e4m3 operands)", "value": fl / ms_per_step / 1e9, "unit": "TFLOPs/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
+        "config": {"workload": prob.name, "B": B, "N": Nq, "Nk": prob.keys, "Hq": Hq, "Hkv": prob.Hkv, "d": d, "causal": prob.causal,
+                   "fwd_flops": fl, "entry_points": "fa_fp8_fwd"},
+        "roofline": {"bound": "mfma", "achieved": ach, "peak": 5000.0, "unit": "TFLOP/s", "frac": ach / 5000.0, "traffic": None,
+                     "avg_kernel_ms": kern_ms, "kernel": "fwd_fp8_kernel"},
+        "kernel_sources": kernel_sources_id(),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import attention_oracle as orc
+        t0 = time.perf_counter()
+        units = 0
+        while time.perf_counter() - t0 < 10.0 and units < B * Hq:
+            b, h = divmod(units, Hq)
+            g = h // (Hq // prob.Hkv)
+            orc.head_forward(dq * orc.widen_e4m3(prob.Q[b, :, h]), dk * orc.widen_e4m3(prob.K[b, :, g]),
+                             dv * orc.widen_e4m3(prob.V[b, :, g]), prob.scale, prob.causal)
+            units += 1
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": fl / (B * Hq) * units / dt / 1e12, "unit": "TFLOPs/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"{units} of {B * Hq} (sequence, head) units of {prob.name}, forward, float64 numpy, {dt:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
 def bench_decode(args, prob, binding) -> int:
     """Few query rows against a long key/value cache: one step is one fa_splitkv_fwd call (the split
     kernel and the merge). HBM-bound: the roofline is bytes that must move over the call's duration."""
@@ -403,6 +457,8 @@ def main() -> int:
         print(json.dumps({"copy_calibration_bytes": args.copy_calibration, "copies": 5}))
         return 0
     prob = inputs.make_config(args.workload)
+    if prob.dtype == "e4m3":
+        return bench_fp8(args, prob, binding)
     if prob.Nk and not prob.varlen and prob.N * (prob.Hq // prob.Hkv) <= 256:
         return bench_decode(args, prob, binding)
 

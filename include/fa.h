@@ -318,6 +318,26 @@ int fa_blocksparse_bwd(const void* Q, const void* K, const void* V, const void* 
                        void* stream);
 
 /*
+ * Forward pass on FP8 operands (section 5, "Discussion and Future Directions", names FP8; the
+ * convention is this library's). Q8 [B, Nq, Hq, d] and K8 [B, Nk, Hkv, d] hold OCP FP8 E4M3 bytes
+ * (1 sign, 4 exponent, 3 significand bits, bias 7, largest finite value 448), token-major like the
+ * 16-bit tensors. V is handed over KEY-MAJOR: Vt8 [B, Hkv, d, vt_stride] E4M3, element (b, g, t, c)
+ * = V[b, c, g, t], `vt_stride` (bytes between rows) a multiple of 64 and at least Nk rounded up to
+ * 64, the padding past Nk holding finite values (zeros). Each tensor has one float scale,
+ * x = descale * x8, all three positive and finite (FA_ERR_SHAPE otherwise, as for a bad stride).
+ * Computes O = softmax(scale * (descale_q Q8)(descale_k K8)^T [+ causal]) (descale_v V8) with
+ * float32 accumulation and softmax statistics; the probabilities are rounded to E4M3 (times 2^8,
+ * relative to the row's running maximum) as operands of the second product, the only error beyond
+ * the bfloat16 rounding of O. O [B, Nq, Hq, d] is bfloat16, LSE [B, Hq, Nq] float32 (of the
+ * dequantised, scaled scores). d in {64, 128}; grouped heads and two lengths as fa_cross_fwd
+ * (causal needs Nq <= Nk). All pointers 16-byte aligned.
+ */
+int fa_fp8_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE,
+               int B, int Hq, int Hkv, int Nq, int Nk, int d, long long vt_stride,
+               float scale, float descale_q, float descale_k, float descale_v,
+               int causal, void* stream);
+
+/*
  * Two lengths in the packed ragged layout: sequence s owns query rows
  * cu_seqlens_q[s] .. cu_seqlens_q[s+1] of Q, O, dO, dQ [total_q, Hq, d] and key/value rows
  * cu_seqlens_k[s] .. cu_seqlens_k[s+1] of K, V, dK, dV [total_k, Hkv, d]; LSE is [Hq, total_q].

@@ -61,6 +61,7 @@ SIGNATURES = {
     "fa_blocksparse_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_blocksparse_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int] +
                            [ctypes.c_longlong] * 2 + [_c_void_p]),
+    "fa_fp8_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [ctypes.c_longlong] + [_c_float] * 4 + [_c_int, _c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
@@ -228,6 +229,10 @@ def fa_blocksparse_bwd_raw(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B,
                            bs, hs, stream=0) -> int:
     return load().fa_blocksparse_bwd(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
                                      int(causal), block, bs, hs, stream)
+
+
+def fa_fp8_fwd_raw(Q8, K8, Vt8, O, LSE, B, Hq, Hkv, Nq, Nk, d, vt_stride, scale, dq, dk, dv, causal, stream=0) -> int:
+    return load().fa_fp8_fwd(Q8, K8, Vt8, O, LSE, B, Hq, Hkv, Nq, Nk, d, vt_stride, scale, dq, dk, dv, int(causal), stream)
 
 
 def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
@@ -611,6 +616,38 @@ def fa_blocksparse_bwd(Q, K, V, block_mask, block: int, O, dO, LSE, scale: float
                                   _ptr(dK), _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
                                   causal, block, bs, hs, _stream()))
     return dQ, dK, dV
+
+
+def fp8_key_major(V8):
+    """V8 [B, Nk, Hkv, d] uint8 (E4M3 bytes) -> the key-major tensor fa_fp8_fwd takes: [B, Hkv, d, stride] with
+    stride = Nk rounded up to 64, the padding zero."""
+    import torch
+    B, Nk, Hkv, d = V8.shape
+    stride = (Nk + 63) // 64 * 64
+    Vt = torch.zeros((B, Hkv, d, stride), dtype=torch.uint8, device=V8.device)
+    Vt[..., :Nk] = V8.permute(0, 2, 3, 1)
+    return Vt
+
+
+def fa_fp8_fwd(Q8, K8, Vt8, Nk: int, scale: float, descale_q: float, descale_k: float, descale_v: float, causal: bool,
+               O=None, LSE=None):
+    """Forward on E4M3 operands. Q8 [B,Nq,Hq,d], K8 [B,Nk,Hkv,d] uint8; Vt8 [B,Hkv,d,stride] uint8 as made by
+    fp8_key_major. Returns O [B,Nq,Hq,d] bf16 and LSE [B,Hq,Nq] fp32."""
+    import torch
+    for t, nm in ((Q8, "Q8"), (K8, "K8"), (Vt8, "Vt8")):
+        _need(t, nm, torch.uint8, None, Q8.device)
+    if Q8.dim() != 4 or K8.dim() != 4 or Vt8.dim() != 4:
+        raise ValueError("Q8 must be [B, Nq, Hq, d], K8 [B, Nk, Hkv, d], Vt8 [B, Hkv, d, stride]")
+    B, Nq, Hq, d = Q8.shape
+    Hkv = K8.shape[2]
+    _need(K8, "K8", torch.uint8, (B, Nk, Hkv, d))
+    if tuple(Vt8.shape[:3]) != (B, Hkv, d) or Vt8.shape[3] % 64 or Vt8.shape[3] < Nk:
+        raise ValueError("Vt8 must be [B, Hkv, d, stride] with stride a multiple of 64 and at least Nk")
+    O = _out(O, "O", (B, Nq, Hq, d), torch.bfloat16, Q8.device)
+    LSE = _out(LSE, "LSE", (B, Hq, Nq), torch.float32, Q8.device)
+    _check(fa_fp8_fwd_raw(_ptr(Q8), _ptr(K8), _ptr(Vt8), _ptr(O), _ptr(LSE), B, Hq, Hkv, Nq, Nk, d, Vt8.shape[3], scale,
+                          descale_q, descale_k, descale_v, causal, _stream()))
+    return O, LSE
 
 
 def fa_varlen_cross_fwd(Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int, scale: float,

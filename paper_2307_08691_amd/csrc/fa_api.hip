@@ -532,6 +532,33 @@ int fa_blocksparse_bwd(const void* Q, const void* K, const void* V, const void* 
                    with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), causal);
 }
 
+int fa_fp8_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+               int Nk, int d, long long vt_stride, float scale, float descale_q, float descale_k, float descale_v,
+               int causal, void* stream) {
+  if (!Q8 || !K8 || !Vt8 || !O || !LSE) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
+  for (float ds : {descale_q, descale_k, descale_v})
+    if (!(ds > 0.f) || !std::isfinite(ds)) return FA_ERR_SHAPE;
+  if (vt_stride % 64 != 0 || vt_stride < ((long long)Nk + 63) / 64 * 64) return FA_ERR_SHAPE;
+  if (!aligned16(Q8) || !aligned16(K8) || !aligned16(Vt8) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
+  fa::Fp8Args a;
+  a.p = make_problem(nullptr, B, Nq, Nk, Hq, Hkv, d, (long)B * Nq, scale * descale_q * descale_k);
+  a.Q = Q8;
+  a.K = K8;
+  a.Vt = Vt8;
+  a.O = (__bf16*)O;
+  a.LSE = LSE;
+  a.vt_stride = (long)vt_stride;
+  a.descale_v = descale_v;
+  hipError_t e = fa::launch_fwd_fp8(a, d, causal, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return FA_ERR_LAUNCH;
+  }
+  return FA_OK;
+}
+
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,
                               int max_k) {
   if (int e = check_varlen(cu_q, nseq, total_q, max_q)) return e;

@@ -32,7 +32,21 @@ struct BwdArgs {
   float* Dvec;   // workspace: rowsum(dO o O), laid out like LSE
 };
 
+// FP8 (E4M3) forward: Q, K one byte per element in the token-major layout, V key-major
+// [B, Hkv, d, vt_stride]; p.scale is the softmax scaling times the scales of Q and K
+struct Fp8Args {
+  Problem p;
+  const void* Q;
+  const void* K;
+  const void* Vt;
+  __bf16* O;
+  float* LSE;
+  long vt_stride;   // bytes between the rows of V^T: a multiple of 64, at least Nk rounded up to 64
+  float descale_v;
+};
+
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st);
+hipError_t launch_fwd_fp8(const Fp8Args& a, int d, int causal, hipStream_t st);
 // stages: bit 0 D pre-pass, bit 1 dK/dV kernel, bit 2 dQ kernel
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st);
 // ragged batches with two lengths: O (or dQ) = 0 and L = -inf for the query rows of sequences without keys

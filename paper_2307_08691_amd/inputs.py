@@ -271,6 +271,10 @@ CONFIGS = {
     "local_d128_n8k_w1024": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=False, seed=1022, window=(1023, 0)),
     "local_d128_n16k_w2048": dict(kind="dense", B=1, N=16384, Hq=16, Hkv=16, d=128, causal=False, seed=1023, window=(2047, 0)),
     "local_d64_n8k_w512x2": dict(kind="dense", B=2, N=8192, Hq=32, Hkv=32, d=64, causal=False, seed=1024, window=(512, 512)),
+    # FP8 (E4M3) operands, forward only: the benchmark shape and the long non-causal one
+    "fp8_d128_n8k_causal": dict(kind="fp8", B=2, Nq=8192, Nk=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1027),
+    "fp8_d128_n16k_full": dict(kind="fp8", B=1, Nq=16384, Nk=16384, Hq=16, Hkv=16, d=128, causal=False, seed=1028),
+    "fp8_d64_n8k_causal": dict(kind="fp8", B=2, Nq=8192, Nk=8192, Hq=32, Hkv=32, d=64, causal=True, seed=1029),
     # block-sparse: blocks of 128 x 128, half of them kept (one pattern per head), under the causal rule
     "blocksparse_d128_n8k_causal_half": dict(kind="dense", B=2, N=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1025,
                                              block_pattern=dict(seed=17600, block=128, density=0.5)),
@@ -326,6 +330,8 @@ def make_config(name: str) -> AttnProblem:
         prob = make_dense(name=name, **c)
     elif kind == "cross":
         prob = make_cross(name=name, **c)
+    elif kind == "fp8":
+        prob = make_fp8(name=name, **c)
     else:
         lens = ragged_lengths(c["seed"], c.pop("nseq"), c.pop("lo"), c.pop("hi"))
         prob = make_varlen(lens, name=name, **c)

@@ -35,15 +35,15 @@ def resource_remarks(source):
 
 @pytest.fixture(scope="module")
 def remarks():
-    with concurrent.futures.ThreadPoolExecutor(3) as ex:
-        a, b, c = ex.map(resource_remarks, ["fa_fwd.hip", "fa_bwd.hip", "fa_d256.hip"])
-    return {**a, **b, **c}
+    with concurrent.futures.ThreadPoolExecutor(4) as ex:
+        parts = list(ex.map(resource_remarks, ["fa_fwd.hip", "fa_bwd.hip", "fa_d256.hip", "fa_fp8.hip"]))
+    return {k: v for part in parts for k, v in part.items()}
 
 
 def test_every_kernel_was_seen(remarks):
     names = " ".join(remarks)
     for k in ("fwd_kernel", "fwd_chain_kernel", "fwd_merge_kernel", "bwd_prep_kernel", "bwd_dkdv_kernel", "bwd_dq_kernel",
-              "fwd256_kernel", "dkdv256_kernel", "dq256_kernel"):
+              "fwd256_kernel", "dkdv256_kernel", "dq256_kernel", "fwd_fp8_kernel", "keyless_rows_kernel"):
         assert k in names
     assert len(remarks) >= 60  # every instantiation reports
 
