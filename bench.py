@@ -522,7 +522,7 @@ def main() -> int:
         dq_ms = r.event_ms(lambda: r.stages(4), args.steps)
         out["roofline"] = roof(2.0 * fwd_fl, dkdv_ms, "bwd_dkdv_kernel")
         out["roofline_dq"] = roof(1.5 * fwd_fl, dq_ms, "bwd_dq_kernel")
-        out["bwd"]["prep_ms"] = prep_ms
+        out["bwd"]["prep_ms"] = prep_ms  # (a launch of its own only here: fa_bwd computes D inside the dQ kernel)
     else:
         # no per-kernel entry point for this workload: the three backward launches together, against
         # the 3.5 x forward FLOPs they execute (7 products)

@@ -85,11 +85,12 @@ int fa_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
  * same Q, K, V, scale and causal flag. Writes dQ, dK, dV (bfloat16).
  * `workspace` is device scratch of at least fa_bwd_workspace_bytes() bytes,
  * 16-byte aligned; its contents are undefined on entry and on return. It holds
- * D = rowsum(dO o O) (Algorithm 2, line 4). Three kernels are enqueued: the D
- * pre-pass, a column-block kernel that produces dK and dV (section 3.2,
- * "Backward pass"), and a row-block kernel that produces dQ by recomputing
- * the probabilities once more instead of accumulating across workgroups with
- * atomic adds. All three outputs are bit-reproducible.
+ * D = rowsum(dO o O) (Algorithm 2, line 4). Two kernels are enqueued: a row-block
+ * kernel that computes D for its rows and produces dQ by recomputing the
+ * probabilities (instead of accumulating dQ across workgroups with atomic adds),
+ * then a column-block kernel that produces dK and dV (section 3.2, "Backward
+ * pass"). Head dimension 256, dropout, mask, window and pattern variants run the
+ * D pre-pass as a launch of its own first. All three outputs are bit-reproducible.
  */
 size_t fa_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int d);
 int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
@@ -98,9 +99,10 @@ int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const voi
            int B, int Hq, int Hkv, int N, int d, float scale, int causal, void* stream);
 
 /*
- * Profiling aid: fa_bwd restricted to a subset of its three launches, so that
- * each can be timed on its own. `stages` is a bit mask; fa_bwd equals
- * FA_STAGE_PREP | FA_STAGE_DKDV | FA_STAGE_DQ. Both later stages read the D
+ * Profiling aid: the backward as three launches (D pre-pass, dK/dV kernel, dQ kernel)
+ * restricted to a subset of them, so that each can be timed on its own. `stages`
+ * is a bit mask; all three bits give the results of fa_bwd (which itself folds the
+ * pre-pass into the dQ kernel: one launch and one pass over dO fewer). Both later stages read the D
  * the prep stage writes, so results are correct only if it ran first on the
  * same arguments. Same validation and errors as fa_bwd; stages == 0 or bits
  * outside the mask return FA_ERR_SHAPE.

@@ -1,6 +1,7 @@
 // Backward pass of exact attention for gfx950 (Algorithm 2 of the paper).
 //
-// Three launches on the caller's stream:
+// Three launches on the caller's stream (the plain full backward folds the first into the
+// third, which then runs before the second: two launches, see OWN_D):
 //   1. prep:  D = rowsum(dO o O) (Algorithm 2, line 4)
 //   2. dK/dV: one workgroup per block of 256 keys of one (sequence, key/value head)
 //             (section 3.2 "Backward pass"); it loops over the query heads that share the
@@ -743,7 +744,11 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // (a private 32 x 64 piece per block, copied HBM -> LDS one vector phase ahead).
 // LOCAL: sliding window, as in the forward kernel (only the column blocks inside the band are
 // walked; the element mask on the blocks that straddle an edge of it).
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false>
+// OWN_D: the kernel computes D_i = rowsum(dO_i o O_i) (line 4) of its own rows itself, from the
+// dO_i operands it holds anyway and one pass over its O_i rows, and writes it for the dK/dV kernel,
+// which then runs after this one: the whole backward without the separate D pre-pass.
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false,
+          bool OWN_D = false>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
@@ -798,7 +803,24 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const long stat = s * p.lse_seq_stride + (long)h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + rowc;
   float Lq = row < n ? a.LSE[stat] * kLog2e : INFINITY;  // rows past the end: P = 0
   if ((MASK || LOCAL) && Lq == -INFINITY) Lq = INFINITY;  // a row that the mask (the pattern) left without keys: P = 0
-  const float Dq = a.Dvec[stat];
+  float Dq;
+  if constexpr (OWN_D) {
+    // this lane holds half of its row of dO_i (the elements 16 ks + 8 hh ..): the same half of O_i,
+    // multiplied and summed, and the other half from the partner lane
+    const __bf16* op = a.O + ((si.tok0 + rowc) * p.Hq + h) * dh + 8 * hh;
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      if (!PAD || 16 * ks + 8 * hh < dh) {
+        const bf16x8 o = *(const bf16x8*)(op + 16 * ks);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) part += widen<F16>(o, t) * widen<F16>(dOf[ks], t);
+      }
+    Dq = sum_with_partner32(part);
+    if (row < n && hh == 0) a.Dvec[stat] = Dq;
+  } else {
+    Dq = a.Dvec[stat];
+  }
 
   f32x16 dQt[DT];
 #pragma unroll
@@ -1045,6 +1067,21 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   const long nrows = (long)a.p.total_tokens * a.p.Hq;
   constexpr int RPB = 256 / (D / 8);
   hipError_t e = hipSuccess;
+  // The whole backward on the plain paths (no dropout, mask, window or pattern): two launches. The
+  // dQ kernel goes first and computes D on the way, the dK/dV kernel follows and reads it.
+  const bool plain = !a.p.mask && !a.p.drop_thr && !a.p.bmask && a.p.win_left < 0 && a.p.win_right < 0;
+  if (stages == 7 && plain) {
+    dim3 qgrid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+    if (a.p.d != D) {
+      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true, false, false, true>), qgrid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true, false, false, true>), qgrid, dim3(512), 0, st, a);
+    } else {
+      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, false, false, false, true>), qgrid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, false, false, true>), qgrid, dim3(512), 0, st, a);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    stages = 2;  // what remains: the dK/dV kernel
+  }
   if (stages & 1) {
     hipLaunchKernelGGL((bwd_prep_kernel<D, F16>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
