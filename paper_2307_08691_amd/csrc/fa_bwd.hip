@@ -110,8 +110,13 @@ constexpr int dkdv_block_keys(int D, bool dropout, bool mask) { return dkdv_wide
 // window reaches its 256 keys, a wavefront computes only on those that reach its own 32 keys
 // (leading and trailing tiles are sat out), and the element mask is applied on the tiles that
 // straddle an edge of the band.
-template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false>
+//
+// DH (PAD only): the head dimension rounded up to a multiple of 32; the products run over the
+// first DH columns of the D-wide tiles only (see the forward kernel).
+template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false,
+          int DH = D>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
+  static_assert(DH == D || (PAD && DH % 32 == 0 && DH < D), "a narrower product width is for padded head dimensions");
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
   constexpr bool KREG = !MASK && !DROPOUT;  // K_j operands of the wavefront's 32 keys in registers
@@ -120,7 +125,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int BC = dkdv_block_keys(D, DROPOUT, MASK);  // keys per workgroup
   constexpr int QTW = D == 128 ? 1 : 2;  // 32-row query tiles per wavefront per step
   constexpr int BR = 32 * QTW;          // query rows of one tile
-  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int ROWB = 2 * D;           // row bytes of the Q_i, dO_i, K_j, V_j tiles
   constexpr int RING = WIDE ? 4 : 5;
   // byte offsets inside the LDS block (WIDE: K_j never enters LDS, V_j only when it is not in registers)
@@ -661,8 +666,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       const long kvoff = ((si.tok0k + key0) * p.Hkv + g) * dh;
       int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop
       asm volatile("" : "+v"(ln));
-      store_rows_via_lds<DT, F16>(stg, dKt, p.scale, a.dK + kvoff, (long)p.Hkv * dh, nk - key0, dh, ln);
-      store_rows_via_lds<DT, F16>(stg, dVt, 1.f, a.dV + kvoff, (long)p.Hkv * dh, nk - key0, dh, ln);
+      store_tiles_via_lds<DT, F16>(stg, dKt, p.scale, a.dK + kvoff, (long)p.Hkv * dh, nk - key0, dh, ln);
+      store_tiles_via_lds<DT, F16>(stg, dVt, 1.f, a.dV + kvoff, (long)p.Hkv * dh, nk - key0, dh, ln);
     }
     return;
   }
@@ -747,13 +752,15 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 // OWN_D: the kernel computes D_i = rowsum(dO_i o O_i) (line 4) of its own rows itself, from the
 // dO_i operands it holds anyway and one pass over its O_i rows, and writes it for the dK/dV kernel,
 // which then runs after this one: the whole backward without the separate D pre-pass.
+// DH (PAD only): the narrower product width of a padded head dimension (see the forward kernel).
 template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false, bool LOCAL = false,
-          bool OWN_D = false>
+          bool OWN_D = false, int DH = D>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
+  static_assert(DH == D || (PAD && DH % 32 == 0 && DH < D), "a narrower product width is for padded head dimensions");
   static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
-  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
   constexpr int MASKB = 32 * BC * 2;             // one wavefront's piece of M for one block
@@ -1049,16 +1056,22 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   {
     // dQ_i through the one ring slot that is neither in use nor the target of a copy issued
     // past the last block, as whole rows (see store_rows_via_lds)
-    static_assert(RING == 4 && BUFB / 8 == 32 * 32 * DT, "the staging area of a wavefront is an eighth of a ring slot");
+    static_assert(RING == 4 && BUFB / 8 == 32 * D, "the staging area of a wavefront is an eighth of a ring slot");
     char* stg = smem + ((ncol + 3) % RING) * BUFB + w * (BUFB / 8);
     __bf16* op = a.dQ + ((si.tok0 + wrow0) * p.Hq + h) * dh;
     const long ostride = (long)p.Hq * dh;
     int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop
     asm volatile("" : "+v"(ln));
+    if constexpr (DT % 2 == 0) {
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
-      store_rows_via_lds<DT / 2, F16>(stg, &dQt[half * (DT / 2)], p.scale, op + half * (D / 2), ostride, n - wrow0,
-                                      dh - half * (D / 2), ln);
+      for (int half = 0; half < 2; ++half)
+        store_rows_via_lds<DT / 2, F16>(stg, &dQt[half * (DT / 2)], p.scale, op + half * (DH / 2), ostride, n - wrow0,
+                                        dh - half * (DH / 2), ln);
+    } else {  // (an odd number of 32-column tiles: one at a time)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+        store_rows_via_lds<1, F16>(stg, &dQt[dt], p.scale, op + 32 * dt, ostride, n - wrow0, dh - 32 * dt, ln);
+    }
   }
 }
 
@@ -1066,13 +1079,17 @@ template <int D, bool F16>
 static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStream_t st) {
   const long nrows = (long)a.p.total_tokens * a.p.Hq;
   constexpr int RPB = 256 / (D / 8);
+  constexpr int DN = D == 128 ? 96 : 32;  // the narrower product width of this tile width (padded head dimensions)
   hipError_t e = hipSuccess;
   // The whole backward on the plain paths (no dropout, mask, window or pattern): two launches. The
   // dQ kernel goes first and computes D on the way, the dK/dV kernel follows and reads it.
   const bool plain = !a.p.mask && !a.p.drop_thr && !a.p.bmask && a.p.win_left < 0 && a.p.win_right < 0;
   if (stages == 7 && plain) {
     dim3 qgrid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
-    if (a.p.d != D) {
+    if (a.p.d != D && a.p.d <= DN) {
+      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true, false, false, true, DN>), qgrid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true, false, false, true, DN>), qgrid, dim3(512), 0, st, a);
+    } else if (a.p.d != D) {
       if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true, false, false, true>), qgrid, dim3(512), 0, st, a);
       else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true, false, false, true>), qgrid, dim3(512), 0, st, a);
     } else {
@@ -1105,8 +1122,13 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     }
     if (done) {
     } else if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
-      if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
-      else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
+      if (a.p.d <= DN) {
+        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, false, true, false, false, DN>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, true, false, false, DN>), grid, dim3(512), 0, st, a);
+      } else {
+        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
+      }
       done = true;
     }
     if constexpr (!F16) {
@@ -1137,8 +1159,13 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     }
     if (done) {
     } else if (a.p.d != D) {
-      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
-      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
+      if (a.p.d <= DN) {
+        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true, false, false, false, DN>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true, false, false, false, DN>), grid, dim3(512), 0, st, a);
+      } else {
+        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, true>), grid, dim3(512), 0, st, a);
+      }
       done = true;
     }
     if constexpr (!F16) {

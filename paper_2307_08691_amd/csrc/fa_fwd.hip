@@ -88,8 +88,13 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return __buil
 // is applied on the blocks that straddle an edge of the band. A row's first visible key may
 // lie in a later block than its wavefront's first one, so the guards for "no key seen yet"
 // of the split-key kernel apply. Instantiated with CAUSAL = false (win_right = 0 is the rule).
+//
+// DH (PAD only): the head dimension rounded up to a multiple of 32. The tiles in LDS keep the
+// width D (row pitch, swizzle and copies are those of the full tile), but the products only run
+// over the first DH columns: D = 128 with DH = 96 does three quarters of the matrix work of the
+// full width, D = 64 with DH = 32 half.
 template <int D, bool CAUSAL, bool SPLIT, bool F16, bool DROPOUT = false, bool PAD = false, bool MASK = false,
-          bool LOCAL = false>
+          bool LOCAL = false, int DH = D>
 __global__ __launch_bounds__(512)
     __attribute__((amdgpu_waves_per_eu(fwd_two_per_cu(D, DROPOUT, MASK || LOCAL) ? 4 : 2, fwd_two_per_cu(D, DROPOUT, MASK || LOCAL) ? 4 : 2))) void
     fwd_kernel(FwdArgs a) {
@@ -98,8 +103,9 @@ __global__ __launch_bounds__(512)
   constexpr int AHEAD_QK = TWO ? 1 : kFwdAheadQK, AHEAD_PV = TWO ? 1 : kFwdAheadPV;
   static_assert(!MASK || (!SPLIT && !F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
-  constexpr int KS = D / 16;  // contraction steps of the first product
-  constexpr int DT = D / 32;  // 32-row tiles of O^T
+  static_assert(DH == D || (PAD && DH % 32 == 0 && DH < D), "a narrower product width is for padded head dimensions");
+  constexpr int KS = DH / 16;  // contraction steps of the first product
+  constexpr int DT = DH / 32;  // 32-row tiles of O^T
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = BC * ROWB, BUFB = 2 * TILEB;  // one buffer = K_j | V_j
 
@@ -483,16 +489,22 @@ __global__ __launch_bounds__(512)
   {
     // O through the ring slot that neither holds a block still in use nor receives one of the
     // copies issued past the last block (those fill the three slots after block ncol - 1)
-    static_assert(RING == 4 && BUFB / 8 == 32 * 32 * DT, "the staging area of a wavefront is an eighth of a ring slot");
+    static_assert(RING == 4 && BUFB / 8 == 32 * D, "the staging area of a wavefront is an eighth of a ring slot");
     char* stg = smem + ((ncol + 3) % RING) * BUFB + w * (BUFB / 8);
     __bf16* op = a.O + ((si.tok0 + prow0) * p.Hq + h) * dh;
     const long ostride = (long)p.Hq * dh;
     int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop
     asm volatile("" : "+v"(ln));
+    if constexpr (DT % 2 == 0) {
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      store_rows_via_lds<DT / 2, F16>(stg, &O[half * (DT / 2)], inv, op + half * (D / 2), ostride, n - prow0,
-                                      dh - half * (D / 2), ln);
+      for (int half = 0; half < 2; ++half) {
+        store_rows_via_lds<DT / 2, F16>(stg, &O[half * (DT / 2)], inv, op + half * (DH / 2), ostride, n - prow0,
+                                        dh - half * (DH / 2), ln);
+      }
+    } else {  // (an odd number of 32-column tiles: one at a time)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+        store_rows_via_lds<1, F16>(stg, &O[dt], inv, op + 32 * dt, ostride, n - prow0, dh - 32 * dt, ln);
     }
     if (row < n && hh == 0)
       a.LSE[s * p.lse_seq_stride + h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + row] =
@@ -895,8 +907,14 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     }
   }
   if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
-    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, false, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, true>), grid, block, 0, st, a);
+    constexpr int DN = D == 128 ? 96 : 32;  // the narrower product width of this tile width
+    if (a.p.d <= DN) {
+      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, false, true, false, false, DN>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, true, false, false, DN>), grid, block, 0, st, a);
+    } else {
+      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, false, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, true>), grid, block, 0, st, a);
+    }
     return hipGetLastError();
   }
   if constexpr (!F16) {

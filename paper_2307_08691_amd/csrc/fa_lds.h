@@ -203,6 +203,18 @@ __device__ __forceinline__ void store_rows_via_lds(char* stg, const f32x16* acc,
   }
 }
 
+// The same for NT tiles where NT need not be a power of two (three tiles: one at a time).
+template <int NT, bool F16>
+__device__ __forceinline__ void store_tiles_via_lds(char* stg, const f32x16* acc, float mul, __bf16* g, long gstride,
+                                                    int nrows, int ncols, int lane) {
+  if constexpr ((NT & (NT - 1)) == 0) {
+    store_rows_via_lds<NT, F16>(stg, acc, mul, g, gstride, nrows, ncols, lane);
+  } else {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) store_rows_via_lds<1, F16>(stg, acc + t, mul, g + 32 * t, gstride, nrows, ncols - 32 * t, lane);
+  }
+}
+
 // Issue-order hints for the machine scheduler (one scheduling group each, in program
 // order): without them the compiler tends to wait for every LDS operand right before
 // the MFMA that uses it, which exposes the LDS latency once per MFMA.
