@@ -55,12 +55,10 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "unset",
-    "d128_n8k_causal": {"fwd_kernel": 647689454, "bwd_dkdv_kernel": 828062947, "bwd_dq_kernel": 740116376},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269784965, "bwd_dkdv_kernel": 405079995, "bwd_dq_kernel": 337935017},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 884646395, "bwd_dkdv_kernel": 879984373, "bwd_dq_kernel": 830892697},
-    "d256_n8k_causal": {"fwd_kernel": 791084128, "bwd_dkdv_kernel": 898424133, "bwd_dq_kernel": 772954746},  # fwd256 / dkdv256 / dq256
-    "decode_b8_on_8k": {"fwd_kernel": 288777216},  # split kernel + merge, profiles/bench_decode_b8_on_8k_kernel_stats.md
+    "sources": "2bb54ff2f148",
+    "d128_n8k_causal": {"fwd_kernel": 680513090, "bwd_dkdv_kernel": 841851599, "bwd_dq_kernel": 717905621},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269804113, "bwd_dkdv_kernel": 405200195, "bwd_dq_kernel": 338086201},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 873108946, "bwd_dkdv_kernel": 880117876, "bwd_dq_kernel": 831731514},
 }
 
 
