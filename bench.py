@@ -55,7 +55,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "2bb54ff2f148",
+    "sources": "4629dd21b9bb",
     "d128_n8k_causal": {"fwd_kernel": 680513090, "bwd_dkdv_kernel": 841851599, "bwd_dq_kernel": 717905621},
     "sweep_d128_n8192_full": {"fwd_kernel": 269804113, "bwd_dkdv_kernel": 405200195, "bwd_dq_kernel": 338086201},
     "sweep_d64_n8192_causal": {"fwd_kernel": 873108946, "bwd_dkdv_kernel": 880117876, "bwd_dq_kernel": 831731514},
@@ -63,13 +63,13 @@ MEASURED_TRAFFIC = {
 
 
 def kernel_sources_id() -> str:
-    """Short hash of the kernel sources (csrc/*.hip, *.h): identifies what a counter pass measured."""
+    """Short hash of the sources of the bf16 forward and backward kernels (the ones the counter passes
+    cover): identifies what a counter pass measured."""
     d = os.path.join(ROOT, "paper_2307_08691_amd", "csrc")
     h = hashlib.sha1()
-    for f in sorted(os.listdir(d)):
-        if f.endswith((".hip", ".h")):
-            h.update(f.encode())
-            h.update(open(os.path.join(d, f), "rb").read())
+    for f in ("fa_bwd.hip", "fa_common.h", "fa_fwd.hip", "fa_kernels.h", "fa_lds.h"):
+        h.update(f.encode())
+        h.update(open(os.path.join(d, f), "rb").read())
     return h.hexdigest()[:12]
 
 

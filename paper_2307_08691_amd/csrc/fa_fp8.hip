@@ -50,8 +50,10 @@ __device__ __forceinline__ f32x16 mfma_fp8(i32x8 a, i32x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
+// (d = 64: 32 KiB of LDS and fewer than 128 registers, so two workgroups share a compute unit and one's
+// start-up and epilogue overlap the other's loop, as in the bf16 kernel)
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_fp8_kernel(Fp8Args a) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2))) void fwd_fp8_kernel(Fp8Args a) {
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = D / 64;   // contraction steps of the first product
   constexpr int DT = D / 32;   // 32-row tiles of O^T
