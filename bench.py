@@ -11,7 +11,9 @@ and reports GB/s of compulsory traffic against the HBM roofline. Throughput is c
 paper's formula (section 4.1): forward 4*N^2*d FLOPs per head and sequence, halved under the
 causal mask, backward 2.5x that.
 
-The timed region holds exactly `--steps` steps and nothing else (no events inside). After it,
+Before the `--warmup` steps the same step runs untimed for `--settle` seconds (a fresh process on
+an idle GPU otherwise measures the clock ramp). The timed region holds exactly `--steps` steps and
+nothing else (no events inside). After it,
 outside the timed region, the same number of forward calls and of backward calls are timed
 apart with HIP events, and (dense bf16 workloads) every backward kernel on its own through
 fa_bwd_stages: those per-kernel durations feed the roofline objects.
@@ -422,6 +424,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--settle", type=float, default=0.25, metavar="SECONDS",
+                    help="untimed work before the warm-up steps, so that the clocks have settled (0: none)")
     ap.add_argument("--workload", default="d128_n8k_causal")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true", help="profiling aid: a step is the forward alone")
@@ -462,6 +466,13 @@ def main() -> int:
 
     r = Runner(prob, binding, torch)
     step = r.fwd if args.fwd_only else r.both
+    # A fresh process on an idle GPU first measures the clock ramp, not the kernels: a quarter of a
+    # second of the same work, untimed, before the warm-up steps the caller asked for.
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < args.settle:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
