@@ -320,6 +320,52 @@ int fa_blocksparse_bwd(const void* Q, const void* K, const void* V, const void* 
                        void* stream);
 
 /*
+ * The dropout, mask, window and block-sparse entry points for IEEE half precision (fp16) elements:
+ * each is its bfloat16 namesake with every 16-bit tensor (Q, K, V, O, dO, dQ, dK, dV, and the
+ * elementwise mask M of the mask pair) holding fp16, as fa_cross_fwd_f16 / fa_cross_bwd_f16 are
+ * to fa_cross_fwd / fa_cross_bwd (section 2.1 argues for FP16 and BF16 matrix units alike).
+ * LSE, the workspace, the block pattern's bytes, the dropout generator and every reading stated
+ * above are unchanged; so are arguments, limits and errors. An fp16 mask entry is finite (at most
+ * 65504 in magnitude) or -inf.
+ */
+int fa_dropout_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                       float p_drop, uint64_t seed, void* stream);
+int fa_dropout_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                       const float* LSE, void* dQ, void* dK, void* dV,
+                       void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                       float p_drop, uint64_t seed, void* stream);
+int fa_mask_fwd_f16(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE,
+                    int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                    long long mask_batch_stride, long long mask_head_stride,
+                    long long mask_row_stride, void* stream);
+int fa_mask_bwd_f16(const void* Q, const void* K, const void* V, const void* M, const void* O,
+                    const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                    void* workspace, size_t workspace_bytes,
+                    int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                    long long mask_batch_stride, long long mask_head_stride,
+                    long long mask_row_stride, void* stream);
+int fa_local_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                     int window_left, int window_right, void* stream);
+int fa_local_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                     const float* LSE, void* dQ, void* dK, void* dV,
+                     void* workspace, size_t workspace_bytes,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                     int window_left, int window_right, void* stream);
+int fa_blocksparse_fwd_f16(const void* Q, const void* K, const void* V, const void* block_mask,
+                           void* O, float* LSE, int B, int Hq, int Hkv, int Nq, int Nk, int d,
+                           float scale, int causal, int block,
+                           long long mask_batch_stride, long long mask_head_stride, void* stream);
+int fa_blocksparse_bwd_f16(const void* Q, const void* K, const void* V, const void* block_mask,
+                           const void* O, const void* dO, const float* LSE,
+                           void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                           int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                           int block, long long mask_batch_stride, long long mask_head_stride,
+                           void* stream);
+
+/*
  * Forward pass on FP8 operands (section 5, "Discussion and Future Directions", names FP8; the
  * convention is this library's). Q8 [B, Nq, Hq, d] and K8 [B, Nk, Hkv, d] hold OCP FP8 E4M3 bytes
  * (1 sign, 4 exponent, 3 significand bits, bias 7, largest finite value 448), token-major like the

@@ -47,19 +47,30 @@ SIGNATURES = {
     "fa_cross_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_dropout_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 +
+                       [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_dropout_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 +
                        [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_varlen_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 +
                               [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_varlen_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
                               [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_mask_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
+    "fa_mask_fwd_f16": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_mask_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
                     [ctypes.c_longlong] * 3 + [_c_void_p]),
+    "fa_mask_bwd_f16": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
+                    [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_local_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_local_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_local_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_blocksparse_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
+    "fa_blocksparse_fwd_f16": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_blocksparse_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int] +
+                           [ctypes.c_longlong] * 2 + [_c_void_p]),
+    "fa_blocksparse_bwd_f16": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int] +
                            [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_fp8_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [ctypes.c_longlong] + [_c_float] * 4 + [_c_int, _c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
@@ -179,14 +190,16 @@ def fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d) -> int:
     return load().fa_cross_bwd_workspace_bytes(B, Hq, Hkv, Nq, Nk, d)
 
 
-def fa_dropout_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop, seed, stream=0) -> int:
-    return load().fa_dropout_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), p_drop, seed, stream)
+def fa_dropout_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop, seed, stream=0, f16=False) -> int:
+    fn = load().fa_dropout_fwd_f16 if f16 else load().fa_dropout_fwd
+    return fn(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), p_drop, seed, stream)
 
 
 def fa_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop,
-                       seed, stream=0) -> int:
-    return load().fa_dropout_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
-                                 int(causal), p_drop, seed, stream)
+                       seed, stream=0, f16=False) -> int:
+    fn = load().fa_dropout_bwd_f16 if f16 else load().fa_dropout_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), p_drop, seed,
+              stream)
 
 
 def fa_varlen_dropout_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed,
@@ -201,34 +214,38 @@ def fa_varlen_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu,
                                         Hkv, d, scale, int(causal), p_drop, seed, stream)
 
 
-def fa_mask_fwd_raw(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs, mask_hs, mask_rs, stream=0) -> int:
-    return load().fa_mask_fwd(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), mask_bs, mask_hs, mask_rs,
-                              stream)
+def fa_mask_fwd_raw(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs, mask_hs, mask_rs, stream=0, f16=False) -> int:
+    fn = load().fa_mask_fwd_f16 if f16 else load().fa_mask_fwd
+    return fn(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), mask_bs, mask_hs, mask_rs, stream)
 
 
 def fa_mask_bwd_raw(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs,
-                    mask_hs, mask_rs, stream=0) -> int:
-    return load().fa_mask_bwd(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
-                              int(causal), mask_bs, mask_hs, mask_rs, stream)
+                    mask_hs, mask_rs, stream=0, f16=False) -> int:
+    fn = load().fa_mask_bwd_f16 if f16 else load().fa_mask_bwd
+    return fn(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), mask_bs,
+              mask_hs, mask_rs, stream)
 
 
-def fa_local_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0) -> int:
-    return load().fa_local_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream)
+def fa_local_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0, f16=False) -> int:
+    fn = load().fa_local_fwd_f16 if f16 else load().fa_local_fwd
+    return fn(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream)
 
 
-def fa_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0) -> int:
-    return load().fa_local_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right,
-                               stream)
+def fa_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0, f16=False) -> int:
+    fn = load().fa_local_bwd_f16 if f16 else load().fa_local_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream)
 
 
-def fa_blocksparse_fwd_raw(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block, bs, hs, stream=0) -> int:
-    return load().fa_blocksparse_fwd(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), block, bs, hs, stream)
+def fa_blocksparse_fwd_raw(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block, bs, hs, stream=0, f16=False) -> int:
+    fn = load().fa_blocksparse_fwd_f16 if f16 else load().fa_blocksparse_fwd
+    return fn(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), block, bs, hs, stream)
 
 
 def fa_blocksparse_bwd_raw(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, block,
-                           bs, hs, stream=0) -> int:
-    return load().fa_blocksparse_bwd(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
-                                     int(causal), block, bs, hs, stream)
+                           bs, hs, stream=0, f16=False) -> int:
+    fn = load().fa_blocksparse_bwd_f16 if f16 else load().fa_blocksparse_bwd
+    return fn(Q, K, V, BM, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), block, bs,
+              hs, stream)
 
 
 def fa_fp8_fwd_raw(Q8, K8, Vt8, O, LSE, B, Hq, Hkv, Nq, Nk, d, vt_stride, scale, dq, dk, dv, causal, stream=0) -> int:
@@ -470,12 +487,12 @@ def fa_cross_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=No
 
 
 def fa_dropout_fwd(Q, K, V, scale: float, causal: bool, p_drop: float, seed: int, O=None, LSE=None):
-    """Forward with dropout on P. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
+    """Forward with dropout on P. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 or fp16."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
-                              causal, p_drop, seed, _stream()))
+                              causal, p_drop, seed, _stream(), x.et == torch.float16))
     return O, LSE
 
 
@@ -483,12 +500,12 @@ def fa_dropout_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, p_drop: floa
                    dV=None, workspace=None):
     """Backward with the dropout mask of fa_dropout_fwd for the same p_drop and seed."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                               _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, p_drop, seed,
-                              _stream()))
+                              _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 
@@ -514,18 +531,19 @@ def fa_varlen_dropout_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scal
     return dQ, dK, dV
 
 
-def mask_buffer(Bm: int, Hm: int, Nq: int, Nk: int, device="cuda"):
-    """An elementwise mask [Bm, Hm, Nq, Nk] (bf16, zeros) whose rows are padded in memory to a
-    multiple of 8 elements, as fa_mask_fwd / fa_mask_bwd require; Bm, Hm = 1 shares the mask."""
+def mask_buffer(Bm: int, Hm: int, Nq: int, Nk: int, device="cuda", dtype=None):
+    """An elementwise mask [Bm, Hm, Nq, Nk] (zeros; bf16, or the fp16 of fp16 Q, K, V) whose rows are
+    padded in memory to a multiple of 8 elements, as fa_mask_fwd / fa_mask_bwd require; Bm, Hm = 1
+    shares the mask."""
     import torch
     rs = (Nk + 7) // 8 * 8
-    return torch.zeros((Bm, Hm, Nq, rs), dtype=torch.bfloat16, device=device)[..., :Nk]
+    return torch.zeros((Bm, Hm, Nq, rs), dtype=dtype or torch.bfloat16, device=device)[..., :Nk]
 
 
 def _mask_strides(M, x):
     import torch
-    if M.dtype != torch.bfloat16 or M.device != x.dev:
-        raise ValueError("M must be a bfloat16 tensor on the device of Q")
+    if M.dtype != x.et or M.device != x.dev:
+        raise ValueError("M must have the element type of Q and live on its device")
     if M.dim() != 4 or M.shape[0] not in (1, x.B) or M.shape[1] not in (1, x.Hq) or tuple(M.shape[2:]) != (x.Nq, x.Nk):
         raise ValueError("M must be [1 or B, 1 or Hq, Nq, Nk]")
     if M.stride(3) != 1:
@@ -534,38 +552,38 @@ def _mask_strides(M, x):
 
 
 def fa_mask_fwd(Q, K, V, M, scale: float, causal: bool, O=None, LSE=None):
-    """Forward with the mask M added to the scaled scores. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16; M as
+    """Forward with the mask M added to the scaled scores. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 or fp16; M (same type) as
     made by mask_buffer (entries finite or -inf)."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     bs, hs, rs = _mask_strides(M, x)
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_mask_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d,
-                           scale, causal, bs, hs, rs, _stream()))
+                           scale, causal, bs, hs, rs, _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_mask_bwd(Q, K, V, M, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
     """Backward with the mask of fa_mask_fwd; M receives no gradient."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     bs, hs, rs = _mask_strides(M, x)
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_mask_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
                            _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, bs, hs, rs,
-                           _stream()))
+                           _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 
 def fa_local_fwd(Q, K, V, scale: float, window_left: int, window_right: int, O=None, LSE=None):
     """Sliding window: the query at position q = r + Nk - Nq sees keys q - window_left .. q + window_right
-    (a negative bound: none). Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
+    (a negative bound: none). Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 or fp16."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_local_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
-                            window_left, window_right, _stream()))
+                            window_left, window_right, _stream(), x.et == torch.float16))
     return O, LSE
 
 
@@ -573,12 +591,12 @@ def fa_local_bwd(Q, K, V, O, dO, LSE, scale: float, window_left: int, window_rig
                  workspace=None):
     """Backward of fa_local_fwd for the same window."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_local_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                             _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, window_left, window_right,
-                            _stream()))
+                            _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 
@@ -594,13 +612,13 @@ def _block_mask_strides(BM, x, block):
 
 def fa_blocksparse_fwd(Q, K, V, block_mask, block: int, scale: float, causal: bool, O=None, LSE=None):
     """Block-sparse forward: block_mask uint8 [1 or B, 1 or Hq, ceil(Nq/block), ceil(Nk/block)], non-zero = the
-    block of `block` x `block` scores takes part. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16."""
+    block of `block` x `block` scores takes part. Q [B,Nq,Hq,d], K,V [B,Nk,Hkv,d] bf16 or fp16."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     bs, hs = _block_mask_strides(block_mask, x, block)
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_blocksparse_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(block_mask), _ptr(O), _ptr(LSE), x.B, x.Hq, x.Hkv, x.Nq,
-                                  x.Nk, x.d, scale, causal, block, bs, hs, _stream()))
+                                  x.Nk, x.d, scale, causal, block, bs, hs, _stream(), x.et == torch.float16))
     return O, LSE
 
 
@@ -608,13 +626,13 @@ def fa_blocksparse_bwd(Q, K, V, block_mask, block: int, O, dO, LSE, scale: float
                        workspace=None):
     """Backward of fa_blocksparse_fwd for the same pattern."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     bs, hs = _block_mask_strides(block_mask, x, block)
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
     _check(fa_blocksparse_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(block_mask), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ),
                                   _ptr(dK), _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
-                                  causal, block, bs, hs, _stream()))
+                                  causal, block, bs, hs, _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 

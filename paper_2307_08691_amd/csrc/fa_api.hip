@@ -138,6 +138,10 @@ Options half_precision(int f16) {
   o.f16 = f16;
   return o;
 }
+Options of_type(Options o, int f16) {
+  o.f16 = f16;
+  return o;
+}
 Options with_dropout(float p_drop, uint64_t seed) {
   Options o;
   o.dropout = true;
@@ -447,31 +451,90 @@ int fa_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O,
                    stream, half_precision(1));
 }
 
+static int dropout_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq,
+                           int Hkv, int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed,
+                           void* stream) {
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream,
+                   of_type(with_dropout(p_drop, seed), f16));
+}
+
 int fa_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
                    int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
-  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream, with_dropout(p_drop, seed));
+  return dropout_fwd_any(0, Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop, seed, stream);
+}
+
+int fa_dropout_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
+                       int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  return dropout_fwd_any(1, Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, p_drop, seed, stream);
+}
+
+static int dropout_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                           const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                           int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, float p_drop,
+                           uint64_t seed, void* stream) {
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, of_type(with_dropout(p_drop, seed), f16));
 }
 
 int fa_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
                    void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
                    int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
-  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                   stream, with_dropout(p_drop, seed));
+  return dropout_bwd_any(0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                         causal, p_drop, seed, stream);
 }
 
-int fa_mask_fwd(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE, int B, int Hq, int Hkv,
-                int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
-                long long mask_head_stride, long long mask_row_stride, void* stream) {
+int fa_dropout_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                       void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                       int Nq, int Nk, int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  return dropout_bwd_any(1, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                         causal, p_drop, seed, stream);
+}
+
+static int mask_fwd_any(int f16, const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE,
+                        int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                        long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                        void* stream) {
   return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream,
-                   with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride));
+                   of_type(with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride), f16));
+}
+
+int fa_mask_fwd(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE, int B, int Hq,
+                int Hkv, int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
+                long long mask_head_stride, long long mask_row_stride, void* stream) {
+  return mask_fwd_any(0, Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_batch_stride, mask_head_stride,
+                      mask_row_stride, stream);
+}
+
+int fa_mask_fwd_f16(const void* Q, const void* K, const void* V, const void* M, void* O, float* LSE, int B, int Hq,
+                    int Hkv, int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
+                    long long mask_head_stride, long long mask_row_stride, void* stream) {
+  return mask_fwd_any(1, Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_batch_stride, mask_head_stride,
+                      mask_row_stride, stream);
+}
+
+static int mask_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* M, const void* O,
+                        const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                        size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                        long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                        void* stream) {
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, of_type(with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride), f16));
 }
 
 int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq,
                 int Hkv, int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
                 long long mask_head_stride, long long mask_row_stride, void* stream) {
-  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                   stream, with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride));
+  return mask_bwd_any(0, Q, K, V, M, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                      causal, mask_batch_stride, mask_head_stride, mask_row_stride, stream);
+}
+
+int fa_mask_bwd_f16(const void* Q, const void* K, const void* V, const void* M, const void* O, const void* dO,
+                    const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B,
+                    int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, long long mask_batch_stride,
+                    long long mask_head_stride, long long mask_row_stride, void* stream) {
+  return mask_bwd_any(1, Q, K, V, M, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                      causal, mask_batch_stride, mask_head_stride, mask_row_stride, stream);
 }
 
 // Sliding window. Without any bound this is plain attention and with win_right = 0 alone the
@@ -487,23 +550,51 @@ static int window_route(int Nq, int Nk, int& left, int& right, int& causal) {
   return FA_OK;
 }
 
-int fa_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
-                 int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+static int local_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq,
+                         int Hkv, int Nq, int Nk, int d, float scale, int window_left, int window_right,
+                         void* stream) {
   int causal = 0;
   if (B > 0 && Nq > 0 && Nk > 0)
     if (int e = window_route(Nq, Nk, window_left, window_right, causal)) return e;
+  const bool none = window_left < 0 && window_right < 0;
   return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, stream,
-                   window_left < 0 && window_right < 0 ? half_precision(0) : with_window(window_left, window_right));
+                   none ? half_precision(f16) : of_type(with_window(window_left, window_right), f16));
+}
+
+int fa_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                 int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+  return local_fwd_any(0, Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, window_left, window_right, stream);
+}
+
+int fa_local_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,
+                     int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+  return local_fwd_any(1, Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, window_left, window_right, stream);
+}
+
+static int local_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                         const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                         int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int window_left, int window_right,
+                         void* stream) {
+  int causal = 0;
+  if (B > 0 && Nq > 0 && Nk > 0)
+    if (int e = window_route(Nq, Nk, window_left, window_right, causal)) return e;
+  const bool none = window_left < 0 && window_right < 0;
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, none ? half_precision(f16) : of_type(with_window(window_left, window_right), f16));
 }
 
 int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
-                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
-                 int Nq, int Nk, int d, float scale, int window_left, int window_right, void* stream) {
-  int causal = 0;
-  if (B > 0 && Nq > 0 && Nk > 0)
-    if (int e = window_route(Nq, Nk, window_left, window_right, causal)) return e;
-  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
-                   stream, window_left < 0 && window_right < 0 ? half_precision(0) : with_window(window_left, window_right));
+                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int Nq,
+                 int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+  return local_bwd_any(0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                       window_left, window_right, stream);
+}
+
+int fa_local_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                     void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv,
+                     int Nq, int Nk, int d, float scale, int window_left, int window_right, void* stream) {
+  return local_bwd_any(1, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
+                       window_left, window_right, stream);
 }
 
 static Options with_block_pattern(const void* block_mask, int block, long long bs, long long hs, int causal) {
@@ -515,21 +606,55 @@ static Options with_block_pattern(const void* block_mask, int block, long long b
   return o;
 }
 
+static int blocksparse_fwd_any(int f16, const void* Q, const void* K, const void* V, const void* block_mask, void* O,
+                               float* LSE, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                               int block, long long mask_batch_stride, long long mask_head_stride, void* stream) {
+  if (!block_mask) return FA_ERR_NULL;
+  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, 0, stream,
+                   of_type(with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), f16),
+                   causal);
+}
+
 int fa_blocksparse_fwd(const void* Q, const void* K, const void* V, const void* block_mask, void* O, float* LSE, int B,
                        int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, int block,
                        long long mask_batch_stride, long long mask_head_stride, void* stream) {
+  return blocksparse_fwd_any(0, Q, K, V, block_mask, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block,
+                             mask_batch_stride, mask_head_stride, stream);
+}
+
+int fa_blocksparse_fwd_f16(const void* Q, const void* K, const void* V, const void* block_mask, void* O, float* LSE,
+                           int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal, int block,
+                           long long mask_batch_stride, long long mask_head_stride, void* stream) {
+  return blocksparse_fwd_any(1, Q, K, V, block_mask, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block,
+                             mask_batch_stride, mask_head_stride, stream);
+}
+
+static int blocksparse_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* block_mask,
+                               const void* O, const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                               void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d,
+                               float scale, int causal, int block, long long mask_batch_stride,
+                               long long mask_head_stride, void* stream) {
   if (!block_mask) return FA_ERR_NULL;
-  return cross_fwd(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, 0, stream,
-                   with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), causal);
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, 0, stream,
+                   of_type(with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), f16),
+                   causal);
 }
 
 int fa_blocksparse_bwd(const void* Q, const void* K, const void* V, const void* block_mask, const void* O,
                        const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
                        size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
                        int block, long long mask_batch_stride, long long mask_head_stride, void* stream) {
-  if (!block_mask) return FA_ERR_NULL;
-  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, 0, stream,
-                   with_block_pattern(block_mask, block, mask_batch_stride, mask_head_stride, causal), causal);
+  return blocksparse_bwd_any(0, Q, K, V, block_mask, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv,
+                             Nq, Nk, d, scale, causal, block, mask_batch_stride, mask_head_stride, stream);
+}
+
+int fa_blocksparse_bwd_f16(const void* Q, const void* K, const void* V, const void* block_mask, const void* O,
+                           const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                           size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                           int causal, int block, long long mask_batch_stride, long long mask_head_stride,
+                           void* stream) {
+  return blocksparse_bwd_any(1, Q, K, V, block_mask, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv,
+                             Nq, Nk, d, scale, causal, block, mask_batch_stride, mask_head_stride, stream);
 }
 
 int fa_fp8_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv, int Nq,

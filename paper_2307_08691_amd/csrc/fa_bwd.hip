@@ -117,8 +117,8 @@ template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, 
           int DH = D>
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   static_assert(DH == D || (PAD && DH % 32 == 0 && DH < D), "a narrower product width is for padded head dimensions");
-  static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
-  static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
+  static_assert(!MASK || (!DROPOUT && !PAD), "the mask variant is built for the plain kernel");
+  static_assert(!LOCAL || (!CAUSAL && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain kernel");
   constexpr bool KREG = !MASK && !DROPOUT;  // K_j operands of the wavefront's 32 keys in registers
   constexpr bool VREG = D == 64 && !MASK && !DROPOUT;  // at d = 64 V_j's as well
   constexpr bool WIDE = dkdv_wide(D, DROPOUT, MASK);
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int NM2 = QTW * 4 * DT;  // dV and dK: 16 MFMAs
   // (mask, window / pattern: a shorter prefetch, their bookkeeping needs the registers)
   constexpr int AH = MASK ? (D == 128 ? 1 : 2) : LOCAL && D == 128 ? 1 : (KREG && D == 128 ? 3 : kDkdvAhead);
-  // MASK: this lane's entries of M for the wavefront's next tile (raw bfloat16 bits), row by row
+  // MASK: this lane's entries of M for the wavefront's next tile (raw 16-bit elements), row by row
   uint32_t mraw[MASK ? QTW * 16 : 1];
   auto issue_mask_loads = [&](const Cursor& c) {
     if constexpr (MASK) {
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         for (int u = 0; u < 4; ++u) {
           float sub = -Lv[u];
           if constexpr (MASK)
-            sub = __builtin_fmaf(__builtin_bit_cast(float, mraw[16 * tq + 4 * r4 + u] << 16), kLog2e, sub);
+            sub = __builtin_fmaf(widen_half<F16>(mraw[16 * tq + 4 * r4 + u], false), kLog2e, sub);
           S[tq][4 * r4 + u] = fast_exp2(__builtin_fmaf(S[tq][4 * r4 + u], c2, sub));
         }
       }
@@ -757,8 +757,8 @@ template <int D, bool CAUSAL, bool F16, bool DROPOUT = false, bool PAD = false, 
           bool OWN_D = false, int DH = D>
 __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   static_assert(DH == D || (PAD && DH % 32 == 0 && DH < D), "a narrower product width is for padded head dimensions");
-  static_assert(!MASK || (!F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
-  static_assert(!LOCAL || (!CAUSAL && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
+  static_assert(!MASK || (!DROPOUT && !PAD), "the mask variant is built for the plain kernel");
+  static_assert(!LOCAL || (!CAUSAL && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
   constexpr int KS = DH / 16, DT = DH / 32;
   constexpr int ROWB = 2 * D;
@@ -994,7 +994,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
           const u32x2 mv = *(const u32x2*)(mbuf + (zm ^ (16 * (4 * kt + q4))));
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
-            const float mf = __builtin_bit_cast(float, (u & 1) ? (mv[u >> 1] & 0xffff0000u) : (mv[u >> 1] << 16));
+            const float mf = widen_half<F16>(mv[u >> 1], u & 1);
             S[kt][4 * q4 + u] = fast_exp2(__builtin_fmaf(S[kt][4 * q4 + u], c2, __builtin_fmaf(mf, kLog2e, -Lq)));
           }
         }
@@ -1105,18 +1105,18 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   }
   if (stages & 2) {
     // keys per workgroup differ between the instantiations
-    const bool special = !F16 && (a.p.mask || a.p.drop_thr);
+    const bool special = a.p.mask || a.p.drop_thr;
     const int bck = special ? dkdv_block_keys(D, true, true) : dkdv_block_keys(D, false, false);
     dim3 grid(grid_size((a.p.Nk + bck - 1) / bck, a.p.Hkv * a.p.nseq));
     bool done = false;
-    if constexpr (!F16) {
+    {
       if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern
-        hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
       } else
       if (a.p.mask) {
-        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, false, false, false, true>), grid, dim3(512), 0, st, a);
-        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, false, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
       }
     }
@@ -1131,10 +1131,10 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
       }
       done = true;
     }
-    if constexpr (!F16) {
+    {
       if (!done && a.p.drop_thr) {
-        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, false, true>), grid, dim3(512), 0, st, a);
-        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, false, true>), grid, dim3(512), 0, st, a);
+        if (causal) hipLaunchKernelGGL((bwd_dkdv_kernel<D, true, F16, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dkdv_kernel<D, false, F16, true>), grid, dim3(512), 0, st, a);
         done = true;
       }
     }
@@ -1146,14 +1146,14 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
   if (stages & 4) {
     dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
     bool done = false;
-    if constexpr (!F16) {
+    {
       if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern
-        hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
       } else
       if (a.p.mask) {
-        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, false, false, false, true>), grid, dim3(512), 0, st, a);
-        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, false, false, true>), grid, dim3(512), 0, st, a);
+        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, false, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, true>), grid, dim3(512), 0, st, a);
         done = true;
       }
     }
@@ -1168,10 +1168,10 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
       }
       done = true;
     }
-    if constexpr (!F16) {
+    {
       if (!done && a.p.drop_thr) {
-        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, false, true>), grid, dim3(512), 0, st, a);
-        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, false, true>), grid, dim3(512), 0, st, a);
+        if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, true>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, true>), grid, dim3(512), 0, st, a);
         done = true;
       }
     }

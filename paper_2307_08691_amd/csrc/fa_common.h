@@ -206,6 +206,13 @@ __device__ __forceinline__ float widen(bf16x8 v, int t) {
   else return (float)v[t];
 }
 
+// The 16-bit element in the low (hi = false) or high half of a 32-bit word, widened to float32.
+template <bool F16>
+__device__ __forceinline__ float widen_half(uint32_t w, bool hi) {
+  if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (unsigned short)(hi ? w >> 16 : w));
+  else return __builtin_bit_cast(float, hi ? (w & 0xffff0000u) : (w << 16));
+}
+
 // Dropout generator (defined by this library, the same function as the CPU checker's): for
 // head index bh = sequence * Hq + head, query r and key c,
 //   x = (c / 4) * 0x9E3779B1 + r * 0x85EBCA77 + (seed_mix xor bh * 0xC2B2AE3D), mixed by

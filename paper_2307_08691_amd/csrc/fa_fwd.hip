@@ -99,9 +99,9 @@ __global__ __launch_bounds__(512)
     __attribute__((amdgpu_waves_per_eu(fwd_two_per_cu(D, DROPOUT, MASK || LOCAL) ? 4 : 2, fwd_two_per_cu(D, DROPOUT, MASK || LOCAL) ? 4 : 2))) void
     fwd_kernel(FwdArgs a) {
   constexpr bool TWO = fwd_two_per_cu(D, DROPOUT, MASK || LOCAL);
-  static_assert(!LOCAL || (!CAUSAL && !SPLIT && !F16 && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain bf16 kernel");
+  static_assert(!LOCAL || (!CAUSAL && !SPLIT && !DROPOUT && !PAD && !MASK), "the window variant is built for the plain kernel");
   constexpr int AHEAD_QK = TWO ? 1 : kFwdAheadQK, AHEAD_PV = TWO ? 1 : kFwdAheadPV;
-  static_assert(!MASK || (!SPLIT && !F16 && !DROPOUT && !PAD), "the mask variant is built for the plain bf16 kernel");
+  static_assert(!MASK || (!SPLIT && !DROPOUT && !PAD), "the mask variant is built for the plain kernel");
   constexpr int BR = 256, BC = 64, RING = 4;
   static_assert(DH == D || (PAD && DH % 32 == 0 && DH < D), "a narrower product width is for padded head dimensions");
   constexpr int KS = DH / 16;  // contraction steps of the first product
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(512)
           const u32x2 mv = *(const u32x2*)(mbuf + (zm ^ (16 * (4 * kt + q4))));
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
-            const float mf = __builtin_bit_cast(float, (u & 1) ? (mv[u >> 1] & 0xffff0000u) : (mv[u >> 1] << 16));
+            const float mf = widen_half<F16>(mv[u >> 1], u & 1);
             S[kt][4 * q4 + u] = __builtin_fmaf(S[kt][4 * q4 + u], p.scale, mf);
           }
         }
@@ -893,18 +893,14 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     return hipGetLastError();
   }
   dim3 grid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
-  if constexpr (!F16) {
-    if (a.p.mask) {  // the entry points keep everything else away from it
-      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, false, false, true>), grid, block, 0, st, a);
-      else hipLaunchKernelGGL((fwd_kernel<D, false, false, false, false, false, true>), grid, block, 0, st, a);
-      return hipGetLastError();
-    }
+  if (a.p.mask) {  // the entry points keep everything else away from it
+    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, false, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, false, true>), grid, block, 0, st, a);
+    return hipGetLastError();
   }
-  if constexpr (!F16) {
-    if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern (the entry points keep everything else away from them)
-      hipLaunchKernelGGL((fwd_kernel<D, false, false, false, false, false, false, true>), grid, block, 0, st, a);
-      return hipGetLastError();
-    }
+  if (a.p.win_left >= 0 || a.p.win_right >= 0 || a.p.bmask) {  // sliding window, block-sparse pattern (the entry points keep everything else away from them)
+    hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, false, false, false, true>), grid, block, 0, st, a);
+    return hipGetLastError();
   }
   if (a.p.d != D) {  // padded head dimension (the entry points keep dropout away from it)
     constexpr int DN = D == 128 ? 96 : 32;  // the narrower product width of this tile width
@@ -917,12 +913,10 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
     }
     return hipGetLastError();
   }
-  if constexpr (!F16) {
-    if (a.p.drop_thr) {
-      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, false, true>), grid, block, 0, st, a);
-      else hipLaunchKernelGGL((fwd_kernel<D, false, false, false, true>), grid, block, 0, st, a);
-      return hipGetLastError();
-    }
+  if (a.p.drop_thr) {
+    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, false, F16, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fwd_kernel<D, false, false, F16, true>), grid, block, 0, st, a);
+    return hipGetLastError();
   }
   if constexpr (D == 128) {
     // chained items (fwd_chain_kernel): dense batches of short sequences (at most 16 key blocks:

@@ -31,19 +31,29 @@ def additive_mask_gpu(bm, nq, nk, block):
 
 
 def check_blocksparse(prob, bm, block):
-    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    Q, K, V, dO = (pu.to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
     BM = torch.from_numpy(bm.astype(np.uint8)).cuda()
     O, L = binding.fa_blocksparse_fwd(Q, K, V, BM, block, prob.scale, prob.causal)
     dQ, dK, dV = binding.fa_blocksparse_bwd(Q, K, V, BM, block, O, dO, L, prob.scale, prob.causal)
     torch.cuda.synchronize()
-    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
+    Qf, Kf, Vf, dOf = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     exp = {}
     exp["O"], exp["LSE"] = orc.attention_forward_blocksparse(Qf, Kf, Vf, prob.scale, prob.causal, bm, block)
     exp["dQ"], exp["dK"], exp["dV"] = orc.attention_backward_blocksparse(Qf, Kf, Vf, dOf, prob.scale, prob.causal, bm, block)
     ref = pu.reference_batch(Q, K, V, dO, prob.scale, prob.causal, M=additive_mask_gpu(bm, prob.N, prob.keys, block))
     pu.judge(f"block pattern {block} {bm.shape[0]}x{bm.shape[1]} {pu.describe(prob)}",
-             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))}, exp, ref, d=prob.d)
+             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))}, exp, ref,
+             dtype=prob.dtype, d=prob.d)
     return O, L, dQ, dK, dV
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq,Nk,block,density", [(300, 300, 64, 0.5), (700, 700, 128, 0.5), (300, 1000, 64, 0.3), (1100, 1100, 256, 0.5)])
+def test_patterns_in_half_precision(Nq, Nk, block, density, d, causal):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=4, Hkv=2, d=d, causal=causal, seed=17050 + Nq + Nk, dtype="f16")
+    check_blocksparse(prob, draw_pattern(17060 + Nq, 2, 4, Nq, Nk, block, density), block)
 
 
 @pytest.mark.parametrize("causal", [False, True])

@@ -16,7 +16,7 @@ import parity_util as pu  # noqa: E402
 
 
 def run(prob, p_drop, seed):
-    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    Q, K, V, dO = (pu.to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
     O, L = binding.fa_dropout_fwd(Q, K, V, prob.scale, prob.causal, p_drop, seed)
     dQ, dK, dV = binding.fa_dropout_bwd(Q, K, V, O, dO, L, prob.scale, prob.causal, p_drop, seed)
     torch.cuda.synchronize()
@@ -31,15 +31,16 @@ def keep_masks(seed, p_drop, Hq):
 
 def check_dropout(prob, p_drop, seed):
     got = run(prob, p_drop, seed)
-    Q, K, V, dO = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
+    Q, K, V, dO = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     exp = {}
     exp["O"], exp["LSE"] = orc.attention_forward_dropout(Q, K, V, prob.scale, prob.causal, p_drop, seed)
     exp["dQ"], exp["dK"], exp["dV"] = orc.attention_backward_dropout(Q, K, V, dO, prob.scale, prob.causal, p_drop, seed)
     keep_of, rp = keep_masks(seed, p_drop, prob.Hq)
-    ref = pu.reference_batch(*(pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO)), prob.scale, prob.causal,
-                             keep_of=keep_of, rp=rp)
+    ref = pu.reference_batch(*(pu.to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO)), prob.scale,
+                             prob.causal, keep_of=keep_of, rp=rp)
     res = pu.judge(f"dropout p={p_drop} {pu.describe(prob)}", {k: pu.to_f64(v) for k, v in got.items()}, exp, ref,
-                   standard=False, d=prob.d)
+                   standard=False, dtype=prob.dtype, d=prob.d)
     return {k: v[0] for k, v in res.items()}
 
 
@@ -50,6 +51,13 @@ def check_dropout(prob, p_drop, seed):
 def test_dropout_matches_the_oracle(Nq, Nk, Hq, Hkv, d, p_drop, causal):
     prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=6000 + Nq + Nk)
     check_dropout(prob, p_drop, seed=0x1234ABCD5678 + Nq)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,Nk,Hq,Hkv,d", [(65, 65, 2, 2, 64), (257, 300, 4, 2, 128), (300, 515, 2, 1, 64), (700, 700, 2, 2, 128)])
+def test_dropout_in_half_precision(Nq, Nk, Hq, Hkv, d, causal):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=6050 + Nq + Nk, dtype="f16")
+    check_dropout(prob, 0.25, seed=0x77AA11 + Nk)
 
 
 def test_zero_probability_reproduces_the_plain_entry_points_bitwise():

@@ -27,18 +27,28 @@ def window_mask_gpu(nq, nk, left, right):
 
 
 def check_local(prob, left, right):
-    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    Q, K, V, dO = (pu.to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
     O, L = binding.fa_local_fwd(Q, K, V, prob.scale, left, right)
     dQ, dK, dV = binding.fa_local_bwd(Q, K, V, O, dO, L, prob.scale, left, right)
     torch.cuda.synchronize()
-    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
+    Qf, Kf, Vf, dOf = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     exp = {}
     exp["O"], exp["LSE"] = orc.attention_forward_local(Qf, Kf, Vf, prob.scale, left, right)
     exp["dQ"], exp["dK"], exp["dV"] = orc.attention_backward_local(Qf, Kf, Vf, dOf, prob.scale, left, right)
     ref = pu.reference_batch(Q, K, V, dO, prob.scale, False, M=window_mask_gpu(prob.N, prob.keys, left, right))
     pu.judge(f"window ({left},{right}) {pu.describe(prob)}",
-             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))}, exp, ref, d=prob.d)
+             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))}, exp, ref,
+             dtype=prob.dtype, d=prob.d)
     return O, L, dQ, dK, dV
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq,Nk,left,right", [(65, 65, 3, 3), (300, 1000, 128, 0), (700, 700, 31, 0), (700, 700, 200, 5),
+                                             (515, 515, -1, 40), (515, 515, 256, 256)])
+def test_windows_in_half_precision(Nq, Nk, left, right, d):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=4, Hkv=2, d=d, causal=False, seed=16050 + Nq + Nk + left, dtype="f16")
+    check_local(prob, left, right)
 
 
 @pytest.mark.parametrize("d", [64, 128])

@@ -13,8 +13,8 @@ torch = pytest.importorskip("torch")
 import parity_util as pu  # noqa: E402
 
 
-def make_mask(seed, Bm, Hm, Nq, Nk, kind):
-    """Mask values as bfloat16 bit patterns [Bm, Hm, Nq, Nk]: 'bias' N(0, 2^2); 'bool' 0 / -inf with
+def make_mask(seed, Bm, Hm, Nq, Nk, kind, dtype="bf16"):
+    """Mask values as bit patterns of the element type [Bm, Hm, Nq, Nk]: 'bias' N(0, 2^2); 'bool' 0 / -inf with
     30 % removed; 'mixed' bias with 30 % removed; key 0 always stays (every row keeps one entry,
     also under the causal rule). 'dead' additionally removes whole rows."""
     g = np.random.default_rng(seed)
@@ -27,21 +27,22 @@ def make_mask(seed, Bm, Hm, Nq, Nk, kind):
     if kind == "dead":
         rows = g.random((Bm, Hm, Nq)) < 0.2
         m[rows] = -np.inf
-    return inputs.f32_to_bf16_bits(m)
+    return inputs.f32_to_f16_bits(m) if dtype == "f16" else inputs.f32_to_bf16_bits(m)
 
 
-def mask_to_gpu(bits):
+def mask_to_gpu(bits, dtype="bf16"):
     Bm, Hm, Nq, Nk = bits.shape
-    M = binding.mask_buffer(Bm, Hm, Nq, Nk)
-    M.copy_(pu.to_gpu(bits))
+    M = binding.mask_buffer(Bm, Hm, Nq, Nk, dtype=torch.float16 if dtype == "f16" else torch.bfloat16)
+    M.copy_(pu.to_gpu(bits, dtype))
     return M
 
 
 def check_mask(prob, mbits, fwd_only=False):
-    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
-    M = mask_to_gpu(mbits)
+    Q, K, V, dO = (pu.to_gpu(x, prob.dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    M = mask_to_gpu(mbits, prob.dtype)
     O, L = binding.fa_mask_fwd(Q, K, V, M, prob.scale, prob.causal)
-    Qf, Kf, Vf, dOf, Mf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO, mbits))
+    widen = orc.widen_f16 if prob.dtype == "f16" else orc.widen_bf16
+    Qf, Kf, Vf, dOf, Mf = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO, mbits))
     eO, eL = orc.attention_forward_masked(Qf, Kf, Vf, Mf, prob.scale, prob.causal)
     got = {"O": O, "LSE": L}
     exp = {"O": eO, "LSE": eL}
@@ -52,7 +53,8 @@ def check_mask(prob, mbits, fwd_only=False):
     torch.cuda.synchronize()
     Bm, Hm, Nq, Nk = mbits.shape
     ref = pu.reference_batch(Q, K, V, dO, prob.scale, prob.causal, backward=not fwd_only, M=M[:, :, :, :Nk])
-    res = pu.judge(f"mask {pu.describe(prob)} shared {Bm}x{Hm}", {k: pu.to_f64(v) for k, v in got.items()}, exp, ref, d=prob.d)
+    res = pu.judge(f"mask {pu.describe(prob)} shared {Bm}x{Hm}", {k: pu.to_f64(v) for k, v in got.items()}, exp, ref,
+                   dtype=prob.dtype, d=prob.d)
     return {k: v[0] for k, v in res.items()}
 
 
@@ -63,6 +65,14 @@ def check_mask(prob, mbits, fwd_only=False):
 def test_masked_self_attention(N, kind, d, causal):
     prob = inputs.make_dense(B=2, N=N, Hq=2, Hkv=2, d=d, causal=causal, seed=9000 + N)
     check_mask(prob, make_mask(9100 + N, 2, 2, N, N, kind))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("kind", ["bias", "mixed", "dead"])
+@pytest.mark.parametrize("Nq,Nk,Hq,Hkv,d", [(65, 65, 2, 2, 64), (70, 333, 4, 2, 128), (300, 515, 2, 1, 64), (515, 515, 2, 2, 128)])
+def test_masks_in_half_precision(Nq, Nk, Hq, Hkv, d, kind, causal):
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=9050 + Nq + Nk, dtype="f16")
+    check_mask(prob, make_mask(9060 + Nq, 2, Hq, Nq, Nk, kind, dtype="f16"))
 
 
 @pytest.mark.parametrize("causal", [False, True])
