@@ -302,8 +302,9 @@ int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, con
  * array of bytes [Bm, Hm, ceil(Nq/block), ceil(Nk/block)], rows dense, addressed through the two
  * strides in bytes (0 shares the pattern over sequences or heads); it is read, never written.
  * `block` is a power of two, at least 64 (FA_ERR_SHAPE otherwise). Wavefronts skip the blocks
- * that the pattern removes from their rows (or keys); a workgroup still brings in every key
- * block (row tile) inside its causal range, so time falls with the density but not to zero.
+ * that the pattern removes from their rows (or keys), and a workgroup whose 256 rows (keys) keep
+ * at most half of the key blocks (row tiles) inside its causal range visits only those, so time
+ * falls with the density.
  * Otherwise as fa_cross_fwd / fa_cross_bwd (layouts, workspace, grouped heads, errors).
  * bfloat16, d in {64, 128}; at most 262144 keys and ceil(Nq/32) * (Hq/Hkv) <= 4096
  * (FA_ERR_UNSUPPORTED beyond).

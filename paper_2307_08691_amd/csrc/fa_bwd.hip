@@ -134,8 +134,9 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   constexpr int TILEB = BR * ROWB, BUFB = 2 * TILEB;  // one Q_i (or dO_i) tile; one ring slot = Q_i | dO_i
   constexpr int LS_OFF = QDO_OFF + RING * BUFB;       // [slot][row] floats
   constexpr int DV_OFF = LS_OFF + RING * BR * 4;
-  constexpr int BITS_OFF = DV_OFF + RING * BR * 4;  // LOCAL: one activity bitmap per wavefront (over the tiles it visits)
-  constexpr int SMEM = BITS_OFF + (LOCAL ? 8 * 8 * kPatternWords : 0);
+  constexpr int BITS_OFF = DV_OFF + RING * BR * 4;  // LOCAL: one activity bitmap per wavefront (over the tiles in its range)
+  constexpr int LIST_OFF = BITS_OFF + 8 * 8 * kPatternWords;  // LOCAL: the tiles the workgroup visits, four bytes each
+  constexpr int SMEM = LOCAL ? LIST_OFF + 4 * 64 * kPatternWords : BITS_OFF;
   static_assert(VT_OFF + BC * ROWB <= 65536 && BUFB <= 32768, "immediate offsets must fit 16 bits");
   static_assert(WIDE || 4 * DT * 16 * 64 * 4 <= RING * BUFB, "the final reduction reuses the ring");
   static_assert(SMEM <= 160 * 1024, "LDS of one compute unit");
@@ -204,6 +205,89 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   };
   const Cursor tile0 = {g * p.G, i_first, 0, ((si.tok0 + (long)i_first * BR) * p.Hq + g * p.G) * dh,
                         stat_base + (long)g * p.G * p.lse_head_stride + (long)i_first * BR};
+  // (an entry of the visit list below: the tile's number in that order, and its row tile in the upper half)
+  auto cursor_at = [&](unsigned entry, int slot) {
+    const int tt = entry & 0xffff, it = entry >> 16, hq = g * p.G + tt - (it - i_first) * p.G;
+    return Cursor{hq, it, slot, ((si.tok0 + (long)it * BR) * p.Hq + hq) * dh,
+                  stat_base + (long)hq * p.lse_head_stride + (long)it * BR};
+  };
+
+  // (256 keys per workgroup) Leading tiles in which every score of THIS wavefront's 32 keys is
+  // masked (its keys lie above the tile's last row, or past the end of the sequence), and under a
+  // window trailing ones: the wavefront only keeps up with the copies and the barriers.
+  int skip = 0, t_stop = T;  // this wavefront computes on tiles skip .. t_stop - 1
+  if (j0 + 32 * kgi >= nk) skip = T;
+  else if ((CAUSAL || wr >= 0) && j0 + 32 * kgi > off + (LOCAL ? wr : 0)) {
+    const int first_useful = (j0 + 32 * kgi - off - (LOCAL ? wr : 0)) / BR;  // first row tile that reaches this wavefront's keys
+    skip = (first_useful - i_first) * p.G < T ? (first_useful - i_first) * p.G : T;
+  }
+  if (LOCAL && wl >= 0) {  // one past the last row tile whose rows still see this wavefront's last key
+    const long last_row = (long)j0 + 32 * kgi + 31 - off + wl;
+    const long stop = (last_row / BR + 1 - i_first) * p.G;
+    if (stop < t_stop) t_stop = (int)stop;
+  }
+  if (t_stop < skip) t_stop = skip;
+
+  // Block-sparse pattern: whether this wavefront has anything to do on tile t (row tile
+  // i_first + t / G of query head g G + t % G; its rows lie in one row block of the pattern, its 32
+  // keys in one key block; t inside skip .. t_stop) is one bit of the wavefront's bitmap, gathered
+  // here for every t. The workgroup then visits only the tiles that some wavefront has a bit for:
+  // every wavefront compacts the union of the eight bitmaps into the same list, so neither copies
+  // nor phases are spent on a tile that the pattern removes from all 256 keys.
+  const bool sparse = LOCAL && p.bmask != nullptr;
+  const unsigned* visit = (const unsigned*)(smem + LIST_OFF);
+  int Tv = T;  // tiles the workgroup visits
+  bool listed = false;  // the visit follows the list
+  if (LOCAL && sparse) {
+    unsigned long long* bits = (unsigned long long*)(smem + BITS_OFF) + v * kPatternWords;
+    const uint8_t* bm0 = p.bmask + s * p.bmask_bs + (long)((j0 + 32 * kgi < nk ? j0 + 32 * kgi : nk - 1) >> p.bmask_log2);
+    for (int q = 0; q * 64 < T; q += 4) {  // (four words a round: their loads are in flight together)
+      uint8_t b[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int tt = (q + u) * 64 + lane;
+        const int it = i_first + tt / p.G, hq = g * p.G + tt % p.G;
+        b[u] = tt >= skip && tt < t_stop ? bm0[hq * p.bmask_hs + (long)((it * BR) >> p.bmask_log2) * p.bmask_cols] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(b[u] != 0);
+        if (lane == 0 && (q + u) * 64 < T) bits[q + u] = m;
+      }
+    }
+    lds_barrier();
+    const unsigned long long* all_bits = (const unsigned long long*)(smem + BITS_OFF);
+    int cnt = 0;
+    for (int q = 0; q * 64 < T; ++q) {
+      unsigned long long u = 0;
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) u |= all_bits[ww * kPatternWords + q];
+      const bool on = ((u >> lane) & 1) != 0;
+      const unsigned long long m64 = __builtin_amdgcn_ballot_w64(on);
+      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(m64 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m64, 0u));
+      const int tt = q * 64 + lane;
+      if (on) ((unsigned*)visit)[cnt + before] = (unsigned)tt | ((unsigned)(i_first + tt / p.G) << 16);  // (all eight wavefronts write the same list)
+      cnt += __builtin_popcountll(m64);
+    }
+    // (a visit that the list would shorten by less than half stays the plain one: see the forward kernel)
+    listed = 2 * cnt <= T;
+    if (listed) Tv = cnt;
+  }
+  // The list entry of the tile at position t of the visit (past its end: the last one). Lane l keeps
+  // entry win_base + l, so that a lookup is a lane read; step t asks for positions t .. t + 3.
+  int win_base = 0;
+  unsigned win = LOCAL && listed ? visit[lane] : 0u;
+  auto tile_no = [&](int t) {
+    if (!(LOCAL && listed)) return (unsigned)t;
+    const int tc = t < Tv ? t : Tv - 1;
+    if (tc < 0) return 0u;
+    if ((unsigned)(tc - win_base) >= 64u) {
+      win_base = tc < 8 ? 0 : tc - 8;
+      const int e = win_base + lane;
+      win = visit[e < 64 * kPatternWords ? e : 64 * kPatternWords - 1];
+    }
+    return (unsigned)__builtin_amdgcn_readlane(win, tc - win_base);
+  };
 
   // Q_i, dO_i (line 9) go HBM -> LDS directly; L_i, D_i travel through two registers of the
   // issuing group's first BR threads. The raw statistics are only touched (scaled, masked)
@@ -274,7 +358,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   }
   {
     Cursor c = tile0;
-    for (int t = 0; t < (WIDE ? 2 : 3) && t < T; ++t) {
+    for (int t = 0; t < (WIDE ? 2 : 3) && t < Tv; ++t) {
+      if (LOCAL && listed) c = cursor_at(tile_no(t), t);
       const long first = c.qoff - (long)c.it * BR * qstride;  // row 0 of this head
       char* dst = smem + QDO_OFF + c.slot * BUFB;
       tile_load_async<D, BR, 8, PAD>(dst, a.Q + first, qstride, c.it * BR, n - 1, v, lane, dh / 8);
@@ -548,43 +633,13 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       }
       lds_barrier();
     };
-    // Leading tiles in which every score of THIS wavefront's 32 keys is masked (its keys lie
-    // above the tile's last row, or past the end of the sequence): the wavefront only keeps up
-    // with the copies and the barriers.
-    int skip = 0, t_stop = T;  // this wavefront computes on tiles skip .. t_stop - 1
-    if (j0 + 32 * kgi >= nk) skip = T;
-    else if ((CAUSAL || wr >= 0) && j0 + 32 * kgi > off + (LOCAL ? wr : 0)) {
-      const int first_useful = (j0 + 32 * kgi - off - (LOCAL ? wr : 0)) / BR;  // first row tile that reaches this wavefront's keys
-      skip = (first_useful - i_first) * p.G < T ? (first_useful - i_first) * p.G : T;
-    }
-    if (LOCAL && wl >= 0) {  // one past the last row tile whose rows still see this wavefront's last key
-      const long last_row = (long)j0 + 32 * kgi + 31 - off + wl;
-      const long stop = (last_row / BR + 1 - i_first) * p.G;
-      if (stop < t_stop) t_stop = (int)stop;
-    }
-    if (t_stop < skip) t_stop = skip;
     if constexpr (LOCAL) {
-      // Window and block-sparse pattern: tile by tile. Whether this wavefront has anything to do on
-      // tile t (row tile i_first + t / G of query head g G + t % G; its rows lie in one row block of
-      // the pattern, its 32 keys in one key block) is one bit of the wavefront's bitmap, gathered
-      // here for every t.
-      const bool sparse = p.bmask != nullptr;
-      unsigned long long* bits = (unsigned long long*)(smem + BITS_OFF) + v * kPatternWords;
-      if (sparse) {
-        const uint8_t* bm0 = p.bmask + s * p.bmask_bs + (long)((j0 + 32 * kgi < nk ? j0 + 32 * kgi : nk - 1) >> p.bmask_log2);
-        for (int q = 0; q * 64 < T; ++q) {
-          const int tt = q * 64 + lane;
-          const int it = i_first + tt / p.G, hq = g * p.G + tt % p.G;
-          const bool on = tt < T && bm0[hq * p.bmask_hs + (long)((it * BR) >> p.bmask_log2) * p.bmask_cols] != 0;
-          const unsigned long long m = __builtin_amdgcn_ballot_w64(on);
-          if (lane == 0) bits[q] = m;
-        }
-      }
+      // Window and block-sparse pattern: tile by tile, over the tiles the workgroup visits.
+      const unsigned long long* bits = (const unsigned long long*)(smem + BITS_OFF) + v * kPatternWords;
       int word_q = -1;
       unsigned long long word = 0;
-      auto active = [&](int t) {
-        if (t < skip || t >= t_stop) return false;
-        if (!sparse) return true;
+      auto active = [&](int t) {  // t: a tile's number in the full order
+        if (!sparse) return t >= skip && t < t_stop;
         if ((t >> 6) != word_q) {
           word_q = t >> 6;
           word = bits[word_q];
@@ -604,15 +659,13 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       for (int i = 0; i < AH; ++i) pre[i] = (bf16x8){0};
 #pragma unroll
       for (int tq = 0; tq < QTW; ++tq) Pf[tq][0] = Pf[tq][1] = dSf[tq][0] = dSf[tq][1] = (bf16x8){0};
-      bool was = false;  // tile t - 1 was active
-      for (int t = 0; t < T; ++t) {
-        const bool now = active(t);
+      bool was = false;  // the tile visited before this one was active
+      auto step = [&](int t, bool now) {  // one tile: this wavefront's share of its two phases
         if (was || now) fused_stream();
         end_matrix_phase();
-        if (grp == 0 && t + 2 < T) {
+        if (grp == 0 && t + 2 < Tv) {
           issue_loads(ld);
           pending = ld.slot;
-          advance(ld, 1);
         }
         if (now) {
           phase_v(cur);
@@ -623,8 +676,40 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         }
         lds_barrier();
         prev = cur;
-        advance(cur, 1);
         was = now;
+      };
+      if (!listed) {
+        for (int t = 0; t < Tv; ++t) {
+          step(t, active(t));
+          advance(ld, 1);
+          advance(cur, 1);
+        }
+      } else {
+        // Following the list, the cursors of positions t, t + 1, t + 2 are carried along and one new
+        // one (position t + 3) is made per step: by one advance when that tile follows the one before
+        // it in the full order, which inside a block of the pattern it does, from scratch otherwise.
+        auto follow = [&](const Cursor& from, unsigned from_entry, unsigned entry, int slot) {
+          if ((entry & 0xffff) == (from_entry & 0xffff) + 1) {
+            Cursor c = from;
+            advance(c, 1);
+            return c;
+          }
+          return cursor_at(entry, slot);
+        };
+        const unsigned e0 = tile_no(0), e1 = tile_no(1);
+        unsigned ld_entry = tile_no(2);
+        cur = cursor_at(e0, 0);
+        Cursor nx = follow(cur, e0, e1, 1);
+        ld = follow(nx, e1, ld_entry, 2);
+        for (int t = 0; t < Tv; ++t) {
+          step(t, active(tile_no(t) & 0xffff));
+          const unsigned e3 = tile_no(t + 3);
+          const Cursor c3 = follow(ld, ld_entry, e3, (t + 3) % RING);
+          cur = nx;
+          nx = ld;
+          ld = c3;
+          ld_entry = e3;
+        }
       }
       if (was) {
         __builtin_amdgcn_s_setprio(2);
@@ -766,8 +851,10 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   constexpr int MASKB = 32 * BC * 2;             // one wavefront's piece of M for one block
   constexpr int MPW = MASK ? MASKB / 1024 : 0;  // copies per wavefront per block
 
-  // (LOCAL: behind the ring, one activity bitmap per wavefront, as in the forward kernel)
-  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0) + (LOCAL ? 8 * 8 * kPatternWords : 0)];
+  // (LOCAL: behind the ring, one activity bitmap per wavefront and the list of the key blocks that
+  // the workgroup visits, as in the forward kernel)
+  constexpr int BITSB = 8 * 8 * kPatternWords, LISTB = 2 * 64 * kPatternWords;
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0) + (LOCAL ? BITSB + LISTB : 0)];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -849,14 +936,66 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   if (LOCAL && wl >= 0 && i0 + off > wl) jb = (i0 + off - wl) / BC;
   if (ncol < jb) ncol = jb;
 
+  // block-sparse pattern: the wavefront's bitmap over the key blocks, and the list of the blocks
+  // that any of the eight bitmaps keeps, which is what the workgroup walks (see the forward kernel)
+  const unsigned long long* pattern_bits = (const unsigned long long*)(smem + RING * BUFB) + w * kPatternWords;
+  const unsigned short* visit = (const unsigned short*)(smem + RING * BUFB + BITSB);
+  const bool sparse = LOCAL && p.bmask != nullptr;
+  int tb = jb, tend = ncol;  // positions of the walk; position t stands for block t unless the pattern thins the walk
+  bool listed = false;       // the walk follows the list
+  if (LOCAL && sparse) {
+    const int r0 = wrow0 < n ? wrow0 : n - 1;
+    const uint8_t* bm_row = p.bmask + s * p.bmask_bs + h * p.bmask_hs + (long)(r0 >> p.bmask_log2) * p.bmask_cols;
+    for (int q = jb >> 6; q * 64 < ncol; q += 4) {  // (four words a round: their loads are in flight together)
+      uint8_t b[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int jj = (q + u) * 64 + lane;
+        b[u] = jj < ncol ? bm_row[(jj * BC) >> p.bmask_log2] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned long long bits = __builtin_amdgcn_ballot_w64(b[u] != 0);
+        if (lane == 0 && (q + u) * 64 < ncol) ((unsigned long long*)pattern_bits)[q + u] = bits;
+      }
+    }
+    lds_barrier();
+    const unsigned long long* all_bits = (const unsigned long long*)(smem + RING * BUFB);
+    int cnt = 0;
+    for (int q = jb >> 6; q * 64 < ncol; ++q) {
+      unsigned long long u = 0;
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) u |= all_bits[ww * kPatternWords + q];
+      const int jj = q * 64 + lane;
+      const bool on = ((u >> lane) & 1) != 0 && jj >= jb && jj < ncol;
+      const unsigned long long m64 = __builtin_amdgcn_ballot_w64(on);
+      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(m64 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m64, 0u));
+      if (on) ((unsigned short*)visit)[cnt + before] = (unsigned short)jj;  // (all eight wavefronts write the same list)
+      cnt += __builtin_popcountll(m64);
+    }
+    // (a walk that the list would shorten by less than half stays the plain one: a thinned walk pays
+    // for its lookups in every phase, and a block nobody computes on costs little more than its copies)
+    listed = 2 * cnt <= ncol - jb;
+    if (listed) {
+      tb = 0;
+      tend = cnt;
+    }
+  }
+  // the block at position t (past the end of the walk: any block; its tiles are copied and never read)
+  auto blk = [&](int t) {
+    if (!(LOCAL && listed)) return t;
+    const int tc = t < tend ? t : tend - 1;
+    return tc < 0 ? 0 : __builtin_amdgcn_readfirstlane((int)visit[tc]);
+  };
+
   // tile copies: group 1 brings in the K tiles, group 0 the V tiles, each at the start of its
   // own vector phase (see the forward kernel)
   TileLoader<D, BC, 4, PAD> loader;
   loader.init(kstride, w & 3, lane, dh / 8);
   constexpr int TPW = TileLoader<D, BC, 4, PAD>::PER;
-  auto issue_tile = [&](int j) {
-    char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
-    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
+  auto issue_tile = [&](int t) {  // the block at position t of the walk
+    char* dst = smem + (t % RING) * BUFB + (grp == 0 ? TILEB : 0);
+    loader.load(dst, grp == 0 ? Vb : Kb, kstride, blk(t) * BC, nk - 1, w & 3, lane);
   };
   char* mbuf = smem + RING * BUFB + w * MASKB;
   const __bf16* Mb = MASK ? p.mask + s * p.mask_bs + h * p.mask_hs : nullptr;
@@ -877,8 +1016,8 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       }
     }
   };
-  issue_tile(jb);
-  issue_tile(jb + 1);
+  issue_tile(tb);
+  issue_tile(tb + 1);
   issue_mask(jb);
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
@@ -904,19 +1043,6 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   // last and (window) first visible column of this lane's row
   const int lim_row = CAUSAL || wr >= 0 ? (row + off + (LOCAL ? wr : 0) < nk - 1 ? row + off + (LOCAL ? wr : 0) : nk - 1) : nk - 1;
   const int lo_row = wl >= 0 ? row + off - wl : 0;
-  // block-sparse pattern: the wavefront's bitmap over the key blocks (see the forward kernel)
-  const unsigned long long* pattern_bits = (const unsigned long long*)(smem + RING * BUFB) + w * kPatternWords;
-  const bool sparse = LOCAL && p.bmask != nullptr;
-  if (LOCAL && sparse) {
-    const int r0 = wrow0 < n ? wrow0 : n - 1;
-    const uint8_t* bm_row = p.bmask + s * p.bmask_bs + h * p.bmask_hs + (long)(r0 >> p.bmask_log2) * p.bmask_cols;
-    for (int q = 0; q * 64 < ncol_all; ++q) {
-      const int jj = q * 64 + lane;
-      const bool on = jj < ncol_all && bm_row[(jj * BC) >> p.bmask_log2] != 0;
-      const unsigned long long bits = __builtin_amdgcn_ballot_w64(on);
-      if (lane == 0) ((unsigned long long*)pattern_bits)[q] = bits;
-    }
-  }
   int pattern_q = -1;                 // which word of the bitmap `pattern_word` holds
   unsigned long long pattern_word = 0;
   // a block is skipped by a wavefront when every score it would produce is masked
@@ -940,11 +1066,11 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   bf16x8 dSf[2][2];
 
   // ================= matrix phase j =================
-  auto matrix_phase = [&](int j) {
+  auto matrix_phase = [&](int t) {
     __builtin_amdgcn_s_setprio(2);
-    if (j < ncol && wave_sees(j)) {
+    if (t < tend && wave_sees(blk(t))) {
       // ---- S^T = K_j Q_i^T (line 10), dP^T = V_j dO_i^T (line 13)
-      const int zk = zrow + (j % RING) * BUFB;
+      const int zk = zrow + (t % RING) * BUFB;
       S[0] = S[1] = dP[0] = dP[1] = (f32x16){0};
       mfma_stream<4 * KS, MASK && D == 128 ? 2 : 4, 1>(  // (mask, d = 128: shorter operand prefetch, the registers go to M)
           [&](int i) {
@@ -958,9 +1084,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
             else S[kt] = mfma32<F16>(x, Qf[ks], S[kt]);
           });
     }
-    if (j > jb && wave_sees(j - 1)) {
-      // ---- dQ_i^T += K_{j-1}^T dS^T (line 15)
-      const int kb = ((j - 1) % RING) * BUFB;
+    if (t > tb && wave_sees(blk(t - 1))) {
+      // ---- dQ_i^T += K_{j-1}^T dS^T (line 15), j - 1 the block before this one in the walk
+      const int kb = ((t - 1) % RING) * BUFB;
       const int zc0 = zcol[0] + kb, zc1 = zcol[1] + kb;
       mfma_stream<4 * DT, MASK && D == 128 ? 2 : 3, 2>(
           [&](int i) {
@@ -976,8 +1102,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
                                            (p.drop_seed ^ (uint32_t)(s * p.Hq + h) * kDropHead)
                                      : 0u;
   // ================= vector phase j: P = exp(S - L) (line 11), dS = P o (dP - D) (line 14) =================
-  auto vector_phase = [&](int j) {
-    if (j >= ncol || !wave_sees(j)) return;
+  auto vector_phase = [&](int t) {
+    const int j = blk(t);
+    if (t >= tend || !wave_sees(j)) return;
     const int col0 = j * BC;
     const bool need_mask = (CAUSAL && col0 + BC - 1 > wrow0 + off) || (col0 + BC > nk) ||
                            (LOCAL && ((wr >= 0 && col0 + BC - 1 > wrow0 + off + wr) || (wl >= 0 && col0 < wrow_last - wl)));
@@ -1026,9 +1153,9 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     }
   };
 
-  // phases: see the forward kernel
+  // phases: see the forward kernel (j counts positions of the walk)
   if (grp == 0) {
-    for (int j = jb; j <= ncol; ++j) {
+    for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
       lds_barrier();
       issue_tile(j + 2);
@@ -1038,13 +1165,13 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       lds_barrier();
     }
   } else {
-    issue_tile(jb + 2);
+    issue_tile(tb + 2);
     lds_barrier();
-    for (int j = jb; j <= ncol; ++j) {
+    for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
       wait_vmem_upto<TPW + MPW>();
       lds_barrier();
-      if (j < ncol) {
+      if (j < tend) {
         issue_tile(j + 3);
         vector_phase(j);
         issue_mask(j + 1);
@@ -1057,7 +1184,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     // dQ_i through the one ring slot that is neither in use nor the target of a copy issued
     // past the last block, as whole rows (see store_rows_via_lds)
     static_assert(RING == 4 && BUFB / 8 == 32 * D, "the staging area of a wavefront is an eighth of a ring slot");
-    char* stg = smem + ((ncol + 3) % RING) * BUFB + w * (BUFB / 8);
+    char* stg = smem + ((tend + 3) % RING) * BUFB + w * (BUFB / 8);
     __bf16* op = a.dQ + ((si.tok0 + wrow0) * p.Hq + h) * dh;
     const long ostride = (long)p.Hq * dh;
     int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop

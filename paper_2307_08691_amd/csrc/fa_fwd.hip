@@ -113,8 +113,10 @@ __global__ __launch_bounds__(512)
   constexpr int MPW = MASK ? MASKB / 1024 : 0;  // copies per wavefront per block
 
   // (LOCAL: behind the ring, one bitmap of kPatternWords 64-bit words per wavefront: which key blocks
-  // the block-sparse pattern leaves to its rows)
-  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0) + (LOCAL ? 8 * 8 * kPatternWords : 0)];
+  // the block-sparse pattern leaves to its rows; behind them the list of the key blocks that it
+  // leaves to any row of the workgroup, two bytes each)
+  constexpr int BITSB = 8 * 8 * kPatternWords, LISTB = 2 * 64 * kPatternWords;
+  __shared__ __attribute__((aligned(1024))) char smem[RING * BUFB + (MASK ? 8 * MASKB : 0) + (LOCAL ? BITSB + LISTB : 0)];
 
   const Problem& p = a.p;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -190,6 +192,63 @@ __global__ __launch_bounds__(512)
   }
   if (ncol < jb) ncol = jb;  // nothing visible in this share: the loops below still run once
 
+  // Block-sparse pattern: the wavefront's 32 rows lie in one row block of the pattern (blocks are
+  // at least 64 rows and the wavefront starts at a multiple of 32), so whether it has anything to
+  // do in key block j is one bit, gathered here for every j (one byte per lane and ballot) into
+  // the wavefront's bitmap. It is read back a word at a time.
+  // The workgroup then walks only the blocks that some wavefront of it has a bit for: every
+  // wavefront compacts the union of the eight bitmaps (inside jb .. ncol) into the same list, so
+  // neither copies nor phases are spent on a block that the pattern removes from all 256 rows.
+  const unsigned long long* pattern_bits = (const unsigned long long*)(smem + RING * BUFB) + w * kPatternWords;
+  const unsigned short* visit = (const unsigned short*)(smem + RING * BUFB + BITSB);
+  const bool sparse = LOCAL && p.bmask != nullptr;
+  int tb = jb, tend = ncol;  // positions of the walk; position t stands for block t unless the pattern thins the walk
+  bool listed = false;       // the walk follows the list
+  if (LOCAL && sparse) {
+    const int r0 = prow0 < n ? prow0 : n - 1;
+    const uint8_t* bm_row = p.bmask + s * p.bmask_bs + bc.head * p.bmask_hs + (long)(r0 >> p.bmask_log2) * p.bmask_cols;
+    for (int q = jb >> 6; q * 64 < ncol; q += 4) {  // (four words a round: their loads are in flight together)
+      uint8_t b[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int jj = (q + u) * 64 + lane;
+        b[u] = jj < ncol ? bm_row[(jj * BC) >> p.bmask_log2] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned long long bits = __builtin_amdgcn_ballot_w64(b[u] != 0);
+        if (lane == 0 && (q + u) * 64 < ncol) ((unsigned long long*)pattern_bits)[q + u] = bits;
+      }
+    }
+    lds_barrier();
+    const unsigned long long* all_bits = (const unsigned long long*)(smem + RING * BUFB);
+    int cnt = 0;
+    for (int q = jb >> 6; q * 64 < ncol; ++q) {
+      unsigned long long u = 0;
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) u |= all_bits[ww * kPatternWords + q];
+      const int jj = q * 64 + lane;
+      const bool on = ((u >> lane) & 1) != 0 && jj >= jb && jj < ncol;
+      const unsigned long long m64 = __builtin_amdgcn_ballot_w64(on);
+      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(m64 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m64, 0u));
+      if (on) ((unsigned short*)visit)[cnt + before] = (unsigned short)jj;  // (all eight wavefronts write the same list)
+      cnt += __builtin_popcountll(m64);
+    }
+    // (a walk that the list would shorten by less than half stays the plain one: a thinned walk pays
+    // for its lookups in every phase, and a block nobody computes on costs little more than its copies)
+    listed = 2 * cnt <= ncol - jb;
+    if (listed) {
+      tb = 0;
+      tend = cnt;
+    }
+  }
+  // the block at position t (past the end of the walk: any block; its tiles are copied and never read)
+  auto blk = [&](int t) {
+    if (!(LOCAL && listed)) return t;
+    const int tc = t < tend ? t : tend - 1;
+    return tc < 0 ? 0 : __builtin_amdgcn_readfirstlane((int)visit[tc]);
+  };
+
   // Tile loads. Issuing a tile's copies stalls the issuing wavefronts for a few hundred
   // cycles (the memory pipeline takes 16 bytes x 64 lanes at a time), so a wavefront only
   // issues copies at the start of its VECTOR phase, while the other group keeps the MFMA pipe
@@ -199,9 +258,9 @@ __global__ __launch_bounds__(512)
   TileLoader<D, BC, 4, PAD> loader;
   loader.init(kstride, w & 3, lane, dh / 8);
   constexpr int TPW = TileLoader<D, BC, 4, PAD>::PER;  // copies per wavefront per tile
-  auto issue_tile = [&](int j) {  // group 0: V_j, group 1: K_j
-    char* dst = smem + (j % RING) * BUFB + (grp == 0 ? TILEB : 0);
-    loader.load(dst, grp == 0 ? Vb : Kb, kstride, j * BC, nk - 1, w & 3, lane);
+  auto issue_tile = [&](int t) {  // the block at position t of the walk; group 0: its V_j, group 1: its K_j
+    char* dst = smem + (t % RING) * BUFB + (grp == 0 ? TILEB : 0);
+    loader.load(dst, grp == 0 ? Vb : Kb, kstride, blk(t) * BC, nk - 1, w & 3, lane);
   };
   // MASK: this wavefront's rows of M, columns of block j (rows and columns clamped into the
   // tensor: what lies past the end is never used). Issued unconditionally, once per vector
@@ -225,9 +284,9 @@ __global__ __launch_bounds__(512)
       }
     }
   };
-  {  // blocks 0 and 1: both tiles, split over the two groups as above
-    issue_tile(jb);
-    issue_tile(jb + 1);
+  {  // the first two blocks: both tiles, split over the two groups as above
+    issue_tile(tb);
+    issue_tile(tb + 1);
     issue_mask(jb);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) touch(Qf[ks]);
@@ -252,22 +311,6 @@ __global__ __launch_bounds__(512)
   // last and (window) first visible column of this lane's row
   const int lim_row = CAUSAL || wr >= 0 ? (row + off + (LOCAL ? wr : 0) < nk - 1 ? row + off + (LOCAL ? wr : 0) : nk - 1) : nk - 1;
   const int lo_row = wl >= 0 ? row + off - wl : 0;
-  // Block-sparse pattern: the wavefront's 32 rows lie in one row block of the pattern (blocks are
-  // at least 64 rows and the wavefront starts at a multiple of 32), so whether it has anything to
-  // do in key block j is one bit, gathered here for every j (one byte per lane and ballot) into
-  // the wavefront's bitmap. It is read back a word at a time.
-  const unsigned long long* pattern_bits = (const unsigned long long*)(smem + RING * BUFB) + w * kPatternWords;
-  const bool sparse = LOCAL && p.bmask != nullptr;
-  if (LOCAL && sparse) {
-    const int r0 = prow0 < n ? prow0 : n - 1;
-    const uint8_t* bm_row = p.bmask + s * p.bmask_bs + bc.head * p.bmask_hs + (long)(r0 >> p.bmask_log2) * p.bmask_cols;
-    for (int q = 0; q * 64 < ncol_all; ++q) {
-      const int jj = q * 64 + lane;
-      const bool on = jj < ncol_all && bm_row[(jj * BC) >> p.bmask_log2] != 0;
-      const unsigned long long bits = __builtin_amdgcn_ballot_w64(on);
-      if (lane == 0) ((unsigned long long*)pattern_bits)[q] = bits;
-    }
-  }
   int pattern_q = -1;                 // which word of the bitmap `pattern_word` holds
   unsigned long long pattern_word = 0;
   // a block is skipped by a wavefront when every score it would produce is masked
@@ -295,19 +338,19 @@ __global__ __launch_bounds__(512)
                                      : 0u;
 
   // ================= matrix phase j: S^T of block j, O^T update with block j - 1 =================
-  auto matrix_phase = [&](int j) {
+  auto matrix_phase = [&](int t) {
     __builtin_amdgcn_s_setprio(FA_FWD_MATRIX_PRIO);  // the MFMA stream must not wait behind the other group's VALU work
-    if (wave_on && j < ncol && wave_sees(j)) {
+    if (wave_on && t < tend && wave_sees(blk(t))) {
       // ---- S^T = K_j Q_i^T (Algorithm 1, line 8)
-      const int zk = zrow + (j % RING) * BUFB;
+      const int zk = zrow + (t % RING) * BUFB;
       S[0] = S[1] = (f32x16){0};
       mfma_stream<2 * KS, AHEAD_QK, 1>(
           [&](int i) { return lds_b128(smem, (zk ^ (32 * (i >> 1))) + (i & 1) * 32 * ROWB); },
           [&](int i, bf16x8 x) { S[i & 1] = mfma32<F16>(x, Qf[i >> 1], S[i & 1]); });
     }
-    if (wave_on && j > jb && wave_sees(j - 1)) {
-      // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10)
-      const int vb = ((j - 1) % RING) * BUFB + TILEB;
+    if (wave_on && t > tb && wave_sees(blk(t - 1))) {
+      // ---- O^T += V_{j-1}^T P^T (Algorithm 1, line 10), j - 1 the block before this one in the walk
+      const int vb = ((t - 1) % RING) * BUFB + TILEB;
       const int zv0 = zcol[0] + vb, zv1 = zcol[1] + vb;
       mfma_stream<4 * DT, AHEAD_PV, 2>(
           [&](int i) {
@@ -320,8 +363,9 @@ __global__ __launch_bounds__(512)
   };
 
   // ================= vector phase j: online softmax of block j (Algorithm 1, line 9) =================
-  auto vector_phase = [&](int j) {
-    if (!wave_on || j >= ncol || !wave_sees(j)) return;
+  auto vector_phase = [&](int t) {
+    const int j = blk(t);
+    if (!wave_on || t >= tend || !wave_sees(j)) return;
     const int col0 = j * BC;
     if constexpr (MASK) {
       wait_vmem_upto<TPW>();  // the copies of this piece of M are older than this phase's tile copies
@@ -396,7 +440,7 @@ __global__ __launch_bounds__(512)
     // The first block of a row (m = -inf) always takes the second path, and so do the
     // instantiations in which a row may still have seen no key (split keys, elementwise mask)
     // and the one that has no registers left to keep S beside the exponentials.
-    bool advance = !FAST || j == jb;
+    bool advance = !FAST || t == tb;
     if (!advance) {
       exponentials(m * cs);
       advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << kFwdLazyLog2)) != 0;
@@ -436,8 +480,9 @@ __global__ __launch_bounds__(512)
   // requested (by group 1) at phi = 2m and first read at phi = 2m + 4; V_{m+2} is requested
   // (by group 0) at phi = 2m + 1 and first read at phi = 2m + 6. A group waits, at the end of
   // a later phase of its own, until only its newest tile is still in flight.
+  // (j counts positions of the walk: the blocks themselves unless a pattern thins the walk)
   if (grp == 0) {
-    for (int j = jb; j <= ncol; ++j) {
+    for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
       lds_barrier();
       issue_tile(j + 2);
@@ -447,13 +492,13 @@ __global__ __launch_bounds__(512)
       lds_barrier();
     }
   } else {
-    issue_tile(jb + 2);
+    issue_tile(tb + 2);
     lds_barrier();
-    for (int j = jb; j <= ncol; ++j) {
+    for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
       wait_vmem_upto<TPW + MPW>();
       lds_barrier();
-      if (j < ncol) {
+      if (j < tend) {
         issue_tile(j + 3);
         vector_phase(j);
         issue_mask(j + 1);
@@ -490,7 +535,7 @@ __global__ __launch_bounds__(512)
     // O through the ring slot that neither holds a block still in use nor receives one of the
     // copies issued past the last block (those fill the three slots after block ncol - 1)
     static_assert(RING == 4 && BUFB / 8 == 32 * D, "the staging area of a wavefront is an eighth of a ring slot");
-    char* stg = smem + ((ncol + 3) % RING) * BUFB + w * (BUFB / 8);
+    char* stg = smem + ((tend + 3) % RING) * BUFB + w * (BUFB / 8);
     __bf16* op = a.O + ((si.tok0 + prow0) * p.Hq + h) * dh;
     const long ostride = (long)p.Hq * dh;
     int ln = lane;  // recomputed here: nothing of the staging addresses is to live across the main loop

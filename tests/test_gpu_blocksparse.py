@@ -134,12 +134,25 @@ def test_bad_patterns_are_rejected():
 
 
 @pytest.mark.timeout(600)
-def test_full_size_pattern_sampled_units():
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d,block,density", [(128, 64, 0.1), (64, 64, 0.1), (128, 256, 0.2)])
+def test_thin_patterns_with_long_visit_lists(d, block, density, causal):
+    """Patterns thin enough that the workgroups walk their compacted lists of blocks, long enough that
+    a list has a few hundred entries (4096 tokens, four query heads per key/value head: 512 row tiles
+    per key block at d = 128), with a pattern of its own per query head."""
+    prob = inputs.make_cross(B=1, Nq=4096, Nk=4096, Hq=4, Hkv=1, d=d, causal=causal, seed=17700 + d + block)
+    check_blocksparse(prob, draw_pattern(17710 + d + block, 1, 4, 4096, 4096, block, density), block)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["blocksparse_d128_n8k_causal_half", "blocksparse_d128_n8k_causal_eighth"])
+def test_full_size_pattern_sampled_units(name):
     """The benchmark shape (B=2, N=8192, 16 heads of 128, causal) under a pattern of 128 x 128 blocks,
-    one per head, half of the blocks below the diagonal removed; the diagonal and the first key block stay."""
-    prob = inputs.make_config("blocksparse_d128_n8k_causal_half")
+    one per head, half (seven eighths) of the blocks below the diagonal removed; the diagonal and the
+    first key block stay."""
+    prob = inputs.make_config(name)
     N, block = prob.N, prob.meta["block_pattern"]["block"]
-    bm = inputs.block_pattern(prob.meta["block_pattern"]["seed"], 1, prob.Hq, N, N, block, 0.5, True)
+    bm = inputs.block_pattern(prob.meta["block_pattern"]["seed"], 1, prob.Hq, N, N, block, prob.meta["block_pattern"]["density"], True)
     Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     BM = torch.from_numpy(bm.astype(np.uint8)).cuda()
     O, L = binding.fa_blocksparse_fwd(Q, K, V, BM, block, prob.scale, True)
