@@ -74,6 +74,8 @@ Readings taken where the text is silent or inconsistent:
         entries, rows counted from query 0 and keys from key 0; an entry of S is kept iff
         its block is set (and the causal rule, if asked for, keeps it).
     A row left without entries has P = 0, O = 0, L = -inf, as with the elementwise mask.
+    In a packed ragged batch the window applies inside each sequence, positions counted from
+    the sequence's first token (one length per sequence, so p = r).
 
   * FP8 operands (section 5 names FP8 as a direction; no algorithm is given). Reading: Q, K, V
     arrive quantised to OCP FP8 E4M3 (1 sign, 4 exponent, 3 significand bits, bias 7, largest
@@ -576,6 +578,31 @@ def attention_backward_local(Q, K, V, dO, scale, left, right):
     """Dense batch backward with the window (left, right): dQ, dK, dV."""
     vis = window_visible(Q.shape[1], K.shape[1], left, right)
     return _pattern_batch(Q, K, V, dO, scale, False, lambda b, h: vis)[2:]
+
+
+def varlen_forward_local(Q, K, V, cu_seqlens, scale, left, right):
+    """Packed ragged forward with the window (left, right): every sequence is its own attention
+    problem and positions count from its start. Q [T,Hq,d], K,V [T,Hkv,d]; returns O [T,Hq,d], L [Hq,T]."""
+    T, Hq, d = Q.shape
+    O = np.zeros((T, Hq, d), dtype=np.float64)
+    L = np.zeros((Hq, T), dtype=np.float64)
+    for s in range(len(cu_seqlens) - 1):
+        a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        if e > a:
+            o, lse = attention_forward_local(Q[None, a:e], K[None, a:e], V[None, a:e], scale, left, right)
+            O[a:e], L[:, a:e] = o[0], lse[0]
+    return O, L
+
+
+def varlen_backward_local(Q, K, V, dO, cu_seqlens, scale, left, right):
+    """Packed ragged backward with the window (left, right): dQ [T,Hq,d], dK, dV [T,Hkv,d]."""
+    dQ, dK, dV = np.zeros(Q.shape), np.zeros(K.shape), np.zeros(V.shape)
+    for s in range(len(cu_seqlens) - 1):
+        a, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        if e > a:
+            dq, dk, dv = attention_backward_local(Q[None, a:e], K[None, a:e], V[None, a:e], dO[None, a:e], scale, left, right)
+            dQ[a:e], dK[a:e], dV[a:e] = dq[0], dk[0], dv[0]
+    return dQ, dK, dV
 
 
 def attention_forward_blocksparse(Q, K, V, scale, causal, block_mask, block):

@@ -1068,6 +1068,55 @@ def test_pattern_batch_wrappers_map_heads_and_shared_masks():
         assert np.array_equal(Ol[1, :, h], o) and np.array_equal(Ll[1, h], lse)
 
 
+def test_ragged_window_against_scalar_loops_and_its_reductions():
+    """Packed sequences under a window: brute force over (sequence, head, row) with the window
+    counted from the start of each sequence; a window that binds nothing is the ragged oracle
+    without one; (none, 0) is its causal form; another sequence's tokens change nothing; the
+    gradients are the finite differences of sum(O * dO)."""
+    g = np.random.default_rng(4711)
+    lens, Hq, Hkv, d, left, right, scale = [5, 0, 9, 1], 4, 2, 3, 2, 1, 0.6
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    Q, dO = g.standard_normal((T, Hq, d)), g.standard_normal((T, Hq, d))
+    K, V = g.standard_normal((T, Hkv, d)), g.standard_normal((T, Hkv, d))
+    O, L = orc.varlen_forward_local(Q, K, V, cu, scale, left, right)
+    for s_, n in enumerate(lens):
+        a = int(cu[s_])
+        for h in range(Hq):
+            for r in range(n):
+                cols = [c for c in range(n) if r - left <= c <= r + right]
+                sc = [scale * sum(Q[a + r, h, t] * K[a + c, h // 2, t] for t in range(d)) for c in cols]
+                mx = max(sc)
+                den = sum(math.exp(x - mx) for x in sc)
+                assert abs(L[h, a + r] - (mx + math.log(den))) < 1e-12
+                for t in range(d):
+                    want = sum(math.exp(x - mx) / den * V[a + c, h // 2, t] for x, c in zip(sc, cols))
+                    assert abs(O[a + r, h, t] - want) < 1e-12
+    for (l, r, causal) in ((100, 100, False), (-1, -1, False), (-1, 0, True), (9, 0, True)):
+        O1, L1 = orc.varlen_forward_local(Q, K, V, cu, scale, l, r)
+        O2, L2 = orc.varlen_forward(Q, K, V, cu, scale, causal)
+        assert np.allclose(O1, O2, atol=1e-13) and np.allclose(L1, L2, atol=1e-13)
+        for x, y in zip(orc.varlen_backward_local(Q, K, V, dO, cu, scale, l, r), orc.varlen_backward(Q, K, V, dO, cu, scale, causal)):
+            assert np.allclose(x, y, atol=1e-13)
+    K2, V2 = K.copy(), V.copy()
+    K2[:5] += 1.0
+    V2[:5] -= 2.0
+    O3, L3 = orc.varlen_forward_local(Q, K2, V2, cu, scale, left, right)
+    assert np.array_equal(O3[5:], O[5:]) and np.array_equal(L3[:, 5:], L[:, 5:]) and not np.allclose(O3[:5], O[:5])
+    dQ, dK, dV = orc.varlen_backward_local(Q, K, V, dO, cu, scale, left, right)
+    f = lambda q, k, v: float(np.sum(orc.varlen_forward_local(q, k, v, cu, scale, left, right)[0] * dO))  # noqa: E731
+    eps = 1e-6
+    for (X, G, which) in ((Q, dQ, 0), (K, dK, 1), (V, dV, 2)):
+        for idx in ((0, 0, 0), (7, 1, 2), (T - 1, 0, 1)):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[idx] += eps
+            Xm[idx] -= eps
+            args_p = [Q, K, V]
+            args_m = [Q, K, V]
+            args_p[which], args_m[which] = Xp, Xm
+            assert abs((f(*args_p) - f(*args_m)) / (2 * eps) - G[idx]) < 1e-7
+
+
 # ---------------------------------------------------------------------------
 # FP8 (E4M3) inputs
 # ---------------------------------------------------------------------------
