@@ -294,6 +294,25 @@ int fa_local_bwd(const void* Q, const void* K, const void* V, const void* O, con
                  int window_left, int window_right, void* stream);
 
 /*
+ * Local attention over a packed ragged batch: fa_varlen_fwd / fa_varlen_bwd with the window of
+ * fa_local_fwd / fa_local_bwd applied inside every sequence, positions counted from the sequence's
+ * first token (one length per sequence, so query r stands at position r). Layouts, cu_seqlens,
+ * max_seqlen, workspace (fa_varlen_bwd_workspace_bytes) and errors as for fa_varlen_fwd /
+ * fa_varlen_bwd; window arguments as for fa_local_fwd. bfloat16, d in {64, 128}
+ * (FA_ERR_UNSUPPORTED otherwise) unless the bounds reduce to plain or causal attention.
+ */
+int fa_varlen_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                        const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                        int Hq, int Hkv, int d, float scale,
+                        int window_left, int window_right, void* stream);
+int fa_varlen_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* LSE, void* dQ, void* dK, void* dV,
+                        void* workspace, size_t workspace_bytes,
+                        const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                        int Hq, int Hkv, int d, float scale,
+                        int window_left, int window_right, void* stream);
+
+/*
  * Block-sparse attention (section 5 names it beside local attention). Reading: `block_mask` holds
  * one byte per block of `block` x `block` entries of S, row blocks counted from query 0 and key
  * blocks from key 0; an entry of S takes part in the softmax iff its block's byte is non-zero

@@ -66,6 +66,9 @@ SIGNATURES = {
     "fa_local_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_varlen_local_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_varlen_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
+                            [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_blocksparse_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_blocksparse_fwd_f16": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_blocksparse_bwd": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int] +
@@ -234,6 +237,16 @@ def fa_local_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right,
 def fa_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0, f16=False) -> int:
     fn = load().fa_local_bwd_f16 if f16 else load().fa_local_bwd
     return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream)
+
+
+def fa_varlen_local_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left, right, stream=0) -> int:
+    return load().fa_varlen_local_fwd(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left, right, stream)
+
+
+def fa_varlen_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale,
+                            left, right, stream=0) -> int:
+    return load().fa_varlen_local_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv,
+                                      d, scale, left, right, stream)
 
 
 def fa_blocksparse_fwd_raw(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block, bs, hs, stream=0, f16=False) -> int:
@@ -597,6 +610,29 @@ def fa_local_bwd(Q, K, V, O, dO, LSE, scale: float, window_left: int, window_rig
     _check(fa_local_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                             _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, window_left, window_right,
                             _stream(), x.et == torch.float16))
+    return dQ, dK, dV
+
+
+def fa_varlen_local_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, window_left: int, window_right: int,
+                        O=None, LSE=None):
+    """Packed ragged forward with the sliding window of fa_local_fwd inside every sequence. Q [T,Hq,d],
+    K,V [T,Hkv,d] bf16; cu_seqlens int32 on the GPU."""
+    x = _packed(Q, K, V, cu_seqlens)
+    O, LSE = _fwd_outputs(x, O, LSE)
+    _check(fa_varlen_local_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), x.nseq, x.Tq,
+                                   max_seqlen, x.Hq, x.Hkv, x.d, scale, window_left, window_right, _stream()))
+    return O, LSE
+
+
+def fa_varlen_local_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, window_left: int,
+                        window_right: int, dQ=None, dK=None, dV=None, workspace=None):
+    """Backward of fa_varlen_local_fwd for the same window."""
+    x = _packed(Q, K, V, cu_seqlens)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
+    _check(fa_varlen_local_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                                   _ptr(dV), _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen, x.Hq,
+                                   x.Hkv, x.d, scale, window_left, window_right, _stream()))
     return dQ, dK, dV
 
 

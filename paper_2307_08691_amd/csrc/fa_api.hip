@@ -330,7 +330,7 @@ static int varlen_fwd(const void* Q, const void* K, const void* V, void* O, floa
                       void* stream, const Options& opt) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
   if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, !opt.dropout)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.window))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
   return run_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, max_seqlen, max_seqlen, total_tokens, Hq, Hkv, d, scale, causal,
                  stream, 0, nullptr, nullptr, opt);
@@ -362,7 +362,7 @@ static int varlen_bwd(const void* Q, const void* K, const void* V, const void* O
                       float scale, int causal, void* stream, const Options& opt) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
   if (int e = check_varlen(cu_seqlens, nseq, total_tokens, max_seqlen)) return e;
-  if (int e = check_common(Hq, Hkv, d, scale, !opt.dropout)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, !(opt.dropout || opt.window))) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return FA_ERR_ALIGN;
@@ -682,6 +682,32 @@ int fa_fp8_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* 
     return FA_ERR_LAUNCH;
   }
   return FA_OK;
+}
+
+// Sliding window over a packed ragged batch: the routing of fa_local_fwd with the longest
+// sequence standing for both lengths (a bound that reaches past it binds nowhere).
+int fa_varlen_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
+                        int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale,
+                        int window_left, int window_right, void* stream) {
+  int causal = 0;
+  if (max_seqlen > 0)
+    if (int e = window_route(max_seqlen, max_seqlen, window_left, window_right, causal)) return e;
+  const bool none = window_left < 0 && window_right < 0;
+  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
+                    none ? Options() : with_window(window_left, window_right));
+}
+
+int fa_varlen_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                        void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                        const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d,
+                        float scale, int window_left, int window_right, void* stream) {
+  int causal = 0;
+  if (max_seqlen > 0)
+    if (int e = window_route(max_seqlen, max_seqlen, window_left, window_right, causal)) return e;
+  const bool none = window_left < 0 && window_right < 0;
+  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
+                    max_seqlen, Hq, Hkv, d, scale, causal, stream,
+                    none ? Options() : with_window(window_left, window_right));
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,

@@ -238,11 +238,13 @@ def run_oracle(prob: AttnProblem, backward: bool = True):
     return out
 
 
-def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=None, M=None, keep_of=None, rp=1.0):
+def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=None, M=None, keep_of=None, rp=1.0,
+                    M_of=None):
     """The 16-bit reference over a whole batch, in the oracle's layouts. Q, K, V, dO: torch tensors
     on the GPU, dense [B, N, H, d] or packed [T, H, d] with cumulative offsets cu_q (and cu_k for
-    two lengths). M: torch [Bm, Hm, Nq, Nk] or None (dense only). keep_of(seq, head, nq, nk) ->
-    torch bool [nq, nk] or None. dK, dV of grouped heads are summed in float64."""
+    two lengths). M: torch [Bm, Hm, Nq, Nk] or None (dense only), or M_of(seq, head, nq, nk) ->
+    torch [nq, nk]. keep_of(seq, head, nq, nk) -> torch bool [nq, nk] or None. dK, dV of grouped
+    heads are summed in float64."""
     packed = cu_q is not None
     Hq, Hkv = Q.shape[-2], K.shape[-2]
     G = Hq // Hkv
@@ -265,6 +267,8 @@ def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=N
             qs, ks, vs, gs = Q[s], K[s], V[s], dO[s]
         for h in range(Hq):
             m = None if M is None else M[s if M.shape[0] > 1 else 0, h if M.shape[1] > 1 else 0]
+            if M_of is not None:
+                m = M_of(s, h, qs.shape[0], ks.shape[0])
             keep = None if keep_of is None else keep_of(s, h, qs.shape[0], ks.shape[0])
             r = reference_head(qs[:, h], ks[:, h // G], vs[:, h // G], gs[:, h], scale, causal, M=m, keep=keep, rp=rp,
                                backward=backward)
