@@ -77,6 +77,12 @@ Readings taken where the text is silent or inconsistent:
     In a packed ragged batch the window applies inside each sequence, positions counted from
     the sequence's first token (one length per sequence, so p = r).
 
+  * a key/value cache (section 3.1's multi-query paragraph speaks of the inference setting the
+    two lengths exist for; no layout is given). Reading: a cache is storage, not arithmetic:
+    sequence b attends to the first seqlens_k[b] keys of its cache, wherever they lie (one
+    contiguous slab per sequence, or fixed-size pages named by a table), with the two-length
+    definition above; rows that then see no key have P = 0.
+
   * FP8 operands (section 5 names FP8 as a direction; no algorithm is given). Reading: Q, K, V
     arrive quantised to OCP FP8 E4M3 (1 sign, 4 exponent, 3 significand bits, bias 7, largest
     finite value 448, no infinities) with one float scale per tensor, x = descale * x8; the
@@ -603,6 +609,38 @@ def varlen_backward_local(Q, K, V, dO, cu_seqlens, scale, left, right):
             dq, dk, dv = attention_backward_local(Q[None, a:e], K[None, a:e], V[None, a:e], dO[None, a:e], scale, left, right)
             dQ[a:e], dK[a:e], dV[a:e] = dq[0], dk[0], dv[0]
     return dQ, dK, dV
+
+
+def kvcache_forward(Q, Kcache, Vcache, scale, causal, seqlens_k=None, block_table=None):
+    """Forward of Nq new queries per sequence against a key/value cache (the inference setting of
+    the multi-query paragraph of section 3.1; two lengths as in the header). Sequence b attends to
+    the first seqlens_k[b] keys of its cache (all of them when seqlens_k is None); under the causal
+    rule query r stands at position r + seqlens_k[b] - Nq. A row that sees no key (an empty cache,
+    or more queries than keys under the causal rule) has P = 0: O = 0, L = -inf.
+    Contiguous cache: Kcache, Vcache [B, Nk_max, Hkv, d]. Paged cache: Kcache, Vcache
+    [pages, page_size, Hkv, d] and block_table [B, pages per sequence] of page numbers; key c of
+    sequence b is row c % page_size of page block_table[b, c // page_size].
+    Q [B, Nq, Hq, d] -> O [B, Nq, Hq, d], L [B, Hq, Nq]."""
+    B, Nq, Hq, d = Q.shape
+    G = _group(Hq, Kcache.shape[2])
+    O = np.zeros((B, Nq, Hq, d), dtype=np.float64)
+    L = np.full((B, Hq, Nq), -np.inf, dtype=np.float64)
+    for b in range(B):
+        if block_table is None:
+            nk = Kcache.shape[1] if seqlens_k is None else int(seqlens_k[b])
+            k, v = Kcache[b, :nk], Vcache[b, :nk]
+        else:
+            page = Kcache.shape[1]
+            nk = block_table.shape[1] * page if seqlens_k is None else int(seqlens_k[b])
+            rows = [(int(block_table[b, c // page]), c % page) for c in range(nk)]
+            k = np.array([Kcache[pg, r] for pg, r in rows]).reshape(nk, Kcache.shape[2], d)
+            v = np.array([Vcache[pg, r] for pg, r in rows]).reshape(nk, Vcache.shape[2], d)
+        if nk == 0:
+            continue
+        vis = window_visible(Nq, nk, -1, 0) if causal else np.ones((Nq, nk), dtype=bool)
+        for h in range(Hq):
+            O[b, :, h], L[b, h], _ = head_forward_pattern(Q[b, :, h], k[:, h // G], v[:, h // G], vis, scale)
+    return O, L
 
 
 def attention_forward_blocksparse(Q, K, V, scale, causal, block_mask, block):

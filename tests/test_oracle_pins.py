@@ -1117,6 +1117,60 @@ def test_ragged_window_against_scalar_loops_and_its_reductions():
             assert abs((f(*args_p) - f(*args_m)) / (2 * eps) - G[idx]) < 1e-7
 
 
+def test_kvcache_forward_against_scalar_loops_and_its_reductions():
+    """Queries against a cache with per-sequence lengths, contiguous and paged: brute force over
+    (sequence, head, row); full lengths without pages are the two-length forward; a shuffled page
+    table over shuffled pages changes nothing; cache rows past a sequence's length are never read;
+    an empty cache and causal rows above the first key give O = 0, L = -inf."""
+    g = np.random.default_rng(815)
+    B, Nq, Hq, Hkv, d, page, ppseq, scale = 3, 3, 4, 2, 2, 4, 3, 0.8
+    cap = page * ppseq
+    lens = np.array([cap, 5, 0])
+    Q = g.standard_normal((B, Nq, Hq, d))
+    Kc, Vc = g.standard_normal((B, cap, Hkv, d)), g.standard_normal((B, cap, Hkv, d))
+    for causal in (False, True):
+        O, L = orc.kvcache_forward(Q, Kc, Vc, scale, causal, lens)
+        for b in range(B):
+            nk = int(lens[b])
+            for h in range(Hq):
+                for r in range(Nq):
+                    cols = [c for c in range(nk) if not causal or c <= r + nk - Nq]
+                    if not cols:
+                        assert np.all(O[b, r, h] == 0) and L[b, h, r] == -np.inf
+                        continue
+                    sc = [scale * sum(Q[b, r, h, t] * Kc[b, c, h // 2, t] for t in range(d)) for c in cols]
+                    mx = max(sc)
+                    den = sum(math.exp(x - mx) for x in sc)
+                    assert abs(L[b, h, r] - (mx + math.log(den))) < 1e-12
+                    for t in range(d):
+                        want = sum(math.exp(x - mx) / den * Vc[b, c, h // 2, t] for x, c in zip(sc, cols))
+                        assert abs(O[b, r, h, t] - want) < 1e-12
+        # full lengths, no pages: the two-length forward
+        O1, L1 = orc.kvcache_forward(Q, Kc, Vc, scale, causal)
+        O2, L2 = orc.attention_forward(Q, Kc, Vc, scale, causal)
+        assert np.allclose(O1, O2, atol=1e-13) and np.allclose(L1, L2, atol=1e-13)
+        # the same cache cut into pages that lie shuffled in a pool
+        perm = g.permutation(B * ppseq)
+        table = perm.reshape(B, ppseq)
+        Kp, Vp = np.zeros((B * ppseq, page, Hkv, d)), np.zeros((B * ppseq, page, Hkv, d))
+        for b in range(B):
+            for i in range(ppseq):
+                Kp[table[b, i]] = Kc[b, i * page:(i + 1) * page]
+                Vp[table[b, i]] = Vc[b, i * page:(i + 1) * page]
+        O3, L3 = orc.kvcache_forward(Q, Kp, Vp, scale, causal, lens, table)
+        assert np.array_equal(O3, O) and np.array_equal(L3, L)
+        # what lies past a sequence's length is not part of it
+        K2, V2 = Kc.copy(), Vc.copy()
+        K2[1, 5:] = 1e3
+        V2[1, 5:] = -1e3
+        K2[2] = np.nan
+        O4, L4 = orc.kvcache_forward(Q, K2, V2, scale, causal, lens)
+        assert np.array_equal(O4, O) and np.array_equal(L4, L)
+    # more queries than keys under the causal rule: the first rows stand before key 0
+    O5, L5 = orc.kvcache_forward(Q, Kc, Vc, scale, True, np.array([2, 2, 2]))
+    assert np.all(O5[:, 0] == 0) and np.all(L5[:, :, 0] == -np.inf) and np.all(np.isfinite(L5[:, :, 1:]))
+
+
 # ---------------------------------------------------------------------------
 # FP8 (E4M3) inputs
 # ---------------------------------------------------------------------------
