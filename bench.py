@@ -370,13 +370,33 @@ def bench_decode(args, prob, binding) -> int:
 
     Q, K, V = (gpu(x) for x in (prob.Q, prob.K, prob.V))
     B, Nq, Hq, d = Q.shape
-    splits = binding.splitkv_default_splits(B, Hq, prob.Hkv, Nq, prob.Nk)
+    splits = binding.splitkv_default_splits(B, Hq, prob.Hkv, Nq, prob.Nk, ragged=bool(prob.meta.get("cache")))
     O = torch.empty_like(Q)
     LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device="cuda")
     ws = torch.empty(binding.fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, splits), dtype=torch.uint8, device="cuda")
+    cache = prob.meta.get("cache")
+    lens = None
+    if cache:  # per-sequence lengths over a paged cache: fa_kvcache_fwd
+        from paper_2307_08691_amd import inputs
+        page = cache["page"]
+        lens, table = inputs.cache_layout(cache["seed"], B, prob.Nk, page)
+        pps = table.shape[1]
+        tbl = torch.from_numpy(table).cuda()
+        Kp, Vp = torch.empty((B * pps, page) + tuple(K.shape[2:]), dtype=K.dtype, device="cuda"), None
+        Vp = torch.empty_like(Kp)
+        Kp[tbl.long().flatten()] = K.view(B * pps, page, *K.shape[2:])  # (the drawn slabs, cut into pages)
+        Vp[tbl.long().flatten()] = V.view(B * pps, page, *V.shape[2:])
+        sl = torch.from_numpy(lens).cuda()
+        del K, V
 
-    def step():
-        binding.fa_splitkv_fwd(Q, K, V, prob.scale, prob.causal, splits, O=O, LSE=LSE, workspace=ws)
+        def step():
+            binding.fa_kvcache_fwd(Q, Kp, Vp, prob.scale, prob.causal, seqlens_k=sl, block_table=tbl, num_splits=splits,
+                                   O=O, LSE=LSE, workspace=ws)
+        kv_elems = 2.0 * float(lens.sum()) * prob.Hkv * d
+    else:
+        def step():
+            binding.fa_splitkv_fwd(Q, K, V, prob.scale, prob.causal, splits, O=O, LSE=LSE, workspace=ws)
+        kv_elems = float(K.numel() + V.numel())
 
     for _ in range(args.warmup):
         step()
@@ -391,14 +411,15 @@ def bench_decode(args, prob, binding) -> int:
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     kern_ms = e0.elapsed_time(e1) / args.steps
     # bytes that must move: K and V once, Q read and O written once, LSE written
-    alg_bytes = 2.0 * (K.numel() + V.numel() + Q.numel() + O.numel()) + 4.0 * LSE.numel()
+    alg_bytes = 2.0 * (kv_elems + Q.numel() + O.numel()) + 4.0 * LSE.numel()
     gbs = alg_bytes / (kern_ms * 1e-3) / 1e9
     out = {
         "metric": "decode attention forward, GB/s of compulsory traffic (bf16)", "value": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": prob.name, "B": B, "Nq": Nq, "Nk": prob.Nk, "Hq": Hq, "Hkv": prob.Hkv, "d": d,
-                   "causal": prob.causal, "num_splits": splits, "algorithmic_bytes": alg_bytes},
+                   "causal": prob.causal, "num_splits": splits, "algorithmic_bytes": alg_bytes,
+                   **({"page": cache["page"], "cached_keys": int(lens.sum())} if cache else {})},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
                      **traffic_fields(prob.name, "fwd_kernel"), "avg_kernel_ms": kern_ms,
                      "kernel": "fwd_kernel<.., split> + fwd_merge_kernel"},
@@ -409,8 +430,9 @@ def bench_decode(args, prob, binding) -> int:
         n = 0
         while time.perf_counter() - t0 < 10.0:
             b = n % B
-            orc.attention_forward(orc.widen_bf16(prob.Q[b:b + 1]), orc.widen_bf16(prob.K[b:b + 1]),
-                                  orc.widen_bf16(prob.V[b:b + 1]), prob.scale, prob.causal)
+            nk = prob.Nk if lens is None else int(lens[b])
+            orc.attention_forward(orc.widen_bf16(prob.Q[b:b + 1]), orc.widen_bf16(prob.K[b:b + 1, :nk]),
+                                  orc.widen_bf16(prob.V[b:b + 1, :nk]), prob.scale, prob.causal)
             n += 1
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": alg_bytes / B * n / dt / 1e9, "unit": "GB/s", "cores": len(os.sched_getaffinity(0)),

@@ -454,6 +454,32 @@ int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* 
                    int num_splits, void* stream);
 
 /*
+ * Forward against a key/value cache (the inference setting that the multi-query / grouped-query
+ * paragraph of section 3.1 refers to; a cache is storage: the arithmetic is fa_splitkv_fwd's).
+ * Nq new queries per sequence, Q [B, Nq, Hq, d], attend to the first seqlens_k[b] keys of sequence
+ * b's cache; under the causal rule query r stands at position r + seqlens_k[b] - Nq. seqlens_k is a
+ * DEVICE array of B int32 (nullptr: every sequence holds Nk keys); values are clamped into 0 .. Nk.
+ * A row that sees no key (an empty cache, or more queries than cached keys under the causal rule)
+ * gets O = 0, LSE = -inf.
+ *   block_table == nullptr: Kcache, Vcache [B, Nk, Hkv, d], one slab of Nk rows (the capacity)
+ *     per sequence; page_size and pages_per_seq are ignored.
+ *   block_table != nullptr: Kcache, Vcache [pages, page_size, Hkv, d] are pools of pages and
+ *     block_table a DEVICE array [B, pages_per_seq] of int32 page numbers: key c of sequence b is
+ *     row c mod page_size of page block_table[b][c / page_size]. page_size is a power of two, at
+ *     least 64 (FA_ERR_UNSUPPORTED otherwise); pages_per_seq * page_size >= Nk, the largest length
+ *     any sequence may have (FA_ERR_SHAPE otherwise). Entries past a sequence's last page are never
+ *     read; the entries that are read must name pages inside the pools (not checked).
+ * The key sequence of every (sequence, key/value head) is split over num_splits workgroups as in
+ * fa_splitkv_fwd: same workspace (fa_splitkv_fwd_workspace_bytes), limits (d in {64, 128},
+ * bfloat16, 1 <= num_splits <= FA_SPLITKV_MAX_SPLITS) and errors. Nothing is written to the caches.
+ */
+int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
+                   const int32_t* block_table, void* O, float* LSE,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq,
+                   float scale, int causal, int num_splits, void* stream);
+
+/*
  * Measurement aid, not part of either algorithm: a register-resident loop of the bf16 MFMA
  * the kernels are built on (v_mfma_f32_32x32x16_bf16), the "matmul throughput" the paper
  * sets the non-matmul work against (section 2.1, section 3.1), measured on this device

@@ -131,6 +131,9 @@ struct Options {
   const void* bmask = nullptr;      // block-sparse pattern (with window = true): bytes, two strides, block size
   long long bmask_bs = 0, bmask_hs = 0;
   int block = 0;
+  const int32_t* seqlens_k = nullptr;    // key/value cache (split forward only): per-sequence lengths,
+  const int32_t* block_table = nullptr;  // page table with its row stride, log2 of the page size
+  int page_log2 = 0, table_stride = 0;
 };
 
 Options half_precision(int f16) {
@@ -206,6 +209,10 @@ int run_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, co
   a.Lpart = ws ? (float*)ws + (size_t)nsplit * total * Hq * d : nullptr;
   a.p = make_problem(cu, nseq, N, Nk, Hq, Hkv, d, total, scale, cu_k, opt.f16);
   if (int e = apply_options(a.p, opt)) return e;
+  a.seqlens_k = opt.seqlens_k;
+  a.block_table = opt.block_table;
+  a.page_log2 = opt.page_log2;
+  a.table_stride = opt.table_stride;
   a.Q = (const __bf16*)Q;
   a.K = (const __bf16*)K;
   a.V = (const __bf16*)V;
@@ -761,6 +768,33 @@ int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* 
   if (workspace_bytes < fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)) return FA_ERR_WORKSPACE;
   return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, num_splits,
                  workspace);
+}
+
+int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
+                   const int32_t* block_table, void* O, float* LSE, void* workspace, size_t workspace_bytes, int B,
+                   int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq, float scale, int causal,
+                   int num_splits, void* stream) {
+  if (!Q || !Kcache || !Vcache || !O || !LSE || !workspace) return FA_ERR_NULL;
+  if (int e = check_cross(B, Nq, Nk, causal)) return e;
+  if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
+  if (num_splits < 1 || num_splits > FA_SPLITKV_MAX_SPLITS) return FA_ERR_SHAPE;
+  if ((long)Nq * (Hq / Hkv) > 0x7fffffffL) return FA_ERR_SHAPE;
+  Options opt;
+  opt.seqlens_k = seqlens_k;
+  if (block_table) {
+    if (page_size < 64 || (page_size & (page_size - 1))) return FA_ERR_UNSUPPORTED;  // whole blocks of 64 keys per page
+    if (pages_per_seq < 1 || (long)pages_per_seq * page_size < Nk) return FA_ERR_SHAPE;
+    opt.block_table = block_table;
+    opt.page_log2 = __builtin_ctz((unsigned)page_size);
+    opt.table_stride = pages_per_seq;
+  }
+  if (!aligned16(Q) || !aligned16(Kcache) || !aligned16(Vcache) || !aligned16(O) || !aligned16(LSE) ||
+      !aligned16(workspace) || (reinterpret_cast<uintptr_t>(seqlens_k) & 3u) ||
+      (reinterpret_cast<uintptr_t>(block_table) & 3u))
+    return FA_ERR_ALIGN;
+  if (workspace_bytes < fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)) return FA_ERR_WORKSPACE;
+  return run_fwd(Q, Kcache, Vcache, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream,
+                 num_splits, workspace, nullptr, opt);
 }
 
 size_t fa_mfma_probe_scratch_bytes(void) { return 16 + (size_t)256 * 512 * sizeof(float); }

@@ -131,11 +131,16 @@ __global__ __launch_bounds__(512)
   const int rowblk = SPLIT ? bc.blk / nsplit : nblk - 1 - bc.blk;  // not split: longest causal rows first
   const int s = bc.seq;
   const SeqInfo si = seq_info(p, s);
-  const int n = si.n, nk = si.nk;  // query rows, key rows
+  int nk_ = si.nk;
+  if (SPLIT && a.seqlens_k) {  // a key/value cache filled up to a length of its own per sequence
+    const int len = a.seqlens_k[s];
+    nk_ = len < 0 ? 0 : (len < p.Nk ? len : p.Nk);
+  }
+  const int n = si.n, nk = nk_;  // query rows, key rows
   const int off = nk - n;          // position of query 0 among the keys (causal alignment)
   const int nrows = SPLIT ? n * p.G : n;  // rows of the (packed) row dimension
   const int i0 = rowblk * BR;
-  if (i0 >= nrows || nk == 0) return;  // (a sequence without keys: see keyless_rows_kernel)
+  if (i0 >= nrows || nk == 0) return;  // (a sequence without keys: see keyless_rows_kernel, fwd_merge_kernel)
   const int g = SPLIT ? bc.head : bc.head / p.G;
   const int dh = PAD ? p.d : D;  // row length in memory
   const long kstride = (long)p.Hkv * dh;
@@ -190,7 +195,12 @@ __global__ __launch_bounds__(512)
     }
     if (LOCAL && wl >= 0 && i0 + off > wl) jb = (i0 + off - wl) / BC;  // the first block the first row sees
   }
-  if (ncol < jb) ncol = jb;  // nothing visible in this share: the loops below still run once
+  if (SPLIT && jb >= ncol) {  // this share holds no key that the workgroup's rows see: L = -inf says so to the merge
+    if (row_ok && hh == 0)
+      a.Lpart[(long)split * p.total_tokens * p.Hq + s * p.lse_seq_stride + h * p.lse_head_stride + row] = -INFINITY;
+    return;
+  }
+  if (ncol < jb) ncol = jb;  // nothing visible: the loops below still run once
 
   // Block-sparse pattern: the wavefront's 32 rows lie in one row block of the pattern (blocks are
   // at least 64 rows and the wavefront starts at a multiple of 32), so whether it has anything to
@@ -260,6 +270,17 @@ __global__ __launch_bounds__(512)
   constexpr int TPW = TileLoader<D, BC, 4, PAD>::PER;  // copies per wavefront per tile
   auto issue_tile = [&](int t) {  // the block at position t of the walk; group 0: its V_j, group 1: its K_j
     char* dst = smem + (t % RING) * BUFB + (grp == 0 ? TILEB : 0);
+    if (SPLIT && a.block_table) {
+      // paged cache: a block of 64 keys lies inside one page (pages are multiples of 64 rows);
+      // copies past the last block fetch the last block again (never read)
+      const int jc = t < ncol_all ? t : ncol_all - 1;
+      const int key0 = jc * BC, in_page = key0 & ((1 << a.page_log2) - 1);
+      const int pg = __builtin_amdgcn_readfirstlane(a.block_table[(long)s * a.table_stride + (key0 >> a.page_log2)]);
+      const __bf16* base = (grp == 0 ? a.V : a.K) + (((long)pg << a.page_log2) * p.Hkv + g) * dh;
+      const int last = nk - 1 - (key0 - in_page);  // the sequence's last key, counted from the page's first row
+      loader.load(dst, base, kstride, in_page, last < (1 << a.page_log2) - 1 ? last : (1 << a.page_log2) - 1, w & 3, lane);
+      return;
+    }
     loader.load(dst, grp == 0 ? Vb : Kb, kstride, blk(t) * BC, nk - 1, w & 3, lane);
   };
   // MASK: this wavefront's rows of M, columns of block j (rows and columns clamped into the
@@ -884,17 +905,27 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
   const int h = (int)(r - tok * p.Hq);
   const long b = tok / p.N, q = tok - b * p.N;
   const long li = b * p.lse_seq_stride + (long)h * p.lse_head_stride + q;
+  // (a cache without keys: the split kernel wrote nothing for this sequence)
+  const bool keyless = a.seqlens_k && a.seqlens_k[b] <= 0;
   float mx = -INFINITY;
-  for (int k = 0; k < a.nsplit; ++k) mx = fmaxf(mx, a.Lpart[(long)k * nrows + li]);
+  if (!keyless)
+    for (int k = 0; k < a.nsplit; ++k) mx = fmaxf(mx, a.Lpart[(long)k * nrows + li]);
+  if (mx == -INFINITY) {  // no share holds a key that this row sees: P = 0, so O = 0 and L = -inf
+    *(u32x2*)(a.O + r * D + 4 * c) = (u32x2){0u, 0u};
+    if (c == 0) a.LSE[li] = -INFINITY;
+    return;
+  }
   float z = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int k = 0; k < a.nsplit; ++k) {
-    const float wgt = __expf(a.Lpart[(long)k * nrows + li] - mx);  // shares without keys: exp(-inf) = 0
+    const float lp = a.Lpart[(long)k * nrows + li];
+    if (lp == -INFINITY) continue;  // a share without keys for this row (it may have written no partial O at all)
+    const float wgt = __expf(lp - mx);
     const f32x4 o = *(const f32x4*)(a.Opart + ((long)k * nrows + r) * D + 4 * c);
     z += wgt;
     acc += o * wgt;
   }
-  const float inv = 1.f / z;  // at least one share holds a visible key
+  const float inv = 1.f / z;  // some share holds a visible key
   u32x2 o;
   o[0] = pack2<F16>(acc[0] * inv, acc[1] * inv);
   o[1] = pack2<F16>(acc[2] * inv, acc[3] * inv);

@@ -16,6 +16,13 @@ struct FwdArgs {
   int nsplit;
   float* Opart;
   float* Lpart;
+  // key/value cache (split kernel only): sequence s attends to its first seqlens_k[s] keys (nullptr: all
+  // p.Nk; values are clamped into 0 .. p.Nk). With a block table (nullptr: one slab of p.Nk rows per
+  // sequence) K and V are pools of pages of 2^page_log2 rows (a multiple of 64) and key c of sequence s
+  // is row c mod 2^page_log2 of page block_table[s * table_stride + (c >> page_log2)].
+  const int32_t* seqlens_k;
+  const int32_t* block_table;
+  int page_log2, table_stride;
 };
 
 struct BwdArgs {

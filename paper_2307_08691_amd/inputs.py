@@ -29,6 +29,7 @@ __all__ = [
     "make_varlen",
     "shape_only",
     "block_pattern",
+    "cache_layout",
     "CONFIGS",
     "make_config",
 ]
@@ -246,6 +247,9 @@ CONFIGS = {
     # decoding: one new token per sequence against a cache of 8192 keys, grouped heads (forward only)
     "decode_b8_on_8k": dict(kind="cross", B=8, Nq=1, Nk=8192, Hq=32, Hkv=8, d=128, causal=True, seed=1008),
     "decode_b1_on_128k": dict(kind="cross", B=1, Nq=1, Nk=131072, Hq=32, Hkv=8, d=128, causal=True, seed=1009),
+    # a serving batch: 64 sequences with 1 .. 8192 cached keys each, the caches cut into pages of 256 keys
+    "decode_paged_b64_to_8k": dict(kind="cross", B=64, Nq=1, Nk=8192, Hq=32, Hkv=8, d=128, causal=True, seed=1030,
+                                   cache=dict(page=256, seed=18600)),
     # half precision elements, the shape of d128_n8k_causal
     "f16_d128_n8k_causal": dict(kind="cross", B=2, Nq=8192, Nk=8192, Hq=16, Hkv=16, d=128, causal=True, seed=1010,
                                 dtype="f16"),
@@ -309,6 +313,18 @@ def block_pattern(seed: int, Bm: int, Hm: int, nq: int, nk: int, block: int, den
     return bm
 
 
+def cache_layout(seed: int, B: int, capacity: int, page: int):
+    """Per-sequence key counts, uniform in 1 .. capacity (the first sequence full, the second holding
+    one key), and a page table [B, capacity / page] over a shuffled pool: (lengths, table)."""
+    g = np.random.default_rng(seed)
+    lens = g.integers(1, capacity + 1, B)
+    lens[0] = capacity
+    if B > 1:
+        lens[1] = 1
+    pps = -(-capacity // page)
+    return lens.astype(np.int32), g.permutation(B * pps).reshape(B, pps).astype(np.int32)
+
+
 def ragged_lengths(seed: int, nseq: int, lo: int, hi: int) -> np.ndarray:
     """Sequence lengths uniform in [lo, hi], drawn before the tensors from a
     generator of their own so they do not depend on the tensor shapes."""
@@ -325,7 +341,7 @@ def shape_only(B, N, Hq, Hkv, d, causal, name, scale=None) -> AttnProblem:
 def make_config(name: str) -> AttnProblem:
     c = dict(CONFIGS[name])
     kind = c.pop("kind")
-    options = {k: c.pop(k) for k in ("dropout", "mask", "window", "block_pattern") if k in c}  # entry-point options, not part of the draw
+    options = {k: c.pop(k) for k in ("dropout", "mask", "window", "block_pattern", "cache") if k in c}  # entry-point options, not part of the draw
     if kind == "dense":
         prob = make_dense(name=name, **c)
     elif kind == "cross":

@@ -215,6 +215,8 @@ def test_split_key_entry_point_rejects_bad_arguments():
     assert binding.splitkv_default_splits(8, 32, 8, 1, 8192) == 4
     assert binding.splitkv_default_splits(64, 32, 8, 1, 8192) == 1
     assert binding.splitkv_default_splits(1, 8, 8, 1, 100) == 1
+    assert binding.splitkv_default_splits(64, 32, 8, 1, 8192, ragged=True) == 4
+    assert binding.splitkv_default_splits(8, 32, 8, 1, 8192, ragged=True) == 8
 
 
 def test_mfma_probe_rejects_bad_arguments():
