@@ -480,6 +480,41 @@ int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const 
                    float scale, int causal, int num_splits, void* stream);
 
 /*
+ * The packed ragged entry points (one and two lengths), the split-key forward and the key/value
+ * cache forward for IEEE half precision (fp16) elements: each is its bfloat16 namesake with every
+ * 16-bit tensor holding fp16, as fa_cross_fwd_f16 / fa_cross_bwd_f16 are to fa_cross_fwd /
+ * fa_cross_bwd. LSE, workspaces, offset arrays, lengths, page tables, limits and errors are
+ * unchanged.
+ */
+int fa_varlen_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                      const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                      int Hq, int Hkv, int d, float scale, int causal, void* stream);
+int fa_varlen_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                      const float* LSE, void* dQ, void* dK, void* dV,
+                      void* workspace, size_t workspace_bytes,
+                      const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                      int Hq, int Hkv, int d, float scale, int causal, void* stream);
+int fa_varlen_cross_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq,
+                            int total_q, int total_k, int max_seqlen_q, int max_seqlen_k,
+                            int Hq, int Hkv, int d, float scale, int causal, void* stream);
+int fa_varlen_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                            const float* LSE, void* dQ, void* dK, void* dV,
+                            void* workspace, size_t workspace_bytes,
+                            const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq,
+                            int total_q, int total_k, int max_seqlen_q, int max_seqlen_k,
+                            int Hq, int Hkv, int d, float scale, int causal, void* stream);
+int fa_splitkv_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                       void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                       int num_splits, void* stream);
+int fa_kvcache_fwd_f16(const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
+                       const int32_t* block_table, void* O, float* LSE,
+                       void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq,
+                       float scale, int causal, int num_splits, void* stream);
+
+/*
  * Measurement aid, not part of either algorithm: a register-resident loop of the bf16 MFMA
  * the kernels are built on (v_mfma_f32_32x32x16_bf16), the "matmul throughput" the paper
  * sets the non-matmul work against (section 2.1, section 3.1), measured on this device

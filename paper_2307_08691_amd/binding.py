@@ -38,8 +38,11 @@ SIGNATURES = {
     "fa_bwd_stages": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 5 +
                       [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_varlen_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_bwd_workspace_bytes": (_c_size_t, [_c_int] * 4),
     "fa_varlen_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
+                      [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
                       [_c_float, _c_int, _c_void_p]),
     "fa_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_void_p]),
     "fa_cross_bwd_workspace_bytes": (_c_size_t, [_c_int] * 6),
@@ -77,11 +80,16 @@ SIGNATURES = {
                            [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_fp8_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [ctypes.c_longlong] + [_c_float] * 4 + [_c_int, _c_void_p]),
     "fa_varlen_cross_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_cross_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_void_p] * 2 + [_c_int] * 8 + [_c_float, _c_int, _c_void_p]),
     "fa_varlen_cross_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
+                            [_c_float, _c_int, _c_void_p]),
+    "fa_varlen_cross_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] * 2 + [_c_int] * 8 +
                             [_c_float, _c_int, _c_void_p]),
     "fa_splitkv_fwd_workspace_bytes": (_c_size_t, [_c_int] * 5),
     "fa_splitkv_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_splitkv_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_kvcache_fwd": (_c_int, [_c_void_p] * 7 + [_c_void_p, _c_size_t] + [_c_int] * 8 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_kvcache_fwd_f16": (_c_int, [_c_void_p] * 7 + [_c_void_p, _c_size_t] + [_c_int] * 8 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_mfma_probe_scratch_bytes": (_c_size_t, []),
     "fa_mfma_probe": (_c_int, [_c_int, _c_int, _c_void_p, _c_void_p]),
 }
@@ -161,14 +169,16 @@ def fa_bwd_stages_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv,
                                 stages, stream)
 
 
-def fa_varlen_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, causal, stream=0) -> int:
-    return load().fa_varlen_fwd(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, int(causal), stream)
+def fa_varlen_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, causal, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_fwd_f16 if f16 else load().fa_varlen_fwd
+    return fn(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, int(causal), stream)
 
 
 def fa_varlen_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale,
-                      causal, stream=0) -> int:
-    return load().fa_varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv,
-                                d, scale, int(causal), stream)
+                      causal, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_bwd_f16 if f16 else load().fa_varlen_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale,
+              int(causal), stream)
 
 
 def fa_bwd_workspace_bytes(B, Hq, Hkv, N, d) -> int:
@@ -267,30 +277,33 @@ def fa_fp8_fwd_raw(Q8, K8, Vt8, O, LSE, B, Hq, Hkv, Nq, Nk, d, vt_stride, scale,
 
 
 def fa_varlen_cross_fwd_raw(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale,
-                            causal, stream=0) -> int:
-    return load().fa_varlen_cross_fwd(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d,
-                                      scale, int(causal), stream)
+                            causal, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_cross_fwd_f16 if f16 else load().fa_varlen_cross_fwd
+    return fn(Q, K, V, O, LSE, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq, Hkv, d, scale, int(causal),
+              stream)
 
 
 def fa_varlen_cross_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu_q, cu_k, nseq, total_q, total_k, max_q,
-                            max_k, Hq, Hkv, d, scale, causal, stream=0) -> int:
-    return load().fa_varlen_cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu_q, cu_k, nseq, total_q,
-                                      total_k, max_q, max_k, Hq, Hkv, d, scale, int(causal), stream)
+                            max_k, Hq, Hkv, d, scale, causal, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_cross_bwd_f16 if f16 else load().fa_varlen_cross_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu_q, cu_k, nseq, total_q, total_k, max_q, max_k, Hq,
+              Hkv, d, scale, int(causal), stream)
 
 
 def fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits) -> int:
     return load().fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)
 
 
-def fa_splitkv_fwd_raw(Q, K, V, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, num_splits, stream=0) -> int:
-    return load().fa_splitkv_fwd(Q, K, V, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), num_splits,
-                                 stream)
+def fa_splitkv_fwd_raw(Q, K, V, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, num_splits, stream=0, f16=False) -> int:
+    fn = load().fa_splitkv_fwd_f16 if f16 else load().fa_splitkv_fwd
+    return fn(Q, K, V, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), num_splits, stream)
 
 
 def fa_kvcache_fwd_raw(Q, Kc, Vc, seqlens_k, block_table, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, page_size,
-                       pages_per_seq, scale, causal, num_splits, stream=0) -> int:
-    return load().fa_kvcache_fwd(Q, Kc, Vc, seqlens_k, block_table, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, page_size,
-                                 pages_per_seq, scale, int(causal), num_splits, stream)
+                       pages_per_seq, scale, causal, num_splits, stream=0, f16=False) -> int:
+    fn = load().fa_kvcache_fwd_f16 if f16 else load().fa_kvcache_fwd
+    return fn(Q, Kc, Vc, seqlens_k, block_table, O, LSE, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, page_size,
+              pages_per_seq, scale, int(causal), num_splits, stream)
 
 
 def fa_mfma_probe_scratch_bytes() -> int:
@@ -375,16 +388,18 @@ def _dense(Q, K, V, allowed=None, one_length=False):
     return x
 
 
-def _packed(Q, K, V, cu_q, cu_k=None):
-    """Q [Tq,Hq,d], K, V [Tk,Hkv,d] bf16 and the int32 offset arrays (one for one length) -> dimensions."""
+def _packed(Q, K, V, cu_q, cu_k=None, allowed=None):
+    """Q [Tq,Hq,d], K, V [Tk,Hkv,d] of one element type (bf16 unless `allowed` says otherwise) and the
+    int32 offset arrays (one for one length) -> dimensions."""
     import torch
-    _need(Q, "Q", torch.bfloat16)
+    et = _elem_type(Q, allowed or (torch.bfloat16,))
+    _need(Q, "Q", et)
     if Q.dim() != 3 or K.dim() != 3:
         raise ValueError("Q must be [T, Hq, d] and K, V [T, Hkv, d]")
     x = _Dims()
     x.Tq, x.Hq, x.d = Q.shape
     x.Tk, x.Hkv = K.shape[0], K.shape[1]
-    x.et, x.dev = torch.bfloat16, Q.device
+    x.et, x.dev = et, Q.device
     if cu_k is None and x.Tk != x.Tq:
         raise ValueError("K, V must hold as many tokens as Q (two lengths: the fa_varlen_cross_* entry points)")
     _need(K, "K", x.et, (x.Tk, x.Hkv, x.d), x.dev)
@@ -464,22 +479,24 @@ def fa_bwd_stages(Q, K, V, O, dO, LSE, scale: float, causal: bool, stages: int, 
 def fa_varlen_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, causal: bool, O=None, LSE=None):
     """Packed ragged forward. Q [T,Hq,d], K,V [T,Hkv,d] bf16, cu_seqlens int32 on the GPU.
     Returns O [T,Hq,d] bf16 and LSE [Hq,T] fp32."""
-    x = _packed(Q, K, V, cu_seqlens)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens, allowed=(torch.bfloat16, torch.float16))
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_varlen_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen,
-                             x.Hq, x.Hkv, x.d, scale, causal, _stream()))
+                             x.Hq, x.Hkv, x.d, scale, causal, _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_varlen_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, causal: bool,
                   dQ=None, dK=None, dV=None, workspace=None):
     """Packed ragged backward. Returns dQ [T,Hq,d], dK, dV [T,Hkv,d] (bf16)."""
-    x = _packed(Q, K, V, cu_seqlens)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens, allowed=(torch.bfloat16, torch.float16))
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                              _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen, x.Hq, x.Hkv, x.d, scale,
-                             causal, _stream()))
+                             causal, _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 
@@ -714,23 +731,25 @@ def fa_fp8_fwd(Q8, K8, Vt8, Nk: int, scale: float, descale_q: float, descale_k: 
 def fa_varlen_cross_fwd(Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int, scale: float,
                         causal: bool, O=None, LSE=None):
     """Packed ragged forward with two lengths. Q [Tq,Hq,d], K,V [Tk,Hkv,d] bf16; offsets int32 on the GPU."""
-    x = _packed(Q, K, V, cu_seqlens_q, cu_seqlens_k)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens_q, cu_seqlens_k, allowed=(torch.bfloat16, torch.float16))
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_varlen_cross_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens_q), _ptr(cu_seqlens_k),
                                    x.nseq, x.Tq, x.Tk, max_seqlen_q, max_seqlen_k, x.Hq, x.Hkv, x.d, scale, causal,
-                                   _stream()))
+                                   _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_varlen_cross_bwd(Q, K, V, O, dO, LSE, cu_seqlens_q, cu_seqlens_k, max_seqlen_q: int, max_seqlen_k: int,
                         scale: float, causal: bool, dQ=None, dK=None, dV=None, workspace=None):
     """Packed ragged backward with two lengths. Returns dQ [Tq,Hq,d], dK, dV [Tk,Hkv,d] bf16."""
-    x = _packed(Q, K, V, cu_seqlens_q, cu_seqlens_k)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens_q, cu_seqlens_k, allowed=(torch.bfloat16, torch.float16))
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_cross_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK), _ptr(dV),
                                    _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens_q), _ptr(cu_seqlens_k), x.nseq, x.Tq, x.Tk,
-                                   max_seqlen_q, max_seqlen_k, x.Hq, x.Hkv, x.d, scale, causal, _stream()))
+                                   max_seqlen_q, max_seqlen_k, x.Hq, x.Hkv, x.d, scale, causal, _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 
@@ -754,30 +773,31 @@ def splitkv_default_splits(B, Hq, Hkv, Nq, Nk, ragged: bool = False) -> int:
 def fa_splitkv_fwd(Q, K, V, scale: float, causal: bool, num_splits: int = 0, O=None, LSE=None, workspace=None):
     """Few query rows against many keys; layouts and results as fa_cross_fwd. num_splits = 0 picks a default."""
     import torch
-    x = _dense(Q, K, V, (torch.bfloat16,))
+    x = _dense(Q, K, V)
     if num_splits <= 0:
         num_splits = splitkv_default_splits(x.B, x.Hq, x.Hkv, x.Nq, x.Nk)
     O, LSE = _fwd_outputs(x, O, LSE)
     ws = _workspace(workspace, fa_splitkv_fwd_workspace_bytes(x.B, x.Hq, x.Nq, x.d, num_splits), x.dev)
     _check(fa_splitkv_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv,
-                              x.Nq, x.Nk, x.d, scale, causal, num_splits, _stream()))
+                              x.Nq, x.Nk, x.d, scale, causal, num_splits, _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_kvcache_fwd(Q, Kcache, Vcache, scale: float, causal: bool, seqlens_k=None, block_table=None, max_seqlen_k: int = 0,
                    num_splits: int = 0, O=None, LSE=None, workspace=None):
-    """Nq new queries per sequence, Q [B,Nq,Hq,d] bf16, against a key/value cache of which sequence b
+    """Nq new queries per sequence, Q [B,Nq,Hq,d] bf16 or fp16, against a key/value cache of which sequence b
     uses its first seqlens_k[b] keys (int32 on the GPU; None: all). Contiguous cache: Kcache, Vcache
     [B,Nk,Hkv,d]. Paged: Kcache, Vcache [pages,page_size,Hkv,d] and block_table [B,pages_per_seq]
     int32 on the GPU; max_seqlen_k (0: pages_per_seq * page_size) bounds the lengths.
-    Returns O [B,Nq,Hq,d] bf16 and LSE [B,Hq,Nq] fp32. num_splits = 0 picks a default."""
+    Returns O [B,Nq,Hq,d] of that type and LSE [B,Hq,Nq] fp32. num_splits = 0 picks a default."""
     import torch
-    _need(Q, "Q", torch.bfloat16)
+    et = _elem_type(Q)
+    _need(Q, "Q", et)
     if Q.dim() != 4 or Kcache.dim() != 4:
         raise ValueError("Q must be [B, Nq, Hq, d] and the caches [B, Nk, Hkv, d] or [pages, page_size, Hkv, d]")
     x = _Dims()
     x.B, x.Nq, x.Hq, x.d = Q.shape
-    x.Hkv, x.et, x.dev = Kcache.shape[2], torch.bfloat16, Q.device
+    x.Hkv, x.et, x.dev = Kcache.shape[2], et, Q.device
     _need(Kcache, "Kcache", x.et, None, x.dev)
     _need(Vcache, "Vcache", x.et, tuple(Kcache.shape), x.dev)
     if Kcache.shape[3] != x.d:
@@ -803,7 +823,7 @@ def fa_kvcache_fwd(Q, Kcache, Vcache, scale: float, causal: bool, seqlens_k=None
     _check(fa_kvcache_fwd_raw(_ptr(Q), _ptr(Kcache), _ptr(Vcache), _ptr(seqlens_k) if seqlens_k is not None else 0,
                               _ptr(block_table) if block_table is not None else 0, _ptr(O), _ptr(LSE), _ptr(ws),
                               _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, page_size, pages_per_seq, scale, causal,
-                              num_splits, _stream()))
+                              num_splits, _stream(), et == torch.float16))
     return O, LSE
 
 

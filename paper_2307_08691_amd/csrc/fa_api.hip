@@ -343,11 +343,25 @@ static int varlen_fwd(const void* Q, const void* K, const void* V, void* O, floa
                  stream, 0, nullptr, nullptr, opt);
 }
 
+static int varlen_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                          const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                          int d, float scale, int causal, void* stream) {
+  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
+                    half_precision(f16));
+}
+
 int fa_varlen_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
                   int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
                   void* stream) {
-  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
-                    Options());
+  return varlen_fwd_any(0, Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal,
+                        stream);
+}
+
+int fa_varlen_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
+                      int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
+                      void* stream) {
+  return varlen_fwd_any(1, Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal,
+                        stream);
 }
 
 int fa_varlen_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
@@ -378,12 +392,28 @@ static int varlen_bwd(const void* Q, const void* K, const void* V, const void* O
                  Hkv, d, scale, causal, 7, stream, nullptr, opt);
 }
 
+static int varlen_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                          const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                          const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                          int d, float scale, int causal, void* stream) {
+  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
+                    max_seqlen, Hq, Hkv, d, scale, causal, stream, half_precision(f16));
+}
+
 int fa_varlen_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
                   void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, const int32_t* cu_seqlens,
                   int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
                   void* stream) {
-  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
-                    max_seqlen, Hq, Hkv, d, scale, causal, stream, Options());
+  return varlen_bwd_any(0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq,
+                        total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream);
+}
+
+int fa_varlen_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                      void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                      const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d,
+                      float scale, int causal, void* stream) {
+  return varlen_bwd_any(1, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq,
+                        total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream);
 }
 
 int fa_varlen_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
@@ -723,22 +753,38 @@ static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq
   return check_varlen(cu_k, nseq, total_k, max_k);
 }
 
-int fa_varlen_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens_q,
-                        const int32_t* cu_seqlens_k, int nseq, int total_q, int total_k, int max_seqlen_q,
-                        int max_seqlen_k, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
+static int varlen_cross_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq, int total_q,
+                                int total_k, int max_seqlen_q, int max_seqlen_k, int Hq, int Hkv, int d, float scale,
+                                int causal, void* stream) {
   if (!Q || !K || !V || !O || !LSE) return FA_ERR_NULL;
   if (int e = check_varlen_cross(cu_seqlens_q, cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q, max_seqlen_k)) return e;
   if (int e = check_common(Hq, Hkv, d, scale)) return e;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return FA_ERR_ALIGN;
   return run_fwd(Q, K, V, O, LSE, cu_seqlens_q, nseq, max_seqlen_q, max_seqlen_k, total_q, Hq, Hkv, d, scale, causal,
-                 stream, 0, nullptr, cu_seqlens_k);
+                 stream, 0, nullptr, cu_seqlens_k, half_precision(f16));
 }
 
-int fa_varlen_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
-                        void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
-                        const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq, int total_q, int total_k,
-                        int max_seqlen_q, int max_seqlen_k, int Hq, int Hkv, int d, float scale, int causal,
-                        void* stream) {
+int fa_varlen_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens_q,
+                        const int32_t* cu_seqlens_k, int nseq, int total_q, int total_k, int max_seqlen_q,
+                        int max_seqlen_k, int Hq, int Hkv, int d, float scale, int causal, void* stream) {
+  return varlen_cross_fwd_any(0, Q, K, V, O, LSE, cu_seqlens_q, cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q,
+                              max_seqlen_k, Hq, Hkv, d, scale, causal, stream);
+}
+
+int fa_varlen_cross_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq, int total_q,
+                            int total_k, int max_seqlen_q, int max_seqlen_k, int Hq, int Hkv, int d, float scale,
+                            int causal, void* stream) {
+  return varlen_cross_fwd_any(1, Q, K, V, O, LSE, cu_seqlens_q, cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q,
+                              max_seqlen_k, Hq, Hkv, d, scale, causal, stream);
+}
+
+static int varlen_cross_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                                size_t workspace_bytes, const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k,
+                                int nseq, int total_q, int total_k, int max_seqlen_q, int max_seqlen_k, int Hq,
+                                int Hkv, int d, float scale, int causal, void* stream) {
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return FA_ERR_NULL;
   if (int e = check_varlen_cross(cu_seqlens_q, cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q, max_seqlen_k)) return e;
   if (int e = check_common(Hq, Hkv, d, scale)) return e;
@@ -747,7 +793,27 @@ int fa_varlen_cross_bwd(const void* Q, const void* K, const void* V, const void*
     return FA_ERR_ALIGN;
   if (workspace_bytes < ws_bytes(total_q, Hq, d)) return FA_ERR_WORKSPACE;
   return run_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, cu_seqlens_q, nseq, max_seqlen_q, max_seqlen_k, total_q,
-                 Hq, Hkv, d, scale, causal, 7, stream, cu_seqlens_k);
+                 Hq, Hkv, d, scale, causal, 7, stream, cu_seqlens_k, half_precision(f16));
+}
+
+int fa_varlen_cross_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                        void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                        const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq, int total_q, int total_k,
+                        int max_seqlen_q, int max_seqlen_k, int Hq, int Hkv, int d, float scale, int causal,
+                        void* stream) {
+  return varlen_cross_bwd_any(0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens_q,
+                              cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q, max_seqlen_k, Hq, Hkv, d, scale,
+                              causal, stream);
+}
+
+int fa_varlen_cross_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                            const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                            const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int nseq, int total_q,
+                            int total_k, int max_seqlen_q, int max_seqlen_k, int Hq, int Hkv, int d, float scale,
+                            int causal, void* stream) {
+  return varlen_cross_bwd_any(1, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens_q,
+                              cu_seqlens_k, nseq, total_q, total_k, max_seqlen_q, max_seqlen_k, Hq, Hkv, d, scale,
+                              causal, stream);
 }
 
 size_t fa_splitkv_fwd_workspace_bytes(int B, int Hq, int Nq, int d, int num_splits) {
@@ -755,9 +821,9 @@ size_t fa_splitkv_fwd_workspace_bytes(int B, int Hq, int Nq, int d, int num_spli
   return round_up((size_t)num_splits * B * Nq * Hq * (d + 1) * sizeof(float), 256);
 }
 
-int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, void* workspace,
-                   size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
-                   int num_splits, void* stream) {
+static int splitkv_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE, void* workspace,
+                           size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                           int causal, int num_splits, void* stream) {
   if (!Q || !K || !V || !O || !LSE || !workspace) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
   if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
@@ -767,19 +833,33 @@ int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* 
     return FA_ERR_ALIGN;
   if (workspace_bytes < fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)) return FA_ERR_WORKSPACE;
   return run_fwd(Q, K, V, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream, num_splits,
-                 workspace);
+                 workspace, nullptr, half_precision(f16));
 }
 
-int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
-                   const int32_t* block_table, void* O, float* LSE, void* workspace, size_t workspace_bytes, int B,
-                   int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq, float scale, int causal,
+int fa_splitkv_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, void* workspace,
+                   size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
                    int num_splits, void* stream) {
+  return splitkv_fwd_any(0, Q, K, V, O, LSE, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                         num_splits, stream);
+}
+
+int fa_splitkv_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE, void* workspace,
+                       size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                       int num_splits, void* stream) {
+  return splitkv_fwd_any(1, Q, K, V, O, LSE, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                         num_splits, stream);
+}
+
+static int kvcache_fwd_any(int f16, const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
+                           const int32_t* block_table, void* O, float* LSE, void* workspace, size_t workspace_bytes,
+                           int B, int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq,
+                           float scale, int causal, int num_splits, void* stream) {
   if (!Q || !Kcache || !Vcache || !O || !LSE || !workspace) return FA_ERR_NULL;
   if (int e = check_cross(B, Nq, Nk, causal)) return e;
   if (int e = check_common(Hq, Hkv, d, scale, false)) return e;
   if (num_splits < 1 || num_splits > FA_SPLITKV_MAX_SPLITS) return FA_ERR_SHAPE;
   if ((long)Nq * (Hq / Hkv) > 0x7fffffffL) return FA_ERR_SHAPE;
-  Options opt;
+  Options opt = half_precision(f16);
   opt.seqlens_k = seqlens_k;
   if (block_table) {
     if (page_size < 64 || (page_size & (page_size - 1))) return FA_ERR_UNSUPPORTED;  // whole blocks of 64 keys per page
@@ -795,6 +875,22 @@ int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const 
   if (workspace_bytes < fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, num_splits)) return FA_ERR_WORKSPACE;
   return run_fwd(Q, Kcache, Vcache, O, LSE, nullptr, B, Nq, Nk, (long)B * Nq, Hq, Hkv, d, scale, causal, stream,
                  num_splits, workspace, nullptr, opt);
+}
+
+int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
+                   const int32_t* block_table, void* O, float* LSE, void* workspace, size_t workspace_bytes, int B,
+                   int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq, float scale, int causal,
+                   int num_splits, void* stream) {
+  return kvcache_fwd_any(0, Q, Kcache, Vcache, seqlens_k, block_table, O, LSE, workspace, workspace_bytes, B, Hq, Hkv,
+                         Nq, Nk, d, page_size, pages_per_seq, scale, causal, num_splits, stream);
+}
+
+int fa_kvcache_fwd_f16(const void* Q, const void* Kcache, const void* Vcache, const int32_t* seqlens_k,
+                       const int32_t* block_table, void* O, float* LSE, void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, int page_size, int pages_per_seq, float scale,
+                       int causal, int num_splits, void* stream) {
+  return kvcache_fwd_any(1, Q, Kcache, Vcache, seqlens_k, block_table, O, LSE, workspace, workspace_bytes, B, Hq, Hkv,
+                         Nq, Nk, d, page_size, pages_per_seq, scale, causal, num_splits, stream);
 }
 
 size_t fa_mfma_probe_scratch_bytes(void) { return 16 + (size_t)256 * 512 * sizeof(float); }

@@ -216,20 +216,20 @@ def make_fp8(B, Nq, Nk, Hq, Hkv, d, causal, seed, scale=None, name="fp8") -> Att
 
 
 def make_varlen(seqlens, Hq, Hkv, d, causal, seed, scale=None,
-                name="varlen") -> AttnProblem:
+                name="varlen", dtype="bf16") -> AttnProblem:
     """Packed ragged batch: tokens of all sequences concatenated."""
     seqlens = np.asarray(seqlens, dtype=np.int64)
     cu = np.zeros(len(seqlens) + 1, dtype=np.int32)
     cu[1:] = np.cumsum(seqlens)
     T = int(cu[-1])
     rng = np.random.default_rng(seed)
-    Q = _draw(rng, (T, Hq, d))
-    K = _draw(rng, (T, Hkv, d))
-    V = _draw(rng, (T, Hkv, d))
-    dO = _draw(rng, (T, Hq, d))
+    Q = _draw(rng, (T, Hq, d), dtype=dtype)
+    K = _draw(rng, (T, Hkv, d), dtype=dtype)
+    V = _draw(rng, (T, Hkv, d), dtype=dtype)
+    dO = _draw(rng, (T, Hq, d), dtype=dtype)
     return AttnProblem(name=name, Q=Q, K=K, V=V, dO=dO, Hq=Hq, Hkv=Hkv, d=d,
                        scale=float(scale if scale is not None else d ** -0.5),
-                       causal=bool(causal), cu_seqlens=cu, seed=seed,
+                       causal=bool(causal), cu_seqlens=cu, seed=seed, dtype=dtype,
                        meta={"max_seqlen": int(seqlens.max()) if len(seqlens) else 0})
 
 
