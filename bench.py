@@ -57,10 +57,10 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "4629dd21b9bb",
-    "d128_n8k_causal": {"fwd_kernel": 680513090, "bwd_dkdv_kernel": 841851599, "bwd_dq_kernel": 717905621},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269804113, "bwd_dkdv_kernel": 405200195, "bwd_dq_kernel": 338086201},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 873108946, "bwd_dkdv_kernel": 880117876, "bwd_dq_kernel": 831731514},
+    "sources": "0e95ec7c36ab",
+    "d128_n8k_causal": {"fwd_kernel": 658555881, "bwd_dkdv_kernel": 878704701, "bwd_dq_kernel": 732921521},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269785445, "bwd_dkdv_kernel": 405113984, "bwd_dq_kernel": 337860946},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 870471604, "bwd_dkdv_kernel": 881238500, "bwd_dq_kernel": 831303347},
 }
 
 
