@@ -61,6 +61,8 @@ Readings taken where the text is silent or inconsistent:
     softmax; reading: P = 0 on that row, hence O = 0, L = -inf, and the row
     contributes nothing to any gradient. M is [Bm, Hm, Nq, Nk] with Bm in
     {1, B} and Hm in {1, Hq} (size 1 = shared).
+    Read as a learned bias M has a gradient of its own: dM = dS = P o (dP - D), the dS of
+    Algorithm 2 before the factor `scale` (removed entries: 0).
 
   * local (sliding-window) and block-sparse attention (section 5 names them as patterns the
     method combines with; no definition is given). Reading: both only REMOVE entries of S
@@ -472,6 +474,32 @@ def head_backward_masked(q, k, v, mask, do, scale, causal):
     big_d = np.sum(do * o, axis=1, keepdims=True)
     ds = p * (dp - big_d)
     return scale * (ds @ k), scale * (ds.T @ q), dv
+
+
+def head_backward_mask_gradient(q, k, v, mask, do, scale, causal):
+    """One head: dM, the derivative of sum(O * dO) with respect to the mask added to the scaled
+    scores. S = scale * Q K^T + M, so dM = dS = P o (dP - D) of Algorithm 2 (without the factor
+    `scale` that dQ and dK carry). Entries that are removed (M = -inf, or above the causal
+    diagonal) have P = 0 and so dM = 0: moving them by a finite amount changes nothing."""
+    o, _, p = head_forward_masked(q, k, v, mask, scale, causal)
+    dp = do @ v.T
+    big_d = np.sum(do * o, axis=1, keepdims=True)
+    return p * (dp - big_d)
+
+
+def attention_backward_mask_gradient(Q, K, V, M, dO, scale, causal):
+    """Dense batch: dM [B, Hq, Nq, Nk] for a mask with an entry of its own per (sequence, head)
+    (M [B, Hq, Nq, Nk]; a shared mask's gradient would be the sum over what shares it)."""
+    B, Nq, Hq, d = Q.shape
+    G = _group(Hq, K.shape[2])
+    if M.shape[0] != B or M.shape[1] != Hq:
+        raise ValueError("the mask gradient is defined here for M [B, Hq, Nq, Nk]")
+    dM = np.empty((B, Hq, Nq, K.shape[1]), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            dM[b, h] = head_backward_mask_gradient(Q[b, :, h], K[b, :, h // G], V[b, :, h // G], M[b, h], dO[b, :, h],
+                                                   scale, causal)
+    return dM
 
 
 def _mask_of(M, b, h):

@@ -837,6 +837,42 @@ def test_masked_backward_matches_finite_differences(causal):
         assert not got[0][1].any()  # the row without any key has no gradient
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_mask_gradient_matches_finite_differences_and_its_invariants(causal):
+    """dM against central differences of sum(O * dO) over every finite entry of M (brute-force
+    forward); zero where the entry is removed; every row of dM sums to zero (a constant added to a
+    row of M changes no probability); dQ = scale * dM K and dK = scale * dM^T Q."""
+    nq, nk, d, scale = 4, 6, 3, 0.45
+    q, k, v, do = rnd(250, nq, d), rnd(251, nk, d), rnd(252, nk, d), rnd(253, nq, d)
+    m = some_mask(254, nq, nk, dead_row=None if causal else 1)
+    dm = orc.head_backward_mask_gradient(q, k, v, m, do, scale, causal)
+
+    def loss(mm):
+        O, _ = brute_forward_masked(q.tolist(), k.tolist(), v.tolist(), mm.tolist(), scale, causal)
+        return float(np.sum(np.asarray(O) * do))
+
+    for idx in np.ndindex(nq, nk):
+        if np.isneginf(m[idx]) or (causal and idx[1] > idx[0] + nk - nq):
+            assert dm[idx] == 0.0
+            continue
+        mp, mm_ = m.copy(), m.copy()
+        mp[idx] += 1e-5
+        mm_[idx] -= 1e-5
+        assert abs((loss(mp) - loss(mm_)) / 2e-5 - dm[idx]) < 1e-8, idx
+    assert np.max(np.abs(dm.sum(axis=1))) < 1e-14
+    dq, dk, _ = orc.head_backward_masked(q, k, v, m, do, scale, causal)
+    np.testing.assert_allclose(scale * dm @ k, dq, atol=1e-14)
+    np.testing.assert_allclose(scale * dm.T @ q, dk, atol=1e-14)
+    # the batch wrapper is the head function per (sequence, head), grouped heads included
+    Q, K, V, dO = rnd(255, 2, nq, 4, d), rnd(256, 2, nk, 2, d), rnd(257, 2, nk, 2, d), rnd(258, 2, nq, 4, d)
+    M = np.stack([np.stack([some_mask(260 + 4 * b + h, nq, nk, dead_row=None) for h in range(4)]) for b in range(2)])
+    dM = orc.attention_backward_mask_gradient(Q, K, V, M, dO, scale, causal)
+    for b in range(2):
+        for h in range(4):
+            assert np.array_equal(dM[b, h], orc.head_backward_mask_gradient(Q[b, :, h], K[b, :, h // 2], V[b, :, h // 2],
+                                                                           M[b, h], dO[b, :, h], scale, causal))
+
+
 def test_masked_batch_wrapper_shares_masks_over_batch_and_heads():
     B, Nq, Nk, Hq, Hkv, d = 2, 3, 5, 4, 2, 2
     Q, K, V, dO = rnd(250, B, Nq, Hq, d), rnd(251, B, Nk, Hkv, d), rnd(252, B, Nk, Hkv, d), rnd(253, B, Nq, Hq, d)
