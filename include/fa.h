@@ -270,6 +270,37 @@ int fa_mask_bwd(const void* Q, const void* K, const void* V, const void* M, cons
                 void* stream);
 
 /*
+ * fa_mask_bwd that also returns the gradient of the mask, for a mask read as a learned bias (the
+ * footnote of section 2.2 names masking and no more; with S = scale * Q K^T + M the derivative with
+ * respect to M is Algorithm 2's dS = P o (dP - D), before the factor `scale` that dQ and dK carry).
+ * dM (device, element type of Q, 16-byte aligned) receives entry (b, h, r, c) at
+ *     dM[b * dmask_batch_stride + h * dmask_head_stride + r * dmask_row_stride + c]
+ * for EVERY (sequence, query head), also when M itself is shared over sequences or heads (the
+ * gradient of a shared mask is the sum of dM over what shares it, left to the caller). Strides in
+ * elements, multiples of 8, dmask_row_stride >= Nk rounded up to 8, dmask_head_stride >= Nq rows,
+ * dmask_batch_stride >= Hq heads (FA_ERR_SHAPE otherwise). Entries that M removes get 0. Up to three
+ * elements of a row's padding past column Nk may be written (zeros). With causal = 1 the kernels
+ * never visit blocks of 64 keys that lie wholly above a wavefront's 32 rows: those entries (all
+ * zero) are NOT written, so pass dM zero-filled when the causal rule is on. Everything else,
+ * dQ, dK, dV included, is fa_mask_bwd (or fa_mask_bwd_f16). Writing dM costs N_q x N_k elements of
+ * HBM traffic per head, which the rest of the pass avoids.
+ */
+int fa_mask_bwd_dmask(const void* Q, const void* K, const void* V, const void* M, const void* O,
+                      const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* dM,
+                      void* workspace, size_t workspace_bytes,
+                      int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                      long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                      long long dmask_batch_stride, long long dmask_head_stride,
+                      long long dmask_row_stride, void* stream);
+int fa_mask_bwd_dmask_f16(const void* Q, const void* K, const void* V, const void* M, const void* O,
+                          const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* dM,
+                          void* workspace, size_t workspace_bytes,
+                          int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                          long long mask_batch_stride, long long mask_head_stride,
+                          long long mask_row_stride, long long dmask_batch_stride,
+                          long long dmask_head_stride, long long dmask_row_stride, void* stream);
+
+/*
  * Local (sliding-window) attention (section 5, "Discussion and Future Directions", names local
  * attention as a pattern the method combines with; the block skipping of section 3.1.1,
  * "Causal masking", is what makes it cheap). Reading: with query r standing at position

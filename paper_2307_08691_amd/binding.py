@@ -65,6 +65,10 @@ SIGNATURES = {
                     [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_mask_bwd_f16": (_c_int, [_c_void_p] * 10 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
                     [ctypes.c_longlong] * 3 + [_c_void_p]),
+    "fa_mask_bwd_dmask": (_c_int, [_c_void_p] * 11 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
+                          [ctypes.c_longlong] * 6 + [_c_void_p]),
+    "fa_mask_bwd_dmask_f16": (_c_int, [_c_void_p] * 11 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int] +
+                          [ctypes.c_longlong] * 6 + [_c_void_p]),
     "fa_local_fwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
@@ -238,6 +242,13 @@ def fa_mask_bwd_raw(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv
     fn = load().fa_mask_bwd_f16 if f16 else load().fa_mask_bwd
     return fn(Q, K, V, M, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), mask_bs,
               mask_hs, mask_rs, stream)
+
+
+def fa_mask_bwd_dmask_raw(Q, K, V, M, O, dO, LSE, dQ, dK, dV, dM, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs,
+                          mask_hs, mask_rs, dm_bs, dm_hs, dm_rs, stream=0, f16=False) -> int:
+    fn = load().fa_mask_bwd_dmask_f16 if f16 else load().fa_mask_bwd_dmask
+    return fn(Q, K, V, M, O, dO, LSE, dQ, dK, dV, dM, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, int(causal), mask_bs,
+              mask_hs, mask_rs, dm_bs, dm_hs, dm_rs, stream)
 
 
 def fa_local_fwd_raw(Q, K, V, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream=0, f16=False) -> int:
@@ -611,6 +622,26 @@ def fa_mask_bwd(Q, K, V, M, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=
                            _ptr(dV), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale, causal, bs, hs, rs,
                            _stream(), x.et == torch.float16))
     return dQ, dK, dV
+
+
+def fa_mask_bwd_dmask(Q, K, V, M, O, dO, LSE, scale: float, causal: bool, dQ=None, dK=None, dV=None, dM=None, workspace=None):
+    """fa_mask_bwd that also returns dM [B, Hq, Nq, Nk] (the gradient of a mask read as a bias), a view
+    into a zero-filled buffer whose rows are padded to a multiple of 8 elements. A caller-supplied dM
+    must be such a view (mask_buffer(B, Hq, Nq, Nk, dtype=...)) and, under the causal rule, zero-filled."""
+    import torch
+    x = _dense(Q, K, V)
+    bs, hs, rs = _mask_strides(M, x)
+    dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
+    if dM is None:
+        dM = mask_buffer(x.B, x.Hq, x.Nq, x.Nk, device=x.dev, dtype=x.et)
+    if dM.dtype != x.et or dM.device != x.dev or tuple(dM.shape) != (x.B, x.Hq, x.Nq, x.Nk) or dM.stride(3) != 1:
+        raise ValueError("dM must be [B, Hq, Nq, Nk] of the element type of Q, on its device, key dimension contiguous")
+    ws = _workspace(workspace, fa_cross_bwd_workspace_bytes(x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d), x.dev)
+    _check(fa_mask_bwd_dmask_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
+                                 _ptr(dV), _ptr(dM), _ptr(ws), _wsbytes(ws), x.B, x.Hq, x.Hkv, x.Nq, x.Nk, x.d, scale,
+                                 causal, bs, hs, rs, dM.stride(0), dM.stride(1), dM.stride(2), _stream(),
+                                 x.et == torch.float16))
+    return dQ, dK, dV, dM
 
 
 def fa_local_fwd(Q, K, V, scale: float, window_left: int, window_right: int, O=None, LSE=None):

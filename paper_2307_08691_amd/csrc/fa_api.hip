@@ -134,6 +134,8 @@ struct Options {
   const int32_t* seqlens_k = nullptr;    // key/value cache (split forward only): per-sequence lengths,
   const int32_t* block_table = nullptr;  // page table with its row stride, log2 of the page size
   int page_log2 = 0, table_stride = 0;
+  void* dM = nullptr;                    // masked backward: where the gradient of the mask goes, with its strides
+  long long dm_bs = 0, dm_hs = 0, dm_rs = 0;
 };
 
 Options half_precision(int f16) {
@@ -243,6 +245,10 @@ int run_bwd(const void* Q, const void* K, const void* V, const void* O, const vo
   a.dK = (__bf16*)dK;
   a.dV = (__bf16*)dV;
   a.Dvec = (float*)ws;
+  a.dM = (__bf16*)opt.dM;
+  a.dm_bs = (long)opt.dm_bs;
+  a.dm_hs = (long)opt.dm_hs;
+  a.dm_rs = (long)opt.dm_rs;
   hipError_t e = fa::launch_bwd(a, d, causal, stages, (hipStream_t)stream);
   if (e != hipSuccess) {
     g_last_hip_error = (int)e;
@@ -572,6 +578,50 @@ int fa_mask_bwd_f16(const void* Q, const void* K, const void* V, const void* M, 
                     long long mask_head_stride, long long mask_row_stride, void* stream) {
   return mask_bwd_any(1, Q, K, V, M, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale,
                       causal, mask_batch_stride, mask_head_stride, mask_row_stride, stream);
+}
+
+static int mask_bwd_dmask_any(int f16, const void* Q, const void* K, const void* V, const void* M, const void* O,
+                              const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* dM, void* workspace,
+                              size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale,
+                              int causal, long long mask_batch_stride, long long mask_head_stride,
+                              long long mask_row_stride, long long dmask_batch_stride, long long dmask_head_stride,
+                              long long dmask_row_stride, void* stream) {
+  if (!dM) return FA_ERR_NULL;
+  if (!aligned16(dM)) return FA_ERR_ALIGN;
+  // every (sequence, head) has rows of its own in dM: strides as for M, none of them zero
+  if (dmask_row_stride < (((long long)Nk + 7) & ~7LL) || dmask_row_stride % 8 || dmask_head_stride % 8 ||
+      dmask_batch_stride % 8 || dmask_head_stride < dmask_row_stride * Nq ||
+      dmask_batch_stride < dmask_head_stride * Hq)
+    return FA_ERR_SHAPE;
+  Options opt = of_type(with_mask(M, mask_batch_stride, mask_head_stride, mask_row_stride), f16);
+  opt.dM = dM;
+  opt.dm_bs = dmask_batch_stride;
+  opt.dm_hs = dmask_head_stride;
+  opt.dm_rs = dmask_row_stride;
+  return cross_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d, scale, causal,
+                   stream, opt);
+}
+
+int fa_mask_bwd_dmask(const void* Q, const void* K, const void* V, const void* M, const void* O, const void* dO,
+                      const float* LSE, void* dQ, void* dK, void* dV, void* dM, void* workspace, size_t workspace_bytes,
+                      int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                      long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                      long long dmask_batch_stride, long long dmask_head_stride, long long dmask_row_stride,
+                      void* stream) {
+  return mask_bwd_dmask_any(0, Q, K, V, M, O, dO, LSE, dQ, dK, dV, dM, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d,
+                            scale, causal, mask_batch_stride, mask_head_stride, mask_row_stride, dmask_batch_stride,
+                            dmask_head_stride, dmask_row_stride, stream);
+}
+
+int fa_mask_bwd_dmask_f16(const void* Q, const void* K, const void* V, const void* M, const void* O, const void* dO,
+                          const float* LSE, void* dQ, void* dK, void* dV, void* dM, void* workspace,
+                          size_t workspace_bytes, int B, int Hq, int Hkv, int Nq, int Nk, int d, float scale, int causal,
+                          long long mask_batch_stride, long long mask_head_stride, long long mask_row_stride,
+                          long long dmask_batch_stride, long long dmask_head_stride, long long dmask_row_stride,
+                          void* stream) {
+  return mask_bwd_dmask_any(1, Q, K, V, M, O, dO, LSE, dQ, dK, dV, dM, workspace, workspace_bytes, B, Hq, Hkv, Nq, Nk, d,
+                            scale, causal, mask_batch_stride, mask_head_stride, mask_row_stride, dmask_batch_stride,
+                            dmask_head_stride, dmask_row_stride, stream);
 }
 
 // Sliding window. Without any bound this is plain attention and with win_right = 0 alone the

@@ -1148,6 +1148,23 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) dP[kt][r] = NEGD ? S[kt][r] * dP[kt][r] : S[kt][r] * (dP[kt][r] - Dq);
+      if constexpr (MASK) {
+        // dM = dS (the mask enters the scores unscaled): this lane's four groups of four neighbouring
+        // keys of its row, 8 bytes each; removed entries have P = 0 and store zeros. Groups that start
+        // past the last key are left out (a group may reach up to three columns into the row's padding).
+        if (a.dM && row < n) {
+          long o = (long)row * a.dm_rs + col0 + 32 * kt + 4 * hh;
+          asm volatile("" : "+v"(o));  // (recomputed for every block instead of held in registers)
+          __bf16* dst = a.dM + s * a.dm_bs + (long)h * a.dm_hs + o;
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 x;
+            x[0] = pack2<F16>(dP[kt][4 * q4], dP[kt][4 * q4 + 1]);
+            x[1] = pack2<F16>(dP[kt][4 * q4 + 2], dP[kt][4 * q4 + 3]);
+            if (col0 + 32 * kt + 8 * q4 + 4 * hh < nk) *(u32x2*)(dst + 8 * q4) = x;
+          }
+        }
+      }
       dSf[kt][0] = pack8<F16>(dP[kt], 0);
       dSf[kt][1] = pack8<F16>(dP[kt], 1);
     }

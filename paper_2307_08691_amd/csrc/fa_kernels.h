@@ -37,6 +37,10 @@ struct BwdArgs {
   __bf16* dK;
   __bf16* dV;
   float* Dvec;   // workspace: rowsum(dO o O), laid out like LSE
+  // gradient of the elementwise mask (mask instantiation of the dQ kernel only; nullptr: not asked for):
+  // dM = dS in the element type, entry (s, h, r, c) at dM[s * dm_bs + h * dm_hs + r * dm_rs + c]
+  __bf16* dM;
+  long dm_bs, dm_hs, dm_rs;
 };
 
 // FP8 (E4M3) forward: Q, K one byte per element in the token-major layout, V key-major

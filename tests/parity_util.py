@@ -40,7 +40,7 @@ from paper_2307_08691_amd.inputs import AttnProblem
 TOL_O = 2e-2
 TOL_GRAD = 5e-2
 TOL_LSE = 1e-3
-FIXED = {"O": TOL_O, "LSE": TOL_LSE, "dQ": TOL_GRAD, "dK": TOL_GRAD, "dV": TOL_GRAD}
+FIXED = {"O": TOL_O, "LSE": TOL_LSE, "dQ": TOL_GRAD, "dK": TOL_GRAD, "dV": TOL_GRAD, "dM": TOL_GRAD}
 
 
 def to_gpu(bits: np.ndarray, dtype: str = "bf16"):
@@ -127,6 +127,7 @@ def reference_head(q, k, v, do, scale, causal, M=None, keep=None, rp=1.0, backwa
         big_d = (do.float() * o.float()).sum(dim=-1, keepdim=True)
         ds = (p.float() * (dp - big_d)).to(et)
         del dp
+        out["dM"] = ds  # (left on the GPU: only the mask-gradient tests fetch it)
         out["dQ"] = to_f64(((ds @ k).float() * scale).to(et))
         out["dK"] = to_f64(((ds.T @ q).float() * scale).to(et))
     return out
@@ -239,7 +240,7 @@ def run_oracle(prob: AttnProblem, backward: bool = True):
 
 
 def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=None, M=None, keep_of=None, rp=1.0,
-                    M_of=None):
+                    M_of=None, want_dm=False):
     """The 16-bit reference over a whole batch, in the oracle's layouts. Q, K, V, dO: torch tensors
     on the GPU, dense [B, N, H, d] or packed [T, H, d] with cumulative offsets cu_q (and cu_k for
     two lengths). M: torch [Bm, Hm, Nq, Nk] or None (dense only), or M_of(seq, head, nq, nk) ->
@@ -257,6 +258,8 @@ def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=N
         out = {"O": np.zeros(tuple(Q.shape)), "LSE": np.zeros((nseq, Hq, Q.shape[1]))}
     if backward:
         out.update(dQ=np.zeros(tuple(Q.shape)), dK=np.zeros(tuple(K.shape)), dV=np.zeros(tuple(V.shape)))
+    if want_dm:  # dense only: the 16-bit dS of every (sequence, head)
+        out["dM"] = np.zeros((nseq, Hq, Q.shape[1], K.shape[1]))
     for s in range(nseq):
         if packed:
             a, e, ak, ek = int(cu_q[s]), int(cu_q[s + 1]), int(cu_k[s]), int(cu_k[s + 1])
@@ -286,6 +289,8 @@ def reference_batch(Q, K, V, dO, scale, causal, backward=True, cu_q=None, cu_k=N
                     out["dQ"][s, :, h] = r["dQ"]
                     out["dK"][s, :, h // G] += r["dK"]
                     out["dV"][s, :, h // G] += r["dV"]
+                if want_dm:
+                    out["dM"][s, h] = to_f64(r["dM"])
     return out
 
 

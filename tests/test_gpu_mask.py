@@ -137,6 +137,39 @@ def test_the_causal_rule_written_as_a_mask():
     assert float((L1 - L2).abs().max()) <= 1e-5
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("Nq,Nk,Hq,Hkv,d,kind,Bm,Hm", [(65, 65, 2, 2, 64, "bias", 2, 2), (70, 333, 4, 2, 128, "mixed", 2, 4),
+                                                       (300, 515, 2, 1, 64, "dead", 2, 2), (515, 515, 4, 2, 128, "mixed", 1, 1),
+                                                       (257, 300, 2, 2, 128, "bias", 2, 1)])
+def test_gradient_of_the_mask(Nq, Nk, Hq, Hkv, d, kind, Bm, Hm, dtype, causal):
+    """fa_mask_bwd_dmask: dM = dS for every (sequence, head), also under shared masks, against the
+    oracle's mask gradient and the 16-bit reference's dS; dQ, dK, dV are those of fa_mask_bwd bit for bit;
+    the padding of dM's rows holds nothing but zeros; entries the mask or the causal rule removes are 0."""
+    prob = inputs.make_cross(B=2, Nq=Nq, Nk=Nk, Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=9300 + Nq + Nk, dtype=dtype)
+    mbits = make_mask(9310 + Nq, Bm, Hm, Nq, Nk, kind, dtype=dtype)
+    Q, K, V, dO = (pu.to_gpu(x, dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    M = mask_to_gpu(mbits, dtype)
+    O, L = binding.fa_mask_fwd(Q, K, V, M, prob.scale, causal)
+    dQ, dK, dV, dM = binding.fa_mask_bwd_dmask(Q, K, V, M, O, dO, L, prob.scale, causal)
+    g2 = binding.fa_mask_bwd(Q, K, V, M, O, dO, L, prob.scale, causal)
+    torch.cuda.synchronize()
+    for a, b in zip((dQ, dK, dV), g2):
+        assert torch.equal(a, b)
+    widen = orc.widen_f16 if dtype == "f16" else orc.widen_bf16
+    Qf, Kf, Vf, dOf, Mf = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO, mbits))
+    Mfull = np.broadcast_to(Mf, (2, Hq, Nq, Nk))
+    exp = orc.attention_backward_mask_gradient(Qf, Kf, Vf, Mfull, dOf, prob.scale, causal)
+    ref = pu.reference_batch(Q, K, V, dO, prob.scale, causal, M=M[:, :, :, :Nk], want_dm=True)
+    # (no fixed bound is stated for dM anywhere: the yardstick clause alone, error <= the 16-bit reference's + 1 ulp)
+    pu.judge(f"mask gradient {pu.describe(prob)} {kind} shared {Bm}x{Hm}", {"dM": pu.to_f64(dM)}, {"dM": exp}, ref,
+             standard=False, dtype=dtype, d=d)
+    gone = np.isneginf(Mfull) | (causal & (np.arange(Nk)[None, :] > np.arange(Nq)[:, None] + Nk - Nq))[None, None]
+    assert not pu.to_f64(dM)[gone].any()
+    whole = dM.as_strided((2, Hq, Nq, dM.stride(2)), (dM.stride(0), dM.stride(1), dM.stride(2), 1))
+    assert not whole[..., Nk:].float().abs().any()
+
+
 def test_bad_mask_descriptions_are_rejected():
     q = torch.zeros(1, 16, 2, 64, dtype=torch.bfloat16, device="cuda")
     o = torch.empty_like(q)
