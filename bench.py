@@ -65,11 +65,11 @@ MEASURED_TRAFFIC = {
 
 
 def kernel_sources_id() -> str:
-    """Short hash of the sources of the bf16 forward and backward kernels (the ones the counter passes
-    cover): identifies what a counter pass measured."""
+    """Short hash of the sources of the bf16 forward, backward and decode kernels (the ones the counter
+    passes cover): identifies what a counter pass measured."""
     d = os.path.join(ROOT, "paper_2307_08691_amd", "csrc")
     h = hashlib.sha1()
-    for f in ("fa_bwd.hip", "fa_common.h", "fa_fwd.hip", "fa_kernels.h", "fa_lds.h"):
+    for f in ("fa_bwd.hip", "fa_common.h", "fa_decode.hip", "fa_fwd.hip", "fa_kernels.h", "fa_lds.h"):
         h.update(f.encode())
         h.update(open(os.path.join(d, f), "rb").read())
     return h.hexdigest()[:12]
@@ -375,6 +375,7 @@ def bench_decode(args, prob, binding) -> int:
     LSE = torch.empty((B, Hq, Nq), dtype=torch.float32, device="cuda")
     ws = torch.empty(binding.fa_splitkv_fwd_workspace_bytes(B, Hq, Nq, d, splits), dtype=torch.uint8, device="cuda")
     cache = prob.meta.get("cache")
+    few_rows = Nq * (Hq // prob.Hkv) <= 32  # one row tile per key/value head: the library runs its decode kernel
     lens = None
     if cache:  # per-sequence lengths over a paged cache: fa_kvcache_fwd
         from paper_2307_08691_amd import inputs
@@ -421,8 +422,8 @@ def bench_decode(args, prob, binding) -> int:
                    "causal": prob.causal, "num_splits": splits, "algorithmic_bytes": alg_bytes,
                    **({"page": cache["page"], "cached_keys": int(lens.sum())} if cache else {})},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
-                     **traffic_fields(prob.name, "fwd_kernel"), "avg_kernel_ms": kern_ms,
-                     "kernel": "fwd_kernel<.., split> + fwd_merge_kernel"},
+                     **traffic_fields(prob.name, "fwd_decode_kernel" if few_rows else "fwd_kernel"), "avg_kernel_ms": kern_ms,
+                     "kernel": ("fwd_decode_kernel" if few_rows else "fwd_kernel<.., split>") + " + fwd_merge_kernel"},
     }
     if not args.no_cpu_baseline:
         from oracle import attention_oracle as orc

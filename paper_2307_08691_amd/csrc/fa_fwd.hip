@@ -958,11 +958,15 @@ template <int D, bool F16>
 static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
   dim3 block(512);
   if (a.nsplit > 0) {
-    const int nblk = (a.p.N * a.p.G + 255) / 256;
-    dim3 grid(grid_size(nblk * a.nsplit, a.p.Hkv * a.p.nseq));
-    if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, true, F16>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((fwd_kernel<D, false, true, F16>), grid, block, 0, st, a);
-    if (hipError_t e = hipGetLastError()) return e;
+    if (a.p.N * a.p.G <= 32) {  // one row tile per key/value head: the wavefronts divide the keys (fa_decode.hip)
+      if (hipError_t e = launch_fwd_decode(a, D, causal, st)) return e;
+    } else {
+      const int nblk = (a.p.N * a.p.G + 255) / 256;
+      dim3 grid(grid_size(nblk * a.nsplit, a.p.Hkv * a.p.nseq));
+      if (causal) hipLaunchKernelGGL((fwd_kernel<D, true, true, F16>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((fwd_kernel<D, false, true, F16>), grid, block, 0, st, a);
+      if (hipError_t e = hipGetLastError()) return e;
+    }
     constexpr int RPB = 256 / (D / 4);
     const long nrows = (long)a.p.total_tokens * a.p.Hq;
     hipLaunchKernelGGL((fwd_merge_kernel<D, F16>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);

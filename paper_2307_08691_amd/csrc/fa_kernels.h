@@ -57,6 +57,9 @@ struct Fp8Args {
 };
 
 hipError_t launch_fwd(const FwdArgs& a, int d, int causal, hipStream_t st);
+// split forward for at most 32 (query row, head of the group) pairs per key/value head (fa_decode.hip):
+// writes the shares' partial results like the split kernel; d in {64, 128}
+hipError_t launch_fwd_decode(const FwdArgs& a, int d, int causal, hipStream_t st);
 hipError_t launch_fwd_fp8(const Fp8Args& a, int d, int causal, hipStream_t st);
 // stages: bit 0 D pre-pass, bit 1 dK/dV kernel, bit 2 dQ kernel
 hipError_t launch_bwd(const BwdArgs& a, int d, int causal, int stages, hipStream_t st);

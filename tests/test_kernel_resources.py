@@ -36,7 +36,7 @@ def resource_remarks(source):
 @pytest.fixture(scope="module")
 def remarks():
     with concurrent.futures.ThreadPoolExecutor(4) as ex:
-        parts = list(ex.map(resource_remarks, ["fa_fwd.hip", "fa_bwd.hip", "fa_d256.hip", "fa_fp8.hip"]))
+        parts = list(ex.map(resource_remarks, ["fa_fwd.hip", "fa_bwd.hip", "fa_d256.hip", "fa_fp8.hip", "fa_decode.hip"]))
     return {k: v for part in parts for k, v in part.items()}
 
 
