@@ -57,10 +57,12 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "0e95ec7c36ab",
-    "d128_n8k_causal": {"fwd_kernel": 658555881, "bwd_dkdv_kernel": 878704701, "bwd_dq_kernel": 732921521},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269785445, "bwd_dkdv_kernel": 405113984, "bwd_dq_kernel": 337860946},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 870471604, "bwd_dkdv_kernel": 881238500, "bwd_dq_kernel": 831303347},
+    "sources": "0742979f981f",
+    "d128_n8k_causal": {"fwd_kernel": 675900830, "bwd_dkdv_kernel": 860072425, "bwd_dq_kernel": 734544732},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269785398, "bwd_dkdv_kernel": 405110450, "bwd_dq_kernel": 338076377},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 877169259, "bwd_dkdv_kernel": 880516321, "bwd_dq_kernel": 831736174},
+    "decode_b8_on_8k": {"fwd_decode_kernel": 269481180},
+    "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1023158325},
 }
 
 
@@ -80,7 +82,7 @@ def traffic_fields(workload: str, kernel: str) -> dict:
     if rec is None:
         return {"traffic": None}
     if MEASURED_TRAFFIC["sources"] == kernel_sources_id():
-        return {"traffic": rec, "traffic_from": f"profiles/pmc_{workload}_kernels.md"}
+        return {"traffic": rec, "traffic_from": f"profiles/{'bench' if workload.startswith('decode') else 'pmc'}_{workload}_{'kernel_stats' if workload.startswith('decode') else 'kernels'}.md"}
     return {"traffic": None, "traffic_recorded": {"bytes": rec, "profile": f"profiles/pmc_{workload}_kernels.md",
                                                   "kernel_sources": MEASURED_TRAFFIC["sources"],
                                                   "note": "measured on other kernel sources than this run's"}}
