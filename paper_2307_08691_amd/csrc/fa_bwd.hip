@@ -156,7 +156,13 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   const SeqInfo si = seq_info(p, s);
   const int n = si.n, nk = si.nk;  // query rows, key rows
   const int off = nk - n;          // position of query 0 among the keys (causal alignment)
-  const int j0 = bc.blk * BC;
+  // Causal: a key block's work grows with the number of rows below it, so the launch order (block 0
+  // first) is the longest-first order when block indices count from the END of the longest possible
+  // sequence: a shorter sequence of a ragged batch owns the last of them, and its blocks are handed out
+  // among the equally long remainders of the longer ones instead of ahead of them.
+  const int jblk = CAUSAL ? bc.blk - ((p.Nk + BC - 1) / BC - (nk + BC - 1) / BC) : bc.blk;
+  if (jblk < 0) return;
+  const int j0 = jblk * BC;
   if (j0 >= nk) return;
   const int dh = PAD ? p.d : D;  // row length in memory
   const long qstride = (long)p.Hq * dh, kstride = (long)p.Hkv * dh;
