@@ -46,8 +46,10 @@ constexpr int kFwdAheadQK = 4, kFwdAheadPV = 3;
 // The reference of the running softmax is only advanced (and O, l rescaled) when a lane's share
 // of a block's row sum exceeds 2^kFwdLazyLog2 (instantiations without the fast path: when some
 // row's maximum outgrew the reference by that factor); until then exponentials are taken against
-// the older reference and may reach 2^kFwdLazyLog2.
-constexpr int kFwdLazyLog2 = 8;
+// the older reference and may reach 2^kFwdLazyLog2. Half precision operands end at 65504 = 2^16;
+// bfloat16 has float32's range, and the wider margin saves most of the remaining advances when the
+// scores spread widely (3x the usual range: the row maximum grows by some 20 bits over 16k keys).
+constexpr int kFwdLazyLog2Half = 8, kFwdLazyLog2Bf16 = 20;
 // d = 128: workgroups that take several items in a row and overlap an item's start-up with the
 // end of the one before (fwd_chain_kernel), for sequences of at most kFwdChainMaxN keys
 constexpr int kFwdChainMaxN = 1024;
@@ -464,7 +466,7 @@ __global__ __launch_bounds__(512)
     bool advance = !FAST || t == tb;
     if (!advance) {
       exponentials(m * cs);
-      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << kFwdLazyLog2)) != 0;
+      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << (F16 ? kFwdLazyLog2Half : kFwdLazyLog2Bf16))) != 0;
     }
     if (advance) {
       float mx = max3(S[0][0], S[0][1], S[1][0]);
@@ -480,7 +482,7 @@ __global__ __launch_bounds__(512)
       // finite from the first block on and exp2(-inf) = 0 covers the start (not so with split
       // keys or a mask: GUARD). Without the fast path the reference is advanced only when some
       // row's maximum outgrew it by a factor 2^kFwdLazyLog2.
-      if (FAST || __builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)kFwdLazyLog2) != 0) {
+      if (FAST || __builtin_amdgcn_ballot_w64((m_new - m) * cs > (float)(F16 ? kFwdLazyLog2Half : kFwdLazyLog2Bf16)) != 0) {
         // (split, mask: a row that has still seen no key has m = m_new = -inf and nothing to rescale)
         const float alpha = GUARD && m_new == -INFINITY ? 1.f : fast_exp2((m - m_new) * cs);
         l *= alpha;
@@ -788,7 +790,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     bool advance = j == 0;
     if (!advance) {
       exponentials(m * c2);
-      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << kFwdLazyLog2)) != 0;
+      advance = __builtin_amdgcn_ballot_w64(rs0 + rs1 > (float)(1 << (F16 ? kFwdLazyLog2Half : kFwdLazyLog2Bf16))) != 0;
     }
     if (advance) {
       float mx = max3(S[0][0], S[0][1], S[1][0]);

@@ -60,3 +60,13 @@ def test_extreme_score_ranges(qk_mult, d, causal):
     growing along the keys: the running reference is advanced many times)."""
     prob = inputs.make_dense(B=1, N=700, Hq=2, Hkv=1, d=d, causal=causal, seed=14000 + d, qk_mult=qk_mult)
     check(prob)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d,qk_mult", [(64, 2.0), (128, 2.5), (128, 4.0)])
+def test_wide_scores_over_many_blocks(d, qk_mult, causal):
+    """4096 keys with scores several times the usual range: the row maximum keeps growing by tens of
+    bits along the keys, so exponentials are taken against a reference far below it (the forward
+    kernels let it lag by up to 2^20 for bfloat16) and the reference is advanced a few times per row."""
+    prob = inputs.make_dense(B=1, N=4096, Hq=2, Hkv=1, d=d, causal=causal, seed=14100 + d, qk_mult=qk_mult)
+    check(prob)
