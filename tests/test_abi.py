@@ -219,6 +219,61 @@ def test_split_key_entry_point_rejects_bad_arguments():
     assert binding.splitkv_default_splits(8, 32, 8, 1, 8192, ragged=True) == 8
 
 
+def test_window_pattern_cache_fp8_and_mask_gradient_entry_points_reject_bad_arguments():
+    def local(Nq=64, Nk=64, d=128, left=10, right=0, Q=P):
+        return binding.fa_local_fwd_raw(Q, P, P, P, P, 1, 4, 2, Nq, Nk, d, 0.1, left, right, 0)
+    assert local(Q=0) == binding.FA_ERR_NULL
+    assert local(Nq=65) == binding.FA_ERR_SHAPE          # a query would stand before the first key
+    assert local(d=96) == binding.FA_ERR_UNSUPPORTED     # a real window: the two tile widths only
+
+    def vlocal(cu=P, mx=400, d=128, left=10, right=0):
+        return binding.fa_varlen_local_fwd_raw(P, P, P, P, P, cu, 4, 1000, mx, 4, 2, d, 0.1, left, right, 0)
+    assert vlocal(cu=0) == binding.FA_ERR_NULL
+    assert vlocal(mx=2000) == binding.FA_ERR_SHAPE
+    assert vlocal(d=96) == binding.FA_ERR_UNSUPPORTED
+
+    def sparse(BM=P, block=128, bs=0, hs=0, Nk=512):
+        return binding.fa_blocksparse_fwd_raw(P, P, P, BM, P, P, 1, 4, 2, 512, Nk, 128, 0.1, 0, block, bs, hs, 0)
+    assert sparse(BM=0) == binding.FA_ERR_NULL
+    assert sparse(block=32) == binding.FA_ERR_SHAPE      # below the kernels' key block
+    assert sparse(block=96) == binding.FA_ERR_SHAPE      # not a power of two
+    assert sparse(hs=-8) == binding.FA_ERR_SHAPE
+    assert sparse(Nk=64 * 64 * 64 + 64) == binding.FA_ERR_UNSUPPORTED  # more key blocks than a bitmap holds
+
+    def cache(Q=P, sl=P, table=0, page=0, pps=0, Nk=1000, d=128, splits=2, ws_bytes=1 << 30):
+        return binding.fa_kvcache_fwd_raw(Q, P, P, sl, table, P, P, P, ws_bytes, 2, 4, 2, 1, Nk, d, page, pps, 0.1, 1, splits, 0)
+    assert cache(Q=0) == binding.FA_ERR_NULL
+    assert cache(sl=P + 2) == binding.FA_ERR_ALIGN       # lengths and tables are int32 arrays
+    assert cache(table=P, page=32, pps=64) == binding.FA_ERR_UNSUPPORTED   # a page holds whole blocks of 64 keys
+    assert cache(table=P, page=192, pps=8) == binding.FA_ERR_UNSUPPORTED   # and is a power of two
+    assert cache(table=P, page=64, pps=15) == binding.FA_ERR_SHAPE         # 960 rows of pages for up to 1000 keys
+    assert cache(table=P, page=64, pps=0) == binding.FA_ERR_SHAPE
+    assert cache(d=96) == binding.FA_ERR_UNSUPPORTED
+    assert cache(splits=0) == binding.FA_ERR_SHAPE
+    assert cache(ws_bytes=16) == binding.FA_ERR_WORKSPACE
+
+    def fp8(stride=1024, dq=1.0, dv=1.0, d=128, Nk=1000):
+        return binding.fa_fp8_fwd_raw(P, P, P, P, P, 1, 4, 2, 64, Nk, d, stride, 0.1, dq, 1.0, dv, 0, 0)
+    assert fp8(stride=1000) == binding.FA_ERR_SHAPE      # rows of V^T: a multiple of 64 bytes
+    assert fp8(stride=960) == binding.FA_ERR_SHAPE       # and at least the keys rounded up to 64
+    assert fp8(dq=0.0) == binding.FA_ERR_SHAPE
+    assert fp8(dv=float("inf")) == binding.FA_ERR_SHAPE
+    assert fp8(d=96) == binding.FA_ERR_UNSUPPORTED
+
+    def dmask(dM=P, rs=304, hs=304 * 64, bs=304 * 64 * 4, ws_bytes=1 << 20):
+        return binding.fa_mask_bwd_dmask_raw(P, P, P, P, P, P, P, P, P, P, dM, P, ws_bytes, 1, 4, 2, 64, 300, 128, 0.1, 0,
+                                             0, 0, 304, bs, hs, rs, 0)
+    assert dmask(dM=0) == binding.FA_ERR_NULL
+    assert dmask(dM=P + 8) == binding.FA_ERR_ALIGN
+    assert dmask(rs=296) == binding.FA_ERR_SHAPE         # rows shorter than the keys rounded up to 8
+    assert dmask(hs=0) == binding.FA_ERR_SHAPE           # dM is never shared over heads or sequences
+    assert dmask(bs=304 * 64) == binding.FA_ERR_SHAPE
+    assert dmask(ws_bytes=16) == binding.FA_ERR_WORKSPACE
+
+    # the entry point that allocates nothing: the size limit comes before anything else
+    assert binding.fa_bwd_noalloc_raw(P, P, P, P, P, P, P, P, P, 64, 32, 32, 8192, 128, 0.1, 1, 0) == binding.FA_ERR_WORKSPACE
+
+
 def test_mfma_probe_rejects_bad_arguments():
     assert binding.fa_mfma_probe_scratch_bytes() == 16 + 256 * 512 * 4
     assert binding.fa_mfma_probe_raw(10, 0, 0) == binding.FA_ERR_NULL
