@@ -50,6 +50,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA peak
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes recorded
 # under profiles/pmc_<workload>_kernels.md, already scaled by the copy-kernel factors given there.
@@ -225,6 +226,16 @@ def three_rates(prob, fwd_ms, bwd_ms, both_ms):
          "fwd_bwd_tflops": round(3.5 * fl / both_ms / 1e9, 1)}
     for k in ("fwd", "bwd", "fwd_bwd"):
         r[k + "_frac_of_peak"] = round(r[k + "_tflops"] / PEAK_BF16_TFLOPS, 4)
+    if not prob.varlen:
+        # What the HBM roofline (8 TB/s) allows for this shape: the credited FLOPs over the time the
+        # bytes that the kernels must move would take (the per-kernel figures of the roofline object:
+        # forward Q, O, K, V, L; dK/dV kernel Q, dO, L, D, K, V read and dK, dV written; dQ kernel Q, dO, O,
+        # L, K, V read and dQ, D written). Below the MFMA peak for short sequences: those points are HBM-bound.
+        B, N, Nk, Hq, Hkv, d = prob.B, prob.N, prob.keys, prob.Hq, prob.Hkv, prob.d
+        by_f = B * Hq * (4 * N * d + 4 * N) + B * Hkv * 4 * Nk * d
+        by_b = B * Hq * (4 * N * d + 8 * N) + B * Hkv * 8 * Nk * d + B * Hq * (8 * N * d + 12 * N) + B * Hkv * 4 * Nk * d
+        for k, mult, by in (("fwd", 1.0, by_f), ("bwd", 2.5, by_b), ("fwd_bwd", 3.5, by_f + by_b)):
+            r[k + "_hbm_bound_tflops"] = round(mult * fl / (by / (PEAK_HBM_GBS * 1e9)) / 1e12, 1)
     return r
 
 
