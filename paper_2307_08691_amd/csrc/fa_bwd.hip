@@ -903,24 +903,6 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   const long stat = s * p.lse_seq_stride + (long)h * p.lse_head_stride + (p.cu_seqlens ? si.tok0 : 0) + rowc;
   float Lq = row < n ? a.LSE[stat] * kLog2e : INFINITY;  // rows past the end: P = 0
   if ((MASK || LOCAL) && Lq == -INFINITY) Lq = INFINITY;  // a row that the mask (the pattern) left without keys: P = 0
-  float Dq;
-  if constexpr (OWN_D) {
-    // this lane holds half of its row of dO_i (the elements 16 ks + 8 hh ..): the same half of O_i,
-    // multiplied and summed, and the other half from the partner lane
-    const __bf16* op = a.O + ((si.tok0 + rowc) * p.Hq + h) * dh + 8 * hh;
-    float part = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      if (!PAD || 16 * ks + 8 * hh < dh) {
-        const bf16x8 o = *(const bf16x8*)(op + 16 * ks);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) part += widen<F16>(o, t) * widen<F16>(dOf[ks], t);
-      }
-    Dq = sum_with_partner32(part);
-    if (row < n && hh == 0) a.Dvec[stat] = Dq;
-  } else {
-    Dq = a.Dvec[stat];
-  }
 
   f32x16 dQt[DT];
 #pragma unroll
@@ -1025,6 +1007,25 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
   issue_tile(tb);
   issue_tile(tb + 1);
   issue_mask(jb);
+  // (D after the first tile copies have been requested: summing it waits for O_i, and the copies need not wait with it)
+  float Dq;
+  if constexpr (OWN_D) {
+    // this lane holds half of its row of dO_i (the elements 16 ks + 8 hh ..): the same half of O_i,
+    // multiplied and summed, and the other half from the partner lane
+    const __bf16* op = a.O + ((si.tok0 + rowc) * p.Hq + h) * dh + 8 * hh;
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      if (!PAD || 16 * ks + 8 * hh < dh) {
+        const bf16x8 o = *(const bf16x8*)(op + 16 * ks);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) part += widen<F16>(o, t) * widen<F16>(dOf[ks], t);
+      }
+    Dq = sum_with_partner32(part);
+    if (row < n && hh == 0) a.Dvec[stat] = Dq;
+  } else {
+    Dq = a.Dvec[stat];
+  }
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     touch(Qf[ks]);
