@@ -58,10 +58,10 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "0742979f981f",
-    "d128_n8k_causal": {"fwd_kernel": 675900830, "bwd_dkdv_kernel": 860072425, "bwd_dq_kernel": 734544732},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269785398, "bwd_dkdv_kernel": 405110450, "bwd_dq_kernel": 338076377},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 877169259, "bwd_dkdv_kernel": 880516321, "bwd_dq_kernel": 831736174},
+    "sources": "e963c46eadb2",
+    "d128_n8k_causal": {"fwd_kernel": 658090889, "bwd_dkdv_kernel": 867126221, "bwd_dq_kernel": 716587069},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269785393, "bwd_dkdv_kernel": 405589081, "bwd_dq_kernel": 337874219},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 870235376, "bwd_dkdv_kernel": 883183748, "bwd_dq_kernel": 830628260},
     "decode_b8_on_8k": {"fwd_decode_kernel": 269481180},
     "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1023158325},
 }
