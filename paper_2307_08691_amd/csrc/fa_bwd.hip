@@ -555,7 +555,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
   // read has been in LDS for two phases, so they need not wait for the barrier.
   Cursor cur = tile0, prev = tile0, ld = tile0;
   int pending = -1;      // ring slot whose statistics wait in lraw / draw
-  auto end_matrix_phase = [&]() {
+  auto end_matrix_work = [&]() {  // everything of end_matrix_phase but its barrier
     __builtin_amdgcn_s_setprio(0);
     // The copies requested in the last vector phase: complete, then visible. The wait and the
     // touches are unconditional so that the compiler sees no path on which the statistics
@@ -572,6 +572,9 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
       commit_stats(pending);
       pending = -1;
     }
+  };
+  auto end_matrix_phase = [&]() {
+    end_matrix_work();
     lds_barrier();
   };
   auto vector_phase = [&](int tau, bool do_v) {  // phase tau + 1, if it exists
@@ -625,21 +628,16 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     // the slot of tile t - 2, whose last reader was group 1's M' in phase 2t - 1; they are
     // complete and visible when the barrier of phase 2t + 2 falls, two phases before group 0
     // reads the tile. A ring of four slots suffices.
+    // Of the two barriers per tile only one is executed: group 0's after its vector phase, which
+    // is group 1's after its matrix phase. It orders everything that goes through LDS (a tile and its
+    // statistics are requested after the barrier that follows their slot's last readers, waited for
+    // and committed before the next but one, and first read after that one); the other one only made
+    // the two wavefronts of a SIMD change phase together, and without it a matrix phase that ends
+    // early runs on into the vector phase (see the forward kernel).
     advance(ld, 2);
-    if (grp == 1) lds_barrier();
-    auto vector_phase_w = [&](int t, bool do_v) {
-      if (grp == 0 && t + 2 < T) {
-        issue_loads(ld);
-        pending = ld.slot;
-        advance(ld, 1);
-      }
-      if (do_v) {
-        phase_v(cur);
-        mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
-      }
-      lds_barrier();
-    };
     if constexpr (LOCAL) {
+      // (the window / pattern instantiation keeps both barriers of a tile: group 1 one phase behind group 0)
+      if (grp == 1) lds_barrier();
       // Window and block-sparse pattern: tile by tile, over the tiles the workgroup visits.
       const unsigned long long* bits = (const unsigned long long*)(smem + BITS_OFF) + v * kPatternWords;
       int word_q = -1;
@@ -721,32 +719,77 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         __builtin_amdgcn_s_setprio(2);
         mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
       }
+      end_matrix_phase();
+      if (grp == 0) lds_barrier();  // group 1's last phase
     } else {
-    int t = 0;
-    for (; t < skip; ++t) {
-      end_matrix_phase();
-      vector_phase_w(t, false);
-      advance(cur, 1);
-    }
-    if (t < T) {
-      __builtin_amdgcn_s_setprio(2);
-      mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
-      end_matrix_phase();
-      vector_phase_w(t, true);
-      for (++t; t < T; ++t) {
-        prev = cur;
-        advance(cur, 1);
-        fused_stream();
+      // The loops are written out once per group: which of the two barriers a group executes is then
+      // fixed in the code (as a run-time condition on both of them the compiler's output failed its own
+      // verification, and as lambdas generic in the group the accumulators ended up in memory).
+      auto vector_work = [&](int t, bool do_v, bool loads) {  // a vector phase without its barrier
+        if (loads && t + 2 < T) {
+          issue_loads(ld);
+          pending = ld.slot;
+          advance(ld, 1);
+        }
+        if (do_v) {
+          phase_v(cur);
+          mfma_stream_begin<NM2, AH, 2>(pre, [&](int i) { return load_m2(cur, i); });
+        }
+      };
+      if (grp == 0) {  // barrier after the vector phase; this group requests the tiles
+        int t = 0;
+        for (; t < skip; ++t) {
+          end_matrix_work();
+          vector_work(t, false, true);
+          lds_barrier();
+          advance(cur, 1);
+        }
+        if (t < T) {
+          __builtin_amdgcn_s_setprio(2);
+          mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
+          end_matrix_work();
+          vector_work(t, true, true);
+          lds_barrier();
+          for (++t; t < T; ++t) {
+            prev = cur;
+            advance(cur, 1);
+            fused_stream();
+            end_matrix_work();
+            vector_work(t, true, true);
+            lds_barrier();
+          }
+          prev = cur;
+          __builtin_amdgcn_s_setprio(2);
+          mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
+        }
+        end_matrix_work();
+        lds_barrier();  // (none was executed for the last matrix phase)
+      } else {  // barrier after the matrix phase
+        int t = 0;
+        for (; t < skip; ++t) {
+          end_matrix_phase();
+          vector_work(t, false, false);
+          advance(cur, 1);
+        }
+        if (t < T) {
+          __builtin_amdgcn_s_setprio(2);
+          mfma_stream<NM, AH, 2>([&](int i) { return load_m(cur, i); }, mma_m);
+          end_matrix_phase();
+          vector_work(t, true, false);
+          for (++t; t < T; ++t) {
+            prev = cur;
+            advance(cur, 1);
+            fused_stream();
+            end_matrix_phase();
+            vector_work(t, true, false);
+          }
+          prev = cur;
+          __builtin_amdgcn_s_setprio(2);
+          mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
+        }
         end_matrix_phase();
-        vector_phase_w(t, true);
       }
-      prev = cur;
-      __builtin_amdgcn_s_setprio(2);
-      mfma_stream_run<NM2, AH, 2>(pre, [&](int i) { return load_m2(prev, i); }, mma_m2);
     }
-    }
-    end_matrix_phase();
-    if (grp == 0) lds_barrier();  // group 1's last phase
 
     // ---- write dK_j, dV_j (line 18); dK carries the scaling. The ring is idle now (no copy is
     // requested past the last tile): each wavefront stages its rows there and stores whole rows.
@@ -1177,11 +1220,11 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     }
   };
 
-  // phases: see the forward kernel (j counts positions of the walk)
+  // phases: see the forward kernel (j counts positions of the walk; one barrier per block, the one
+  // between a group's matrix and vector phase is left out as in the forward kernel's one-workgroup form)
   if (grp == 0) {
     for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
-      lds_barrier();
       issue_tile(j + 2);
       vector_phase(j);
       issue_mask(j + 1);
@@ -1190,7 +1233,6 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
     }
   } else {
     issue_tile(tb + 2);
-    lds_barrier();
     for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
       wait_vmem_upto<TPW + MPW>();
@@ -1199,7 +1241,6 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs a) {
         issue_tile(j + 3);
         vector_phase(j);
         issue_mask(j + 1);
-        lds_barrier();
       }
     }
   }

@@ -504,10 +504,21 @@ __global__ __launch_bounds__(512)
   // (by group 0) at phi = 2m + 1 and first read at phi = 2m + 6. A group waits, at the end of
   // a later phase of its own, until only its newest tile is still in flight.
   // (j counts positions of the walk: the blocks themselves unless a pattern thins the walk)
+  //
+  // With one workgroup per compute unit only every second of those barriers is kept (MID false):
+  // the one after group 0's vector phase j / group 1's matrix phase j. It alone orders everything
+  // that goes through LDS: a tile is requested two barriers before its first reader starts, its
+  // copies are waited for right before the barrier in between, and the slot it takes was last read
+  // (K_{j-2} in matrix phase j - 2, V_{j-2} in matrix phase j - 1 of both groups) before the barrier
+  // that precedes the request. What the barrier in the middle added was that the two wavefronts of a
+  // SIMD change phase together; without it a matrix phase that ends early runs into the vector phase
+  // at once instead of waiting for the other group (+2% at d = 128; with two workgroups per compute
+  // unit, four wavefronts per SIMD, it measured 3% slower and stays).
+  constexpr bool MID = TWO;
   if (grp == 0) {
     for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
-      lds_barrier();
+      if (MID) lds_barrier();
       issue_tile(j + 2);
       vector_phase(j);
       issue_mask(j + 1);
@@ -516,7 +527,7 @@ __global__ __launch_bounds__(512)
     }
   } else {
     issue_tile(tb + 2);
-    lds_barrier();
+    if (MID) lds_barrier();
     for (int j = tb; j <= tend; ++j) {
       matrix_phase(j);
       wait_vmem_upto<TPW + MPW>();
@@ -525,7 +536,7 @@ __global__ __launch_bounds__(512)
         issue_tile(j + 3);
         vector_phase(j);
         issue_mask(j + 1);
-        lds_barrier();
+        if (MID) lds_barrier();
       }
     }
   }
