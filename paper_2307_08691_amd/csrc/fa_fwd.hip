@@ -849,10 +849,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // waits of the last two blocks let the newer of these stay in flight; the wait after the last
     // barrier completes all but the newest TPW, i.e. everything the next item reads.
     constexpr int LATE = 2 * TPW + KS;
+    // (one barrier per block, as in fwd_kernel's one-workgroup form: the barriers that followed no
+    // wait are left out)
     if constexpr (GRP == 0) {
       for (int j = 0; j <= ncol; ++j) {
         matrix_phase(j);
-        lds_barrier();
         issue_tile(j + 2);
         if (j == jq) request_next_q();
         vector_phase(j);
@@ -863,7 +864,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     } else {
       issue_tile(2);
-      lds_barrier();
       for (int j = 0; j <= ncol; ++j) {
         matrix_phase(j);
         if (j == jq + 1) wait_vmem_upto<LATE>();
@@ -873,7 +873,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           if (j == jq) request_next_q();
           issue_tile(j + 3);
           vector_phase(j);
-          lds_barrier();
         }
       }
     }
