@@ -234,7 +234,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4
     l += rs0 + rs1;  // (in units of 2^-8)
   };
 
-  // phases: see fwd_kernel
+  // phases: see fwd_kernel (both barriers of a block are kept here: leaving out the one that follows
+  // no wait, as the bf16 kernels with one workgroup per compute unit do, measured 1-4% slower; the
+  // vector phase is the longer one in this kernel)
   if (grp == 0) {
     for (int j = 0; j <= ncol; ++j) {
       matrix_phase(j);
