@@ -58,10 +58,10 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "e963c46eadb2",
-    "d128_n8k_causal": {"fwd_kernel": 658090889, "bwd_dkdv_kernel": 867126221, "bwd_dq_kernel": 716587069},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269785393, "bwd_dkdv_kernel": 405589081, "bwd_dq_kernel": 337874219},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 870235376, "bwd_dkdv_kernel": 883183748, "bwd_dq_kernel": 830628260},
+    "sources": "aec77368490d",
+    "d128_n8k_causal": {"fwd_kernel": 666515000, "bwd_dkdv_kernel": 866913721, "bwd_dq_kernel": 727687501},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269806953, "bwd_dkdv_kernel": 405162857, "bwd_dq_kernel": 338172765},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 874434693, "bwd_dkdv_kernel": 881142552, "bwd_dq_kernel": 831774463},
     "decode_b8_on_8k": {"fwd_decode_kernel": 269481180},
     "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1023158325},
 }
