@@ -475,7 +475,9 @@ int fa_varlen_cross_bwd(const void* Q, const void* K, const void* V, const void*
  * fa_splitkv_fwd_workspace_bytes() bytes, undefined on entry and exit. 1 <= num_splits <=
  * FA_SPLITKV_MAX_SPLITS, otherwise FA_ERR_SHAPE; more shares than 64-key blocks leave the
  * extra ones empty. Results differ from fa_cross_fwd only by rounding (the partial sums are
- * combined in a different order).
+ * combined in a different order). When the rows of one key/value head, Nq * (Hq / Hkv), number at
+ * most 32 (decoding), a kernel of its own runs in which the wavefronts of a workgroup divide the
+ * keys of the share among themselves instead of the rows; nothing changes for the caller.
  */
 #define FA_SPLITKV_MAX_SPLITS 128
 size_t fa_splitkv_fwd_workspace_bytes(int B, int Hq, int Nq, int d, int num_splits);
