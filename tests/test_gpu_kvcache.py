@@ -168,3 +168,14 @@ def test_bad_cache_descriptions_are_rejected():
     with pytest.raises(ValueError):
         binding.fa_kvcache_fwd(q, pool, pool, 0.125, False, seqlens_k=torch.zeros(3, dtype=torch.int32, device="cuda"),
                                block_table=table)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq,Hq,Hkv", [(4, 8, 1), (32, 2, 2), (16, 4, 2), (33, 1, 1), (5, 8, 1), (1, 32, 1)])
+def test_row_counts_around_the_decode_kernel_limit(Nq, Hq, Hkv, d, causal):
+    """Nq * (Hq / Hkv) = 32 rows per key/value head is the most the decode kernel takes (one MFMA row
+    tile); 33 and 40 go to the row-block kernel. Lengths from one key to the capacity, more shares
+    than some sequences have key blocks (empty shares), a length that ends inside a 32-key tile."""
+    cap, lens = 2000, [2000, 1, 33, 95, 1024, 0, 1999]
+    check_contiguous(draw(18600 + Nq + Hq + d, len(lens), Nq, cap, Hq, Hkv, d), lens, causal, 7)
