@@ -58,12 +58,12 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "aec77368490d",
+    "sources": "e1c4fc7f5c93",
     "d128_n8k_causal": {"fwd_kernel": 666515000, "bwd_dkdv_kernel": 866913721, "bwd_dq_kernel": 727687501},
     "sweep_d128_n8192_full": {"fwd_kernel": 269806953, "bwd_dkdv_kernel": 405162857, "bwd_dq_kernel": 338172765},
     "sweep_d64_n8192_causal": {"fwd_kernel": 874434693, "bwd_dkdv_kernel": 881142552, "bwd_dq_kernel": 831774463},
-    "decode_b8_on_8k": {"fwd_decode_kernel": 269481180},
-    "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1023158325},
+    "decode_b8_on_8k": {"fwd_decode_kernel": 269476674},
+    "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1020339704},
 }
 
 

@@ -790,13 +790,15 @@ FA_SPLITKV_MAX_SPLITS = 128
 def splitkv_default_splits(B, Hq, Hkv, Nq, Nk, ragged: bool = False) -> int:
     """About one workgroup per compute unit, and at least 8 blocks of 64 keys per share (measured:
     more, shorter shares cost more in prologues and in the merge than they gain in parallelism).
-    ragged (a cache with a length of its own per sequence, Nk the capacity): about eight workgroups
-    per compute unit and at least 16 blocks per share of a full cache; the shares of short sequences
-    are short, and more of them even the load out (measured on 64 sequences of 1 .. 8192 keys: 4
-    shares 3.7 TB/s, 1 share 2.6, 16 shares 2.9)."""
+    ragged (a cache with a length of its own per sequence, Nk the capacity): the same for up to 128
+    sequences in decoding shapes, where the decode kernel hands the sequences out longest first
+    (measured on 64 sequences of 1 .. 8192 keys: 1 share 5.0 TB/s, 4 shares 4.3, 16 shares 2.5);
+    otherwise about eight workgroups per compute unit and at least 16 blocks per share of a full
+    cache, since more, shorter shares then even the load out (same batch in launch order: 4 shares
+    3.7 TB/s, 1 share 2.6, 16 shares 2.9)."""
     units = B * Hkv * ((Nq * (Hq // Hkv) + 255) // 256)
     blocks = (Nk + 63) // 64
-    if ragged:
+    if ragged and not (B <= 128 and Nq * (Hq // Hkv) <= 32):
         return max(1, min(FA_SPLITKV_MAX_SPLITS, blocks // 16, -(-2048 // units)))
     return max(1, min(FA_SPLITKV_MAX_SPLITS, blocks // 8, -(-256 // units)))
 

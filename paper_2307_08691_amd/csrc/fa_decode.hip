@@ -46,7 +46,35 @@ __global__ __launch_bounds__(512) void fwd_decode_kernel(FwdArgs a) {
   const int nsplit = a.nsplit;
   const BlockCoord bc = block_coord<false>(nsplit, p.Hkv, p.nseq);
   if (!bc.valid) return;
-  const int split = bc.blk, g = bc.head, s = bc.seq;
+  const int split = bc.blk, g = bc.head;
+  // Sequences of uneven cache lengths are handed out longest first: the workgroups of an XCD take
+  // their (sequence, head) pairs in launch order, and a long sequence that starts last leaves the
+  // other compute units idle at the end. bc.seq is therefore read as a RANK, and the sequence of that
+  // rank (by length, ties by index) is found here: lane c counts the sequences that come before
+  // candidate c. Done by every wavefront for itself (a few hundred scalar loads that hit L2); batches
+  // of more than kRankMax sequences keep the launch order.
+  constexpr int kRankMax = 128;
+  int s_ = bc.seq;
+  if (a.seqlens_k && p.nseq > 1 && p.nseq <= kRankMax) {
+    auto len_of = [&](int i) {
+      const int len = a.seqlens_k[i];
+      return len < 0 ? 0 : (len < p.Nk ? len : p.Nk);
+    };
+    int found = 0;
+    for (int c0 = 0; c0 < p.nseq; c0 += 64) {
+      const int c = c0 + lane;
+      const int lc = c < p.nseq ? len_of(c) : -1;
+      int before = 0;
+      for (int j = 0; j < p.nseq; ++j) {
+        const int lj = __builtin_amdgcn_readfirstlane(len_of(j));
+        before += (lj > lc || (lj == lc && j < c)) ? 1 : 0;
+      }
+      const unsigned long long hit = __builtin_amdgcn_ballot_w64(c < p.nseq && before == bc.seq);
+      if (hit) found = c0 + __builtin_ctzll(hit);
+    }
+    s_ = found;
+  }
+  const int s = __builtin_amdgcn_readfirstlane(s_);
   const SeqInfo si = seq_info(p, s);
   int nk_ = si.nk;
   if (a.seqlens_k) {  // a key/value cache filled up to a length of its own per sequence

@@ -215,8 +215,10 @@ def test_split_key_entry_point_rejects_bad_arguments():
     assert binding.splitkv_default_splits(8, 32, 8, 1, 8192) == 4
     assert binding.splitkv_default_splits(64, 32, 8, 1, 8192) == 1
     assert binding.splitkv_default_splits(1, 8, 8, 1, 100) == 1
-    assert binding.splitkv_default_splits(64, 32, 8, 1, 8192, ragged=True) == 4
-    assert binding.splitkv_default_splits(8, 32, 8, 1, 8192, ragged=True) == 8
+    assert binding.splitkv_default_splits(64, 32, 8, 1, 8192, ragged=True) == 1    # decode kernel: longest first
+    assert binding.splitkv_default_splits(8, 32, 8, 1, 8192, ragged=True) == 4
+    assert binding.splitkv_default_splits(64, 32, 8, 16, 8192, ragged=True) == 4   # 64 rows per key/value head: launch order
+    assert binding.splitkv_default_splits(200, 32, 8, 1, 8192, ragged=True) == 2
 
 
 def test_window_pattern_cache_fp8_and_mask_gradient_entry_points_reject_bad_arguments():

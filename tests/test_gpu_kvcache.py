@@ -179,3 +179,13 @@ def test_row_counts_around_the_decode_kernel_limit(Nq, Hq, Hkv, d, causal):
     than some sequences have key blocks (empty shares), a length that ends inside a 32-key tile."""
     cap, lens = 2000, [2000, 1, 33, 95, 1024, 0, 1999]
     check_contiguous(draw(18600 + Nq + Hq + d, len(lens), Nq, cap, Hq, Hkv, d), lens, causal, 7)
+
+
+@pytest.mark.parametrize("B", [2, 64, 128, 129])
+def test_many_sequences_with_equal_and_uneven_lengths(B):
+    """The decode kernel hands up to 128 sequences out longest first (a rank per workgroup, ties by
+    index); 129 keep the launch order. Lengths with many ties, zeros among them."""
+    cap, Hq, Hkv, d = 256, 4, 2, 64
+    g = np.random.default_rng(18700 + B)
+    lens = [int(x) for x in g.choice([0, 1, 64, 64, 100, 256, 256, 255], B)]
+    check_contiguous(draw(18701 + B, B, 1, cap, Hq, Hkv, d), lens, True, 2)
