@@ -109,30 +109,45 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4
   // K tile: 64 rows (keys, clamped to the last one) of D bytes; V^T tile: D rows (always complete:
   // rows are padded to 64 keys in memory) of 64 bytes. Each copy instruction fills 1 KiB of LDS;
   // the swizzle is applied by choosing which global chunk a lane fetches.
+  // (the per-lane byte offsets of an interior tile are computed once; a tile then costs one scalar
+  // base address and TPW copy instructions. Only K tiles at the end of the sequence, whose rows have to
+  // be clamped, recompute their addresses.)
+  unsigned toff[TPW];
+#pragma unroll
+  for (int u = 0; u < TPW; ++u) {
+    if (grp == 1) {
+      const int r = ((w & 3) + 4 * u) * KRPI + lane / KCPR;
+      toff[u] = (unsigned)(r * kstride + 16 * ((lane % KCPR) ^ swz_k8<KROWB>(r)));
+    } else {
+      const int r = ((w & 3) + 4 * u) * 16 + lane / 4;
+      toff[u] = (unsigned)(r * a.vt_stride + 16 * ((lane % 4) ^ swz_v8(r)));
+    }
+  }
   auto issue_tile = [&](int j) {
     char* dst = smem + (j % RING) * BUFB;
-    int ln = lane;
-    asm volatile("" : "+v"(ln));  // (addresses recomputed per tile instead of held in registers)
     if (grp == 1) {
+      if (j * BC + BC <= nk) {
+        const char* base = (const char*)Kb + (long)j * BC * kstride;
 #pragma unroll
-      for (int u = 0; u < TPW; ++u) {
-        const int rb = ((w & 3) + 4 * u) * KRPI;
-        const int r = rb + ln / KCPR;
-        const int c = (ln % KCPR) ^ swz_k8<KROWB>(r);
-        int key = j * BC + r;
-        key = key < nk - 1 ? key : nk - 1;
-        dma16(Kb + (long)key * kstride + 16 * c, dst + rb * KROWB);
+        for (int u = 0; u < TPW; ++u) dma16_uniform(base, toff[u], dst + ((w & 3) + 4 * u) * KRPI * KROWB);
+      } else {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));  // (addresses of this rare path are not to be held in registers)
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+          const int rb = ((w & 3) + 4 * u) * KRPI;
+          const int r = rb + ln / KCPR;
+          const int c = (ln % KCPR) ^ swz_k8<KROWB>(r);
+          int key = j * BC + r;
+          key = key < nk - 1 ? key : nk - 1;
+          dma16(Kb + (long)key * kstride + 16 * c, dst + rb * KROWB);
+        }
       }
     } else {
+      // (blocks past the end are requested like the others, their data is never read: stay inside the rows)
+      const char* base = (const char*)Vb + (long)(j < ncol_all ? j : ncol_all - 1) * BC;
 #pragma unroll
-      for (int u = 0; u < TPW; ++u) {
-        const int rb = ((w & 3) + 4 * u) * 16;  // 16 rows of 64 bytes per instruction
-        const int r = rb + ln / 4;
-        const int c = (ln % 4) ^ swz_v8(r);
-        // (blocks past the end are requested like the others, their data is never read: stay inside the rows)
-        const long col = (long)(j < ncol_all ? j : ncol_all - 1) * BC;
-        dma16(Vb + (long)r * a.vt_stride + col + 16 * c, dst + KTILE + rb * 64);
-      }
+      for (int u = 0; u < TPW; ++u) dma16_uniform(base, toff[u], dst + KTILE + ((w & 3) + 4 * u) * 16 * 64);
     }
   };
   issue_tile(0);
@@ -159,6 +174,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4
   f32x16 S[2];
   i32x8 Pf;
 
+  // (the operands of both products come from LDS as they are needed; requesting them several MFMAs
+  // early through a register ring, as the bf16 kernels do, measured 7% slower here)
   auto matrix_phase = [&](int j) {
     __builtin_amdgcn_s_setprio(2);
     if (j < ncol && (!CAUSAL || j * BC <= wrow_last)) {  // S^T = K_j Q_i^T (line 8)
