@@ -481,14 +481,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // tile t = (head g G + t / per_head, row tile i_first + t % per_head)
   float lraw = 0.f, draw = 0.f;
   bool stat_ok = false;
+  // (tiles are requested in order: the head and row tile of the next request are carried along, and
+  // the per-lane offsets of an interior tile are computed once, so that a request costs a scalar base
+  // address and the copy instructions; only the last row tile of a sequence clamps its rows)
+  TileLoader<kHalf, BR, 4, false> qloader;
+  qloader.init(qstride, w, lane, kHalf / 8);
+  int next_hq = g * p.G, next_it = i_first;
   auto issue_tile = [&](int t) {
-    const int hq = g * p.G + t / per_head, it = i_first + t % per_head;
+    const int hq = next_hq, it = next_it;
+    if (++next_it == nrt) {
+      next_it = i_first;
+      ++next_hq;
+    }
     char* st = smem + (t & 1) * STAGEB;
     const long head0 = (si.tok0 * p.Hq + hq) * D;  // row 0 of this head
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      tile_load_async<kHalf, BR, 4, false>(st + half * HALFB, a.Q + head0 + half * kHalf, qstride, it * BR, n - 1, w, lane);
-      tile_load_async<kHalf, BR, 4, false>(st + (2 + half) * HALFB, a.dO + head0 + half * kHalf, qstride, it * BR, n - 1, w, lane);
+      qloader.load(st + half * HALFB, a.Q + head0 + half * kHalf, qstride, it * BR, n - 1, w, lane);
+      qloader.load(st + (2 + half) * HALFB, a.dO + head0 + half * kHalf, qstride, it * BR, n - 1, w, lane);
     }
     if (tid < BR) {
       const int r = it * BR + tid;
@@ -510,6 +520,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   f32x16 S, dP;
   bf16x8 Pf[2], dSf[2];
 
+  int cur_it = i_first;  // row tile of tile t
   for (int t = 0; t < T; ++t) {
     wait_vmem();  // tile t and its statistics have arrived
     touch(lraw);
@@ -523,7 +534,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     lds_barrier();
     if (t + 1 < T) issue_tile(t + 1);  // into the other stage, which everyone left at the last barrier
     const int st = (t & 1) * STAGEB;
-    const int r0 = (i_first + t % per_head) * BR;  // first query row of the tile
+    const int r0 = cur_it * BR;  // first query row of the tile
+    if (++cur_it == nrt) cur_it = i_first;
     // ---- S = Q_i K_j^T (line 10)
     S = (f32x16){0};
     mfma_stream<KS, 4, 1>(
