@@ -513,12 +513,32 @@ int fa_kvcache_fwd(const void* Q, const void* Kcache, const void* Vcache, const 
                    float scale, int causal, int num_splits, void* stream);
 
 /*
- * The packed ragged entry points (one and two lengths), the split-key forward and the key/value
- * cache forward for IEEE half precision (fp16) elements: each is its bfloat16 namesake with every
+ * The packed ragged entry points (one and two lengths, with dropout, with a window), the split-key
+ * forward and the key/value cache forward for IEEE half precision (fp16) elements: each is its bfloat16 namesake with every
  * 16-bit tensor holding fp16, as fa_cross_fwd_f16 / fa_cross_bwd_f16 are to fa_cross_fwd /
  * fa_cross_bwd. LSE, workspaces, offset arrays, lengths, page tables, limits and errors are
  * unchanged.
  */
+int fa_varlen_dropout_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                              const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                              int Hq, int Hkv, int d, float scale, int causal,
+                              float p_drop, uint64_t seed, void* stream);
+int fa_varlen_dropout_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                              const float* LSE, void* dQ, void* dK, void* dV,
+                              void* workspace, size_t workspace_bytes,
+                              const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                              int Hq, int Hkv, int d, float scale, int causal,
+                              float p_drop, uint64_t seed, void* stream);
+int fa_varlen_local_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                            int Hq, int Hkv, int d, float scale,
+                            int window_left, int window_right, void* stream);
+int fa_varlen_local_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                            const float* LSE, void* dQ, void* dK, void* dV,
+                            void* workspace, size_t workspace_bytes,
+                            const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
+                            int Hq, int Hkv, int d, float scale,
+                            int window_left, int window_right, void* stream);
 int fa_varlen_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
                       const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen,
                       int Hq, int Hkv, int d, float scale, int causal, void* stream);

@@ -57,7 +57,11 @@ SIGNATURES = {
                        [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_varlen_dropout_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 +
                               [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_varlen_dropout_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 +
+                              [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_varlen_dropout_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
+                              [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
+    "fa_varlen_dropout_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
                               [_c_float, _c_int, _c_float, ctypes.c_uint64, _c_void_p]),
     "fa_mask_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
     "fa_mask_fwd_f16": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int] + [ctypes.c_longlong] * 3 + [_c_void_p]),
@@ -74,7 +78,10 @@ SIGNATURES = {
     "fa_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_local_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_varlen_local_fwd": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_varlen_local_fwd_f16": (_c_int, [_c_void_p] * 5 + [_c_void_p] + [_c_int] * 6 + [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_varlen_local_bwd": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
+                            [_c_float, _c_int, _c_int, _c_void_p]),
+    "fa_varlen_local_bwd_f16": (_c_int, [_c_void_p] * 9 + [_c_void_p, _c_size_t] + [_c_void_p] + [_c_int] * 6 +
                             [_c_float, _c_int, _c_int, _c_void_p]),
     "fa_blocksparse_fwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
     "fa_blocksparse_fwd_f16": (_c_int, [_c_void_p] * 6 + [_c_int] * 6 + [_c_float, _c_int, _c_int] + [ctypes.c_longlong] * 2 + [_c_void_p]),
@@ -221,15 +228,16 @@ def fa_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv
 
 
 def fa_varlen_dropout_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed,
-                              stream=0) -> int:
-    return load().fa_varlen_dropout_fwd(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, int(causal),
-                                        p_drop, seed, stream)
+                              stream=0, f16=False) -> int:
+    fn = load().fa_varlen_dropout_fwd_f16 if f16 else load().fa_varlen_dropout_fwd
+    return fn(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, int(causal), p_drop, seed, stream)
 
 
 def fa_varlen_dropout_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d,
-                              scale, causal, p_drop, seed, stream=0) -> int:
-    return load().fa_varlen_dropout_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq,
-                                        Hkv, d, scale, int(causal), p_drop, seed, stream)
+                              scale, causal, p_drop, seed, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_dropout_bwd_f16 if f16 else load().fa_varlen_dropout_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale,
+              int(causal), p_drop, seed, stream)
 
 
 def fa_mask_fwd_raw(Q, K, V, M, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, mask_bs, mask_hs, mask_rs, stream=0, f16=False) -> int:
@@ -261,14 +269,16 @@ def fa_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, 
     return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, B, Hq, Hkv, Nq, Nk, d, scale, left, right, stream)
 
 
-def fa_varlen_local_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left, right, stream=0) -> int:
-    return load().fa_varlen_local_fwd(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left, right, stream)
+def fa_varlen_local_fwd_raw(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left, right, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_local_fwd_f16 if f16 else load().fa_varlen_local_fwd
+    return fn(Q, K, V, O, LSE, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left, right, stream)
 
 
 def fa_varlen_local_bwd_raw(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale,
-                            left, right, stream=0) -> int:
-    return load().fa_varlen_local_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv,
-                                      d, scale, left, right, stream)
+                            left, right, stream=0, f16=False) -> int:
+    fn = load().fa_varlen_local_bwd_f16 if f16 else load().fa_varlen_local_bwd
+    return fn(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ws_bytes, cu, nseq, total, max_seqlen, Hq, Hkv, d, scale, left,
+              right, stream)
 
 
 def fa_blocksparse_fwd_raw(Q, K, V, BM, O, LSE, B, Hq, Hkv, Nq, Nk, d, scale, causal, block, bs, hs, stream=0, f16=False) -> int:
@@ -560,22 +570,24 @@ def fa_dropout_bwd(Q, K, V, O, dO, LSE, scale: float, causal: bool, p_drop: floa
 def fa_varlen_dropout_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, causal: bool, p_drop: float, seed: int,
                           O=None, LSE=None):
     """Packed ragged forward with dropout on P. Q [T,Hq,d], K,V [T,Hkv,d] bf16; cu_seqlens int32 on the GPU."""
-    x = _packed(Q, K, V, cu_seqlens)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens, allowed=(torch.bfloat16, torch.float16))
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_varlen_dropout_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), x.nseq, x.Tq,
-                                     max_seqlen, x.Hq, x.Hkv, x.d, scale, causal, p_drop, seed, _stream()))
+                                     max_seqlen, x.Hq, x.Hkv, x.d, scale, causal, p_drop, seed, _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_varlen_dropout_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, causal: bool, p_drop: float,
                           seed: int, dQ=None, dK=None, dV=None, workspace=None):
     """Packed ragged backward with the dropout mask of fa_varlen_dropout_fwd for the same p_drop and seed."""
-    x = _packed(Q, K, V, cu_seqlens)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens, allowed=(torch.bfloat16, torch.float16))
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_dropout_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
                                      _ptr(dV), _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen, x.Hq,
-                                     x.Hkv, x.d, scale, causal, p_drop, seed, _stream()))
+                                     x.Hkv, x.d, scale, causal, p_drop, seed, _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 
@@ -672,22 +684,24 @@ def fa_varlen_local_fwd(Q, K, V, cu_seqlens, max_seqlen: int, scale: float, wind
                         O=None, LSE=None):
     """Packed ragged forward with the sliding window of fa_local_fwd inside every sequence. Q [T,Hq,d],
     K,V [T,Hkv,d] bf16; cu_seqlens int32 on the GPU."""
-    x = _packed(Q, K, V, cu_seqlens)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens, allowed=(torch.bfloat16, torch.float16))
     O, LSE = _fwd_outputs(x, O, LSE)
     _check(fa_varlen_local_fwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(cu_seqlens), x.nseq, x.Tq,
-                                   max_seqlen, x.Hq, x.Hkv, x.d, scale, window_left, window_right, _stream()))
+                                   max_seqlen, x.Hq, x.Hkv, x.d, scale, window_left, window_right, _stream(), x.et == torch.float16))
     return O, LSE
 
 
 def fa_varlen_local_bwd(Q, K, V, O, dO, LSE, cu_seqlens, max_seqlen: int, scale: float, window_left: int,
                         window_right: int, dQ=None, dK=None, dV=None, workspace=None):
     """Backward of fa_varlen_local_fwd for the same window."""
-    x = _packed(Q, K, V, cu_seqlens)
+    import torch
+    x = _packed(Q, K, V, cu_seqlens, allowed=(torch.bfloat16, torch.float16))
     dQ, dK, dV = _bwd_tensors(x, O, dO, LSE, dQ, dK, dV)
     ws = _workspace(workspace, fa_varlen_bwd_workspace_bytes(x.Tq, x.Hq, x.Hkv, x.d), x.dev)
     _check(fa_varlen_local_bwd_raw(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(dQ), _ptr(dK),
                                    _ptr(dV), _ptr(ws), _wsbytes(ws), _ptr(cu_seqlens), x.nseq, x.Tq, max_seqlen, x.Hq,
-                                   x.Hkv, x.d, scale, window_left, window_right, _stream()))
+                                   x.Hkv, x.d, scale, window_left, window_right, _stream(), x.et == torch.float16))
     return dQ, dK, dV
 
 

@@ -370,11 +370,26 @@ int fa_varlen_fwd_f16(const void* Q, const void* K, const void* V, void* O, floa
                         stream);
 }
 
+static int varlen_dropout_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                  const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq,
+                                  int Hkv, int d, float scale, int causal, float p_drop, uint64_t seed,
+                                  void* stream) {
+  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
+                    of_type(with_dropout(p_drop, seed), f16));
+}
+
 int fa_varlen_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
                           int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale, int causal,
                           float p_drop, uint64_t seed, void* stream) {
-  return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
-                    with_dropout(p_drop, seed));
+  return varlen_dropout_fwd_any(0, Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale,
+                                causal, p_drop, seed, stream);
+}
+
+int fa_varlen_dropout_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                              const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                              int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  return varlen_dropout_fwd_any(1, Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale,
+                                causal, p_drop, seed, stream);
 }
 
 size_t fa_varlen_bwd_workspace_bytes(int total_tokens, int Hq, int Hkv, int d) {
@@ -422,12 +437,29 @@ int fa_varlen_bwd_f16(const void* Q, const void* K, const void* V, const void* O
                         total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream);
 }
 
+static int varlen_dropout_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                  const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                                  size_t workspace_bytes, const int32_t* cu_seqlens, int nseq, int total_tokens,
+                                  int max_seqlen, int Hq, int Hkv, int d, float scale, int causal, float p_drop,
+                                  uint64_t seed, void* stream) {
+  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
+                    max_seqlen, Hq, Hkv, d, scale, causal, stream, of_type(with_dropout(p_drop, seed), f16));
+}
+
 int fa_varlen_dropout_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                           const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
                           const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
                           int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
-  return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
-                    max_seqlen, Hq, Hkv, d, scale, causal, stream, with_dropout(p_drop, seed));
+  return varlen_dropout_bwd_any(0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq,
+                                total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed, stream);
+}
+
+int fa_varlen_dropout_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                              const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                              const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                              int d, float scale, int causal, float p_drop, uint64_t seed, void* stream) {
+  return varlen_dropout_bwd_any(1, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq,
+                                total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, p_drop, seed, stream);
 }
 
 static int check_cross(int B, int Nq, int Nk, int causal) {
@@ -773,28 +805,59 @@ int fa_fp8_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* 
 
 // Sliding window over a packed ragged batch: the routing of fa_local_fwd with the longest
 // sequence standing for both lengths (a bound that reaches past it binds nowhere).
-int fa_varlen_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
-                        int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale,
-                        int window_left, int window_right, void* stream) {
+static int varlen_local_fwd_any(int f16, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq,
+                                int Hkv, int d, float scale, int window_left, int window_right, void* stream) {
   int causal = 0;
   if (max_seqlen > 0)
     if (int e = window_route(max_seqlen, max_seqlen, window_left, window_right, causal)) return e;
   const bool none = window_left < 0 && window_right < 0;
   return varlen_fwd(Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale, causal, stream,
-                    none ? Options() : with_window(window_left, window_right));
+                    none ? half_precision(f16) : of_type(with_window(window_left, window_right), f16));
 }
 
-int fa_varlen_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
-                        void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
-                        const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d,
-                        float scale, int window_left, int window_right, void* stream) {
+int fa_varlen_local_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, const int32_t* cu_seqlens,
+                        int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d, float scale,
+                        int window_left, int window_right, void* stream) {
+  return varlen_local_fwd_any(0, Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale,
+                              window_left, window_right, stream);
+}
+
+int fa_varlen_local_fwd_f16(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                            int d, float scale, int window_left, int window_right, void* stream) {
+  return varlen_local_fwd_any(1, Q, K, V, O, LSE, cu_seqlens, nseq, total_tokens, max_seqlen, Hq, Hkv, d, scale,
+                              window_left, window_right, stream);
+}
+
+static int varlen_local_bwd_any(int f16, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                                size_t workspace_bytes, const int32_t* cu_seqlens, int nseq, int total_tokens,
+                                int max_seqlen, int Hq, int Hkv, int d, float scale, int window_left,
+                                int window_right, void* stream) {
   int causal = 0;
   if (max_seqlen > 0)
     if (int e = window_route(max_seqlen, max_seqlen, window_left, window_right, causal)) return e;
   const bool none = window_left < 0 && window_right < 0;
   return varlen_bwd(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq, total_tokens,
                     max_seqlen, Hq, Hkv, d, scale, causal, stream,
-                    none ? Options() : with_window(window_left, window_right));
+                    none ? half_precision(f16) : of_type(with_window(window_left, window_right), f16));
+}
+
+int fa_varlen_local_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                        void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                        const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv, int d,
+                        float scale, int window_left, int window_right, void* stream) {
+  return varlen_local_bwd_any(0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq,
+                              total_tokens, max_seqlen, Hq, Hkv, d, scale, window_left, window_right, stream);
+}
+
+int fa_varlen_local_bwd_f16(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                            const float* LSE, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                            const int32_t* cu_seqlens, int nseq, int total_tokens, int max_seqlen, int Hq, int Hkv,
+                            int d, float scale, int window_left, int window_right, void* stream) {
+  return varlen_local_bwd_any(1, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, cu_seqlens, nseq,
+                              total_tokens, max_seqlen, Hq, Hkv, d, scale, window_left, window_right, stream);
 }
 
 static int check_varlen_cross(const int32_t* cu_q, const int32_t* cu_k, int nseq, int total_q, int total_k, int max_q,

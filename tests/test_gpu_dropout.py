@@ -94,25 +94,27 @@ def test_kept_fraction_seen_through_the_output():
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 2, 2), (128, 4, 2)])
-def test_ragged_batches_with_dropout(d, Hq, Hkv, causal):
+def test_ragged_batches_with_dropout(d, Hq, Hkv, causal, dtype):
     """fa_varlen_dropout_fwd / bwd against the oracle's ragged dropout: the generator counts rows and
     columns from the start of each sequence and uses sequence * Hq + head as its head index."""
-    prob = inputs.make_varlen([100, 257, 1, 31, 300], Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=6100 + d)
-    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    prob = inputs.make_varlen([100, 257, 1, 31, 300], Hq=Hq, Hkv=Hkv, d=d, causal=causal, seed=6100 + d, dtype=dtype)
+    Q, K, V, dO = (pu.to_gpu(x, dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
     cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
     p_drop, seed = 0.25, 0x1234567890ABCDEF
     O, L = binding.fa_varlen_dropout_fwd(Q, K, V, cu, 300, prob.scale, causal, p_drop, seed)
     dQ, dK, dV = binding.fa_varlen_dropout_bwd(Q, K, V, O, dO, L, cu, 300, prob.scale, causal, p_drop, seed)
     torch.cuda.synchronize()
-    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    widen = orc.widen_f16 if dtype == "f16" else orc.widen_bf16
+    Qf, Kf, Vf, dOf = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     eO, eL = orc.varlen_forward_dropout(Qf, Kf, Vf, prob.cu_seqlens, prob.scale, causal, p_drop, seed)
     edQ, edK, edV = orc.varlen_backward_dropout(Qf, Kf, Vf, dOf, prob.cu_seqlens, prob.scale, causal, p_drop, seed)
     keep_of, rp = keep_masks(seed, p_drop, Hq)
     ref = pu.reference_batch(Q, K, V, dO, prob.scale, causal, cu_q=prob.cu_seqlens, keep_of=keep_of, rp=rp)
     pu.judge(f"ragged dropout d{d} H{Hq}/{Hkv} causal={causal}",
              {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))},
-             dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, standard=False, d=d)
+             dict(O=eO, LSE=eL, dQ=edQ, dK=edK, dV=edV), ref, standard=False, dtype=dtype, d=d)
 
 
 @pytest.mark.timeout(600)

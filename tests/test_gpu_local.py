@@ -74,26 +74,29 @@ def test_grouped_heads(d, Hq, Hkv):
     check_local(prob, 40, 70)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(64, 2, 2), (128, 4, 2)])
 @pytest.mark.parametrize("left,right", [(0, 0), (31, 0), (100, 0), (300, 0), (40, 70), (-1, 40), (64, -1)])
-def test_windows_inside_the_sequences_of_a_ragged_batch(left, right, d, Hq, Hkv):
+def test_windows_inside_the_sequences_of_a_ragged_batch(left, right, d, Hq, Hkv, dtype):
     """fa_varlen_local_fwd / bwd: sequences shorter and longer than the window and than the kernels'
     blocks, one of one token, one without tokens; positions count from each sequence's start."""
     lens = [100, 257, 1, 0, 31, 700, 64]
-    prob = inputs.make_varlen(lens, Hq=Hq, Hkv=Hkv, d=d, causal=False, seed=16600 + d + left)
-    Q, K, V, dO = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    prob = inputs.make_varlen(lens, Hq=Hq, Hkv=Hkv, d=d, causal=False, seed=16600 + d + left, dtype=dtype)
+    Q, K, V, dO = (pu.to_gpu(x, dtype) for x in (prob.Q, prob.K, prob.V, prob.dO))
     cu = torch.from_numpy(prob.cu_seqlens.astype(np.int32)).cuda()
     O, L = binding.fa_varlen_local_fwd(Q, K, V, cu, max(lens), prob.scale, left, right)
     dQ, dK, dV = binding.fa_varlen_local_bwd(Q, K, V, O, dO, L, cu, max(lens), prob.scale, left, right)
     torch.cuda.synchronize()
-    Qf, Kf, Vf, dOf = (orc.widen_bf16(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
+    widen = orc.widen_f16 if dtype == "f16" else orc.widen_bf16
+    Qf, Kf, Vf, dOf = (widen(x) for x in (prob.Q, prob.K, prob.V, prob.dO))
     exp = {}
     exp["O"], exp["LSE"] = orc.varlen_forward_local(Qf, Kf, Vf, prob.cu_seqlens, prob.scale, left, right)
     exp["dQ"], exp["dK"], exp["dV"] = orc.varlen_backward_local(Qf, Kf, Vf, dOf, prob.cu_seqlens, prob.scale, left, right)
     ref = pu.reference_batch(Q, K, V, dO, prob.scale, False, cu_q=prob.cu_seqlens,
                              M_of=lambda s, h, nq, nk: window_mask_gpu(nq, nk, left, right)[0, 0])
     pu.judge(f"ragged window ({left},{right}) d{d} H{Hq}/{Hkv}",
-             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))}, exp, ref, d=d)
+             {nm: pu.to_f64(t) for nm, t in (("O", O), ("LSE", L), ("dQ", dQ), ("dK", dK), ("dV", dV))}, exp, ref,
+             dtype=dtype, d=d)
 
 
 def test_ragged_bounds_that_bind_nothing_are_the_ragged_entry_points_bitwise():
