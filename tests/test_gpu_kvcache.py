@@ -189,3 +189,46 @@ def test_many_sequences_with_equal_and_uneven_lengths(B):
     g = np.random.default_rng(18700 + B)
     lens = [int(x) for x in g.choice([0, 1, 64, 64, 100, 256, 256, 255], B)]
     check_contiguous(draw(18701 + B, B, 1, cap, Hq, Hkv, d), lens, True, 2)
+
+
+def test_decoding_steps_replay_from_a_captured_graph():
+    """A serving loop captures one decoding step into a HIP graph and replays it while the cache grows:
+    the lengths, the page table and the cache contents live in device buffers that change between
+    replays, the launch itself does not. Every replay must give the eager result bit for bit."""
+    B, cap, Hq, Hkv, d, page = 6, 1024, 8, 2, 128, 128
+    prob = draw(18800, B, 1, cap, Hq, Hkv, d)
+    Q, Kc, Vc = (pu.to_gpu(x) for x in (prob.Q, prob.K, prob.V))
+    lens = [1000, 1, 300, 64, 0, 777]
+    Kp, Vp, table = page_out(Kc, Vc, [cap] * B, page, 18801)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    splits = 2
+    O = torch.empty_like(Q)
+    L = torch.empty(B, Hq, 1, device="cuda")
+    ws = torch.empty(binding.fa_splitkv_fwd_workspace_bytes(B, Hq, 1, d, splits), dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.fa_kvcache_fwd(Q, Kp, Vp, prob.scale, True, seqlens_k=sl, block_table=table, num_splits=splits, O=O, LSE=L,
+                               workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for trial in range(4):
+        if trial:  # the batch moves on: longer caches, new queries, pages that changed hands
+            sl.copy_(torch.clamp(sl + 17 * trial, max=cap))
+            Q.copy_(torch.randn_like(Q))
+            table.copy_(table.flip(0) if trial == 2 else table)
+        step()
+        torch.cuda.synchronize()
+        eager = [O.clone(), L.clone()]
+        O.fill_(float("nan"))
+        L.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(eager[0], O) and torch.equal(eager[1], L)
