@@ -82,7 +82,20 @@ __global__ __launch_bounds__(512) void fwd_decode_kernel(FwdArgs a) {
     nk_ = len < 0 ? 0 : (len < p.Nk ? len : p.Nk);
   }
   const int n = si.n, nk = nk_;
-  if (n == 0 || nk == 0) return;  // (no keys: fwd_merge_kernel fills the rows)
+  // With a single share there is nothing to merge: the workgroup writes O and LSE themselves (and
+  // the launch leaves fwd_merge_kernel out), also for a sequence without keys.
+  const bool direct = nsplit == 1;
+  if (n == 0) return;
+  if (nk == 0) {  // (several shares: fwd_merge_kernel fills the rows)
+    if (direct) {
+      for (int i = tid; i < n * p.G * (D / 8); i += 512) {  // 16-byte pieces of the rows of this key/value head
+        const int prow_ = i / (D / 8), q_ = prow_ / p.G, h_ = g * p.G + prow_ % p.G;
+        *(u32x4*)(a.O + ((si.tok0 + q_) * p.Hq + h_) * D + 8 * (i % (D / 8))) = (u32x4){0, 0, 0, 0};
+        if (i % (D / 8) == 0) a.LSE[s * p.lse_seq_stride + (long)h_ * p.lse_head_stride + q_] = -INFINITY;
+      }
+    }
+    return;
+  }
   const int off = nk - n;
   const int nrows = n * p.G;  // packed rows: query * G + head of the group; at most 32 (the launch checks)
 
@@ -256,18 +269,39 @@ __global__ __launch_bounds__(512) void fwd_decode_kernel(FwdArgs a) {
     const int prow2 = ok ? r : nrows - 1;
     const int row2 = prow2 / p.G, h2 = g * p.G + prow2 % p.G;
     const float inv = den > 0.f ? 1.f / den : 0.f;  // no visible key in this share: O = 0, L = -inf
-    float* op = a.Opart + (((long)split * p.total_tokens + si.tok0 + row2) * p.Hq + h2) * D;
+    float out[D / 16];
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) {
       const int dcol = dg * (D / 16) + i;
       float acc = 0.f;
 #pragma unroll
       for (int ww = 0; ww < 8; ++ww) acc += wgt[ww] * ((const float*)(smem + ww * WAVEB))[dcol * 32 + r];
-      if (ok) op[dcol] = acc * inv;
+      out[i] = acc * inv;
     }
-    if (ok && dg == 0)
-      a.Lpart[(long)split * p.total_tokens * p.Hq + s * p.lse_seq_stride + (long)h2 * p.lse_head_stride + row2] =
-          den > 0.f ? mm * p.scale + fast_log2(den) * kLn2 : -INFINITY;
+    const float lse = den > 0.f ? mm * p.scale + fast_log2(den) * kLn2 : -INFINITY;
+    const long lidx = s * p.lse_seq_stride + (long)h2 * p.lse_head_stride + row2;
+    if (direct) {  // the final result, rounded to the element type
+      if (ok) {
+        __bf16* op = a.O + ((si.tok0 + row2) * p.Hq + h2) * D + dg * (D / 16);
+        if constexpr (D == 128) {  // eight columns: 16 bytes
+          u32x4 v;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[u] = pack2<F16>(out[2 * u], out[2 * u + 1]);
+          *(u32x4*)op = v;
+        } else {  // four columns: 8 bytes
+          u32x2 v;
+          v[0] = pack2<F16>(out[0], out[1]);
+          v[1] = pack2<F16>(out[2], out[3]);
+          *(u32x2*)op = v;
+        }
+        if (dg == 0) a.LSE[lidx] = lse;
+      }
+    } else if (ok) {
+      float* op = a.Opart + (((long)split * p.total_tokens + si.tok0 + row2) * p.Hq + h2) * D + dg * (D / 16);
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) op[i] = out[i];
+      if (dg == 0) a.Lpart[(long)split * p.total_tokens * p.Hq + lidx] = lse;
+    }
   }
 }
 

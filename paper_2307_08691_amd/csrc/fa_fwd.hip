@@ -972,6 +972,7 @@ static hipError_t launch_fwd_d(const FwdArgs& a, int causal, hipStream_t st) {
   if (a.nsplit > 0) {
     if (a.p.N * a.p.G <= 32) {  // one row tile per key/value head: the wavefronts divide the keys (fa_decode.hip)
       if (hipError_t e = launch_fwd_decode(a, D, causal, st)) return e;
+      if (a.nsplit == 1) return hipSuccess;  // (a single share: that kernel has written O and LSE itself)
     } else {
       const int nblk = (a.p.N * a.p.G + 255) / 256;
       dim3 grid(grid_size(nblk * a.nsplit, a.p.Hkv * a.p.nseq));
