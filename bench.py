@@ -58,12 +58,12 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "e1c4fc7f5c93",
+    "sources": "d521e4cb80f9",
     "d128_n8k_causal": {"fwd_kernel": 666515000, "bwd_dkdv_kernel": 866913721, "bwd_dq_kernel": 727687501},
     "sweep_d128_n8192_full": {"fwd_kernel": 269806953, "bwd_dkdv_kernel": 405162857, "bwd_dq_kernel": 338172765},
     "sweep_d64_n8192_causal": {"fwd_kernel": 874434693, "bwd_dkdv_kernel": 881142552, "bwd_dq_kernel": 831774463},
-    "decode_b8_on_8k": {"fwd_decode_kernel": 269476674},
-    "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1020339704},
+    "decode_b8_on_8k": {"fwd_decode_kernel": 269316633},
+    "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1019765575},
 }
 
 
@@ -436,7 +436,7 @@ def bench_decode(args, prob, binding) -> int:
                    **({"page": cache["page"], "cached_keys": int(lens.sum())} if cache else {})},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
                      **traffic_fields(prob.name, "fwd_decode_kernel" if few_rows else "fwd_kernel"), "avg_kernel_ms": kern_ms,
-                     "kernel": ("fwd_decode_kernel" if few_rows else "fwd_kernel<.., split>") + " + fwd_merge_kernel"},
+                     "kernel": ("fwd_decode_kernel" if few_rows else "fwd_kernel<.., split>") + ("" if few_rows and splits == 1 else " + fwd_merge_kernel")},
     }
     if not args.no_cpu_baseline:
         from oracle import attention_oracle as orc
