@@ -59,9 +59,9 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
     "sources": "d521e4cb80f9",
-    "d128_n8k_causal": {"fwd_kernel": 666515000, "bwd_dkdv_kernel": 866913721, "bwd_dq_kernel": 727687501},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269806953, "bwd_dkdv_kernel": 405162857, "bwd_dq_kernel": 338172765},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 874434693, "bwd_dkdv_kernel": 881142552, "bwd_dq_kernel": 831774463},
+    "d128_n8k_causal": {"fwd_kernel": 660837263, "bwd_dkdv_kernel": 866593834, "bwd_dq_kernel": 726436289},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269807006, "bwd_dkdv_kernel": 405172718, "bwd_dq_kernel": 338105817},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 873262377, "bwd_dkdv_kernel": 882411534, "bwd_dq_kernel": 831776843},
     "decode_b8_on_8k": {"fwd_decode_kernel": 269316633},
     "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1019765575},
 }
