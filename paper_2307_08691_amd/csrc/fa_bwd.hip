@@ -1290,6 +1290,11 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     stages = 2;  // what remains: the dK/dV kernel
+  } else if (stages == 7 && !a.p.mask && !a.p.drop_thr && a.p.d == D) {  // sliding window, block-sparse pattern: the same two launches
+    dim3 qgrid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
+    hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, false, true, true>), qgrid, dim3(512), 0, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    stages = 2;
   }
   if (stages & 1) {
     hipLaunchKernelGGL((bwd_prep_kernel<D, F16>), dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st, a);
