@@ -569,10 +569,9 @@ def main() -> int:
         out["roofline_dq"] = roof(1.5 * fwd_fl, dq_ms, "bwd_dq_kernel")
         out["bwd"]["prep_ms"] = prep_ms  # (a launch of its own only here: fa_bwd computes D inside the dQ kernel)
     else:
-        # no per-kernel entry point for this workload: the backward launches together (D pre-pass where
-        # the entry point has one: dropout, mask, d = 256), against the 3.5 x forward FLOPs they execute (7 products)
-        own_d = prob.meta.get("window") or prob.meta.get("block_pattern")
-        out["roofline"] = roof(3.5 * fwd_fl, bwd_ms, ("" if own_d else "bwd_prep_kernel + ") + "bwd_dkdv_kernel + bwd_dq_kernel")
+        # no per-kernel entry point for this workload: the backward launches together (with a D pre-pass
+        # only at d = 256), against the 3.5 x forward FLOPs they execute (7 products)
+        out["roofline"] = roof(3.5 * fwd_fl, bwd_ms, ("bwd_prep_kernel + " if prob.d == 256 else "") + "bwd_dkdv_kernel + bwd_dq_kernel")
     # what the matrix pipe sustains on this machine with every operand in registers (outside the timed region)
     out["mfma_loop"] = {}
     for key, rnd in (("constant_operands", False), ("random_operands", True)):

@@ -1290,9 +1290,17 @@ static hipError_t launch_bwd_d(const BwdArgs& a, int causal, int stages, hipStre
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     stages = 2;  // what remains: the dK/dV kernel
-  } else if (stages == 7 && !a.p.mask && !a.p.drop_thr && a.p.d == D) {  // sliding window, block-sparse pattern: the same two launches
+  } else if (stages == 7 && a.p.d == D) {  // sliding window or block-sparse pattern, mask, dropout: the same two launches
     dim3 qgrid(grid_size((a.p.N + 255) / 256, a.p.Hq * a.p.nseq));
-    hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, false, true, true>), qgrid, dim3(512), 0, st, a);
+    if (a.p.mask) {
+      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, false, false, true, false, true>), qgrid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, true, false, true>), qgrid, dim3(512), 0, st, a);
+    } else if (a.p.drop_thr) {
+      if (causal) hipLaunchKernelGGL((bwd_dq_kernel<D, true, F16, true, false, false, false, true>), qgrid, dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, true, false, false, false, true>), qgrid, dim3(512), 0, st, a);
+    } else {
+      hipLaunchKernelGGL((bwd_dq_kernel<D, false, F16, false, false, false, true, true>), qgrid, dim3(512), 0, st, a);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     stages = 2;
   }
