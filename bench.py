@@ -58,10 +58,10 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 # the kernel sources are the ones they were measured on (`sources`: kernel_sources_id() at the time
 # of the measurement); otherwise `traffic` is null and the stale figure moves to `traffic_recorded`.
 MEASURED_TRAFFIC = {
-    "sources": "d521e4cb80f9",
-    "d128_n8k_causal": {"fwd_kernel": 660837263, "bwd_dkdv_kernel": 866593834, "bwd_dq_kernel": 726436289},
-    "sweep_d128_n8192_full": {"fwd_kernel": 269807006, "bwd_dkdv_kernel": 405172718, "bwd_dq_kernel": 338105817},
-    "sweep_d64_n8192_causal": {"fwd_kernel": 873262377, "bwd_dkdv_kernel": 882411534, "bwd_dq_kernel": 831776843},
+    "sources": "aa63587ade56",
+    "d128_n8k_causal": {"fwd_kernel": 657936517, "bwd_dkdv_kernel": 862384831, "bwd_dq_kernel": 736812614},
+    "sweep_d128_n8192_full": {"fwd_kernel": 269806409, "bwd_dkdv_kernel": 405186020, "bwd_dq_kernel": 338038522},
+    "sweep_d64_n8192_causal": {"fwd_kernel": 873743558, "bwd_dkdv_kernel": 883456292, "bwd_dq_kernel": 831791357},
     "decode_b8_on_8k": {"fwd_decode_kernel": 269316633},
     "decode_paged_b64_to_8k": {"fwd_decode_kernel": 1019765575},
 }
