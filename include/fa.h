@@ -89,8 +89,8 @@ int fa_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
  * kernel that computes D for its rows and produces dQ by recomputing the
  * probabilities (instead of accumulating dQ across workgroups with atomic adds),
  * then a column-block kernel that produces dK and dV (section 3.2, "Backward
- * pass"). Head dimension 256, dropout, mask, window and pattern variants run the
- * D pre-pass as a launch of its own first. All three outputs are bit-reproducible.
+ * pass"). Head dimension 256 runs the D pre-pass as a launch of its own first.
+ * All three outputs are bit-reproducible.
  */
 size_t fa_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int d);
 int fa_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
